@@ -1,0 +1,139 @@
+"""Benchmark of the BOF4 hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one Llama-7B-shaped transformer block of synthetic bf16 weights
+(workload 1: 202,375,168 weights, block 64, signed absmax / BOF4-S codebook, OPQ at q = 0.95):
+    bof4_quantize (outlier extraction, absmax, normalise, assign, pack)  ->  bof4_dequantize (decode + outlier
+    scatter)  ->  bof4_lloyd_step (normalise, assign, per-level sums)  ->  bof4_codebook_update (host).
+Inputs are resident in HBM before the timed region.  Successive steps rotate over several independently seeded
+copies of the workload so that no step finds its input in the last-level cache.
+
+Prints ONE JSON line: whole-path throughput in GB/s of bf16 weights, with per-call rates, the roofline record of
+the dominant kernel (HIP-event timed) and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2505_06653_amd import binding, codebooks, inputs  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+BLOCK = 64
+
+
+def cpu_baseline(w_sample, cb, T):
+    """Oracle (as it stands) on a bounded sample of the same workload; reported baseline only."""
+    import oracle
+    wb = inputs.bits(w_sample)
+    n = wb.size
+    t0 = time.perf_counter()
+    st, codes, scales, oidx, oval, nout = oracle.quantize(wb, BLOCK, cb, 1, opq_T=T)
+    t1 = time.perf_counter()
+    oracle.dequantize(codes, scales, n, BLOCK, cb, oidx, oval)
+    t2 = time.perf_counter()
+    oracle.lloyd_step(wb, BLOCK, cb, 1, opq_T=T)
+    t3 = time.perf_counter()
+    total = t3 - t0
+    return {"value": 2.0 * n / total / 1e9, "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {n} weights of the workload; quantize {t1 - t0:.2f}s and dequantize {t2 - t1:.2f}s run "
+                      f"on 1 thread, lloyd_step {t3 - t2:.2f}s on {oracle.num_threads()} OpenMP threads",
+            "lloyd_weights_per_s": n / (t3 - t2)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--replicas", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 (sharding is described in DESIGN.md)",
+              file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    binding.lib()
+
+    cb = codebooks.array(codebooks.BOF4S_MSE[BLOCK])
+    T = binding.bof4_opq_threshold(0.95, BLOCK)
+    ws_list = [inputs.flatten(inputs.llama7b_block(seed=50 + r, device=dev)) for r in range(args.replicas)]
+    n = ws_list[0].numel()
+    cap = n // 64
+    codes = torch.empty(n // 2, dtype=torch.uint8, device=dev)
+    scales = torch.empty(n // BLOCK, dtype=torch.float16, device=dev)
+    oidx = torch.empty(cap, dtype=torch.int64, device=dev)
+    oval = torch.empty(cap, dtype=torch.float16, device=dev)
+    deq = torch.empty(n, dtype=torch.bfloat16, device=dev)
+    ws = binding.alloc_workspace(n, BLOCK, cap, dev)
+    names = ("quantize", "dequantize", "lloyd_step")
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    n_out_seen = 0
+
+    def step(i, events=None):
+        nonlocal n_out_seen
+        w = ws_list[i % len(ws_list)]
+        if events:
+            events[0].record()
+        _, _, gi, gv, k = binding.bof4_quantize(w, BLOCK, cb, 1, opq_T=T, out_capacity=cap, codes=codes,
+                                                scales=scales, out_idx=oidx, out_val=oval, ws=ws)
+        if events:
+            events[1].record()
+        binding.bof4_dequantize(codes, scales, n, BLOCK, cb, gi, gv, out=deq)
+        if events:
+            events[2].record()
+        st = binding.bof4_lloyd_step(w, BLOCK, cb, 1, opq_T=T, ws=ws, raw=True)
+        if events:
+            events[3].record()
+        binding.bof4_codebook_update(st, codebooks.PIN_BOF4S, cb)
+        n_out_seen = k
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, ev[i])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    ms = {nm: float(np.mean([ev[i][k].elapsed_time(ev[i][k + 1]) for i in range(args.steps)]))
+          for k, nm in enumerate(names)}
+    rho = n_out_seen / n
+    alg_bytes = {"quantize": (2.0 + 0.5 + 2.0 / BLOCK + 10.0 * rho) * n,
+                 "dequantize": (0.5 + 2.0 / BLOCK + 10.0 * rho + 2.0) * n,
+                 "lloyd_step": 2.0 * n}
+    dominant = max(names, key=lambda k: ms[k])
+    achieved = alg_bytes[dominant] / (ms[dominant] * 1e-3) / 1e9
+    per_call = {nm: {"ms": ms[nm], "GBps_bf16": 2.0 * n / (ms[nm] * 1e-3) / 1e9,
+                     "GBps_algorithmic": alg_bytes[nm] / (ms[nm] * 1e-3) / 1e9,
+                     "hbm_frac": alg_bytes[nm] / (ms[nm] * 1e-3) / 1e9 / HBM_PEAK_GBS} for nm in names}
+    out = {
+        "metric": "GB/s bf16 weights quantized & weights/s per Lloyd step; % of HBM peak",
+        "value": 2.0 * n * args.steps / dt / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 in, f32 normalise/assign, f64 sums", "data": "synthetic",
+        "config": {"workload": "configs[1]: one Llama-7B-shaped block, 202,375,168 bf16 weights, Student-t(5) std 0.02 "
+                               "with log-normal(0,0.3) row scale, block 64, signed absmax (BOF4-S), OPQ q=0.95; "
+                               "step = quantize + dequantize + lloyd_step + codebook_update",
+                   "n_weights": n, "block": BLOCK, "outlier_fraction": rho, "replicas": len(ws_list)},
+        "lloyd_weights_per_s": n / (ms["lloyd_step"] * 1e-3),
+        "per_call": per_call,
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(ws_list[0][: 1 << 26].cpu(), cb, T)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

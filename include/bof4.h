@@ -1,0 +1,115 @@
+/*
+ * bof4.h - C ABI of the MI355X (gfx950) hot path of BOF4 / BOF4-S / OPQ 4-bit block-wise weight quantisation
+ * (arxiv 2505.06653).
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) addresses owned by the caller; "host" pointers are ordinary host memory.
+ *     The library keeps no state between calls, allocates nothing and frees nothing.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Work is enqueued on it; a call that
+ *     returns results to host memory synchronises that stream before returning (stated per call).
+ *   - Weights are bfloat16 bit patterns, flat; block b is elements [b*block, (b+1)*block).  `block` must be
+ *     32, 64, 128 or 256 and `n` a positive multiple of it.
+ *   - A codebook is 16 finite, strictly ascending doubles (host).  Code c means level index c (paper level c+1).
+ *   - Return value: BOF4_OK or a negative error code; bof4_last_error() gives a message for the calling thread,
+ *     bof4_last_hip_error() the raw hipError_t of the last BOF4_ERR_HIP.
+ *   - Required alignment: weight pointers 16 bytes, code pointers 4 bytes, scale / outlier-value pointers
+ *     2 bytes, outlier-index pointers 8 bytes, workspace 256 bytes.  Misalignment is BOF4_ERR_ARG.
+ */
+#ifndef BOF4_H
+#define BOF4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BOF4_OK 0
+#define BOF4_ERR_ARG (-1)       /* null / misaligned pointer, bad n or block, codebook not finite and ascending, T < 0 */
+#define BOF4_ERR_CAPACITY (-2)  /* outlier buffers too small; *n_outliers holds the required count              */
+#define BOF4_ERR_WORKSPACE (-3) /* ws_bytes below bof4_workspace_bytes(...)                                    */
+#define BOF4_ERR_HIP (-4)       /* a HIP runtime call failed                                                   */
+
+/* Per-region sums of one Lloyd / EM expectation pass (section 3.2 eq. 6; appendix B.3). */
+typedef struct {
+    double num[16];      /* sum over region l of g * x      (numerator of eq. 6)                               */
+    double den[16];      /* sum over region l of g          (denominator of eq. 6)                             */
+    uint64_t cnt[16];    /* K_l: normalised weights that fell into region l                                    */
+    double sse;          /* sum of g * (x - level[code])^2: n_used * MSE(W, Q(W)) by the decomposition of B.3  */
+    uint64_t n_used;     /* weights that entered the sums (n minus outliers)                                   */
+    uint64_t n_outliers; /* weights excluded by OPQ                                                            */
+} bof4_lloyd_stats;
+
+/* Bytes of device workspace that bof4_quantize (with outlier buffers of `out_capacity` entries; 0 if OPQ is not
+ * used) and bof4_lloyd_step need for `n` weights in blocks of `block` - the larger of the two.  Pure host
+ * function; 0 on invalid arguments. */
+size_t bof4_workspace_bytes(uint64_t n, uint32_t block, uint64_t out_capacity);
+
+/* OPQ threshold T = F_M^{-1}(q) for Gaussian weights (section 3.3 eq. 9 with F_M = (2G-1)^I of appendix B.1):
+ * the q-quantile of the absolute maximum of `block` standard normal variables.  Pure host function; NaN on
+ * invalid arguments. */
+double bof4_opq_threshold(double q, uint32_t block);
+
+/* The 15 binary32 decision thresholds the kernels compare against: thr[k] is the largest binary32 number not
+ * above the mid-point of levels k and k+1 (nearest-neighbour rule of section 3.2; a value exactly on a mid-point
+ * goes to the lower level).  code(x) = number of k with x > thr[k].  Pure host function. */
+int bof4_thresholds(const double* cb_host, float* thr_host);
+
+/*
+ * One expectation pass of the data-driven Lloyd / EM codebook optimisation (section 3.2 eq. 6, appendix B.3).
+ * Every block is normalised by its absolute (signed_norm = 0, section 2.1 eq. 1-2) or signed (signed_norm = 1,
+ * section 3.1 eq. 4) maximum as stored in binary16, each normalised weight x is assigned to its nearest level,
+ * and the sums of eq. 6 are accumulated per region with g = (block constant)^2 (weight_by_max2 = 1) or g = 1
+ * (weight_by_max2 = 0, the normalised-error variant of appendix D).  With opq_T > 0 the OPQ outliers of
+ * section 3.3 are replaced by zero before the maximum search and take no part in the sums.
+ *   w_dev       n bfloat16 weights (device, read only)
+ *   cb_host     16 levels (host)
+ *   out_host    result (host); the call synchronises `stream`
+ *   ws_dev      workspace of at least bof4_workspace_bytes(n, block, 0) bytes (device); contents undefined after
+ * The result is bit-identical from run to run (fixed reduction order).
+ */
+int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                    double opq_T, int weight_by_max2, bof4_lloyd_stats* out_host, void* ws_dev, size_t ws_bytes,
+                    void* stream);
+
+/* Maximisation step (section 3.2, eq. 6 and its last paragraph): level l moves to num[l]/den[l] unless bit l of
+ * pinned_mask is set or the region is empty (den[l] == 0).  Pure host function; cb_host is updated in place. */
+int bof4_codebook_update(const bof4_lloyd_stats* stats_host, uint16_t pinned_mask, double* cb_host);
+
+/*
+ * Quantise (sections 2.1, 3.1, 3.3): OPQ outlier extraction (opq_T > 0), block (signed) absmax, normalisation,
+ * nearest-of-16 assignment, nibble packing.
+ *   codes_dev        n/2 bytes; element 2j in the low nibble of byte j, element 2j+1 in the high nibble
+ *   scales_dev       n/block binary16 block constants (the sign is kept when signed_norm = 1)
+ *   out_idx_dev / out_val_dev   outlier list in ascending flat index: int64 index, binary16 value; capacity
+ *                    `out_capacity` entries each; ignored (may be NULL) when opq_T == 0
+ *   n_outliers_host  receives the number of outliers (0 when opq_T == 0)
+ *   ws_dev           workspace of at least bof4_workspace_bytes(n, block, out_capacity) bytes; needed only
+ *                    when opq_T > 0
+ * With opq_T > 0 the call synchronises `stream`; with opq_T == 0 it only enqueues.
+ * On BOF4_ERR_CAPACITY codes and scales are complete, the outlier list is not.
+ */
+int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                  double opq_T, uint8_t* codes_dev, uint16_t* scales_dev, int64_t* out_idx_dev,
+                  uint16_t* out_val_dev, uint64_t out_capacity, uint64_t* n_outliers_host, void* ws_dev,
+                  size_t ws_bytes, void* stream);
+
+/*
+ * Dequantise (section 2.1 eq. 3): w~ = block constant * level[code] as one binary32 product rounded to
+ * bfloat16, then the outliers (section 3.3) are written back over their zero placeholders.
+ *   w_out_dev   n bfloat16 values (device)
+ * Only enqueues; out_idx_dev entries must lie in [0, n) (not checked on the device side beyond a bounds test
+ * that skips offending entries).
+ */
+int bof4_dequantize(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t n, uint32_t block,
+                    const double* cb_host, const int64_t* out_idx_dev, const uint16_t* out_val_dev,
+                    uint64_t n_outliers, void* w_out_dev, void* stream);
+
+const char* bof4_last_error(void);
+int bof4_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BOF4_H */

@@ -1,0 +1,179 @@
+"""Thin ctypes binding of include/bof4.h: argument marshalling only, every step of the path runs in the HIP library.
+
+torch supplies device memory (tensors) and the stream; nothing is computed here.  The functions carry the names of
+the C entry points.  A missing library is an error (there is no fallback of any kind).
+"""
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libbof4_hip.so")
+
+BOF4_OK, BOF4_ERR_ARG, BOF4_ERR_CAPACITY, BOF4_ERR_WORKSPACE, BOF4_ERR_HIP = 0, -1, -2, -3, -4
+EXPORTS = ("bof4_workspace_bytes", "bof4_opq_threshold", "bof4_thresholds", "bof4_lloyd_step",
+           "bof4_codebook_update", "bof4_quantize", "bof4_dequantize", "bof4_last_error", "bof4_last_hip_error")
+
+
+class Bof4Error(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"bof4 error {code}: {msg}")
+        self.code = code
+
+
+class LloydStats(ctypes.Structure):
+    _fields_ = [("num", ctypes.c_double * 16), ("den", ctypes.c_double * 16), ("cnt", ctypes.c_uint64 * 16),
+                ("sse", ctypes.c_double), ("n_used", ctypes.c_uint64), ("n_outliers", ctypes.c_uint64)]
+
+    def as_dict(self):
+        return {"num": np.array(self.num[:], dtype=np.float64), "den": np.array(self.den[:], dtype=np.float64),
+                "cnt": np.array(self.cnt[:], dtype=np.uint64), "sse": float(self.sse),
+                "n_used": int(self.n_used), "n_outliers": int(self.n_outliers)}
+
+
+_lib = None
+
+
+def lib():
+    """Load libbof4_hip.so (built by `python -m paper_2505_06653_amd.build`); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} not built - run `python -m paper_2505_06653_amd.build` "
+                              "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, f64p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_double)
+        L.bof4_workspace_bytes.restype = ctypes.c_size_t
+        L.bof4_workspace_bytes.argtypes = [ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64]
+        L.bof4_opq_threshold.restype = ctypes.c_double
+        L.bof4_opq_threshold.argtypes = [ctypes.c_double, ctypes.c_uint32]
+        L.bof4_thresholds.restype = ctypes.c_int
+        L.bof4_thresholds.argtypes = [f64p, ctypes.POINTER(ctypes.c_float)]
+        L.bof4_lloyd_step.restype = ctypes.c_int
+        L.bof4_lloyd_step.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint32, f64p, ctypes.c_int, ctypes.c_double,
+                                      ctypes.c_int, ctypes.POINTER(LloydStats), vp, ctypes.c_size_t, vp]
+        L.bof4_codebook_update.restype = ctypes.c_int
+        L.bof4_codebook_update.argtypes = [ctypes.POINTER(LloydStats), ctypes.c_uint16, f64p]
+        L.bof4_quantize.restype = ctypes.c_int
+        L.bof4_quantize.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint32, f64p, ctypes.c_int, ctypes.c_double,
+                                    vp, vp, vp, vp, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint64), vp,
+                                    ctypes.c_size_t, vp]
+        L.bof4_dequantize.restype = ctypes.c_int
+        L.bof4_dequantize.argtypes = [vp, vp, ctypes.c_uint64, ctypes.c_uint32, f64p, vp, vp, ctypes.c_uint64, vp, vp]
+        L.bof4_last_error.restype = ctypes.c_char_p
+        L.bof4_last_hip_error.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _check(code, allow=()):
+    if code != BOF4_OK and code not in allow:
+        raise Bof4Error(code, lib().bof4_last_error().decode())
+    return code
+
+
+def _cb(cb):
+    cb = np.ascontiguousarray(cb, dtype=np.float64)
+    if cb.shape != (16,):
+        raise ValueError("codebook must have 16 levels")
+    return cb, cb.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def bof4_workspace_bytes(n, block, out_capacity=0):
+    return int(lib().bof4_workspace_bytes(n, block, out_capacity))
+
+
+def bof4_opq_threshold(q, block):
+    return float(lib().bof4_opq_threshold(q, block))
+
+
+def bof4_thresholds(cb):
+    cb, cbp = _cb(cb)
+    thr = np.zeros(15, dtype=np.float32)
+    _check(lib().bof4_thresholds(cbp, thr.ctypes.data_as(ctypes.POINTER(ctypes.c_float))))
+    return thr
+
+
+def bof4_codebook_update(stats, pinned_mask, cb):
+    """stats: LloydStats (as returned by bof4_lloyd_step(..., raw=True)) or its dict form.  Returns new float64[16]."""
+    cb, _ = _cb(cb)
+    cb = cb.copy()
+    if not isinstance(stats, LloydStats):
+        s = LloydStats()
+        for l in range(16):
+            s.num[l], s.den[l], s.cnt[l] = float(stats["num"][l]), float(stats["den"][l]), int(stats["cnt"][l])
+        s.sse, s.n_used, s.n_outliers = float(stats["sse"]), int(stats["n_used"]), int(stats["n_outliers"])
+        stats = s
+    _check(lib().bof4_codebook_update(ctypes.byref(stats), pinned_mask,
+                                      cb.ctypes.data_as(ctypes.POINTER(ctypes.c_double))))
+    return cb
+
+
+def alloc_workspace(n, block, out_capacity=0, device="cuda"):
+    nbytes = max(bof4_workspace_bytes(n, block, out_capacity), 256)
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def bof4_lloyd_step(w, block, cb, signed, opq_T=0.0, weight_by_max2=True, ws=None, stream=None, raw=False):
+    """w: flat bf16 device tensor.  Returns the statistics as a dict (or the ctypes struct with raw=True)."""
+    assert w.dtype == torch.bfloat16 and w.is_cuda and w.is_contiguous()
+    n = w.numel()
+    cb, cbp = _cb(cb)
+    if ws is None:
+        ws = alloc_workspace(n, block, 0, w.device)
+    out = LloydStats()
+    _check(lib().bof4_lloyd_step(_ptr(w), n, block, cbp, int(signed), float(opq_T), int(bool(weight_by_max2)),
+                                 ctypes.byref(out), _ptr(ws), ws.numel(), _stream(stream)))
+    return out if raw else out.as_dict()
+
+
+def bof4_quantize(w, block, cb, signed, opq_T=0.0, out_capacity=0, codes=None, scales=None, out_idx=None,
+                  out_val=None, ws=None, stream=None, allow_overflow=False):
+    """w: flat bf16 device tensor.  Returns (codes u8[n/2], scales f16[n/block], out_idx i64[k], out_val f16[k],
+    n_outliers).  Output tensors are allocated here unless passed in."""
+    assert w.dtype == torch.bfloat16 and w.is_cuda and w.is_contiguous()
+    n = w.numel()
+    dev = w.device
+    cb, cbp = _cb(cb)
+    if codes is None:
+        codes = torch.empty(max(n // 2, 1), dtype=torch.uint8, device=dev)
+    if scales is None:
+        scales = torch.empty(max(n // max(block, 1), 1), dtype=torch.float16, device=dev)
+    if opq_T > 0:
+        if out_idx is None:
+            out_idx = torch.empty(max(out_capacity, 1), dtype=torch.int64, device=dev)
+        if out_val is None:
+            out_val = torch.empty(max(out_capacity, 1), dtype=torch.float16, device=dev)
+        if ws is None:
+            ws = alloc_workspace(n, block, out_capacity, dev)
+    nout = ctypes.c_uint64(0)
+    code = lib().bof4_quantize(_ptr(w), n, block, cbp, int(signed), float(opq_T), _ptr(codes), _ptr(scales),
+                               _ptr(out_idx), _ptr(out_val), out_capacity, ctypes.byref(nout), _ptr(ws),
+                               0 if ws is None else ws.numel(), _stream(stream))
+    _check(code, allow=(BOF4_ERR_CAPACITY,) if allow_overflow else ())
+    k = min(int(nout.value), out_capacity)
+    return (codes, scales, None if out_idx is None else out_idx[:k], None if out_val is None else out_val[:k],
+            int(nout.value))
+
+
+def bof4_dequantize(codes, scales, n, block, cb, out_idx=None, out_val=None, out=None, stream=None):
+    """Returns the flat bf16 device tensor of n dequantised weights."""
+    cb, cbp = _cb(cb)
+    if out is None:
+        out = torch.empty(n, dtype=torch.bfloat16, device=codes.device)
+    k = 0 if out_idx is None else int(out_idx.numel())
+    _check(lib().bof4_dequantize(_ptr(codes), _ptr(scales), n, block, cbp, _ptr(out_idx) if k else None,
+                                 _ptr(out_val) if k else None, k, _ptr(out), _stream(stream)))
+    return out

@@ -1,0 +1,738 @@
+// bof4.hip - HIP (gfx950) implementation of the C ABI declared in include/bof4.h.
+//
+// Hot path of BOF4 / BOF4-S / OPQ (arxiv 2505.06653): block (signed) absmax normalisation (section 2.1 eq. 1-3,
+// section 3.1 eq. 4), nearest-of-16 assignment (section 3.2), 4-bit packing, OPQ outlier extraction (section 3.3
+// eq. 9, appendix E.1), decoding, and the per-region sums of the data-driven Lloyd step (section 3.2 eq. 6,
+// appendix B.3).  Nothing here is a dense contraction, so there is no MFMA: the kernels are streaming scans
+// bounded by HBM bandwidth and plain VALU issue.
+//
+// Rounding contract shared by all kernels (and by the independent CPU oracle used in the tests):
+//   * the block constant is stored as binary16 and the quantiser normalises by the stored value;
+//   * x = w / m is one correctly rounded binary32 division, denormals kept;
+//   * code(x) = #{k : x > thr[k]}, thr[k] = largest binary32 <= mid-point of levels k, k+1;
+//   * the lowest index wins when several elements share the largest magnitude;
+//   * OPQ: w^2 * I(I-1) > T^2 * V with V = fma(-S, S, I*Q) in binary64, S = sum w, Q = sum w^2 over the block.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+
+#include "bof4.h"
+
+namespace {
+
+// ------------------------------------------------------------------------------------------------ host state
+thread_local char g_err[256] = "";
+thread_local int g_hip_err = 0;
+
+int fail(int code, const char* msg) {
+    snprintf(g_err, sizeof(g_err), "%s", msg);
+    return code;
+}
+int fail_hip(hipError_t e, const char* where) {
+    g_hip_err = (int)e;
+    snprintf(g_err, sizeof(g_err), "%s: %s", where, hipGetErrorString(e));
+    return BOF4_ERR_HIP;
+}
+#define HIP_TRY(expr)                                  \
+    do {                                               \
+        hipError_t e_ = (expr);                        \
+        if (e_ != hipSuccess) return fail_hip(e_, #expr); \
+    } while (0)
+
+bool valid_block(uint32_t b) { return b == 32 || b == 64 || b == 128 || b == 256; }
+bool valid_codebook(const double* cb) {
+    if (!cb) return false;
+    for (int l = 0; l < 16; ++l)
+        if (!std::isfinite(cb[l])) return false;
+    for (int l = 1; l < 16; ++l)
+        if (!(cb[l] > cb[l - 1])) return false;
+    return true;
+}
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Codebook-derived constants handed to the kernels by value (kernel argument segment, no device allocation).
+struct CodebookArgs {
+    float thr[16];   // 15 decision thresholds (+1 pad)
+    float lv32[16];  // levels rounded to binary32 (decoder)
+    double cb64[16]; // levels in binary64 (Lloyd error term)
+};
+
+void make_thresholds(const double* cb, float* thr) {
+    for (int k = 0; k < 15; ++k) {
+        double mid = (cb[k] + cb[k + 1]) * 0.5;
+        float f = (float)mid;  // round to nearest
+        if ((double)f > mid) f = std::nextafterf(f, -INFINITY);
+        thr[k] = f;
+    }
+}
+CodebookArgs make_codebook_args(const double* cb) {
+    CodebookArgs a;
+    make_thresholds(cb, a.thr);
+    a.thr[15] = INFINITY;
+    for (int l = 0; l < 16; ++l) {
+        a.lv32[l] = (float)cb[l];
+        a.cb64[l] = cb[l];
+    }
+    return a;
+}
+
+// ------------------------------------------------------------------------------------------------ workspace
+constexpr uint32_t QTILE = 2048;         // weights per quantise tile (256 threads x 8)
+constexpr uint32_t LLOYD_MAX_GRID = 768; // persistent workgroups of the Lloyd pass
+constexpr uint32_t LLOYD_SLOTS = 56;     // num[16] den[16] cnt[16] sse n_outliers (+pad) per partial
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct QuantWsLayout {
+    size_t header, tile_cnt, tile_base, tile_off, stage_idx, stage_val, total;
+};
+QuantWsLayout quant_ws_layout(uint64_t n, uint64_t cap) {
+    QuantWsLayout L;
+    uint64_t nt = (n + QTILE - 1) / QTILE;
+    size_t o = 0;
+    L.header = o;    o += 256;
+    L.tile_cnt = o;  o += align_up(nt * 4, 256);
+    L.tile_base = o; o += align_up(nt * 8, 256);
+    L.tile_off = o;  o += align_up(nt * 8, 256);
+    L.stage_idx = o; o += align_up(cap * 8, 256);
+    L.stage_val = o; o += align_up(cap * 2, 256);
+    L.total = o;
+    return L;
+}
+size_t lloyd_ws_bytes() { return (size_t)(LLOYD_MAX_GRID + 1) * LLOYD_SLOTS * 8; }
+
+// ------------------------------------------------------------------------------------------------ device helpers
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float f) {
+    _Float16 h = (_Float16)f;  // v_cvt_f16_f32, round to nearest even
+    unsigned short s;
+    __builtin_memcpy(&s, &h, 2);
+    return s;
+}
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t b) {
+    unsigned short s = (unsigned short)b;
+    _Float16 h;
+    __builtin_memcpy(&h, &s, 2);
+    return (float)h;
+}
+__device__ __forceinline__ int assign_code(float x, const CodebookArgs& cb) {
+    int code = 0;
+#pragma unroll
+    for (int k = 0; k < 15; ++k) code += (x > cb.thr[k]) ? 1 : 0;
+    return code;
+}
+// argmax key: larger magnitude first, then lower index; the sign rides in bit 0 and never decides.
+__device__ __forceinline__ uint32_t max_key(uint32_t bits16, uint32_t idx) {
+    return ((bits16 & 0x7fffu) << 16) | ((0x7fffu - idx) << 1) | (bits16 >> 15);
+}
+template <int WIDTH>
+__device__ __forceinline__ uint32_t group_max_u32(uint32_t v) {
+#pragma unroll
+    for (int m = 1; m < WIDTH; m <<= 1) v = max(v, (uint32_t)__shfl_xor((int)v, m, 64));
+    return v;
+}
+template <int WIDTH>
+__device__ __forceinline__ double group_sum_f64(double v) {
+#pragma unroll
+    for (int m = 1; m < WIDTH; m <<= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------------ quantise
+// One lane owns 8 consecutive weights (one 16-byte load); a block of I weights spans I/8 neighbouring lanes.
+template <int I, bool SIGNED, bool OPQ>
+__global__ __launch_bounds__(256) void quantize_kernel(const uint4* __restrict__ w, uint64_t n_vec,
+                                                        CodebookArgs cb, double T2, uint32_t* __restrict__ codes,
+                                                        uint16_t* __restrict__ scales, uint64_t* total_ctr,
+                                                        uint32_t* tile_cnt, uint64_t* tile_base,
+                                                        int64_t* stage_idx, uint16_t* stage_val, uint64_t capacity) {
+    constexpr int G = I / 8;  // lanes per block
+    __shared__ uint32_t wave_tot[4];
+    __shared__ uint64_t base_sh;
+    const uint64_t tile = blockIdx.x;
+    const uint64_t v = tile * 256 + threadIdx.x;
+    const bool active = v < n_vec;
+    uint4 q = active ? w[v] : make_uint4(0, 0, 0, 0);
+    uint32_t r[4] = {q.x, q.y, q.z, q.w};
+    uint32_t b[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) b[e] = (e & 1) ? (r[e >> 1] >> 16) : (r[e >> 1] & 0xffffu);
+    const uint32_t lane_in_group = threadIdx.x & (G - 1);
+
+    uint32_t omask = 0;
+    if (OPQ) {
+        double S = 0.0, Q = 0.0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            double d = (double)bf16_bits_to_f32(b[e]);
+            S += d;
+            Q = fma(d, d, Q);
+        }
+        S = group_sum_f64<G>(S);
+        Q = group_sum_f64<G>(Q);
+        double V = fma(-S, S, (double)I * Q);
+        double rhs = T2 * V;
+        constexpr double II1 = (double)I * (double)(I - 1);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            double d = (double)bf16_bits_to_f32(b[e]);
+            if (V > 0.0 && (d * d) * II1 > rhs) omask |= 1u << e;
+        }
+    }
+    uint32_t key = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        uint32_t be = (omask >> e) & 1u ? 0u : b[e];
+        key = max(key, max_key(be, lane_in_group * 8 + e));
+    }
+    key = group_max_u32<G>(key);
+    uint32_t mbits = (key >> 16) | (SIGNED ? ((key & 1u) << 15) : 0u);
+    float m = bf16_bits_to_f32(mbits);
+    uint32_t s16 = f32_to_f16_bits(m);
+    float m_eff = f16_bits_to_f32(s16);
+    uint32_t packed = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float f = (omask >> e) & 1u ? 0.0f : bf16_bits_to_f32(b[e]);
+        float x = (m_eff == 0.0f) ? 0.0f : f / m_eff;
+        packed |= (uint32_t)assign_code(x, cb) << (4 * e);
+    }
+    if (active) {
+        codes[v] = packed;
+        if (lane_in_group == 0) scales[v / G] = (uint16_t)s16;
+    }
+    if (OPQ) {
+        // ordered compaction of this tile's outliers into a contiguous run of the staging list
+        const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        uint32_t cntv = active ? __popc(omask) : 0;
+        uint32_t incl = cntv;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            uint32_t t = (uint32_t)__shfl_up((int)incl, d, 64);
+            if (lane >= (uint32_t)d) incl += t;
+        }
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();
+        uint32_t wbase = 0, tot = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            uint32_t t = wave_tot[k];
+            if ((uint32_t)k < wave) wbase += t;
+            tot += t;
+        }
+        if (threadIdx.x == 0) {
+            uint64_t base = 0;
+            if (tot) base = atomicAdd((unsigned long long*)total_ctr, (unsigned long long)tot);
+            base_sh = base;
+            tile_cnt[tile] = tot;
+            tile_base[tile] = base;
+        }
+        __syncthreads();
+        if (cntv) {
+            uint64_t pos = base_sh + wbase + (incl - cntv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if ((omask >> e) & 1u) {
+                    if (pos < capacity) {
+                        stage_idx[pos] = (int64_t)(v * 8 + e);
+                        stage_val[pos] = (uint16_t)f32_to_f16_bits(bf16_bits_to_f32(b[e]));
+                    }
+                    ++pos;
+                }
+            }
+        }
+    }
+}
+
+// Exclusive prefix sum of the per-tile outlier counts (one workgroup, tiles in index order).
+__global__ __launch_bounds__(1024) void tile_scan_kernel(const uint32_t* __restrict__ tile_cnt, uint64_t n_tiles,
+                                                          uint64_t* __restrict__ tile_off) {
+    __shared__ uint64_t wsum[16];
+    __shared__ uint64_t carry_sh;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0) carry_sh = 0;
+    __syncthreads();
+    for (uint64_t t0 = 0; t0 < n_tiles; t0 += 1024) {
+        uint64_t t = t0 + threadIdx.x;
+        uint64_t c = t < n_tiles ? tile_cnt[t] : 0;
+        uint64_t incl = c;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            uint64_t u = (uint64_t)__shfl_up((long long)incl, d, 64);
+            if (lane >= (uint32_t)d) incl += u;
+        }
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        uint64_t wbase = 0, tot = 0;
+        for (int k = 0; k < 16; ++k) {
+            uint64_t u = wsum[k];
+            if ((uint32_t)k < wave) wbase += u;
+            tot += u;
+        }
+        uint64_t carry = carry_sh;
+        if (t < n_tiles) tile_off[t] = carry + wbase + incl - c;
+        __syncthreads();
+        if (threadIdx.x == 0) carry_sh = carry + tot;
+        __syncthreads();
+    }
+}
+
+// Move every tile's run from the staging list to its final, globally ascending position.
+__global__ __launch_bounds__(256) void outlier_gather_kernel(const uint32_t* __restrict__ tile_cnt,
+                                                              const uint64_t* __restrict__ tile_base,
+                                                              const uint64_t* __restrict__ tile_off,
+                                                              uint64_t n_tiles, const int64_t* __restrict__ stage_idx,
+                                                              const uint16_t* __restrict__ stage_val,
+                                                              int64_t* __restrict__ out_idx,
+                                                              uint16_t* __restrict__ out_val, uint64_t capacity) {
+    uint64_t t = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= n_tiles) return;
+    uint32_t c = tile_cnt[t];
+    uint64_t src = tile_base[t], dst = tile_off[t];
+    for (uint32_t j = 0; j < c; ++j) {
+        if (src + j < capacity && dst + j < capacity) {
+            out_idx[dst + j] = stage_idx[src + j];
+            out_val[dst + j] = stage_val[src + j];
+        }
+    }
+}
+
+__global__ void zero_u64_kernel(uint64_t* p) { *p = 0; }
+
+// ------------------------------------------------------------------------------------------------ dequantise
+template <int I>
+__global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restrict__ codes,
+                                                          const uint16_t* __restrict__ scales, uint64_t n_vec,
+                                                          CodebookArgs cb, uint4* __restrict__ out) {
+    constexpr int G = I / 8;
+    __shared__ float lv[16];
+    if (threadIdx.x < 16) lv[threadIdx.x] = cb.lv32[threadIdx.x];
+    __syncthreads();
+    uint64_t v = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v >= n_vec) return;
+    uint32_t c = codes[v];
+    float s = f16_bits_to_f32(scales[v / G]);
+    uint32_t o[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        uint32_t lo = f32_to_bf16_rne(s * lv[(c >> (8 * p)) & 15u]);
+        uint32_t hi = f32_to_bf16_rne(s * lv[(c >> (8 * p + 4)) & 15u]);
+        o[p] = lo | (hi << 16);
+    }
+    out[v] = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+__global__ __launch_bounds__(256) void outlier_scatter_kernel(const int64_t* __restrict__ idx,
+                                                               const uint16_t* __restrict__ val, uint64_t k,
+                                                               uint64_t n, uint16_t* __restrict__ out) {
+    uint64_t t = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= k) return;
+    int64_t i = idx[t];
+    if (i < 0 || (uint64_t)i >= n) return;
+    out[i] = (uint16_t)f32_to_bf16_rne(f16_bits_to_f32(val[t]));
+}
+
+// ------------------------------------------------------------------------------------------------ Lloyd step
+// One lane owns a segment of SEG = min(I, 64) consecutive weights; a block spans I/SEG neighbouring lanes.  Per-level
+// sums of the current block live in lane-private LDS columns (no conflicts, no atomics, fixed order) and are folded
+// into per-lane registers with the block weight g once per block.
+template <int I, bool SIGNED, bool OPQ, bool W2>
+__global__ __launch_bounds__(256) void lloyd_kernel(const uint4* __restrict__ w, uint64_t n_seg, CodebookArgs cb,
+                                                     double T2, double* __restrict__ partials) {
+    constexpr int SEG = I < 64 ? I : 64;
+    constexpr int LPB = I / SEG;
+    constexpr int NV = SEG / 8;
+    __shared__ double sx[16 * 256];
+    __shared__ uint32_t cn[16 * 256];
+    __shared__ double cbl[16];
+    __shared__ double red[4][LLOYD_SLOTS];
+    const uint32_t tid = threadIdx.x;
+    if (tid < 16) cbl[tid] = cb.cb64[tid];
+#pragma unroll
+    for (int l = 0; l < 16; ++l) {
+        sx[l * 256 + tid] = 0.0;
+        cn[l * 256 + tid] = 0;
+    }
+    __syncthreads();
+    double num[16], den[16], sse = 0.0;
+    uint32_t cnt[16];
+    uint64_t nout = 0;
+#pragma unroll
+    for (int l = 0; l < 16; ++l) {
+        num[l] = 0.0;
+        den[l] = 0.0;
+        cnt[l] = 0;
+    }
+    const uint64_t stride = (uint64_t)gridDim.x * 256;
+    const uint64_t rounds = (n_seg + stride - 1) / stride;
+    const uint32_t lane_in_block = tid & (LPB - 1);
+    for (uint64_t it = 0; it < rounds; ++it) {
+        const uint64_t seg = it * stride + (uint64_t)blockIdx.x * 256 + tid;
+        const bool active = seg < n_seg;
+        uint32_t r[SEG / 2];
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            uint4 q = active ? w[seg * NV + k] : make_uint4(0, 0, 0, 0);
+            r[4 * k] = q.x;
+            r[4 * k + 1] = q.y;
+            r[4 * k + 2] = q.z;
+            r[4 * k + 3] = q.w;
+        }
+        uint64_t omask = 0;
+        if (OPQ) {
+            double S = 0.0, Q = 0.0;
+#pragma unroll
+            for (int e = 0; e < SEG; ++e) {
+                uint32_t be = (e & 1) ? (r[e >> 1] >> 16) : (r[e >> 1] & 0xffffu);
+                double d = (double)bf16_bits_to_f32(be);
+                S += d;
+                Q = fma(d, d, Q);
+            }
+            S = group_sum_f64<LPB>(S);
+            Q = group_sum_f64<LPB>(Q);
+            double V = fma(-S, S, (double)I * Q);
+            double rhs = T2 * V;
+            constexpr double II1 = (double)I * (double)(I - 1);
+#pragma unroll
+            for (int e = 0; e < SEG; ++e) {
+                uint32_t be = (e & 1) ? (r[e >> 1] >> 16) : (r[e >> 1] & 0xffffu);
+                double d = (double)bf16_bits_to_f32(be);
+                if (V > 0.0 && (d * d) * II1 > rhs) omask |= 1ull << e;
+            }
+        }
+        uint32_t key = 0;
+#pragma unroll
+        for (int e = 0; e < SEG; ++e) {
+            uint32_t be = (e & 1) ? (r[e >> 1] >> 16) : (r[e >> 1] & 0xffffu);
+            if ((omask >> e) & 1ull) be = 0;
+            key = max(key, max_key(be, lane_in_block * SEG + e));
+        }
+        key = group_max_u32<LPB>(key);
+        uint32_t mbits = (key >> 16) | (SIGNED ? ((key & 1u) << 15) : 0u);
+        float m_eff = f16_bits_to_f32(f32_to_f16_bits(bf16_bits_to_f32(mbits)));
+        double g = W2 ? (double)m_eff * (double)m_eff : 1.0;
+        double sse_b = 0.0;
+        if (active) {
+#pragma unroll
+            for (int e = 0; e < SEG; ++e) {
+                if ((omask >> e) & 1ull) continue;
+                uint32_t be = (e & 1) ? (r[e >> 1] >> 16) : (r[e >> 1] & 0xffffu);
+                float f = bf16_bits_to_f32(be);
+                float x = (m_eff == 0.0f) ? 0.0f : f / m_eff;
+                int code = assign_code(x, cb);
+                double xd = (double)x;
+                sx[code * 256 + tid] += xd;
+                cn[code * 256 + tid] += 1;
+                double d = xd - cbl[code];
+                sse_b = fma(d, d, sse_b);
+            }
+            nout += __popcll(omask);
+#pragma unroll
+            for (int l = 0; l < 16; ++l) {
+                double s = sx[l * 256 + tid];
+                uint32_t c = cn[l * 256 + tid];
+                num[l] = fma(g, s, num[l]);
+                den[l] = fma(g, (double)c, den[l]);
+                cnt[l] += c;
+                sx[l * 256 + tid] = 0.0;
+                cn[l * 256 + tid] = 0;
+            }
+            sse = fma(g, sse_b, sse);
+        }
+    }
+    // fixed-order reduction: butterfly inside each wave, then the four waves in index order
+    const uint32_t lane = tid & 63, wave = tid >> 6;
+    auto wave_sum_f64 = [](double v) {
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+        return v;
+    };
+    auto wave_sum_u64 = [](uint64_t v) {
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) v += (uint64_t)__shfl_xor((long long)v, m, 64);
+        return v;
+    };
+#pragma unroll
+    for (int l = 0; l < 16; ++l) {
+        double a = wave_sum_f64(num[l]);
+        double b2 = wave_sum_f64(den[l]);
+        uint64_t c = wave_sum_u64((uint64_t)cnt[l]);
+        if (lane == 0) {
+            red[wave][l] = a;
+            red[wave][16 + l] = b2;
+            red[wave][32 + l] = __longlong_as_double((long long)c);
+        }
+    }
+    {
+        double a = wave_sum_f64(sse);
+        uint64_t c = wave_sum_u64(nout);
+        if (lane == 0) {
+            red[wave][48] = a;
+            red[wave][49] = __longlong_as_double((long long)c);
+        }
+    }
+    __syncthreads();
+    if (tid < 50) {
+        double* dst = partials + (uint64_t)blockIdx.x * LLOYD_SLOTS;
+        bool is_int = (tid >= 32 && tid < 48) || tid == 49;
+        if (is_int) {
+            uint64_t s = 0;
+            for (int k = 0; k < 4; ++k) s += (uint64_t)__double_as_longlong(red[k][tid]);
+            dst[tid] = __longlong_as_double((long long)s);
+        } else {
+            double s = 0.0;
+            for (int k = 0; k < 4; ++k) s += red[k][tid];
+            dst[tid] = s;
+        }
+    }
+}
+
+// Sum the per-workgroup partials in workgroup order into the slot after the last partial.
+__global__ __launch_bounds__(64) void lloyd_final_kernel(double* __restrict__ partials, uint32_t n_part) {
+    uint32_t q = threadIdx.x;
+    if (q >= 50) return;
+    bool is_int = (q >= 32 && q < 48) || q == 49;
+    double* dst = partials + (uint64_t)n_part * LLOYD_SLOTS;
+    if (is_int) {
+        uint64_t s = 0;
+        for (uint32_t p = 0; p < n_part; ++p) s += (uint64_t)__double_as_longlong(partials[(uint64_t)p * LLOYD_SLOTS + q]);
+        dst[q] = __longlong_as_double((long long)s);
+    } else {
+        double s = 0.0;
+        for (uint32_t p = 0; p < n_part; ++p) s += partials[(uint64_t)p * LLOYD_SLOTS + q];
+        dst[q] = s;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------ dispatch
+template <int I, bool SIGNED, bool OPQ>
+void launch_quantize(dim3 grid, hipStream_t s, const uint4* w, uint64_t n_vec, const CodebookArgs& cb, double T2,
+                     uint32_t* codes, uint16_t* scales, uint64_t* total, uint32_t* tc, uint64_t* tb, int64_t* si,
+                     uint16_t* sv, uint64_t cap) {
+    hipLaunchKernelGGL((quantize_kernel<I, SIGNED, OPQ>), grid, dim3(256), 0, s, w, n_vec, cb, T2, codes, scales,
+                       total, tc, tb, si, sv, cap);
+}
+template <int I>
+void launch_quantize_i(bool sg, bool opq, dim3 grid, hipStream_t s, const uint4* w, uint64_t n_vec,
+                       const CodebookArgs& cb, double T2, uint32_t* codes, uint16_t* scales, uint64_t* total,
+                       uint32_t* tc, uint64_t* tb, int64_t* si, uint16_t* sv, uint64_t cap) {
+    if (sg && opq) launch_quantize<I, true, true>(grid, s, w, n_vec, cb, T2, codes, scales, total, tc, tb, si, sv, cap);
+    else if (sg) launch_quantize<I, true, false>(grid, s, w, n_vec, cb, T2, codes, scales, total, tc, tb, si, sv, cap);
+    else if (opq) launch_quantize<I, false, true>(grid, s, w, n_vec, cb, T2, codes, scales, total, tc, tb, si, sv, cap);
+    else launch_quantize<I, false, false>(grid, s, w, n_vec, cb, T2, codes, scales, total, tc, tb, si, sv, cap);
+}
+
+template <int I, bool SIGNED, bool OPQ>
+void launch_lloyd2(bool w2, dim3 grid, hipStream_t s, const uint4* w, uint64_t n_seg, const CodebookArgs& cb,
+                   double T2, double* partials) {
+    if (w2) hipLaunchKernelGGL((lloyd_kernel<I, SIGNED, OPQ, true>), grid, dim3(256), 0, s, w, n_seg, cb, T2, partials);
+    else hipLaunchKernelGGL((lloyd_kernel<I, SIGNED, OPQ, false>), grid, dim3(256), 0, s, w, n_seg, cb, T2, partials);
+}
+template <int I>
+void launch_lloyd_i(bool sg, bool opq, bool w2, dim3 grid, hipStream_t s, const uint4* w, uint64_t n_seg,
+                    const CodebookArgs& cb, double T2, double* partials) {
+    if (sg && opq) launch_lloyd2<I, true, true>(w2, grid, s, w, n_seg, cb, T2, partials);
+    else if (sg) launch_lloyd2<I, true, false>(w2, grid, s, w, n_seg, cb, T2, partials);
+    else if (opq) launch_lloyd2<I, false, true>(w2, grid, s, w, n_seg, cb, T2, partials);
+    else launch_lloyd2<I, false, false>(w2, grid, s, w, n_seg, cb, T2, partials);
+}
+
+}  // namespace
+
+// ================================================================================================ C ABI
+extern "C" {
+
+const char* bof4_last_error(void) { return g_err; }
+int bof4_last_hip_error(void) { return g_hip_err; }
+
+size_t bof4_workspace_bytes(uint64_t n, uint32_t block, uint64_t out_capacity) {
+    if (!valid_block(block) || n == 0 || n % block != 0) return 0;
+    size_t q = quant_ws_layout(n, out_capacity).total;
+    size_t l = lloyd_ws_bytes();
+    return q > l ? q : l;
+}
+
+double bof4_opq_threshold(double q, uint32_t block) {
+    if (!(q > 0.0 && q < 1.0) || block < 2) return NAN;
+    // F_M(t) = (2 G(t) - 1)^I = q  <=>  G(t) = (1 + q^(1/I)) / 2; Newton on the normal cdf written with erfc
+    const double p = 0.5 * (1.0 + std::exp(std::log(q) / (double)block));
+    const double tail = 1.0 - p;  // upper tail probability
+    double t = std::sqrt(-2.0 * std::log(tail));
+    for (int it = 0; it < 100; ++it) {
+        double up = 0.5 * std::erfc(t / std::sqrt(2.0));
+        double pdf = std::exp(-0.5 * t * t) / std::sqrt(2.0 * M_PI);
+        double step = (up - tail) / pdf;
+        t += step;
+        if (std::fabs(step) < 1e-15 * std::fabs(t)) break;
+    }
+    return t;
+}
+
+int bof4_thresholds(const double* cb_host, float* thr_host) {
+    if (!valid_codebook(cb_host) || !thr_host) return fail(BOF4_ERR_ARG, "bof4_thresholds: bad codebook or null output");
+    make_thresholds(cb_host, thr_host);
+    return BOF4_OK;
+}
+
+int bof4_codebook_update(const bof4_lloyd_stats* st, uint16_t pinned_mask, double* cb_host) {
+    if (!st || !cb_host) return fail(BOF4_ERR_ARG, "bof4_codebook_update: null pointer");
+    for (int l = 0; l < 16; ++l) {
+        if ((pinned_mask >> l) & 1u) continue;
+        if (st->den[l] > 0.0) cb_host[l] = st->num[l] / st->den[l];
+    }
+    return BOF4_OK;
+}
+
+int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm, double opq_T,
+                  uint8_t* codes_dev, uint16_t* scales_dev, int64_t* out_idx_dev, uint16_t* out_val_dev,
+                  uint64_t out_capacity, uint64_t* n_outliers_host, void* ws_dev, size_t ws_bytes, void* stream) {
+    if (!w_dev || !codes_dev || !scales_dev || !n_outliers_host) return fail(BOF4_ERR_ARG, "bof4_quantize: null pointer");
+    if (!valid_block(block) || n == 0 || n % block != 0) return fail(BOF4_ERR_ARG, "bof4_quantize: bad n or block");
+    if (!valid_codebook(cb_host)) return fail(BOF4_ERR_ARG, "bof4_quantize: codebook must be 16 finite ascending levels");
+    if (!(opq_T >= 0.0) || !std::isfinite(opq_T)) return fail(BOF4_ERR_ARG, "bof4_quantize: opq_T must be finite and >= 0");
+    if (!aligned(w_dev, 16) || !aligned(codes_dev, 4) || !aligned(scales_dev, 2))
+        return fail(BOF4_ERR_ARG, "bof4_quantize: misaligned pointer");
+    const bool opq = opq_T > 0.0;
+    hipStream_t s = (hipStream_t)stream;
+    const uint64_t n_vec = n / 8;
+    const uint64_t n_tiles = (n + QTILE - 1) / QTILE;
+    if (n_tiles > 0x7fffffffull) return fail(BOF4_ERR_ARG, "bof4_quantize: n too large for one call");
+    CodebookArgs cb = make_codebook_args(cb_host);
+    uint64_t* total = nullptr;
+    uint32_t* tc = nullptr;
+    uint64_t *tb = nullptr, *to = nullptr;
+    int64_t* si = nullptr;
+    uint16_t* sv = nullptr;
+    if (opq) {
+        if (out_capacity > 0 && (!out_idx_dev || !out_val_dev)) return fail(BOF4_ERR_ARG, "bof4_quantize: null outlier buffers");
+        if (!aligned(out_idx_dev, 8) || !aligned(out_val_dev, 2)) return fail(BOF4_ERR_ARG, "bof4_quantize: misaligned outlier buffers");
+        if (!ws_dev || !aligned(ws_dev, 256)) return fail(BOF4_ERR_ARG, "bof4_quantize: workspace null or misaligned");
+        QuantWsLayout L = quant_ws_layout(n, out_capacity);
+        if (ws_bytes < L.total) return fail(BOF4_ERR_WORKSPACE, "bof4_quantize: workspace too small");
+        char* base = (char*)ws_dev;
+        total = (uint64_t*)(base + L.header);
+        tc = (uint32_t*)(base + L.tile_cnt);
+        tb = (uint64_t*)(base + L.tile_base);
+        to = (uint64_t*)(base + L.tile_off);
+        si = (int64_t*)(base + L.stage_idx);
+        sv = (uint16_t*)(base + L.stage_val);
+        hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, s, total);
+    }
+    dim3 grid((uint32_t)n_tiles);
+    const double T2 = opq_T * opq_T;
+    const uint4* w = (const uint4*)w_dev;
+    uint32_t* codes = (uint32_t*)codes_dev;
+    switch (block) {
+        case 32: launch_quantize_i<32>(signed_norm != 0, opq, grid, s, w, n_vec, cb, T2, codes, scales_dev, total, tc, tb, si, sv, out_capacity); break;
+        case 64: launch_quantize_i<64>(signed_norm != 0, opq, grid, s, w, n_vec, cb, T2, codes, scales_dev, total, tc, tb, si, sv, out_capacity); break;
+        case 128: launch_quantize_i<128>(signed_norm != 0, opq, grid, s, w, n_vec, cb, T2, codes, scales_dev, total, tc, tb, si, sv, out_capacity); break;
+        default: launch_quantize_i<256>(signed_norm != 0, opq, grid, s, w, n_vec, cb, T2, codes, scales_dev, total, tc, tb, si, sv, out_capacity); break;
+    }
+    HIP_TRY(hipGetLastError());
+    *n_outliers_host = 0;
+    if (opq) {
+        hipLaunchKernelGGL(tile_scan_kernel, dim3(1), dim3(1024), 0, s, tc, n_tiles, to);
+        hipLaunchKernelGGL(outlier_gather_kernel, dim3((uint32_t)((n_tiles + 255) / 256)), dim3(256), 0, s, tc, tb, to,
+                           n_tiles, si, sv, out_idx_dev, out_val_dev, out_capacity);
+        HIP_TRY(hipGetLastError());
+        uint64_t tot = 0;
+        HIP_TRY(hipMemcpyAsync(&tot, total, 8, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        *n_outliers_host = tot;
+        if (tot > out_capacity) return fail(BOF4_ERR_CAPACITY, "bof4_quantize: outlier buffers too small");
+    }
+    return BOF4_OK;
+}
+
+int bof4_dequantize(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t n, uint32_t block,
+                    const double* cb_host, const int64_t* out_idx_dev, const uint16_t* out_val_dev,
+                    uint64_t n_outliers, void* w_out_dev, void* stream) {
+    if (!codes_dev || !scales_dev || !w_out_dev) return fail(BOF4_ERR_ARG, "bof4_dequantize: null pointer");
+    if (!valid_block(block) || n == 0 || n % block != 0) return fail(BOF4_ERR_ARG, "bof4_dequantize: bad n or block");
+    if (!valid_codebook(cb_host)) return fail(BOF4_ERR_ARG, "bof4_dequantize: codebook must be 16 finite ascending levels");
+    if (n_outliers > 0 && (!out_idx_dev || !out_val_dev)) return fail(BOF4_ERR_ARG, "bof4_dequantize: null outlier buffers");
+    if (!aligned(w_out_dev, 16) || !aligned(codes_dev, 4) || !aligned(scales_dev, 2) || !aligned(out_idx_dev, 8) ||
+        !aligned(out_val_dev, 2))
+        return fail(BOF4_ERR_ARG, "bof4_dequantize: misaligned pointer");
+    hipStream_t s = (hipStream_t)stream;
+    const uint64_t n_vec = n / 8;
+    const uint64_t nb = (n_vec + 255) / 256;
+    if (nb > 0x7fffffffull) return fail(BOF4_ERR_ARG, "bof4_dequantize: n too large for one call");
+    CodebookArgs cb = make_codebook_args(cb_host);
+    dim3 grid((uint32_t)nb);
+    const uint32_t* codes = (const uint32_t*)codes_dev;
+    uint4* out = (uint4*)w_out_dev;
+    switch (block) {
+        case 32: hipLaunchKernelGGL(dequantize_kernel<32>, grid, dim3(256), 0, s, codes, scales_dev, n_vec, cb, out); break;
+        case 64: hipLaunchKernelGGL(dequantize_kernel<64>, grid, dim3(256), 0, s, codes, scales_dev, n_vec, cb, out); break;
+        case 128: hipLaunchKernelGGL(dequantize_kernel<128>, grid, dim3(256), 0, s, codes, scales_dev, n_vec, cb, out); break;
+        default: hipLaunchKernelGGL(dequantize_kernel<256>, grid, dim3(256), 0, s, codes, scales_dev, n_vec, cb, out); break;
+    }
+    if (n_outliers > 0) {
+        uint64_t ob = (n_outliers + 255) / 256;
+        if (ob > 0x7fffffffull) return fail(BOF4_ERR_ARG, "bof4_dequantize: too many outliers for one call");
+        hipLaunchKernelGGL(outlier_scatter_kernel, dim3((uint32_t)ob), dim3(256), 0, s, out_idx_dev, out_val_dev,
+                           n_outliers, n, (uint16_t*)w_out_dev);
+    }
+    HIP_TRY(hipGetLastError());
+    return BOF4_OK;
+}
+
+int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                    double opq_T, int weight_by_max2, bof4_lloyd_stats* out_host, void* ws_dev, size_t ws_bytes,
+                    void* stream) {
+    if (!w_dev || !out_host) return fail(BOF4_ERR_ARG, "bof4_lloyd_step: null pointer");
+    if (!valid_block(block) || n == 0 || n % block != 0) return fail(BOF4_ERR_ARG, "bof4_lloyd_step: bad n or block");
+    if (!valid_codebook(cb_host)) return fail(BOF4_ERR_ARG, "bof4_lloyd_step: codebook must be 16 finite ascending levels");
+    if (!(opq_T >= 0.0) || !std::isfinite(opq_T)) return fail(BOF4_ERR_ARG, "bof4_lloyd_step: opq_T must be finite and >= 0");
+    if (!aligned(w_dev, 16)) return fail(BOF4_ERR_ARG, "bof4_lloyd_step: misaligned weights");
+    if (!ws_dev || !aligned(ws_dev, 256)) return fail(BOF4_ERR_ARG, "bof4_lloyd_step: workspace null or misaligned");
+    if (ws_bytes < lloyd_ws_bytes()) return fail(BOF4_ERR_WORKSPACE, "bof4_lloyd_step: workspace too small");
+    hipStream_t s = (hipStream_t)stream;
+    const uint32_t seg = block < 64 ? block : 64;
+    const uint64_t n_seg = n / seg;
+    uint64_t want = (n_seg + 255) / 256;
+    const uint32_t grid = (uint32_t)(want < LLOYD_MAX_GRID ? want : LLOYD_MAX_GRID);
+    CodebookArgs cb = make_codebook_args(cb_host);
+    double* partials = (double*)ws_dev;
+    const double T2 = opq_T * opq_T;
+    const bool opq = opq_T > 0.0, sg = signed_norm != 0, w2 = weight_by_max2 != 0;
+    const uint4* w = (const uint4*)w_dev;
+    switch (block) {
+        case 32: launch_lloyd_i<32>(sg, opq, w2, dim3(grid), s, w, n_seg, cb, T2, partials); break;
+        case 64: launch_lloyd_i<64>(sg, opq, w2, dim3(grid), s, w, n_seg, cb, T2, partials); break;
+        case 128: launch_lloyd_i<128>(sg, opq, w2, dim3(grid), s, w, n_seg, cb, T2, partials); break;
+        default: launch_lloyd_i<256>(sg, opq, w2, dim3(grid), s, w, n_seg, cb, T2, partials); break;
+    }
+    hipLaunchKernelGGL(lloyd_final_kernel, dim3(1), dim3(64), 0, s, partials, grid);
+    HIP_TRY(hipGetLastError());
+    double fin[LLOYD_SLOTS];
+    HIP_TRY(hipMemcpyAsync(fin, partials + (uint64_t)grid * LLOYD_SLOTS, 50 * 8, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    uint64_t used = 0;
+    for (int l = 0; l < 16; ++l) {
+        out_host->num[l] = fin[l];
+        out_host->den[l] = fin[16 + l];
+        uint64_t c;
+        memcpy(&c, &fin[32 + l], 8);
+        out_host->cnt[l] = c;
+        used += c;
+    }
+    out_host->sse = fin[48];
+    uint64_t no;
+    memcpy(&no, &fin[49], 8);
+    out_host->n_used = used;
+    out_host->n_outliers = no;
+    return BOF4_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,195 @@
+"""GPU parity: the HIP library (called through its C ABI) against the CPU oracle, element by element, on seeded
+inputs small enough for the oracle yet spanning several tiles and a ragged last tile.
+
+Bars: codes, scales, outlier lists, dequantised bf16 and Lloyd counts bit-exact; Lloyd sums, updated levels and
+MSE within relative 1e-9 (binary64 sums whose terms are exact products, added in a different order)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_06653_amd import binding, codebooks, inputs
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+RTOL = 1e-9
+
+
+def cb_for(block, signed):
+    if signed:
+        return codebooks.array(codebooks.BOF4S_MSE[block])
+    return codebooks.array(codebooks.BOF4_MSE_64)
+
+
+def to_np_u16(t):
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def make_weights(rows, cols, seed, outliers=True):
+    wm = inputs.student_t_matrix(rows, cols, 5.0, 0.02, 0.3, seed=seed)
+    if outliers:
+        inputs.plant_outliers(wm, seed=seed + 1, frac=0.002)
+    return wm.reshape(-1)
+
+
+def compare_quantize(w_cpu, block, cb, signed, T):
+    wb = inputs.bits(w_cpu)
+    st, codes, scales, oidx, oval, nout = oracle.quantize(wb, block, cb, signed, opq_T=T)
+    assert st == oracle.OK
+    w = w_cpu.to(DEV)
+    g_codes, g_scales, g_idx, g_val, g_nout = binding.bof4_quantize(w, block, cb, signed, opq_T=T,
+                                                                    out_capacity=max(nout, 1) + 7 if T > 0 else 0)
+    torch.cuda.synchronize()
+    assert g_nout == nout
+    assert np.array_equal(g_scales.view(torch.int16).cpu().numpy().view(np.uint16), scales)
+    assert np.array_equal(g_codes.cpu().numpy(), codes)
+    if T > 0:
+        assert np.array_equal(g_idx.cpu().numpy(), oidx)
+        assert np.array_equal(to_np_u16(g_val), oval)
+    # decoder: same inputs (they are equal), same bits out
+    st, deq = oracle.dequantize(codes, scales, wb.size, block, cb, oidx if T > 0 else None, oval if T > 0 else None)
+    assert st == oracle.OK
+    g_deq = binding.bof4_dequantize(g_codes, g_scales, wb.size, block, cb, g_idx if T > 0 else None,
+                                    g_val if T > 0 else None)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np_u16(g_deq), deq)
+    return nout
+
+
+def assert_stats_close(g, o):
+    assert np.array_equal(g["cnt"], o["cnt"])
+    assert g["n_used"] == o["n_used"] and g["n_outliers"] == o["n_outliers"]
+    assert np.allclose(g["den"], o["den"], rtol=RTOL, atol=0.0)
+    # a region's numerator may cancel (zero level); compare against the region's mass instead of itself
+    scale = np.maximum(np.abs(o["num"]), o["den"] * 1e-3)
+    assert np.all(np.abs(g["num"] - o["num"]) <= RTOL * scale)
+    assert abs(g["sse"] - o["sse"]) <= RTOL * o["sse"]
+
+
+@pytest.mark.parametrize("block", [32, 64, 128, 256])
+@pytest.mark.parametrize("signed", [0, 1])
+@pytest.mark.parametrize("opq", [0, 1])
+def test_quantize_dequantize_bit_exact(block, signed, opq):
+    # 13 x 1024 weights: 6.5 tiles of 2048, ragged tail
+    w = make_weights(13, 1024, seed=100 + block + signed)
+    T = oracle.opq_threshold(0.95, block) if opq else 0.0
+    nout = compare_quantize(w, block, cb_for(block, signed), signed, T)
+    assert (nout > 0) == bool(opq)
+
+
+@pytest.mark.parametrize("block", [32, 64, 128, 256])
+@pytest.mark.parametrize("signed", [0, 1])
+@pytest.mark.parametrize("opq", [0, 1])
+@pytest.mark.parametrize("w2", [1, 0])
+def test_lloyd_step_parity(block, signed, opq, w2):
+    # 301 x 1024 = 308224 weights: more segments than one pass of a small grid, ragged tail in the last round
+    w = make_weights(301, 1024, seed=200 + block)
+    cb = cb_for(block, signed)
+    T = oracle.opq_threshold(0.95, block) if opq else 0.0
+    st, o = oracle.lloyd_step(inputs.bits(w), block, cb, signed, opq_T=T, weight_by_max2=bool(w2))
+    assert st == oracle.OK
+    g = binding.bof4_lloyd_step(w.to(DEV), block, cb, signed, opq_T=T, weight_by_max2=bool(w2))
+    assert_stats_close(g, o)
+    pins = codebooks.PIN_BOF4S if signed else codebooks.PIN_BOF4
+    assert np.allclose(binding.bof4_codebook_update(g, pins, cb), oracle.codebook_update(o, pins, cb), rtol=RTOL, atol=0)
+
+
+def test_config0_twenty_lloyd_iterations_then_quantize():
+    """Workload 0: 1024 x 1024 N(0, 0.02^2), block 64, signed absmax, 20 EM iterations from the quantile start,
+    every step compared; then quantise + pack + dequantise with the final codebook."""
+    w = inputs.gaussian_matrix(1024, 1024, 0.02, seed=0).reshape(-1)
+    wb, wd = inputs.bits(w), w.to(DEV)
+    cb = codebooks.gaussian_quantile_init()
+    ws = binding.alloc_workspace(w.numel(), 64)
+    mse = []
+    for it in range(20):
+        st, o = oracle.lloyd_step(wb, 64, cb, 1)
+        g = binding.bof4_lloyd_step(wd, 64, cb, 1, ws=ws)
+        assert_stats_close(g, o)
+        mse.append(g["sse"] / g["n_used"])
+        cb_o = oracle.codebook_update(o, codebooks.PIN_BOF4S, cb)
+        cb_g = binding.bof4_codebook_update(g, codebooks.PIN_BOF4S, cb)
+        assert np.allclose(cb_g, cb_o, rtol=RTOL, atol=0.0)
+        cb = cb_o
+    assert all(b <= a for a, b in zip(mse, mse[1:]))
+    compare_quantize(w, 64, cb, 1, 0.0)
+
+
+def test_lloyd_is_bit_reproducible():
+    w = make_weights(64, 1024, seed=5).to(DEV)
+    cb = cb_for(64, 1)
+    T = oracle.opq_threshold(0.95, 64)
+    runs = [binding.bof4_lloyd_step(w, 64, cb, 1, opq_T=T) for _ in range(3)]
+    for r in runs[1:]:
+        assert np.array_equal(r["num"], runs[0]["num"]) and np.array_equal(r["den"], runs[0]["den"])
+        assert r["sse"] == runs[0]["sse"] and np.array_equal(r["cnt"], runs[0]["cnt"])
+
+
+def bf16(vals):
+    return torch.tensor(vals, dtype=torch.float32).to(torch.bfloat16)
+
+
+@pytest.mark.parametrize("signed", [0, 1])
+def test_degenerate_blocks(signed):
+    """All-zero block, -0.0, equal magnitudes of opposite sign (lowest index wins), exact mid-point values,
+    a constant block, tiny (subnormal-range) and large block constants, a single block as the whole input."""
+    blocks = []
+    blocks.append(torch.zeros(64))                                        # all zero
+    z = torch.zeros(64); z[3] = -0.0; z[10] = -0.0; blocks.append(z)      # negative zeros only
+    t = torch.zeros(64); t[5] = -1.0; t[9] = 1.0; t[20] = 0.5; blocks.append(t)   # +-tie, negative first
+    t = torch.zeros(64); t[5] = 1.0; t[9] = -1.0; t[20] = -0.5; blocks.append(t)  # +-tie, positive first
+    blocks.append(torch.full((64,), 0.75))                                # constant block
+    blocks.append(torch.linspace(-1, 1, 64) * 3e-6)                       # constant below binary16 normal range
+    blocks.append(torch.linspace(-1, 1, 64) * 2e-8)                       # rounds to zero or one binary16 ulp
+    blocks.append(torch.linspace(-1, 1, 64) * 6.0e4)                      # near binary16 maximum
+    blocks.append(torch.linspace(-1, 1, 64) * 1e-30)                      # constant flushes to zero in binary16
+    g = torch.Generator().manual_seed(1)
+    blocks.append(torch.randn(64, generator=g) * torch.exp2(torch.randint(-40, 10, (64,), generator=g).float()))
+    w = torch.cat(blocks).to(torch.bfloat16)
+    cb = cb_for(64, signed)
+    compare_quantize(w, 64, cb, signed, 0.0)
+    compare_quantize(w, 64, cb, signed, oracle.opq_threshold(0.95, 64))
+    compare_quantize(w[:64], 64, cb, signed, 0.0)
+    st, o = oracle.lloyd_step(inputs.bits(w), 64, cb, signed)
+    assert_stats_close(binding.bof4_lloyd_step(w.to(DEV), 64, cb, signed), o)
+    # dyadic codebook whose mid-points are bf16 numbers: exact ties go to the lower level on both sides
+    dy = np.array([-1, -.75, -.5, -.375, -.25, -.125, -.0625, 0, .0625, .125, .25, .375, .5, .625, .75, 1.0])
+    mids = 0.5 * (dy[:-1] + dy[1:])
+    t = torch.zeros(64)
+    t[:15] = torch.tensor(mids, dtype=torch.float32)
+    t[63] = 1.0
+    compare_quantize(t.to(torch.bfloat16), 64, dy, signed, 0.0)
+
+
+def test_dequantize_arbitrary_codes_and_scales():
+    g = torch.Generator().manual_seed(9)
+    n, block = 64 * 333, 64
+    codes = torch.randint(0, 256, (n // 2,), generator=g, dtype=torch.int32).to(torch.uint8)
+    sc = (torch.randn(n // block, generator=g) * torch.exp2(torch.randint(-30, 14, (n // block,), generator=g).float()))
+    scales = sc.to(torch.float16)
+    cb = cb_for(64, 1)
+    st, deq = oracle.dequantize(codes.numpy(), scales.view(torch.int16).numpy().view(np.uint16), n, block, cb)
+    got = binding.bof4_dequantize(codes.to(DEV), scales.to(DEV), n, block, cb)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np_u16(got), deq)
+
+
+def test_capacity_overflow_and_workspace_errors():
+    w = make_weights(16, 1024, seed=77)
+    T = oracle.opq_threshold(0.95, 64)
+    cb = cb_for(64, 1)
+    full = oracle.quantize(inputs.bits(w), 64, cb, 1, opq_T=T)
+    assert full[5] > 3
+    wd = w.to(DEV)
+    r = binding.bof4_quantize(wd, 64, cb, 1, opq_T=T, out_capacity=3, allow_overflow=True)
+    assert r[4] == full[5]                                   # required count reported
+    assert np.array_equal(r[0].cpu().numpy(), full[1])       # codes and scales still complete
+    with pytest.raises(binding.Bof4Error) as e:
+        binding.bof4_quantize(wd, 64, cb, 1, opq_T=T, out_capacity=3)
+    assert e.value.code == binding.BOF4_ERR_CAPACITY
+    with pytest.raises(binding.Bof4Error) as e:
+        binding.bof4_quantize(wd, 64, cb, 1, opq_T=T, out_capacity=64, ws=torch.empty(256, dtype=torch.uint8, device=DEV))
+    assert e.value.code == binding.BOF4_ERR_WORKSPACE
+    with pytest.raises(binding.Bof4Error) as e:
+        binding.bof4_lloyd_step(wd, 64, cb, 1, ws=torch.empty(256, dtype=torch.uint8, device=DEV))
+    assert e.value.code == binding.BOF4_ERR_WORKSPACE

@@ -1,0 +1,109 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and its pure host functions and
+argument validation behave as the header says.  No compute call is made (no GPU here)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+from scipy.stats import norm
+
+import oracle
+from paper_2505_06653_amd import binding, codebooks
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CB = codebooks.array(codebooks.BOF4S_MSE[64])
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "bof4.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bof4_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = binding.lib()
+    syms = declared_symbols()
+    assert set(syms) == set(binding.EXPORTS)
+    for s in syms:
+        assert hasattr(L, s), s
+
+
+def test_thresholds_are_round_down_midpoints():
+    rng = np.random.default_rng(0)
+    for cb in (CB, codebooks.array(codebooks.BOF4_MSE_64), np.sort(rng.uniform(-1, 1, 16))):
+        thr = binding.bof4_thresholds(cb)
+        mid = 0.5 * (cb[:-1] + cb[1:])
+        assert np.all(thr.astype(np.float64) <= mid)
+        assert np.all(np.nextafter(thr, np.float32(np.inf)).astype(np.float64) > mid)
+        # for every binary32 x around a threshold the kernel's compare equals the binary64 mid-point compare
+        for k in range(15):
+            x = thr[k]
+            for _ in range(4):
+                x = np.nextafter(x, np.float32(-np.inf))
+            for _ in range(9):
+                assert (x > thr[k]) == (float(x) > mid[k])
+                x = np.nextafter(x, np.float32(np.inf))
+
+
+def test_opq_threshold_matches_closed_form_and_oracle():
+    for block in (32, 64, 128, 256):
+        for q in (0.9, 0.95, 0.97, 0.99):
+            t = binding.bof4_opq_threshold(q, block)
+            assert abs(t - norm.ppf((1 + q ** (1.0 / block)) / 2)) < 1e-10
+            assert abs(t - oracle.opq_threshold(q, block)) < 1e-11
+    assert np.isnan(binding.bof4_opq_threshold(1.5, 64))
+
+
+def test_codebook_update_matches_oracle_and_respects_pins():
+    rng = np.random.default_rng(1)
+    stats = {"num": rng.standard_normal(16), "den": rng.uniform(0.5, 2, 16), "cnt": rng.integers(1, 100, 16),
+             "sse": 1.0, "n_used": 100, "n_outliers": 0}
+    stats["den"][3] = 0.0  # empty region keeps its level
+    for mask in (0, codebooks.PIN_BOF4, codebooks.PIN_BOF4S, 0xFFFF):
+        got = binding.bof4_codebook_update(stats, mask, CB)
+        assert np.array_equal(got, oracle.codebook_update(stats, mask, CB))
+        for l in range(16):
+            if (mask >> l) & 1 or l == 3:
+                assert got[l] == CB[l]
+            else:
+                assert got[l] == stats["num"][l] / stats["den"][l]
+
+
+def test_workspace_bytes():
+    assert binding.bof4_workspace_bytes(0, 64) == 0
+    assert binding.bof4_workspace_bytes(100, 64) == 0
+    assert binding.bof4_workspace_bytes(1 << 20, 48) == 0
+    small = binding.bof4_workspace_bytes(1 << 20, 64, 0)
+    big = binding.bof4_workspace_bytes(1 << 30, 64, 1 << 24)
+    assert small > 0 and big > small and big >= (1 << 24) * 10
+
+
+def test_argument_validation_returns_error_codes_without_touching_the_gpu():
+    L = binding.lib()
+    cbp = CB.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+    bad_cb = CB[::-1].copy()
+    bad_cbp = bad_cb.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+    nout = ctypes.c_uint64(0)
+    fake, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1002)
+    q = lambda w, n, blk, c, T, codes, scales: L.bof4_quantize(w, n, blk, c, 1, T, codes, scales, None, None, 0,
+                                                                ctypes.byref(nout), None, 0, None)
+    assert q(None, 1024, 64, cbp, 0.0, fake, fake) == binding.BOF4_ERR_ARG        # null weights
+    assert q(fake, 1000, 64, cbp, 0.0, fake, fake) == binding.BOF4_ERR_ARG        # n not a multiple of block
+    assert q(fake, 0, 64, cbp, 0.0, fake, fake) == binding.BOF4_ERR_ARG           # empty input
+    assert q(fake, 1024, 48, cbp, 0.0, fake, fake) == binding.BOF4_ERR_ARG        # unsupported block size
+    assert q(fake, 1024, 64, bad_cbp, 0.0, fake, fake) == binding.BOF4_ERR_ARG    # unsorted codebook
+    assert q(fake, 1024, 64, cbp, -1.0, fake, fake) == binding.BOF4_ERR_ARG       # negative threshold
+    assert q(odd, 1024, 64, cbp, 0.0, fake, fake) == binding.BOF4_ERR_ARG         # misaligned weights
+    assert q(fake, 1024, 64, cbp, 3.0, fake, fake) == binding.BOF4_ERR_ARG        # OPQ without workspace
+    assert b"workspace" in L.bof4_last_error()
+    st = binding.LloydStats()
+    assert L.bof4_lloyd_step(fake, 1024, 64, cbp, 1, 0.0, 1, ctypes.byref(st), ctypes.c_void_p(0x1010), 1 << 30, None) == binding.BOF4_ERR_ARG
+    ws = ctypes.c_void_p(0x10000)
+    assert L.bof4_lloyd_step(fake, 1024, 64, cbp, 1, 0.0, 1, ctypes.byref(st), ws, 16, None) == binding.BOF4_ERR_WORKSPACE
+    assert L.bof4_dequantize(fake, fake, 1024, 64, cbp, None, None, 5, fake, None) == binding.BOF4_ERR_ARG
+    assert L.bof4_dequantize(fake, fake, 1024, 64, bad_cbp, None, None, 0, fake, None) == binding.BOF4_ERR_ARG
+    nan_cb = CB.copy()
+    nan_cb[4] = np.nan
+    assert L.bof4_thresholds(nan_cb.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+                             (ctypes.c_float * 15)()) == binding.BOF4_ERR_ARG
