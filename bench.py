@@ -54,6 +54,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--replicas", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--opq", type=int, default=1, help="0 runs the path without outlier extraction (not the headline)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (sharding is described in DESIGN.md)",
@@ -64,7 +65,7 @@ def main():
     binding.lib()
 
     cb = codebooks.array(codebooks.BOF4S_MSE[BLOCK])
-    T = binding.bof4_opq_threshold(0.95, BLOCK)
+    T = binding.bof4_opq_threshold(0.95, BLOCK) if args.opq else 0.0
     ws_list = [inputs.flatten(inputs.llama7b_block(seed=50 + r, device=dev)) for r in range(args.replicas)]
     n = ws_list[0].numel()
     cap = n // 64
@@ -87,7 +88,7 @@ def main():
                                                 scales=scales, out_idx=oidx, out_val=oval, ws=ws)
         if events:
             events[1].record()
-        binding.bof4_dequantize(codes, scales, n, BLOCK, cb, gi, gv, out=deq)
+        binding.bof4_dequantize(codes, scales, n, BLOCK, cb, gi if k else None, gv if k else None, out=deq)
         if events:
             events[2].record()
         st = binding.bof4_lloyd_step(w, BLOCK, cb, 1, opq_T=T, ws=ws, raw=True)
@@ -122,7 +123,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16 in, f32 normalise/assign, f64 sums", "data": "synthetic",
         "config": {"workload": "configs[1]: one Llama-7B-shaped block, 202,375,168 bf16 weights, Student-t(5) std 0.02 "
-                               "with log-normal(0,0.3) row scale, block 64, signed absmax (BOF4-S), OPQ q=0.95; "
+                               "with log-normal(0,0.3) row scale, block 64, signed absmax (BOF4-S), OPQ q=0.95" + ("" if args.opq else " OFF") + "; "
                                "step = quantize + dequantize + lloyd_step + codebook_update",
                    "n_weights": n, "block": BLOCK, "outlier_fraction": rho, "replicas": len(ws_list)},
         "lloyd_weights_per_s": n / (ms["lloyd_step"] * 1e-3),

@@ -20,8 +20,11 @@
 #include <cstring>
 
 #include "bof4.h"
+#include "bof4_device.h"
+#include "bof4_segment.h"
 
 namespace {
+using namespace bof4;
 
 // ------------------------------------------------------------------------------------------------ host state
 thread_local char g_err[256] = "";
@@ -53,13 +56,6 @@ bool valid_codebook(const double* cb) {
 }
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-// Codebook-derived constants handed to the kernels by value (kernel argument segment, no device allocation).
-struct CodebookArgs {
-    float thr[16];   // 15 decision thresholds (+1 pad)
-    float lv32[16];  // levels rounded to binary32 (decoder)
-    double cb64[16]; // levels in binary64 (Lloyd error term)
-};
-
 void make_thresholds(const double* cb, float* thr) {
     for (int k = 0; k < 15; ++k) {
         double mid = (cb[k] + cb[k + 1]) * 0.5;
@@ -77,6 +73,50 @@ CodebookArgs make_codebook_args(const double* cb) {
         a.cb64[l] = cb[l];
     }
     return a;
+}
+
+// Host replica of the kernels' bin index (same fused multiply-add, same mask): monotone in x.
+uint32_t host_bin(float x) {
+    float t = std::fmaf(x, BIN_SCALE, BIN_MAGIC);
+    uint32_t u;
+    std::memcpy(&u, &t, 4);
+    return (u & BIN_MASK) >> 3;
+}
+// Builds the per-bin (threshold, base code) table: for x in bin b, code(x) = base[b] + (x > thr[b]).  A bin that
+// two thresholds cut, or a threshold too close to zero, switches the shortcut path off (fast = 0).
+BinTable make_bin_table(const CodebookArgs& cb) {
+    BinTable t;
+    float xlo[33], xhi[33];
+    xlo[0] = -1.0f;
+    xhi[32] = 1.0f;
+    for (uint32_t b = 1; b <= 32; ++b) {  // smallest x whose bin is >= b, by bisection over binary32 values
+        float lo = -1.0f, hi = 1.0f;      // bin(lo) < b <= bin(hi)
+        while (std::nextafterf(lo, hi) != hi) {
+            float mid = 0.5f * lo + 0.5f * hi;
+            if (!(mid > lo && mid < hi)) mid = std::nextafterf(lo, hi);
+            if (host_bin(mid) >= b) hi = mid; else lo = mid;
+        }
+        xlo[b] = hi;
+        xhi[b - 1] = lo;
+    }
+    t.fast = 1;
+    for (uint32_t b = 0; b <= 32; ++b) {
+        uint32_t base = 0, inside = 0;
+        float thr = INFINITY;
+        for (int k = 0; k < 15; ++k) {
+            if (cb.thr[k] < xlo[b]) base++;
+            else if (cb.thr[k] < xhi[b]) { inside++; thr = cb.thr[k]; }
+        }
+        if (inside > 1) t.fast = 0;
+        t.base[b] = base;
+        t.thr[b] = thr;
+    }
+    t.code_of_zero = 0;
+    for (int k = 0; k < 15; ++k) {
+        if (0.0f > cb.thr[k]) t.code_of_zero++;
+        if (std::fabs(cb.thr[k]) < 0x1p-30f) t.fast = 0;
+    }
+    return t;
 }
 
 // ------------------------------------------------------------------------------------------------ workspace
@@ -101,35 +141,15 @@ QuantWsLayout quant_ws_layout(uint64_t n, uint64_t cap) {
     L.total = o;
     return L;
 }
-size_t lloyd_ws_bytes() { return (size_t)(LLOYD_MAX_GRID + 1) * LLOYD_SLOTS * 8; }
+constexpr uint32_t SEG_GRID = 512;       // persistent workgroups of the segment kernels (2 per CU)
+size_t lloyd_ws_bytes() {
+    size_t a = (size_t)(LLOYD_MAX_GRID + 1) * LLOYD_SLOTS * 8;
+    size_t b = ((size_t)SEG_GRID * WAVES_PER_WG + 1) * LLOYD_PART * 8;
+    return a > b ? a : b;
+}
 
 // ------------------------------------------------------------------------------------------------ device helpers
-__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
-
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
-}
-__device__ __forceinline__ uint32_t f32_to_f16_bits(float f) {
-    _Float16 h = (_Float16)f;  // v_cvt_f16_f32, round to nearest even
-    unsigned short s;
-    __builtin_memcpy(&s, &h, 2);
-    return s;
-}
-__device__ __forceinline__ float f16_bits_to_f32(uint32_t b) {
-    unsigned short s = (unsigned short)b;
-    _Float16 h;
-    __builtin_memcpy(&h, &s, 2);
-    return (float)h;
-}
-__device__ __forceinline__ int assign_code(float x, const CodebookArgs& cb) {
-    int code = 0;
-#pragma unroll
-    for (int k = 0; k < 15; ++k) code += (x > cb.thr[k]) ? 1 : 0;
-    return code;
-}
+__device__ __forceinline__ int assign_code(float x, const CodebookArgs& cb) { return assign_code_generic(x, cb); }
 // argmax key: larger magnitude first, then lower index; the sign rides in bit 0 and never decides.
 __device__ __forceinline__ uint32_t max_key(uint32_t bits16, uint32_t idx) {
     return ((bits16 & 0x7fffu) << 16) | ((0x7fffu - idx) << 1) | (bits16 >> 15);
@@ -627,6 +647,31 @@ int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* c
         sv = (uint16_t*)(base + L.stage_val);
         hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, s, total);
     }
+    if (!opq) {
+        BinTable bt = make_bin_table(cb);
+        const uint32_t seg = block < 64 ? block : 64;
+        const uint64_t n_seg = n / seg;
+        const uint64_t tiles = (n_seg + 63) / 64;
+        uint64_t want = (tiles + WAVES_PER_WG - 1) / WAVES_PER_WG;
+        dim3 sgrid((uint32_t)(want < SEG_GRID ? want : SEG_GRID));
+        const uint4* wv = (const uint4*)w_dev;
+        uint32_t* cd = (uint32_t*)codes_dev;
+#define BOF4_LAUNCH_SEGQ(II)                                                                                          \
+    if (bt.fast) hipLaunchKernelGGL((seg_quantize_kernel<II, true>), sgrid, dim3(256), 0, s, wv, n_seg, cb, bt,       \
+                                    signed_norm, cd, scales_dev);                                                     \
+    else hipLaunchKernelGGL((seg_quantize_kernel<II, false>), sgrid, dim3(256), 0, s, wv, n_seg, cb, bt, signed_norm, \
+                            cd, scales_dev);
+        switch (block) {
+            case 32: BOF4_LAUNCH_SEGQ(32) break;
+            case 64: BOF4_LAUNCH_SEGQ(64) break;
+            case 128: BOF4_LAUNCH_SEGQ(128) break;
+            default: BOF4_LAUNCH_SEGQ(256) break;
+        }
+#undef BOF4_LAUNCH_SEGQ
+        HIP_TRY(hipGetLastError());
+        *n_outliers_host = 0;
+        return BOF4_OK;
+    }
     dim3 grid((uint32_t)n_tiles);
     const double T2 = opq_T * opq_T;
     const uint4* w = (const uint4*)w_dev;
@@ -701,12 +746,34 @@ int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double*
     const uint32_t seg = block < 64 ? block : 64;
     const uint64_t n_seg = n / seg;
     uint64_t want = (n_seg + 255) / 256;
-    const uint32_t grid = (uint32_t)(want < LLOYD_MAX_GRID ? want : LLOYD_MAX_GRID);
+    uint32_t grid = (uint32_t)(want < LLOYD_MAX_GRID ? want : LLOYD_MAX_GRID);
     CodebookArgs cb = make_codebook_args(cb_host);
     double* partials = (double*)ws_dev;
     const double T2 = opq_T * opq_T;
     const bool opq = opq_T > 0.0, sg = signed_norm != 0, w2 = weight_by_max2 != 0;
     const uint4* w = (const uint4*)w_dev;
+    if (!opq) {
+        BinTable bt = make_bin_table(cb);
+        const uint64_t tiles = (n_seg + 63) / 64;
+        uint64_t wantg = (tiles + WAVES_PER_WG - 1) / WAVES_PER_WG;
+        const uint32_t sgrid = (uint32_t)(wantg < SEG_GRID ? wantg : SEG_GRID);
+        const uint32_t n_part = sgrid * WAVES_PER_WG;
+#define BOF4_LAUNCH_SEGL(II)                                                                                         \
+    if (bt.fast) hipLaunchKernelGGL((seg_lloyd_kernel<II, true>), dim3(sgrid), dim3(256), 0, s, w, n_seg, cb, bt,    \
+                                    signed_norm, weight_by_max2, partials);                                          \
+    else hipLaunchKernelGGL((seg_lloyd_kernel<II, false>), dim3(sgrid), dim3(256), 0, s, w, n_seg, cb, bt,           \
+                            signed_norm, weight_by_max2, partials);
+        switch (block) {
+            case 32: BOF4_LAUNCH_SEGL(32) break;
+            case 64: BOF4_LAUNCH_SEGL(64) break;
+            case 128: BOF4_LAUNCH_SEGL(128) break;
+            default: BOF4_LAUNCH_SEGL(256) break;
+        }
+#undef BOF4_LAUNCH_SEGL
+        hipLaunchKernelGGL(seg_lloyd_final_kernel, dim3(1), dim3(1024), 0, s, partials, n_part, cb, bt.code_of_zero,
+                           partials + (uint64_t)n_part * LLOYD_PART);
+        grid = n_part;  // the final record sits after the last partial
+    } else {
     switch (block) {
         case 32: launch_lloyd_i<32>(sg, opq, w2, dim3(grid), s, w, n_seg, cb, T2, partials); break;
         case 64: launch_lloyd_i<64>(sg, opq, w2, dim3(grid), s, w, n_seg, cb, T2, partials); break;
@@ -714,6 +781,7 @@ int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double*
         default: launch_lloyd_i<256>(sg, opq, w2, dim3(grid), s, w, n_seg, cb, T2, partials); break;
     }
     hipLaunchKernelGGL(lloyd_final_kernel, dim3(1), dim3(64), 0, s, partials, grid);
+    }
     HIP_TRY(hipGetLastError());
     double fin[LLOYD_SLOTS];
     HIP_TRY(hipMemcpyAsync(fin, partials + (uint64_t)grid * LLOYD_SLOTS, 50 * 8, hipMemcpyDeviceToHost, s));
