@@ -121,8 +121,6 @@ BinTable make_bin_table(const CodebookArgs& cb) {
 
 // ------------------------------------------------------------------------------------------------ workspace
 constexpr uint32_t QTILE = 2048;         // weights per quantise tile (256 threads x 8)
-constexpr uint32_t LLOYD_MAX_GRID = 768; // persistent workgroups of the Lloyd pass
-constexpr uint32_t LLOYD_SLOTS = 56;     // num[16] den[16] cnt[16] sse n_outliers (+pad) per partial
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct QuantWsLayout {
@@ -141,12 +139,31 @@ QuantWsLayout quant_ws_layout(uint64_t n, uint64_t cap) {
     L.total = o;
     return L;
 }
-constexpr uint32_t SEG_GRID = 512;       // persistent workgroups of the segment kernels (2 per CU)
-size_t lloyd_ws_bytes() {
-    size_t a = (size_t)(LLOYD_MAX_GRID + 1) * LLOYD_SLOTS * 8;
-    size_t b = ((size_t)SEG_GRID * WAVES_PER_WG + 1) * LLOYD_PART * 8;
+constexpr uint32_t SEG_GRID = 512;
+struct SegWsLayout {
+    size_t header, wave_count, wave_off, idx, val, total;
+    uint32_t region_cap;
+};       // persistent workgroups of the segment kernels (2 per CU)
+SegWsLayout seg_ws_layout(uint64_t cap) {
+    SegWsLayout L;
+    const uint64_t nw = (uint64_t)SEG_GRID * WAVES_PER_WG;
+    uint64_t rc = 4 * ((cap + nw - 1) / nw) + 64;  // four times the even share: room for uneven outlier density
+    if (rc > 0x7fffffffull) rc = 0x7fffffffull;
+    L.region_cap = (uint32_t)rc;
+    size_t o = 0;
+    L.header = o;     o += 256;
+    L.wave_count = o; o += align_up(nw * 4, 256);
+    L.wave_off = o;   o += align_up(nw * 8, 256);
+    L.idx = o;        o += align_up(nw * rc * 8, 256);
+    L.val = o;        o += align_up(nw * rc * 2, 256);
+    L.total = o;
+    return L;
+}
+size_t quant_ws_bytes(uint64_t n, uint64_t cap) {
+    size_t a = quant_ws_layout(n, cap).total, b = seg_ws_layout(cap).total;
     return a > b ? a : b;
 }
+size_t lloyd_ws_bytes() { return ((size_t)SEG_GRID * WAVES_PER_WG + 1) * LLOYD_PART * 8; }
 
 // ------------------------------------------------------------------------------------------------ device helpers
 __device__ __forceinline__ int assign_code(float x, const CodebookArgs& cb) { return assign_code_generic(x, cb); }
@@ -326,7 +343,7 @@ __global__ __launch_bounds__(256) void outlier_gather_kernel(const uint32_t* __r
     }
 }
 
-__global__ void zero_u64_kernel(uint64_t* p) { *p = 0; }
+__global__ void zero_u64_kernel(uint64_t* p) { p[threadIdx.x] = 0; }
 
 // ------------------------------------------------------------------------------------------------ dequantise
 template <int I>
@@ -361,178 +378,6 @@ __global__ __launch_bounds__(256) void outlier_scatter_kernel(const int64_t* __r
     out[i] = (uint16_t)f32_to_bf16_rne(f16_bits_to_f32(val[t]));
 }
 
-// ------------------------------------------------------------------------------------------------ Lloyd step
-// One lane owns a segment of SEG = min(I, 64) consecutive weights; a block spans I/SEG neighbouring lanes.  Per-level
-// sums of the current block live in lane-private LDS columns (no conflicts, no atomics, fixed order) and are folded
-// into per-lane registers with the block weight g once per block.
-template <int I, bool SIGNED, bool OPQ, bool W2>
-__global__ __launch_bounds__(256) void lloyd_kernel(const uint4* __restrict__ w, uint64_t n_seg, CodebookArgs cb,
-                                                     double T2, double* __restrict__ partials) {
-    constexpr int SEG = I < 64 ? I : 64;
-    constexpr int LPB = I / SEG;
-    constexpr int NV = SEG / 8;
-    __shared__ double sx[16 * 256];
-    __shared__ uint32_t cn[16 * 256];
-    __shared__ double cbl[16];
-    __shared__ double red[4][LLOYD_SLOTS];
-    const uint32_t tid = threadIdx.x;
-    if (tid < 16) cbl[tid] = cb.cb64[tid];
-#pragma unroll
-    for (int l = 0; l < 16; ++l) {
-        sx[l * 256 + tid] = 0.0;
-        cn[l * 256 + tid] = 0;
-    }
-    __syncthreads();
-    double num[16], den[16], sse = 0.0;
-    uint32_t cnt[16];
-    uint64_t nout = 0;
-#pragma unroll
-    for (int l = 0; l < 16; ++l) {
-        num[l] = 0.0;
-        den[l] = 0.0;
-        cnt[l] = 0;
-    }
-    const uint64_t stride = (uint64_t)gridDim.x * 256;
-    const uint64_t rounds = (n_seg + stride - 1) / stride;
-    const uint32_t lane_in_block = tid & (LPB - 1);
-    for (uint64_t it = 0; it < rounds; ++it) {
-        const uint64_t seg = it * stride + (uint64_t)blockIdx.x * 256 + tid;
-        const bool active = seg < n_seg;
-        uint32_t r[SEG / 2];
-#pragma unroll
-        for (int k = 0; k < NV; ++k) {
-            uint4 q = active ? w[seg * NV + k] : make_uint4(0, 0, 0, 0);
-            r[4 * k] = q.x;
-            r[4 * k + 1] = q.y;
-            r[4 * k + 2] = q.z;
-            r[4 * k + 3] = q.w;
-        }
-        uint64_t omask = 0;
-        if (OPQ) {
-            double S = 0.0, Q = 0.0;
-#pragma unroll
-            for (int e = 0; e < SEG; ++e) {
-                uint32_t be = (e & 1) ? (r[e >> 1] >> 16) : (r[e >> 1] & 0xffffu);
-                double d = (double)bf16_bits_to_f32(be);
-                S += d;
-                Q = fma(d, d, Q);
-            }
-            S = group_sum_f64<LPB>(S);
-            Q = group_sum_f64<LPB>(Q);
-            double V = fma(-S, S, (double)I * Q);
-            double rhs = T2 * V;
-            constexpr double II1 = (double)I * (double)(I - 1);
-#pragma unroll
-            for (int e = 0; e < SEG; ++e) {
-                uint32_t be = (e & 1) ? (r[e >> 1] >> 16) : (r[e >> 1] & 0xffffu);
-                double d = (double)bf16_bits_to_f32(be);
-                if (V > 0.0 && (d * d) * II1 > rhs) omask |= 1ull << e;
-            }
-        }
-        uint32_t key = 0;
-#pragma unroll
-        for (int e = 0; e < SEG; ++e) {
-            uint32_t be = (e & 1) ? (r[e >> 1] >> 16) : (r[e >> 1] & 0xffffu);
-            if ((omask >> e) & 1ull) be = 0;
-            key = max(key, max_key(be, lane_in_block * SEG + e));
-        }
-        key = group_max_u32<LPB>(key);
-        uint32_t mbits = (key >> 16) | (SIGNED ? ((key & 1u) << 15) : 0u);
-        float m_eff = f16_bits_to_f32(f32_to_f16_bits(bf16_bits_to_f32(mbits)));
-        double g = W2 ? (double)m_eff * (double)m_eff : 1.0;
-        double sse_b = 0.0;
-        if (active) {
-#pragma unroll
-            for (int e = 0; e < SEG; ++e) {
-                if ((omask >> e) & 1ull) continue;
-                uint32_t be = (e & 1) ? (r[e >> 1] >> 16) : (r[e >> 1] & 0xffffu);
-                float f = bf16_bits_to_f32(be);
-                float x = (m_eff == 0.0f) ? 0.0f : f / m_eff;
-                int code = assign_code(x, cb);
-                double xd = (double)x;
-                sx[code * 256 + tid] += xd;
-                cn[code * 256 + tid] += 1;
-                double d = xd - cbl[code];
-                sse_b = fma(d, d, sse_b);
-            }
-            nout += __popcll(omask);
-#pragma unroll
-            for (int l = 0; l < 16; ++l) {
-                double s = sx[l * 256 + tid];
-                uint32_t c = cn[l * 256 + tid];
-                num[l] = fma(g, s, num[l]);
-                den[l] = fma(g, (double)c, den[l]);
-                cnt[l] += c;
-                sx[l * 256 + tid] = 0.0;
-                cn[l * 256 + tid] = 0;
-            }
-            sse = fma(g, sse_b, sse);
-        }
-    }
-    // fixed-order reduction: butterfly inside each wave, then the four waves in index order
-    const uint32_t lane = tid & 63, wave = tid >> 6;
-    auto wave_sum_f64 = [](double v) {
-#pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-        return v;
-    };
-    auto wave_sum_u64 = [](uint64_t v) {
-#pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) v += (uint64_t)__shfl_xor((long long)v, m, 64);
-        return v;
-    };
-#pragma unroll
-    for (int l = 0; l < 16; ++l) {
-        double a = wave_sum_f64(num[l]);
-        double b2 = wave_sum_f64(den[l]);
-        uint64_t c = wave_sum_u64((uint64_t)cnt[l]);
-        if (lane == 0) {
-            red[wave][l] = a;
-            red[wave][16 + l] = b2;
-            red[wave][32 + l] = __longlong_as_double((long long)c);
-        }
-    }
-    {
-        double a = wave_sum_f64(sse);
-        uint64_t c = wave_sum_u64(nout);
-        if (lane == 0) {
-            red[wave][48] = a;
-            red[wave][49] = __longlong_as_double((long long)c);
-        }
-    }
-    __syncthreads();
-    if (tid < 50) {
-        double* dst = partials + (uint64_t)blockIdx.x * LLOYD_SLOTS;
-        bool is_int = (tid >= 32 && tid < 48) || tid == 49;
-        if (is_int) {
-            uint64_t s = 0;
-            for (int k = 0; k < 4; ++k) s += (uint64_t)__double_as_longlong(red[k][tid]);
-            dst[tid] = __longlong_as_double((long long)s);
-        } else {
-            double s = 0.0;
-            for (int k = 0; k < 4; ++k) s += red[k][tid];
-            dst[tid] = s;
-        }
-    }
-}
-
-// Sum the per-workgroup partials in workgroup order into the slot after the last partial.
-__global__ __launch_bounds__(64) void lloyd_final_kernel(double* __restrict__ partials, uint32_t n_part) {
-    uint32_t q = threadIdx.x;
-    if (q >= 50) return;
-    bool is_int = (q >= 32 && q < 48) || q == 49;
-    double* dst = partials + (uint64_t)n_part * LLOYD_SLOTS;
-    if (is_int) {
-        uint64_t s = 0;
-        for (uint32_t p = 0; p < n_part; ++p) s += (uint64_t)__double_as_longlong(partials[(uint64_t)p * LLOYD_SLOTS + q]);
-        dst[q] = __longlong_as_double((long long)s);
-    } else {
-        double s = 0.0;
-        for (uint32_t p = 0; p < n_part; ++p) s += partials[(uint64_t)p * LLOYD_SLOTS + q];
-        dst[q] = s;
-    }
-}
-
 // ------------------------------------------------------------------------------------------------ dispatch
 template <int I, bool SIGNED, bool OPQ>
 void launch_quantize(dim3 grid, hipStream_t s, const uint4* w, uint64_t n_vec, const CodebookArgs& cb, double T2,
@@ -551,21 +396,6 @@ void launch_quantize_i(bool sg, bool opq, dim3 grid, hipStream_t s, const uint4*
     else launch_quantize<I, false, false>(grid, s, w, n_vec, cb, T2, codes, scales, total, tc, tb, si, sv, cap);
 }
 
-template <int I, bool SIGNED, bool OPQ>
-void launch_lloyd2(bool w2, dim3 grid, hipStream_t s, const uint4* w, uint64_t n_seg, const CodebookArgs& cb,
-                   double T2, double* partials) {
-    if (w2) hipLaunchKernelGGL((lloyd_kernel<I, SIGNED, OPQ, true>), grid, dim3(256), 0, s, w, n_seg, cb, T2, partials);
-    else hipLaunchKernelGGL((lloyd_kernel<I, SIGNED, OPQ, false>), grid, dim3(256), 0, s, w, n_seg, cb, T2, partials);
-}
-template <int I>
-void launch_lloyd_i(bool sg, bool opq, bool w2, dim3 grid, hipStream_t s, const uint4* w, uint64_t n_seg,
-                    const CodebookArgs& cb, double T2, double* partials) {
-    if (sg && opq) launch_lloyd2<I, true, true>(w2, grid, s, w, n_seg, cb, T2, partials);
-    else if (sg) launch_lloyd2<I, true, false>(w2, grid, s, w, n_seg, cb, T2, partials);
-    else if (opq) launch_lloyd2<I, false, true>(w2, grid, s, w, n_seg, cb, T2, partials);
-    else launch_lloyd2<I, false, false>(w2, grid, s, w, n_seg, cb, T2, partials);
-}
-
 }  // namespace
 
 // ================================================================================================ C ABI
@@ -576,7 +406,7 @@ int bof4_last_hip_error(void) { return g_hip_err; }
 
 size_t bof4_workspace_bytes(uint64_t n, uint32_t block, uint64_t out_capacity) {
     if (!valid_block(block) || n == 0 || n % block != 0) return 0;
-    size_t q = quant_ws_layout(n, out_capacity).total;
+    size_t q = quant_ws_bytes(n, out_capacity);
     size_t l = lloyd_ws_bytes();
     return q > l ? q : l;
 }
@@ -623,78 +453,98 @@ int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* c
         return fail(BOF4_ERR_ARG, "bof4_quantize: misaligned pointer");
     const bool opq = opq_T > 0.0;
     hipStream_t s = (hipStream_t)stream;
-    const uint64_t n_vec = n / 8;
     const uint64_t n_tiles = (n + QTILE - 1) / QTILE;
     if (n_tiles > 0x7fffffffull) return fail(BOF4_ERR_ARG, "bof4_quantize: n too large for one call");
-    CodebookArgs cb = make_codebook_args(cb_host);
-    uint64_t* total = nullptr;
-    uint32_t* tc = nullptr;
-    uint64_t *tb = nullptr, *to = nullptr;
-    int64_t* si = nullptr;
-    uint16_t* sv = nullptr;
     if (opq) {
         if (out_capacity > 0 && (!out_idx_dev || !out_val_dev)) return fail(BOF4_ERR_ARG, "bof4_quantize: null outlier buffers");
         if (!aligned(out_idx_dev, 8) || !aligned(out_val_dev, 2)) return fail(BOF4_ERR_ARG, "bof4_quantize: misaligned outlier buffers");
         if (!ws_dev || !aligned(ws_dev, 256)) return fail(BOF4_ERR_ARG, "bof4_quantize: workspace null or misaligned");
-        QuantWsLayout L = quant_ws_layout(n, out_capacity);
-        if (ws_bytes < L.total) return fail(BOF4_ERR_WORKSPACE, "bof4_quantize: workspace too small");
-        char* base = (char*)ws_dev;
-        total = (uint64_t*)(base + L.header);
-        tc = (uint32_t*)(base + L.tile_cnt);
-        tb = (uint64_t*)(base + L.tile_base);
-        to = (uint64_t*)(base + L.tile_off);
-        si = (int64_t*)(base + L.stage_idx);
-        sv = (uint16_t*)(base + L.stage_val);
-        hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, s, total);
+        if (ws_bytes < quant_ws_bytes(n, out_capacity)) return fail(BOF4_ERR_WORKSPACE, "bof4_quantize: workspace too small");
     }
-    if (!opq) {
-        BinTable bt = make_bin_table(cb);
-        const uint32_t seg = block < 64 ? block : 64;
-        const uint64_t n_seg = n / seg;
-        const uint64_t tiles = (n_seg + 63) / 64;
-        uint64_t want = (tiles + WAVES_PER_WG - 1) / WAVES_PER_WG;
-        dim3 sgrid((uint32_t)(want < SEG_GRID ? want : SEG_GRID));
-        const uint4* wv = (const uint4*)w_dev;
-        uint32_t* cd = (uint32_t*)codes_dev;
-#define BOF4_LAUNCH_SEGQ(II)                                                                                          \
-    if (bt.fast) hipLaunchKernelGGL((seg_quantize_kernel<II, true>), sgrid, dim3(256), 0, s, wv, n_seg, cb, bt,       \
-                                    signed_norm, cd, scales_dev);                                                     \
-    else hipLaunchKernelGGL((seg_quantize_kernel<II, false>), sgrid, dim3(256), 0, s, wv, n_seg, cb, bt, signed_norm, \
-                            cd, scales_dev);
-        switch (block) {
-            case 32: BOF4_LAUNCH_SEGQ(32) break;
-            case 64: BOF4_LAUNCH_SEGQ(64) break;
-            case 128: BOF4_LAUNCH_SEGQ(128) break;
-            default: BOF4_LAUNCH_SEGQ(256) break;
-        }
-#undef BOF4_LAUNCH_SEGQ
-        HIP_TRY(hipGetLastError());
-        *n_outliers_host = 0;
-        return BOF4_OK;
-    }
-    dim3 grid((uint32_t)n_tiles);
+    const CodebookArgs cb = make_codebook_args(cb_host);
+    const BinTable bt = make_bin_table(cb);
     const double T2 = opq_T * opq_T;
-    const uint4* w = (const uint4*)w_dev;
-    uint32_t* codes = (uint32_t*)codes_dev;
-    switch (block) {
-        case 32: launch_quantize_i<32>(signed_norm != 0, opq, grid, s, w, n_vec, cb, T2, codes, scales_dev, total, tc, tb, si, sv, out_capacity); break;
-        case 64: launch_quantize_i<64>(signed_norm != 0, opq, grid, s, w, n_vec, cb, T2, codes, scales_dev, total, tc, tb, si, sv, out_capacity); break;
-        case 128: launch_quantize_i<128>(signed_norm != 0, opq, grid, s, w, n_vec, cb, T2, codes, scales_dev, total, tc, tb, si, sv, out_capacity); break;
-        default: launch_quantize_i<256>(signed_norm != 0, opq, grid, s, w, n_vec, cb, T2, codes, scales_dev, total, tc, tb, si, sv, out_capacity); break;
+    const uint32_t seg = block < 64 ? block : 64;
+    const uint64_t n_seg = n / seg;
+    const uint64_t tiles = (n_seg + 63) / 64;
+    const uint64_t want = (tiles + WAVES_PER_WG - 1) / WAVES_PER_WG;
+    const uint32_t sgrid = (uint32_t)(want < SEG_GRID ? want : SEG_GRID);
+    const uint32_t n_waves = sgrid * WAVES_PER_WG;
+    const uint4* wv = (const uint4*)w_dev;
+    uint32_t* cd = (uint32_t*)codes_dev;
+    OutlierStage os = {nullptr, nullptr, nullptr, nullptr, 0};
+    SegWsLayout SL = seg_ws_layout(out_capacity);
+    uint64_t* total_dev = nullptr;
+    uint64_t* wave_off = nullptr;
+    if (opq) {
+        char* base = (char*)ws_dev;
+        total_dev = (uint64_t*)(base + SL.header);
+        os.overflow = (uint32_t*)(base + SL.header + 8);
+        os.wave_count = (uint32_t*)(base + SL.wave_count);
+        wave_off = (uint64_t*)(base + SL.wave_off);
+        os.idx = (int64_t*)(base + SL.idx);
+        os.val = (uint16_t*)(base + SL.val);
+        os.region_cap = SL.region_cap;
+        hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(2), 0, s, total_dev);  // total and overflow flag
     }
+#define BOF4_LAUNCH_SEGQ(II)                                                                                           \
+    if (bt.fast && opq) hipLaunchKernelGGL((seg_quantize_kernel<II, true, true>), dim3(sgrid), dim3(256), 0, s, wv,    \
+                                           n_seg, cb, bt, signed_norm, T2, cd, scales_dev, os);                        \
+    else if (bt.fast) hipLaunchKernelGGL((seg_quantize_kernel<II, true, false>), dim3(sgrid), dim3(256), 0, s, wv,     \
+                                         n_seg, cb, bt, signed_norm, T2, cd, scales_dev, os);                          \
+    else if (opq) hipLaunchKernelGGL((seg_quantize_kernel<II, false, true>), dim3(sgrid), dim3(256), 0, s, wv, n_seg,  \
+                                     cb, bt, signed_norm, T2, cd, scales_dev, os);                                     \
+    else hipLaunchKernelGGL((seg_quantize_kernel<II, false, false>), dim3(sgrid), dim3(256), 0, s, wv, n_seg, cb, bt,  \
+                            signed_norm, T2, cd, scales_dev, os);
+    switch (block) {
+        case 32: BOF4_LAUNCH_SEGQ(32) break;
+        case 64: BOF4_LAUNCH_SEGQ(64) break;
+        case 128: BOF4_LAUNCH_SEGQ(128) break;
+        default: BOF4_LAUNCH_SEGQ(256) break;
+    }
+#undef BOF4_LAUNCH_SEGQ
     HIP_TRY(hipGetLastError());
     *n_outliers_host = 0;
-    if (opq) {
+    if (!opq) return BOF4_OK;
+
+    hipLaunchKernelGGL(seg_outlier_scan_kernel, dim3(1), dim3(1024), 0, s, os.wave_count, n_waves, wave_off, total_dev);
+    hipLaunchKernelGGL(seg_outlier_gather_kernel, dim3(n_waves), dim3(64), 0, s, os, wave_off, out_idx_dev, out_val_dev,
+                       out_capacity);
+    HIP_TRY(hipGetLastError());
+    uint64_t head[2] = {0, 0};
+    HIP_TRY(hipMemcpyAsync(head, total_dev, 16, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    uint64_t tot = head[0];
+    if ((uint32_t)head[1] != 0 && tot <= out_capacity) {
+        // Some wave found more outliers than its staging region holds although the caller's buffers are large enough
+        // (outliers piled up in one stretch of the tensor): redo the extraction with the general, slower kernel that
+        // appends tile by tile through one global counter.
+        QuantWsLayout L = quant_ws_layout(n, out_capacity);
+        char* base = (char*)ws_dev;
+        uint64_t* total = (uint64_t*)(base + L.header);
+        uint32_t* tc = (uint32_t*)(base + L.tile_cnt);
+        uint64_t* tb = (uint64_t*)(base + L.tile_base);
+        uint64_t* to = (uint64_t*)(base + L.tile_off);
+        int64_t* si = (int64_t*)(base + L.stage_idx);
+        uint16_t* sv = (uint16_t*)(base + L.stage_val);
+        hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, s, total);
+        const uint64_t n_vec = n / 8;
+        dim3 grid((uint32_t)n_tiles);
+        switch (block) {
+            case 32: launch_quantize_i<32>(signed_norm != 0, true, grid, s, wv, n_vec, cb, T2, cd, scales_dev, total, tc, tb, si, sv, out_capacity); break;
+            case 64: launch_quantize_i<64>(signed_norm != 0, true, grid, s, wv, n_vec, cb, T2, cd, scales_dev, total, tc, tb, si, sv, out_capacity); break;
+            case 128: launch_quantize_i<128>(signed_norm != 0, true, grid, s, wv, n_vec, cb, T2, cd, scales_dev, total, tc, tb, si, sv, out_capacity); break;
+            default: launch_quantize_i<256>(signed_norm != 0, true, grid, s, wv, n_vec, cb, T2, cd, scales_dev, total, tc, tb, si, sv, out_capacity); break;
+        }
         hipLaunchKernelGGL(tile_scan_kernel, dim3(1), dim3(1024), 0, s, tc, n_tiles, to);
         hipLaunchKernelGGL(outlier_gather_kernel, dim3((uint32_t)((n_tiles + 255) / 256)), dim3(256), 0, s, tc, tb, to,
                            n_tiles, si, sv, out_idx_dev, out_val_dev, out_capacity);
         HIP_TRY(hipGetLastError());
-        uint64_t tot = 0;
         HIP_TRY(hipMemcpyAsync(&tot, total, 8, hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
-        *n_outliers_host = tot;
-        if (tot > out_capacity) return fail(BOF4_ERR_CAPACITY, "bof4_quantize: outlier buffers too small");
     }
+    *n_outliers_host = tot;
+    if (tot > out_capacity) return fail(BOF4_ERR_CAPACITY, "bof4_quantize: outlier buffers too small");
     return BOF4_OK;
 }
 
@@ -745,24 +595,29 @@ int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double*
     hipStream_t s = (hipStream_t)stream;
     const uint32_t seg = block < 64 ? block : 64;
     const uint64_t n_seg = n / seg;
-    uint64_t want = (n_seg + 255) / 256;
-    uint32_t grid = (uint32_t)(want < LLOYD_MAX_GRID ? want : LLOYD_MAX_GRID);
+    uint32_t grid = 0;
     CodebookArgs cb = make_codebook_args(cb_host);
     double* partials = (double*)ws_dev;
     const double T2 = opq_T * opq_T;
-    const bool opq = opq_T > 0.0, sg = signed_norm != 0, w2 = weight_by_max2 != 0;
+    const bool opq = opq_T > 0.0;
     const uint4* w = (const uint4*)w_dev;
-    if (!opq) {
+    {
         BinTable bt = make_bin_table(cb);
         const uint64_t tiles = (n_seg + 63) / 64;
         uint64_t wantg = (tiles + WAVES_PER_WG - 1) / WAVES_PER_WG;
         const uint32_t sgrid = (uint32_t)(wantg < SEG_GRID ? wantg : SEG_GRID);
         const uint32_t n_part = sgrid * WAVES_PER_WG;
-#define BOF4_LAUNCH_SEGL(II)                                                                                         \
-    if (bt.fast) hipLaunchKernelGGL((seg_lloyd_kernel<II, true>), dim3(sgrid), dim3(256), 0, s, w, n_seg, cb, bt,    \
-                                    signed_norm, weight_by_max2, partials);                                          \
-    else hipLaunchKernelGGL((seg_lloyd_kernel<II, false>), dim3(sgrid), dim3(256), 0, s, w, n_seg, cb, bt,           \
-                            signed_norm, weight_by_max2, partials);
+#define BOF4_LAUNCH_SEGL(II)                                                                                           \
+    if (bt.fast && opq) hipLaunchKernelGGL((seg_lloyd_kernel<II, true, true>), dim3(sgrid), dim3(256), 0, s, w, n_seg, \
+                                           cb, bt, signed_norm, weight_by_max2, T2, LLOYD_INC_MUL, LLOYD_INC_ADD,      \
+                                           partials);                                                                  \
+    else if (bt.fast) hipLaunchKernelGGL((seg_lloyd_kernel<II, true, false>), dim3(sgrid), dim3(256), 0, s, w, n_seg,  \
+                                         cb, bt, signed_norm, weight_by_max2, T2, LLOYD_INC_MUL, LLOYD_INC_ADD,        \
+                                         partials);                                                                    \
+    else if (opq) hipLaunchKernelGGL((seg_lloyd_kernel<II, false, true>), dim3(sgrid), dim3(256), 0, s, w, n_seg, cb,  \
+                                     bt, signed_norm, weight_by_max2, T2, LLOYD_INC_MUL, LLOYD_INC_ADD, partials);     \
+    else hipLaunchKernelGGL((seg_lloyd_kernel<II, false, false>), dim3(sgrid), dim3(256), 0, s, w, n_seg, cb, bt,      \
+                            signed_norm, weight_by_max2, T2, LLOYD_INC_MUL, LLOYD_INC_ADD, partials);
         switch (block) {
             case 32: BOF4_LAUNCH_SEGL(32) break;
             case 64: BOF4_LAUNCH_SEGL(64) break;
@@ -773,18 +628,10 @@ int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double*
         hipLaunchKernelGGL(seg_lloyd_final_kernel, dim3(1), dim3(1024), 0, s, partials, n_part, cb, bt.code_of_zero,
                            partials + (uint64_t)n_part * LLOYD_PART);
         grid = n_part;  // the final record sits after the last partial
-    } else {
-    switch (block) {
-        case 32: launch_lloyd_i<32>(sg, opq, w2, dim3(grid), s, w, n_seg, cb, T2, partials); break;
-        case 64: launch_lloyd_i<64>(sg, opq, w2, dim3(grid), s, w, n_seg, cb, T2, partials); break;
-        case 128: launch_lloyd_i<128>(sg, opq, w2, dim3(grid), s, w, n_seg, cb, T2, partials); break;
-        default: launch_lloyd_i<256>(sg, opq, w2, dim3(grid), s, w, n_seg, cb, T2, partials); break;
-    }
-    hipLaunchKernelGGL(lloyd_final_kernel, dim3(1), dim3(64), 0, s, partials, grid);
     }
     HIP_TRY(hipGetLastError());
-    double fin[LLOYD_SLOTS];
-    HIP_TRY(hipMemcpyAsync(fin, partials + (uint64_t)grid * LLOYD_SLOTS, 50 * 8, hipMemcpyDeviceToHost, s));
+    double fin[LLOYD_PART];
+    HIP_TRY(hipMemcpyAsync(fin, partials + (uint64_t)grid * LLOYD_PART, 50 * 8, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     uint64_t used = 0;
     for (int l = 0; l < 16; ++l) {

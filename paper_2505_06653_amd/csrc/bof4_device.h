@@ -86,6 +86,33 @@ __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
     return o;
 }
 
+__device__ __forceinline__ uint32_t pk_sub_i16(uint32_t a, uint32_t b) {
+    s16x2 x, y;
+    __builtin_memcpy(&x, &a, 4);
+    __builtin_memcpy(&y, &b, 4);
+    s16x2 r = x - y;
+    uint32_t o;
+    __builtin_memcpy(&o, &r, 4);
+    return o;
+}
+__device__ __forceinline__ uint32_t pk_sub_u16(uint32_t a, uint32_t b) {  // per-half wrap-around difference
+    u16x2 x, y;
+    __builtin_memcpy(&x, &a, 4);
+    __builtin_memcpy(&y, &b, 4);
+    u16x2 r = x - y;
+    uint32_t o;
+    __builtin_memcpy(&o, &r, 4);
+    return o;
+}
+__device__ __forceinline__ uint32_t pk_sign_mask_i16(uint32_t a) {  // 0xFFFF in every half that is negative
+    s16x2 x;
+    __builtin_memcpy(&x, &a, 4);
+    s16x2 r = x >> 15;
+    uint32_t o;
+    __builtin_memcpy(&o, &r, 4);
+    return o;
+}
+
 // Slow, always-valid nearest-level search.
 __device__ __forceinline__ int assign_code_generic(float x, const CodebookArgs& cb) {
     int code = 0;

@@ -128,28 +128,103 @@ __device__ __forceinline__ void block_constant(const uint32_t (&R)[SegCfg<I>::NR
     }
 }
 
-// ================================================================================================ quantise
-template <int I, bool FAST>
-__global__ __launch_bounds__(256) void seg_quantize_kernel(const uint4* __restrict__ w, uint64_t n_seg,
-                                                            CodebookArgs cb, BinTable bt, int signed_norm,
-                                                            uint32_t* __restrict__ codes,
-                                                            uint16_t* __restrict__ scales) {
+// ---------------------------------------------------------------------------------------------- OPQ (section 3.3)
+// Outlier rule of eq. 9 with the corrected sample deviation of appendix E.1, in the square-root-free binary64 form
+//   w^2 I (I-1) > T^2 V,   V = I sum w^2 - (sum w)^2 = fma(-S, S, I Q).
+// Both sides are monotone in |w|, so per block there is one bfloat16 pattern theta with: outlier <=> |w| > theta.
+// theta is found from an approximate square root and settled with the exact binary64 test on its neighbours, so
+// every element's decision equals the direct evaluation of the inequality.  0x7FFF means "no outliers".
+template <int I>
+__device__ __forceinline__ uint32_t opq_theta(const uint32_t (&R)[SegCfg<I>::NR], double T2) {
     using C = SegCfg<I>;
-    __shared__ __attribute__((aligned(16))) char stage_all[WAVES_PER_WG * C::STAGE_BYTES];
-    __shared__ uint2 tab[33];
+    double S = 0.0, Q = 0.0;
+#pragma unroll
+    for (int e = 0; e < C::SEG; ++e) {
+        double d = (double)seg_f32(R, e);
+        S += d;
+        Q = fma(d, d, Q);
+    }
+#pragma unroll
+    for (int m = 1; m < C::LPB; m <<= 1) {
+        S += __shfl_xor(S, m, 64);
+        Q += __shfl_xor(Q, m, 64);
+    }
+    const double V = fma(-S, S, (double)I * Q);
+    uint32_t theta = 0x7FFFu;
+    if (V > 0.0) {
+        constexpr double II1 = (double)I * (double)(I - 1);
+        const double rhs = T2 * V;
+        const float t = (float)__builtin_sqrt(rhs * (1.0 / II1));  // binary64 root: no under/overflow of tau^2
+        uint32_t b0 = __float_as_uint(t) >> 16;
+        b0 = min(max(b0, 1u), 0x7F7Eu);
+        auto is_out = [&](uint32_t b) {
+            double v = (double)bf16_bits_to_f32(b);
+            return (v * v) * II1 > rhs;
+        };
+        theta = b0 - 1;
+        if (!is_out(b0)) theta = b0;
+        if (!is_out(b0 + 1)) theta = b0 + 1;
+    }
+    return theta;
+}
+// Replace the outliers of the segment by +0 (they then count as x = 0), count them, and note which packed registers
+// held one (bit d of `regmap` for register d).
+template <int I>
+__device__ __forceinline__ void opq_zero_outliers(uint32_t (&R)[SegCfg<I>::NR], uint32_t theta, uint32_t& count,
+                                                  uint32_t& regmap) {
+    using C = SegCfg<I>;
+    const uint32_t th2 = theta * 0x10001u;
+    uint32_t kacc = 0;  // two 16-bit counters
+    regmap = 0;
+#pragma unroll
+    for (int d = C::NR - 1; d >= 0; --d) {
+        uint32_t a = R[d] & 0x7fff7fffu;
+        uint32_t mask = pk_sign_mask_i16(pk_sub_i16(th2, a));  // 0xFFFF in every half with |w| > theta
+        R[d] &= ~mask;
+        kacc = pk_sub_u16(kacc, mask);                         // minus (-1) = plus one, per half
+        regmap = regmap * 2u + (mask != 0u ? 1u : 0u);
+    }
+    count = (kacc & 0xffffu) + (kacc >> 16);
+}
+
+// ================================================================================================ quantise
+// Outlier staging of the quantise kernel: every wave appends the outliers of its (contiguous, ascending) tile range to
+// a region of its own, in ascending flat index, and reports how many it found.  A later pass turns the per-wave
+// counts into offsets and copies the regions into the caller's list.  A wave that finds more than its region holds
+// keeps counting (the count stays exact) and raises `overflow`; the host then repeats the call on the general path.
+struct OutlierStage {
+    int64_t* idx;          // [n_waves * region_cap]
+    uint16_t* val;         // [n_waves * region_cap]
+    uint32_t* wave_count;  // [n_waves]
+    uint32_t* overflow;    // single flag
+    uint32_t region_cap;
+};
+
+template <int I, bool FAST, bool OPQ>
+__global__ __launch_bounds__(256) void seg_quantize_kernel(const uint4* __restrict__ w, uint64_t n_seg,
+                                                            CodebookArgs cb, BinTable bt, int signed_norm, double T2,
+                                                            uint32_t* __restrict__ codes,
+                                                            uint16_t* __restrict__ scales, OutlierStage os) {
+    using C = SegCfg<I>;
+    struct Shared {  // one object, so that the table sits at LDS offset 0 (reachable by an immediate offset)
+        uint2 tab[40];
+        char stage[WAVES_PER_WG * C::STAGE_BYTES];
+    };
+    __shared__ __attribute__((aligned(16))) Shared sh;
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < 33) tab[tid] = make_uint2(__float_as_uint(bt.thr[tid]), bt.base[tid]);
+    if (tid < 33) sh.tab[tid] = make_uint2(__float_as_uint(bt.thr[tid]), bt.base[tid]);
     __syncthreads();
-    char* stage = stage_all + wave * C::STAGE_BYTES;
+    const uint2* tab = sh.tab;
+    char* stage = sh.stage + wave * C::STAGE_BYTES;
     const uint64_t n_vec = n_seg * C::NV;
     const uint64_t n_tiles = (n_seg + 63) / 64;
     const uint64_t n_waves = (uint64_t)gridDim.x * WAVES_PER_WG;
     const uint64_t gw = (uint64_t)blockIdx.x * WAVES_PER_WG + wave;
     const uint64_t t0 = n_tiles * gw / n_waves, t1 = n_tiles * (gw + 1) / n_waves;
-    if (t0 >= t1) return;
+    uint32_t wcount = 0;  // outliers this wave has found so far (wave-uniform)
     uint4 G[C::NV];
     uint32_t R[C::NR];
-    tile_issue_loads<I>(w, t0 * 64 * C::NV, n_vec, lane, G);
+    if (t0 < t1) tile_issue_loads<I>(w, t0 * 64 * C::NV, n_vec, lane, G);
     for (uint64_t t = t0; t < t1; ++t) {
         wave_lds_fence();
         tile_stage<I>(stage, lane, G);
@@ -158,6 +233,11 @@ __global__ __launch_bounds__(256) void seg_quantize_kernel(const uint4* __restri
         tile_fetch<I>(stage, lane, R);
         const uint64_t seg = t * 64 + lane;
         const bool active = seg < n_seg;
+        uint32_t theta = 0x7FFFu, k_out = 0, regmap = 0;
+        if (OPQ) {
+            theta = opq_theta<I>(R, T2);
+            opq_zero_outliers<I>(R, theta, k_out, regmap);
+        }
         uint32_t maxabs, sign;
         block_constant<I>(R, lane, signed_norm != 0, maxabs, sign);
         const float m = bf16_bits_to_f32(maxabs | (sign << 15));
@@ -169,13 +249,18 @@ __global__ __launch_bounds__(256) void seg_quantize_kernel(const uint4* __restri
             const BlockDiv dv = make_block_div(m_eff);
 #pragma unroll
             for (int j = 0; j < C::SEG / 8; ++j) {
+                float x[8];
+                uint2 en[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {  // eight table reads in flight
+                    x[e] = div_fast(seg_f32(R, 8 * j + e), dv);
+                    uint32_t off = __float_as_uint(__builtin_fmaf(x[e], BIN_SCALE, BIN_MAGIC)) & BIN_MASK;
+                    en[e] = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(tab) + off);
+                }
                 uint32_t acc = 0;
 #pragma unroll
                 for (int e = 7; e >= 0; --e) {
-                    float x = div_fast(seg_f32(R, 8 * j + e), dv);
-                    uint32_t off = __float_as_uint(__builtin_fmaf(x, BIN_SCALE, BIN_MAGIC)) & BIN_MASK;
-                    uint2 en = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(tab) + off);
-                    uint32_t code = en.y + (x > __uint_as_float(en.x) ? 1u : 0u);
+                    uint32_t code = en[e].y + (x[e] > __uint_as_float(en[e].x) ? 1u : 0u);
                     acc = (acc << 4) + code;
                 }
                 out[j] = acc;
@@ -199,6 +284,92 @@ __global__ __launch_bounds__(256) void seg_quantize_kernel(const uint4* __restri
             for (int q = 0; q < C::SEG / 32; ++q) dst[q] = make_uint4(out[4 * q], out[4 * q + 1], out[4 * q + 2], out[4 * q + 3]);
             if ((lane & (C::LPB - 1)) == 0) scales[seg / C::LPB] = (uint16_t)s16;
         }
+        if (OPQ) {
+            uint32_t incl = k_out;  // inclusive prefix of the per-lane counts = order of the flat indices
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                uint32_t up = (uint32_t)__shfl_up((int)incl, d, 64);
+                if (lane >= (uint32_t)d) incl += up;
+            }
+            const uint32_t total = (uint32_t)__shfl((int)incl, 63, 64);
+            if (total != 0) {  // wave-uniform
+                uint32_t pos = wcount + incl - k_out;
+                const uint64_t region = gw * (uint64_t)os.region_cap;
+                const char* myseg = stage + lane * C::PITCH;  // the staged tile still holds the original values
+                while (regmap != 0) {
+                    const uint32_t d = (uint32_t)__builtin_ctz(regmap);
+                    regmap &= regmap - 1;
+                    const uint32_t orig = *reinterpret_cast<const uint32_t*>(myseg + 4 * d);
+#pragma unroll
+                    for (uint32_t h = 0; h < 2; ++h) {
+                        const uint32_t b = h ? (orig >> 16) : (orig & 0xffffu);
+                        if ((b & 0x7fffu) > theta) {
+                            if (pos < os.region_cap) {
+                                os.idx[region + pos] = (int64_t)(seg * C::SEG + 2 * d + h);
+                                os.val[region + pos] = (uint16_t)f32_to_f16_bits(bf16_bits_to_f32(b));
+                            }
+                            ++pos;
+                        }
+                    }
+                }
+                wcount += total;
+            }
+        }
+    }
+    if (OPQ && lane == 0) {
+        os.wave_count[gw] = wcount;
+        if (wcount > os.region_cap) atomicOr(os.overflow, 1u);
+    }
+}
+
+// Exclusive prefix sum over the per-wave outlier counts (one workgroup); also publishes the grand total.
+__global__ __launch_bounds__(1024) void seg_outlier_scan_kernel(const uint32_t* __restrict__ wave_count,
+                                                                 uint32_t n_waves, uint64_t* __restrict__ wave_off,
+                                                                 uint64_t* __restrict__ total_out) {
+    __shared__ uint64_t wsum[16];
+    __shared__ uint64_t carry_sh;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0) carry_sh = 0;
+    __syncthreads();
+    for (uint32_t base = 0; base < n_waves; base += 1024) {
+        const uint32_t i = base + threadIdx.x;
+        const uint64_t c = i < n_waves ? wave_count[i] : 0;
+        uint64_t incl = c;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            uint64_t up = (uint64_t)__shfl_up((long long)incl, d, 64);
+            if (lane >= (uint32_t)d) incl += up;
+        }
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        uint64_t wbase = 0, tot = 0;
+        for (int k = 0; k < 16; ++k) {
+            uint64_t u = wsum[k];
+            if ((uint32_t)k < wave) wbase += u;
+            tot += u;
+        }
+        const uint64_t carry = carry_sh;
+        if (i < n_waves) wave_off[i] = carry + wbase + incl - c;
+        __syncthreads();
+        if (threadIdx.x == 0) carry_sh = carry + tot;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *total_out = carry_sh;
+}
+
+// One wave per staging region: copy it to its final place in the caller's (ascending) outlier list.
+__global__ __launch_bounds__(64) void seg_outlier_gather_kernel(OutlierStage os, const uint64_t* __restrict__ wave_off,
+                                                                 int64_t* __restrict__ out_idx,
+                                                                 uint16_t* __restrict__ out_val, uint64_t capacity) {
+    const uint64_t r = blockIdx.x;
+    uint32_t c = os.wave_count[r];
+    if (c > os.region_cap) c = os.region_cap;
+    const uint64_t src = r * (uint64_t)os.region_cap, dst = wave_off[r];
+    for (uint32_t j = threadIdx.x; j < c; j += 64) {
+        if (dst + j < capacity) {
+            out_idx[dst + j] = os.idx[src + j];
+            out_val[dst + j] = os.val[src + j];
+        }
     }
 }
 
@@ -209,34 +380,42 @@ __global__ __launch_bounds__(256) void seg_quantize_kernel(const uint4* __restri
 // integer.  Adding up to 256 of these as integers gives 15 K 2^52 + sum (x + 1) 2^40 with the second term below
 // 2^52, so count K and sum separate again exactly.  Once per block the 16 columns are folded, with the block
 // weight g, into binary64 registers:  A += g sum(x + 1),  den15 += g 15 K,  cnt15 += 15 K.
+// The two constants are passed as kernel arguments (not literals) so that the increment is one three-operand
+// fused multiply-add whose addend register pair is not overwritten.
 constexpr double LLOYD_INC_MUL = 0x1p-1020;
 constexpr double LLOYD_INC_ADD = 0x1p-1008 + 0x1p-1020;
 
-template <int I, bool FAST>
+// Elements per batch of the Lloyd inner loop: the table reads of a batch are issued together, then its adds.
+constexpr int LLOYD_BATCH = 16;
+
+template <int I, bool FAST, bool OPQ>
 __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict__ w, uint64_t n_seg, CodebookArgs cb,
-                                                         BinTable bt, int signed_norm, int weight_by_max2,
+                                                         BinTable bt, int signed_norm, int weight_by_max2, double T2,
+                                                         double inc_mul, double inc_add,
                                                          double* __restrict__ partials) {
     using C = SegCfg<I>;
-    __shared__ __attribute__((aligned(16))) char stage_all[WAVES_PER_WG * C::STAGE_BYTES];
-    __shared__ unsigned long long acc_all[WAVES_PER_WG * 16 * 64];
-    __shared__ uint2 tab[33];
+    struct Shared {  // one object, so that the table sits at LDS offset 0 (reachable by an immediate offset)
+        uint2 tab[40];
+        unsigned long long acc[WAVES_PER_WG * 16 * 64];
+        char stage[WAVES_PER_WG * C::STAGE_BYTES];
+    };
+    __shared__ __attribute__((aligned(16))) Shared sh;
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < 33) tab[tid] = make_uint2(__float_as_uint(bt.thr[tid]), bt.base[tid]);
-    unsigned long long* acc = acc_all + wave * 16 * 64;
+    if (tid < 33) sh.tab[tid] = make_uint2(__float_as_uint(bt.thr[tid]), bt.base[tid]);
+    const uint2* tab = sh.tab;
+    unsigned long long* acc = sh.acc + wave * 16 * 64;
 #pragma unroll
     for (int l = 0; l < 16; ++l) acc[l * 64 + lane] = 0ull;
     __syncthreads();
-    char* stage = stage_all + wave * C::STAGE_BYTES;
-    const uint32_t acc_lane = (uint32_t)(uintptr_t)(acc + lane);  // LDS byte address of this lane's column
-    (void)acc_lane;
+    char* stage = sh.stage + wave * C::STAGE_BYTES;
     const uint64_t n_vec = n_seg * C::NV;
     const uint64_t n_tiles = (n_seg + 63) / 64;
     const uint64_t n_waves = (uint64_t)gridDim.x * WAVES_PER_WG;
     const uint64_t gw = (uint64_t)blockIdx.x * WAVES_PER_WG + wave;
     const uint64_t t0 = n_tiles * gw / n_waves, t1 = n_tiles * (gw + 1) / n_waves;
 
-    double A[16], den15[16], sxx_g = 0.0;
-    uint32_t cnt15[16];
+    double A[16], den15[16], sxx_g = 0.0, kout_g = 0.0;
+    uint32_t cnt15[16], kout = 0;
 #pragma unroll
     for (int l = 0; l < 16; ++l) {
         A[l] = 0.0;
@@ -254,6 +433,11 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
         tile_fetch<I>(stage, lane, R);
         const uint64_t seg = t * 64 + lane;
         const bool active = seg < n_seg;
+        uint32_t k_out = 0;
+        if (OPQ) {
+            uint32_t regmap;
+            opq_zero_outliers<I>(R, opq_theta<I>(R, T2), k_out, regmap);
+        }
         uint32_t maxabs, sign;
         block_constant<I>(R, lane, signed_norm != 0, maxabs, sign);
         const float m = bf16_bits_to_f32(maxabs | (sign << 15));
@@ -265,15 +449,23 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
             if (fast) {
                 const BlockDiv dv = make_block_div(m_eff);
 #pragma unroll
-                for (int e = 0; e < C::SEG; ++e) {
-                    float x = div_fast(seg_f32(R, e), dv);
-                    uint32_t off = __float_as_uint(__builtin_fmaf(x, BIN_SCALE, BIN_MAGIC)) & BIN_MASK;
-                    uint2 en = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(tab) + off);
-                    uint32_t code = en.y + (x > __uint_as_float(en.x) ? 1u : 0u);
-                    double xd = (double)x;
-                    double inc = fma(xd, LLOYD_INC_MUL, LLOYD_INC_ADD);
-                    atomicAdd(&acc[code * 64 + lane], (unsigned long long)__double_as_longlong(inc));
-                    sxx = fma(xd, xd, sxx);
+                for (int b0 = 0; b0 < C::SEG; b0 += LLOYD_BATCH) {
+                    float x[LLOYD_BATCH];
+                    uint2 en[LLOYD_BATCH];
+#pragma unroll
+                    for (int e = 0; e < LLOYD_BATCH; ++e) {  // table reads of a whole batch in flight ...
+                        x[e] = div_fast(seg_f32(R, b0 + e), dv);
+                        uint32_t off = __float_as_uint(__builtin_fmaf(x[e], BIN_SCALE, BIN_MAGIC)) & BIN_MASK;
+                        en[e] = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(tab) + off);
+                    }
+#pragma unroll
+                    for (int e = 0; e < LLOYD_BATCH; ++e) {  // ... before the first LDS add of the batch
+                        uint32_t code = en[e].y + (x[e] > __uint_as_float(en[e].x) ? 1u : 0u);
+                        double xd = (double)x[e];
+                        double inc = fma(xd, inc_mul, inc_add);
+                        atomicAdd(&acc[code * 64 + lane], (unsigned long long)__double_as_longlong(inc));
+                        sxx = fma(xd, xd, sxx);
+                    }
                 }
             } else {
 #pragma unroll
@@ -282,15 +474,20 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
                     float x = (m_eff == 0.0f) ? 0.0f : f / m_eff;
                     uint32_t code = (uint32_t)assign_code_generic(x, cb);
                     double xd = (double)x;
-                    double inc = fma(xd, LLOYD_INC_MUL, LLOYD_INC_ADD);
+                    double inc = fma(xd, inc_mul, inc_add);
                     atomicAdd(&acc[code * 64 + lane], (unsigned long long)__double_as_longlong(inc));
                     sxx = fma(xd, xd, sxx);
                 }
             }
             const double gs = g * 0x1p-40;
+            unsigned long long col[16];
+#pragma unroll
+            for (int l = 0; l < 16; ++l) col[l] = acc[l * 64 + lane];  // 16 reads in flight, then 16 clears
+#pragma unroll
+            for (int l = 0; l < 16; ++l) acc[l * 64 + lane] = 0ull;
 #pragma unroll
             for (int l = 0; l < 16; ++l) {
-                unsigned long long v = atomicExch(&acc[l * 64 + lane], 0ull);
+                unsigned long long v = col[l];
                 uint32_t hi = (uint32_t)(v >> 32), lo = (uint32_t)v;
                 uint32_t k15 = hi >> 20;
                 double D = __hiloint2double((int)((hi & 0xFFFFFu) | 0x43300000u), (int)lo) - 0x1p52;  // sum (x+1) 2^40
@@ -299,6 +496,10 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
                 cnt15[l] += k15;
             }
             sxx_g = fma(g, sxx, sxx_g);
+            if (OPQ) {  // the zeroed outliers went into the sums as x = 0; remember what to take out again
+                kout_g = fma(g, (double)k_out, kout_g);
+                kout += k_out;
+            }
         }
     }
     // fixed-order butterfly inside the wave; lane 0 stores the wave's partial
@@ -320,13 +521,18 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
         }
     }
     {
-        double a = sxx_g;
+        double a = sxx_g, kg = kout_g;
+        unsigned long long kc = kout;
 #pragma unroll
-        for (int mk = 32; mk >= 1; mk >>= 1) a += __shfl_xor(a, mk, 64);
+        for (int mk = 32; mk >= 1; mk >>= 1) {
+            a += __shfl_xor(a, mk, 64);
+            kg += __shfl_xor(kg, mk, 64);
+            kc += (unsigned long long)__shfl_xor((long long)kc, mk, 64);
+        }
         if (lane == 0) {
             dst[48] = a;
-            dst[49] = 0.0;                       // sum of g * (outliers per block): none without OPQ
-            dst[50] = __longlong_as_double(0ll); // outlier count
+            dst[49] = kg;                                  // sum of g * (outliers of the block)
+            dst[50] = __longlong_as_double((long long)kc); // outlier count
         }
     }
 }
@@ -337,46 +543,69 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
 __global__ __launch_bounds__(1024) void seg_lloyd_final_kernel(const double* __restrict__ partials, uint32_t n_part,
                                                                 CodebookArgs cb, uint32_t code_of_zero,
                                                                 double* __restrict__ out) {
+    __shared__ double red[16][LLOYD_PART];
     __shared__ double tot[LLOYD_PART];
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (uint32_t q = wave; q < 51; q += 16) {
+    // lane = quantity, wave w takes partials w, w+16, ... in order (each read is one contiguous record); eight
+    // independent loads are in flight before they are added, in index order
+    if (lane < 51) {
+        const bool is_int = (lane >= 32 && lane < 48) || lane == 50;
+        double s = 0.0;
+        unsigned long long si = 0;
+        for (uint32_t p0 = wave; p0 < n_part; p0 += 16 * 8) {
+            double v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                uint32_t p = p0 + 16 * u;
+                v[u] = p < n_part ? partials[(uint64_t)p * LLOYD_PART + lane] : 0.0;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (is_int) si += (unsigned long long)__double_as_longlong(v[u]);
+                else s += v[u];
+            }
+        }
+        red[wave][lane] = is_int ? __longlong_as_double((long long)si) : s;
+    }
+    __syncthreads();
+    if (threadIdx.x < 51) {
+        const uint32_t q = threadIdx.x;
         const bool is_int = (q >= 32 && q < 48) || q == 50;
         double s = 0.0;
         unsigned long long si = 0;
-        for (uint32_t p = lane; p < n_part; p += 64) {
-            double v = partials[(uint64_t)p * LLOYD_PART + q];
-            if (is_int) si += (unsigned long long)__double_as_longlong(v);
-            else s += v;
+        for (int k = 0; k < 16; ++k) {
+            if (is_int) si += (unsigned long long)__double_as_longlong(red[k][q]);
+            else s += red[k][q];
         }
-#pragma unroll
-        for (int mk = 32; mk >= 1; mk >>= 1) {
-            s += __shfl_xor(s, mk, 64);
-            si += (unsigned long long)__shfl_xor((long long)si, mk, 64);
+        tot[q] = is_int ? __longlong_as_double((long long)si) : s;
+    }
+    __syncthreads();
+    __shared__ double sse_part[16];
+    if (threadIdx.x < 16) {
+        const uint32_t l = threadIdx.x;
+        const double koutg = tot[49];
+        const unsigned long long kout = (unsigned long long)__double_as_longlong(tot[50]);
+        double den = tot[16 + l] * (1.0 / 15.0);
+        double a = tot[l];
+        // 15 K is a multiple of 15 below 2^53: the binary64 quotient is the exact integer
+        unsigned long long c = (unsigned long long)((double)(unsigned long long)__double_as_longlong(tot[32 + l]) / 15.0);
+        if (l == code_of_zero) {  // zeroed outliers were counted as x = 0: take them out again
+            den -= koutg;
+            a -= koutg;
+            c -= kout;
         }
-        if (lane == 0) tot[q] = is_int ? __longlong_as_double((long long)si) : s;
+        double num = a - den;
+        out[l] = num;
+        out[16 + l] = den;
+        out[32 + l] = __longlong_as_double((long long)c);
+        sse_part[l] = cb.cb64[l] * (cb.cb64[l] * den - 2.0 * num);
+        if (l == 0) out[49] = __longlong_as_double((long long)kout);
     }
     __syncthreads();
     if (threadIdx.x == 0) {
         double sse = tot[48];
-        const double koutg = tot[49];
-        const unsigned long long kout = (unsigned long long)__double_as_longlong(tot[50]);
-        for (int l = 0; l < 16; ++l) {
-            double den = tot[16 + l] / 15.0;
-            double a = tot[l];
-            unsigned long long c = (unsigned long long)__double_as_longlong(tot[32 + l]) / 15ull;
-            if ((uint32_t)l == code_of_zero) {  // zeroed outliers were counted as x = 0: take them out again
-                den -= koutg;
-                a -= koutg;
-                c -= kout;
-            }
-            double num = a - den;
-            out[l] = num;
-            out[16 + l] = den;
-            out[32 + l] = __longlong_as_double((long long)c);
-            sse += cb.cb64[l] * (cb.cb64[l] * den - 2.0 * num);
-        }
+        for (int l = 0; l < 16; ++l) sse += sse_part[l];
         out[48] = sse;
-        out[49] = __longlong_as_double((long long)kout);
     }
 }
 

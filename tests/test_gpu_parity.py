@@ -161,6 +161,26 @@ def test_degenerate_blocks(signed):
     compare_quantize(t.to(torch.bfloat16), 64, dy, signed, 0.0)
 
 
+def test_outliers_piled_up_in_one_stretch():
+    """Blocks of a constant plus tiny noise make every element an outlier by the paper's rule (|w| >> sigma_b T).
+    A few hundred such blocks in a row exceed what one wave may stage and send the call down its general path;
+    the result must be the same list."""
+    w = make_weights(301, 1024, seed=31, outliers=False)
+    g = torch.Generator().manual_seed(32)
+    n_flat = 64 * 200
+    w[4096:4096 + n_flat] = (1.0 + 0.004 * torch.randn(n_flat, generator=g)).to(torch.bfloat16)
+    for block in (64, 256):
+        T = oracle.opq_threshold(0.95, block)
+        wb = inputs.bits(w)
+        st, codes, scales, oidx, oval, nout = oracle.quantize(wb, block, cb_for(block, 1), 1, opq_T=T)
+        assert nout > 5000
+        gc, gs, gi, gv, gn = binding.bof4_quantize(w.to(DEV), block, cb_for(block, 1), 1, opq_T=T, out_capacity=nout + 100)
+        assert gn == nout and np.array_equal(gi.cpu().numpy(), oidx) and np.array_equal(to_np_u16(gv), oval)
+        assert np.array_equal(gc.cpu().numpy(), codes) and np.array_equal(to_np_u16(gs), scales)
+        st, o = oracle.lloyd_step(wb, block, cb_for(block, 1), 1, opq_T=T)
+        assert_stats_close(binding.bof4_lloyd_step(w.to(DEV), block, cb_for(block, 1), 1, opq_T=T), o)
+
+
 def test_dequantize_arbitrary_codes_and_scales():
     g = torch.Generator().manual_seed(9)
     n, block = 64 * 333, 64
