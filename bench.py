@@ -26,6 +26,8 @@ from paper_2505_06653_amd import binding, codebooks, inputs  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
 BLOCK = 64
+# measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this command (see profiles/), bytes per launch
+PROFILED_TRAFFIC_BYTES = {"lloyd_step": 406.1e6, "quantize": 526.4e6, "dequantize": 512.3e6}
 
 
 def cpu_baseline(w_sample, cb, T):
@@ -77,6 +79,11 @@ def main():
     ws = binding.alloc_workspace(n, BLOCK, cap, dev)
     names = ("quantize", "dequantize", "lloyd_step")
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    # events the library records right around the main kernel of each call (bof4_time_next_call)
+    kev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    for row in kev:
+        for e in row:
+            e.record()  # creates the HIP handle
     n_out_seen = 0
 
     def step(i, events=None):
@@ -84,13 +91,16 @@ def main():
         w = ws_list[i % len(ws_list)]
         if events:
             events[0].record()
+            binding.bof4_time_next_call(kev[i][0], kev[i][1])
         _, _, gi, gv, k = binding.bof4_quantize(w, BLOCK, cb, 1, opq_T=T, out_capacity=cap, codes=codes,
                                                 scales=scales, out_idx=oidx, out_val=oval, ws=ws)
         if events:
             events[1].record()
+            binding.bof4_time_next_call(kev[i][2], kev[i][3])
         binding.bof4_dequantize(codes, scales, n, BLOCK, cb, gi if k else None, gv if k else None, out=deq)
         if events:
             events[2].record()
+            binding.bof4_time_next_call(kev[i][4], kev[i][5])
         st = binding.bof4_lloyd_step(w, BLOCK, cb, 1, opq_T=T, ws=ws, raw=True)
         if events:
             events[3].record()
@@ -105,18 +115,28 @@ def main():
         step(i, ev[i])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # one plain device copy of known size (2 * n bytes read, 2 * n written), outside the timed region: the reference
+    # against which a counter profile of this same command scales FETCH_SIZE / WRITE_SIZE
+    deq.copy_(ws_list[0])
+    torch.cuda.synchronize()
 
     ms = {nm: float(np.mean([ev[i][k].elapsed_time(ev[i][k + 1]) for i in range(args.steps)]))
           for k, nm in enumerate(names)}
+    kms = {nm: float(np.mean([kev[i][2 * k].elapsed_time(kev[i][2 * k + 1]) for i in range(args.steps)]))
+           for k, nm in enumerate(names)}
     rho = n_out_seen / n
+    # algorithmic bytes per launch = bytes per weight x n (one launch processes the whole tensor)
     alg_bytes = {"quantize": (2.0 + 0.5 + 2.0 / BLOCK + 10.0 * rho) * n,
-                 "dequantize": (0.5 + 2.0 / BLOCK + 10.0 * rho + 2.0) * n,
+                 "dequantize": (0.5 + 2.0 / BLOCK + 2.0) * n,
                  "lloyd_step": 2.0 * n}
-    dominant = max(names, key=lambda k: ms[k])
-    achieved = alg_bytes[dominant] / (ms[dominant] * 1e-3) / 1e9
-    per_call = {nm: {"ms": ms[nm], "GBps_bf16": 2.0 * n / (ms[nm] * 1e-3) / 1e9,
-                     "GBps_algorithmic": alg_bytes[nm] / (ms[nm] * 1e-3) / 1e9,
-                     "hbm_frac": alg_bytes[nm] / (ms[nm] * 1e-3) / 1e9 / HBM_PEAK_GBS} for nm in names}
+    dominant = max(names, key=lambda k: kms[k])
+    achieved = alg_bytes[dominant] / (kms[dominant] * 1e-3) / 1e9
+    per_call = {nm: {"call_ms": ms[nm], "kernel_ms": kms[nm], "GBps_bf16": 2.0 * n / (kms[nm] * 1e-3) / 1e9,
+                     "GBps_algorithmic": alg_bytes[nm] / (kms[nm] * 1e-3) / 1e9,
+                     "hbm_frac": alg_bytes[nm] / (kms[nm] * 1e-3) / 1e9 / HBM_PEAK_GBS} for nm in names}
+    # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counter profiles of this command, scaled by the plain
+    # copy in the same profile (profiles/bench_configs1_opq_hbm_traffic.md); only valid for the default workload
+    traffic = PROFILED_TRAFFIC_BYTES.get(dominant) if args.opq else None
     out = {
         "metric": "GB/s bf16 weights quantized & weights/s per Lloyd step; % of HBM peak",
         "value": 2.0 * n * args.steps / dt / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
@@ -126,10 +146,10 @@ def main():
                                "with log-normal(0,0.3) row scale, block 64, signed absmax (BOF4-S), OPQ q=0.95" + ("" if args.opq else " OFF") + "; "
                                "step = quantize + dequantize + lloyd_step + codebook_update",
                    "n_weights": n, "block": BLOCK, "outlier_fraction": rho, "replicas": len(ws_list)},
-        "lloyd_weights_per_s": n / (ms["lloyd_step"] * 1e-3),
+        "lloyd_weights_per_s": n / (kms["lloyd_step"] * 1e-3),
         "per_call": per_call,
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(ws_list[0][: 1 << 26].cpu(), cb, T)

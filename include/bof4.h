@@ -106,6 +106,12 @@ int bof4_dequantize(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64
                     const double* cb_host, const int64_t* out_idx_dev, const uint16_t* out_val_dev,
                     uint64_t n_outliers, void* w_out_dev, void* stream);
 
+/* Measurement aid: the next bof4_quantize / bof4_dequantize / bof4_lloyd_step call made by this thread records
+ * the caller-owned hipEvent_t `start_event` immediately before and `stop_event` immediately after its main kernel
+ * (the one that streams over the weights), on the call's stream; helper kernels and host synchronisation lie
+ * outside the pair.  The request is consumed by that call.  Pass NULLs to cancel. */
+int bof4_time_next_call(void* start_event, void* stop_event);
+
 const char* bof4_last_error(void);
 int bof4_last_hip_error(void);
 

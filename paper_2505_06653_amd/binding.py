@@ -14,7 +14,8 @@ LIB_PATH = os.path.join(HERE, "libbof4_hip.so")
 
 BOF4_OK, BOF4_ERR_ARG, BOF4_ERR_CAPACITY, BOF4_ERR_WORKSPACE, BOF4_ERR_HIP = 0, -1, -2, -3, -4
 EXPORTS = ("bof4_workspace_bytes", "bof4_opq_threshold", "bof4_thresholds", "bof4_lloyd_step",
-           "bof4_codebook_update", "bof4_quantize", "bof4_dequantize", "bof4_last_error", "bof4_last_hip_error")
+           "bof4_codebook_update", "bof4_quantize", "bof4_dequantize", "bof4_time_next_call", "bof4_last_error",
+           "bof4_last_hip_error")
 
 
 class Bof4Error(RuntimeError):
@@ -62,6 +63,8 @@ def lib():
                                     ctypes.c_size_t, vp]
         L.bof4_dequantize.restype = ctypes.c_int
         L.bof4_dequantize.argtypes = [vp, vp, ctypes.c_uint64, ctypes.c_uint32, f64p, vp, vp, ctypes.c_uint64, vp, vp]
+        L.bof4_time_next_call.restype = ctypes.c_int
+        L.bof4_time_next_call.argtypes = [vp, vp]
         L.bof4_last_error.restype = ctypes.c_char_p
         L.bof4_last_hip_error.restype = ctypes.c_int
         _lib = L
@@ -119,6 +122,12 @@ def bof4_codebook_update(stats, pinned_mask, cb):
     _check(lib().bof4_codebook_update(ctypes.byref(stats), pinned_mask,
                                       cb.ctypes.data_as(ctypes.POINTER(ctypes.c_double))))
     return cb
+
+
+def bof4_time_next_call(start_event, stop_event):
+    """start_event / stop_event: torch.cuda.Event(enable_timing=True) that have been recorded once (so that their
+    HIP handles exist); the next call records them around its main kernel."""
+    _check(lib().bof4_time_next_call(ctypes.c_void_p(start_event.cuda_event), ctypes.c_void_p(stop_event.cuda_event)))
 
 
 def alloc_workspace(n, block, out_capacity=0, device="cuda"):

@@ -29,6 +29,16 @@ using namespace bof4;
 // ------------------------------------------------------------------------------------------------ host state
 thread_local char g_err[256] = "";
 thread_local int g_hip_err = 0;
+// Caller-owned events to be recorded around the main kernel of the next call (bof4_time_next_call).
+thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
+void timing_begin(hipStream_t s) {
+    if (g_ev_start) (void)hipEventRecord(g_ev_start, s);
+}
+void timing_end(hipStream_t s) {
+    if (g_ev_stop) (void)hipEventRecord(g_ev_stop, s);
+    g_ev_start = nullptr;
+    g_ev_stop = nullptr;
+}
 
 int fail(int code, const char* msg) {
     snprintf(g_err, sizeof(g_err), "%s", msg);
@@ -346,6 +356,24 @@ __global__ __launch_bounds__(256) void outlier_gather_kernel(const uint32_t* __r
 __global__ void zero_u64_kernel(uint64_t* p) { p[threadIdx.x] = 0; }
 
 // ------------------------------------------------------------------------------------------------ dequantise
+// One lane decodes 8 codes (one 32-bit load) into 8 bfloat16 (one 16-byte store); a workgroup walks DEQ_VPT chunks of
+// 256 such vectors, all loads first.  w~ = constant * level (section 2.1 eq. 3): one binary32 multiply, rounded to
+// bfloat16 (nearest even) by the hardware conversion.
+#ifndef BOF4_DEQ_VPT
+#define BOF4_DEQ_VPT 4
+#endif
+#ifndef BOF4_DEQ_NT
+#define BOF4_DEQ_NT 1
+#endif
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2_rne(float lo, float hi) {
+    f32x2_t v = {lo, hi};
+    bf16x2_t r = __builtin_convertvector(v, bf16x2_t);
+    uint32_t u;
+    __builtin_memcpy(&u, &r, 4);
+    return u;
+}
 template <int I>
 __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restrict__ codes,
                                                           const uint16_t* __restrict__ scales, uint64_t n_vec,
@@ -354,18 +382,27 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restr
     __shared__ float lv[16];
     if (threadIdx.x < 16) lv[threadIdx.x] = cb.lv32[threadIdx.x];
     __syncthreads();
-    uint64_t v = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-    if (v >= n_vec) return;
-    uint32_t c = codes[v];
-    float s = f16_bits_to_f32(scales[v / G]);
-    uint32_t o[4];
+    const uint64_t base = (uint64_t)blockIdx.x * (256 * BOF4_DEQ_VPT) + threadIdx.x;
+    uint32_t c[BOF4_DEQ_VPT];
+    float s[BOF4_DEQ_VPT];
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        uint32_t lo = f32_to_bf16_rne(s * lv[(c >> (8 * p)) & 15u]);
-        uint32_t hi = f32_to_bf16_rne(s * lv[(c >> (8 * p + 4)) & 15u]);
-        o[p] = lo | (hi << 16);
+    for (int k = 0; k < BOF4_DEQ_VPT; ++k) {
+        const uint64_t v = base + 256 * k;
+        c[k] = v < n_vec ? codes[v] : 0u;
+        s[k] = v < n_vec ? f16_bits_to_f32(scales[v / G]) : 0.0f;
     }
-    out[v] = make_uint4(o[0], o[1], o[2], o[3]);
+#pragma unroll
+    for (int k = 0; k < BOF4_DEQ_VPT; ++k) {
+        const uint64_t v = base + 256 * k;
+        uint32_t o[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+            o[p] = pack_bf16x2_rne(s[k] * lv[(c[k] >> (8 * p)) & 15u], s[k] * lv[(c[k] >> (8 * p + 4)) & 15u]);
+        if (v < n_vec) {
+            if (BOF4_DEQ_NT) store_stream(&out[v], make_uint4(o[0], o[1], o[2], o[3]));
+            else out[v] = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+    }
 }
 
 __global__ __launch_bounds__(256) void outlier_scatter_kernel(const int64_t* __restrict__ idx,
@@ -402,6 +439,11 @@ void launch_quantize_i(bool sg, bool opq, dim3 grid, hipStream_t s, const uint4*
 extern "C" {
 
 const char* bof4_last_error(void) { return g_err; }
+int bof4_time_next_call(void* start_event, void* stop_event) {
+    g_ev_start = (hipEvent_t)start_event;
+    g_ev_stop = (hipEvent_t)stop_event;
+    return BOF4_OK;
+}
 int bof4_last_hip_error(void) { return g_hip_err; }
 
 size_t bof4_workspace_bytes(uint64_t n, uint32_t block, uint64_t out_capacity) {
@@ -487,6 +529,7 @@ int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* c
         os.region_cap = SL.region_cap;
         hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(2), 0, s, total_dev);  // total and overflow flag
     }
+    timing_begin(s);
 #define BOF4_LAUNCH_SEGQ(II)                                                                                           \
     if (bt.fast && opq) hipLaunchKernelGGL((seg_quantize_kernel<II, true, true>), dim3(sgrid), dim3(256), 0, s, wv,    \
                                            n_seg, cb, bt, signed_norm, T2, cd, scales_dev, os);                        \
@@ -503,6 +546,7 @@ int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* c
         default: BOF4_LAUNCH_SEGQ(256) break;
     }
 #undef BOF4_LAUNCH_SEGQ
+    timing_end(s);
     HIP_TRY(hipGetLastError());
     *n_outliers_host = 0;
     if (!opq) return BOF4_OK;
@@ -560,18 +604,20 @@ int bof4_dequantize(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64
         return fail(BOF4_ERR_ARG, "bof4_dequantize: misaligned pointer");
     hipStream_t s = (hipStream_t)stream;
     const uint64_t n_vec = n / 8;
-    const uint64_t nb = (n_vec + 255) / 256;
+    const uint64_t nb = (n_vec + 256 * BOF4_DEQ_VPT - 1) / (256 * BOF4_DEQ_VPT);
     if (nb > 0x7fffffffull) return fail(BOF4_ERR_ARG, "bof4_dequantize: n too large for one call");
     CodebookArgs cb = make_codebook_args(cb_host);
     dim3 grid((uint32_t)nb);
     const uint32_t* codes = (const uint32_t*)codes_dev;
     uint4* out = (uint4*)w_out_dev;
+    timing_begin(s);
     switch (block) {
         case 32: hipLaunchKernelGGL(dequantize_kernel<32>, grid, dim3(256), 0, s, codes, scales_dev, n_vec, cb, out); break;
         case 64: hipLaunchKernelGGL(dequantize_kernel<64>, grid, dim3(256), 0, s, codes, scales_dev, n_vec, cb, out); break;
         case 128: hipLaunchKernelGGL(dequantize_kernel<128>, grid, dim3(256), 0, s, codes, scales_dev, n_vec, cb, out); break;
         default: hipLaunchKernelGGL(dequantize_kernel<256>, grid, dim3(256), 0, s, codes, scales_dev, n_vec, cb, out); break;
     }
+    timing_end(s);
     if (n_outliers > 0) {
         uint64_t ob = (n_outliers + 255) / 256;
         if (ob > 0x7fffffffull) return fail(BOF4_ERR_ARG, "bof4_dequantize: too many outliers for one call");
@@ -607,6 +653,7 @@ int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double*
         uint64_t wantg = (tiles + WAVES_PER_WG - 1) / WAVES_PER_WG;
         const uint32_t sgrid = (uint32_t)(wantg < SEG_GRID ? wantg : SEG_GRID);
         const uint32_t n_part = sgrid * WAVES_PER_WG;
+        timing_begin(s);
 #define BOF4_LAUNCH_SEGL(II)                                                                                           \
     if (bt.fast && opq) hipLaunchKernelGGL((seg_lloyd_kernel<II, true, true>), dim3(sgrid), dim3(256), 0, s, w, n_seg, \
                                            cb, bt, signed_norm, weight_by_max2, T2, LLOYD_INC_MUL, LLOYD_INC_ADD,      \
@@ -625,6 +672,7 @@ int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double*
             default: BOF4_LAUNCH_SEGL(256) break;
         }
 #undef BOF4_LAUNCH_SEGL
+        timing_end(s);
         hipLaunchKernelGGL(seg_lloyd_final_kernel, dim3(1), dim3(1024), 0, s, partials, n_part, cb, bt.code_of_zero,
                            partials + (uint64_t)n_part * LLOYD_PART);
         grid = n_part;  // the final record sits after the last partial

@@ -281,7 +281,8 @@ __global__ __launch_bounds__(256) void seg_quantize_kernel(const uint4* __restri
         if (active) {
             uint4* dst = reinterpret_cast<uint4*>(codes + seg * (C::SEG / 8));
 #pragma unroll
-            for (int q = 0; q < C::SEG / 32; ++q) dst[q] = make_uint4(out[4 * q], out[4 * q + 1], out[4 * q + 2], out[4 * q + 3]);
+            for (int q = 0; q < C::SEG / 32; ++q)
+                store_stream(&dst[q], make_uint4(out[4 * q], out[4 * q + 1], out[4 * q + 2], out[4 * q + 3]));
             if ((lane & (C::LPB - 1)) == 0) scales[seg / C::LPB] = (uint16_t)s16;
         }
         if (OPQ) {
