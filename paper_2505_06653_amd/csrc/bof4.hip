@@ -173,7 +173,7 @@ size_t quant_ws_bytes(uint64_t n, uint64_t cap) {
     size_t a = quant_ws_layout(n, cap).total, b = seg_ws_layout(cap).total;
     return a > b ? a : b;
 }
-size_t lloyd_ws_bytes() { return ((size_t)SEG_GRID * WAVES_PER_WG + 1) * LLOYD_PART * 8; }
+size_t lloyd_ws_bytes() { return ((size_t)SEG_GRID + 1) * LLOYD_PART * 8; }
 
 // ------------------------------------------------------------------------------------------------ device helpers
 __device__ __forceinline__ int assign_code(float x, const CodebookArgs& cb) { return assign_code_generic(x, cb); }
@@ -353,7 +353,7 @@ __global__ __launch_bounds__(256) void outlier_gather_kernel(const uint32_t* __r
     }
 }
 
-__global__ void zero_u64_kernel(uint64_t* p) { p[threadIdx.x] = 0; }
+__global__ void zero_u64_kernel(uint64_t* p) { *p = 0; }
 
 // ------------------------------------------------------------------------------------------------ dequantise
 // One lane decodes 8 codes (one 32-bit load) into 8 bfloat16 (one 16-byte store); a workgroup walks DEQ_VPT chunks of
@@ -514,20 +514,18 @@ int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* c
     const uint32_t n_waves = sgrid * WAVES_PER_WG;
     const uint4* wv = (const uint4*)w_dev;
     uint32_t* cd = (uint32_t*)codes_dev;
-    OutlierStage os = {nullptr, nullptr, nullptr, nullptr, 0};
+    OutlierStage os = {nullptr, nullptr, nullptr, 0};
     SegWsLayout SL = seg_ws_layout(out_capacity);
     uint64_t* total_dev = nullptr;
     uint64_t* wave_off = nullptr;
     if (opq) {
         char* base = (char*)ws_dev;
         total_dev = (uint64_t*)(base + SL.header);
-        os.overflow = (uint32_t*)(base + SL.header + 8);
         os.wave_count = (uint32_t*)(base + SL.wave_count);
         wave_off = (uint64_t*)(base + SL.wave_off);
         os.idx = (int64_t*)(base + SL.idx);
         os.val = (uint16_t*)(base + SL.val);
         os.region_cap = SL.region_cap;
-        hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(2), 0, s, total_dev);  // total and overflow flag
     }
     timing_begin(s);
 #define BOF4_LAUNCH_SEGQ(II)                                                                                           \
@@ -551,7 +549,8 @@ int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* c
     *n_outliers_host = 0;
     if (!opq) return BOF4_OK;
 
-    hipLaunchKernelGGL(seg_outlier_scan_kernel, dim3(1), dim3(1024), 0, s, os.wave_count, n_waves, wave_off, total_dev);
+    hipLaunchKernelGGL(seg_outlier_scan_kernel, dim3(1), dim3(1024), 0, s, os.wave_count, n_waves, os.region_cap, wave_off,
+                       total_dev);
     hipLaunchKernelGGL(seg_outlier_gather_kernel, dim3(n_waves), dim3(64), 0, s, os, wave_off, out_idx_dev, out_val_dev,
                        out_capacity);
     HIP_TRY(hipGetLastError());
@@ -559,7 +558,7 @@ int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* c
     HIP_TRY(hipMemcpyAsync(head, total_dev, 16, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     uint64_t tot = head[0];
-    if ((uint32_t)head[1] != 0 && tot <= out_capacity) {
+    if (head[1] != 0 && tot <= out_capacity) {
         // Some wave found more outliers than its staging region holds although the caller's buffers are large enough
         // (outliers piled up in one stretch of the tensor): redo the extraction with the general, slower kernel that
         // appends tile by tile through one global counter.
@@ -652,7 +651,7 @@ int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double*
         const uint64_t tiles = (n_seg + 63) / 64;
         uint64_t wantg = (tiles + WAVES_PER_WG - 1) / WAVES_PER_WG;
         const uint32_t sgrid = (uint32_t)(wantg < SEG_GRID ? wantg : SEG_GRID);
-        const uint32_t n_part = sgrid * WAVES_PER_WG;
+        const uint32_t n_part = sgrid;  // one partial record per workgroup
         timing_begin(s);
 #define BOF4_LAUNCH_SEGL(II)                                                                                           \
     if (bt.fast && opq) hipLaunchKernelGGL((seg_lloyd_kernel<II, true, true>), dim3(sgrid), dim3(256), 0, s, w, n_seg, \

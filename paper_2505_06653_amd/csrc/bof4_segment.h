@@ -169,7 +169,7 @@ __device__ __forceinline__ uint32_t opq_theta(const uint32_t (&R)[SegCfg<I>::NR]
 }
 // Replace the outliers of the segment by +0 (they then count as x = 0), count them, and note which packed registers
 // held one (bit d of `regmap` for register d).
-template <int I>
+template <int I, bool WANT_MAP>
 __device__ __forceinline__ void opq_zero_outliers(uint32_t (&R)[SegCfg<I>::NR], uint32_t theta, uint32_t& count,
                                                   uint32_t& regmap) {
     using C = SegCfg<I>;
@@ -182,7 +182,7 @@ __device__ __forceinline__ void opq_zero_outliers(uint32_t (&R)[SegCfg<I>::NR], 
         uint32_t mask = pk_sign_mask_i16(pk_sub_i16(th2, a));  // 0xFFFF in every half with |w| > theta
         R[d] &= ~mask;
         kacc = pk_sub_u16(kacc, mask);                         // minus (-1) = plus one, per half
-        regmap = regmap * 2u + (mask != 0u ? 1u : 0u);
+        if (WANT_MAP) regmap = regmap * 2u + (mask != 0u ? 1u : 0u);
     }
     count = (kacc & 0xffffu) + (kacc >> 16);
 }
@@ -191,12 +191,11 @@ __device__ __forceinline__ void opq_zero_outliers(uint32_t (&R)[SegCfg<I>::NR], 
 // Outlier staging of the quantise kernel: every wave appends the outliers of its (contiguous, ascending) tile range to
 // a region of its own, in ascending flat index, and reports how many it found.  A later pass turns the per-wave
 // counts into offsets and copies the regions into the caller's list.  A wave that finds more than its region holds
-// keeps counting (the count stays exact) and raises `overflow`; the host then repeats the call on the general path.
+// keeps counting (the count stays exact); the scan pass notices it and the host repeats the call on the general path.
 struct OutlierStage {
     int64_t* idx;          // [n_waves * region_cap]
     uint16_t* val;         // [n_waves * region_cap]
     uint32_t* wave_count;  // [n_waves]
-    uint32_t* overflow;    // single flag
     uint32_t region_cap;
 };
 
@@ -236,7 +235,7 @@ __global__ __launch_bounds__(256) void seg_quantize_kernel(const uint4* __restri
         uint32_t theta = 0x7FFFu, k_out = 0, regmap = 0;
         if (OPQ) {
             theta = opq_theta<I>(R, T2);
-            opq_zero_outliers<I>(R, theta, k_out, regmap);
+            opq_zero_outliers<I, true>(R, theta, k_out, regmap);
         }
         uint32_t maxabs, sign;
         block_constant<I>(R, lane, signed_norm != 0, maxabs, sign);
@@ -317,24 +316,26 @@ __global__ __launch_bounds__(256) void seg_quantize_kernel(const uint4* __restri
             }
         }
     }
-    if (OPQ && lane == 0) {
-        os.wave_count[gw] = wcount;
-        if (wcount > os.region_cap) atomicOr(os.overflow, 1u);
-    }
+    if (OPQ && lane == 0) os.wave_count[gw] = wcount;
 }
 
 // Exclusive prefix sum over the per-wave outlier counts (one workgroup); also publishes the grand total.
+// total_out[0] = number of outliers, total_out[1] = 1 if some wave overflowed its staging region.
 __global__ __launch_bounds__(1024) void seg_outlier_scan_kernel(const uint32_t* __restrict__ wave_count,
-                                                                 uint32_t n_waves, uint64_t* __restrict__ wave_off,
+                                                                 uint32_t n_waves, uint32_t region_cap,
+                                                                 uint64_t* __restrict__ wave_off,
                                                                  uint64_t* __restrict__ total_out) {
     __shared__ uint64_t wsum[16];
     __shared__ uint64_t carry_sh;
+    __shared__ uint32_t over_sh;
+    if (threadIdx.x == 0) over_sh = 0;
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (threadIdx.x == 0) carry_sh = 0;
     __syncthreads();
     for (uint32_t base = 0; base < n_waves; base += 1024) {
         const uint32_t i = base + threadIdx.x;
         const uint64_t c = i < n_waves ? wave_count[i] : 0;
+        if (c > region_cap) over_sh = 1;  // benign race: every writer stores 1
         uint64_t incl = c;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
@@ -355,7 +356,10 @@ __global__ __launch_bounds__(1024) void seg_outlier_scan_kernel(const uint32_t* 
         if (threadIdx.x == 0) carry_sh = carry + tot;
         __syncthreads();
     }
-    if (threadIdx.x == 0) *total_out = carry_sh;
+    if (threadIdx.x == 0) {
+        total_out[0] = carry_sh;
+        total_out[1] = over_sh;
+    }
 }
 
 // One wave per staging region: copy it to its final place in the caller's (ascending) outlier list.
@@ -437,7 +441,7 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
         uint32_t k_out = 0;
         if (OPQ) {
             uint32_t regmap;
-            opq_zero_outliers<I>(R, opq_theta<I>(R, T2), k_out, regmap);
+            opq_zero_outliers<I, false>(R, opq_theta<I>(R, T2), k_out, regmap);
         }
         uint32_t maxabs, sign;
         block_constant<I>(R, lane, signed_norm != 0, maxabs, sign);
@@ -503,8 +507,9 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
             }
         }
     }
-    // fixed-order butterfly inside the wave; lane 0 stores the wave's partial
-    double* dst = partials + gw * LLOYD_PART;
+    // fixed-order butterfly inside the wave, then the four waves of the workgroup in wave order
+    __shared__ double wave_totals[WAVES_PER_WG * LLOYD_PART];
+    double* wtot = wave_totals + wave * LLOYD_PART;
 #pragma unroll
     for (int l = 0; l < 16; ++l) {
         double a = A[l], d = den15[l];
@@ -516,9 +521,9 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
             c += (unsigned long long)__shfl_xor((long long)c, mk, 64);
         }
         if (lane == 0) {
-            dst[l] = a;
-            dst[16 + l] = d;
-            dst[32 + l] = __longlong_as_double((long long)c);
+            wtot[l] = a;
+            wtot[16 + l] = d;
+            wtot[32 + l] = __longlong_as_double((long long)c);
         }
     }
     {
@@ -531,10 +536,22 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
             kc += (unsigned long long)__shfl_xor((long long)kc, mk, 64);
         }
         if (lane == 0) {
-            dst[48] = a;
-            dst[49] = kg;                                  // sum of g * (outliers of the block)
-            dst[50] = __longlong_as_double((long long)kc); // outlier count
+            wtot[48] = a;
+            wtot[49] = kg;                                  // sum of g * (outliers of the block)
+            wtot[50] = __longlong_as_double((long long)kc); // outlier count
         }
+    }
+    __syncthreads();
+    if (tid < 51) {
+        const double* all = wave_totals;
+        const bool is_int = (tid >= 32 && tid < 48) || tid == 50;
+        double sd = 0.0;
+        unsigned long long si = 0;
+        for (int k = 0; k < WAVES_PER_WG; ++k) {
+            if (is_int) si += (unsigned long long)__double_as_longlong(all[k * LLOYD_PART + tid]);
+            else sd += all[k * LLOYD_PART + tid];
+        }
+        partials[(uint64_t)blockIdx.x * LLOYD_PART + tid] = is_int ? __longlong_as_double((long long)si) : sd;
     }
 }
 
