@@ -149,14 +149,18 @@ QuantWsLayout quant_ws_layout(uint64_t n, uint64_t cap) {
     L.total = o;
     return L;
 }
-constexpr uint32_t SEG_GRID = 512;
+#ifndef BOF4_QUANT_GRID
+#define BOF4_QUANT_GRID 512
+#endif
+constexpr uint32_t SEG_GRID = 512;              // persistent workgroups of the Lloyd kernel (2 per CU, LDS-bound)
+constexpr uint32_t QUANT_GRID = BOF4_QUANT_GRID;  // persistent workgroups of the quantise kernel
 struct SegWsLayout {
     size_t header, wave_count, wave_off, idx, val, total;
     uint32_t region_cap;
 };       // persistent workgroups of the segment kernels (2 per CU)
 SegWsLayout seg_ws_layout(uint64_t cap) {
     SegWsLayout L;
-    const uint64_t nw = (uint64_t)SEG_GRID * WAVES_PER_WG;
+    const uint64_t nw = (uint64_t)QUANT_GRID * WAVES_PER_WG;
     uint64_t rc = 4 * ((cap + nw - 1) / nw) + 64;  // four times the even share: room for uneven outlier density
     if (rc > 0x7fffffffull) rc = 0x7fffffffull;
     L.region_cap = (uint32_t)rc;
@@ -510,7 +514,7 @@ int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* c
     const uint64_t n_seg = n / seg;
     const uint64_t tiles = (n_seg + 63) / 64;
     const uint64_t want = (tiles + WAVES_PER_WG - 1) / WAVES_PER_WG;
-    const uint32_t sgrid = (uint32_t)(want < SEG_GRID ? want : SEG_GRID);
+    const uint32_t sgrid = (uint32_t)(want < QUANT_GRID ? want : QUANT_GRID);
     const uint32_t n_waves = sgrid * WAVES_PER_WG;
     const uint4* wv = (const uint4*)w_dev;
     uint32_t* cd = (uint32_t*)codes_dev;

@@ -391,7 +391,10 @@ constexpr double LLOYD_INC_MUL = 0x1p-1020;
 constexpr double LLOYD_INC_ADD = 0x1p-1008 + 0x1p-1020;
 
 // Elements per batch of the Lloyd inner loop: the table reads of a batch are issued together, then its adds.
-constexpr int LLOYD_BATCH = 16;
+#ifndef BOF4_LLOYD_BATCH
+#define BOF4_LLOYD_BATCH 16
+#endif
+constexpr int LLOYD_BATCH = BOF4_LLOYD_BATCH;
 
 template <int I, bool FAST, bool OPQ>
 __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict__ w, uint64_t n_seg, CodebookArgs cb,
@@ -487,9 +490,7 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
             const double gs = g * 0x1p-40;
             unsigned long long col[16];
 #pragma unroll
-            for (int l = 0; l < 16; ++l) col[l] = acc[l * 64 + lane];  // 16 reads in flight, then 16 clears
-#pragma unroll
-            for (int l = 0; l < 16; ++l) acc[l * 64 + lane] = 0ull;
+            for (int l = 0; l < 16; ++l) col[l] = atomicExch(&acc[l * 64 + lane], 0ull);  // read and clear, 16 in flight
 #pragma unroll
             for (int l = 0; l < 16; ++l) {
                 unsigned long long v = col[l];
