@@ -56,6 +56,12 @@ double bof4_opq_threshold(double q, uint32_t block);
  * goes to the lower level).  code(x) = number of k with x > thr[k].  Pure host function. */
 int bof4_thresholds(const double* cb_host, float* thr_host);
 
+/* The bin table of the kernels' branch-free nearest-level search (same rule as bof4_thresholds, different
+ * evaluation): a normalised weight x in [-1, 1] falls into bin b = (bits(fma(x, 16, 2^20 + 16)) & 0x1F8) / 8 of 33,
+ * and code(x) = base33[b] + (x > thr33[b]).  *fast_host is 0 when the codebook does not fit this form (two thresholds
+ * within one bin, or one closer to zero than 2^-30); the kernels then count the 15 thresholds.  Pure host function. */
+int bof4_bin_table(const double* cb_host, float* thr33_host, uint32_t* base33_host, int* fast_host);
+
 /*
  * One expectation pass of the data-driven Lloyd / EM codebook optimisation (section 3.2 eq. 6, appendix B.3).
  * Every block is normalised by its absolute (signed_norm = 0, section 2.1 eq. 1-2) or signed (signed_norm = 1,

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libbof4_hip.so")
 
 BOF4_OK, BOF4_ERR_ARG, BOF4_ERR_CAPACITY, BOF4_ERR_WORKSPACE, BOF4_ERR_HIP = 0, -1, -2, -3, -4
-EXPORTS = ("bof4_workspace_bytes", "bof4_opq_threshold", "bof4_thresholds", "bof4_lloyd_step",
+EXPORTS = ("bof4_workspace_bytes", "bof4_opq_threshold", "bof4_thresholds", "bof4_bin_table", "bof4_lloyd_step",
            "bof4_codebook_update", "bof4_quantize", "bof4_dequantize", "bof4_time_next_call", "bof4_last_error",
            "bof4_last_hip_error")
 
@@ -52,6 +52,9 @@ def lib():
         L.bof4_opq_threshold.argtypes = [ctypes.c_double, ctypes.c_uint32]
         L.bof4_thresholds.restype = ctypes.c_int
         L.bof4_thresholds.argtypes = [f64p, ctypes.POINTER(ctypes.c_float)]
+        L.bof4_bin_table.restype = ctypes.c_int
+        L.bof4_bin_table.argtypes = [f64p, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_uint32),
+                                     ctypes.POINTER(ctypes.c_int)]
         L.bof4_lloyd_step.restype = ctypes.c_int
         L.bof4_lloyd_step.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint32, f64p, ctypes.c_int, ctypes.c_double,
                                       ctypes.c_int, ctypes.POINTER(LloydStats), vp, ctypes.c_size_t, vp]
@@ -107,6 +110,17 @@ def bof4_thresholds(cb):
     thr = np.zeros(15, dtype=np.float32)
     _check(lib().bof4_thresholds(cbp, thr.ctypes.data_as(ctypes.POINTER(ctypes.c_float))))
     return thr
+
+
+def bof4_bin_table(cb):
+    """Returns (thr float32[33], base uint32[33], fast bool)."""
+    cb, cbp = _cb(cb)
+    thr = np.zeros(33, dtype=np.float32)
+    base = np.zeros(33, dtype=np.uint32)
+    fast = ctypes.c_int(0)
+    _check(lib().bof4_bin_table(cbp, thr.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
+                                base.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)), ctypes.byref(fast)))
+    return thr, base, bool(fast.value)
 
 
 def bof4_codebook_update(stats, pinned_mask, cb):

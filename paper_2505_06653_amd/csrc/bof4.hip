@@ -479,6 +479,18 @@ int bof4_thresholds(const double* cb_host, float* thr_host) {
     return BOF4_OK;
 }
 
+int bof4_bin_table(const double* cb_host, float* thr33_host, uint32_t* base33_host, int* fast_host) {
+    if (!valid_codebook(cb_host) || !thr33_host || !base33_host || !fast_host)
+        return fail(BOF4_ERR_ARG, "bof4_bin_table: bad codebook or null output");
+    const BinTable t = make_bin_table(make_codebook_args(cb_host));
+    for (int b = 0; b < 33; ++b) {
+        thr33_host[b] = t.thr[b];
+        base33_host[b] = t.base[b];
+    }
+    *fast_host = (int)t.fast;
+    return BOF4_OK;
+}
+
 int bof4_codebook_update(const bof4_lloyd_stats* st, uint16_t pinned_mask, double* cb_host) {
     if (!st || !cb_host) return fail(BOF4_ERR_ARG, "bof4_codebook_update: null pointer");
     for (int l = 0; l < 16; ++l) {
