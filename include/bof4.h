@@ -71,7 +71,8 @@ int bof4_bin_table(const double* cb_host, float* thr33_host, uint32_t* base33_ho
  * section 3.3 are replaced by zero before the maximum search and take no part in the sums.
  *   w_dev       n bfloat16 weights (device, read only)
  *   cb_host     16 levels (host)
- *   out_host    result (host); the call synchronises `stream`
+ *   out_host    result (host); the call synchronises `stream`.  If it lies in pinned (device-visible) host memory
+ *               the GPU writes it in place and no copy is made
  *   ws_dev      workspace of at least bof4_workspace_bytes(n, block, 0) bytes (device); contents undefined after
  * The result is bit-identical from run to run (fixed reduction order).
  */
@@ -90,7 +91,7 @@ int bof4_codebook_update(const bof4_lloyd_stats* stats_host, uint16_t pinned_mas
  *   scales_dev       n/block binary16 block constants (the sign is kept when signed_norm = 1)
  *   out_idx_dev / out_val_dev   outlier list in ascending flat index: int64 index, binary16 value; capacity
  *                    `out_capacity` entries each; ignored (may be NULL) when opq_T == 0
- *   n_outliers_host  receives the number of outliers (0 when opq_T == 0)
+ *   n_outliers_host  receives the number of outliers (0 when opq_T == 0); pinned host memory is written in place
  *   ws_dev           workspace of at least bof4_workspace_bytes(n, block, out_capacity) bytes; needed only
  *                    when opq_T > 0
  * With opq_T > 0 the call synchronises `stream`; with opq_T == 0 it only enqueues.

@@ -149,21 +149,35 @@ def alloc_workspace(n, block, out_capacity=0, device="cuda"):
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
-def bof4_lloyd_step(w, block, cb, signed, opq_T=0.0, weight_by_max2=True, ws=None, stream=None, raw=False):
-    """w: flat bf16 device tensor.  Returns the statistics as a dict (or the ctypes struct with raw=True)."""
+def pinned_lloyd_stats():
+    """A LloydStats record in pinned host memory (the GPU then writes results in place).  Returns (struct, keepalive)."""
+    buf = torch.zeros(ctypes.sizeof(LloydStats), dtype=torch.uint8).pin_memory()
+    return LloydStats.from_address(buf.data_ptr()), buf
+
+
+def pinned_counter():
+    """A uint64 outlier counter in pinned host memory.  Returns (ctypes.c_uint64, keepalive)."""
+    buf = torch.zeros(1, dtype=torch.int64).pin_memory()
+    return ctypes.c_uint64.from_address(buf.data_ptr()), buf
+
+
+def bof4_lloyd_step(w, block, cb, signed, opq_T=0.0, weight_by_max2=True, ws=None, stream=None, raw=False, out=None):
+    """w: flat bf16 device tensor.  Returns the statistics as a dict (or the ctypes struct with raw=True).
+    `out`: optional LloydStats to fill (e.g. from pinned_lloyd_stats())."""
     assert w.dtype == torch.bfloat16 and w.is_cuda and w.is_contiguous()
     n = w.numel()
     cb, cbp = _cb(cb)
     if ws is None:
         ws = alloc_workspace(n, block, 0, w.device)
-    out = LloydStats()
+    if out is None:
+        out = LloydStats()
     _check(lib().bof4_lloyd_step(_ptr(w), n, block, cbp, int(signed), float(opq_T), int(bool(weight_by_max2)),
                                  ctypes.byref(out), _ptr(ws), ws.numel(), _stream(stream)))
     return out if raw else out.as_dict()
 
 
 def bof4_quantize(w, block, cb, signed, opq_T=0.0, out_capacity=0, codes=None, scales=None, out_idx=None,
-                  out_val=None, ws=None, stream=None, allow_overflow=False):
+                  out_val=None, ws=None, stream=None, allow_overflow=False, counter=None):
     """w: flat bf16 device tensor.  Returns (codes u8[n/2], scales f16[n/block], out_idx i64[k], out_val f16[k],
     n_outliers).  Output tensors are allocated here unless passed in."""
     assert w.dtype == torch.bfloat16 and w.is_cuda and w.is_contiguous()
@@ -181,7 +195,7 @@ def bof4_quantize(w, block, cb, signed, opq_T=0.0, out_capacity=0, codes=None, s
             out_val = torch.empty(max(out_capacity, 1), dtype=torch.float16, device=dev)
         if ws is None:
             ws = alloc_workspace(n, block, out_capacity, dev)
-    nout = ctypes.c_uint64(0)
+    nout = counter if counter is not None else ctypes.c_uint64(0)
     code = lib().bof4_quantize(_ptr(w), n, block, cbp, int(signed), float(opq_T), _ptr(codes), _ptr(scales),
                                _ptr(out_idx), _ptr(out_val), out_capacity, ctypes.byref(nout), _ptr(ws),
                                0 if ws is None else ws.numel(), _stream(stream))

@@ -55,6 +55,18 @@ int fail_hip(hipError_t e, const char* where) {
         if (e_ != hipSuccess) return fail_hip(e_, #expr); \
     } while (0)
 
+// Device address of a host pointer that the GPU can write (pinned / registered memory), or nullptr for ordinary
+// pageable memory.
+void* device_view_of_host(const void* host_ptr) {
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, host_ptr) != hipSuccess) {
+        (void)hipGetLastError();  // pageable memory is reported as an error: not one
+        return nullptr;
+    }
+    if (attr.type != hipMemoryTypeHost) return nullptr;
+    return attr.devicePointer;
+}
+
 bool valid_block(uint32_t b) { return b == 32 || b == 64 || b == 128 || b == 256; }
 bool valid_codebook(const double* cb) {
     if (!cb) return false;
@@ -565,16 +577,21 @@ int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* c
     *n_outliers_host = 0;
     if (!opq) return BOF4_OK;
 
+    // total_dev[0] = count, with bit 63 set if a wave overflowed its staging region.  A caller's counter in pinned
+    // host memory receives it straight from the scan kernel.
+    uint64_t* direct = (uint64_t*)device_view_of_host(n_outliers_host);
     hipLaunchKernelGGL(seg_outlier_scan_kernel, dim3(1), dim3(1024), 0, s, os.wave_count, n_waves, os.region_cap, wave_off,
-                       total_dev);
+                       direct ? direct : total_dev);
     hipLaunchKernelGGL(seg_outlier_gather_kernel, dim3(n_waves), dim3(64), 0, s, os, wave_off, out_idx_dev, out_val_dev,
                        out_capacity);
     HIP_TRY(hipGetLastError());
-    uint64_t head[2] = {0, 0};
-    HIP_TRY(hipMemcpyAsync(head, total_dev, 16, hipMemcpyDeviceToHost, s));
+    uint64_t head = 0;
+    if (!direct) HIP_TRY(hipMemcpyAsync(&head, total_dev, 8, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
-    uint64_t tot = head[0];
-    if (head[1] != 0 && tot <= out_capacity) {
+    if (direct) head = *n_outliers_host;
+    uint64_t tot = head & ~(1ull << 63);
+    const bool staged_overflow = (head >> 63) != 0;
+    if (staged_overflow && tot <= out_capacity) {
         // Some wave found more outliers than its staging region holds although the caller's buffers are large enough
         // (outliers piled up in one stretch of the tensor): redo the extraction with the general, slower kernel that
         // appends tile by tile through one global counter.
@@ -656,7 +673,6 @@ int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double*
     hipStream_t s = (hipStream_t)stream;
     const uint32_t seg = block < 64 ? block : 64;
     const uint64_t n_seg = n / seg;
-    uint32_t grid = 0;
     CodebookArgs cb = make_codebook_args(cb_host);
     double* partials = (double*)ws_dev;
     const double T2 = opq_T * opq_T;
@@ -688,28 +704,17 @@ int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double*
         }
 #undef BOF4_LAUNCH_SEGL
         timing_end(s);
+        // The result record has the layout of bof4_lloyd_stats.  If the caller's struct lies in pinned (device-visible)
+        // host memory the final kernel writes it in place; otherwise it goes through the workspace and one copy.
+        static_assert(sizeof(bof4_lloyd_stats) == 51 * 8, "result record and bof4_lloyd_stats must match");
+        double* rec_dev = partials + (uint64_t)n_part * LLOYD_PART;
+        double* direct = (double*)device_view_of_host(out_host);
         hipLaunchKernelGGL(seg_lloyd_final_kernel, dim3(1), dim3(1024), 0, s, partials, n_part, cb, bt.code_of_zero,
-                           partials + (uint64_t)n_part * LLOYD_PART);
-        grid = n_part;  // the final record sits after the last partial
+                           direct ? direct : rec_dev);
+        HIP_TRY(hipGetLastError());
+        if (!direct) HIP_TRY(hipMemcpyAsync(out_host, rec_dev, sizeof(bof4_lloyd_stats), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
     }
-    HIP_TRY(hipGetLastError());
-    double fin[LLOYD_PART];
-    HIP_TRY(hipMemcpyAsync(fin, partials + (uint64_t)grid * LLOYD_PART, 50 * 8, hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipStreamSynchronize(s));
-    uint64_t used = 0;
-    for (int l = 0; l < 16; ++l) {
-        out_host->num[l] = fin[l];
-        out_host->den[l] = fin[16 + l];
-        uint64_t c;
-        memcpy(&c, &fin[32 + l], 8);
-        out_host->cnt[l] = c;
-        used += c;
-    }
-    out_host->sse = fin[48];
-    uint64_t no;
-    memcpy(&no, &fin[49], 8);
-    out_host->n_used = used;
-    out_host->n_outliers = no;
     return BOF4_OK;
 }
 

@@ -320,7 +320,7 @@ __global__ __launch_bounds__(256) void seg_quantize_kernel(const uint4* __restri
 }
 
 // Exclusive prefix sum over the per-wave outlier counts (one workgroup); also publishes the grand total.
-// total_out[0] = number of outliers, total_out[1] = 1 if some wave overflowed its staging region.
+// *total_out = number of outliers, with bit 63 set if some wave overflowed its staging region.
 __global__ __launch_bounds__(1024) void seg_outlier_scan_kernel(const uint32_t* __restrict__ wave_count,
                                                                  uint32_t n_waves, uint32_t region_cap,
                                                                  uint64_t* __restrict__ wave_off,
@@ -356,10 +356,7 @@ __global__ __launch_bounds__(1024) void seg_outlier_scan_kernel(const uint32_t* 
         if (threadIdx.x == 0) carry_sh = carry + tot;
         __syncthreads();
     }
-    if (threadIdx.x == 0) {
-        total_out[0] = carry_sh;
-        total_out[1] = over_sh;
-    }
+    if (threadIdx.x == 0) *total_out = carry_sh | ((uint64_t)over_sh << 63);
 }
 
 // One wave per staging region: copy it to its final place in the caller's (ascending) outlier list.
@@ -558,7 +555,8 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
 
 // Reduce the per-wave partials in a fixed order and turn them into the statistics of the C ABI:
 //   num = A - den,  sse = sum g x^2 - 2 sum_l c_l num_l + sum_l c_l^2 den_l   (the three sums of the expanded square).
-// out[0..15] num, [16..31] den, [32..47] cnt (as integer bits), [48] sse, [49] n_outliers (integer bits).
+// `out` has the memory layout of bof4_lloyd_stats: [0..15] num, [16..31] den, [32..47] cnt (integers), [48] sse,
+// [49] n_used, [50] n_outliers (integers); it may point into the workspace or at device-visible host memory.
 __global__ __launch_bounds__(1024) void seg_lloyd_final_kernel(const double* __restrict__ partials, uint32_t n_part,
                                                                 CodebookArgs cb, uint32_t code_of_zero,
                                                                 double* __restrict__ out) {
@@ -600,6 +598,7 @@ __global__ __launch_bounds__(1024) void seg_lloyd_final_kernel(const double* __r
     }
     __syncthreads();
     __shared__ double sse_part[16];
+    __shared__ unsigned long long cnt_part[16];
     if (threadIdx.x < 16) {
         const uint32_t l = threadIdx.x;
         const double koutg = tot[49];
@@ -618,13 +617,19 @@ __global__ __launch_bounds__(1024) void seg_lloyd_final_kernel(const double* __r
         out[16 + l] = den;
         out[32 + l] = __longlong_as_double((long long)c);
         sse_part[l] = cb.cb64[l] * (cb.cb64[l] * den - 2.0 * num);
-        if (l == 0) out[49] = __longlong_as_double((long long)kout);
+        cnt_part[l] = c;
+        if (l == 0) out[50] = __longlong_as_double((long long)kout);
     }
     __syncthreads();
     if (threadIdx.x == 0) {
         double sse = tot[48];
-        for (int l = 0; l < 16; ++l) sse += sse_part[l];
+        unsigned long long used = 0;
+        for (int l = 0; l < 16; ++l) {
+            sse += sse_part[l];
+            used += cnt_part[l];
+        }
         out[48] = sse;
+        out[49] = __longlong_as_double((long long)used);
     }
 }
 

@@ -213,3 +213,21 @@ def test_capacity_overflow_and_workspace_errors():
     with pytest.raises(binding.Bof4Error) as e:
         binding.bof4_lloyd_step(wd, 64, cb, 1, ws=torch.empty(256, dtype=torch.uint8, device=DEV))
     assert e.value.code == binding.BOF4_ERR_WORKSPACE
+
+
+def test_results_in_pinned_host_memory_are_written_in_place():
+    """Result records in pinned host memory are filled by the GPU directly; same numbers as the copy path."""
+    w = make_weights(64, 1024, seed=91)
+    cb = cb_for(64, 1)
+    T = oracle.opq_threshold(0.95, 64)
+    wd = w.to(DEV)
+    ref = binding.bof4_lloyd_step(wd, 64, cb, 1, opq_T=T)
+    rec, keep = binding.pinned_lloyd_stats()
+    got = binding.bof4_lloyd_step(wd, 64, cb, 1, opq_T=T, out=rec)
+    assert np.array_equal(got["num"], ref["num"]) and np.array_equal(got["cnt"], ref["cnt"])
+    assert got["sse"] == ref["sse"] and got["n_used"] == ref["n_used"] and got["n_outliers"] == ref["n_outliers"]
+    ctr, keep2 = binding.pinned_counter()
+    a = binding.bof4_quantize(wd, 64, cb, 1, opq_T=T, out_capacity=4096)
+    b = binding.bof4_quantize(wd, 64, cb, 1, opq_T=T, out_capacity=4096, counter=ctr)
+    assert a[4] == b[4] == ctr.value and a[4] > 0
+    assert torch.equal(a[2], b[2]) and torch.equal(a[0], b[0])
