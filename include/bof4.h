@@ -106,6 +106,9 @@ int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* c
  * Dequantise (section 2.1 eq. 3): w~ = block constant * level[code] as one binary32 product rounded to
  * bfloat16, then the outliers (section 3.3) are written back over their zero placeholders.
  *   w_out_dev   n bfloat16 values (device)
+ *   out_idx_dev / out_val_dev   n_outliers entries in ascending flat index, as bof4_quantize writes them (the
+ *               write-back re-decodes each 16-weight group that holds outliers and relies on the outliers of one
+ *               group being adjacent in the list; of two entries with the same index the later one wins)
  * Only enqueues; out_idx_dev entries must lie in [0, n) (not checked on the device side beyond a bounds test
  * that skips offending entries).
  */

@@ -378,9 +378,7 @@ __global__ void zero_u64_kernel(uint64_t* p) { *p = 0; }
 #ifndef BOF4_DEQ_VPT
 #define BOF4_DEQ_VPT 4
 #endif
-#ifndef BOF4_DEQ_NT
-#define BOF4_DEQ_NT 1
-#endif
+constexpr uint64_t DEQ_RESIDENT_WGS = 2048;  // 256 compute units x 8 workgroups of 256 lanes
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2_rne(float lo, float hi) {
@@ -390,45 +388,111 @@ __device__ __forceinline__ uint32_t pack_bf16x2_rne(float lo, float hi) {
     __builtin_memcpy(&u, &r, 4);
     return u;
 }
-template <int I>
+// With an outlier list (section 3.3: outliers are kept in 16 bit beside the codes and replace their zero
+// placeholders) a workgroup takes a contiguous run of tiles (256 * DEQ_VPT * 8 weights each).  It finds once where
+// its first weight falls in the ascending list - a 256-way search, three rounds for any list a call can carry -
+// and then walks the list forward: every tile is decoded into LDS, one lane per listed outlier overwrites its
+// weight there, and the tile is stored.  Every output line is written exactly once: patching lines that have left
+// the caches costs a partial write each, about as much as writing a third of the tensor again.
+template <int I, bool OUTLIERS>
 __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restrict__ codes,
                                                           const uint16_t* __restrict__ scales, uint64_t n_vec,
-                                                          CodebookArgs cb, uint4* __restrict__ out) {
+                                                          uint32_t tiles_per_wg, CodebookArgs cb,
+                                                          const int64_t* __restrict__ out_idx,
+                                                          const uint16_t* __restrict__ out_val, uint64_t n_out,
+                                                          uint4* __restrict__ out) {
     constexpr int G = I / 8;
+    constexpr int TILE_VEC = 256 * BOF4_DEQ_VPT;
     __shared__ float lv[16];
+    __shared__ uint4 stage[OUTLIERS ? TILE_VEC : 1];
     if (threadIdx.x < 16) lv[threadIdx.x] = cb.lv32[threadIdx.x];
     __syncthreads();
-    const uint64_t base = (uint64_t)blockIdx.x * (256 * BOF4_DEQ_VPT) + threadIdx.x;
-    uint32_t c[BOF4_DEQ_VPT];
-    float s[BOF4_DEQ_VPT];
-#pragma unroll
-    for (int k = 0; k < BOF4_DEQ_VPT; ++k) {
-        const uint64_t v = base + 256 * k;
-        c[k] = v < n_vec ? codes[v] : 0u;
-        s[k] = v < n_vec ? f16_bits_to_f32(scales[v / G]) : 0.0f;
-    }
-#pragma unroll
-    for (int k = 0; k < BOF4_DEQ_VPT; ++k) {
-        const uint64_t v = base + 256 * k;
-        uint32_t o[4];
-#pragma unroll
-        for (int p = 0; p < 4; ++p)
-            o[p] = pack_bf16x2_rne(s[k] * lv[(c[k] >> (8 * p)) & 15u], s[k] * lv[(c[k] >> (8 * p + 4)) & 15u]);
-        if (v < n_vec) {
-            if (BOF4_DEQ_NT) store_stream(&out[v], make_uint4(o[0], o[1], o[2], o[3]));
-            else out[v] = make_uint4(o[0], o[1], o[2], o[3]);
+    const uint64_t first_tile = (uint64_t)blockIdx.x * tiles_per_wg;
+    uint64_t lo = 0;
+    if (OUTLIERS) {
+        // first list position whose index is >= the workgroup's first weight; invariant: every entry before lo is
+        // smaller, every entry from hi on is not
+        const int64_t target = (int64_t)(first_tile * TILE_VEC * 8);
+        uint64_t hi = n_out;
+        while (lo < hi) {
+            const uint64_t step = (hi - lo + 255) / 256;
+            const uint64_t p = lo + threadIdx.x * step;
+            const int below = (p < hi && out_idx[p] < target) ? 1 : 0;
+            const uint64_t cnt = (uint64_t)__syncthreads_count(below);  // the list ascends: the first cnt probes
+            const uint64_t new_hi = lo + cnt * step;
+            if (cnt > 0) lo = lo + (cnt - 1) * step + 1;
+            if (new_hi < hi) hi = new_hi;
         }
     }
-}
-
-__global__ __launch_bounds__(256) void outlier_scatter_kernel(const int64_t* __restrict__ idx,
-                                                               const uint16_t* __restrict__ val, uint64_t k,
-                                                               uint64_t n, uint16_t* __restrict__ out) {
-    uint64_t t = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-    if (t >= k) return;
-    int64_t i = idx[t];
-    if (i < 0 || (uint64_t)i >= n) return;
-    out[i] = (uint16_t)f32_to_bf16_rne(f16_bits_to_f32(val[t]));
+    for (uint32_t t = 0; t < tiles_per_wg; ++t) {
+        const uint64_t tile = first_tile + t;
+        const uint64_t base = tile * TILE_VEC + threadIdx.x;
+        if (tile * TILE_VEC >= n_vec) break;
+        // the first 256 list entries from the current position travel together with the codes
+        int64_t pre_i = -1, pre_nxt = -1;
+        uint32_t pre_val = 0;
+        if (OUTLIERS) {
+            const uint64_t j = lo + threadIdx.x;
+            if (j < n_out) {
+                pre_i = out_idx[j];
+                pre_val = out_val[j];
+            }
+            if (j + 1 < n_out) pre_nxt = out_idx[j + 1];
+        }
+        uint32_t c[BOF4_DEQ_VPT];
+        float s[BOF4_DEQ_VPT];
+#pragma unroll
+        for (int k = 0; k < BOF4_DEQ_VPT; ++k) {
+            const uint64_t v = base + 256 * k;
+            c[k] = v < n_vec ? codes[v] : 0u;
+            s[k] = v < n_vec ? f16_bits_to_f32(scales[v / G]) : 0.0f;
+        }
+#pragma unroll
+        for (int k = 0; k < BOF4_DEQ_VPT; ++k) {
+            const uint64_t v = base + 256 * k;
+            uint32_t o[4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p)
+                o[p] = pack_bf16x2_rne(s[k] * lv[(c[k] >> (8 * p)) & 15u], s[k] * lv[(c[k] >> (8 * p + 4)) & 15u]);
+            if (OUTLIERS) {
+                stage[256 * k + threadIdx.x] = make_uint4(o[0], o[1], o[2], o[3]);
+            } else if (v < n_vec) {
+                store_stream(&out[v], make_uint4(o[0], o[1], o[2], o[3]));
+            }
+        }
+        if (OUTLIERS) {
+            __syncthreads();
+            const int64_t tile_begin = (int64_t)(tile * TILE_VEC * 8);
+            const int64_t tile_end = tile_begin + TILE_VEC * 8;
+            uint16_t* stage16 = reinterpret_cast<uint16_t*>(stage);
+            for (bool first = true;; first = false) {
+                const uint64_t j = lo + threadIdx.x;
+                int64_t i = pre_i, nxt = pre_nxt;
+                uint32_t val = pre_val;
+                if (!first) {
+                    i = nxt = -1;
+                    if (j < n_out) {
+                        i = out_idx[j];
+                        val = out_val[j];
+                    }
+                    if (j + 1 < n_out) nxt = out_idx[j + 1];
+                }
+                const int inside = (j < n_out && i >= tile_begin && i < tile_end) ? 1 : 0;
+                // of several entries with one index the last one counts
+                if (inside && nxt != i) stage16[i - tile_begin] = (uint16_t)f32_to_bf16_rne(f16_bits_to_f32(val));
+                const uint32_t cnt = (uint32_t)__syncthreads_count(inside);
+                lo += cnt;
+                if (cnt < 256) break;
+            }
+            // the barrier inside the loop has ordered the patches before these reads
+#pragma unroll
+            for (int k = 0; k < BOF4_DEQ_VPT; ++k) {
+                const uint64_t v = base + 256 * k;
+                if (v < n_vec) store_stream(&out[v], stage[256 * k + threadIdx.x]);
+            }
+            __syncthreads();  // the next tile overwrites the stage
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------------ dispatch
@@ -636,26 +700,32 @@ int bof4_dequantize(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64
         return fail(BOF4_ERR_ARG, "bof4_dequantize: misaligned pointer");
     hipStream_t s = (hipStream_t)stream;
     const uint64_t n_vec = n / 8;
-    const uint64_t nb = (n_vec + 256 * BOF4_DEQ_VPT - 1) / (256 * BOF4_DEQ_VPT);
-    if (nb > 0x7fffffffull) return fail(BOF4_ERR_ARG, "bof4_dequantize: n too large for one call");
+    const uint64_t n_tiles = (n_vec + 256 * BOF4_DEQ_VPT - 1) / (256 * BOF4_DEQ_VPT);
+    // without a list one workgroup per tile; with one, DEQ_RESIDENT_WGS workgroups that each walk a run of tiles
+    uint64_t tiles_per_wg = n_outliers > 0 ? (n_tiles + DEQ_RESIDENT_WGS - 1) / DEQ_RESIDENT_WGS : 1;
+    const uint64_t nb = (n_tiles + tiles_per_wg - 1) / tiles_per_wg;
+    if (nb > 0x7fffffffull || tiles_per_wg > 0xffffffffull)
+        return fail(BOF4_ERR_ARG, "bof4_dequantize: n too large for one call");
     CodebookArgs cb = make_codebook_args(cb_host);
     dim3 grid((uint32_t)nb);
     const uint32_t* codes = (const uint32_t*)codes_dev;
     uint4* out = (uint4*)w_out_dev;
     timing_begin(s);
+#define BOF4_LAUNCH_DEQ(I_)                                                                                        \
+    if (n_outliers > 0)                                                                                            \
+        hipLaunchKernelGGL((dequantize_kernel<I_, true>), grid, dim3(256), 0, s, codes, scales_dev, n_vec,          \
+                           (uint32_t)tiles_per_wg, cb, out_idx_dev, out_val_dev, n_outliers, out);                                             \
+    else                                                                                                           \
+        hipLaunchKernelGGL((dequantize_kernel<I_, false>), grid, dim3(256), 0, s, codes, scales_dev, n_vec,         \
+                           (uint32_t)tiles_per_wg, cb, out_idx_dev, out_val_dev, n_outliers, out);
     switch (block) {
-        case 32: hipLaunchKernelGGL(dequantize_kernel<32>, grid, dim3(256), 0, s, codes, scales_dev, n_vec, cb, out); break;
-        case 64: hipLaunchKernelGGL(dequantize_kernel<64>, grid, dim3(256), 0, s, codes, scales_dev, n_vec, cb, out); break;
-        case 128: hipLaunchKernelGGL(dequantize_kernel<128>, grid, dim3(256), 0, s, codes, scales_dev, n_vec, cb, out); break;
-        default: hipLaunchKernelGGL(dequantize_kernel<256>, grid, dim3(256), 0, s, codes, scales_dev, n_vec, cb, out); break;
+        case 32: BOF4_LAUNCH_DEQ(32) break;
+        case 64: BOF4_LAUNCH_DEQ(64) break;
+        case 128: BOF4_LAUNCH_DEQ(128) break;
+        default: BOF4_LAUNCH_DEQ(256) break;
     }
+#undef BOF4_LAUNCH_DEQ
     timing_end(s);
-    if (n_outliers > 0) {
-        uint64_t ob = (n_outliers + 255) / 256;
-        if (ob > 0x7fffffffull) return fail(BOF4_ERR_ARG, "bof4_dequantize: too many outliers for one call");
-        hipLaunchKernelGGL(outlier_scatter_kernel, dim3((uint32_t)ob), dim3(256), 0, s, out_idx_dev, out_val_dev,
-                           n_outliers, n, (uint16_t*)w_out_dev);
-    }
     HIP_TRY(hipGetLastError());
     return BOF4_OK;
 }

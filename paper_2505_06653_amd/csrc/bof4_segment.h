@@ -388,10 +388,7 @@ constexpr double LLOYD_INC_MUL = 0x1p-1020;
 constexpr double LLOYD_INC_ADD = 0x1p-1008 + 0x1p-1020;
 
 // Elements per batch of the Lloyd inner loop: the table reads of a batch are issued together, then its adds.
-#ifndef BOF4_LLOYD_BATCH
-#define BOF4_LLOYD_BATCH 16
-#endif
-constexpr int LLOYD_BATCH = BOF4_LLOYD_BATCH;
+constexpr int LLOYD_BATCH = 16;
 
 template <int I, bool FAST, bool OPQ>
 __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict__ w, uint64_t n_seg, CodebookArgs cb,

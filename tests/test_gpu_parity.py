@@ -194,6 +194,30 @@ def test_dequantize_arbitrary_codes_and_scales():
     assert np.array_equal(to_np_u16(got), deq)
 
 
+@pytest.mark.parametrize("block", [32, 64, 128, 256])
+def test_dequantize_outlier_write_back_clusters(block):
+    """Outliers packed several to a 16-weight group, on both sides of group and block boundaries, at the first and
+    last weight, and one index listed twice (the later value wins in both implementations)."""
+    g = torch.Generator().manual_seed(19 + block)
+    n = block * 97
+    codes = torch.randint(0, 256, (n // 2,), generator=g, dtype=torch.int32).to(torch.uint8)
+    scales = (torch.randn(n // block, generator=g) * 0.05).to(torch.float16)
+    idx = sorted(set([0, 1, 2, 15, 16, 17, 31, 32, block - 1, block, block + 1, 5 * block + 7, 5 * block + 8,
+                      5 * block + 9, 5 * block + 15, n - 17, n - 16, n - 2, n - 1]
+                     + torch.randint(0, n, (300,), generator=g).tolist()))
+    idx.insert(idx.index(17), 17)
+    idx = np.array(idx, dtype=np.int64)
+    val = (torch.randn(idx.size, generator=g) * 3).to(torch.float16)
+    cb = cb_for(block, 1)
+    val_np = val.view(torch.int16).numpy().view(np.uint16)
+    st, deq = oracle.dequantize(codes.numpy(), scales.view(torch.int16).numpy().view(np.uint16), n, block, cb, idx,
+                                val_np)
+    got = binding.bof4_dequantize(codes.to(DEV), scales.to(DEV), n, block, cb, torch.from_numpy(idx).to(DEV),
+                                  val.to(DEV))
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np_u16(got), deq)
+
+
 def test_capacity_overflow_and_workspace_errors():
     w = make_weights(16, 1024, seed=77)
     T = oracle.opq_threshold(0.95, 64)
