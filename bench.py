@@ -86,29 +86,34 @@ def main():
     stats_rec, _keep1 = binding.pinned_lloyd_stats()   # results land in pinned host memory: no copy
     counter, _keep2 = binding.pinned_counter()
     names = ("quantize", "dequantize", "lloyd_step")
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    # events the library records right around the main kernel of each call (bof4_time_next_call)
-    kev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    # Kernel-level HIP events, recorded by the library right around the main kernel of a call (bof4_time_next_call).
+    # An event record costs about 5 us of stream time, so timed step i brackets only the kernel of call i % 3: every
+    # kernel is sampled over the whole timed region at two records per step.
+    kev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
     for row in kev:
         for e in row:
             e.record()  # creates the HIP handle
     n_out_seen = 0
 
-    def step(i, events=None):
+    def step(i, timed_call=None, events=None):
         nonlocal n_out_seen
         w = ws_list[i % len(ws_list)]
         if events:
             events[0].record()
+        if timed_call == 0:
             binding.bof4_time_next_call(kev[i][0], kev[i][1])
-        _, _, gi, gv, k = binding.bof4_quantize(w, BLOCK, cb, 1, opq_T=T, out_capacity=cap, codes=codes,
-                                                scales=scales, out_idx=oidx, out_val=oval, ws=ws, counter=counter)
+        k = binding.bof4_quantize(w, BLOCK, cb, 1, opq_T=T, out_capacity=cap, codes=codes, scales=scales,
+                                  out_idx=oidx, out_val=oval, ws=ws, counter=counter, trim=False)[4]
         if events:
             events[1].record()
-            binding.bof4_time_next_call(kev[i][2], kev[i][3])
-        binding.bof4_dequantize(codes, scales, n, BLOCK, cb, gi if k else None, gv if k else None, out=deq)
+        if timed_call == 1:
+            binding.bof4_time_next_call(kev[i][0], kev[i][1])
+        binding.bof4_dequantize(codes, scales, n, BLOCK, cb, oidx if k else None, oval if k else None, out=deq,
+                                n_outliers=k)
         if events:
             events[2].record()
-            binding.bof4_time_next_call(kev[i][4], kev[i][5])
+        if timed_call == 2:
+            binding.bof4_time_next_call(kev[i][0], kev[i][1])
         st = binding.bof4_lloyd_step(w, BLOCK, cb, 1, opq_T=0.0, ws=ws, raw=True, out=stats_rec)
         if events:
             events[3].record()
@@ -120,24 +125,35 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i, ev[i])
+        step(i, timed_call=i % 3)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # per-call times (kernels, helper kernels and host waits of one call), from a few extra steps outside the timed
+    # region so that their event records do not slow the timed one
+    n_extra = min(args.steps, 6)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(n_extra)]
+    for i in range(n_extra):
+        step(args.steps + i, events=ev[i])
+    torch.cuda.synchronize()
     # one plain device copy of known size (2 * n bytes read, 2 * n written), outside the timed region: the reference
     # against which a counter profile of this same command scales FETCH_SIZE / WRITE_SIZE
     deq.copy_(ws_list[0])
     torch.cuda.synchronize()
 
-    ms = {nm: float(np.mean([ev[i][k].elapsed_time(ev[i][k + 1]) for i in range(args.steps)]))
+    ms = {nm: float(np.mean([ev[i][k].elapsed_time(ev[i][k + 1]) for i in range(n_extra)]))
           for k, nm in enumerate(names)}
-    kms = {nm: float(np.mean([kev[i][2 * k].elapsed_time(kev[i][2 * k + 1]) for i in range(args.steps)]))
-           for k, nm in enumerate(names)}
+    kms = {}
+    for c, nm in enumerate(names):
+        samples = [kev[i][0].elapsed_time(kev[i][1]) for i in range(args.steps) if i % 3 == c]
+        if not samples:  # fewer than three timed steps: no sample of this kernel
+            samples = [float("nan")]
+        kms[nm] = float(np.mean(samples))
     rho = n_out_seen / n
     # algorithmic bytes per launch = bytes per weight x n (one launch processes the whole tensor)
     alg_bytes = {"quantize": (2.0 + 0.5 + 2.0 / BLOCK + 10.0 * rho) * n,
                  "dequantize": (0.5 + 2.0 / BLOCK + 2.0 + 10.0 * rho) * n,
                  "lloyd_step": 2.0 * n}
-    dominant = max(names, key=lambda k: kms[k])
+    dominant = max(names, key=lambda k: kms[k] if kms[k] == kms[k] else -1.0)
     achieved = alg_bytes[dominant] / (kms[dominant] * 1e-3) / 1e9
     per_call = {nm: {"call_ms": ms[nm], "kernel_ms": kms[nm], "GBps_bf16": 2.0 * n / (kms[nm] * 1e-3) / 1e9,
                      "GBps_algorithmic": alg_bytes[nm] / (kms[nm] * 1e-3) / 1e9,

@@ -71,8 +71,10 @@ int bof4_bin_table(const double* cb_host, float* thr33_host, uint32_t* base33_ho
  * section 3.3 are replaced by zero before the maximum search and take no part in the sums.
  *   w_dev       n bfloat16 weights (device, read only)
  *   cb_host     16 levels (host)
- *   out_host    result (host); the call synchronises `stream`.  If it lies in pinned (device-visible) host memory
- *               the GPU writes it in place and no copy is made
+ *   out_host    result (host), valid on return.  If it lies in ordinary memory the call copies it there and
+ *               synchronises `stream`.  If it lies in pinned (device-visible) host memory the GPU writes it in place
+ *               and the call returns as soon as the record has arrived (the stream may still be finishing the
+ *               call's last kernel; later work on `stream` is ordered behind it as usual)
  *   ws_dev      workspace of at least bof4_workspace_bytes(n, block, 0) bytes (device); contents undefined after
  * The result is bit-identical from run to run (fixed reduction order).
  */
@@ -91,10 +93,13 @@ int bof4_codebook_update(const bof4_lloyd_stats* stats_host, uint16_t pinned_mas
  *   scales_dev       n/block binary16 block constants (the sign is kept when signed_norm = 1)
  *   out_idx_dev / out_val_dev   outlier list in ascending flat index: int64 index, binary16 value; capacity
  *                    `out_capacity` entries each; ignored (may be NULL) when opq_T == 0
- *   n_outliers_host  receives the number of outliers (0 when opq_T == 0); pinned host memory is written in place
+ *   n_outliers_host  receives the number of outliers (0 when opq_T == 0), valid on return; pinned host memory is
+ *                    written by the GPU in place
  *   ws_dev           workspace of at least bof4_workspace_bytes(n, block, out_capacity) bytes; needed only
  *                    when opq_T > 0
- * With opq_T > 0 the call synchronises `stream`; with opq_T == 0 it only enqueues.
+ * With opq_T == 0 the call only enqueues.  With opq_T > 0 it waits for the count: it synchronises `stream`, or,
+ * with a pinned counter, returns as soon as the count has arrived; codes, scales and the outlier list are then
+ * complete in stream order (a later call or copy on `stream` sees them; another stream must wait for `stream`).
  * On BOF4_ERR_CAPACITY codes and scales are complete, the outlier list is not.
  */
 int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,

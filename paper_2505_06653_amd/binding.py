@@ -177,9 +177,10 @@ def bof4_lloyd_step(w, block, cb, signed, opq_T=0.0, weight_by_max2=True, ws=Non
 
 
 def bof4_quantize(w, block, cb, signed, opq_T=0.0, out_capacity=0, codes=None, scales=None, out_idx=None,
-                  out_val=None, ws=None, stream=None, allow_overflow=False, counter=None):
+                  out_val=None, ws=None, stream=None, allow_overflow=False, counter=None, trim=True):
     """w: flat bf16 device tensor.  Returns (codes u8[n/2], scales f16[n/block], out_idx i64[k], out_val f16[k],
-    n_outliers).  Output tensors are allocated here unless passed in."""
+    n_outliers).  Output tensors are allocated here unless passed in; trim=False returns the outlier buffers whole
+    (the first n_outliers entries are the list)."""
     assert w.dtype == torch.bfloat16 and w.is_cuda and w.is_contiguous()
     n = w.numel()
     dev = w.device
@@ -200,17 +201,24 @@ def bof4_quantize(w, block, cb, signed, opq_T=0.0, out_capacity=0, codes=None, s
                                _ptr(out_idx), _ptr(out_val), out_capacity, ctypes.byref(nout), _ptr(ws),
                                0 if ws is None else ws.numel(), _stream(stream))
     _check(code, allow=(BOF4_ERR_CAPACITY,) if allow_overflow else ())
+    if not trim:
+        return codes, scales, out_idx, out_val, int(nout.value)
     k = min(int(nout.value), out_capacity)
     return (codes, scales, None if out_idx is None else out_idx[:k], None if out_val is None else out_val[:k],
             int(nout.value))
 
 
-def bof4_dequantize(codes, scales, n, block, cb, out_idx=None, out_val=None, out=None, stream=None):
-    """Returns the flat bf16 device tensor of n dequantised weights."""
+def bof4_dequantize(codes, scales, n, block, cb, out_idx=None, out_val=None, out=None, stream=None, n_outliers=None):
+    """Returns the flat bf16 device tensor of n dequantised weights.  The outlier list is the first n_outliers
+    entries of out_idx / out_val (all of them if n_outliers is None)."""
     cb, cbp = _cb(cb)
     if out is None:
         out = torch.empty(n, dtype=torch.bfloat16, device=codes.device)
     k = 0 if out_idx is None else int(out_idx.numel())
+    if n_outliers is not None:
+        if n_outliers > k:
+            raise ValueError("n_outliers exceeds the list")
+        k = int(n_outliers)
     _check(lib().bof4_dequantize(_ptr(codes), _ptr(scales), n, block, cbp, _ptr(out_idx) if k else None,
                                  _ptr(out_val) if k else None, k, _ptr(out), _stream(stream)))
     return out

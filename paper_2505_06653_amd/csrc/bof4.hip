@@ -14,6 +14,7 @@
 //   * OPQ: w^2 * I(I-1) > T^2 * V with V = fma(-S, S, I*Q) in binary64, S = sum w, Q = sum w^2 over the block.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <cstdio>
@@ -106,21 +107,28 @@ uint32_t host_bin(float x) {
 }
 // Builds the per-bin (threshold, base code) table: for x in bin b, code(x) = base[b] + (x > thr[b]).  A bin that
 // two thresholds cut, or a threshold too close to zero, switches the shortcut path off (fast = 0).
-BinTable make_bin_table(const CodebookArgs& cb) {
-    BinTable t;
-    float xlo[33], xhi[33];
-    xlo[0] = -1.0f;
-    xhi[32] = 1.0f;
-    for (uint32_t b = 1; b <= 32; ++b) {  // smallest x whose bin is >= b, by bisection over binary32 values
-        float lo = -1.0f, hi = 1.0f;      // bin(lo) < b <= bin(hi)
-        while (std::nextafterf(lo, hi) != hi) {
-            float mid = 0.5f * lo + 0.5f * hi;
-            if (!(mid > lo && mid < hi)) mid = std::nextafterf(lo, hi);
-            if (host_bin(mid) >= b) hi = mid; else lo = mid;
+struct BinEdges {
+    float xlo[33], xhi[33];  // smallest and largest binary32 x in [-1, 1] that falls into each bin
+    BinEdges() {
+        xlo[0] = -1.0f;
+        xhi[32] = 1.0f;
+        for (uint32_t b = 1; b <= 32; ++b) {  // smallest x whose bin is >= b, by bisection over binary32 values
+            float lo = -1.0f, hi = 1.0f;      // bin(lo) < b <= bin(hi)
+            while (std::nextafterf(lo, hi) != hi) {
+                float mid = 0.5f * lo + 0.5f * hi;
+                if (!(mid > lo && mid < hi)) mid = std::nextafterf(lo, hi);
+                if (host_bin(mid) >= b) hi = mid; else lo = mid;
+            }
+            xlo[b] = hi;
+            xhi[b - 1] = lo;
         }
-        xlo[b] = hi;
-        xhi[b - 1] = lo;
     }
+};
+BinTable make_bin_table(const CodebookArgs& cb) {
+    static const BinEdges edges;  // the same for every codebook: found once
+    const float* xlo = edges.xlo;
+    const float* xhi = edges.xhi;
+    BinTable t;
     t.fast = 1;
     for (uint32_t b = 0; b <= 32; ++b) {
         uint32_t base = 0, inside = 0;
@@ -167,9 +175,9 @@ QuantWsLayout quant_ws_layout(uint64_t n, uint64_t cap) {
 constexpr uint32_t SEG_GRID = 512;              // persistent workgroups of the Lloyd kernel (2 per CU, LDS-bound)
 constexpr uint32_t QUANT_GRID = BOF4_QUANT_GRID;  // persistent workgroups of the quantise kernel
 struct SegWsLayout {
-    size_t header, wave_count, wave_off, idx, val, total;
+    size_t header, wave_count, idx, val, total;
     uint32_t region_cap;
-};       // persistent workgroups of the segment kernels (2 per CU)
+};
 SegWsLayout seg_ws_layout(uint64_t cap) {
     SegWsLayout L;
     const uint64_t nw = (uint64_t)QUANT_GRID * WAVES_PER_WG;
@@ -179,7 +187,6 @@ SegWsLayout seg_ws_layout(uint64_t cap) {
     size_t o = 0;
     L.header = o;     o += 256;
     L.wave_count = o; o += align_up(nw * 4, 256);
-    L.wave_off = o;   o += align_up(nw * 8, 256);
     L.idx = o;        o += align_up(nw * rc * 8, 256);
     L.val = o;        o += align_up(nw * rc * 2, 256);
     L.total = o;
@@ -188,6 +195,40 @@ SegWsLayout seg_ws_layout(uint64_t cap) {
 size_t quant_ws_bytes(uint64_t n, uint64_t cap) {
     size_t a = quant_ws_layout(n, cap).total, b = seg_ws_layout(cap).total;
     return a > b ? a : b;
+}
+// Wait for the stream to drain.  The calls that hand results to the host are short (a fraction of a millisecond), so
+// the host first polls the stream, which notices completion sooner than the blocking wait; work that takes longer
+// than the polling budget falls through to the blocking wait.
+hipError_t wait_for_stream(hipStream_t s) {
+    for (int spin = 0; spin < 4000; ++spin) {
+        const hipError_t q = hipStreamQuery(s);
+        if (q == hipSuccess) return hipSuccess;
+        if (q != hipErrorNotReady) return q;
+    }
+    return hipStreamSynchronize(s);
+}
+// Wait for a result that the last kernel of a call stores straight into pinned host memory.  The host puts
+// FLAG_PENDING, a value no result can have, into the 64-bit word that the kernel writes last (with release
+// semantics at system scope, so the rest of the record is there first) and watches that word; every so often it
+// also asks the stream, so that an error, or a store that only becomes visible when the kernel has ended, ends the
+// watch.  On return the result is in host memory; the call's device outputs are complete in stream order.
+constexpr uint64_t FLAG_PENDING = ~0ull;
+hipError_t wait_for_flag(hipStream_t s, const uint64_t* flag_host) {
+    const volatile uint64_t* flag = flag_host;
+    for (uint32_t spin = 1;; ++spin) {
+        if (*flag != FLAG_PENDING) {
+            std::atomic_thread_fence(std::memory_order_acquire);
+            return hipSuccess;
+        }
+        if ((spin & 255u) == 0) {
+            const hipError_t q = hipStreamQuery(s);
+            if (q != hipErrorNotReady) {
+                if (q != hipSuccess) return q;
+                break;  // drained
+            }
+        }
+    }
+    return hipStreamSynchronize(s);
 }
 size_t lloyd_ws_bytes() { return ((size_t)SEG_GRID + 1) * LLOYD_PART * 8; }
 
@@ -609,12 +650,10 @@ int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* c
     OutlierStage os = {nullptr, nullptr, nullptr, 0};
     SegWsLayout SL = seg_ws_layout(out_capacity);
     uint64_t* total_dev = nullptr;
-    uint64_t* wave_off = nullptr;
     if (opq) {
         char* base = (char*)ws_dev;
         total_dev = (uint64_t*)(base + SL.header);
         os.wave_count = (uint32_t*)(base + SL.wave_count);
-        wave_off = (uint64_t*)(base + SL.wave_off);
         os.idx = (int64_t*)(base + SL.idx);
         os.val = (uint16_t*)(base + SL.val);
         os.region_cap = SL.region_cap;
@@ -638,21 +677,26 @@ int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* c
 #undef BOF4_LAUNCH_SEGQ
     timing_end(s);
     HIP_TRY(hipGetLastError());
-    *n_outliers_host = 0;
-    if (!opq) return BOF4_OK;
+    if (!opq) {
+        *n_outliers_host = 0;
+        return BOF4_OK;
+    }
 
     // total_dev[0] = count, with bit 63 set if a wave overflowed its staging region.  A caller's counter in pinned
-    // host memory receives it straight from the scan kernel.
+    // host memory receives it straight from the gather kernel.
     uint64_t* direct = (uint64_t*)device_view_of_host(n_outliers_host);
-    hipLaunchKernelGGL(seg_outlier_scan_kernel, dim3(1), dim3(1024), 0, s, os.wave_count, n_waves, os.region_cap, wave_off,
-                       direct ? direct : total_dev);
-    hipLaunchKernelGGL(seg_outlier_gather_kernel, dim3(n_waves), dim3(64), 0, s, os, wave_off, out_idx_dev, out_val_dev,
-                       out_capacity);
+    *n_outliers_host = direct ? FLAG_PENDING : 0;
+    hipLaunchKernelGGL(seg_outlier_gather_kernel, dim3(n_waves), dim3(64), 0, s, os, n_waves, out_idx_dev, out_val_dev,
+                       out_capacity, direct ? direct : total_dev);
     HIP_TRY(hipGetLastError());
     uint64_t head = 0;
-    if (!direct) HIP_TRY(hipMemcpyAsync(&head, total_dev, 8, hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipStreamSynchronize(s));
-    if (direct) head = *n_outliers_host;
+    if (direct) {
+        HIP_TRY(wait_for_flag(s, n_outliers_host));
+        head = *n_outliers_host;
+    } else {
+        HIP_TRY(hipMemcpyAsync(&head, total_dev, 8, hipMemcpyDeviceToHost, s));
+        HIP_TRY(wait_for_stream(s));
+    }
     uint64_t tot = head & ~(1ull << 63);
     const bool staged_overflow = (head >> 63) != 0;
     if (staged_overflow && tot <= out_capacity) {
@@ -681,7 +725,7 @@ int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* c
                            n_tiles, si, sv, out_idx_dev, out_val_dev, out_capacity);
         HIP_TRY(hipGetLastError());
         HIP_TRY(hipMemcpyAsync(&tot, total, 8, hipMemcpyDeviceToHost, s));
-        HIP_TRY(hipStreamSynchronize(s));
+        HIP_TRY(wait_for_stream(s));
     }
     *n_outliers_host = tot;
     if (tot > out_capacity) return fail(BOF4_ERR_CAPACITY, "bof4_quantize: outlier buffers too small");
@@ -779,11 +823,16 @@ int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double*
         static_assert(sizeof(bof4_lloyd_stats) == 51 * 8, "result record and bof4_lloyd_stats must match");
         double* rec_dev = partials + (uint64_t)n_part * LLOYD_PART;
         double* direct = (double*)device_view_of_host(out_host);
+        if (direct) out_host->n_used = FLAG_PENDING;  // the word the final kernel writes last
         hipLaunchKernelGGL(seg_lloyd_final_kernel, dim3(1), dim3(1024), 0, s, partials, n_part, cb, bt.code_of_zero,
                            direct ? direct : rec_dev);
         HIP_TRY(hipGetLastError());
-        if (!direct) HIP_TRY(hipMemcpyAsync(out_host, rec_dev, sizeof(bof4_lloyd_stats), hipMemcpyDeviceToHost, s));
-        HIP_TRY(hipStreamSynchronize(s));
+        if (direct) {
+            HIP_TRY(wait_for_flag(s, &out_host->n_used));
+        } else {
+            HIP_TRY(hipMemcpyAsync(out_host, rec_dev, sizeof(bof4_lloyd_stats), hipMemcpyDeviceToHost, s));
+            HIP_TRY(wait_for_stream(s));
+        }
     }
     return BOF4_OK;
 }

@@ -319,58 +319,47 @@ __global__ __launch_bounds__(256) void seg_quantize_kernel(const uint4* __restri
     if (OPQ && lane == 0) os.wave_count[gw] = wcount;
 }
 
-// Exclusive prefix sum over the per-wave outlier counts (one workgroup); also publishes the grand total.
-// *total_out = number of outliers, with bit 63 set if some wave overflowed its staging region.
-__global__ __launch_bounds__(1024) void seg_outlier_scan_kernel(const uint32_t* __restrict__ wave_count,
-                                                                 uint32_t n_waves, uint32_t region_cap,
-                                                                 uint64_t* __restrict__ wave_off,
-                                                                 uint64_t* __restrict__ total_out) {
-    __shared__ uint64_t wsum[16];
-    __shared__ uint64_t carry_sh;
-    __shared__ uint32_t over_sh;
-    if (threadIdx.x == 0) over_sh = 0;
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (threadIdx.x == 0) carry_sh = 0;
-    __syncthreads();
-    for (uint32_t base = 0; base < n_waves; base += 1024) {
-        const uint32_t i = base + threadIdx.x;
-        const uint64_t c = i < n_waves ? wave_count[i] : 0;
-        if (c > region_cap) over_sh = 1;  // benign race: every writer stores 1
-        uint64_t incl = c;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            uint64_t up = (uint64_t)__shfl_up((long long)incl, d, 64);
-            if (lane >= (uint32_t)d) incl += up;
-        }
-        if (lane == 63) wsum[wave] = incl;
-        __syncthreads();
-        uint64_t wbase = 0, tot = 0;
-        for (int k = 0; k < 16; ++k) {
-            uint64_t u = wsum[k];
-            if ((uint32_t)k < wave) wbase += u;
-            tot += u;
-        }
-        const uint64_t carry = carry_sh;
-        if (i < n_waves) wave_off[i] = carry + wbase + incl - c;
-        __syncthreads();
-        if (threadIdx.x == 0) carry_sh = carry + tot;
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) *total_out = carry_sh | ((uint64_t)over_sh << 63);
-}
-
-// One wave per staging region: copy it to its final place in the caller's (ascending) outlier list.
-__global__ __launch_bounds__(64) void seg_outlier_gather_kernel(OutlierStage os, const uint64_t* __restrict__ wave_off,
+// One wave per staging region: it adds up the outlier counts of the regions before its own (that sum is where its
+// entries start in the caller's ascending list) and copies its region there.  The wave of the last region has then
+// seen every count: it publishes *total_out = number of outliers, with bit 63 set if some wave overflowed its
+// staging region.
+__global__ __launch_bounds__(64) void seg_outlier_gather_kernel(OutlierStage os, uint32_t n_waves,
                                                                  int64_t* __restrict__ out_idx,
-                                                                 uint16_t* __restrict__ out_val, uint64_t capacity) {
-    const uint64_t r = blockIdx.x;
-    uint32_t c = os.wave_count[r];
-    if (c > os.region_cap) c = os.region_cap;
-    const uint64_t src = r * (uint64_t)os.region_cap, dst = wave_off[r];
-    for (uint32_t j = threadIdx.x; j < c; j += 64) {
-        if (dst + j < capacity) {
-            out_idx[dst + j] = os.idx[src + j];
-            out_val[dst + j] = os.val[src + j];
+                                                                 uint16_t* __restrict__ out_val, uint64_t capacity,
+                                                                 uint64_t* __restrict__ total_out) {
+    const uint32_t r = blockIdx.x, lane = threadIdx.x;
+    uint64_t before = 0;
+    uint32_t over = 0;
+    for (uint32_t i0 = 0; i0 < r; i0 += 64 * 16) {  // 16 independent loads in flight per lane
+        uint32_t ci[16];
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const uint32_t i = i0 + 64 * t + lane;
+            ci[t] = i < r ? os.wave_count[i] : 0u;
+        }
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            before += ci[t];
+            over |= (ci[t] > os.region_cap) ? 1u : 0u;
+        }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        before += (uint64_t)__shfl_xor((long long)before, d, 64);
+        over |= (uint32_t)__shfl_xor((int)over, d, 64);
+    }
+    const uint32_t own = os.wave_count[r];
+    if (r == n_waves - 1 && lane == 0)  // one 64-bit store at system scope: a host that watches the word sees it whole
+        __hip_atomic_store(reinterpret_cast<unsigned long long*>(total_out),
+                           (unsigned long long)((before + own) |
+                                                ((uint64_t)((over | (own > os.region_cap ? 1u : 0u)) != 0) << 63)),
+                           __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    const uint32_t c = own > os.region_cap ? os.region_cap : own;
+    const uint64_t src = (uint64_t)r * os.region_cap;
+    for (uint32_t j = lane; j < c; j += 64) {
+        if (before + j < capacity) {
+            out_idx[before + j] = os.idx[src + j];
+            out_val[before + j] = os.val[src + j];
         }
     }
 }
@@ -626,7 +615,10 @@ __global__ __launch_bounds__(1024) void seg_lloyd_final_kernel(const double* __r
             used += cnt_part[l];
         }
         out[48] = sse;
-        out[49] = __longlong_as_double((long long)used);
+        // written last, after everything above has reached system memory: a host that watches this word may read
+        // the record as soon as it changes
+        __hip_atomic_store(reinterpret_cast<unsigned long long*>(&out[49]), used, __ATOMIC_RELEASE,
+                           __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 
