@@ -113,6 +113,19 @@ __device__ __forceinline__ uint32_t pk_sign_mask_i16(uint32_t a) {  // 0xFFFF in
     return o;
 }
 
+// a.lo * b.lo + a.hi * b.hi + c for packed bfloat16 pairs, accumulated in binary32 (one instruction).  The rounding
+// of the intermediate results is not specified; users allow DOT2_ROUNDINGS * 2^-24 * (|a.lo b.lo| + |a.hi b.hi| + |c|)
+// of error per call: twice what the instruction was observed to reach at worst (3.0; the GPU tests repeat that
+// measurement).
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+constexpr float DOT2_ROUNDINGS = 6.0f;
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+    bf16x2 x, y;
+    __builtin_memcpy(&x, &a, 4);
+    __builtin_memcpy(&y, &b, 4);
+    return __builtin_amdgcn_fdot2_f32_bf16(x, y, c, false);
+}
+
 // Slow, always-valid nearest-level search.
 __device__ __forceinline__ int assign_code_generic(float x, const CodebookArgs& cb) {
     int code = 0;

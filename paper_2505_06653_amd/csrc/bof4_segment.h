@@ -132,10 +132,30 @@ __device__ __forceinline__ void block_constant(const uint32_t (&R)[SegCfg<I>::NR
 // Outlier rule of eq. 9 with the corrected sample deviation of appendix E.1, in the square-root-free binary64 form
 //   w^2 I (I-1) > T^2 V,   V = I sum w^2 - (sum w)^2 = fma(-S, S, I Q).
 // Both sides are monotone in |w|, so per block there is one bfloat16 pattern theta with: outlier <=> |w| > theta.
-// theta is found from an approximate square root and settled with the exact binary64 test on its neighbours, so
-// every element's decision equals the direct evaluation of the inequality.  0x7FFF means "no outliers".
+// 0x7FFF means "no outliers".
+
+// theta for a given right-hand side rhs = T^2 V > 0: from an approximate square root, settled with the exact
+// binary64 test on its neighbours, so that (v v) I (I-1) > rhs holds exactly for the patterns above theta.
 template <int I>
-__device__ __forceinline__ uint32_t opq_theta(const uint32_t (&R)[SegCfg<I>::NR], double T2) {
+__device__ __forceinline__ bool opq_is_out(uint32_t b, double rhs) {
+    constexpr double II1 = (double)I * (double)(I - 1);
+    const double v = (double)bf16_bits_to_f32(b);
+    return (v * v) * II1 > rhs;
+}
+template <int I>
+__device__ __forceinline__ uint32_t opq_theta_of(double rhs) {
+    constexpr double II1 = (double)I * (double)(I - 1);
+    const float t = (float)__builtin_sqrt(rhs * (1.0 / II1));  // binary64 root: no under/overflow of tau^2
+    uint32_t b0 = __float_as_uint(t) >> 16;
+    b0 = min(max(b0, 1u), 0x7F7Eu);
+    uint32_t theta = b0 - 1;
+    if (!opq_is_out<I>(b0, rhs)) theta = b0;
+    if (!opq_is_out<I>(b0 + 1, rhs)) theta = b0 + 1;
+    return theta;
+}
+// The plain evaluation: S and Q in binary64 (every term is exact).
+template <int I>
+__device__ __forceinline__ uint32_t opq_theta_exact(const uint32_t (&R)[SegCfg<I>::NR], double T2) {
     using C = SegCfg<I>;
     double S = 0.0, Q = 0.0;
 #pragma unroll
@@ -150,41 +170,75 @@ __device__ __forceinline__ uint32_t opq_theta(const uint32_t (&R)[SegCfg<I>::NR]
         Q += __shfl_xor(Q, m, 64);
     }
     const double V = fma(-S, S, (double)I * Q);
-    uint32_t theta = 0x7FFFu;
-    if (V > 0.0) {
-        constexpr double II1 = (double)I * (double)(I - 1);
-        const double rhs = T2 * V;
-        const float t = (float)__builtin_sqrt(rhs * (1.0 / II1));  // binary64 root: no under/overflow of tau^2
-        uint32_t b0 = __float_as_uint(t) >> 16;
-        b0 = min(max(b0, 1u), 0x7F7Eu);
-        auto is_out = [&](uint32_t b) {
-            double v = (double)bf16_bits_to_f32(b);
-            return (v * v) * II1 > rhs;
-        };
-        theta = b0 - 1;
-        if (!is_out(b0)) theta = b0;
-        if (!is_out(b0 + 1)) theta = b0 + 1;
+    return V > 0.0 ? opq_theta_of<I>(T2 * V) : 0x7FFFu;
+}
+// The same theta at a quarter of the instructions.  S~ and Q~ come from packed binary32 dot products (one per two
+// weights, no unpacking), four chains per lane.  Each chain of L = NR / 4 products with non-negative terms is off by
+// at most DOT2_ROUNDINGS u (L + 1) times its sum (u = 2^-24); joining chains and lanes adds less than 6 u, so
+//   |Q~ - Q| <= eps Q,   |S~ - S| <= eps A,   A = sum |w| <= sqrt(I Q),   eps = (DOT2_ROUNDINGS (L + 1) + 6) u,
+// and V~ = I Q~ - S~^2 is within E = 3.05 eps I Q~ of V.  theta is monotone in V: if theta(V~ - E) also holds at
+// V~ + E it is the exact one.  Otherwise (about one block in 500), or if Q~ is too small or too large for binary32
+// products to be trusted, the wave takes the plain evaluation.
+template <int I>
+__device__ __forceinline__ uint32_t opq_theta(const uint32_t (&R)[SegCfg<I>::NR], double T2) {
+    using C = SegCfg<I>;
+    constexpr uint32_t ONES = 0x3F803F80u;  // (1.0, 1.0)
+    constexpr double EPS = ((double)DOT2_ROUNDINGS * (C::NR / 4 + 1) + 6.0) * 0x1p-24;
+    float q[4] = {0.0f, 0.0f, 0.0f, 0.0f}, s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int d = 0; d < C::NR; ++d) {
+        q[d & 3] = dot2_bf16(R[d], R[d], q[d & 3]);
+        s[d & 3] = dot2_bf16(R[d], ONES, s[d & 3]);
     }
+    float Qf = (q[0] + q[1]) + (q[2] + q[3]), Sf = (s[0] + s[1]) + (s[2] + s[3]);
+#pragma unroll
+    for (int m = 1; m < C::LPB; m <<= 1) {
+        Qf += __shfl_xor(Qf, m, 64);
+        Sf += __shfl_xor(Sf, m, 64);
+    }
+    const double IQ = (double)I * (double)Qf;
+    const double V = fma(-(double)Sf, (double)Sf, IQ), E = (3.05 * EPS) * IQ;
+    bool settled = false;
+    uint32_t theta = 0x7FFFu;
+    if (Qf > 0x1p-80f && Qf < 0x1p100f && V - E > 0.0) {
+        theta = opq_theta_of<I>(T2 * (V - E));
+        settled = opq_is_out<I>(theta + 1, T2 * (V + E));
+    }
+    if (__builtin_amdgcn_ballot_w64(!settled) != 0) theta = opq_theta_exact<I>(R, T2);  // wave-uniform
     return theta;
 }
-// Replace the outliers of the segment by +0 (they then count as x = 0), count them, and note which packed registers
-// held one (bit d of `regmap` for register d).
-template <int I, bool WANT_MAP>
-__device__ __forceinline__ void opq_zero_outliers(uint32_t (&R)[SegCfg<I>::NR], uint32_t theta, uint32_t& count,
-                                                  uint32_t& regmap) {
+
+// Replace the outliers of the segment by +0 (they then count as x = 0) and mark them: packed register d of the
+// segment sets bit (d & 15) of map[d >> 4] for its low half (element 2 d) and bit 16 + (d & 15) for its high half
+// (element 2 d + 1).
+template <int I>
+__device__ __forceinline__ void opq_zero_outliers(uint32_t (&R)[SegCfg<I>::NR], uint32_t theta, uint32_t (&map)[2]) {
     using C = SegCfg<I>;
     const uint32_t th2 = theta * 0x10001u;
-    uint32_t kacc = 0;  // two 16-bit counters
-    regmap = 0;
+    map[0] = map[1] = 0;
 #pragma unroll
-    for (int d = C::NR - 1; d >= 0; --d) {
+    for (int d = 0; d < C::NR; ++d) {
         uint32_t a = R[d] & 0x7fff7fffu;
         uint32_t mask = pk_sign_mask_i16(pk_sub_i16(th2, a));  // 0xFFFF in every half with |w| > theta
         R[d] &= ~mask;
-        kacc = pk_sub_u16(kacc, mask);                         // minus (-1) = plus one, per half
-        if (WANT_MAP) regmap = regmap * 2u + (mask != 0u ? 1u : 0u);
+        map[d >> 4] |= mask & (0x00010001u << (d & 15));
     }
-    count = (kacc & 0xffffu) + (kacc >> 16);
+}
+__device__ __forceinline__ uint32_t opq_count(const uint32_t (&map)[2]) {
+    return (uint32_t)__builtin_popcount(map[0]) + (uint32_t)__builtin_popcount(map[1]);
+}
+// Takes the lowest marked element out of the map and returns its index in the segment (map must not be empty).
+__device__ __forceinline__ uint32_t opq_pop_lowest(uint32_t (&map)[2]) {
+    const bool first = map[0] != 0u;
+    const uint32_t m = first ? map[0] : map[1];
+    const uint32_t lo = m & 0xffffu, hi = m >> 16;
+    const uint32_t klo = lo ? (uint32_t)__builtin_ctz(lo) : 16u, khi = hi ? (uint32_t)__builtin_ctz(hi) : 16u;
+    const bool take_lo = klo <= khi;  // element 2 k before element 2 k + 1
+    const uint32_t k = take_lo ? klo : khi;
+    const uint32_t cleared = m & ~((take_lo ? 1u : 0x10000u) << k);
+    if (first) map[0] = cleared;
+    else map[1] = cleared;
+    return (first ? 0u : 32u) + 2u * k + (take_lo ? 0u : 1u);
 }
 
 // ================================================================================================ quantise
@@ -192,6 +246,9 @@ __device__ __forceinline__ void opq_zero_outliers(uint32_t (&R)[SegCfg<I>::NR], 
 // a region of its own, in ascending flat index, and reports how many it found.  A later pass turns the per-wave
 // counts into offsets and copies the regions into the caller's list.  A wave that finds more than its region holds
 // keeps counting (the count stays exact); the scan pass notices it and the host repeats the call on the general path.
+#ifndef BOF4_Q_MINW
+#define BOF4_Q_MINW 2
+#endif
 struct OutlierStage {
     int64_t* idx;          // [n_waves * region_cap]
     uint16_t* val;         // [n_waves * region_cap]
@@ -200,7 +257,7 @@ struct OutlierStage {
 };
 
 template <int I, bool FAST, bool OPQ>
-__global__ __launch_bounds__(256) void seg_quantize_kernel(const uint4* __restrict__ w, uint64_t n_seg,
+__global__ __launch_bounds__(256, BOF4_Q_MINW) void seg_quantize_kernel(const uint4* __restrict__ w, uint64_t n_seg,
                                                             CodebookArgs cb, BinTable bt, int signed_norm, double T2,
                                                             uint32_t* __restrict__ codes,
                                                             uint16_t* __restrict__ scales, OutlierStage os) {
@@ -232,10 +289,10 @@ __global__ __launch_bounds__(256) void seg_quantize_kernel(const uint4* __restri
         tile_fetch<I>(stage, lane, R);
         const uint64_t seg = t * 64 + lane;
         const bool active = seg < n_seg;
-        uint32_t theta = 0x7FFFu, k_out = 0, regmap = 0;
+        uint32_t k_out = 0, omap[2] = {0, 0};
         if (OPQ) {
-            theta = opq_theta<I>(R, T2);
-            opq_zero_outliers<I, true>(R, theta, k_out, regmap);
+            opq_zero_outliers<I>(R, opq_theta<I>(R, T2), omap);
+            k_out = opq_count(omap);
         }
         uint32_t maxabs, sign;
         block_constant<I>(R, lane, signed_norm != 0, maxabs, sign);
@@ -296,21 +353,14 @@ __global__ __launch_bounds__(256) void seg_quantize_kernel(const uint4* __restri
                 uint32_t pos = wcount + incl - k_out;
                 const uint64_t region = gw * (uint64_t)os.region_cap;
                 const char* myseg = stage + lane * C::PITCH;  // the staged tile still holds the original values
-                while (regmap != 0) {
-                    const uint32_t d = (uint32_t)__builtin_ctz(regmap);
-                    regmap &= regmap - 1;
-                    const uint32_t orig = *reinterpret_cast<const uint32_t*>(myseg + 4 * d);
-#pragma unroll
-                    for (uint32_t h = 0; h < 2; ++h) {
-                        const uint32_t b = h ? (orig >> 16) : (orig & 0xffffu);
-                        if ((b & 0x7fffu) > theta) {
-                            if (pos < os.region_cap) {
-                                os.idx[region + pos] = (int64_t)(seg * C::SEG + 2 * d + h);
-                                os.val[region + pos] = (uint16_t)f32_to_f16_bits(bf16_bits_to_f32(b));
-                            }
-                            ++pos;
-                        }
+                while ((omap[0] | omap[1]) != 0u) {  // lanes run dry at different times
+                    const uint32_t e = opq_pop_lowest(omap);
+                    const uint32_t b = *reinterpret_cast<const uint16_t*>(myseg + 2 * e);
+                    if (pos < os.region_cap) {
+                        os.idx[region + pos] = (int64_t)(seg * C::SEG + e);
+                        os.val[region + pos] = (uint16_t)f32_to_f16_bits(bf16_bits_to_f32(b));
                     }
+                    ++pos;
                 }
                 wcount += total;
             }
@@ -426,8 +476,9 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
         const bool active = seg < n_seg;
         uint32_t k_out = 0;
         if (OPQ) {
-            uint32_t regmap;
-            opq_zero_outliers<I, false>(R, opq_theta<I>(R, T2), k_out, regmap);
+            uint32_t omap[2];
+            opq_zero_outliers<I>(R, opq_theta<I>(R, T2), omap);
+            k_out = opq_count(omap);
         }
         uint32_t maxabs, sign;
         block_constant<I>(R, lane, signed_norm != 0, maxabs, sign);
@@ -435,6 +486,9 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
         const float m_eff = f16_bits_to_f32(f32_to_f16_bits(m));
         const double g = weight_by_max2 ? (double)m_eff * (double)m_eff : 1.0;
         double sxx = 0.0;
+#ifdef BOF4_EXP_SXX4
+        double sxq[4] = {0.0, 0.0, 0.0, 0.0};
+#endif
         bool fast = FAST && __builtin_amdgcn_ballot_w64(!maxabs_is_ordinary(maxabs)) == 0;
         if (active) {
             if (fast) {
@@ -455,9 +509,16 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
                         double xd = (double)x[e];
                         double inc = fma(xd, inc_mul, inc_add);
                         atomicAdd(&acc[code * 64 + lane], (unsigned long long)__double_as_longlong(inc));
+#ifdef BOF4_EXP_SXX4
+                        sxq[e & 3] = fma(xd, xd, sxq[e & 3]);
+#else
                         sxx = fma(xd, xd, sxx);
+#endif
                     }
                 }
+#ifdef BOF4_EXP_SXX4
+                sxx = (sxq[0] + sxq[1]) + (sxq[2] + sxq[3]);
+#endif
             } else {
 #pragma unroll
                 for (int e = 0; e < C::SEG; ++e) {

@@ -67,3 +67,61 @@ extern "C" int bof4_check_pairs(const float* thr15, const float* lv16, const flo
     hipLaunchKernelGGL(check_pairs_kernel, dim3(2 * span), dim3(256), 0, (hipStream_t)stream, cb, bt, out_dev);
     return (int)hipGetLastError();
 }
+
+// ------------------------------------------------------------------------------------------------ dot2 error
+// Measures the error of dot2_bf16 (one v_dot2c_f32_bf16) against the exact value of a.lo b.lo + a.hi b.hi + c on
+// pseudo-random operands, in units of 2^-24 (|a.lo b.lo| + |a.hi b.hi| + |c|) - the quantity the OPQ statistics'
+// error allowance is stated in.  Regimes: 0 general, 1 products that nearly cancel, 2 b = (1, 1) with a running sum,
+// 3 a = b (squares) with a non-negative running sum.  out[r] = bit pattern of the largest ratio seen in regime r
+// (non-negative doubles order like their bit patterns), out[4 + r] = samples.
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z += 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+__device__ __forceinline__ uint32_t bf16_pattern(uint64_t r, int exp_lo, int exp_span) {  // sign, exponent, mantissa
+    const uint32_t sign = (uint32_t)(r & 1u), man = (uint32_t)((r >> 1) & 0x7fu);
+    const uint32_t e = (uint32_t)(127 + exp_lo + (int)((r >> 8) % (uint64_t)exp_span));
+    return (sign << 15) | (e << 7) | man;
+}
+__global__ __launch_bounds__(256) void check_dot2_kernel(uint64_t seed, uint32_t per_thread,
+                                                         unsigned long long* out) {
+    const uint64_t tid = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    double worst[4] = {0.0, 0.0, 0.0, 0.0};
+    for (uint32_t it = 0; it < per_thread; ++it) {
+        const uint64_t r0 = mix64(seed + tid * 0x100000001B3ull + it), r1 = mix64(r0), r2 = mix64(r1);
+        const uint32_t regime = (uint32_t)(r2 >> 62);
+        uint32_t a0 = bf16_pattern(r0, -9, 19), a1 = bf16_pattern(r0 >> 20, -9, 19);
+        uint32_t b0 = bf16_pattern(r1, -9, 19), b1 = bf16_pattern(r1 >> 20, -9, 19);
+        float c = __uint_as_float((uint32_t)((r2 & 0x807fffffu) | ((uint32_t)(127 - 20 + (int)((r2 >> 32) % 41u)) << 23)));
+        if (regime == 1) {  // second product close to minus the first
+            a1 = a0 ^ 0x8000u;
+            b1 = (b0 & 0xff80u) | ((b0 + (uint32_t)((r2 >> 40) & 3u)) & 0x7fu);
+            if ((r2 >> 50) & 1u) c = 0.0f;
+        } else if (regime == 2) {
+            b0 = b1 = 0x3f80u;
+        } else if (regime == 3) {
+            b0 = a0;
+            b1 = a1;
+            c = fabsf(c);
+        }
+        const double p0 = (double)bf16_bits_to_f32(a0) * (double)bf16_bits_to_f32(b0);  // exact: 16-bit products
+        const double p1 = (double)bf16_bits_to_f32(a1) * (double)bf16_bits_to_f32(b1);
+        const double s = p0 + p1;  // exact: the operands' exponents differ by at most 36
+        const double hi = s + (double)c, bb = hi - s;  // hi + lo = s + c exactly (two-sum)
+        const double lo = (s - (hi - bb)) + ((double)c - bb);
+        const float h = dot2_bf16(a0 | (a1 << 16), b0 | (b1 << 16), c);
+        const double err = fabs(((double)h - hi) - lo);
+        const double allowance = 0x1p-24 * (fabs(p0) + fabs(p1) + fabs((double)c));
+        const double ratio = err / allowance;
+        if (ratio > worst[regime]) worst[regime] = ratio;
+        atomicAdd(&out[4 + regime], 1ull);
+    }
+    for (int r = 0; r < 4; ++r) atomicMax(&out[r], (unsigned long long)__double_as_longlong(worst[r]));
+}
+extern "C" int bof4_check_dot2(uint64_t seed, uint32_t blocks, uint32_t per_thread, unsigned long long* out_dev,
+                               void* stream) {
+    hipLaunchKernelGGL(check_dot2_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, seed, per_thread, out_dev);
+    return (int)hipGetLastError();
+}

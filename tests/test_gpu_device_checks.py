@@ -44,3 +44,21 @@ def test_shortcut_division_and_bin_table_equal_the_plain_definitions(name):
     assert bad_range == 0        # |x| <= 1 always
     assert bad_code == 0         # same level as the 15-compare search on the IEEE quotient, tiny weights included
     print(f"{name}: {n} pairs, quotient differs for {bad_tiny} weights below 2^-60 (codes equal)")
+
+
+def test_dot2_error_stays_inside_the_allowance_of_the_opq_statistics():
+    """The approximate OPQ statistics allow DOT2_ROUNDINGS (= 6) * 2^-24 * (|a.lo b.lo| + |a.hi b.hi| + |c|) of error
+    per v_dot2c_f32_bf16; the instruction's measured error (3.0 at worst, as of three truncations) must stay
+    well below that."""
+    L = ctypes.CDLL(os.path.join(HERE, "libbof4_device_checks.so"))
+    L.bof4_check_dot2.argtypes = [ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p]
+    out = torch.zeros(8, dtype=torch.int64, device="cuda")
+    rc = L.bof4_check_dot2(20250506653, 4096, 256, ctypes.c_void_p(out.data_ptr()),
+                           ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    assert rc == 0
+    torch.cuda.synchronize()
+    o = out.cpu().numpy()
+    ratios = o[:4].view(np.float64)
+    print("dot2 error / (2^-24 * sum of magnitudes), worst per regime:", ratios, "samples", o[4:])
+    assert o[4:].sum() == 4096 * 256 * 256 and (o[4:] > 10_000_000).all()
+    assert (ratios <= 3.5).all()
