@@ -169,11 +169,8 @@ QuantWsLayout quant_ws_layout(uint64_t n, uint64_t cap) {
     L.total = o;
     return L;
 }
-#ifndef BOF4_QUANT_GRID
-#define BOF4_QUANT_GRID 512
-#endif
 constexpr uint32_t SEG_GRID = 512;              // persistent workgroups of the Lloyd kernel (2 per CU, LDS-bound)
-constexpr uint32_t QUANT_GRID = BOF4_QUANT_GRID;  // persistent workgroups of the quantise kernel
+constexpr uint32_t QUANT_GRID = 512;              // persistent workgroups of the quantise kernel
 struct SegWsLayout {
     size_t header, wave_count, idx, val, total;
     uint32_t region_cap;
@@ -416,9 +413,8 @@ __global__ void zero_u64_kernel(uint64_t* p) { *p = 0; }
 // One lane decodes 8 codes (one 32-bit load) into 8 bfloat16 (one 16-byte store); a workgroup walks DEQ_VPT chunks of
 // 256 such vectors, all loads first.  w~ = constant * level (section 2.1 eq. 3): one binary32 multiply, rounded to
 // bfloat16 (nearest even) by the hardware conversion.
-#ifndef BOF4_DEQ_VPT
-#define BOF4_DEQ_VPT 4
-#endif
+
+constexpr int DEQ_VPT = 4;  // 16-byte vectors per lane and tile
 constexpr uint64_t DEQ_RESIDENT_WGS = 2048;  // 256 compute units x 8 workgroups of 256 lanes
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
@@ -443,7 +439,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restr
                                                           const uint16_t* __restrict__ out_val, uint64_t n_out,
                                                           uint4* __restrict__ out) {
     constexpr int G = I / 8;
-    constexpr int TILE_VEC = 256 * BOF4_DEQ_VPT;
+    constexpr int TILE_VEC = 256 * DEQ_VPT;
     __shared__ float lv[16];
     __shared__ uint4 stage[OUTLIERS ? TILE_VEC : 1];
     if (threadIdx.x < 16) lv[threadIdx.x] = cb.lv32[threadIdx.x];
@@ -480,16 +476,16 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restr
             }
             if (j + 1 < n_out) pre_nxt = out_idx[j + 1];
         }
-        uint32_t c[BOF4_DEQ_VPT];
-        float s[BOF4_DEQ_VPT];
+        uint32_t c[DEQ_VPT];
+        float s[DEQ_VPT];
 #pragma unroll
-        for (int k = 0; k < BOF4_DEQ_VPT; ++k) {
+        for (int k = 0; k < DEQ_VPT; ++k) {
             const uint64_t v = base + 256 * k;
             c[k] = v < n_vec ? codes[v] : 0u;
             s[k] = v < n_vec ? f16_bits_to_f32(scales[v / G]) : 0.0f;
         }
 #pragma unroll
-        for (int k = 0; k < BOF4_DEQ_VPT; ++k) {
+        for (int k = 0; k < DEQ_VPT; ++k) {
             const uint64_t v = base + 256 * k;
             uint32_t o[4];
 #pragma unroll
@@ -527,7 +523,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restr
             }
             // the barrier inside the loop has ordered the patches before these reads
 #pragma unroll
-            for (int k = 0; k < BOF4_DEQ_VPT; ++k) {
+            for (int k = 0; k < DEQ_VPT; ++k) {
                 const uint64_t v = base + 256 * k;
                 if (v < n_vec) store_stream(&out[v], stage[256 * k + threadIdx.x]);
             }
@@ -744,7 +740,7 @@ int bof4_dequantize(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64
         return fail(BOF4_ERR_ARG, "bof4_dequantize: misaligned pointer");
     hipStream_t s = (hipStream_t)stream;
     const uint64_t n_vec = n / 8;
-    const uint64_t n_tiles = (n_vec + 256 * BOF4_DEQ_VPT - 1) / (256 * BOF4_DEQ_VPT);
+    const uint64_t n_tiles = (n_vec + 256 * DEQ_VPT - 1) / (256 * DEQ_VPT);
     // without a list one workgroup per tile; with one, DEQ_RESIDENT_WGS workgroups that each walk a run of tiles
     uint64_t tiles_per_wg = n_outliers > 0 ? (n_tiles + DEQ_RESIDENT_WGS - 1) / DEQ_RESIDENT_WGS : 1;
     const uint64_t nb = (n_tiles + tiles_per_wg - 1) / tiles_per_wg;

@@ -30,10 +30,17 @@ constexpr int LLOYD_PART = 56;  // doubles per per-wave partial: A[16] den15[16]
 template <int I>
 __device__ __forceinline__ void tile_issue_loads(const uint4* __restrict__ w, uint64_t first_vec, uint64_t n_vec,
                                                  uint32_t lane, uint4 (&G)[SegCfg<I>::NV]) {
+    constexpr int NV = SegCfg<I>::NV;
+    if (first_vec + 64 * NV <= n_vec) {  // wave-uniform: a whole tile, one address and constant offsets
+        const uint4* p = w + first_vec + lane;
 #pragma unroll
-    for (int k = 0; k < SegCfg<I>::NV; ++k) {
-        uint64_t v = first_vec + (uint64_t)(64 * k) + lane;
-        G[k] = v < n_vec ? load_stream(&w[v]) : make_uint4(0, 0, 0, 0);
+        for (int k = 0; k < NV; ++k) G[k] = load_stream(p + 64 * k);
+    } else {
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            uint64_t v = first_vec + (uint64_t)(64 * k) + lane;
+            G[k] = v < n_vec ? load_stream(&w[v]) : make_uint4(0, 0, 0, 0);
+        }
     }
 }
 template <int I>
@@ -246,9 +253,6 @@ __device__ __forceinline__ uint32_t opq_pop_lowest(uint32_t (&map)[2]) {
 // a region of its own, in ascending flat index, and reports how many it found.  A later pass turns the per-wave
 // counts into offsets and copies the regions into the caller's list.  A wave that finds more than its region holds
 // keeps counting (the count stays exact); the scan pass notices it and the host repeats the call on the general path.
-#ifndef BOF4_Q_MINW
-#define BOF4_Q_MINW 2
-#endif
 struct OutlierStage {
     int64_t* idx;          // [n_waves * region_cap]
     uint16_t* val;         // [n_waves * region_cap]
@@ -257,7 +261,7 @@ struct OutlierStage {
 };
 
 template <int I, bool FAST, bool OPQ>
-__global__ __launch_bounds__(256, BOF4_Q_MINW) void seg_quantize_kernel(const uint4* __restrict__ w, uint64_t n_seg,
+__global__ __launch_bounds__(256) void seg_quantize_kernel(const uint4* __restrict__ w, uint64_t n_seg,
                                                             CodebookArgs cb, BinTable bt, int signed_norm, double T2,
                                                             uint32_t* __restrict__ codes,
                                                             uint16_t* __restrict__ scales, OutlierStage os) {
@@ -486,9 +490,6 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
         const float m_eff = f16_bits_to_f32(f32_to_f16_bits(m));
         const double g = weight_by_max2 ? (double)m_eff * (double)m_eff : 1.0;
         double sxx = 0.0;
-#ifdef BOF4_EXP_SXX4
-        double sxq[4] = {0.0, 0.0, 0.0, 0.0};
-#endif
         bool fast = FAST && __builtin_amdgcn_ballot_w64(!maxabs_is_ordinary(maxabs)) == 0;
         if (active) {
             if (fast) {
@@ -509,16 +510,10 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
                         double xd = (double)x[e];
                         double inc = fma(xd, inc_mul, inc_add);
                         atomicAdd(&acc[code * 64 + lane], (unsigned long long)__double_as_longlong(inc));
-#ifdef BOF4_EXP_SXX4
-                        sxq[e & 3] = fma(xd, xd, sxq[e & 3]);
-#else
                         sxx = fma(xd, xd, sxx);
-#endif
                     }
                 }
-#ifdef BOF4_EXP_SXX4
-                sxx = (sxq[0] + sxq[1]) + (sxq[2] + sxq[3]);
-#endif
+
             } else {
 #pragma unroll
                 for (int e = 0; e < C::SEG; ++e) {
@@ -540,7 +535,10 @@ __global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict_
                 unsigned long long v = col[l];
                 uint32_t hi = (uint32_t)(v >> 32), lo = (uint32_t)v;
                 uint32_t k15 = hi >> 20;
-                double D = __hiloint2double((int)((hi & 0xFFFFFu) | 0x43300000u), (int)lo) - 0x1p52;  // sum (x+1) 2^40
+                // 2^52 + sum: the column's mantissa under the exponent of 2^52 (one bit-field insert)
+                uint32_t dhi;
+                asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(dhi) : "v"(0xFFFFFu), "v"(hi), "v"(0x43300000u));
+                double D = __hiloint2double((int)dhi, (int)lo) - 0x1p52;  // sum (x+1) 2^40
                 A[l] = fma(gs, D, A[l]);
                 den15[l] = fma(g, (double)k15, den15[l]);
                 cnt15[l] += k15;
