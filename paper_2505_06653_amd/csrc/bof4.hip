@@ -434,7 +434,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2_rne(float lo, float hi) {
 template <int I, bool OUTLIERS>
 __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restrict__ codes,
                                                           const uint16_t* __restrict__ scales, uint64_t n_vec,
-                                                          uint32_t tiles_per_wg, CodebookArgs cb,
+                                                          uint32_t tiles_per_wg, uint32_t window, CodebookArgs cb,
                                                           const int64_t* __restrict__ out_idx,
                                                           const uint16_t* __restrict__ out_val, uint64_t n_out,
                                                           uint4* __restrict__ out) {
@@ -444,7 +444,15 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restr
     __shared__ uint4 stage[OUTLIERS ? TILE_VEC : 1];
     if (threadIdx.x < 16) lv[threadIdx.x] = cb.lv32[threadIdx.x];
     __syncthreads();
-    const uint64_t first_tile = (uint64_t)blockIdx.x * tiles_per_wg;
+    // Workgroups go to the 8 accelerator dies (XCDs, each with an L2 of its own) in turn.  With a list, die k takes
+    // the k-th eighth of the runs, so that the stretch of the list a die's workgroups search and walk is fetched
+    // into one L2 only.
+    uint32_t run = blockIdx.x;
+    if (OUTLIERS) {
+        const uint32_t q = gridDim.x / 8, r = gridDim.x % 8, k = blockIdx.x % 8;
+        run = k * q + (k < r ? k : r) + blockIdx.x / 8;
+    }
+    const uint64_t first_tile = (uint64_t)run * tiles_per_wg;
     uint64_t lo = 0;
     if (OUTLIERS) {
         // first list position whose index is >= the workgroup's first weight; invariant: every entry before lo is
@@ -465,10 +473,10 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restr
         const uint64_t tile = first_tile + t;
         const uint64_t base = tile * TILE_VEC + threadIdx.x;
         if (tile * TILE_VEC >= n_vec) break;
-        // the first 256 list entries from the current position travel together with the codes
+        // the next `window` list entries (the host sizes it to what a tile usually holds) travel with the codes
         int64_t pre_i = -1, pre_nxt = -1;
         uint32_t pre_val = 0;
-        if (OUTLIERS) {
+        if (OUTLIERS && threadIdx.x < window) {
             const uint64_t j = lo + threadIdx.x;
             if (j < n_out) {
                 pre_i = out_idx[j];
@@ -504,22 +512,23 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restr
             uint16_t* stage16 = reinterpret_cast<uint16_t*>(stage);
             for (bool first = true;; first = false) {
                 const uint64_t j = lo + threadIdx.x;
+                const bool mine = threadIdx.x < window;
                 int64_t i = pre_i, nxt = pre_nxt;
                 uint32_t val = pre_val;
                 if (!first) {
                     i = nxt = -1;
-                    if (j < n_out) {
+                    if (mine && j < n_out) {
                         i = out_idx[j];
                         val = out_val[j];
                     }
-                    if (j + 1 < n_out) nxt = out_idx[j + 1];
+                    if (mine && j + 1 < n_out) nxt = out_idx[j + 1];
                 }
-                const int inside = (j < n_out && i >= tile_begin && i < tile_end) ? 1 : 0;
+                const int inside = (mine && j < n_out && i >= tile_begin && i < tile_end) ? 1 : 0;
                 // of several entries with one index the last one counts
                 if (inside && nxt != i) stage16[i - tile_begin] = (uint16_t)f32_to_bf16_rne(f16_bits_to_f32(val));
                 const uint32_t cnt = (uint32_t)__syncthreads_count(inside);
                 lo += cnt;
-                if (cnt < 256) break;
+                if (cnt < window) break;
             }
             // the barrier inside the loop has ordered the patches before these reads
 #pragma unroll
@@ -748,16 +757,19 @@ int bof4_dequantize(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64
         return fail(BOF4_ERR_ARG, "bof4_dequantize: n too large for one call");
     CodebookArgs cb = make_codebook_args(cb_host);
     dim3 grid((uint32_t)nb);
+    // list entries a workgroup looks at per round: what a tile holds on average, rounded up to whole waves
+    uint32_t window = 64;
+    while (window < 256 && (double)window * (double)n_tiles < (double)n_outliers) window += 64;
     const uint32_t* codes = (const uint32_t*)codes_dev;
     uint4* out = (uint4*)w_out_dev;
     timing_begin(s);
 #define BOF4_LAUNCH_DEQ(I_)                                                                                        \
     if (n_outliers > 0)                                                                                            \
         hipLaunchKernelGGL((dequantize_kernel<I_, true>), grid, dim3(256), 0, s, codes, scales_dev, n_vec,          \
-                           (uint32_t)tiles_per_wg, cb, out_idx_dev, out_val_dev, n_outliers, out);                                             \
+                           (uint32_t)tiles_per_wg, window, cb, out_idx_dev, out_val_dev, n_outliers, out);         \
     else                                                                                                           \
         hipLaunchKernelGGL((dequantize_kernel<I_, false>), grid, dim3(256), 0, s, codes, scales_dev, n_vec,         \
-                           (uint32_t)tiles_per_wg, cb, out_idx_dev, out_val_dev, n_outliers, out);
+                           (uint32_t)tiles_per_wg, window, cb, out_idx_dev, out_val_dev, n_outliers, out);
     switch (block) {
         case 32: BOF4_LAUNCH_DEQ(32) break;
         case 64: BOF4_LAUNCH_DEQ(64) break;
