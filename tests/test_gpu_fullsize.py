@@ -71,14 +71,21 @@ def test_config3_opq_stress(block):
     assert_stats_close(binding.bof4_lloyd_step(w, block, cb, 1, opq_T=T), o)
 
 
-def test_config2_codebook_optimisation_13GB():
-    """Workload 2: 32 Llama-7B-shaped blocks resident (6,476,005,376 weights, 12.95 GB), signed absmax, Lloyd
-    iterations from the quantile start; the first two iterations are compared with the oracle."""
+@pytest.fixture(scope="module")
+def workload2():
     parts = [inputs.flatten(inputs.llama7b_block(seed=1000 + b, device=DEV)) for b in range(32)]
     w = torch.cat(parts)
     del parts
     assert w.numel() == 6_476_005_376
-    wb = host_bits(w)
+    yield w, host_bits(w)
+    del w
+    torch.cuda.empty_cache()
+
+
+def test_config2_codebook_optimisation_13GB(workload2):
+    """Workload 2: 32 Llama-7B-shaped blocks resident (6,476,005,376 weights, 12.95 GB), signed absmax, Lloyd
+    iterations from the quantile start; the first two iterations are compared with the oracle."""
+    w, wb = workload2
     cb = codebooks.gaussian_quantile_init()
     ws = binding.alloc_workspace(w.numel(), 64)
     prev = None
@@ -92,6 +99,36 @@ def test_config2_codebook_optimisation_13GB():
         assert prev is None or mse <= prev
         prev = mse
         cb = binding.bof4_codebook_update(g, codebooks.PIN_BOF4S, cb)
+
+
+def test_config2_quantize_dequantize_beyond_2_32_weights(workload2):
+    """The same 6.48 G weights through quantise (OPQ on) and dequantise: flat outlier indices pass 2^32, every code,
+    constant, list entry and decoded weight is compared."""
+    w, wb = workload2
+    T = binding.bof4_opq_threshold(0.95, 64)
+    cb = codebooks.array(codebooks.BOF4S_MSE[64])
+    n = wb.size
+    o_codes, o_scales, o_idx, o_val, o_n = par_oracle.quantize(wb, 64, cb, 1, T)
+    assert o_idx[-1] > 2 ** 32
+    g_codes, g_scales, g_idx, g_val, g_n = binding.bof4_quantize(w, 64, cb, 1, opq_T=T, out_capacity=n // 64)
+    torch.cuda.synchronize()
+    assert g_n == o_n
+    assert np.array_equal(host_bits(g_scales), o_scales)
+    assert np.array_equal(g_codes.cpu().numpy(), o_codes)
+    assert np.array_equal(g_idx.cpu().numpy(), o_idx)
+    assert np.array_equal(host_bits(g_val), o_val)
+    del o_codes
+    g_deq = binding.bof4_dequantize(g_codes, g_scales, n, 64, cb, g_idx, g_val)
+    torch.cuda.synchronize()
+    # decoded weights: the oracle decodes the GPU's (already verified) codes chunk by chunk
+    gc, gs = g_codes.cpu().numpy(), host_bits(g_scales)
+    step = 64 * (1 << 22)
+    for lo in range(0, n, step):
+        hi = min(n, lo + step)
+        a, b = np.searchsorted(o_idx, [lo, hi])
+        o_deq = par_oracle.dequantize(gc[lo // 2:hi // 2], gs[lo // 64:hi // 64], hi - lo, 64, cb, o_idx[a:b] - lo,
+                                      o_val[a:b])
+        assert np.array_equal(host_bits(g_deq[lo:hi]), o_deq), f"decoded weights differ in [{lo}, {hi})"
 
 
 @pytest.mark.parametrize("block", [64, 128, 256])

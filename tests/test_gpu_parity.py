@@ -218,6 +218,28 @@ def test_dequantize_outlier_write_back_clusters(block):
     assert np.array_equal(to_np_u16(got), deq)
 
 
+def test_dequantize_skips_list_entries_outside_the_tensor():
+    """Entries below 0 or at/after n (the oracle rejects such a list) are ignored; the rest is written as usual."""
+    g = torch.Generator().manual_seed(23)
+    n, block = 64 * 150, 64  # one full decoder tile and a ragged second one
+    codes = torch.randint(0, 256, (n // 2,), generator=g, dtype=torch.int32).to(torch.uint8)
+    scales = (torch.randn(n // block, generator=g) * 0.05).to(torch.float16)
+    good = np.array(sorted(set(torch.randint(0, n, (40,), generator=g).tolist() + [0, n - 1])), dtype=np.int64)
+    idx = np.concatenate([np.array([-7, -1], dtype=np.int64), good, np.array([n, n + 5, 2 ** 40], dtype=np.int64)])
+    val = (torch.randn(idx.size, generator=g) * 3).to(torch.float16)
+    cb = cb_for(block, 1)
+    val_np = val.view(torch.int16).numpy().view(np.uint16)
+    st, deq = oracle.dequantize(codes.numpy(), scales.view(torch.int16).numpy().view(np.uint16), n, block, cb, good,
+                                val_np[2:2 + good.size])
+    assert st == oracle.OK
+    out = torch.full((n + 64,), 7.0, dtype=torch.bfloat16, device=DEV)  # guard band behind the tensor
+    binding.bof4_dequantize(codes.to(DEV), scales.to(DEV), n, block, cb, torch.from_numpy(idx).to(DEV), val.to(DEV),
+                            out=out[:n])
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np_u16(out[:n]), deq)
+    assert bool((out[n:] == 7.0).all())
+
+
 def test_capacity_overflow_and_workspace_errors():
     w = make_weights(16, 1024, seed=77)
     T = oracle.opq_threshold(0.95, 64)
