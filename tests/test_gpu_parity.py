@@ -277,3 +277,33 @@ def test_results_in_pinned_host_memory_are_written_in_place():
     b = binding.bof4_quantize(wd, 64, cb, 1, opq_T=T, out_capacity=4096, counter=ctr)
     assert a[4] == b[4] == ctr.value and a[4] > 0
     assert torch.equal(a[2], b[2]) and torch.equal(a[0], b[0])
+
+
+@pytest.mark.parametrize("pinned", [False, True])
+def test_calls_on_a_side_stream(pinned):
+    """The whole path on a stream of the caller's (not the default one), with results in ordinary and in pinned host
+    memory; many calls back to back so that a result read too early, or work that escaped the stream's order, would
+    show.  Compared with the oracle."""
+    side = torch.cuda.Stream()
+    cb = cb_for(64, 1)
+    T = oracle.opq_threshold(0.95, 64)
+    rec, keep = binding.pinned_lloyd_stats() if pinned else (None, None)
+    ctr, keep2 = binding.pinned_counter() if pinned else (None, None)
+    for rep in range(6):
+        w = make_weights(96 + 8 * rep, 1024, seed=400 + rep)
+        wb = inputs.bits(w)
+        st, o_codes, o_scales, o_idx, o_val, o_n = oracle.quantize(wb, 64, cb, 1, opq_T=T)
+        st, o_deq = oracle.dequantize(o_codes, o_scales, wb.size, 64, cb, o_idx, o_val)
+        st, o_stats = oracle.lloyd_step(wb, 64, cb, 1, opq_T=T)
+        wd = w.to(DEV)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            gc, gs, gi, gv, gn = binding.bof4_quantize(wd, 64, cb, 1, opq_T=T, out_capacity=o_n + 8, stream=side,
+                                                       counter=ctr)
+            gd = binding.bof4_dequantize(gc, gs, wb.size, 64, cb, gi, gv, stream=side)
+            g_stats = binding.bof4_lloyd_step(wd, 64, cb, 1, opq_T=T, stream=side, out=rec)
+        side.synchronize()
+        assert gn == o_n and np.array_equal(gi.cpu().numpy(), o_idx) and np.array_equal(to_np_u16(gv), o_val)
+        assert np.array_equal(gc.cpu().numpy(), o_codes) and np.array_equal(to_np_u16(gs), o_scales)
+        assert np.array_equal(to_np_u16(gd), o_deq)
+        assert_stats_close(g_stats, o_stats)
