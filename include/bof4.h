@@ -6,7 +6,7 @@
  *   - "dev" pointers are device (HBM) addresses owned by the caller; "host" pointers are ordinary host memory.
  *     The library keeps no state between calls, allocates nothing and frees nothing.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Work is enqueued on it; a call that
- *     returns results to host memory synchronises that stream before returning (stated per call).
+ *     returns results to host memory waits for them before returning (how is stated per call).
  *   - Weights are bfloat16 bit patterns, flat; block b is elements [b*block, (b+1)*block).  `block` must be
  *     32, 64, 128 or 256 and `n` a positive multiple of it.
  *   - A codebook is 16 finite, strictly ascending doubles (host).  Code c means level index c (paper level c+1).

@@ -170,7 +170,7 @@ QuantWsLayout quant_ws_layout(uint64_t n, uint64_t cap) {
     return L;
 }
 constexpr uint32_t SEG_GRID = 512;              // persistent workgroups of the Lloyd kernel (2 per CU, LDS-bound)
-constexpr uint32_t QUANT_GRID = 512;              // persistent workgroups of the quantise kernel
+constexpr uint32_t QUANT_GRID = 768;              // persistent workgroups of the quantise kernel (3 per CU)
 struct SegWsLayout {
     size_t header, wave_count, idx, val, total;
     uint32_t region_cap;

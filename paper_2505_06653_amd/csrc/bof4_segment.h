@@ -260,8 +260,10 @@ struct OutlierStage {
     uint32_t region_cap;
 };
 
+// Three workgroups per compute unit (three waves per SIMD): the launch bound holds the register count to what that
+// takes; with outlier extraction the kernel is bound by instruction issue and the third wave is worth 8 %.
 template <int I, bool FAST, bool OPQ>
-__global__ __launch_bounds__(256) void seg_quantize_kernel(const uint4* __restrict__ w, uint64_t n_seg,
+__global__ __launch_bounds__(256, 3) void seg_quantize_kernel(const uint4* __restrict__ w, uint64_t n_seg,
                                                             CodebookArgs cb, BinTable bt, int signed_norm, double T2,
                                                             uint32_t* __restrict__ codes,
                                                             uint16_t* __restrict__ scales, OutlierStage os) {
