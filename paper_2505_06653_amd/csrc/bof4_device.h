@@ -126,6 +126,20 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
     return __builtin_amdgcn_fdot2_f32_bf16(x, y, c, false);
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves (6 additions): shifts by
+// 1, 2, 4, 8 inside each row of 16 lanes (lanes shifted in from outside the row read 0), then lane 15 of every row
+// is added to the whole next odd row, then lane 31 to the upper half.  All 64 lanes must be active.
+__device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t x) {
+    int v = (int)x;
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
+    return (uint32_t)v;
+}
+
 // Slow, always-valid nearest-level search.
 __device__ __forceinline__ int assign_code_generic(float x, const CodebookArgs& cb) {
     int code = 0;

@@ -348,13 +348,9 @@ __global__ __launch_bounds__(256, 3) void seg_quantize_kernel(const uint4* __res
             if ((lane & (C::LPB - 1)) == 0) scales[seg / C::LPB] = (uint16_t)s16;
         }
         if (OPQ) {
-            uint32_t incl = k_out;  // inclusive prefix of the per-lane counts = order of the flat indices
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                uint32_t up = (uint32_t)__shfl_up((int)incl, d, 64);
-                if (lane >= (uint32_t)d) incl += up;
-            }
-            const uint32_t total = (uint32_t)__shfl((int)incl, 63, 64);
+            // inclusive prefix of the per-lane counts = order of the flat indices
+            const uint32_t incl = wave_inclusive_scan_u32(k_out);
+            const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
             if (total != 0) {  // wave-uniform
                 uint32_t pos = wcount + incl - k_out;
                 const uint64_t region = gw * (uint64_t)os.region_cap;

@@ -125,3 +125,31 @@ extern "C" int bof4_check_dot2(uint64_t seed, uint32_t blocks, uint32_t per_thre
     hipLaunchKernelGGL(check_dot2_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, seed, per_thread, out_dev);
     return (int)hipGetLastError();
 }
+
+// ------------------------------------------------------------------------------------------------ wave scan
+// wave_inclusive_scan_u32 against a serial prefix sum over the wave's values (read back through LDS).
+// out[0] = mismatching lanes, out[1] = lanes checked.
+__global__ __launch_bounds__(256) void check_scan_kernel(uint64_t seed, uint32_t rounds, unsigned long long* out) {
+    __shared__ uint32_t vals[256];
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned long long bad = 0, n = 0;
+    for (uint32_t it = 0; it < rounds; ++it) {
+        const uint64_t r = mix64(seed + ((uint64_t)blockIdx.x * 256 + threadIdx.x) * 0x100000001B3ull + it);
+        // small counts (as in the kernels), now and then large values whose sums wrap around
+        const uint32_t x = (r & 0x300) ? (uint32_t)(r & 7u) : (uint32_t)(r >> 32);
+        vals[threadIdx.x] = x;
+        __syncthreads();
+        uint32_t ref = 0;
+        for (uint32_t j = 0; j <= lane; ++j) ref += vals[wave * 64 + j];
+        __syncthreads();
+        if (wave_inclusive_scan_u32(x) != ref) ++bad;
+        ++n;
+    }
+    atomicAdd(&out[0], bad);
+    atomicAdd(&out[1], n);
+}
+extern "C" int bof4_check_scan(uint64_t seed, uint32_t blocks, uint32_t rounds, unsigned long long* out_dev,
+                               void* stream) {
+    hipLaunchKernelGGL(check_scan_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, seed, rounds, out_dev);
+    return (int)hipGetLastError();
+}

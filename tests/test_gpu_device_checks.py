@@ -62,3 +62,15 @@ def test_dot2_error_stays_inside_the_allowance_of_the_opq_statistics():
     print("dot2 error / (2^-24 * sum of magnitudes), worst per regime:", ratios, "samples", o[4:])
     assert o[4:].sum() == 4096 * 256 * 256 and (o[4:] > 10_000_000).all()
     assert (ratios <= 3.5).all()
+
+
+def test_wave_prefix_sum_with_dpp_moves_equals_the_serial_sum():
+    L = ctypes.CDLL(os.path.join(HERE, "libbof4_device_checks.so"))
+    L.bof4_check_scan.argtypes = [ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p]
+    out = torch.zeros(2, dtype=torch.int64, device="cuda")
+    rc = L.bof4_check_scan(7, 512, 64, ctypes.c_void_p(out.data_ptr()),
+                           ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    assert rc == 0
+    torch.cuda.synchronize()
+    bad, n = out.cpu().numpy()
+    assert n == 512 * 256 * 64 and bad == 0
