@@ -59,7 +59,7 @@ def lib():
         L.bof4_lloyd_step.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint32, f64p, ctypes.c_int, ctypes.c_double,
                                       ctypes.c_int, ctypes.POINTER(LloydStats), vp, ctypes.c_size_t, vp]
         L.bof4_codebook_update.restype = ctypes.c_int
-        L.bof4_codebook_update.argtypes = [ctypes.POINTER(LloydStats), ctypes.c_uint16, f64p]
+        L.bof4_codebook_update.argtypes = [ctypes.POINTER(LloydStats), ctypes.c_uint16, vp]
         L.bof4_quantize.restype = ctypes.c_int
         L.bof4_quantize.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint32, f64p, ctypes.c_int, ctypes.c_double,
                                     vp, vp, vp, vp, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint64), vp,
@@ -80,21 +80,44 @@ def _check(code, allow=()):
     return code
 
 
+_F64P = ctypes.POINTER(ctypes.c_double)
+_cb_cache = {}  # id(array) -> (array, pointer); holding the array keeps its id from being reused
+
+
 def _cb(cb):
-    cb = np.ascontiguousarray(cb, dtype=np.float64)
-    if cb.shape != (16,):
+    """Codebook as a contiguous float64[16] array plus its ctypes pointer.  Arrays that already have that form are
+    passed through, and their pointer object is kept (building one costs more than the rest of a call's marshalling)."""
+    hit = _cb_cache.get(id(cb))
+    if hit is not None and hit[0] is cb:
+        return cb, hit[1]
+    arr = cb if (type(cb) is np.ndarray and cb.dtype == np.float64 and cb.flags.c_contiguous) \
+        else np.ascontiguousarray(cb, dtype=np.float64)
+    if arr.shape != (16,):
         raise ValueError("codebook must have 16 levels")
-    return cb, cb.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+    ptr = arr.ctypes.data_as(_F64P)
+    if arr is cb:
+        if len(_cb_cache) >= 16:
+            _cb_cache.clear()
+        _cb_cache[id(cb)] = (cb, ptr)
+    return arr, ptr
 
 
 def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
+try:
+    _raw_stream = torch._C._cuda_getCurrentRawStream  # the current stream's handle without building a Stream object
+except AttributeError:  # pragma: no cover
+    _raw_stream = None
+
+
 def _stream(stream):
-    if stream is None:
-        stream = torch.cuda.current_stream()
-    return ctypes.c_void_p(stream.cuda_stream)
+    if stream is not None:
+        return ctypes.c_void_p(stream.cuda_stream)
+    if _raw_stream is not None:
+        return ctypes.c_void_p(_raw_stream(torch.cuda.current_device()))
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
 def bof4_workspace_bytes(n, block, out_capacity=0):
@@ -125,17 +148,17 @@ def bof4_bin_table(cb):
 
 def bof4_codebook_update(stats, pinned_mask, cb):
     """stats: LloydStats (as returned by bof4_lloyd_step(..., raw=True)) or its dict form.  Returns new float64[16]."""
-    cb, _ = _cb(cb)
-    cb = cb.copy()
+    out = np.array(cb, dtype=np.float64)  # a copy: the C function updates in place
+    if out.shape != (16,):
+        raise ValueError("codebook must have 16 levels")
     if not isinstance(stats, LloydStats):
         s = LloydStats()
         for l in range(16):
             s.num[l], s.den[l], s.cnt[l] = float(stats["num"][l]), float(stats["den"][l]), int(stats["cnt"][l])
         s.sse, s.n_used, s.n_outliers = float(stats["sse"]), int(stats["n_used"]), int(stats["n_outliers"])
         stats = s
-    _check(lib().bof4_codebook_update(ctypes.byref(stats), pinned_mask,
-                                      cb.ctypes.data_as(ctypes.POINTER(ctypes.c_double))))
-    return cb
+    _check(lib().bof4_codebook_update(ctypes.byref(stats), pinned_mask, out.ctypes.data))
+    return out
 
 
 def bof4_time_next_call(start_event, stop_event):
