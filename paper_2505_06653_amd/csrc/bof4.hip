@@ -249,6 +249,10 @@ __device__ __forceinline__ double group_sum_f64(double v) {
 }
 
 // ------------------------------------------------------------------------------------------------ quantise
+// General path, slower than the segment kernel of bof4_segment.h and taken only when a wave of that kernel found more
+// outliers than its staging region holds: tiles append their outliers through one global counter, so any
+// distribution of outliers over the tensor fits the caller's capacity.  Plain binary64 OPQ statistics, IEEE
+// division, 15 compares.
 // One lane owns 8 consecutive weights (one 16-byte load); a block of I weights spans I/8 neighbouring lanes.
 template <int I, bool SIGNED, bool OPQ>
 __global__ __launch_bounds__(256) void quantize_kernel(const uint4* __restrict__ w, uint64_t n_vec,
