@@ -493,7 +493,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restr
 #pragma unroll
         for (int k = 0; k < DEQ_VPT; ++k) {
             const uint64_t v = base + 256 * k;
-            c[k] = v < n_vec ? codes[v] : 0u;
+            c[k] = v < n_vec ? __builtin_nontemporal_load(&codes[v]) : 0u;
             s[k] = v < n_vec ? f16_bits_to_f32(scales[v / G]) : 0.0f;
         }
 #pragma unroll
