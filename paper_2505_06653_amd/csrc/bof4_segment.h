@@ -432,7 +432,7 @@ constexpr double LLOYD_INC_ADD = 0x1p-1008 + 0x1p-1020;
 constexpr int LLOYD_BATCH = 16;
 
 template <int I, bool FAST, bool OPQ>
-__global__ __launch_bounds__(256) void seg_lloyd_kernel(const uint4* __restrict__ w, uint64_t n_seg, CodebookArgs cb,
+__global__ __launch_bounds__(256, 2) void seg_lloyd_kernel(const uint4* __restrict__ w, uint64_t n_seg, CodebookArgs cb,
                                                          BinTable bt, int signed_norm, int weight_by_max2, double T2,
                                                          double inc_mul, double inc_add,
                                                          double* __restrict__ partials) {
