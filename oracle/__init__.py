@@ -27,6 +27,16 @@ class LloydStats(ctypes.Structure):
                 "n_used": int(self.n_used), "n_outliers": int(self.n_outliers)}
 
 
+class MaeStats(ctypes.Structure):
+    _fields_ = [("median", ctypes.c_double * 16), ("den", ctypes.c_double * 16), ("cnt", ctypes.c_uint64 * 16),
+                ("sae", ctypes.c_double), ("n_used", ctypes.c_uint64), ("n_outliers", ctypes.c_uint64)]
+
+    def as_dict(self):
+        return {"median": np.array(self.median[:], dtype=np.float64), "den": np.array(self.den[:], dtype=np.float64),
+                "cnt": np.array(self.cnt[:], dtype=np.uint64), "sae": float(self.sae),
+                "n_used": int(self.n_used), "n_outliers": int(self.n_outliers)}
+
+
 def lib():
     global _lib
     if _lib is None:
@@ -50,6 +60,11 @@ def lib():
                                         ctypes.c_double, ctypes.c_int, ctypes.POINTER(LloydStats)]
         L.oracle_codebook_update.restype = ctypes.c_int
         L.oracle_codebook_update.argtypes = [ctypes.POINTER(LloydStats), ctypes.c_uint16, f64p]
+        L.oracle_lloyd_step_mae.restype = ctypes.c_int
+        L.oracle_lloyd_step_mae.argtypes = [u16p, ctypes.c_uint64, ctypes.c_uint32, f64p, ctypes.c_int,
+                                            ctypes.c_double, ctypes.POINTER(MaeStats)]
+        L.oracle_codebook_update_mae.restype = ctypes.c_int
+        L.oracle_codebook_update_mae.argtypes = [ctypes.POINTER(MaeStats), ctypes.c_uint16, f64p]
         L.oracle_f32_to_f16.restype = ctypes.c_uint16
         L.oracle_f32_to_f16.argtypes = [ctypes.c_float]
         L.oracle_f16_to_f32.restype = ctypes.c_float
@@ -138,6 +153,28 @@ def codebook_update(stats, pinned_mask, cb):
     s.n_used = int(stats["n_used"])
     s.n_outliers = int(stats["n_outliers"])
     st = lib().oracle_codebook_update(ctypes.byref(s), pinned_mask, _p(cb, ctypes.c_double))
+    assert st == OK
+    return cb
+
+
+def lloyd_step_mae(w, block, cb, signed, opq_T=0.0):
+    """MAE criterion (weighted medians).  Returns (status, dict with median, den, cnt, sae, n_used, n_outliers)."""
+    w, cb = _w(w), _cb(cb)
+    s = MaeStats()
+    st = lib().oracle_lloyd_step_mae(_p(w, ctypes.c_uint16), w.size, block, _p(cb, ctypes.c_double), int(signed),
+                                     float(opq_T), ctypes.byref(s))
+    return st, s.as_dict()
+
+
+def codebook_update_mae(stats, pinned_mask, cb):
+    """Returns the updated float64[16] codebook (input is not modified)."""
+    cb = _cb(cb).copy()
+    s = MaeStats()
+    for l in range(16):
+        s.median[l] = float(stats["median"][l])
+        s.den[l] = float(stats["den"][l])
+        s.cnt[l] = int(stats["cnt"][l])
+    st = lib().oracle_codebook_update_mae(ctypes.byref(s), pinned_mask, _p(cb, ctypes.c_double))
     assert st == OK
     return cb
 

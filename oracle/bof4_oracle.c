@@ -15,6 +15,9 @@
  *   lloyd step / update        : weighted SSE non-increasing; fixed point on Gaussian samples equals the
  *                                numerically integrated closed form (appendix B.2) and the printed codebooks
  *   OPQ threshold / detection  : closed form F_M^{-1}; Monte-Carlo exceedance = 1-q; planted single outlier
+ *   MAE step (weighted median): brute-force minimiser of sum a|x - c| on tiny inputs; the plain lower median
+ *                                when all blocks weigh the same; fixed point on Gaussian samples equals the
+ *                                printed MAE codebooks
  *   tie rules (equal |w| of opposite sign, exact mid-point x, all-zero block, -0.0): parity unpinned by the
  *   paper - fixed only by the definitions written below.
  *
@@ -372,6 +375,130 @@ int oracle_codebook_update(const oracle_lloyd_stats* st, uint16_t pinned_mask, d
     for (int l = 0; l < NLEVELS; ++l) {
         if ((pinned_mask >> l) & 1u) continue;
         if (st->den[l] > 0.0) cb[l] = st->num[l] / st->den[l];
+    }
+    return ORACLE_OK;
+}
+
+/* ---------------------------------------------------------------- Lloyd / EM, MAE criterion ---------------- */
+
+typedef struct {
+    double median[NLEVELS]; /* weighted median of the normalised weights of region l (NaN: no weight there)   */
+    double den[NLEVELS];    /* sum over region l of |block constant|                                          */
+    uint64_t cnt[NLEVELS];  /* K_l                                                                            */
+    double sae;             /* sum of |block constant| * |x - level[code]|: n_used * MAE(W, Q(W))             */
+    uint64_t n_used;
+    uint64_t n_outliers;
+} oracle_mae_stats;
+
+typedef struct {
+    float x;
+    uint16_t a16; /* |block constant| as stored (binary16 bit pattern without the sign) */
+} mae_sample;
+
+static int cmp_mae_sample(const void* pa, const void* pb) {
+    float a = ((const mae_sample*)pa)->x, b = ((const mae_sample*)pb)->x;
+    return (a > b) - (a < b);
+}
+
+/* |block constant| * 2^24 as an integer: exact for every binary16 number (the smallest subnormal is 2^-24). */
+static uint64_t weight_units(uint16_t a16) { return (uint64_t)ldexp((double)f16_to_f32(a16), 24); }
+
+/*
+ * One expectation pass of Lloyd's algorithm under the MAE criterion (section 3.2 eq. 7-8; appendix B.4): the
+ * new level of region l minimises f(c) = sum_k a_k |x_k - c| over the normalised weights x_k of the region, a_k
+ * being the absolute block maximum of the block that holds x_k (the same for absolute and signed normalisation).
+ * Every minimiser is a weighted median.  The appendix derives that f falls on (x_kappa, x_kappa+1) as long as
+ * sum_{k<=kappa} a_k <= sum_{k>kappa} a_k and rises afterwards, which puts the minimum at the element AFTER
+ * the last kappa for which the inequality holds; its closing formula names x_kappa itself, one element early
+ * (for x = 1, 2, 3 with equal weights it would give 1).  Taken here: the smallest value v among the x_k with
+ *     2 * sum_{x_k <= v} a_k  >=  sum_k a_k ,
+ * i.e. the lower weighted median; it minimises f (checked by brute force in the tests) and does not depend on
+ * the order of equal x_k.  Weights are added as exact integers (units of 2^-24) in 128 bits.  Elements of weight
+ * zero (all-zero blocks) cannot move f and are left out; a region without weight reports NaN and keeps its level.
+ */
+int oracle_lloyd_step_mae(const uint16_t* w, uint64_t n, uint32_t I, const double* cb, int signed_norm, double T,
+                          oracle_mae_stats* out) {
+    if (!w || !cb || !out) return ORACLE_ERR_ARG;
+    if (!valid_block(I) || n == 0 || n % I != 0 || !valid_codebook(cb) || !(T >= 0.0)) return ORACLE_ERR_ARG;
+    double xi[NLEVELS - 1];
+    midpoints(cb, xi);
+    const uint64_t B = n / I;
+    mae_sample* all = (mae_sample*)malloc((size_t)n * sizeof(mae_sample));
+    uint8_t* code_of = (uint8_t*)malloc((size_t)n);
+    if (!all || !code_of) {
+        free(all);
+        free(code_of);
+        return ORACLE_ERR_ARG;
+    }
+    memset(out, 0, sizeof(*out));
+    /* pass 1: normalise and classify every element; 255 marks an outlier */
+#pragma omp parallel for schedule(static)
+    for (int64_t b = 0; b < (int64_t)B; ++b) {
+        float wz[256], x[256];
+        uint8_t is_out[256];
+        uint16_t s16;
+        float m_eff;
+        block_front_end(w + (uint64_t)b * I, I, signed_norm, T, wz, is_out, x, &s16, &m_eff);
+        for (uint32_t i = 0; i < I; ++i) {
+            uint64_t e = (uint64_t)b * I + i;
+            all[e].x = x[i];
+            all[e].a16 = (uint16_t)(s16 & 0x7fffu);
+            code_of[e] = is_out[i] ? 255 : (uint8_t)nearest_level(x[i], xi);
+        }
+    }
+    /* pass 2: per region, collect, sort by x and walk the cumulated weights */
+    for (uint64_t e = 0; e < n; ++e) {
+        if (code_of[e] == 255) {
+            out->n_outliers++;
+            continue;
+        }
+        out->cnt[code_of[e]]++;
+        out->n_used++;
+        out->sae += (double)f16_to_f32(all[e].a16) * fabs((double)all[e].x - cb[code_of[e]]);
+    }
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int l = 0; l < NLEVELS; ++l) {
+        out->median[l] = NAN;
+        uint64_t K = out->cnt[l];
+        if (K == 0) continue;
+        mae_sample* reg = (mae_sample*)malloc((size_t)K * sizeof(mae_sample));
+        if (!reg) {
+            failed = 1;
+            continue;
+        }
+        uint64_t k = 0;
+        for (uint64_t e = 0; e < n; ++e)
+            if (code_of[e] == (uint8_t)l) reg[k++] = all[e];
+        qsort(reg, (size_t)K, sizeof(mae_sample), cmp_mae_sample);
+        unsigned __int128 total = 0, run = 0;
+        for (uint64_t j = 0; j < K; ++j) total += weight_units(reg[j].a16);
+        out->den[l] = ldexp((double)total, -24);
+        if (total != 0) {
+            /* equal x are adjacent: the test is made where a value ends, on everything up to and including it */
+            for (uint64_t j = 0; j < K; ++j) {
+                run += weight_units(reg[j].a16);
+                if (j + 1 < K && reg[j + 1].x == reg[j].x) continue;
+                if (2 * run >= total) {
+                    out->median[l] = (double)reg[j].x;
+                    break;
+                }
+            }
+        }
+        free(reg);
+    }
+    free(all);
+    free(code_of);
+    return failed ? ORACLE_ERR_ARG : ORACLE_OK;
+}
+
+/* Maximisation step under the MAE criterion: an unpinned level whose region carries weight moves to the region's
+ * weighted median (section 3.2 eq. 8). */
+int oracle_codebook_update_mae(const oracle_mae_stats* st, uint16_t pinned_mask, double* cb) {
+    if (!st || !cb) return ORACLE_ERR_ARG;
+    for (int l = 0; l < NLEVELS; ++l) {
+        if ((pinned_mask >> l) & 1u) continue;
+        if (st->median[l] == st->median[l]) cb[l] = st->median[l];
     }
     return ORACLE_OK;
 }

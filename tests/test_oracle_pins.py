@@ -359,3 +359,103 @@ def test_opq_capacity_overflow_and_error_codes():
     assert oracle.quantize(w, 48, CB_S64, 1)[0] == oracle.ERR_ARG                # unsupported block size
     assert oracle.quantize(w, 64, CB_S64[::-1].copy(), 1)[0] == oracle.ERR_ARG   # unsorted codebook
     assert oracle.lloyd_step(w, 64, CB_S64, 1, opq_T=-1.0)[0] == oracle.ERR_ARG
+
+
+# ------------------------------------------------------------------------------------------- MAE criterion
+def _normalised_and_codes(wb, block, cb, signed):
+    """x (binary32), level index and |block constant| of every element, from the (pinned) quantiser outputs."""
+    st, codes, scales, _, _, _ = oracle.quantize(wb, block, cb, signed)
+    assert st == oracle.OK
+    m = np.array([oracle.f16_to_f32(int(s)) for s in scales], dtype=np.float32)
+    w = bf16_val(wb).reshape(-1, block)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        x = np.where(m[:, None] == 0, np.float32(0), w / m[:, None]).astype(np.float32)
+    return x.ravel(), unpack(codes, wb.size), np.repeat(np.abs(m), block)
+
+
+@pytest.mark.parametrize("signed", [0, 1])
+def test_mae_step_median_is_the_smallest_minimiser_of_the_weighted_absolute_error(signed):
+    """Section 3.2 eq. 7 / appendix B.4: the new level minimises f(c) = sum a_k |x_k - c|.  Brute force in exact
+    rational arithmetic over every candidate on small inputs whose blocks have very different maxima."""
+    rng = np.random.default_rng(40 + signed)
+    cb = codebooks.array(codebooks.BOF4S_MAE_64 if signed else codebooks.BOF4_MAE_64)
+    for trial in range(6):
+        nb = 24
+        scale = np.float32(2.0) ** rng.integers(-6, 5, size=(nb, 1)).astype(np.float32)
+        wb = bf16_bits((rng.standard_normal((nb, 32)).astype(np.float32) * scale).ravel())
+        st, s = oracle.lloyd_step_mae(wb, 32, cb, signed)
+        assert st == oracle.OK
+        x, code, a = _normalised_and_codes(wb, 32, cb, signed)
+        for l in range(16):
+            sel = code == l
+            assert s["cnt"][l] == sel.sum()
+            if not sel.any():
+                assert np.isnan(s["median"][l])
+                continue
+            xs = [Fraction(float(v)) for v in x[sel]]
+            ws = [Fraction(float(v)) for v in a[sel]]
+            f = {c: sum(wk * abs(xk - c) for xk, wk in zip(xs, ws)) for c in set(xs)}
+            best = min(f.values())
+            assert Fraction(float(s["median"][l])) == min(c for c, v in f.items() if v == best)
+            assert s["den"][l] == float(sum(ws))
+
+
+def test_mae_step_with_equal_block_maxima_is_the_plain_lower_median():
+    """All blocks share the maximum 1.0, so every weight is 1: the weighted median becomes numpy's sorted
+    element (K - 1) // 2, the count-based lower median."""
+    rng = np.random.default_rng(44)
+    w = (rng.uniform(-0.98, 0.98, size=(400, 64))).astype(np.float32)
+    w[:, 5] = 1.0
+    wb = bf16_bits(w.ravel())
+    cb = codebooks.array(codebooks.BOF4_MAE_64)
+    st, s = oracle.lloyd_step_mae(wb, 64, cb, 0)
+    x, code, a = _normalised_and_codes(wb, 64, cb, 0)
+    assert np.all(a == 1.0)
+    for l in range(16):
+        xs = np.sort(x[code == l])
+        assert s["median"][l] == float(xs[(xs.size - 1) // 2])
+        assert s["den"][l] == xs.size
+
+
+def test_mae_step_error_sum_matches_the_dequantised_weights():
+    """sae = sum |m| |x - c| equals sum |w - m c| up to the rounding of x (one binary32 division)."""
+    wb = inputs.bits(inputs.student_t_matrix(64, 512, nu=5.0, std=0.02, row_sigma=0.3, seed=46))
+    cb = codebooks.array(codebooks.BOF4S_MAE_64)
+    st, s = oracle.lloyd_step_mae(wb, 64, cb, 1)
+    st2, codes, scales, _, _, _ = oracle.quantize(wb, 64, cb, 1)
+    m = np.array([oracle.f16_to_f32(int(v)) for v in scales], dtype=np.float64)
+    w = bf16_val(wb).astype(np.float64).reshape(-1, 64)
+    rec = m[:, None] * cb[unpack(codes, wb.size)].reshape(-1, 64)
+    direct = np.abs(w - rec).sum()
+    assert abs(s["sae"] - direct) <= 1e-6 * direct
+    assert s["n_used"] == wb.size and s["cnt"].sum() == wb.size
+
+
+@pytest.mark.parametrize("signed", [0, 1])
+def test_mae_step_leaves_the_printed_mae_codebook_in_place(signed):
+    """Appendix C prints the MAE-optimal codebooks for Gaussian weights (I = 64).  One expectation step on
+    16.8 M Gaussian samples at that codebook must return its own levels (sampling error 2.5e-4); medians weighted
+    by 1 or by the squared maximum instead of the maximum miss by more than 1e-3."""
+    ref = codebooks.array(codebooks.BOF4S_MAE_64 if signed else codebooks.BOF4_MAE_64)
+    wb = inputs.bits(inputs.gaussian_blocks(1 << 18, 64, seed=21 + signed))
+    st, s = oracle.lloyd_step_mae(wb, 64, ref, signed)
+    assert st == oracle.OK
+    free = [l for l in range(16) if not ((codebooks.PIN_BOF4S if signed else codebooks.PIN_BOF4) >> l) & 1]
+    assert np.abs(s["median"][free] - ref[free]).max() < 5e-4
+
+
+def test_mae_em_objective_never_rises_and_update_respects_pins():
+    wb = inputs.bits(inputs.gaussian_blocks(1 << 13, 64, seed=48))
+    cb = codebooks.gaussian_quantile_init()
+    prev = None
+    for it in range(30):
+        st, s = oracle.lloyd_step_mae(wb, 64, cb, 1)
+        mae = s["sae"] / s["n_used"]
+        assert prev is None or mae <= prev * (1 + 1e-12)
+        prev = mae
+        new = oracle.codebook_update_mae(s, codebooks.PIN_BOF4S, cb)
+        assert new[7] == cb[7] and new[15] == cb[15] and np.all(np.diff(new) > 0)
+        cb = new
+    # far closer to the printed MAE codebook than to the MSE one (they differ by up to 0.06)
+    assert np.abs(cb - codebooks.array(codebooks.BOF4S_MAE_64)).max() < 0.02
+    assert np.abs(cb - codebooks.array(codebooks.BOF4S_MSE[64])).max() > 0.04
