@@ -42,8 +42,8 @@ typedef struct {
 } bof4_lloyd_stats;
 
 /* Bytes of device workspace that bof4_quantize (with outlier buffers of `out_capacity` entries; 0 if OPQ is not
- * used) and bof4_lloyd_step need for `n` weights in blocks of `block` - the larger of the two.  Pure host
- * function; 0 on invalid arguments. */
+ * used), bof4_lloyd_step and bof4_lloyd_step_mae need for `n` weights in blocks of `block` - the largest of the
+ * three.  Pure host function; 0 on invalid arguments. */
 size_t bof4_workspace_bytes(uint64_t n, uint32_t block, uint64_t out_capacity);
 
 /* OPQ threshold T = F_M^{-1}(q) for Gaussian weights (section 3.3 eq. 9 with F_M = (2G-1)^I of appendix B.1):
@@ -85,6 +85,34 @@ int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double*
 /* Maximisation step (section 3.2, eq. 6 and its last paragraph): level l moves to num[l]/den[l] unless bit l of
  * pinned_mask is set or the region is empty (den[l] == 0).  Pure host function; cb_host is updated in place. */
 int bof4_codebook_update(const bof4_lloyd_stats* stats_host, uint16_t pinned_mask, double* cb_host);
+
+/* Per-region results of one Lloyd / EM expectation pass under the MAE criterion (section 3.2 eq. 7-8; appendix B.4). */
+typedef struct {
+    double median[16];   /* weighted median of the normalised weights of region l, weights = absolute block maximum:
+                            the smallest x_k with 2 * sum_{x_j <= x_k} a_j >= sum_j a_j; NaN if the region carries no
+                            weight (empty, or only all-zero blocks)                                                 */
+    double den[16];      /* sum over region l of |block constant|                                                   */
+    uint64_t cnt[16];    /* K_l                                                                                      */
+    double sae;          /* sum of |block constant| * |x - level[code]|: n_used * MAE(W, Q(W))                      */
+    uint64_t n_used;     /* weights that entered the statistics (n minus outliers)                                   */
+    uint64_t n_outliers; /* weights excluded by OPQ                                                                  */
+} bof4_mae_stats;
+
+/*
+ * The expectation pass for the MAE criterion (section 3.2 eq. 7-8, appendix B.4).  Normalisation, assignment and OPQ
+ * as in bof4_lloyd_step; per region the exact weighted median of the normalised weights (weights: the absolute block
+ * maximum as stored in binary16, for absolute and signed normalisation alike) is found by a radix search that reads
+ * the weights three or four times.  The appendix's closing formula names the element before the weighted median;
+ * what is returned is the minimiser that its derivation arrives at.  Weights are added as exact 64-bit integers, which
+ * needs sum over all weights of |block constant| < 2^38 (BOF4_ERR_ARG otherwise).  Arguments, workspace and the
+ * hand-over of the result as for bof4_lloyd_step.  Medians, counts and den are bit-reproducible.
+ */
+int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                        double opq_T, bof4_mae_stats* out_host, void* ws_dev, size_t ws_bytes, void* stream);
+
+/* Maximisation step for the MAE criterion: level l moves to median[l] unless bit l of pinned_mask is set or the region
+ * carries no weight.  Pure host function; cb_host is updated in place. */
+int bof4_codebook_update_mae(const bof4_mae_stats* stats_host, uint16_t pinned_mask, double* cb_host);
 
 /*
  * Quantise (sections 2.1, 3.1, 3.3): OPQ outlier extraction (opq_T > 0), block (signed) absmax, normalisation,

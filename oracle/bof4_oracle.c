@@ -400,8 +400,12 @@ static int cmp_mae_sample(const void* pa, const void* pb) {
     return (a > b) - (a < b);
 }
 
-/* |block constant| * 2^24 as an integer: exact for every binary16 number (the smallest subnormal is 2^-24). */
-static uint64_t weight_units(uint16_t a16) { return (uint64_t)ldexp((double)f16_to_f32(a16), 24); }
+/* |block constant| * 2^24 as an integer: exact for every binary16 number (the smallest subnormal is 2^-24).  A
+ * constant that overflowed binary16 (infinite; out of contract) carries no weight. */
+static uint64_t weight_units(uint16_t a16) {
+    if (a16 >= 0x7C00u) return 0;
+    return (uint64_t)ldexp((double)f16_to_f32(a16), 24);
+}
 
 /*
  * One expectation pass of Lloyd's algorithm under the MAE criterion (section 3.2 eq. 7-8; appendix B.4): the

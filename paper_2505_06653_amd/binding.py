@@ -14,8 +14,8 @@ LIB_PATH = os.path.join(HERE, "libbof4_hip.so")
 
 BOF4_OK, BOF4_ERR_ARG, BOF4_ERR_CAPACITY, BOF4_ERR_WORKSPACE, BOF4_ERR_HIP = 0, -1, -2, -3, -4
 EXPORTS = ("bof4_workspace_bytes", "bof4_opq_threshold", "bof4_thresholds", "bof4_bin_table", "bof4_lloyd_step",
-           "bof4_codebook_update", "bof4_quantize", "bof4_dequantize", "bof4_time_next_call", "bof4_last_error",
-           "bof4_last_hip_error")
+           "bof4_codebook_update", "bof4_lloyd_step_mae", "bof4_codebook_update_mae", "bof4_quantize",
+           "bof4_dequantize", "bof4_time_next_call", "bof4_last_error", "bof4_last_hip_error")
 
 
 class Bof4Error(RuntimeError):
@@ -31,6 +31,16 @@ class LloydStats(ctypes.Structure):
     def as_dict(self):
         return {"num": np.array(self.num[:], dtype=np.float64), "den": np.array(self.den[:], dtype=np.float64),
                 "cnt": np.array(self.cnt[:], dtype=np.uint64), "sse": float(self.sse),
+                "n_used": int(self.n_used), "n_outliers": int(self.n_outliers)}
+
+
+class MaeStats(ctypes.Structure):
+    _fields_ = [("median", ctypes.c_double * 16), ("den", ctypes.c_double * 16), ("cnt", ctypes.c_uint64 * 16),
+                ("sae", ctypes.c_double), ("n_used", ctypes.c_uint64), ("n_outliers", ctypes.c_uint64)]
+
+    def as_dict(self):
+        return {"median": np.array(self.median[:], dtype=np.float64), "den": np.array(self.den[:], dtype=np.float64),
+                "cnt": np.array(self.cnt[:], dtype=np.uint64), "sae": float(self.sae),
                 "n_used": int(self.n_used), "n_outliers": int(self.n_outliers)}
 
 
@@ -60,6 +70,11 @@ def lib():
                                       ctypes.c_int, ctypes.POINTER(LloydStats), vp, ctypes.c_size_t, vp]
         L.bof4_codebook_update.restype = ctypes.c_int
         L.bof4_codebook_update.argtypes = [ctypes.POINTER(LloydStats), ctypes.c_uint16, vp]
+        L.bof4_lloyd_step_mae.restype = ctypes.c_int
+        L.bof4_lloyd_step_mae.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint32, f64p, ctypes.c_int, ctypes.c_double,
+                                          ctypes.POINTER(MaeStats), vp, ctypes.c_size_t, vp]
+        L.bof4_codebook_update_mae.restype = ctypes.c_int
+        L.bof4_codebook_update_mae.argtypes = [ctypes.POINTER(MaeStats), ctypes.c_uint16, vp]
         L.bof4_quantize.restype = ctypes.c_int
         L.bof4_quantize.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint32, f64p, ctypes.c_int, ctypes.c_double,
                                     vp, vp, vp, vp, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint64), vp,
@@ -178,6 +193,12 @@ def pinned_lloyd_stats():
     return LloydStats.from_address(buf.data_ptr()), buf
 
 
+def pinned_mae_stats():
+    """A MaeStats record in pinned host memory.  Returns (struct, keepalive)."""
+    buf = torch.zeros(ctypes.sizeof(MaeStats), dtype=torch.uint8).pin_memory()
+    return MaeStats.from_address(buf.data_ptr()), buf
+
+
 def pinned_counter():
     """A uint64 outlier counter in pinned host memory.  Returns (ctypes.c_uint64, keepalive)."""
     buf = torch.zeros(1, dtype=torch.int64).pin_memory()
@@ -197,6 +218,36 @@ def bof4_lloyd_step(w, block, cb, signed, opq_T=0.0, weight_by_max2=True, ws=Non
     _check(lib().bof4_lloyd_step(_ptr(w), n, block, cbp, int(signed), float(opq_T), int(bool(weight_by_max2)),
                                  ctypes.byref(out), _ptr(ws), ws.numel(), _stream(stream)))
     return out if raw else out.as_dict()
+
+
+def bof4_lloyd_step_mae(w, block, cb, signed, opq_T=0.0, ws=None, stream=None, raw=False, out=None):
+    """MAE criterion: per-region weighted medians.  w: flat bf16 device tensor.  Returns the statistics as a dict
+    (or the ctypes struct with raw=True)."""
+    assert w.dtype == torch.bfloat16 and w.is_cuda and w.is_contiguous()
+    n = w.numel()
+    cb, cbp = _cb(cb)
+    if ws is None:
+        ws = alloc_workspace(n, block, 0, w.device)
+    if out is None:
+        out = MaeStats()
+    _check(lib().bof4_lloyd_step_mae(_ptr(w), n, block, cbp, int(signed), float(opq_T), ctypes.byref(out), _ptr(ws),
+                                     ws.numel(), _stream(stream)))
+    return out if raw else out.as_dict()
+
+
+def bof4_codebook_update_mae(stats, pinned_mask, cb):
+    """stats: MaeStats or its dict form.  Returns new float64[16]."""
+    out = np.array(cb, dtype=np.float64)
+    if out.shape != (16,):
+        raise ValueError("codebook must have 16 levels")
+    if not isinstance(stats, MaeStats):
+        s = MaeStats()
+        for l in range(16):
+            s.median[l], s.den[l], s.cnt[l] = float(stats["median"][l]), float(stats["den"][l]), int(stats["cnt"][l])
+        s.sae, s.n_used, s.n_outliers = float(stats["sae"]), int(stats["n_used"]), int(stats["n_outliers"])
+        stats = s
+    _check(lib().bof4_codebook_update_mae(ctypes.byref(stats), pinned_mask, out.ctypes.data))
+    return out
 
 
 def bof4_quantize(w, block, cb, signed, opq_T=0.0, out_capacity=0, codes=None, scales=None, out_idx=None,

@@ -23,6 +23,7 @@
 #include "bof4.h"
 #include "bof4_device.h"
 #include "bof4_segment.h"
+#include "bof4_mae.h"
 
 namespace {
 using namespace bof4;
@@ -228,6 +229,27 @@ hipError_t wait_for_flag(hipStream_t s, const uint64_t* flag_host) {
     return hipStreamSynchronize(s);
 }
 size_t lloyd_ws_bytes() { return ((size_t)SEG_GRID + 1) * LLOYD_PART * 8; }
+// MAE step: histogram, search state, counters, per-workgroup floating-point partials, result record.
+struct MaeWsLayout {
+    size_t hist, state, counters, sae_part, record, total;
+};
+MaeWsLayout mae_ws_layout() {
+    MaeWsLayout L;
+    size_t o = 0;
+    L.hist = o;     o += 16 * 256 * 8;
+    L.state = o;    o += align_up(16 * sizeof(MaeLevelState), 256);
+    L.counters = o; o += 256;
+    L.sae_part = o; o += align_up((size_t)SEG_GRID * 2 * 8, 256);
+    L.record = o;   o += align_up(MAE_REC * 8, 256);
+    L.total = o;
+    return L;
+}
+// Order-preserving key of a binary32 number (host replica of the kernels' map).
+uint32_t host_order_key(float x) {
+    uint32_t b;
+    std::memcpy(&b, &x, 4);
+    return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
 
 // ------------------------------------------------------------------------------------------------ device helpers
 __device__ __forceinline__ int assign_code(float x, const CodebookArgs& cb) { return assign_code_generic(x, cb); }
@@ -579,8 +601,9 @@ int bof4_last_hip_error(void) { return g_hip_err; }
 size_t bof4_workspace_bytes(uint64_t n, uint32_t block, uint64_t out_capacity) {
     if (!valid_block(block) || n == 0 || n % block != 0) return 0;
     size_t q = quant_ws_bytes(n, out_capacity);
-    size_t l = lloyd_ws_bytes();
-    return q > l ? q : l;
+    const size_t l = lloyd_ws_bytes(), m = mae_ws_layout().total;
+    if (l > q) q = l;
+    return m > q ? m : q;
 }
 
 double bof4_opq_threshold(double q, uint32_t block) {
@@ -846,6 +869,104 @@ int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double*
             HIP_TRY(wait_for_stream(s));
         }
     }
+    return BOF4_OK;
+}
+
+int bof4_codebook_update_mae(const bof4_mae_stats* st, uint16_t pinned_mask, double* cb_host) {
+    if (!st || !cb_host) return fail(BOF4_ERR_ARG, "bof4_codebook_update_mae: null pointer");
+    for (int l = 0; l < 16; ++l) {
+        if ((pinned_mask >> l) & 1u) continue;
+        if (st->median[l] == st->median[l]) cb_host[l] = st->median[l];
+    }
+    return BOF4_OK;
+}
+
+int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                        double opq_T, bof4_mae_stats* out_host, void* ws_dev, size_t ws_bytes, void* stream) {
+    if (!w_dev || !out_host) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: null pointer");
+    if (!valid_block(block) || n == 0 || n % block != 0) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: bad n or block");
+    if (!valid_codebook(cb_host)) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: codebook must be 16 finite ascending levels");
+    if (!(opq_T >= 0.0) || !std::isfinite(opq_T)) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: opq_T must be finite and >= 0");
+    if (!aligned(w_dev, 16)) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: misaligned pointer");
+    if (!ws_dev || !aligned(ws_dev, 256)) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: workspace null or misaligned");
+    const MaeWsLayout ML = mae_ws_layout();
+    if (ws_bytes < ML.total) return fail(BOF4_ERR_WORKSPACE, "bof4_lloyd_step_mae: workspace too small");
+    static_assert(sizeof(bof4_mae_stats) == MAE_REC * 8, "result record and bof4_mae_stats must match");
+    hipStream_t s = (hipStream_t)stream;
+    const CodebookArgs cb = make_codebook_args(cb_host);
+    const BinTable bt = make_bin_table(cb);
+    // Key range of every region.  A normalised weight lies in [-1, 1], up to 1.5 in magnitude when the block constant
+    // is a binary16 subnormal; region l holds thr[l-1] < x <= thr[l].
+    MaeLevelConst lc;
+    uint32_t passes = 1;
+    for (int l = 0; l < 16; ++l) {
+        const float lower = l == 0 ? -2.0f : std::nextafterf(cb.thr[l - 1], INFINITY);
+        const float upper = l == 15 ? 2.0f : cb.thr[l];
+        const uint32_t klo = host_order_key(lower), khi = host_order_key(upper);
+        uint32_t bits = 1;
+        if (khi > klo)
+            while (bits < 32 && ((uint64_t)(khi - klo) >> bits) != 0) ++bits;
+        if (bits > 31) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: a region spans more than 2^31 binary32 values");
+        lc.klo[l] = klo;
+        lc.bits[l] = bits;
+        if ((bits + 7) / 8 > passes) passes = (bits + 7) / 8;
+    }
+    char* base = (char*)ws_dev;
+    unsigned long long* hist = (unsigned long long*)(base + ML.hist);
+    MaeLevelState* state = (MaeLevelState*)(base + ML.state);
+    unsigned long long* counters = (unsigned long long*)(base + ML.counters);
+    double* sae_part = (double*)(base + ML.sae_part);
+    double* rec_dev = (double*)(base + ML.record);
+    const bool opq = opq_T > 0.0;
+    const double T2 = opq_T * opq_T;
+    const uint32_t seg = block < 64 ? block : 64;
+    const uint64_t n_seg = n / seg;
+    const uint64_t tiles = (n_seg + 63) / 64;
+    const uint64_t wantg = (tiles + WAVES_PER_WG - 1) / WAVES_PER_WG;
+    const uint32_t sgrid = (uint32_t)(wantg < SEG_GRID ? wantg : SEG_GRID);
+    const uint4* w = (const uint4*)w_dev;
+    double* direct = (double*)device_view_of_host(out_host);
+    if (direct) out_host->n_used = FLAG_PENDING;  // the word the last kernel writes last
+    hipLaunchKernelGGL(mae_init_kernel, dim3(16), dim3(256), 0, s, lc, state, hist, counters);
+    for (uint32_t p = 0; p < passes; ++p) {
+        const bool first = p == 0;
+        if (first) timing_begin(s);
+#define BOF4_LAUNCH_MAE(II, FIRST_)                                                                                   \
+    if (bt.fast && opq) hipLaunchKernelGGL((mae_pass_kernel<II, true, true, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,  \
+                                           n_seg, cb, bt, signed_norm, T2, state, hist, counters, sae_part);           \
+    else if (bt.fast) hipLaunchKernelGGL((mae_pass_kernel<II, true, false, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,   \
+                                         n_seg, cb, bt, signed_norm, T2, state, hist, counters, sae_part);             \
+    else if (opq) hipLaunchKernelGGL((mae_pass_kernel<II, false, true, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,       \
+                                     n_seg, cb, bt, signed_norm, T2, state, hist, counters, sae_part);                 \
+    else hipLaunchKernelGGL((mae_pass_kernel<II, false, false, FIRST_>), dim3(sgrid), dim3(256), 0, s, w, n_seg, cb,    \
+                            bt, signed_norm, T2, state, hist, counters, sae_part);
+#define BOF4_LAUNCH_MAE_BLOCK(FIRST_)                \
+    switch (block) {                                 \
+        case 32: BOF4_LAUNCH_MAE(32, FIRST_) break;   \
+        case 64: BOF4_LAUNCH_MAE(64, FIRST_) break;   \
+        case 128: BOF4_LAUNCH_MAE(128, FIRST_) break; \
+        default: BOF4_LAUNCH_MAE(256, FIRST_) break;  \
+    }
+        if (first) {
+            BOF4_LAUNCH_MAE_BLOCK(true)
+        } else {
+            BOF4_LAUNCH_MAE_BLOCK(false)
+        }
+#undef BOF4_LAUNCH_MAE_BLOCK
+#undef BOF4_LAUNCH_MAE
+        if (first) timing_end(s);
+        hipLaunchKernelGGL(mae_select_kernel, dim3(1), dim3(1024), 0, s, state, hist, counters, sae_part, sgrid,
+                           first ? 1 : 0, p + 1 == passes ? 1 : 0, direct ? direct : rec_dev);
+    }
+    HIP_TRY(hipGetLastError());
+    if (direct) {
+        HIP_TRY(wait_for_flag(s, &out_host->n_used));
+    } else {
+        HIP_TRY(hipMemcpyAsync(out_host, rec_dev, sizeof(bof4_mae_stats), hipMemcpyDeviceToHost, s));
+        HIP_TRY(wait_for_stream(s));
+    }
+    if (out_host->sae != out_host->sae)
+        return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: block constants too large for exact weighted medians");
     return BOF4_OK;
 }
 

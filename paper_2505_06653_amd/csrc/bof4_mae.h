@@ -1,0 +1,332 @@
+// bof4_mae.h - Lloyd step under the MAE criterion (section 3.2 eq. 7-8, appendix B.4): per region the weighted
+// median of the normalised weights, weighted by the absolute block maximum.
+//
+// A weighted median over 10^8 samples is found without sorting, by a radix search on an order-preserving integer
+// key of x.  Region l can only hold keys between klo[l] (its lower threshold) and its upper threshold, so the search
+// runs on sub = key - klo[l], which has bits[l] <= 31 significant bits; every pass over the weights fixes the next 8
+// of them: a histogram of the weight that falls on each value of those 8 bits (among the elements that agree with
+// the bits fixed so far), then the smallest value d for which twice the weight up to and including d reaches the
+// region's total.  Three passes settle an ordinary region, four the one that contains zero (its keys span both
+// signs).  Weights are exact integers, |block constant| * 2^24 (the constant is a binary16 number), added in 64
+// bits; additions of integers commute, so the result does not depend on the order of the atomics.
+//
+// What is computed is "the smallest x_k with 2 * sum_{x_j <= x_k} a_j >= sum_j a_j" - the lower weighted median,
+// which minimises sum a_j |x_j - c|.  (The closing formula of appendix B.4 names the element before it; its own
+// derivation puts the minimum where this rule does.)
+#pragma once
+#include "bof4_segment.h"
+
+namespace bof4 {
+
+// Search state of one region, in the workspace.
+struct MaeLevelState {
+    uint32_t klo;     // key of the region's lower bound
+    uint32_t hi;      // bits [hi, 32) of sub are fixed to `prefix`; 0 = finished
+    uint32_t prefix;  // their value
+    uint32_t pad;
+    unsigned long long base;   // weight of the elements whose sub lies below prefix << hi
+    unsigned long long total;  // weight of the whole region
+};
+// Per-region constants from the host: key range of the region.
+struct MaeLevelConst {
+    uint32_t klo[16];
+    uint32_t bits[16];  // significant bits of (key of upper bound - klo)
+};
+constexpr int MAE_REC = 51;  // doubles of the result record (layout of bof4_mae_stats)
+
+// Order-preserving map from binary32 to uint32 (negative numbers reversed below the positive ones).
+__device__ __forceinline__ uint32_t order_key(float x) {
+    const uint32_t b = __float_as_uint(x);
+    return b ^ ((uint32_t)((int)b >> 31) | 0x80000000u);
+}
+__device__ __forceinline__ float key_to_float(uint32_t k) {
+    return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
+}
+
+// Sets up the search (state from the host's constants) and clears the accumulators.
+__global__ __launch_bounds__(256) void mae_init_kernel(MaeLevelConst lc, MaeLevelState* __restrict__ state,
+                                                       unsigned long long* __restrict__ hist,
+                                                       unsigned long long* __restrict__ counters) {
+    const uint32_t t = blockIdx.x * 256 + threadIdx.x;
+    if (t < 16 * 256) hist[t] = 0ull;
+    if (t < 24) counters[t] = 0ull;  // cnt[16], n_outliers, spare
+    if (t < 16) {
+        MaeLevelState s;
+        s.klo = lc.klo[t];
+        s.hi = lc.bits[t];
+        s.prefix = 0;
+        s.pad = 0;
+        s.base = 0ull;
+        s.total = 0ull;
+        state[t] = s;
+    }
+}
+
+// One pass over the weights.  FIRST also counts the regions' elements and accumulates the error sum
+// sum |block constant| |x - level| at the current codebook.
+template <int I, bool FAST, bool OPQ, bool FIRST>
+__global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restrict__ w, uint64_t n_seg, CodebookArgs cb,
+                                                           BinTable bt, int signed_norm, double T2,
+                                                           const MaeLevelState* __restrict__ state,
+                                                           unsigned long long* __restrict__ hist_g,
+                                                           unsigned long long* __restrict__ counters,
+                                                           double* __restrict__ sae_part) {
+    using C = SegCfg<I>;
+    struct Shared {  // one object, so that the table sits at LDS offset 0 (reachable by an immediate offset)
+        uint2 tab[40];
+        uint4 info[16];    // per region: klo, (lo | hi << 8 | digit mask << 16), then prefix and active flag -
+                           // in the first pass (no prefix yet, every region active) the region's level as binary64
+        unsigned long long hist[16 * 256];
+        uint32_t cntcol[WAVES_PER_WG * 8 * 64];  // per lane, two 16-bit counters per word: regions 2p and 2p + 1
+        char stage[WAVES_PER_WG * C::STAGE_BYTES];
+    };
+    __shared__ __attribute__((aligned(16))) Shared sh;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < 33) sh.tab[tid] = make_uint2(__float_as_uint(bt.thr[tid]), bt.base[tid]);
+    if (tid < 16) {
+        const MaeLevelState s = state[tid];
+        const uint32_t hi = s.hi, lo = hi > 8 ? hi - 8 : 0;
+        const uint32_t packed = lo | (hi << 8) | (((1u << (hi - lo)) - 1u) << 16);
+        if (FIRST) {
+            const unsigned long long lv = (unsigned long long)__double_as_longlong(cb.cb64[tid]);
+            sh.info[tid] = make_uint4(s.klo, packed, (uint32_t)lv, (uint32_t)(lv >> 32));
+        } else {
+            sh.info[tid] = make_uint4(s.klo, packed, s.prefix, (hi != 0 && s.total != 0ull) ? 1u : 0u);
+        }
+    }
+    for (uint32_t i = tid; i < 16 * 256; i += 256) sh.hist[i] = 0ull;
+    uint32_t* cntcol = sh.cntcol + wave * 8 * 64;
+    if (FIRST) {
+#pragma unroll
+        for (int p = 0; p < 8; ++p) cntcol[p * 64 + lane] = 0u;
+    }
+    __syncthreads();
+    const uint2* tab = sh.tab;
+    char* stage = sh.stage + wave * C::STAGE_BYTES;
+    const uint64_t n_vec = n_seg * C::NV;
+    const uint64_t n_tiles = (n_seg + 63) / 64;
+    const uint64_t n_waves = (uint64_t)gridDim.x * WAVES_PER_WG;
+    const uint64_t gw = (uint64_t)blockIdx.x * WAVES_PER_WG + wave;
+    const uint64_t t0 = n_tiles * gw / n_waves, t1 = n_tiles * (gw + 1) / n_waves;
+
+    // outliers were zeroed: they ran through the loop as x = +0 of the zero region and are taken out again
+    const uint32_t cz = bt.code_of_zero;
+    const uint32_t key0 = order_key(0.0f);
+    double sae = 0.0, w_est = 0.0;
+    uint32_t kout = 0, tiles_since_flush = 0;
+    // 16-bit lane counters go to the global 64-bit counters (integer atomics: order-free) before they can overflow
+    auto flush_counts = [&]() {
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const uint32_t v = cntcol[p * 64 + lane];
+            cntcol[p * 64 + lane] = 0u;
+            uint32_t c0 = v & 0xffffu, c1 = v >> 16;  // at most 65535 each: the wave's sum fits 32 bits
+#pragma unroll
+            for (int mk = 32; mk >= 1; mk >>= 1) {
+                c0 += (uint32_t)__shfl_xor((int)c0, mk, 64);
+                c1 += (uint32_t)__shfl_xor((int)c1, mk, 64);
+            }
+            if (lane == 0) {
+                if (c0) atomicAdd(&counters[2 * p], (unsigned long long)c0);
+                if (c1) atomicAdd(&counters[2 * p + 1], (unsigned long long)c1);
+            }
+        }
+    };
+    uint4 G[C::NV];
+    uint32_t R[C::NR];
+    if (t0 < t1) tile_issue_loads<I>(w, t0 * 64 * C::NV, n_vec, lane, G);
+    for (uint64_t t = t0; t < t1; ++t) {
+        wave_lds_fence();
+        tile_stage<I>(stage, lane, G);
+        if (t + 1 < t1) tile_issue_loads<I>(w, (t + 1) * 64 * C::NV, n_vec, lane, G);
+        wave_lds_fence();
+        tile_fetch<I>(stage, lane, R);
+        const uint64_t seg = t * 64 + lane;
+        const bool active = seg < n_seg;
+        uint32_t k_out = 0;
+        if (OPQ) {
+            uint32_t omap[2];
+            opq_zero_outliers<I>(R, opq_theta<I>(R, T2), omap);
+            k_out = opq_count(omap);
+        }
+        uint32_t maxabs, sign;
+        block_constant<I>(R, lane, signed_norm != 0, maxabs, sign);
+        const float m = bf16_bits_to_f32(maxabs | (sign << 15));
+        const float m_eff = f16_bits_to_f32(f32_to_f16_bits(m));
+        const float a = fabsf(m_eff);
+        // |block constant| in units of 2^-24; a constant beyond binary16 (infinite) carries no weight
+        const unsigned long long W = (a < 65536.0f) ? (unsigned long long)((double)a * 16777216.0) : 0ull;
+        const bool fast = FAST && __builtin_amdgcn_ballot_w64(!maxabs_is_ordinary(maxabs)) == 0;
+        if (active) {
+            const BlockDiv dv = make_block_div(m_eff);
+            double dsum = 0.0;
+#pragma unroll
+            for (int e = 0; e < C::SEG; ++e) {
+                const float f = seg_f32(R, e);
+                float x;
+                uint32_t code;
+                if (fast) {
+                    x = div_fast(f, dv);
+                    const uint32_t off = __float_as_uint(__builtin_fmaf(x, BIN_SCALE, BIN_MAGIC)) & BIN_MASK;
+                    const uint2 en = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(tab) + off);
+                    code = en.y + (x > __uint_as_float(en.x) ? 1u : 0u);
+                } else {
+                    x = (m_eff == 0.0f) ? 0.0f : f / m_eff;
+                    code = (uint32_t)assign_code_generic(x, cb);
+                }
+                const uint4 inf = sh.info[code];
+                const uint32_t sub = order_key(x) - inf.x;
+                const uint32_t lo = inf.y & 0xffu, hi = (inf.y >> 8) & 0xffu, dmask = inf.y >> 16;
+                const bool counts = FIRST ? (hi != 0u && (sub >> hi) == 0u) : (inf.w != 0u && (sub >> hi) == inf.z);
+                if (counts) atomicAdd(&sh.hist[code * 256 + ((sub >> lo) & dmask)], W);
+                if (FIRST) {
+                    atomicAdd(&cntcol[(code >> 1) * 64 + lane], 1u << ((code & 1u) * 16u));
+                    dsum += fabs((double)x - __hiloint2double((int)inf.w, (int)inf.z));
+                    // pin the addition here: left alone, the compiler sinks all 64 of them below the loop and keeps
+                    // every x and level alive until then (it spilled 300 registers)
+                    asm volatile("" : "+v"(dsum));
+                }
+            }
+            if (OPQ && k_out != 0u) {
+                const uint4 inf = sh.info[cz];
+                const uint32_t sub = key0 - inf.x;
+                const uint32_t lo = inf.y & 0xffu, hi = (inf.y >> 8) & 0xffu, dmask = inf.y >> 16;
+                const bool counts = FIRST ? (hi != 0u && (sub >> hi) == 0u) : (inf.w != 0u && (sub >> hi) == inf.z);
+                if (counts)
+                    atomicAdd(&sh.hist[cz * 256 + ((sub >> lo) & dmask)], 0ull - (unsigned long long)k_out * W);
+                if (FIRST) {
+                    atomicAdd(&cntcol[(cz >> 1) * 64 + lane], 0u - (k_out << ((cz & 1u) * 16u)));
+                    dsum -= (double)k_out * fabs(__hiloint2double((int)inf.w, (int)inf.z));
+                    kout += k_out;
+                }
+            }
+            if (FIRST) {
+                sae = fma((double)a, dsum, sae);
+                w_est = fma((double)a, (double)(C::SEG - k_out), w_est);
+            }
+        }
+        if (FIRST && ++tiles_since_flush == 65535u / C::SEG) {
+            flush_counts();
+            tiles_since_flush = 0;
+        }
+    }
+    if (FIRST) {
+        flush_counts();
+        // the two floating-point sums leave as per-workgroup partials (added later in a fixed order)
+        unsigned long long kc = kout;
+        double s = sae, we = w_est;
+#pragma unroll
+        for (int mk = 32; mk >= 1; mk >>= 1) {
+            kc += (unsigned long long)__shfl_xor((long long)kc, mk, 64);
+            s += __shfl_xor(s, mk, 64);
+            we += __shfl_xor(we, mk, 64);
+        }
+        if (lane == 0 && kc != 0ull) atomicAdd(&counters[16], kc);
+        __shared__ double wave_sums[WAVES_PER_WG][2];
+        if (lane == 0) {
+            wave_sums[wave][0] = s;
+            wave_sums[wave][1] = we;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            double s0 = 0.0, s1 = 0.0;
+            for (int k = 0; k < WAVES_PER_WG; ++k) {
+                s0 += wave_sums[k][0];
+                s1 += wave_sums[k][1];
+            }
+            sae_part[2 * blockIdx.x] = s0;
+            sae_part[2 * blockIdx.x + 1] = s1;
+        }
+    }
+    __syncthreads();
+    for (uint32_t i = tid; i < 16 * 256; i += 256) {
+        const unsigned long long v = sh.hist[i];
+        if (v != 0ull) atomicAdd(&hist_g[i], v);
+    }
+}
+
+// After a pass: one wave per region reads its 256 bins, fixes the next digit and clears the bins.  FIRST also takes
+// the region's total from the bins.  LAST writes the result record (layout of bof4_mae_stats): [0..15] median,
+// [16..31] den, [32..47] cnt (integers), [48] sae, [49] n_used, [50] n_outliers (integers); word 49 is stored last, at
+// system scope, so that a host watching it may read the record as soon as it changes.
+__global__ __launch_bounds__(1024) void mae_select_kernel(MaeLevelState* __restrict__ state,
+                                                          unsigned long long* __restrict__ hist,
+                                                          const unsigned long long* __restrict__ counters,
+                                                          const double* __restrict__ sae_part, uint32_t n_part,
+                                                          int first, int last, double* __restrict__ out) {
+    const uint32_t lane = threadIdx.x & 63, l = threadIdx.x >> 6;  // wave l = region l
+    MaeLevelState s = state[l];
+    unsigned long long b[4], sum = 0ull;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        b[k] = hist[l * 256 + 4 * lane + k];
+        hist[l * 256 + 4 * lane + k] = 0ull;
+        sum += b[k];
+    }
+    unsigned long long incl = sum;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned long long up = (unsigned long long)__shfl_up((long long)incl, d, 64);
+        if (lane >= (uint32_t)d) incl += up;
+    }
+    if (first) s.total = (unsigned long long)__shfl((long long)incl, 63, 64);
+    if (s.hi != 0u && s.total != 0ull) {  // wave-uniform
+        const uint32_t lo = s.hi > 8 ? s.hi - 8 : 0;
+        // smallest digit d with 2 (base + weight of digits <= d) >= total; totals stay below 2^62 (checked below)
+        const bool reached = 2ull * (s.base + incl) >= s.total;
+        const unsigned long long ballot = __builtin_amdgcn_ballot_w64(reached);
+        // the bins of this pass hold all the weight between base and the end of the prefix's range, and the prefix
+        // was chosen because the total is reached inside it: some lane has reached it
+        const uint32_t L = ballot ? (uint32_t)__builtin_ctzll(ballot) : 63u;
+        unsigned long long c = s.base + incl - sum;  // weight below this lane's four bins
+        uint32_t k_sel = 3;
+        unsigned long long below = 0ull;
+        bool found = false;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (!found && 2ull * (c + b[k]) >= s.total) {
+                found = true;
+                k_sel = (uint32_t)k;
+                below = c;
+            }
+            c += b[k];
+        }
+        if (!found) below = c - b[3];
+        const uint32_t digit = (uint32_t)__shfl((int)(4 * lane + k_sel), (int)L, 64);
+        const unsigned long long nb = (unsigned long long)__shfl((long long)below, (int)L, 64);
+        s.prefix = (s.prefix << (s.hi - lo)) | digit;
+        s.base = nb;
+        s.hi = lo;
+    }
+    if (lane == 0) state[l] = s;
+    if (!last) return;
+    __shared__ double med[16], den[16];
+    __shared__ unsigned long long cnt[16];
+    if (lane == 0) {
+        med[l] = (s.total != 0ull && s.hi == 0u) ? (double)key_to_float(s.klo + s.prefix) : __builtin_nan("");
+        den[l] = (double)s.total * 0x1p-24;  // correctly rounded conversion of the integer
+        cnt[l] = counters[l];
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double sae = 0.0, w_est = 0.0;
+        for (uint32_t p = 0; p < n_part; ++p) {  // fixed order
+            sae += sae_part[2 * p];
+            w_est += sae_part[2 * p + 1];
+        }
+        unsigned long long used = 0ull;
+        const bool too_large = !(w_est < 0x1p38);  // 64-bit weight sums need sum |constant| < 2^39 (NaN counts too)
+        for (int q = 0; q < 16; ++q) {
+            out[q] = too_large ? __builtin_nan("") : med[q];
+            out[16 + q] = den[q];
+            out[32 + q] = __longlong_as_double((long long)cnt[q]);
+            used += cnt[q];
+        }
+        out[48] = too_large ? __builtin_nan("") : sae;
+        out[50] = __longlong_as_double((long long)counters[16]);
+        __hip_atomic_store(reinterpret_cast<unsigned long long*>(&out[49]), used, __ATOMIC_RELEASE,
+                           __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+}
+
+}  // namespace bof4

@@ -1,0 +1,104 @@
+"""GPU parity of the MAE-criterion Lloyd step (weighted medians) against the oracle: medians, counts and masses
+bit-exact, the error sum to relative 1e-9."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_06653_amd import binding, codebooks, inputs
+from test_gpu_parity import cb_for, make_weights
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+RTOL = 1e-9
+
+
+def mae_cb(block, signed):
+    return codebooks.array(codebooks.BOF4S_MAE_64 if signed else codebooks.BOF4_MAE_64)
+
+
+def assert_mae_close(g, o):
+    assert np.array_equal(g["cnt"], o["cnt"])
+    assert g["n_used"] == o["n_used"] and g["n_outliers"] == o["n_outliers"]
+    assert np.array_equal(g["den"], o["den"])
+    assert np.array_equal(np.isnan(g["median"]), np.isnan(o["median"]))
+    ok = ~np.isnan(o["median"])
+    assert np.array_equal(g["median"][ok], o["median"][ok])  # a median is one of the binary32 samples: exact
+    assert abs(g["sae"] - o["sae"]) <= RTOL * o["sae"]
+
+
+@pytest.mark.parametrize("block", [32, 64, 128, 256])
+@pytest.mark.parametrize("signed", [0, 1])
+@pytest.mark.parametrize("opq", [0, 1])
+def test_mae_step_parity(block, signed, opq):
+    w = make_weights(29, 1024, seed=500 + block + signed)  # 14.5 wave tiles, ragged tail
+    T = oracle.opq_threshold(0.95, block) if opq else 0.0
+    cb = mae_cb(block, signed)
+    st, o = oracle.lloyd_step_mae(inputs.bits(w), block, cb, signed, opq_T=T)
+    assert st == oracle.OK
+    g = binding.bof4_lloyd_step_mae(w.to(DEV), block, cb, signed, opq_T=T)
+    assert (o["n_outliers"] > 0) == bool(opq)
+    assert_mae_close(g, o)
+
+
+def test_mae_em_iterations_follow_the_oracle():
+    """Twelve EM iterations with the MAE criterion from the quantile start: same codebooks as the oracle at every
+    step (the medians are exact), objective never rising."""
+    w = inputs.gaussian_blocks(1 << 12, 64, seed=77)
+    wb, wd = inputs.bits(w), w.to(DEV)
+    cb_g = cb_o = codebooks.gaussian_quantile_init()
+    prev = None
+    for it in range(12):
+        g = binding.bof4_lloyd_step_mae(wd, 64, cb_g, 1)
+        st, o = oracle.lloyd_step_mae(wb, 64, cb_o, 1)
+        assert_mae_close(g, o)
+        mae = g["sae"] / g["n_used"]
+        assert prev is None or mae <= prev * (1 + 1e-12)
+        prev = mae
+        cb_g = binding.bof4_codebook_update_mae(g, codebooks.PIN_BOF4S, cb_g)
+        cb_o = oracle.codebook_update_mae(o, codebooks.PIN_BOF4S, cb_o)
+        assert np.array_equal(cb_g, cb_o)
+
+
+def test_mae_degenerate_inputs():
+    """All-zero blocks (no weight: NaN medians, counts still right), a constant tensor, many equal values, blocks whose
+    maxima differ by 2^20, and a region that stays empty."""
+    cb = mae_cb(64, 1)
+    cases = []
+    cases.append(torch.zeros(64 * 70, dtype=torch.bfloat16))
+    cases.append(torch.full((64 * 70,), 0.375, dtype=torch.bfloat16))
+    g = torch.Generator().manual_seed(5)
+    vals = torch.tensor([-1.0, -0.5, 0.0, 0.25, 0.5, 1.0])[torch.randint(0, 6, (64 * 300,), generator=g)]
+    cases.append(vals.to(torch.bfloat16))
+    big = torch.randn(64 * 200, generator=g).reshape(-1, 64) * torch.exp2(torch.randint(-10, 11, (200, 1), generator=g).float())
+    cases.append(big.reshape(-1).to(torch.bfloat16))
+    tiny = (torch.randn(64 * 64, generator=g) * 1e-7).to(torch.bfloat16)  # constants in binary16's subnormal range
+    cases.append(tiny)
+    for w in cases:
+        for signed in (0, 1):
+            st, o = oracle.lloyd_step_mae(inputs.bits(w), 64, cb, signed)
+            assert st == oracle.OK
+            assert_mae_close(binding.bof4_lloyd_step_mae(w.to(DEV), 64, cb, signed), o)
+
+
+def test_mae_results_in_pinned_memory_and_repeatable():
+    w = make_weights(64, 1024, seed=93).to(DEV)
+    cb = mae_cb(64, 1)
+    ref = binding.bof4_lloyd_step_mae(w, 64, cb, 1)
+    rec, keep = binding.pinned_mae_stats()
+    for _ in range(3):
+        got = binding.bof4_lloyd_step_mae(w, 64, cb, 1, out=rec)
+        assert np.array_equal(got["median"], ref["median"]) and np.array_equal(got["cnt"], ref["cnt"])
+        assert got["sae"] == ref["sae"] and np.array_equal(got["den"], ref["den"])
+
+
+def test_mae_step_argument_errors():
+    w = make_weights(4, 1024, seed=94).to(DEV)
+    cb = mae_cb(64, 1)
+    small = torch.empty(1024, dtype=torch.uint8, device=DEV)
+    with pytest.raises(binding.Bof4Error) as e:
+        binding.bof4_lloyd_step_mae(w, 64, cb, 1, ws=small)
+    assert e.value.code == binding.BOF4_ERR_WORKSPACE
+    with pytest.raises(binding.Bof4Error) as e:
+        binding.bof4_lloyd_step_mae(w, 48, cb, 1)
+    assert e.value.code == binding.BOF4_ERR_ARG
