@@ -933,11 +933,11 @@ int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const dou
         if (first) timing_begin(s);
 #define BOF4_LAUNCH_MAE(II, FIRST_)                                                                                   \
     if (bt.fast && opq) hipLaunchKernelGGL((mae_pass_kernel<II, true, true, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,  \
-                                           n_seg, cb, bt, signed_norm, T2, state, hist, counters, sae_part);           \
+                                           n_seg, cb, bt, signed_norm, T2, state, hist, counters, sae_part);      \
     else if (bt.fast) hipLaunchKernelGGL((mae_pass_kernel<II, true, false, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,   \
-                                         n_seg, cb, bt, signed_norm, T2, state, hist, counters, sae_part);             \
+                                         n_seg, cb, bt, signed_norm, T2, state, hist, counters, sae_part);        \
     else if (opq) hipLaunchKernelGGL((mae_pass_kernel<II, false, true, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,       \
-                                     n_seg, cb, bt, signed_norm, T2, state, hist, counters, sae_part);                 \
+                                     n_seg, cb, bt, signed_norm, T2, state, hist, counters, sae_part);            \
     else hipLaunchKernelGGL((mae_pass_kernel<II, false, false, FIRST_>), dim3(sgrid), dim3(256), 0, s, w, n_seg, cb,    \
                             bt, signed_norm, T2, state, hist, counters, sae_part);
 #define BOF4_LAUNCH_MAE_BLOCK(FIRST_)                \

@@ -160,31 +160,57 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
         if (active) {
             const BlockDiv dv = make_block_div(m_eff);
             double dsum = 0.0;
+            // batches of 8: the table reads of a batch are issued together, then the reads of the regions' search
+            // state, then the (few) histogram additions - two dependent LDS round trips per batch instead of per weight
 #pragma unroll
-            for (int e = 0; e < C::SEG; ++e) {
-                const float f = seg_f32(R, e);
-                float x;
-                uint32_t code;
+            for (int b0 = 0; b0 < C::SEG; b0 += 8) {
+                float x[8];
+                uint32_t code[8];
                 if (fast) {
-                    x = div_fast(f, dv);
-                    const uint32_t off = __float_as_uint(__builtin_fmaf(x, BIN_SCALE, BIN_MAGIC)) & BIN_MASK;
-                    const uint2 en = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(tab) + off);
-                    code = en.y + (x > __uint_as_float(en.x) ? 1u : 0u);
+                    uint2 en[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        x[e] = div_fast(seg_f32(R, b0 + e), dv);
+                        const uint32_t off = __float_as_uint(__builtin_fmaf(x[e], BIN_SCALE, BIN_MAGIC)) & BIN_MASK;
+                        en[e] = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(tab) + off);
+                    }
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) code[e] = en[e].y + (x[e] > __uint_as_float(en[e].x) ? 1u : 0u);
                 } else {
-                    x = (m_eff == 0.0f) ? 0.0f : f / m_eff;
-                    code = (uint32_t)assign_code_generic(x, cb);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float f = seg_f32(R, b0 + e);
+                        x[e] = (m_eff == 0.0f) ? 0.0f : f / m_eff;
+                        code[e] = (uint32_t)assign_code_generic(x[e], cb);
+                    }
                 }
-                const uint4 inf = sh.info[code];
-                const uint32_t sub = order_key(x) - inf.x;
-                const uint32_t lo = inf.y & 0xffu, hi = (inf.y >> 8) & 0xffu, dmask = inf.y >> 16;
-                const bool counts = FIRST ? (hi != 0u && (sub >> hi) == 0u) : (inf.w != 0u && (sub >> hi) == inf.z);
-                if (counts) atomicAdd(&sh.hist[code * 256 + ((sub >> lo) & dmask)], W);
-                if (FIRST) {
-                    atomicAdd(&cntcol[(code >> 1) * 64 + lane], 1u << ((code & 1u) * 16u));
-                    dsum += fabs((double)x - __hiloint2double((int)inf.w, (int)inf.z));
-                    // pin the addition here: left alone, the compiler sinks all 64 of them below the loop and keeps
-                    // every x and level alive until then (it spilled 300 registers)
-                    asm volatile("" : "+v"(dsum));
+                uint4 inf[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) inf[e] = sh.info[code[e]];
+                uint32_t bin[8];
+                bool counts[8], any = false;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t sub = order_key(x[e]) - inf[e].x;
+                    const uint32_t lo = inf[e].y & 0xffu, hi = (inf[e].y >> 8) & 0xffu, dmask = inf[e].y >> 16;
+                    counts[e] = FIRST ? (hi != 0u && (sub >> hi) == 0u) : (inf[e].w != 0u && (sub >> hi) == inf[e].z);
+                    bin[e] = code[e] * 256 + ((sub >> lo) & dmask);
+                    any = any || counts[e];
+                }
+                if (FIRST) {  // every weight lands in some bin: no branches
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        atomicAdd(&sh.hist[bin[e]], counts[e] ? W : 0ull);
+                        atomicAdd(&cntcol[(code[e] >> 1) * 64 + lane], 1u << ((code[e] & 1u) * 16u));
+                        dsum += fabs((double)x[e] - __hiloint2double((int)inf[e].w, (int)inf[e].z));
+                        // pin the addition here: left alone, the compiler sinks all of them below the loop and keeps
+                        // every x and level alive until then (it spilled 300 registers)
+                        asm volatile("" : "+v"(dsum));
+                    }
+                } else if (__builtin_amdgcn_ballot_w64(any) != 0) {  // later passes: one weight in 256 still counts
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (counts[e]) atomicAdd(&sh.hist[bin[e]], W);
                 }
             }
             if (OPQ && k_out != 0u) {
@@ -239,6 +265,7 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
         }
     }
     __syncthreads();
+    // 64-bit integer atomics: exact and order-free (measured: no slower than writing per-workgroup partials)
     for (uint32_t i = tid; i < 16 * 256; i += 256) {
         const unsigned long long v = sh.hist[i];
         if (v != 0ull) atomicAdd(&hist_g[i], v);

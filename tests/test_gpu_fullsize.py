@@ -55,6 +55,16 @@ def test_config1_llama7b_block(llama7b, signed):
     assert_stats_close(binding.bof4_lloyd_step(llama7b, 64, cb, signed), o)
 
 
+@pytest.mark.parametrize("signed", [0, 1])
+def test_config1_mae_step(llama7b, signed):
+    """Workload 1 through one expectation step of the MAE criterion: 16 exact weighted medians over 202 M samples."""
+    from test_gpu_mae import assert_mae_close
+    cb = codebooks.array(codebooks.BOF4S_MAE_64 if signed else codebooks.BOF4_MAE_64)
+    st, o = oracle.lloyd_step_mae(host_bits(llama7b), 64, cb, signed)
+    assert st == oracle.OK
+    assert_mae_close(binding.bof4_lloyd_step_mae(llama7b, 64, cb, signed), o)
+
+
 @pytest.mark.parametrize("block", [32, 64, 128])
 def test_config3_opq_stress(block):
     """Workload 3: the workload-1 matrices with outliers planted at 0.1 % of the entries, OPQ on, signed absmax."""
