@@ -102,3 +102,16 @@ def test_mae_step_argument_errors():
     with pytest.raises(binding.Bof4Error) as e:
         binding.bof4_lloyd_step_mae(w, 48, cb, 1)
     assert e.value.code == binding.BOF4_ERR_ARG
+
+
+def test_mae_step_refuses_weights_too_large_for_exact_sums():
+    """The 64-bit integer weight sums hold sum |block constant| < 2^38 over all weights; 2^26 weights of 65280 exceed
+    that and must be reported, not wrapped around."""
+    w = torch.full((1 << 26,), 65280.0, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(binding.Bof4Error) as e:
+        binding.bof4_lloyd_step_mae(w, 64, mae_cb(64, 1), 1)
+    assert e.value.code == binding.BOF4_ERR_ARG
+    # a hundredth of that passes
+    w = torch.full((1 << 19,), 65280.0, dtype=torch.bfloat16, device=DEV)
+    g = binding.bof4_lloyd_step_mae(w, 64, mae_cb(64, 1), 1)
+    assert g["cnt"].sum() == w.numel() and g["den"].sum() == 65280.0 * w.numel()
