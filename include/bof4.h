@@ -104,11 +104,16 @@ typedef struct {
  * maximum as stored in binary16, for absolute and signed normalisation alike) is found by a radix search that reads
  * the weights three or four times.  The appendix's closing formula names the element before the weighted median;
  * what is returned is the minimiser that its derivation arrives at.  Weights are added as exact 64-bit integers, which
- * needs sum over all weights of |block constant| < 2^38 (BOF4_ERR_ARG otherwise).  Arguments, workspace and the
- * hand-over of the result as for bof4_lloyd_step.  Medians, counts and den are bit-reproducible.
+ * needs sum over all weights of |block constant| < 2^38 (BOF4_ERR_ARG otherwise).
+ *   skip_mask   bit l set: the median of region l is not wanted (a pinned level) and is reported as NaN; cnt and den
+ *               of the region are still returned.  The region that contains zero needs a fourth pass over the
+ *               weights, so skipping it (it is pinned in every BOF4 codebook) saves a quarter of the time
+ * Other arguments, workspace and the hand-over of the result as for bof4_lloyd_step.  Medians, counts and den are
+ * bit-reproducible.
  */
 int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
-                        double opq_T, bof4_mae_stats* out_host, void* ws_dev, size_t ws_bytes, void* stream);
+                        double opq_T, uint16_t skip_mask, bof4_mae_stats* out_host, void* ws_dev, size_t ws_bytes,
+                        void* stream);
 
 /* Maximisation step for the MAE criterion: level l moves to median[l] unless bit l of pinned_mask is set or the region
  * carries no weight.  Pure host function; cb_host is updated in place. */

@@ -882,7 +882,8 @@ int bof4_codebook_update_mae(const bof4_mae_stats* st, uint16_t pinned_mask, dou
 }
 
 int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
-                        double opq_T, bof4_mae_stats* out_host, void* ws_dev, size_t ws_bytes, void* stream) {
+                        double opq_T, uint16_t skip_mask, bof4_mae_stats* out_host, void* ws_dev, size_t ws_bytes,
+                        void* stream) {
     if (!w_dev || !out_host) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: null pointer");
     if (!valid_block(block) || n == 0 || n % block != 0) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: bad n or block");
     if (!valid_codebook(cb_host)) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: codebook must be 16 finite ascending levels");
@@ -909,7 +910,7 @@ int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const dou
         if (bits > 31) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: a region spans more than 2^31 binary32 values");
         lc.klo[l] = klo;
         lc.bits[l] = bits;
-        if ((bits + 7) / 8 > passes) passes = (bits + 7) / 8;
+        if (!((skip_mask >> l) & 1u) && (bits + 7) / 8 > passes) passes = (bits + 7) / 8;
     }
     char* base = (char*)ws_dev;
     unsigned long long* hist = (unsigned long long*)(base + ML.hist);
@@ -956,7 +957,7 @@ int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const dou
 #undef BOF4_LAUNCH_MAE
         if (first) timing_end(s);
         hipLaunchKernelGGL(mae_select_kernel, dim3(1), dim3(1024), 0, s, state, hist, counters, sae_part, sgrid,
-                           first ? 1 : 0, p + 1 == passes ? 1 : 0, direct ? direct : rec_dev);
+                           first ? 1 : 0, p + 1 == passes ? 1 : 0, (uint32_t)skip_mask, direct ? direct : rec_dev);
     }
     HIP_TRY(hipGetLastError());
     if (direct) {

@@ -23,7 +23,7 @@ struct MaeLevelState {
     uint32_t klo;     // key of the region's lower bound
     uint32_t hi;      // bits [hi, 32) of sub are fixed to `prefix`; 0 = finished
     uint32_t prefix;  // their value
-    uint32_t pad;
+    uint32_t pad;     // 1: the caller does not want this region's median (no search after the first pass)
     unsigned long long base;   // weight of the elements whose sub lies below prefix << hi
     unsigned long long total;  // weight of the whole region
 };
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
             const unsigned long long lv = (unsigned long long)__double_as_longlong(cb.cb64[tid]);
             sh.info[tid] = make_uint4(s.klo, packed, (uint32_t)lv, (uint32_t)(lv >> 32));
         } else {
-            sh.info[tid] = make_uint4(s.klo, packed, s.prefix, (hi != 0 && s.total != 0ull) ? 1u : 0u);
+            sh.info[tid] = make_uint4(s.klo, packed, s.prefix, (hi != 0 && s.total != 0ull && s.pad == 0u) ? 1u : 0u);
         }
     }
     for (uint32_t i = tid; i < 16 * 256; i += 256) sh.hist[i] = 0ull;
@@ -280,7 +280,8 @@ __global__ __launch_bounds__(1024) void mae_select_kernel(MaeLevelState* __restr
                                                           unsigned long long* __restrict__ hist,
                                                           const unsigned long long* __restrict__ counters,
                                                           const double* __restrict__ sae_part, uint32_t n_part,
-                                                          int first, int last, double* __restrict__ out) {
+                                                          int first, int last, uint32_t skip_mask,
+                                                          double* __restrict__ out) {
     const uint32_t lane = threadIdx.x & 63, l = threadIdx.x >> 6;  // wave l = region l
     MaeLevelState s = state[l];
     unsigned long long b[4], sum = 0ull;
@@ -297,7 +298,9 @@ __global__ __launch_bounds__(1024) void mae_select_kernel(MaeLevelState* __restr
         if (lane >= (uint32_t)d) incl += up;
     }
     if (first) s.total = (unsigned long long)__shfl((long long)incl, 63, 64);
-    if (s.hi != 0u && s.total != 0ull) {  // wave-uniform
+    const bool skipped = ((skip_mask >> l) & 1u) != 0u;  // only the region's mass was wanted: no search
+    if (skipped) s.pad = 1u;
+    if (!skipped && s.hi != 0u && s.total != 0ull) {  // wave-uniform
         const uint32_t lo = s.hi > 8 ? s.hi - 8 : 0;
         // smallest digit d with 2 (base + weight of digits <= d) >= total; totals stay below 2^62 (checked below)
         const bool reached = 2ull * (s.base + incl) >= s.total;
@@ -330,7 +333,8 @@ __global__ __launch_bounds__(1024) void mae_select_kernel(MaeLevelState* __restr
     __shared__ double med[16], den[16];
     __shared__ unsigned long long cnt[16];
     if (lane == 0) {
-        med[l] = (s.total != 0ull && s.hi == 0u) ? (double)key_to_float(s.klo + s.prefix) : __builtin_nan("");
+        med[l] = (s.total != 0ull && s.hi == 0u && s.pad == 0u) ? (double)key_to_float(s.klo + s.prefix)
+                                                                  : __builtin_nan("");
         den[l] = (double)s.total * 0x1p-24;  // correctly rounded conversion of the integer
         cnt[l] = counters[l];
     }

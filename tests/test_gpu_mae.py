@@ -115,3 +115,21 @@ def test_mae_step_refuses_weights_too_large_for_exact_sums():
     w = torch.full((1 << 19,), 65280.0, dtype=torch.bfloat16, device=DEV)
     g = binding.bof4_lloyd_step_mae(w, 64, mae_cb(64, 1), 1)
     assert g["cnt"].sum() == w.numel() and g["den"].sum() == 65280.0 * w.numel()
+
+
+@pytest.mark.parametrize("signed", [0, 1])
+def test_mae_step_skips_pinned_regions(signed):
+    """With the pinned levels skipped (no fourth pass for the region around zero) the other medians, every count
+    and every mass are unchanged; the skipped medians come back as NaN."""
+    w = make_weights(29, 1024, seed=610 + signed)
+    cb = mae_cb(64, signed)
+    pin = codebooks.PIN_BOF4S if signed else codebooks.PIN_BOF4
+    st, o = oracle.lloyd_step_mae(inputs.bits(w), 64, cb, signed)
+    g = binding.bof4_lloyd_step_mae(w.to(DEV), 64, cb, signed, skip_mask=pin)
+    skipped = np.array([(pin >> l) & 1 for l in range(16)], dtype=bool)
+    assert np.isnan(g["median"][skipped]).all()
+    assert np.array_equal(g["median"][~skipped], o["median"][~skipped])
+    assert np.array_equal(g["cnt"], o["cnt"]) and np.array_equal(g["den"], o["den"])
+    assert abs(g["sae"] - o["sae"]) <= RTOL * o["sae"]
+    new_g = binding.bof4_codebook_update_mae(g, pin, cb)
+    assert np.array_equal(new_g, oracle.codebook_update_mae(o, pin, cb))
