@@ -229,16 +229,16 @@ hipError_t wait_for_flag(hipStream_t s, const uint64_t* flag_host) {
     return hipStreamSynchronize(s);
 }
 size_t lloyd_ws_bytes() { return ((size_t)SEG_GRID + 1) * LLOYD_PART * 8; }
-// MAE step: histogram, search state, counters, per-workgroup floating-point partials, result record.
+// MAE step: histogram, search state, per-wave counts, per-workgroup floating-point partials, result record.
 struct MaeWsLayout {
-    size_t hist, state, counters, sae_part, record, total;
+    size_t hist, state, cnt_part, sae_part, record, total;
 };
 MaeWsLayout mae_ws_layout() {
     MaeWsLayout L;
     size_t o = 0;
     L.hist = o;     o += 16 * 256 * 8;
     L.state = o;    o += align_up(16 * sizeof(MaeLevelState), 256);
-    L.counters = o; o += 256;
+    L.cnt_part = o; o += align_up((size_t)17 * SEG_GRID * WAVES_PER_WG * 8, 256);
     L.sae_part = o; o += align_up((size_t)SEG_GRID * 2 * 8, 256);
     L.record = o;   o += align_up(MAE_REC * 8, 256);
     L.total = o;
@@ -915,7 +915,7 @@ int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const dou
     char* base = (char*)ws_dev;
     unsigned long long* hist = (unsigned long long*)(base + ML.hist);
     MaeLevelState* state = (MaeLevelState*)(base + ML.state);
-    unsigned long long* counters = (unsigned long long*)(base + ML.counters);
+    unsigned long long* cnt_part = (unsigned long long*)(base + ML.cnt_part);
     double* sae_part = (double*)(base + ML.sae_part);
     double* rec_dev = (double*)(base + ML.record);
     const bool opq = opq_T > 0.0;
@@ -928,19 +928,19 @@ int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const dou
     const uint4* w = (const uint4*)w_dev;
     double* direct = (double*)device_view_of_host(out_host);
     if (direct) out_host->n_used = FLAG_PENDING;  // the word the last kernel writes last
-    hipLaunchKernelGGL(mae_init_kernel, dim3(16), dim3(256), 0, s, lc, state, hist, counters);
+    hipLaunchKernelGGL(mae_init_kernel, dim3(16), dim3(256), 0, s, lc, state, hist);
     for (uint32_t p = 0; p < passes; ++p) {
         const bool first = p == 0;
         if (first) timing_begin(s);
 #define BOF4_LAUNCH_MAE(II, FIRST_)                                                                                   \
     if (bt.fast && opq) hipLaunchKernelGGL((mae_pass_kernel<II, true, true, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,  \
-                                           n_seg, cb, bt, signed_norm, T2, state, hist, counters, sae_part);      \
+                                           n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part);      \
     else if (bt.fast) hipLaunchKernelGGL((mae_pass_kernel<II, true, false, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,   \
-                                         n_seg, cb, bt, signed_norm, T2, state, hist, counters, sae_part);        \
+                                         n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part);        \
     else if (opq) hipLaunchKernelGGL((mae_pass_kernel<II, false, true, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,       \
-                                     n_seg, cb, bt, signed_norm, T2, state, hist, counters, sae_part);            \
+                                     n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part);            \
     else hipLaunchKernelGGL((mae_pass_kernel<II, false, false, FIRST_>), dim3(sgrid), dim3(256), 0, s, w, n_seg, cb,    \
-                            bt, signed_norm, T2, state, hist, counters, sae_part);
+                            bt, signed_norm, T2, state, hist, cnt_part, sae_part);
 #define BOF4_LAUNCH_MAE_BLOCK(FIRST_)                \
     switch (block) {                                 \
         case 32: BOF4_LAUNCH_MAE(32, FIRST_) break;   \
@@ -956,7 +956,7 @@ int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const dou
 #undef BOF4_LAUNCH_MAE_BLOCK
 #undef BOF4_LAUNCH_MAE
         if (first) timing_end(s);
-        hipLaunchKernelGGL(mae_select_kernel, dim3(1), dim3(1024), 0, s, state, hist, counters, sae_part, sgrid,
+        hipLaunchKernelGGL(mae_select_kernel, dim3(1), dim3(1024), 0, s, state, hist, cnt_part, sae_part, sgrid,
                            first ? 1 : 0, p + 1 == passes ? 1 : 0, (uint32_t)skip_mask, direct ? direct : rec_dev);
     }
     HIP_TRY(hipGetLastError());

@@ -45,11 +45,9 @@ __device__ __forceinline__ float key_to_float(uint32_t k) {
 
 // Sets up the search (state from the host's constants) and clears the accumulators.
 __global__ __launch_bounds__(256) void mae_init_kernel(MaeLevelConst lc, MaeLevelState* __restrict__ state,
-                                                       unsigned long long* __restrict__ hist,
-                                                       unsigned long long* __restrict__ counters) {
+                                                       unsigned long long* __restrict__ hist) {
     const uint32_t t = blockIdx.x * 256 + threadIdx.x;
     if (t < 16 * 256) hist[t] = 0ull;
-    if (t < 24) counters[t] = 0ull;  // cnt[16], n_outliers, spare
     if (t < 16) {
         MaeLevelState s;
         s.klo = lc.klo[t];
@@ -69,7 +67,7 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
                                                            BinTable bt, int signed_norm, double T2,
                                                            const MaeLevelState* __restrict__ state,
                                                            unsigned long long* __restrict__ hist_g,
-                                                           unsigned long long* __restrict__ counters,
+                                                           unsigned long long* __restrict__ cnt_part,
                                                            double* __restrict__ sae_part) {
     using C = SegCfg<I>;
     struct Shared {  // one object, so that the table sits at LDS offset 0 (reachable by an immediate offset)
@@ -114,7 +112,9 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
     const uint32_t key0 = order_key(0.0f);
     double sae = 0.0, w_est = 0.0;
     uint32_t kout = 0, tiles_since_flush = 0;
-    // 16-bit lane counters go to the global 64-bit counters (integer atomics: order-free) before they can overflow
+    // The 16-bit lane counters are added up over the wave before they can overflow; lane l < 16 keeps the wave's count
+    // of region l.  (Every wave adding its counts to 17 shared words at the end of the kernel cost more than the pass.)
+    unsigned long long wave_cnt = 0ull;
     auto flush_counts = [&]() {
 #pragma unroll
         for (int p = 0; p < 8; ++p) {
@@ -126,10 +126,8 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
                 c0 += (uint32_t)__shfl_xor((int)c0, mk, 64);
                 c1 += (uint32_t)__shfl_xor((int)c1, mk, 64);
             }
-            if (lane == 0) {
-                if (c0) atomicAdd(&counters[2 * p], (unsigned long long)c0);
-                if (c1) atomicAdd(&counters[2 * p + 1], (unsigned long long)c1);
-            }
+            if (lane == 2u * p) wave_cnt += c0;
+            if (lane == 2u * p + 1u) wave_cnt += c1;
         }
     };
     uint4 G[C::NV];
@@ -238,7 +236,8 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
     }
     if (FIRST) {
         flush_counts();
-        // the two floating-point sums leave as per-workgroup partials (added later in a fixed order)
+        // counts leave as per-wave partials [17][waves], the two floating-point sums as per-workgroup partials (added
+        // later in a fixed order)
         unsigned long long kc = kout;
         double s = sae, we = w_est;
 #pragma unroll
@@ -247,7 +246,7 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
             s += __shfl_xor(s, mk, 64);
             we += __shfl_xor(we, mk, 64);
         }
-        if (lane == 0 && kc != 0ull) atomicAdd(&counters[16], kc);
+        if (lane < 17) cnt_part[lane * n_waves + gw] = lane == 16 ? kc : wave_cnt;
         __shared__ double wave_sums[WAVES_PER_WG][2];
         if (lane == 0) {
             wave_sums[wave][0] = s;
@@ -278,7 +277,7 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
 // system scope, so that a host watching it may read the record as soon as it changes.
 __global__ __launch_bounds__(1024) void mae_select_kernel(MaeLevelState* __restrict__ state,
                                                           unsigned long long* __restrict__ hist,
-                                                          const unsigned long long* __restrict__ counters,
+                                                          const unsigned long long* __restrict__ cnt_part,
                                                           const double* __restrict__ sae_part, uint32_t n_part,
                                                           int first, int last, uint32_t skip_mask,
                                                           double* __restrict__ out) {
@@ -331,12 +330,24 @@ __global__ __launch_bounds__(1024) void mae_select_kernel(MaeLevelState* __restr
     if (lane == 0) state[l] = s;
     if (!last) return;
     __shared__ double med[16], den[16];
-    __shared__ unsigned long long cnt[16];
+    __shared__ unsigned long long cnt[17];
+    const uint32_t n_waves = n_part * WAVES_PER_WG;
+    unsigned long long k_l = 0ull, k_out = 0ull;
+    for (uint32_t i = lane; i < n_waves; i += 64) {
+        k_l += cnt_part[l * n_waves + i];
+        if (l == 15) k_out += cnt_part[16 * n_waves + i];
+    }
+#pragma unroll
+    for (int mk = 32; mk >= 1; mk >>= 1) {
+        k_l += (unsigned long long)__shfl_xor((long long)k_l, mk, 64);
+        k_out += (unsigned long long)__shfl_xor((long long)k_out, mk, 64);
+    }
     if (lane == 0) {
         med[l] = (s.total != 0ull && s.hi == 0u && s.pad == 0u) ? (double)key_to_float(s.klo + s.prefix)
                                                                   : __builtin_nan("");
         den[l] = (double)s.total * 0x1p-24;  // correctly rounded conversion of the integer
-        cnt[l] = counters[l];
+        cnt[l] = k_l;
+        if (l == 15) cnt[16] = k_out;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -354,7 +365,7 @@ __global__ __launch_bounds__(1024) void mae_select_kernel(MaeLevelState* __restr
             used += cnt[q];
         }
         out[48] = too_large ? __builtin_nan("") : sae;
-        out[50] = __longlong_as_double((long long)counters[16]);
+        out[50] = __longlong_as_double((long long)cnt[16]);
         __hip_atomic_store(reinterpret_cast<unsigned long long*>(&out[49]), used, __ATOMIC_RELEASE,
                            __HIP_MEMORY_SCOPE_SYSTEM);
     }
