@@ -28,7 +28,7 @@ from paper_2505_06653_amd import binding, codebooks, inputs  # noqa: E402
 HBM_PEAK_GBS = 8000.0
 BLOCK = 64
 # measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this command (see profiles/), bytes per launch
-PROFILED_TRAFFIC_BYTES = {"lloyd_step": 405.4e6, "quantize": 529.6e6, "dequantize": 533.0e6}
+PROFILED_TRAFFIC_BYTES = {"lloyd_step": 405.4e6, "quantize": 529.5e6, "dequantize": 526.2e6}
 
 
 def cpu_baseline(w_samples, cb, T):
