@@ -18,6 +18,9 @@
  *   MAE step (weighted median): brute-force minimiser of sum a|x - c| on tiny inputs; the plain lower median
  *                                when all blocks weigh the same; fixed point on Gaussian samples equals the
  *                                printed MAE codebooks
+ *   decoder inside a matrix-vector product: constant codes (level times sum of x), unit vectors (one column of
+ *                                the decoded matrix), planted outliers, linearity, and the decoded bfloat16 matrix
+ *                                times x within the decoder's rounding bound
  *   tie rules (equal |w| of opposite sign, exact mid-point x, all-zero block, -0.0): parity unpinned by the
  *   paper - fixed only by the definitions written below.
  *
@@ -289,6 +292,49 @@ int oracle_dequantize(const uint8_t* codes, const uint16_t* scales, uint64_t n, 
         w_out[i] = f32_to_bf16_rne(s * lv);
     }
     for (uint64_t k = 0; k < n_outliers; ++k) w_out[out_idx[k]] = f32_to_bf16_rne(f16_to_f32(out_val[k]));
+    return ORACLE_OK;
+}
+
+/* ---------------------------------------------------------------- decoder inside a matrix-vector product --- */
+
+/*
+ * The decoder in use (section 2.1 eq. 3 inside a linear layer; section 3.3 for the outliers; the inference setting of
+ * the appendix on OPQ runtime): the quantised tensor is a row-major [rows x cols] matrix, blocks run along the flat
+ * layout, and for every token t
+ *     y[t][r] = sum_c  w~[r][c] * x[t][c],      w~ = m_b * level[code]   (the exact product of eq. 3, not rounded),
+ * except at listed outlier positions, where w~ is the stored binary16 value (of two entries with one index the later
+ * wins).  The level is taken as the decoder stores it (rounded to binary32); everything else is binary64.  abs_out
+ * receives sum_c |w~ x|, the scale of the rounding error of any finite-precision evaluation.
+ */
+int oracle_gemv(const uint8_t* codes, const uint16_t* scales, uint64_t rows, uint64_t cols, uint32_t I,
+                const double* cb, const int64_t* out_idx, const uint16_t* out_val, uint64_t n_outliers,
+                const uint16_t* x, uint32_t n_tokens, double* y, double* abs_out) {
+    if (!codes || !scales || !cb || !x || !y) return ORACLE_ERR_ARG;
+    if (!valid_block(I) || rows == 0 || cols == 0 || cols % I != 0 || n_tokens == 0 || !valid_codebook(cb))
+        return ORACLE_ERR_ARG;
+    if (n_outliers > 0 && (!out_idx || !out_val)) return ORACLE_ERR_ARG;
+    const uint64_t n = rows * cols;
+    for (uint64_t k = 0; k < n_outliers; ++k)
+        if (out_idx[k] < 0 || (uint64_t)out_idx[k] >= n) return ORACLE_ERR_ARG;
+    double* wt = (double*)malloc(n * sizeof(double));
+    if (!wt) return ORACLE_ERR_ARG;
+    for (uint64_t i = 0; i < n; ++i) {
+        int code = (codes[i >> 1] >> ((i & 1u) * 4)) & 0xf;
+        wt[i] = (double)f16_to_f32(scales[i / I]) * (double)(float)cb[code];
+    }
+    for (uint64_t k = 0; k < n_outliers; ++k) wt[out_idx[k]] = (double)f16_to_f32(out_val[k]);
+    for (uint32_t t = 0; t < n_tokens; ++t)
+        for (uint64_t r = 0; r < rows; ++r) {
+            double acc = 0.0, aacc = 0.0;
+            for (uint64_t c = 0; c < cols; ++c) {
+                const double term = wt[r * cols + c] * (double)bf16_to_f32(x[(uint64_t)t * cols + c]);
+                acc += term;
+                aacc += fabs(term);
+            }
+            y[(uint64_t)t * rows + r] = acc;
+            if (abs_out) abs_out[(uint64_t)t * rows + r] = aacc;
+        }
+    free(wt);
     return ORACLE_OK;
 }
 

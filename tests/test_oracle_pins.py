@@ -459,3 +459,118 @@ def test_mae_em_objective_never_rises_and_update_respects_pins():
     # far closer to the printed MAE codebook than to the MSE one (they differ by up to 0.06)
     assert np.abs(cb - codebooks.array(codebooks.BOF4S_MAE_64)).max() < 0.02
     assert np.abs(cb - codebooks.array(codebooks.BOF4S_MSE[64])).max() > 0.04
+
+
+# ------------------------------------------------------------------------- decoder inside a matrix-vector product
+def _gemv_case(seed, rows, cols, block, n_tokens=1, outliers=0):
+    rng = np.random.default_rng(seed)
+    n = rows * cols
+    c = rng.integers(0, 16, n).astype(np.uint8)
+    packed = (c[0::2] | (c[1::2] << 4)).astype(np.uint8)
+    scales = (rng.standard_normal(n // block).astype(np.float32) * 0.05).astype(np.float16)
+    x = bf16_bits(rng.standard_normal((n_tokens, cols)).astype(np.float32)).reshape(n_tokens, cols)
+    oi = np.sort(rng.choice(n, outliers, replace=False)).astype(np.int64) if outliers else None
+    ov = (rng.standard_normal(outliers).astype(np.float32) * 3).astype(np.float16).view(np.uint16) if outliers else None
+    return c, packed, scales, x, oi, ov
+
+
+def test_gemv_constant_codes_give_level_times_sum_of_x():
+    # every weight of the matrix is level k times a power-of-two constant: y = 2^-3 level_k sum_c x_c, for every row
+    rows, cols, block = 5, 128, 32
+    rng = np.random.default_rng(0)
+    xs = rng.integers(-8, 9, cols).astype(np.float32)  # small integers: the sum is exact in any order
+    x = bf16_bits(xs)
+    for k in (0, 7, 15):
+        packed = np.full(rows * cols // 2, k | (k << 4), dtype=np.uint8)
+        scales = np.full(rows * cols // block, 0.125, dtype=np.float16)
+        st, y, a = oracle.gemv(packed, scales.view(np.uint16), rows, cols, block, CB_S64, x)
+        assert st == oracle.OK
+        lv = float(np.float32(CB_S64[k]))
+        assert np.array_equal(y[0], np.full(rows, 0.125 * lv * float(xs.sum())))
+        assert np.allclose(a[0], 0.125 * abs(lv) * float(np.abs(xs).sum()), rtol=1e-15)
+
+
+def test_gemv_unit_vector_reads_one_column_and_the_pack_layout():
+    # x = e_j picks column j: y[r] = m * level[code(r, j)] exactly; an odd j sits in a high nibble, an even j in a low one
+    rows, cols, block = 7, 64, 32
+    c, packed, scales, _, _, _ = _gemv_case(3, rows, cols, block)
+    lv = CB_U64.astype(np.float32).astype(np.float64)
+    for j in (0, 1, 31, 32, 63):
+        e = np.zeros(cols, dtype=np.float32)
+        e[j] = 1.0
+        st, y, _ = oracle.gemv(packed, scales.view(np.uint16), rows, cols, block, CB_U64, bf16_bits(e))
+        assert st == oracle.OK
+        cm = c.reshape(rows, cols)
+        sm = scales.astype(np.float64).reshape(rows, cols // block)
+        assert np.array_equal(y[0], sm[:, j // block] * lv[cm[:, j]])
+
+
+def test_gemv_transposed_operand_or_wrong_block_direction_would_fail():
+    # rows != cols and one block per half row: the blocks run along the row, the sum along the columns
+    rows, cols, block = 3, 64, 32
+    c, packed, scales, x, _, _ = _gemv_case(4, rows, cols, block)
+    st, y, _ = oracle.gemv(packed, scales.view(np.uint16), rows, cols, block, CB_S64, x)
+    assert st == oracle.OK
+    lv = CB_S64.astype(np.float32).astype(np.float64)
+    xv = bf16_val(x[0]).astype(np.float64)
+    for r in range(rows):
+        tot = Fraction(0)
+        for cc in range(cols):
+            m = Fraction(float(scales[(r * cols + cc) // block]))
+            tot += m * Fraction(float(lv[c[r * cols + cc]])) * Fraction(float(xv[cc]))
+        assert abs(y[0, r] - float(tot)) <= 1e-15 * max(1.0, abs(float(tot))) + 1e-17
+
+
+def test_gemv_outliers_replace_their_weight_and_the_later_duplicate_wins():
+    rows, cols, block = 4, 64, 32
+    c, packed, scales, x, _, _ = _gemv_case(6, rows, cols, block, n_tokens=2)
+    st, y0, _ = oracle.gemv(packed, scales.view(np.uint16), rows, cols, block, CB_S64, x)
+    oi = np.array([5, 70, 70, 255], dtype=np.int64)
+    ov = np.array([2.5, -1.0, 3.0, -0.5], dtype=np.float16)
+    st, y1, _ = oracle.gemv(packed, scales.view(np.uint16), rows, cols, block, CB_S64, x, oi, ov.view(np.uint16))
+    assert st == oracle.OK
+    lv = CB_S64.astype(np.float32).astype(np.float64)
+    xv = bf16_val(x).astype(np.float64)
+    expect = y0.copy()
+    for idx, val in ((5, 2.5), (70, 3.0), (255, -0.5)):
+        r, cc = divmod(idx, cols)
+        old = float(scales[idx // block]) * lv[c[idx]]
+        expect[:, r] += (val - old) * xv[:, cc]
+    assert np.allclose(y1, expect, rtol=0, atol=1e-13)
+    assert not np.allclose(y1, y0)
+    bad = np.array([rows * cols], dtype=np.int64)
+    st, _, _ = oracle.gemv(packed, scales.view(np.uint16), rows, cols, block, CB_S64, x, bad, ov[:1].view(np.uint16))
+    assert st == oracle.ERR_ARG
+
+
+def test_gemv_agrees_with_the_decoded_bf16_matrix_within_the_decoders_rounding():
+    # the decoder rounds every weight to bfloat16 (relative 2^-9 at most); outliers are bfloat16 numbers already
+    rows, cols, block = 16, 256, 64
+    rng = np.random.default_rng(8)
+    w = bf16_bits(rng.standard_normal(rows * cols).astype(np.float32) * 0.02)
+    w[rng.choice(w.size, 12, replace=False)] = bf16_bits(np.full(12, 0.4, dtype=np.float32))
+    T = oracle.opq_threshold(0.95, block)
+    st, codes, scales, oi, ov, k = oracle.quantize(w, block, CB_S64, True, T)
+    assert st == oracle.OK and k >= 12
+    st, deq = oracle.dequantize(codes, scales, w.size, block, CB_S64, oi, ov)
+    x = bf16_bits(rng.standard_normal((3, cols)).astype(np.float32)).reshape(3, cols)
+    st, y, a = oracle.gemv(codes, scales, rows, cols, block, CB_S64, x, oi, ov)
+    assert st == oracle.OK
+    ref = bf16_val(x).astype(np.float64) @ bf16_val(deq).astype(np.float64).reshape(rows, cols).T
+    assert np.all(np.abs(y - ref) <= 2.0 ** -9 * a)
+    assert np.max(np.abs(y - ref)) > 0  # and the two definitions do differ
+    # linear in x: y(x1 + x2) = y(x1) + y(x2) when the sum of the inputs is exact in bfloat16
+    xi = rng.integers(-4, 5, (2, cols)).astype(np.float32)
+    st, ys, _ = oracle.gemv(codes, scales, rows, cols, block, CB_S64, bf16_bits(xi).reshape(2, cols), oi, ov)
+    st, yt, at = oracle.gemv(codes, scales, rows, cols, block, CB_S64, bf16_bits(xi.sum(0)), oi, ov)
+    assert np.all(np.abs(ys.sum(0) - yt[0]) <= 1e-13 * (at[0] + 1))
+
+
+def test_gemv_argument_errors():
+    c, packed, scales, x, _, _ = _gemv_case(9, 2, 64, 32)
+    s16 = scales.view(np.uint16)
+    assert oracle.gemv(packed, s16, 2, 64, 48, CB_S64, x)[0] == oracle.ERR_ARG
+    st = oracle.lib().oracle_gemv(None, None, 2, 64, 32, None, None, None, 0, None, 1, None, None)
+    assert st == oracle.ERR_ARG
+    x96 = bf16_bits(np.zeros(96, dtype=np.float32))
+    assert oracle.gemv(packed[:96], s16[:3], 2, 96, 64, CB_S64, x96)[0] == oracle.ERR_ARG  # cols not a multiple of block
