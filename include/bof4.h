@@ -154,7 +154,30 @@ int bof4_dequantize(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64
                     const double* cb_host, const int64_t* out_idx_dev, const uint16_t* out_val_dev,
                     uint64_t n_outliers, void* w_out_dev, void* stream);
 
-/* Measurement aid: the next bof4_quantize / bof4_dequantize / bof4_lloyd_step call made by this thread records
+/*
+ * The decoder inside a matrix-vector product (section 2.1 eq. 3 applied in a linear layer, outliers of section 3.3
+ * restored; the setting of the appendix on the runtime overhead of OPQ).  The quantised tensor is a row-major
+ * [rows x cols] matrix (blocks along the flat layout, cols a multiple of block) and
+ *     y[t][r] = sum_c w~[r][c] * x[t][c],     w~ = block constant * level[code],
+ * with the exact product of eq. 3 (a weight is not rounded to bfloat16 first, unlike bof4_dequantize), except at the
+ * listed outlier positions, where w~ is the stored binary16 value.  Products and sums are binary32, in a fixed order:
+ * y is bit-reproducible and lies within 64 * 2^-24 * sum_c |w~ x| of the exact sum.
+ *   codes_dev, scales_dev, out_idx_dev, out_val_dev   as bof4_quantize writes them for n = rows * cols; the list
+ *               must be strictly ascending (no index twice); codes_dev needs 16-byte alignment here
+ *   row_ptr_dev rows + 1 offsets into the list, from bof4_outlier_row_offsets; needed when n_outliers > 0
+ *   x_dev       n_tokens x cols bfloat16 (device, 16-byte aligned), y_dev  n_tokens x rows binary32 (device)
+ * Limits: cols <= 30720 (32768 without a list).  The matrix is read once per pair of tokens.  Only enqueues.
+ */
+int bof4_gemv(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols, uint32_t block,
+              const double* cb_host, const int64_t* out_idx_dev, const uint16_t* out_val_dev, uint64_t n_outliers,
+              const uint32_t* row_ptr_dev, const void* x_dev, uint32_t n_tokens, float* y_dev, void* stream);
+
+/* Row offsets of an ascending outlier list (section 3.3) for bof4_gemv: row_ptr[r] = number of entries with flat
+ * index below r * cols, for r = 0 .. rows (rows + 1 values, device).  Made once per matrix.  Only enqueues. */
+int bof4_outlier_row_offsets(const int64_t* out_idx_dev, uint64_t n_outliers, uint64_t rows, uint64_t cols,
+                             uint32_t* row_ptr_dev, void* stream);
+
+/* Measurement aid: the next bof4_quantize / bof4_dequantize / bof4_lloyd_step / bof4_gemv call made by this thread records
  * the caller-owned hipEvent_t `start_event` immediately before and `stop_event` immediately after its main kernel
  * (the one that streams over the weights), on the call's stream; helper kernels and host synchronisation lie
  * outside the pair.  The request is consumed by that call.  Pass NULLs to cancel. */

@@ -24,6 +24,7 @@
 #include "bof4_device.h"
 #include "bof4_segment.h"
 #include "bof4_mae.h"
+#include "bof4_gemv.h"
 
 namespace {
 using namespace bof4;
@@ -804,6 +805,71 @@ int bof4_dequantize(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64
         default: BOF4_LAUNCH_DEQ(256) break;
     }
 #undef BOF4_LAUNCH_DEQ
+    timing_end(s);
+    HIP_TRY(hipGetLastError());
+    return BOF4_OK;
+}
+
+int bof4_outlier_row_offsets(const int64_t* out_idx_dev, uint64_t n_outliers, uint64_t rows, uint64_t cols,
+                             uint32_t* row_ptr_dev, void* stream) {
+    if (!row_ptr_dev || (n_outliers > 0 && !out_idx_dev))
+        return fail(BOF4_ERR_ARG, "bof4_outlier_row_offsets: null pointer");
+    if (rows == 0 || cols == 0 || rows > 0xfffffffeull || cols > 0xffffffffull || n_outliers > 0xffffffffull)
+        return fail(BOF4_ERR_ARG, "bof4_outlier_row_offsets: rows, cols and the list length must fit 32 bits");
+    if (!aligned(out_idx_dev, 8) || !aligned(row_ptr_dev, 4))
+        return fail(BOF4_ERR_ARG, "bof4_outlier_row_offsets: misaligned pointer");
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(outlier_row_offsets_kernel, dim3((uint32_t)((rows + 1 + 255) / 256)), dim3(256), 0, s,
+                       out_idx_dev, (uint32_t)n_outliers, rows, cols, row_ptr_dev);
+    HIP_TRY(hipGetLastError());
+    return BOF4_OK;
+}
+
+int bof4_gemv(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols, uint32_t block,
+              const double* cb_host, const int64_t* out_idx_dev, const uint16_t* out_val_dev, uint64_t n_outliers,
+              const uint32_t* row_ptr_dev, const void* x_dev, uint32_t n_tokens, float* y_dev, void* stream) {
+    if (!codes_dev || !scales_dev || !x_dev || !y_dev) return fail(BOF4_ERR_ARG, "bof4_gemv: null pointer");
+    if (!valid_block(block) || rows == 0 || cols == 0 || cols % block != 0 || n_tokens == 0)
+        return fail(BOF4_ERR_ARG, "bof4_gemv: bad rows, cols (a positive multiple of block), block or n_tokens");
+    const uint32_t strips = (uint32_t)((cols + GEMV_STRIP - 1) / GEMV_STRIP);
+    const uint32_t waves = strips + (n_outliers > 0 ? 1u : 0u);
+    if (rows > 0xfffffffeull || waves > 16)
+        return fail(BOF4_ERR_ARG, "bof4_gemv: at most 2^32 - 2 rows and 30720 columns (32768 without an outlier list)");
+    if (!valid_codebook(cb_host)) return fail(BOF4_ERR_ARG, "bof4_gemv: codebook must be 16 finite ascending levels");
+    if (n_outliers > 0 && (!out_idx_dev || !out_val_dev || !row_ptr_dev))
+        return fail(BOF4_ERR_ARG, "bof4_gemv: null outlier buffers");
+    if (n_outliers > 0xffffffffull) return fail(BOF4_ERR_ARG, "bof4_gemv: more than 2^32 - 1 outliers");
+    if (!aligned(codes_dev, 16) || !aligned(x_dev, 16) || !aligned(scales_dev, 2) || !aligned(y_dev, 4) ||
+        !aligned(out_idx_dev, 8) || !aligned(out_val_dev, 2) || !aligned(row_ptr_dev, 4))
+        return fail(BOF4_ERR_ARG, "bof4_gemv: misaligned pointer (codes and x need 16 bytes)");
+    hipStream_t s = (hipStream_t)stream;
+    const CodebookArgs cb = make_codebook_args(cb_host);
+    uint32_t log2_block = 5;
+    while ((1u << log2_block) < block) ++log2_block;
+    // rows per workgroup: as few as still leave every wave GEMV_UNROLL rows, until the chip holds 16 waves per CU
+    uint32_t rc = GEMV_MAX_RC;
+    while (rc > GEMV_UNROLL && ((rows + rc - 1) / rc) * waves < 4096) rc /= 2;
+    const uint32_t grid = (uint32_t)((rows + rc - 1) / rc);
+    const uint4* codes = (const uint4*)codes_dev;
+    const uint16_t* x = (const uint16_t*)x_dev;
+    timing_begin(s);
+    for (uint32_t t0 = 0; t0 < n_tokens; t0 += GEMV_MAX_TOKENS) {
+        const uint32_t nt = n_tokens - t0 < GEMV_MAX_TOKENS ? n_tokens - t0 : GEMV_MAX_TOKENS;
+        size_t lds = (16 + (size_t)waves * rc * nt) * 4;
+        if (n_outliers > 0) lds += ((size_t)rc + 1 + (size_t)GEMV_CORR * nt) * 4;
+        const uint16_t* xt = x + (uint64_t)t0 * cols;
+        float* yt = y_dev + (uint64_t)t0 * rows;
+#define BOF4_LAUNCH_GEMV(T_, OUT_)                                                                                \
+    hipLaunchKernelGGL((gemv_kernel<T_, OUT_>), dim3(grid), dim3(64 * waves), lds, s, codes, scales_dev,          \
+                       (uint32_t)rows, (uint32_t)cols, log2_block, rc, strips, cb, out_idx_dev, out_val_dev,      \
+                       (uint32_t)n_outliers, row_ptr_dev, xt, yt);
+        if (n_outliers > 0) {
+            if (nt == 1) { BOF4_LAUNCH_GEMV(1, true) } else { BOF4_LAUNCH_GEMV(2, true) }
+        } else {
+            if (nt == 1) { BOF4_LAUNCH_GEMV(1, false) } else { BOF4_LAUNCH_GEMV(2, false) }
+        }
+#undef BOF4_LAUNCH_GEMV
+    }
     timing_end(s);
     HIP_TRY(hipGetLastError());
     return BOF4_OK;
