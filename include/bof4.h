@@ -161,21 +161,29 @@ int bof4_dequantize(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64
  *     y[t][r] = sum_c w~[r][c] * x[t][c],     w~ = block constant * level[code],
  * with the exact product of eq. 3 (a weight is not rounded to bfloat16 first, unlike bof4_dequantize), except at the
  * listed outlier positions, where w~ is the stored binary16 value.  Products and sums are binary32, in a fixed order:
- * y is bit-reproducible and lies within 64 * 2^-24 * sum_c |w~ x| of the exact sum.
- *   codes_dev, scales_dev, out_idx_dev, out_val_dev   as bof4_quantize writes them for n = rows * cols; the list
- *               must be strictly ascending (no index twice); codes_dev needs 16-byte alignment here
- *   row_ptr_dev rows + 1 offsets into the list, from bof4_outlier_row_offsets; needed when n_outliers > 0
+ * y is bit-reproducible and lies within 64 * 2^-24 * sum_c |w~ x| of the exact sum (an outlier position counts with
+ * its decoded placeholder as well as with its value).
+ *   codes_dev, scales_dev   as bof4_quantize writes them for n = rows * cols; codes_dev needs 16-byte alignment here
+ *   table_dev   what bof4_gemv_outlier_table made of the outlier list (n_outliers entries); may be NULL when
+ *               n_outliers == 0
  *   x_dev       n_tokens x cols bfloat16 (device, 16-byte aligned), y_dev  n_tokens x rows binary32 (device)
- * Limits: cols <= 30720 (32768 without a list).  The matrix is read once per pair of tokens.  Only enqueues.
+ * Limits: cols <= 32768.  The matrix is read once per pair of tokens.  Only enqueues.
  */
 int bof4_gemv(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols, uint32_t block,
-              const double* cb_host, const int64_t* out_idx_dev, const uint16_t* out_val_dev, uint64_t n_outliers,
-              const uint32_t* row_ptr_dev, const void* x_dev, uint32_t n_tokens, float* y_dev, void* stream);
+              const double* cb_host, const void* table_dev, uint64_t n_outliers, const void* x_dev,
+              uint32_t n_tokens, float* y_dev, void* stream);
 
-/* Row offsets of an ascending outlier list (section 3.3) for bof4_gemv: row_ptr[r] = number of entries with flat
- * index below r * cols, for r = 0 .. rows (rows + 1 values, device).  Made once per matrix.  Only enqueues. */
-int bof4_outlier_row_offsets(const int64_t* out_idx_dev, uint64_t n_outliers, uint64_t rows, uint64_t cols,
-                             uint32_t* row_ptr_dev, void* stream);
+/* The outlier list (section 3.3) of one quantised matrix in the form bof4_gemv reads: per entry its column and
+ * (stored value - block constant * level[code at that position]), and where the entries of every row and every
+ * stretch of 2048 columns begin.  The list must be strictly ascending (no index twice); an entry outside the matrix
+ * is ignored.  Made once per matrix (it depends on codes, constants, list and codebook); 8-byte aligned buffer of
+ * bof4_gemv_outlier_table_bytes(rows, cols, n_outliers) bytes (device), BOF4_ERR_WORKSPACE if smaller.  Only
+ * enqueues. */
+int bof4_gemv_outlier_table(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols,
+                            uint32_t block, const double* cb_host, const int64_t* out_idx_dev,
+                            const uint16_t* out_val_dev, uint64_t n_outliers, void* table_dev, size_t table_bytes,
+                            void* stream);
+size_t bof4_gemv_outlier_table_bytes(uint64_t rows, uint64_t cols, uint64_t n_outliers);
 
 /* Measurement aid: the next bof4_quantize / bof4_dequantize / bof4_lloyd_step / bof4_gemv call made by this thread records
  * the caller-owned hipEvent_t `start_event` immediately before and `stop_event` immediately after its main kernel

@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(HERE, "libbof4_hip.so")
 BOF4_OK, BOF4_ERR_ARG, BOF4_ERR_CAPACITY, BOF4_ERR_WORKSPACE, BOF4_ERR_HIP = 0, -1, -2, -3, -4
 EXPORTS = ("bof4_workspace_bytes", "bof4_opq_threshold", "bof4_thresholds", "bof4_bin_table", "bof4_lloyd_step",
            "bof4_codebook_update", "bof4_lloyd_step_mae", "bof4_codebook_update_mae", "bof4_quantize",
-           "bof4_dequantize", "bof4_gemv", "bof4_outlier_row_offsets", "bof4_time_next_call", "bof4_last_error",
+           "bof4_dequantize", "bof4_gemv", "bof4_gemv_outlier_table",
+           "bof4_gemv_outlier_table_bytes", "bof4_time_next_call", "bof4_last_error",
            "bof4_last_hip_error")
 
 
@@ -83,10 +84,13 @@ def lib():
         L.bof4_dequantize.restype = ctypes.c_int
         L.bof4_dequantize.argtypes = [vp, vp, ctypes.c_uint64, ctypes.c_uint32, f64p, vp, vp, ctypes.c_uint64, vp, vp]
         L.bof4_gemv.restype = ctypes.c_int
-        L.bof4_gemv.argtypes = [vp, vp, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint32, f64p, vp, vp,
-                                ctypes.c_uint64, vp, vp, ctypes.c_uint32, vp, vp]
-        L.bof4_outlier_row_offsets.restype = ctypes.c_int
-        L.bof4_outlier_row_offsets.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64, vp, vp]
+        L.bof4_gemv.argtypes = [vp, vp, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint32, f64p, vp, ctypes.c_uint64,
+                                vp, ctypes.c_uint32, vp, vp]
+        L.bof4_gemv_outlier_table.restype = ctypes.c_int
+        L.bof4_gemv_outlier_table.argtypes = [vp, vp, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint32, f64p, vp, vp,
+                                              ctypes.c_uint64, vp, ctypes.c_size_t, vp]
+        L.bof4_gemv_outlier_table_bytes.restype = ctypes.c_size_t
+        L.bof4_gemv_outlier_table_bytes.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64]
         L.bof4_time_next_call.restype = ctypes.c_int
         L.bof4_time_next_call.argtypes = [vp, vp]
         L.bof4_last_error.restype = ctypes.c_char_p
@@ -211,20 +215,30 @@ def pinned_counter():
     return ctypes.c_uint64.from_address(buf.data_ptr()), buf
 
 
-def bof4_outlier_row_offsets(out_idx, n_outliers, rows, cols, out=None, stream=None):
-    """Returns the int32 device tensor of rows + 1 offsets into the (ascending) outlier list, for bof4_gemv."""
-    dev = out_idx.device if out_idx is not None else "cuda"
+def bof4_gemv_outlier_table_bytes(rows, cols, n_outliers):
+    return int(lib().bof4_gemv_outlier_table_bytes(rows, cols, n_outliers))
+
+
+def bof4_gemv_outlier_table(codes, scales, rows, cols, block, cb, out_idx, out_val, n_outliers=None, out=None,
+                            stream=None):
+    """The outlier list of one quantised matrix in the form bof4_gemv reads (uint8 device tensor; made once)."""
+    cb, cbp = _cb(cb)
+    k = 0 if out_idx is None else int(out_idx.numel())
+    if n_outliers is not None:
+        if n_outliers > k:
+            raise ValueError("n_outliers exceeds the list")
+        k = int(n_outliers)
     if out is None:
-        out = torch.empty(rows + 1, dtype=torch.int32, device=dev)
-    k = int(n_outliers)
-    _check(lib().bof4_outlier_row_offsets(_ptr(out_idx) if k else None, k, rows, cols, _ptr(out), _stream(stream)))
+        out = torch.empty(bof4_gemv_outlier_table_bytes(rows, cols, k), dtype=torch.uint8, device=codes.device)
+    _check(lib().bof4_gemv_outlier_table(_ptr(codes), _ptr(scales), rows, cols, block, cbp,
+                                         _ptr(out_idx) if k else None, _ptr(out_val) if k else None, k, _ptr(out),
+                                         out.numel(), _stream(stream)))
     return out
 
 
-def bof4_gemv(codes, scales, rows, cols, block, cb, x, out_idx=None, out_val=None, n_outliers=None, row_ptr=None,
-              out=None, stream=None):
+def bof4_gemv(codes, scales, rows, cols, block, cb, x, table=None, n_outliers=0, out=None, stream=None):
     """y = x W~^T for the quantised row-major [rows, cols] matrix; x is bf16 [n_tokens, cols] (or [cols]) on the
-    device, the result float32 [n_tokens, rows]."""
+    device, the result float32 [n_tokens, rows].  `table` (bof4_gemv_outlier_table) brings n_outliers outliers in."""
     cb, cbp = _cb(cb)
     x2 = x if x.dim() == 2 else x[None, :]
     if x2.dtype != torch.bfloat16 or x2.shape[1] != cols or not x2.is_contiguous():
@@ -232,16 +246,11 @@ def bof4_gemv(codes, scales, rows, cols, block, cb, x, out_idx=None, out_val=Non
     n_tokens = int(x2.shape[0])
     if out is None:
         out = torch.empty((n_tokens, rows), dtype=torch.float32, device=x.device)
-    k = 0 if out_idx is None else int(out_idx.numel())
-    if n_outliers is not None:
-        if n_outliers > k:
-            raise ValueError("n_outliers exceeds the list")
-        k = int(n_outliers)
-    if k and row_ptr is None:
-        raise ValueError("an outlier list needs row_ptr (bof4_outlier_row_offsets)")
-    _check(lib().bof4_gemv(_ptr(codes), _ptr(scales), rows, cols, block, cbp, _ptr(out_idx) if k else None,
-                           _ptr(out_val) if k else None, k, _ptr(row_ptr) if k else None, _ptr(x2), n_tokens,
-                           _ptr(out), _stream(stream)))
+    k = int(n_outliers)
+    if k and table is None:
+        raise ValueError("outliers need their table (bof4_gemv_outlier_table)")
+    _check(lib().bof4_gemv(_ptr(codes), _ptr(scales), rows, cols, block, cbp, _ptr(table) if k else None, k,
+                           _ptr(x2), n_tokens, _ptr(out), _stream(stream)))
     return out
 
 

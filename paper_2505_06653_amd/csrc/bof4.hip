@@ -810,59 +810,91 @@ int bof4_dequantize(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64
     return BOF4_OK;
 }
 
-int bof4_outlier_row_offsets(const int64_t* out_idx_dev, uint64_t n_outliers, uint64_t rows, uint64_t cols,
-                             uint32_t* row_ptr_dev, void* stream) {
-    if (!row_ptr_dev || (n_outliers > 0 && !out_idx_dev))
-        return fail(BOF4_ERR_ARG, "bof4_outlier_row_offsets: null pointer");
-    if (rows == 0 || cols == 0 || rows > 0xfffffffeull || cols > 0xffffffffull || n_outliers > 0xffffffffull)
-        return fail(BOF4_ERR_ARG, "bof4_outlier_row_offsets: rows, cols and the list length must fit 32 bits");
-    if (!aligned(out_idx_dev, 8) || !aligned(row_ptr_dev, 4))
-        return fail(BOF4_ERR_ARG, "bof4_outlier_row_offsets: misaligned pointer");
+// Outlier table of bof4_gemv: offsets [rows * strips + 1] (padded to 8 bytes), then one {column, delta} pair per entry.
+struct GemvTableLayout {
+    size_t entries, total;
+};
+GemvTableLayout gemv_table_layout(uint64_t rows, uint64_t strips, uint64_t n_outliers) {
+    GemvTableLayout L;
+    L.entries = align_up((rows * strips + 1) * 4, 8);
+    L.total = L.entries + n_outliers * 8;
+    return L;
+}
+
+size_t bof4_gemv_outlier_table_bytes(uint64_t rows, uint64_t cols, uint64_t n_outliers) {
+    if (rows == 0 || cols == 0) return 0;
+    return gemv_table_layout(rows, (cols + GEMV_STRIP - 1) / GEMV_STRIP, n_outliers).total;
+}
+
+int bof4_gemv_outlier_table(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols,
+                            uint32_t block, const double* cb_host, const int64_t* out_idx_dev,
+                            const uint16_t* out_val_dev, uint64_t n_outliers, void* table_dev, size_t table_bytes,
+                            void* stream) {
+    if (!codes_dev || !scales_dev || !table_dev || (n_outliers > 0 && (!out_idx_dev || !out_val_dev)))
+        return fail(BOF4_ERR_ARG, "bof4_gemv_outlier_table: null pointer");
+    if (!valid_block(block) || rows == 0 || cols == 0 || cols % block != 0)
+        return fail(BOF4_ERR_ARG, "bof4_gemv_outlier_table: bad rows, cols (a positive multiple of block) or block");
+    const uint64_t strips = (cols + GEMV_STRIP - 1) / GEMV_STRIP;
+    if (rows > 0xfffffffeull || strips > GEMV_MAX_STRIPS || n_outliers > 0xffffffffull)
+        return fail(BOF4_ERR_ARG, "bof4_gemv_outlier_table: rows and the list length must fit 32 bits, cols <= 32768");
+    if (!valid_codebook(cb_host))
+        return fail(BOF4_ERR_ARG, "bof4_gemv_outlier_table: codebook must be 16 finite ascending levels");
+    if (!aligned(out_idx_dev, 8) || !aligned(out_val_dev, 2) || !aligned(scales_dev, 2) || !aligned(table_dev, 8))
+        return fail(BOF4_ERR_ARG, "bof4_gemv_outlier_table: misaligned pointer (the table needs 8 bytes)");
+    const GemvTableLayout L = gemv_table_layout(rows, strips, n_outliers);
+    if (table_bytes < L.total) return fail(BOF4_ERR_WORKSPACE, "bof4_gemv_outlier_table: table buffer too small");
     hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(outlier_row_offsets_kernel, dim3((uint32_t)((rows + 1 + 255) / 256)), dim3(256), 0, s,
-                       out_idx_dev, (uint32_t)n_outliers, rows, cols, row_ptr_dev);
+    const CodebookArgs cb = make_codebook_args(cb_host);
+    uint32_t log2_block = 5;
+    while ((1u << log2_block) < block) ++log2_block;
+    const uint64_t count = rows * strips + 1;
+    hipLaunchKernelGGL(outlier_strip_offsets_kernel, dim3((uint32_t)((count + 255) / 256)), dim3(256), 0, s,
+                       out_idx_dev, (uint32_t)n_outliers, rows, cols, (uint32_t)strips, (uint32_t*)table_dev);
+    if (n_outliers > 0)
+        hipLaunchKernelGGL(outlier_delta_kernel, dim3((uint32_t)((n_outliers + 255) / 256)), dim3(256), 0, s,
+                           codes_dev, scales_dev, rows * cols, cols, log2_block, cb, out_idx_dev, out_val_dev,
+                           (uint32_t)n_outliers, (uint2*)((char*)table_dev + L.entries));
     HIP_TRY(hipGetLastError());
     return BOF4_OK;
 }
 
 int bof4_gemv(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols, uint32_t block,
-              const double* cb_host, const int64_t* out_idx_dev, const uint16_t* out_val_dev, uint64_t n_outliers,
-              const uint32_t* row_ptr_dev, const void* x_dev, uint32_t n_tokens, float* y_dev, void* stream) {
+              const double* cb_host, const void* table_dev, uint64_t n_outliers, const void* x_dev,
+              uint32_t n_tokens, float* y_dev, void* stream) {
     if (!codes_dev || !scales_dev || !x_dev || !y_dev) return fail(BOF4_ERR_ARG, "bof4_gemv: null pointer");
     if (!valid_block(block) || rows == 0 || cols == 0 || cols % block != 0 || n_tokens == 0)
         return fail(BOF4_ERR_ARG, "bof4_gemv: bad rows, cols (a positive multiple of block), block or n_tokens");
-    const uint32_t strips = (uint32_t)((cols + GEMV_STRIP - 1) / GEMV_STRIP);
-    const uint32_t waves = strips + (n_outliers > 0 ? 1u : 0u);
-    if (rows > 0xfffffffeull || waves > 16)
-        return fail(BOF4_ERR_ARG, "bof4_gemv: at most 2^32 - 2 rows and 30720 columns (32768 without an outlier list)");
+    const uint64_t strips = (cols + GEMV_STRIP - 1) / GEMV_STRIP;
+    if (rows > 0xfffffffeull || strips > GEMV_MAX_STRIPS)
+        return fail(BOF4_ERR_ARG, "bof4_gemv: at most 2^32 - 2 rows and 32768 columns");
     if (!valid_codebook(cb_host)) return fail(BOF4_ERR_ARG, "bof4_gemv: codebook must be 16 finite ascending levels");
-    if (n_outliers > 0 && (!out_idx_dev || !out_val_dev || !row_ptr_dev))
-        return fail(BOF4_ERR_ARG, "bof4_gemv: null outlier buffers");
+    if (n_outliers > 0 && !table_dev) return fail(BOF4_ERR_ARG, "bof4_gemv: outliers without their table");
     if (n_outliers > 0xffffffffull) return fail(BOF4_ERR_ARG, "bof4_gemv: more than 2^32 - 1 outliers");
     if (!aligned(codes_dev, 16) || !aligned(x_dev, 16) || !aligned(scales_dev, 2) || !aligned(y_dev, 4) ||
-        !aligned(out_idx_dev, 8) || !aligned(out_val_dev, 2) || !aligned(row_ptr_dev, 4))
-        return fail(BOF4_ERR_ARG, "bof4_gemv: misaligned pointer (codes and x need 16 bytes)");
+        !aligned(table_dev, 8))
+        return fail(BOF4_ERR_ARG, "bof4_gemv: misaligned pointer (codes and x need 16 bytes, the table 8)");
+    const uint32_t* offsets_dev = (const uint32_t*)table_dev;
+    const uint2* entries_dev =
+        table_dev ? (const uint2*)((const char*)table_dev + gemv_table_layout(rows, strips, n_outliers).entries) : nullptr;
     hipStream_t s = (hipStream_t)stream;
     const CodebookArgs cb = make_codebook_args(cb_host);
     uint32_t log2_block = 5;
     while ((1u << log2_block) < block) ++log2_block;
-    // rows per workgroup: as few as still leave every wave GEMV_UNROLL rows, until the chip holds 16 waves per CU
+    // rows per workgroup: as few as still leave every wave four rows, until the chip holds 16 waves per CU
     uint32_t rc = GEMV_MAX_RC;
-    while (rc > GEMV_UNROLL && ((rows + rc - 1) / rc) * waves < 4096) rc /= 2;
+    while (rc > 4 && ((rows + rc - 1) / rc) * strips < 4096) rc /= 2;
     const uint32_t grid = (uint32_t)((rows + rc - 1) / rc);
     const uint4* codes = (const uint4*)codes_dev;
     const uint16_t* x = (const uint16_t*)x_dev;
     timing_begin(s);
     for (uint32_t t0 = 0; t0 < n_tokens; t0 += GEMV_MAX_TOKENS) {
         const uint32_t nt = n_tokens - t0 < GEMV_MAX_TOKENS ? n_tokens - t0 : GEMV_MAX_TOKENS;
-        size_t lds = (16 + (size_t)waves * rc * nt) * 4;
-        if (n_outliers > 0) lds += ((size_t)rc + 1 + (size_t)GEMV_CORR * nt) * 4;
         const uint16_t* xt = x + (uint64_t)t0 * cols;
         float* yt = y_dev + (uint64_t)t0 * rows;
 #define BOF4_LAUNCH_GEMV(T_, OUT_)                                                                                \
-    hipLaunchKernelGGL((gemv_kernel<T_, OUT_>), dim3(grid), dim3(64 * waves), lds, s, codes, scales_dev,          \
-                       (uint32_t)rows, (uint32_t)cols, log2_block, rc, strips, cb, out_idx_dev, out_val_dev,      \
-                       (uint32_t)n_outliers, row_ptr_dev, xt, yt);
+    hipLaunchKernelGGL((gemv_kernel<T_, OUT_>), dim3(grid), dim3(64 * (uint32_t)strips), 0, s, codes, scales_dev, \
+                       (uint32_t)rows, (uint32_t)cols, log2_block, rc, cb, offsets_dev, entries_dev,              \
+                       (uint32_t)n_outliers, xt, yt);
         if (n_outliers > 0) {
             if (nt == 1) { BOF4_LAUNCH_GEMV(1, true) } else { BOF4_LAUNCH_GEMV(2, true) }
         } else {

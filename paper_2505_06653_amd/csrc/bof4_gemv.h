@@ -8,9 +8,10 @@
 // lane, one 16-byte load per lane and row) and keeps its slice of x in registers as binary32; it walks the rows of its
 // workgroup's chunk, looks the 32 levels up in a 16-entry LDS table (conflict-free: 16 words in 16 banks), multiplies
 // the row-and-lane sum by the block constant once and adds the 64 lanes up with six DPP additions.  The strips of one
-// row meet in LDS; where an outlier list is given one more wave of the workgroup turns the chunk's entries into
-// corrections (value - m * level[code]) * x[col], one entry per lane, and adds them per row in list order.  Every sum
-// has a fixed order, so y is bit-reproducible.
+// row meet in LDS.  With an outlier list, a table made once per matrix holds per entry its column and
+// value - m * level[code], and where the entries of each row and strip begin; they go one to a lane, and
+// (value - m * level[code]) * x[col] joins that lane's sum before the wave adds up.
+// Every sum has a fixed order, so y is bit-reproducible.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -23,9 +24,8 @@ namespace bof4 {
 
 constexpr uint32_t GEMV_STRIP = 2048;   // columns per wave
 constexpr uint32_t GEMV_MAX_RC = 64;    // rows per workgroup at most: the last step has one lane per row
-constexpr uint32_t GEMV_CORR = 1024;    // list entries the outlier wave handles per round
 constexpr uint32_t GEMV_MAX_TOKENS = 2;    // tokens per launch: their slices of x live in registers
-constexpr uint32_t GEMV_UNROLL = 4;     // rows in flight per wave
+constexpr uint32_t GEMV_MAX_STRIPS = 16;  // waves per workgroup: up to 32768 columns
 
 // Sum over the 64 lanes, delivered in lane 63 (other lanes hold prefixes).  Fixed tree: shifts by 1, 2, 4, 8 inside
 // rows of 16 lanes, then lane 15 of each row into the next odd row, then lane 31 into the upper half.
@@ -42,142 +42,156 @@ __device__ __forceinline__ float wave_sum_lane63(float x) {
     return x;
 }
 
-// row_ptr[r] = number of list entries with index < r * cols, r = 0 .. rows (the list is ascending).
-__global__ __launch_bounds__(256) void outlier_row_offsets_kernel(const int64_t* __restrict__ out_idx, uint32_t n_out,
-                                                                  uint64_t rows, uint64_t cols,
-                                                                  uint32_t* __restrict__ row_ptr) {
-    const uint64_t r = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-    if (r > rows) return;
-    const int64_t target = (int64_t)(r * cols);
+// strip_ptr[r * n_strips + s] = number of list entries with index < r * cols + s * GEMV_STRIP (the list is
+// ascending), for every row and strip, and one closing entry: rows * n_strips + 1 values.
+__global__ __launch_bounds__(256) void outlier_strip_offsets_kernel(const int64_t* __restrict__ out_idx,
+                                                                    uint32_t n_out, uint64_t rows, uint64_t cols,
+                                                                    uint32_t n_strips,
+                                                                    uint32_t* __restrict__ strip_ptr) {
+    const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i > rows * n_strips) return;
+    const uint64_t r = i / n_strips, sidx = i - r * n_strips;
+    const int64_t target = (int64_t)(r * cols + sidx * GEMV_STRIP);
     uint32_t lo = 0, hi = n_out;  // first entry >= target
     while (lo < hi) {
         const uint32_t mid = lo + (hi - lo) / 2;
         if (out_idx[mid] < target) lo = mid + 1; else hi = mid;
     }
-    row_ptr[r] = lo;
+    strip_ptr[i] = lo;
 }
 
-// Dynamic LDS: 16 levels | part[(S + OUTLIERS) * rc * T] | (OUTLIERS) row offsets [rc + 1] | corr[GEMV_CORR * T].
+// The list in the form the product wants it: per entry its column and (value - m * level[code]), what the entry adds
+// to its row's sum per unit of x.  An entry outside the matrix adds nothing.
+__global__ __launch_bounds__(256) void outlier_delta_kernel(const uint8_t* __restrict__ codes8,
+                                                            const uint16_t* __restrict__ scales, uint64_t n,
+                                                            uint64_t cols, uint32_t log2_block, CodebookArgs cb,
+                                                            const int64_t* __restrict__ out_idx,
+                                                            const uint16_t* __restrict__ out_val, uint32_t n_out,
+                                                            uint2* __restrict__ entries) {
+    const uint32_t k = blockIdx.x * 256 + threadIdx.x;
+    if (k >= n_out) return;
+    const uint64_t idx = (uint64_t)out_idx[k];
+    uint2 e = make_uint2(0u, 0u);
+    if (idx < n) {
+        const uint32_t code = (codes8[idx >> 1] >> ((idx & 1u) * 4)) & 15u;
+        e.x = (uint32_t)(idx % cols);
+        e.y = __float_as_uint(fmaf(-f16_bits_to_f32(scales[idx >> log2_block]), cb.lv32[code],  // one rounding
+                                   f16_bits_to_f32(out_val[k])));
+    }
+    entries[k] = e;
+}
+
+// Byte j of v (one instruction; written out so that the compiler does not fold it back into a shift and a mask of the
+// packed codes, which costs two per weight).
+template <int J>
+__device__ __forceinline__ uint32_t byte_of(uint32_t v) {
+    uint32_t r;
+    asm("v_bfe_u32 %0, %1, %2, 8" : "=v"(r) : "v"(v), "n"(8 * J));
+    return r;
+}
+
+// One workgroup: rows [blockIdx.x * rc, ...) of the matrix, one wave per strip.  U rows are in flight per wave.
 template <int T, bool OUTLIERS>
 __global__ __launch_bounds__(1024) void gemv_kernel(const uint4* __restrict__ codes, const uint16_t* __restrict__ scales,
                                                     uint32_t rows, uint32_t cols, uint32_t log2_block, uint32_t rc,
-                                                    uint32_t n_strips, CodebookArgs cb,
-                                                    const int64_t* __restrict__ out_idx,
-                                                    const uint16_t* __restrict__ out_val, uint32_t n_out,
-                                                    const uint32_t* __restrict__ row_ptr,
+                                                    CodebookArgs cb, const uint32_t* __restrict__ strip_ptr,
+                                                    const uint2* __restrict__ entries, uint32_t n_out,
                                                     const uint16_t* __restrict__ x, float* __restrict__ y) {
-    extern __shared__ __attribute__((aligned(16))) float lds[];
-    float* tab = lds;
-    float* part = lds + 16;
-    const uint32_t n_parts = n_strips + (OUTLIERS ? 1u : 0u);
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < 16) tab[tid] = cb.lv32[tid];
+    constexpr uint32_t U = T == 1 ? 4 : 2;
+    struct Shared {  // one object, so that the table sits at LDS offset 0 (reachable by an immediate offset)
+        float tab[16];
+        float part[GEMV_MAX_STRIPS * GEMV_MAX_RC * T];
+    };
+    __shared__ __attribute__((aligned(16))) Shared sh;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_strips = blockDim.x >> 6;
+    if (tid < 16) sh.tab[tid] = cb.lv32[tid];
     const uint32_t r0 = blockIdx.x * rc;
     const uint32_t r1 = min(rows, r0 + rc);
     __syncthreads();
+    const char* tab = reinterpret_cast<const char*>(sh.tab);
 
-    if (wave < n_strips) {
-        const uint32_t col0 = wave * GEMV_STRIP + lane * 32;
-        const bool active = col0 < cols;
-        float xr[T][32];
+    const uint32_t col0 = wave * GEMV_STRIP + lane * 32;
+    const bool active = col0 < cols;
+    float xr[T][32];
 #pragma unroll
-        for (int t = 0; t < T; ++t) {
-            const uint4* xp = reinterpret_cast<const uint4*>(x + (uint64_t)t * cols + col0);
+    for (int t = 0; t < T; ++t) {
+        const uint4* xp = reinterpret_cast<const uint4*>(x + (uint64_t)t * cols + col0);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint4 v = active ? xp[k] : make_uint4(0u, 0u, 0u, 0u);
+            const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                xr[t][8 * k + 2 * i] = __uint_as_float(u[i] << 16);
+                xr[t][8 * k + 2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+            }
+        }
+    }
+    // where this strip's entries of the chunk's rows begin and end: lane j holds row r0 + j
+    uint32_t p_lo = 0, p_hi = 0;
+    if (OUTLIERS && lane < r1 - r0) {
+        p_lo = min(strip_ptr[(uint64_t)(r0 + lane) * n_strips + wave], n_out);
+        p_hi = min(strip_ptr[(uint64_t)(r0 + lane) * n_strips + wave + 1], n_out);
+    }
+    // what one list entry adds: (value - decoded placeholder) * x
+    auto correction = [&](uint2 e, float* c) {
+        const uint32_t col = min(e.x, cols - 1);
+#pragma unroll
+        for (int t = 0; t < T; ++t) c[t] = fmaf(__uint_as_float(e.y), bf16_bits_to_f32(x[(uint64_t)t * cols + col]), c[t]);
+    };
+    for (uint32_t r = r0; r < r1; r += U) {
+        uint4 q[U];
+        float m[U];
+        uint32_t pa[U], pb[U];
+        uint2 oe[U];
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+            const uint32_t rr = min(r + u, r1 - 1);  // rows past the chunk repeat its last row and are dropped
+            const uint64_t e = (uint64_t)rr * cols + col0;
+            q[u] = active ? load_stream(&codes[e >> 5]) : make_uint4(0u, 0u, 0u, 0u);
+            m[u] = active ? f16_bits_to_f32(__builtin_nontemporal_load(&scales[e >> log2_block])) : 0.0f;
+            if (OUTLIERS) {
+                pa[u] = (uint32_t)__builtin_amdgcn_readlane((int)p_lo, (int)(rr - r0));
+                pb[u] = (uint32_t)__builtin_amdgcn_readlane((int)p_hi, (int)(rr - r0));
+                oe[u] = pa[u] + lane < pb[u] ? entries[pa[u] + lane] : make_uint2(0u, 0u);
+            }
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+            const uint32_t w[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
+            float acc[T][2];
+#pragma unroll
+            for (int t = 0; t < T; ++t) acc[t][0] = acc[t][1] = 0.0f;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const uint4 v = active ? xp[k] : make_uint4(0u, 0u, 0u, 0u);
-                const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+                // byte j of `even` = 4 * code of element 2 j, of `odd` = 4 * code of element 2 j + 1
+                const uint32_t even = (w[k] << 2) & 0x3c3c3c3cu, odd = (w[k] >> 2) & 0x3c3c3c3cu;
+                const uint32_t ae[4] = {byte_of<0>(even), byte_of<1>(even), byte_of<2>(even), byte_of<3>(even)};
+                const uint32_t ao[4] = {byte_of<0>(odd), byte_of<1>(odd), byte_of<2>(odd), byte_of<3>(odd)};
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    xr[t][8 * k + 2 * i] = __uint_as_float(u[i] << 16);
-                    xr[t][8 * k + 2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
-                }
-            }
-        }
-        for (uint32_t r = r0; r < r1; r += GEMV_UNROLL) {
-            uint4 q[GEMV_UNROLL];
-            float m[GEMV_UNROLL];
+                for (int j = 0; j < 4; ++j) {
+                    const float le = *reinterpret_cast<const float*>(tab + ae[j]);
+                    const float lo = *reinterpret_cast<const float*>(tab + ao[j]);
 #pragma unroll
-            for (uint32_t u = 0; u < GEMV_UNROLL; ++u) {
-                const uint32_t rr = min(r + u, r1 - 1);  // rows past the chunk repeat its last row and are dropped
-                const uint64_t e = (uint64_t)rr * cols + col0;
-                q[u] = active ? load_stream(&codes[e >> 5]) : make_uint4(0u, 0u, 0u, 0u);
-                m[u] = active ? f16_bits_to_f32(__builtin_nontemporal_load(&scales[e >> log2_block])) : 0.0f;
-            }
-#pragma unroll
-            for (uint32_t u = 0; u < GEMV_UNROLL; ++u) {
-                const uint32_t w[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
-                float acc[T][2];
-#pragma unroll
-                for (int t = 0; t < T; ++t) acc[t][0] = acc[t][1] = 0.0f;
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    // byte j of `even` = 4 * code of element 2 j, of `odd` = 4 * code of element 2 j + 1
-                    const uint32_t even = (w[k] << 2) & 0x3c3c3c3cu, odd = (w[k] >> 2) & 0x3c3c3c3cu;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const float le = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(tab) +
-                                                                         ((even >> (8 * j)) & 0xffu));
-                        const float lo = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(tab) +
-                                                                         ((odd >> (8 * j)) & 0xffu));
-#pragma unroll
-                        for (int t = 0; t < T; ++t) {
-                            acc[t][0] = fmaf(le, xr[t][8 * k + 2 * j], acc[t][0]);
-                            acc[t][1] = fmaf(lo, xr[t][8 * k + 2 * j + 1], acc[t][1]);
-                        }
+                    for (int t = 0; t < T; ++t) {
+                        acc[t][0] = fmaf(le, xr[t][8 * k + 2 * j], acc[t][0]);
+                        acc[t][1] = fmaf(lo, xr[t][8 * k + 2 * j + 1], acc[t][1]);
                     }
                 }
-#pragma unroll
-                for (int t = 0; t < T; ++t) {
-                    const float s = wave_sum_lane63((acc[t][0] + acc[t][1]) * m[u]);
-                    if (lane == 63 && r + u < r1) part[(wave * rc + (r + u - r0)) * T + t] = s;
-                }
             }
-        }
-    } else if (OUTLIERS) {
-        // the outlier wave: corrections of the chunk's list entries, one entry per lane, summed per row in list order
-        uint32_t* rp = reinterpret_cast<uint32_t*>(part + n_parts * rc * T);
-        float* corr = reinterpret_cast<float*>(rp + rc + 1);
-        const uint32_t n_rows = r1 - r0;
-        for (uint32_t j = lane; j <= n_rows; j += 64) rp[j] = min(row_ptr[r0 + j], n_out);
-        wave_lds_fence();
-        const uint32_t e0 = rp[0], e1 = rp[n_rows];
-        const uint32_t my_lo = lane < n_rows ? rp[lane] : 0u, my_hi = lane < n_rows ? rp[lane + 1] : 0u;
-        const uint64_t n = (uint64_t)rows * cols;
-        const uint64_t first = (uint64_t)r0 * cols;
-        const uint8_t* codes8 = reinterpret_cast<const uint8_t*>(codes);
-        float rowcorr[T];
+            float c[T];
 #pragma unroll
-        for (int t = 0; t < T; ++t) rowcorr[t] = 0.0f;
-        for (uint32_t base = e0; base < e1; base += GEMV_CORR) {
-            const uint32_t cnt = min(GEMV_CORR, e1 - base);
-            for (uint32_t k = lane; k < cnt; k += 64) {
-                const uint64_t idx = (uint64_t)out_idx[base + k];
-                float c[T];
-#pragma unroll
-                for (int t = 0; t < T; ++t) c[t] = 0.0f;
-                if (idx >= first && idx < n) {  // an entry outside the matrix changes nothing
-                    const uint32_t col = (uint32_t)(idx - first) % cols;  // the chunk spans fewer than 2^32 weights
-                    const uint32_t code = (codes8[idx >> 1] >> ((idx & 1u) * 4)) & 15u;
-                    const float old = f16_bits_to_f32(scales[idx >> log2_block]) * tab[code];
-                    const float d = f16_bits_to_f32(out_val[base + k]) - old;
-#pragma unroll
-                    for (int t = 0; t < T; ++t) c[t] = d * bf16_bits_to_f32(x[(uint64_t)t * cols + col]);
-                }
-#pragma unroll
-                for (int t = 0; t < T; ++t) corr[k * T + t] = c[t];
+            for (int t = 0; t < T; ++t) c[t] = 0.0f;
+            if (OUTLIERS) {
+                if (pa[u] + lane < pb[u]) correction(oe[u], c);
+                for (uint32_t k = pa[u] + 64 + lane; k < pb[u]; k += 64)  // more than 64 entries in one row and strip
+                    correction(entries[k], c);
             }
-            wave_lds_fence();
-            const uint32_t lo = max(my_lo, base), hi = min(my_hi, base + cnt);
-            for (uint32_t k = lo; k < hi; ++k) {
 #pragma unroll
-                for (int t = 0; t < T; ++t) rowcorr[t] += corr[(k - base) * T + t];
+            for (int t = 0; t < T; ++t) {
+                const float s = wave_sum_lane63(fmaf(acc[t][0] + acc[t][1], m[u], c[t]));
+                if (lane == 63 && r + u < r1) sh.part[(wave * rc + (r + u - r0)) * T + t] = s;
             }
-            wave_lds_fence();
-        }
-        if (lane < n_rows) {
-#pragma unroll
-            for (int t = 0; t < T; ++t) part[(n_strips * rc + lane) * T + t] = rowcorr[t];
         }
     }
     __syncthreads();
@@ -185,7 +199,7 @@ __global__ __launch_bounds__(1024) void gemv_kernel(const uint4* __restrict__ co
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             float s = 0.0f;
-            for (uint32_t p = 0; p < n_parts; ++p) s += part[(p * rc + lane) * T + t];  // strips in order, outliers last
+            for (uint32_t p = 0; p < n_strips; ++p) s += sh.part[(p * rc + lane) * T + t];  // strips in order
             y[(uint64_t)t * rows + r0 + lane] = s;
         }
     }

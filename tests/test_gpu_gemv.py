@@ -46,9 +46,8 @@ def run_gpu(cb, codes, scales, oi, ov, rows, cols, block, x):
     sd = dev_u16(scales)
     k = 0 if oi is None else int(oi.size)
     if k:
-        oid, ovd = dev_i64(oi), dev_u16(ov)
-        rp = binding.bof4_outlier_row_offsets(oid, k, rows, cols)
-        y = binding.bof4_gemv(cd, sd, rows, cols, block, cb, x.to(DEV), oid, ovd, row_ptr=rp)
+        tab = binding.bof4_gemv_outlier_table(cd, sd, rows, cols, block, cb, dev_i64(oi), dev_u16(ov))
+        y = binding.bof4_gemv(cd, sd, rows, cols, block, cb, x.to(DEV), tab, k)
     else:
         y = binding.bof4_gemv(cd, sd, rows, cols, block, cb, x.to(DEV))
     torch.cuda.synchronize()
@@ -130,31 +129,50 @@ def test_gemv_is_bit_reproducible_and_respects_out_and_stream():
     rows, cols, block = 130, 4096, 64
     cb, codes, scales, oi, ov = quantized(rows, cols, block, 1, 1, seed=80)
     cd, sd, oid, ovd = torch.from_numpy(codes).to(DEV), dev_u16(scales), dev_i64(oi), dev_u16(ov)
-    rp = binding.bof4_outlier_row_offsets(oid, oi.size, rows, cols)
+    tab = binding.bof4_gemv_outlier_table(cd, sd, rows, cols, block, cb, oid, ovd)
     x = rand_x(3, cols, 5).to(DEV)
-    y1 = binding.bof4_gemv(cd, sd, rows, cols, block, cb, x, oid, ovd, row_ptr=rp)
+    y1 = binding.bof4_gemv(cd, sd, rows, cols, block, cb, x, tab, oi.size)
     out = torch.full((3, rows), float("nan"), device=DEV)
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
-        y2 = binding.bof4_gemv(cd, sd, rows, cols, block, cb, x, oid, ovd, row_ptr=rp, out=out)
+        y2 = binding.bof4_gemv(cd, sd, rows, cols, block, cb, x, tab, oi.size, out=out)
     side.synchronize()
     torch.cuda.synchronize()
     assert y2 is out and torch.equal(y1, y2)
     # one token alone gives the same numbers as inside a batch
-    y3 = binding.bof4_gemv(cd, sd, rows, cols, block, cb, x[2], oid, ovd, row_ptr=rp)
+    y3 = binding.bof4_gemv(cd, sd, rows, cols, block, cb, x[2], tab, oi.size)
     assert torch.equal(y3[0], y1[2])
 
 
-def test_outlier_row_offsets_match_a_sorted_search():
-    rows, cols = 1000, 4096
+def test_outlier_table_offsets_and_entries():
+    """The table's first part counts the entries below the start of every row and every stretch of 2048 columns; its
+    second part holds column and (value - decoded placeholder) per entry, rounded once to binary32."""
+    rows, cols, block = 1000, 4096 + 1024, 64  # three stretches, the last one half as wide
+    cb, codes, scales, _, _ = quantized(rows, cols, block, 1, 0, seed=82)
     rng = np.random.default_rng(1)
     oi = np.sort(rng.choice(rows * cols, 50_000, replace=False)).astype(np.int64)
     oi = oi[(oi // cols) % 7 != 3]  # rows without entries
-    rp = binding.bof4_outlier_row_offsets(dev_i64(oi), oi.size, rows, cols).cpu().numpy()
-    assert np.array_equal(rp, np.searchsorted(oi, np.arange(rows + 1, dtype=np.int64) * cols, side="left"))
-    rp0 = binding.bof4_outlier_row_offsets(None, 0, 5, 64).cpu().numpy()
-    assert np.array_equal(rp0, np.zeros(6, dtype=np.int32))
+    ov = (rng.standard_normal(oi.size).astype(np.float32) * 0.2).astype(np.float16)
+    nbytes = binding.bof4_gemv_outlier_table_bytes(rows, cols, oi.size)
+    assert nbytes == (rows * 3 + 1 + 1) // 2 * 8 + 8 * oi.size
+    cd, sd = torch.from_numpy(codes).to(DEV), dev_u16(scales)
+    tab = binding.bof4_gemv_outlier_table(cd, sd, rows, cols, block, cb, dev_i64(oi), dev_u16(ov.view(np.uint16)))
+    raw = tab.cpu().numpy()
+    n_off = rows * 3 + 1
+    offs = raw[: 4 * n_off].view(np.uint32)
+    starts = (np.arange(rows, dtype=np.int64)[:, None] * cols + np.arange(3, dtype=np.int64)[None, :] * 2048).reshape(-1)
+    assert np.array_equal(offs, np.searchsorted(oi, np.concatenate([starts, [rows * cols]]), side="left"))
+    ent = raw[(n_off + 1) // 2 * 8:].view(np.uint32).reshape(-1, 2)
+    assert np.array_equal(ent[:, 0], (oi % cols).astype(np.uint32))
+    code = (codes[oi >> 1] >> ((oi & 1) * 4).astype(np.uint8)) & 15
+    old = scales.view(np.float16)[oi // block].astype(np.float64) * cb.astype(np.float32).astype(np.float64)[code]
+    delta = ov.astype(np.float64) - old  # exact product; the difference is exact or off by far less than 2^-24
+    assert np.all(np.abs(ent[:, 1].view(np.float32).astype(np.float64) - delta) <= 2.0 ** -24 * np.abs(delta))
+    with pytest.raises(binding.Bof4Error) as e:
+        binding.bof4_gemv_outlier_table(cd, sd, rows, cols, block, cb, dev_i64(oi), dev_u16(ov.view(np.uint16)),
+                                        out=torch.empty(nbytes - 8, dtype=torch.uint8, device=DEV))
+    assert e.value.code == binding.BOF4_ERR_WORKSPACE
 
 
 def test_gemv_argument_errors():
@@ -172,7 +190,7 @@ def test_gemv_argument_errors():
         binding.bof4_gemv(cd[4:], sd, rows - 1, cols, block, cb, x)
     assert e.value.code == binding.BOF4_ERR_ARG
     with pytest.raises(ValueError):
-        binding.bof4_gemv(cd, sd, rows, cols, block, cb, x, dev_i64(oi), dev_u16(ov))  # a list without row offsets
+        binding.bof4_gemv(cd, sd, rows, cols, block, cb, x, None, 3)  # outliers without their table
     with pytest.raises(ValueError):
         binding.bof4_gemv(cd, sd, rows, cols, block, cb, x.float())
     big = 32768 + 2048
