@@ -891,8 +891,10 @@ int bof4_gemv(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t row
         const uint32_t nt = n_tokens - t0 < GEMV_MAX_TOKENS ? n_tokens - t0 : GEMV_MAX_TOKENS;
         const uint16_t* xt = x + (uint64_t)t0 * cols;
         float* yt = y_dev + (uint64_t)t0 * rows;
+        // with a list every wave keeps its slice of x in LDS as well
+        const size_t lds = n_outliers > 0 ? (size_t)strips * GEMV_STRIP * 2 * nt : 0;
 #define BOF4_LAUNCH_GEMV(T_, OUT_)                                                                                \
-    hipLaunchKernelGGL((gemv_kernel<T_, OUT_>), dim3(grid), dim3(64 * (uint32_t)strips), 0, s, codes, scales_dev, \
+    hipLaunchKernelGGL((gemv_kernel<T_, OUT_>), dim3(grid), dim3(64 * (uint32_t)strips), lds, s, codes, scales_dev, \
                        (uint32_t)rows, (uint32_t)cols, log2_block, rc, cb, offsets_dev, entries_dev,              \
                        (uint32_t)n_outliers, xt, yt);
         if (n_outliers > 0) {

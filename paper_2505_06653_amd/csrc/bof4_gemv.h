@@ -97,7 +97,7 @@ __global__ __launch_bounds__(1024) void gemv_kernel(const uint4* __restrict__ co
                                                     CodebookArgs cb, const uint32_t* __restrict__ strip_ptr,
                                                     const uint2* __restrict__ entries, uint32_t n_out,
                                                     const uint16_t* __restrict__ x, float* __restrict__ y) {
-    constexpr uint32_t U = T == 1 ? 4 : 2;
+    constexpr uint32_t U = (T == 1 && !OUTLIERS) ? 4 : 2;
     struct Shared {  // one object, so that the table sits at LDS offset 0 (reachable by an immediate offset)
         float tab[16];
         float part[GEMV_MAX_STRIPS * GEMV_MAX_RC * T];
@@ -129,36 +129,54 @@ __global__ __launch_bounds__(1024) void gemv_kernel(const uint4* __restrict__ co
     }
     // where this strip's entries of the chunk's rows begin and end: lane j holds row r0 + j
     uint32_t p_lo = 0, p_hi = 0;
-    if (OUTLIERS && lane < r1 - r0) {
-        p_lo = min(strip_ptr[(uint64_t)(r0 + lane) * n_strips + wave], n_out);
-        p_hi = min(strip_ptr[(uint64_t)(r0 + lane) * n_strips + wave + 1], n_out);
+    // with a list, the wave also keeps its slice of x as bfloat16 in LDS, where an entry's column can be looked up
+    extern __shared__ __attribute__((aligned(16))) uint16_t x_lds[];
+    if (OUTLIERS) {
+        if (lane < r1 - r0) {
+            p_lo = min(strip_ptr[(uint64_t)(r0 + lane) * n_strips + wave], n_out);
+            p_hi = min(strip_ptr[(uint64_t)(r0 + lane) * n_strips + wave + 1], n_out);
+        }
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            uint32_t* dst = reinterpret_cast<uint32_t*>(x_lds + ((uint32_t)t * n_strips + wave) * GEMV_STRIP + lane * 32);
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                dst[i] = (__float_as_uint(xr[t][2 * i]) >> 16) | (__float_as_uint(xr[t][2 * i + 1]) & 0xffff0000u);
+        }
+        wave_lds_fence();
     }
     // what one list entry adds: (value - decoded placeholder) * x
     auto correction = [&](uint2 e, float* c) {
-        const uint32_t col = min(e.x, cols - 1);
+        const uint32_t col = (e.x - wave * GEMV_STRIP) & (GEMV_STRIP - 1);  // inside the strip by construction
 #pragma unroll
-        for (int t = 0; t < T; ++t) c[t] = fmaf(__uint_as_float(e.y), bf16_bits_to_f32(x[(uint64_t)t * cols + col]), c[t]);
+        for (int t = 0; t < T; ++t)
+            c[t] = fmaf(__uint_as_float(e.y),
+                        bf16_bits_to_f32(x_lds[((uint32_t)t * n_strips + wave) * GEMV_STRIP + col]), c[t]);
     };
-    for (uint32_t r = r0; r < r1; r += U) {
+    struct Group {  // U rows in flight: codes, block constants, and the rows' first 64 list entries
         uint4 q[U];
         float m[U];
         uint32_t pa[U], pb[U];
         uint2 oe[U];
+    };
+    auto issue = [&](uint32_t r, Group& g) {
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
             const uint32_t rr = min(r + u, r1 - 1);  // rows past the chunk repeat its last row and are dropped
             const uint64_t e = (uint64_t)rr * cols + col0;
-            q[u] = active ? load_stream(&codes[e >> 5]) : make_uint4(0u, 0u, 0u, 0u);
-            m[u] = active ? f16_bits_to_f32(__builtin_nontemporal_load(&scales[e >> log2_block])) : 0.0f;
+            g.q[u] = active ? load_stream(&codes[e >> 5]) : make_uint4(0u, 0u, 0u, 0u);
+            g.m[u] = active ? f16_bits_to_f32(__builtin_nontemporal_load(&scales[e >> log2_block])) : 0.0f;
             if (OUTLIERS) {
-                pa[u] = (uint32_t)__builtin_amdgcn_readlane((int)p_lo, (int)(rr - r0));
-                pb[u] = (uint32_t)__builtin_amdgcn_readlane((int)p_hi, (int)(rr - r0));
-                oe[u] = pa[u] + lane < pb[u] ? entries[pa[u] + lane] : make_uint2(0u, 0u);
+                g.pa[u] = (uint32_t)__builtin_amdgcn_readlane((int)p_lo, (int)(rr - r0));
+                g.pb[u] = (uint32_t)__builtin_amdgcn_readlane((int)p_hi, (int)(rr - r0));
+                g.oe[u] = g.pa[u] + lane < g.pb[u] ? entries[g.pa[u] + lane] : make_uint2(0u, 0u);
             }
         }
+    };
+    auto compute = [&](uint32_t r, const Group& g) {
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
-            const uint32_t w[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
+            const uint32_t w[4] = {g.q[u].x, g.q[u].y, g.q[u].z, g.q[u].w};
             float acc[T][2];
 #pragma unroll
             for (int t = 0; t < T; ++t) acc[t][0] = acc[t][1] = 0.0f;
@@ -183,15 +201,35 @@ __global__ __launch_bounds__(1024) void gemv_kernel(const uint4* __restrict__ co
 #pragma unroll
             for (int t = 0; t < T; ++t) c[t] = 0.0f;
             if (OUTLIERS) {
-                if (pa[u] + lane < pb[u]) correction(oe[u], c);
-                for (uint32_t k = pa[u] + 64 + lane; k < pb[u]; k += 64)  // more than 64 entries in one row and strip
+                if (g.pa[u] + lane < g.pb[u]) correction(g.oe[u], c);
+                for (uint32_t k = g.pa[u] + 64 + lane; k < g.pb[u]; k += 64)  // over 64 entries in one row and strip
                     correction(entries[k], c);
             }
 #pragma unroll
             for (int t = 0; t < T; ++t) {
-                const float s = wave_sum_lane63(fmaf(acc[t][0] + acc[t][1], m[u], c[t]));
+                const float s = wave_sum_lane63(fmaf(acc[t][0] + acc[t][1], g.m[u], c[t]));
                 if (lane == 63 && r + u < r1) sh.part[(wave * rc + (r + u - r0)) * T + t] = s;
             }
+        }
+    };
+    if (T == 1) {
+        // two buffers: the loads of the next U rows are in flight while the current ones are decoded
+        Group A, B;
+        issue(r0, A);
+        for (uint32_t r = r0; r < r1; r += 2 * U) {
+            const bool second = r + U < r1;  // wave-uniform
+            if (second) issue(r + U, B);
+            compute(r, A);
+            if (second) {
+                if (r + 2 * U < r1) issue(r + 2 * U, A);
+                compute(r + U, B);
+            }
+        }
+    } else {  // two tokens: the registers hold two slices of x and one buffer
+        for (uint32_t r = r0; r < r1; r += U) {
+            Group A;
+            issue(r, A);
+            compute(r, A);
         }
     }
     __syncthreads();
