@@ -810,6 +810,38 @@ int bof4_dequantize(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64
     return BOF4_OK;
 }
 
+// Workgroups of one bof4_gemv kernel variant that the current device holds at once (cached per variant, workgroup
+// size and dynamic LDS; 0 on failure).
+uint64_t gemv_resident_workgroups(int variant, uint32_t threads, size_t lds) {
+    struct Key {
+        int device, variant;
+        uint32_t threads;
+        size_t lds;
+        uint64_t slots;
+    };
+    static thread_local Key cache[8] = {};
+    static thread_local int next = 0;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    for (const Key& k : cache)
+        if (k.slots && k.device == dev && k.variant == variant && k.threads == threads && k.lds == lds) return k.slots;
+    int per_cu = 0, cus = 0;
+    hipError_t e;
+    switch (variant) {
+        case 0: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_kernel<1, false>, (int)threads, lds); break;
+        case 1: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_kernel<1, true>, (int)threads, lds); break;
+        case 2: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_kernel<2, false>, (int)threads, lds); break;
+        default: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_kernel<2, true>, (int)threads, lds); break;
+    }
+    if (e != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        return 0;
+    if (per_cu < 1) per_cu = 1;
+    Key& slot = cache[next];
+    next = (next + 1) % 8;
+    slot = Key{dev, variant, threads, lds, (uint64_t)per_cu * (uint64_t)cus};
+    return slot.slots;
+}
+
 // Outlier table of bof4_gemv: offsets [rows * strips + 1] (padded to 8 bytes), then one {column, delta} pair per entry.
 struct GemvTableLayout {
     size_t entries, total;
@@ -880,10 +912,6 @@ int bof4_gemv(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t row
     const CodebookArgs cb = make_codebook_args(cb_host);
     uint32_t log2_block = 5;
     while ((1u << log2_block) < block) ++log2_block;
-    // rows per workgroup: as few as still leave every wave four rows, until the chip holds 16 waves per CU
-    uint32_t rc = GEMV_MAX_RC;
-    while (rc > 4 && ((rows + rc - 1) / rc) * strips < 4096) rc /= 2;
-    const uint32_t grid = (uint32_t)((rows + rc - 1) / rc);
     const uint4* codes = (const uint4*)codes_dev;
     const uint16_t* x = (const uint16_t*)x_dev;
     timing_begin(s);
@@ -893,6 +921,14 @@ int bof4_gemv(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t row
         float* yt = y_dev + (uint64_t)t0 * rows;
         // with a list every wave keeps its slice of x in LDS as well
         const size_t lds = n_outliers > 0 ? (size_t)strips * GEMV_STRIP * 2 * nt : 0;
+        // Rows per workgroup: every workgroup pays for its slice of x, the level table and two barriers, so the
+        // rows are dealt out evenly over as many workgroups as the chip holds at once - one round, no tail.
+        const int variant = (nt == 1 ? 0 : 2) + (n_outliers > 0 ? 1 : 0);
+        const uint64_t slots = gemv_resident_workgroups(variant, 64 * (uint32_t)strips, lds);
+        if (slots == 0) return fail(BOF4_ERR_HIP, "bof4_gemv: occupancy query failed");
+        uint64_t rc64 = (rows + slots - 1) / slots;
+        const uint32_t rc = (uint32_t)(rc64 < 4 ? 4 : rc64 > GEMV_MAX_RC ? GEMV_MAX_RC : rc64);
+        const uint32_t grid = (uint32_t)((rows + rc - 1) / rc);
 #define BOF4_LAUNCH_GEMV(T_, OUT_)                                                                                \
     hipLaunchKernelGGL((gemv_kernel<T_, OUT_>), dim3(grid), dim3(64 * (uint32_t)strips), lds, s, codes, scales_dev, \
                        (uint32_t)rows, (uint32_t)cols, log2_block, rc, cb, offsets_dev, entries_dev,              \

@@ -176,6 +176,7 @@ __global__ __launch_bounds__(1024) void gemv_kernel(const uint4* __restrict__ co
     auto compute = [&](uint32_t r, const Group& g) {
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
+            if (r + u >= r1) break;  // wave-uniform: the chunk's last group may be short
             const uint32_t w[4] = {g.q[u].x, g.q[u].y, g.q[u].z, g.q[u].w};
             float acc[T][2];
 #pragma unroll
@@ -208,12 +209,13 @@ __global__ __launch_bounds__(1024) void gemv_kernel(const uint4* __restrict__ co
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 const float s = wave_sum_lane63(fmaf(acc[t][0] + acc[t][1], g.m[u], c[t]));
-                if (lane == 63 && r + u < r1) sh.part[(wave * rc + (r + u - r0)) * T + t] = s;
+                if (lane == 63) sh.part[(wave * rc + (r + u - r0)) * T + t] = s;
             }
         }
     };
-    if (T == 1) {
-        // two buffers: the loads of the next U rows are in flight while the current ones are decoded
+    if (T == 1 && OUTLIERS) {
+        // two buffers: the loads of the next U rows (list entries included) are in flight while the current ones are
+        // decoded.  Measured: worth 10-35 % with a list; without one the extra registers cost more than they gain.
         Group A, B;
         issue(r0, A);
         for (uint32_t r = r0; r < r1; r += 2 * U) {
@@ -225,7 +227,7 @@ __global__ __launch_bounds__(1024) void gemv_kernel(const uint4* __restrict__ co
                 compute(r + U, B);
             }
         }
-    } else {  // two tokens: the registers hold two slices of x and one buffer
+    } else {
         for (uint32_t r = r0; r < r1; r += U) {
             Group A;
             issue(r, A);
