@@ -31,6 +31,41 @@ BLOCK = 64
 PROFILED_TRAFFIC_BYTES = {"lloyd_step": 405.4e6, "quantize": 529.5e6, "dequantize": 526.2e6}
 
 
+def gemv_block_pass(w_flat, cb, T, dev, passes=20):
+    """The decoder in use (not part of the timed step): one token through the quantised matrices of the block,
+    y = W~ x per matrix with bof4_gemv, outliers included.  Projections that read the same input are one matrix, as
+    an inference engine stores them (q, k, v are adjacent in the flat block, and so are gate and up).  Returns the
+    time of one pass over the block and the rate on the algorithmic bytes (codes, constants, 8 bytes per outlier
+    table entry)."""
+    mats, off = [], 0
+    for name, r, c in (("qkv", 3 * 4096, 4096), ("o", 4096, 4096), ("gate_up", 2 * 11008, 4096), ("down", 4096, 11008)):
+        w = w_flat[off:off + r * c]
+        off += r * c
+        codes, scales, oi, ov, k = binding.bof4_quantize(w, BLOCK, cb, 1, opq_T=T, out_capacity=(r * c) // 50 if T else 0)
+        tab = binding.bof4_gemv_outlier_table(codes, scales, r, c, BLOCK, cb, oi, ov, n_outliers=k) if k else None
+        x = torch.randn((1, c), device=dev).to(torch.bfloat16)
+        y = torch.empty((1, r), dtype=torch.float32, device=dev)
+        mats.append((name, r, c, codes, scales, tab, k, x, y))
+    def one_pass():
+        for name, r, c, codes, scales, tab, k, x, y in mats:
+            binding.bof4_gemv(codes, scales, r, c, BLOCK, cb, x, tab, k, out=y)
+    for _ in range(3):
+        one_pass()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(passes):
+        one_pass()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / passes
+    nbytes = sum((0.5 + 2.0 / BLOCK) * r * c + 8.0 * k for _, r, c, _, _, _, k, _, _ in mats)
+    return {"ms": ms, "GBps_algorithmic": nbytes / (ms * 1e-3) / 1e9, "hbm_frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "outliers": int(sum(m[6] for m in mats)),
+            "note": "four bof4_gemv calls (qkv, o, gate+up, down of the block: all 202,375,168 weights; one token, "
+                    "fp32 accumulation), back to back on one stream, outside the timed step"}
+
+
 def cpu_baseline(w_samples, cb, T):
     """Oracle (as it stands) on a bounded sample of the same workload; reported baseline only."""
     import oracle
@@ -146,6 +181,7 @@ def main():
                                     out=mae_rec)
     torch.cuda.synchronize()
     t_mae = (time.perf_counter() - t_mae) / 3
+    gemv = gemv_block_pass(ws_list[0], cb, T if args.opq else 0.0, dev)
     # one plain device copy of known size (2 * n bytes read, 2 * n written), outside the timed region: the reference
     # against which a counter profile of this same command scales FETCH_SIZE / WRITE_SIZE
     deq.copy_(ws_list[0])
@@ -185,6 +221,7 @@ def main():
         "mae_step": {"call_ms": t_mae * 1e3, "weights_per_s": n / t_mae,
                      "note": "bof4_lloyd_step_mae (exact weighted medians of the 14 free levels, three passes over the weights), outside the "
                              "timed step"},
+        "gemv_block_pass": gemv,
         "per_call": per_call,
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic},

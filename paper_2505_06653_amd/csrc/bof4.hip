@@ -920,19 +920,20 @@ int bof4_gemv(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t row
         const uint16_t* xt = x + (uint64_t)t0 * cols;
         float* yt = y_dev + (uint64_t)t0 * rows;
         // with a list every wave keeps its slice of x in LDS as well
-        const size_t lds = n_outliers > 0 ? (size_t)strips * GEMV_STRIP * 2 * nt : 0;
+        const uint32_t waves = (uint32_t)(strips < GEMV_MAX_WAVES ? strips : GEMV_MAX_WAVES);
+        const size_t lds = n_outliers > 0 ? (size_t)waves * GEMV_STRIP * 2 * nt : 0;
         // Rows per workgroup: every workgroup pays for its slice of x, the level table and two barriers, so the
         // rows are dealt out evenly over as many workgroups as the chip holds at once - one round, no tail.
         const int variant = (nt == 1 ? 0 : 2) + (n_outliers > 0 ? 1 : 0);
-        const uint64_t slots = gemv_resident_workgroups(variant, 64 * (uint32_t)strips, lds);
+        const uint64_t slots = gemv_resident_workgroups(variant, 64 * waves, lds);
         if (slots == 0) return fail(BOF4_ERR_HIP, "bof4_gemv: occupancy query failed");
         uint64_t rc64 = (rows + slots - 1) / slots;
         const uint32_t rc = (uint32_t)(rc64 < 4 ? 4 : rc64 > GEMV_MAX_RC ? GEMV_MAX_RC : rc64);
         const uint32_t grid = (uint32_t)((rows + rc - 1) / rc);
 #define BOF4_LAUNCH_GEMV(T_, OUT_)                                                                                \
-    hipLaunchKernelGGL((gemv_kernel<T_, OUT_>), dim3(grid), dim3(64 * (uint32_t)strips), lds, s, codes, scales_dev, \
-                       (uint32_t)rows, (uint32_t)cols, log2_block, rc, cb, offsets_dev, entries_dev,              \
-                       (uint32_t)n_outliers, xt, yt);
+    hipLaunchKernelGGL((gemv_kernel<T_, OUT_>), dim3(grid), dim3(64 * waves), lds, s, codes, scales_dev,          \
+                       (uint32_t)rows, (uint32_t)cols, log2_block, rc, (uint32_t)strips, cb, offsets_dev,         \
+                       entries_dev, (uint32_t)n_outliers, xt, yt);
         if (n_outliers > 0) {
             if (nt == 1) { BOF4_LAUNCH_GEMV(1, true) } else { BOF4_LAUNCH_GEMV(2, true) }
         } else {

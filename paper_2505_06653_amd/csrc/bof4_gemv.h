@@ -25,7 +25,8 @@ namespace bof4 {
 constexpr uint32_t GEMV_STRIP = 2048;   // columns per wave
 constexpr uint32_t GEMV_MAX_RC = 64;    // rows per workgroup at most: the last step has one lane per row
 constexpr uint32_t GEMV_MAX_TOKENS = 2;    // tokens per launch: their slices of x live in registers
-constexpr uint32_t GEMV_MAX_STRIPS = 16;  // waves per workgroup: up to 32768 columns
+constexpr uint32_t GEMV_MAX_STRIPS = 16;  // up to 32768 columns
+constexpr uint32_t GEMV_MAX_WAVES = 8;    // waves per workgroup: two per SIMD, so that several workgroups pack a CU
 
 // Sum over the 64 lanes, delivered in lane 63 (other lanes hold prefixes).  Fixed tree: shifts by 1, 2, 4, 8 inside
 // rows of 16 lanes, then lane 15 of each row into the next odd row, then lane 31 into the upper half.
@@ -90,35 +91,43 @@ __device__ __forceinline__ uint32_t byte_of(uint32_t v) {
     return r;
 }
 
-// One workgroup: rows [blockIdx.x * rc, ...) of the matrix, one wave per strip.  U rows are in flight per wave.
+// One workgroup: rows [blockIdx.x * rc, ...) of the matrix; wave w takes strips w, w + waves, ... one after the other.
+// U rows are in flight per wave.
 template <int T, bool OUTLIERS>
-__global__ __launch_bounds__(1024) void gemv_kernel(const uint4* __restrict__ codes, const uint16_t* __restrict__ scales,
+__global__ __launch_bounds__(64 * GEMV_MAX_WAVES, 4) void gemv_kernel(const uint4* __restrict__ codes, const uint16_t* __restrict__ scales,
                                                     uint32_t rows, uint32_t cols, uint32_t log2_block, uint32_t rc,
-                                                    CodebookArgs cb, const uint32_t* __restrict__ strip_ptr,
+                                                    uint32_t n_strips, CodebookArgs cb,
+                                                    const uint32_t* __restrict__ strip_ptr,
                                                     const uint2* __restrict__ entries, uint32_t n_out,
                                                     const uint16_t* __restrict__ x, float* __restrict__ y) {
     constexpr uint32_t U = (T == 1 && !OUTLIERS) ? 4 : 2;
     struct Shared {  // one object, so that the table sits at LDS offset 0 (reachable by an immediate offset)
         float tab[16];
-        float part[GEMV_MAX_STRIPS * GEMV_MAX_RC * T];
+        float part[GEMV_MAX_WAVES * GEMV_MAX_RC * T];
     };
     __shared__ __attribute__((aligned(16))) Shared sh;
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_strips = blockDim.x >> 6;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_waves = blockDim.x >> 6;
     if (tid < 16) sh.tab[tid] = cb.lv32[tid];
     const uint32_t r0 = blockIdx.x * rc;
     const uint32_t r1 = min(rows, r0 + rc);
     __syncthreads();
     const char* tab = reinterpret_cast<const char*>(sh.tab);
 
-    const uint32_t col0 = wave * GEMV_STRIP + lane * 32;
+    for (uint32_t strip = wave; strip < n_strips; strip += n_waves) {
+    const uint32_t col0 = strip * GEMV_STRIP + lane * 32;
     const bool active = col0 < cols;
+    // with a list, the wave also keeps its slice of x as bfloat16 in LDS, where an entry's column can be looked up
+    extern __shared__ __attribute__((aligned(16))) uint16_t x_lds[];
+    if (OUTLIERS) wave_lds_fence();  // the previous strip's slice has been read
     float xr[T][32];
 #pragma unroll
     for (int t = 0; t < T; ++t) {
         const uint4* xp = reinterpret_cast<const uint4*>(x + (uint64_t)t * cols + col0);
+        uint4* xl = reinterpret_cast<uint4*>(x_lds + ((uint32_t)t * n_waves + wave) * GEMV_STRIP + lane * 32);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const uint4 v = active ? xp[k] : make_uint4(0u, 0u, 0u, 0u);
+            if (OUTLIERS) xl[k] = v;
             const uint32_t u[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -129,29 +138,20 @@ __global__ __launch_bounds__(1024) void gemv_kernel(const uint4* __restrict__ co
     }
     // where this strip's entries of the chunk's rows begin and end: lane j holds row r0 + j
     uint32_t p_lo = 0, p_hi = 0;
-    // with a list, the wave also keeps its slice of x as bfloat16 in LDS, where an entry's column can be looked up
-    extern __shared__ __attribute__((aligned(16))) uint16_t x_lds[];
     if (OUTLIERS) {
         if (lane < r1 - r0) {
-            p_lo = min(strip_ptr[(uint64_t)(r0 + lane) * n_strips + wave], n_out);
-            p_hi = min(strip_ptr[(uint64_t)(r0 + lane) * n_strips + wave + 1], n_out);
-        }
-#pragma unroll
-        for (int t = 0; t < T; ++t) {
-            uint32_t* dst = reinterpret_cast<uint32_t*>(x_lds + ((uint32_t)t * n_strips + wave) * GEMV_STRIP + lane * 32);
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-                dst[i] = (__float_as_uint(xr[t][2 * i]) >> 16) | (__float_as_uint(xr[t][2 * i + 1]) & 0xffff0000u);
+            p_lo = min(strip_ptr[(uint64_t)(r0 + lane) * n_strips + strip], n_out);
+            p_hi = min(strip_ptr[(uint64_t)(r0 + lane) * n_strips + strip + 1], n_out);
         }
         wave_lds_fence();
     }
     // what one list entry adds: (value - decoded placeholder) * x
     auto correction = [&](uint2 e, float* c) {
-        const uint32_t col = (e.x - wave * GEMV_STRIP) & (GEMV_STRIP - 1);  // inside the strip by construction
+        const uint32_t col = (e.x - strip * GEMV_STRIP) & (GEMV_STRIP - 1);  // inside the strip by construction
 #pragma unroll
         for (int t = 0; t < T; ++t)
             c[t] = fmaf(__uint_as_float(e.y),
-                        bf16_bits_to_f32(x_lds[((uint32_t)t * n_strips + wave) * GEMV_STRIP + col]), c[t]);
+                        bf16_bits_to_f32(x_lds[((uint32_t)t * n_waves + wave) * GEMV_STRIP + col]), c[t]);
     };
     struct Group {  // U rows in flight: codes, block constants, and the rows' first 64 list entries
         uint4 q[U];
@@ -202,14 +202,17 @@ __global__ __launch_bounds__(1024) void gemv_kernel(const uint4* __restrict__ co
 #pragma unroll
             for (int t = 0; t < T; ++t) c[t] = 0.0f;
             if (OUTLIERS) {
-                if (g.pa[u] + lane < g.pb[u]) correction(g.oe[u], c);
+                correction(g.oe[u], c);  // no entry: delta 0 (a non-finite x makes every row non-finite anyway)
                 for (uint32_t k = g.pa[u] + 64 + lane; k < g.pb[u]; k += 64)  // over 64 entries in one row and strip
                     correction(entries[k], c);
             }
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 const float s = wave_sum_lane63(fmaf(acc[t][0] + acc[t][1], g.m[u], c[t]));
-                if (lane == 63) sh.part[(wave * rc + (r + u - r0)) * T + t] = s;
+                if (lane == 63) {  // the wave's strips add up in its own slot
+                    float* slot = &sh.part[(wave * rc + (r + u - r0)) * T + t];
+                    *slot = strip == wave ? s : *slot + s;
+                }
             }
         }
     };
@@ -234,12 +237,13 @@ __global__ __launch_bounds__(1024) void gemv_kernel(const uint4* __restrict__ co
             compute(r, A);
         }
     }
+    }  // strips of this wave
     __syncthreads();
     if (wave == 0 && lane < r1 - r0) {
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             float s = 0.0f;
-            for (uint32_t p = 0; p < n_strips; ++p) s += sh.part[(p * rc + lane) * T + t];  // strips in order
+            for (uint32_t p = 0; p < n_waves; ++p) s += sh.part[(p * rc + lane) * T + t];  // waves in order
             y[(uint64_t)t * rows + r0 + lane] = s;
         }
     }
