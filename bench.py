@@ -66,6 +66,40 @@ def gemv_block_pass(w_flat, cb, T, dev, passes=20):
                     "fp32 accumulation), back to back on one stream, outside the timed step"}
 
 
+def gemv_shapes(dev, calls=50):
+    """bof4_gemv on the matrix shapes of workloads 1 and 4 (Student-t weights, block 64, signed, with and without the
+    OPQ outliers, one and two tokens): microseconds per call from HIP events around `calls` back-to-back calls."""
+    cb = codebooks.array(codebooks.BOF4S_MSE[BLOCK])
+    T = binding.bof4_opq_threshold(0.95, BLOCK)
+    rows_out = []
+    for rows, cols in ((4096, 4096), (12288, 4096), (22016, 4096), (4096, 11008), (8192, 28672), (28672, 8192)):
+        w = inputs.student_t_matrix(rows, cols, 5.0, 0.02, 0.3, seed=rows + cols, device=dev).reshape(-1)
+        n = rows * cols
+        for opq in (0, 1):
+            codes, scales, oi, ov, k = binding.bof4_quantize(w, BLOCK, cb, 1, opq_T=T if opq else 0.0,
+                                                             out_capacity=n // 50 if opq else 0)
+            tab = binding.bof4_gemv_outlier_table(codes, scales, rows, cols, BLOCK, cb, oi, ov, n_outliers=k) if opq else None
+            for nt in (1, 2):
+                x = torch.randn((nt, cols), device=dev).to(torch.bfloat16)
+                y = torch.empty((nt, rows), dtype=torch.float32, device=dev)
+                for _ in range(5):
+                    binding.bof4_gemv(codes, scales, rows, cols, BLOCK, cb, x, tab, k if opq else 0, out=y)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(calls):
+                    binding.bof4_gemv(codes, scales, rows, cols, BLOCK, cb, x, tab, k if opq else 0, out=y)
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / calls
+                nbytes = (0.5 + 2.0 / BLOCK) * n + 8.0 * (k if opq else 0)
+                rows_out.append({"rows": rows, "cols": cols, "outliers": int(k) if opq else 0, "tokens": nt,
+                                 "us_per_call": us, "GBps_algorithmic": nbytes / us / 1e3,
+                                 "hbm_frac": nbytes / us / 1e3 / HBM_PEAK_GBS})
+        del w
+    return rows_out
+
+
 def cpu_baseline(w_samples, cb, T):
     """Oracle (as it stands) on a bounded sample of the same workload; reported baseline only."""
     import oracle
@@ -98,12 +132,18 @@ def main():
     ap.add_argument("--replicas", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--opq", type=int, default=1, help="0 runs the path without outlier extraction (not the headline)")
+    ap.add_argument("--gemv-shapes", action="store_true",
+                    help="instead of the benchmark step: bof4_gemv on a table of matrix shapes, one JSON line")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (sharding is described in DESIGN.md)",
               file=sys.stderr)
         sys.exit(2)
     dev = torch.device("cuda:0")
+    if args.gemv_shapes:
+        torch.cuda.set_device(dev)
+        print(json.dumps({"bof4_gemv": gemv_shapes(dev)}))
+        return
     torch.cuda.set_device(dev)
     binding.lib()
 
