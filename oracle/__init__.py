@@ -27,6 +27,15 @@ class LloydStats(ctypes.Structure):
                 "n_used": int(self.n_used), "n_outliers": int(self.n_outliers)}
 
 
+class ErrorStats(ctypes.Structure):
+    _fields_ = [("sse", ctypes.c_double), ("sae", ctypes.c_double), ("max_abs", ctypes.c_double),
+                ("n_outliers", ctypes.c_uint64), ("n", ctypes.c_uint64)]
+
+    def as_dict(self):
+        return {"sse": self.sse, "sae": self.sae, "max_abs": self.max_abs, "n_outliers": int(self.n_outliers),
+                "n": int(self.n)}
+
+
 class MaeStats(ctypes.Structure):
     _fields_ = [("median", ctypes.c_double * 16), ("den", ctypes.c_double * 16), ("cnt", ctypes.c_uint64 * 16),
                 ("sae", ctypes.c_double), ("n_used", ctypes.c_uint64), ("n_outliers", ctypes.c_uint64)]
@@ -55,6 +64,9 @@ def lib():
         L.oracle_dequantize.restype = ctypes.c_int
         L.oracle_dequantize.argtypes = [u8p, u16p, ctypes.c_uint64, ctypes.c_uint32, f64p, i64p, u16p,
                                         ctypes.c_uint64, u16p]
+        L.oracle_quant_error.restype = ctypes.c_int
+        L.oracle_quant_error.argtypes = [u16p, ctypes.c_uint64, ctypes.c_uint32, f64p, ctypes.c_int, ctypes.c_double,
+                                         ctypes.POINTER(ErrorStats)]
         L.oracle_gemv.restype = ctypes.c_int
         L.oracle_gemv.argtypes = [u8p, u16p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint32, f64p, i64p, u16p,
                                   ctypes.c_uint64, u16p, ctypes.c_uint32, f64p, f64p]
@@ -133,6 +145,15 @@ def dequantize(codes, scales, n, block, cb, out_idx=None, out_val=None):
                                  _p(cb, ctypes.c_double), _p(out_idx, ctypes.c_int64) if k else None,
                                  _p(out_val, ctypes.c_uint16) if k else None, k, _p(out, ctypes.c_uint16))
     return st, out[:n]
+
+
+def quant_error(w, block, cb, signed, opq_T=0.0):
+    """Returns (status, dict: sse, sae, max_abs of w - Q(w) over all weights, n_outliers, n)."""
+    w, cb = _w(w), _cb(cb)
+    st_ = ErrorStats()
+    st = lib().oracle_quant_error(_p(w, ctypes.c_uint16), w.size, block, _p(cb, ctypes.c_double), int(signed),
+                                  float(opq_T), ctypes.byref(st_))
+    return st, st_.as_dict()
 
 
 def gemv(codes, scales, rows, cols, block, cb, x, out_idx=None, out_val=None):

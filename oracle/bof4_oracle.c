@@ -18,6 +18,10 @@
  *   MAE step (weighted median): brute-force minimiser of sum a|x - c| on tiny inputs; the plain lower median
  *                                when all blocks weigh the same; fixed point on Gaussian samples equals the
  *                                printed MAE codebooks
+ *   quantisation error         : zero on a tensor that is already decoded (Q is idempotent); one hand-made block;
+ *                                within the decoder's rounding of the Lloyd step's sse (appendix B.3); the orderings
+ *                                the paper reports (signed below absolute, MAE-/MSE-optimised best on their own
+ *                                metric, OPQ lowers both)
  *   decoder inside a matrix-vector product: constant codes (level times sum of x), unit vectors (one column of
  *                                the decoded matrix), planted outliers, linearity, and the decoded bfloat16 matrix
  *                                times x within the decoder's rounding bound
@@ -293,6 +297,60 @@ int oracle_dequantize(const uint8_t* codes, const uint16_t* scales, uint64_t n, 
     }
     for (uint64_t k = 0; k < n_outliers; ++k) w_out[out_idx[k]] = f32_to_bf16_rne(f16_to_f32(out_val[k]));
     return ORACLE_OK;
+}
+
+/* ---------------------------------------------------------------- quantisation error --------------------- */
+
+typedef struct {
+    double sse;          /* sum over all n weights of (w - Q(w))^2                                             */
+    double sae;          /* sum of |w - Q(w)|                                                                  */
+    double max_abs;      /* largest |w - Q(w)|                                                                 */
+    uint64_t n_outliers; /* weights stored as outliers                                                         */
+    uint64_t n;          /* weights compared                                                                   */
+} oracle_error_stats;
+
+/*
+ * The error of the quantiser on a tensor, as the paper reports it (MSE = sse / n, MAE = sae / n: section 5,
+ * quantisation-error paragraphs and table; the decomposition of appendix B.3 is in terms of the same difference):
+ * Q(w) is what oracle_dequantize returns for what oracle_quantize made of w - the decoded bfloat16 weight, or the
+ * stored outlier.  Nothing else happens here: quantise, decode, subtract, add up in binary64 in index order.
+ */
+int oracle_quant_error(const uint16_t* w, uint64_t n, uint32_t I, const double* cb, int signed_norm, double T,
+                       oracle_error_stats* out) {
+    if (!w || !cb || !out) return ORACLE_ERR_ARG;
+    if (!valid_block(I) || n == 0 || n % I != 0 || !valid_codebook(cb) || !(T >= 0.0)) return ORACLE_ERR_ARG;
+    uint8_t* codes = (uint8_t*)malloc(n / 2);
+    uint16_t* scales = (uint16_t*)malloc((n / I) * sizeof(uint16_t));
+    uint16_t* deq = (uint16_t*)malloc(n * sizeof(uint16_t));
+    const uint64_t cap = T > 0.0 ? n : 0;
+    int64_t* oidx = (int64_t*)malloc((cap ? cap : 1) * sizeof(int64_t));
+    uint16_t* oval = (uint16_t*)malloc((cap ? cap : 1) * sizeof(uint16_t));
+    int st = ORACLE_ERR_ARG;
+    if (codes && scales && deq && oidx && oval) {
+        uint64_t k = 0;
+        st = oracle_quantize(w, n, I, cb, signed_norm, T, codes, scales, oidx, oval, cap, &k);
+        if (st == ORACLE_OK) st = oracle_dequantize(codes, scales, n, I, cb, oidx, oval, k, deq);
+        if (st == ORACLE_OK) {
+            double sse = 0.0, sae = 0.0, mx = 0.0;
+            for (uint64_t i = 0; i < n; ++i) {
+                const double d = (double)bf16_to_f32(w[i]) - (double)bf16_to_f32(deq[i]);
+                sse += d * d;
+                sae += fabs(d);
+                if (fabs(d) > mx) mx = fabs(d);
+            }
+            out->sse = sse;
+            out->sae = sae;
+            out->max_abs = mx;
+            out->n_outliers = k;
+            out->n = n;
+        }
+    }
+    free(codes);
+    free(scales);
+    free(deq);
+    free(oidx);
+    free(oval);
+    return st;
 }
 
 /* ---------------------------------------------------------------- decoder inside a matrix-vector product --- */

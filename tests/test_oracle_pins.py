@@ -574,3 +574,79 @@ def test_gemv_argument_errors():
     assert st == oracle.ERR_ARG
     x96 = bf16_bits(np.zeros(96, dtype=np.float32))
     assert oracle.gemv(packed[:96], s16[:3], 2, 96, 64, CB_S64, x96)[0] == oracle.ERR_ARG  # cols not a multiple of block
+
+
+# ------------------------------------------------------------------------------------------- quantisation error
+def test_quant_error_of_one_hand_made_block():
+    # block of 32: maximum 1.0 (signed constant +1), 0.5 and -0.25 elsewhere zeros; codebook: the printed BOF4-S one
+    w = np.zeros(32, dtype=np.float32)
+    w[3], w[7], w[20] = 1.0, 0.5, -0.25
+    cb = CB_S64
+    st, e = oracle.quant_error(bf16_bits(w), 32, cb, 1)
+    assert st == oracle.OK and e["n"] == 32 and e["n_outliers"] == 0
+    lv = cb.astype(np.float32)
+    def q(x):  # nearest level (no ties here), decoded with constant 1 and rounded to bfloat16
+        c = int(np.argmin(np.abs(cb - x)))
+        return float(bf16_val(bf16_bits(np.array([lv[c]], dtype=np.float32)))[0])
+    errs = np.array([x - q(x) for x in w.astype(np.float64)])
+    assert errs[3] == 0.0  # the block maximum is kept exactly
+    assert e["sse"] == pytest.approx(float((errs ** 2).sum()), rel=1e-14)
+    assert e["sae"] == pytest.approx(float(np.abs(errs).sum()), rel=1e-14)
+    assert e["max_abs"] == float(np.abs(errs).max())
+
+
+@pytest.mark.parametrize("signed", [0, 1])
+def test_quant_error_is_zero_on_a_decoded_tensor(signed):
+    """Q(Q(w)) = Q(w) without outlier storage: the block maximum comes back exactly, every other decoded weight lies
+    within 2^-9 of its level times the constant and is assigned to the same level again."""
+    wb = inputs.bits(inputs.student_t_matrix(64, 512, nu=5.0, std=0.02, row_sigma=0.3, seed=47))
+    cb = CB_S64 if signed else CB_U64
+    st, e0 = oracle.quant_error(wb, 64, cb, signed)
+    assert st == oracle.OK and e0["sse"] > 0 and e0["n_outliers"] == 0
+    st, codes, scales, _, _, _ = oracle.quantize(wb, 64, cb, signed)
+    st, deq = oracle.dequantize(codes, scales, wb.size, 64, cb)
+    st, e = oracle.quant_error(deq, 64, cb, signed)
+    assert st == oracle.OK and e["sse"] == 0.0 and e["sae"] == 0.0 and e["max_abs"] == 0.0
+
+
+def test_quant_error_matches_the_lloyd_steps_sse_within_the_decoders_rounding():
+    """Appendix B.3: MSE(W, Q(W)) = sum m^2 (x - c)^2 / n.  The Lloyd step adds that up from normalised weights; the
+    error pass from decoded bfloat16 weights, each rounded by at most 2^-9 |w~|."""
+    wb = inputs.bits(inputs.gaussian_blocks(4096, 64, seed=48))
+    for signed, cb in ((0, CB_U64), (1, CB_S64)):
+        st, e = oracle.quant_error(wb, 64, cb, signed)
+        st, s = oracle.lloyd_step(wb, 64, cb, signed)
+        assert e["n"] == s["n_used"] == wb.size
+        # |d1^2 - d2^2| summed: 2 |d| * 2^-9 |w~| per weight at most; far less on average (random signs)
+        assert abs(e["sse"] - s["sse"]) <= 0.02 * s["sse"]
+        st, sm = oracle.lloyd_step_mae(wb, 64, cb, signed)
+        assert abs(e["sae"] - sm["sae"]) <= 0.01 * sm["sae"]
+
+
+def test_quant_error_orderings_reported_in_the_paper():
+    """Section 5 on Gaussian weights, I = 64: signed normalisation lowers both errors; the MSE-optimised codebook has
+    the lower MSE, the MAE-optimised one the lower MAE; OPQ lowers both (heavier tails: Student-t weights)."""
+    wb = inputs.bits(inputs.gaussian_blocks(1 << 14, 64, seed=49))
+    err = {}
+    for name, signed, cb in (("u_mse", 0, codebooks.BOF4_MSE_64), ("u_mae", 0, codebooks.BOF4_MAE_64),
+                             ("s_mse", 1, codebooks.BOF4S_MSE[64]), ("s_mae", 1, codebooks.BOF4S_MAE_64)):
+        st, e = oracle.quant_error(wb, 64, codebooks.array(cb), signed)
+        assert st == oracle.OK
+        err[name] = (e["sse"] / e["n"], e["sae"] / e["n"])
+    assert err["s_mse"][0] < err["u_mse"][0] and err["s_mae"][1] < err["u_mae"][1]
+    assert err["u_mse"][0] < err["u_mae"][0] and err["u_mae"][1] < err["u_mse"][1]
+    assert err["s_mse"][0] < err["s_mae"][0] and err["s_mae"][1] < err["s_mse"][1]
+    # the table's ratio of BOF4-S (MSE) to BOF4 (MSE) on real weights is 0.92; Gaussian weights give the same picture
+    assert 0.88 < err["s_mse"][0] / err["u_mse"][0] < 0.96
+    wt = inputs.bits(inputs.student_t_matrix(256, 1024, nu=5.0, std=0.02, row_sigma=0.3, seed=50))
+    st, plain = oracle.quant_error(wt, 64, CB_S64, 1)
+    st, opq = oracle.quant_error(wt, 64, CB_S64, 1, oracle.opq_threshold(0.95, 64))
+    assert opq["n_outliers"] > 0 and opq["sse"] < plain["sse"] and opq["sae"] < plain["sae"]
+
+
+def test_quant_error_argument_errors():
+    wb = bf16_bits(np.zeros(64, dtype=np.float32))
+    assert oracle.quant_error(wb, 48, CB_S64, 1)[0] == oracle.ERR_ARG
+    assert oracle.quant_error(wb[:40], 32, CB_S64, 1)[0] == oracle.ERR_ARG
+    st, e = oracle.quant_error(wb, 64, CB_S64, 1)
+    assert st == oracle.OK and e["sse"] == 0.0 and e["sae"] == 0.0  # all-zero block: decoded as zeros
