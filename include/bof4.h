@@ -154,6 +154,26 @@ int bof4_dequantize(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64
                     const double* cb_host, const int64_t* out_idx_dev, const uint16_t* out_val_dev,
                     uint64_t n_outliers, void* w_out_dev, void* stream);
 
+/* The quantisation error of a tensor (the MSE / MAE figures of section 5 and of the paper's error table; the difference
+ * that appendix B.3 decomposes): sums over all n weights of w - Q(w), where Q(w) is what bof4_dequantize returns for
+ * what bof4_quantize stores - the bfloat16 decoded weight, or the outlier as kept in binary16. */
+typedef struct {
+    double sse;          /* sum (w - Q(w))^2 : n * MSE                                                               */
+    double sae;          /* sum |w - Q(w)|   : n * MAE                                                               */
+    double max_abs;      /* largest |w - Q(w)|                                                                       */
+    uint64_t n_outliers; /* weights the quantiser stores as outliers                                                 */
+    uint64_t n;          /* weights compared                                                                         */
+} bof4_error_stats;
+
+/*
+ * One pass over the weights that quantises, decodes and compares in registers: nothing but the record is written
+ * (2 bytes of memory traffic per weight, against 7 for quantise + dequantise + compare).  Arguments, workspace
+ * (bof4_workspace_bytes(n, block, 0)) and the hand-over of the record as for bof4_lloyd_step.  max_abs and n_outliers
+ * are exact; sse and sae are binary64 sums in a fixed order (bit-reproducible).
+ */
+int bof4_quant_error(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                     double opq_T, bof4_error_stats* out_host, void* ws_dev, size_t ws_bytes, void* stream);
+
 /*
  * The decoder inside a matrix-vector product (section 2.1 eq. 3 applied in a linear layer, outliers of section 3.3
  * restored; the setting of the appendix on the runtime overhead of OPQ).  The quantised tensor is a row-major
@@ -185,7 +205,7 @@ int bof4_gemv_outlier_table(const uint8_t* codes_dev, const uint16_t* scales_dev
                             void* stream);
 size_t bof4_gemv_outlier_table_bytes(uint64_t rows, uint64_t cols, uint64_t n_outliers);
 
-/* Measurement aid: the next bof4_quantize / bof4_dequantize / bof4_lloyd_step / bof4_gemv call made by this thread records
+/* Measurement aid: the next bof4_quantize / bof4_dequantize / bof4_lloyd_step / bof4_quant_error / bof4_gemv call made by this thread records
  * the caller-owned hipEvent_t `start_event` immediately before and `stop_event` immediately after its main kernel
  * (the one that streams over the weights), on the call's stream; helper kernels and host synchronisation lie
  * outside the pair.  The request is consumed by that call.  Pass NULLs to cancel. */

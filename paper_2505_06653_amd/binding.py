@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(HERE, "libbof4_hip.so")
 BOF4_OK, BOF4_ERR_ARG, BOF4_ERR_CAPACITY, BOF4_ERR_WORKSPACE, BOF4_ERR_HIP = 0, -1, -2, -3, -4
 EXPORTS = ("bof4_workspace_bytes", "bof4_opq_threshold", "bof4_thresholds", "bof4_bin_table", "bof4_lloyd_step",
            "bof4_codebook_update", "bof4_lloyd_step_mae", "bof4_codebook_update_mae", "bof4_quantize",
-           "bof4_dequantize", "bof4_gemv", "bof4_gemv_outlier_table",
+           "bof4_dequantize", "bof4_quant_error", "bof4_gemv", "bof4_gemv_outlier_table",
            "bof4_gemv_outlier_table_bytes", "bof4_time_next_call", "bof4_last_error",
            "bof4_last_hip_error")
 
@@ -34,6 +34,15 @@ class LloydStats(ctypes.Structure):
         return {"num": np.array(self.num[:], dtype=np.float64), "den": np.array(self.den[:], dtype=np.float64),
                 "cnt": np.array(self.cnt[:], dtype=np.uint64), "sse": float(self.sse),
                 "n_used": int(self.n_used), "n_outliers": int(self.n_outliers)}
+
+
+class ErrorStats(ctypes.Structure):
+    _fields_ = [("sse", ctypes.c_double), ("sae", ctypes.c_double), ("max_abs", ctypes.c_double),
+                ("n_outliers", ctypes.c_uint64), ("n", ctypes.c_uint64)]
+
+    def as_dict(self):
+        return {"sse": self.sse, "sae": self.sae, "max_abs": self.max_abs, "n_outliers": int(self.n_outliers),
+                "n": int(self.n)}
 
 
 class MaeStats(ctypes.Structure):
@@ -83,6 +92,9 @@ def lib():
                                     ctypes.c_size_t, vp]
         L.bof4_dequantize.restype = ctypes.c_int
         L.bof4_dequantize.argtypes = [vp, vp, ctypes.c_uint64, ctypes.c_uint32, f64p, vp, vp, ctypes.c_uint64, vp, vp]
+        L.bof4_quant_error.restype = ctypes.c_int
+        L.bof4_quant_error.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint32, f64p, ctypes.c_int, ctypes.c_double,
+                                       ctypes.POINTER(ErrorStats), vp, ctypes.c_size_t, vp]
         L.bof4_gemv.restype = ctypes.c_int
         L.bof4_gemv.argtypes = [vp, vp, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint32, f64p, vp, ctypes.c_uint64,
                                 vp, ctypes.c_uint32, vp, vp]
@@ -213,6 +225,24 @@ def pinned_counter():
     """A uint64 outlier counter in pinned host memory.  Returns (ctypes.c_uint64, keepalive)."""
     buf = torch.zeros(1, dtype=torch.int64).pin_memory()
     return ctypes.c_uint64.from_address(buf.data_ptr()), buf
+
+
+def pinned_error_stats():
+    """An ErrorStats record in pinned host memory.  Returns (struct, keepalive)."""
+    buf = torch.zeros(ctypes.sizeof(ErrorStats), dtype=torch.uint8).pin_memory()
+    return ErrorStats.from_address(buf.data_ptr()), buf
+
+
+def bof4_quant_error(w, block, cb, signed, opq_T=0.0, ws=None, stream=None, out=None):
+    """Quantisation error of the flat bf16 device tensor w: dict with sse, sae, max_abs, n_outliers, n."""
+    cb, cbp = _cb(cb)
+    n = w.numel()
+    if ws is None:
+        ws = alloc_workspace(n, block, 0, w.device)
+    rec = out if out is not None else ErrorStats()
+    _check(lib().bof4_quant_error(_ptr(w), n, block, cbp, int(signed), float(opq_T), ctypes.byref(rec), _ptr(ws),
+                                  ws.numel(), _stream(stream)))
+    return rec.as_dict()
 
 
 def bof4_gemv_outlier_table_bytes(rows, cols, n_outliers):

@@ -25,6 +25,7 @@
 #include "bof4_segment.h"
 #include "bof4_mae.h"
 #include "bof4_gemv.h"
+#include "bof4_error.h"
 
 namespace {
 using namespace bof4;
@@ -638,6 +639,61 @@ int bof4_bin_table(const double* cb_host, float* thr33_host, uint32_t* base33_ho
         base33_host[b] = t.base[b];
     }
     *fast_host = (int)t.fast;
+    return BOF4_OK;
+}
+
+int bof4_quant_error(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                     double opq_T, bof4_error_stats* out_host, void* ws_dev, size_t ws_bytes, void* stream) {
+    if (!w_dev || !out_host) return fail(BOF4_ERR_ARG, "bof4_quant_error: null pointer");
+    if (!valid_block(block) || n == 0 || n % block != 0) return fail(BOF4_ERR_ARG, "bof4_quant_error: bad n or block");
+    if (!valid_codebook(cb_host)) return fail(BOF4_ERR_ARG, "bof4_quant_error: codebook must be 16 finite ascending levels");
+    if (!(opq_T >= 0.0) || !std::isfinite(opq_T)) return fail(BOF4_ERR_ARG, "bof4_quant_error: opq_T must be finite and >= 0");
+    if (!aligned(w_dev, 16)) return fail(BOF4_ERR_ARG, "bof4_quant_error: misaligned weights");
+    if (!ws_dev || !aligned(ws_dev, 256)) return fail(BOF4_ERR_ARG, "bof4_quant_error: workspace null or misaligned");
+    static_assert((SEG_GRID + 2) * ERR_PART <= (SEG_GRID + 1) * LLOYD_PART, "the Lloyd workspace holds the error records");
+    if (ws_bytes < lloyd_ws_bytes()) return fail(BOF4_ERR_WORKSPACE, "bof4_quant_error: workspace too small");
+    static_assert(sizeof(bof4_error_stats) == 5 * 8, "result record and bof4_error_stats must match");
+    hipStream_t s = (hipStream_t)stream;
+    const uint32_t seg = block < 64 ? block : 64;
+    const uint64_t n_seg = n / seg;
+    const CodebookArgs cb = make_codebook_args(cb_host);
+    const BinTable bt = make_bin_table(cb);
+    double* partials = (double*)ws_dev;
+    const double T2 = opq_T * opq_T;
+    const bool opq = opq_T > 0.0;
+    const uint4* w = (const uint4*)w_dev;
+    const uint64_t tiles = (n_seg + 63) / 64;
+    const uint64_t wantg = (tiles + WAVES_PER_WG - 1) / WAVES_PER_WG;
+    const uint32_t sgrid = (uint32_t)(wantg < SEG_GRID ? wantg : SEG_GRID);
+    timing_begin(s);
+#define BOF4_LAUNCH_ERR(II)                                                                                          \
+    if (bt.fast && opq) hipLaunchKernelGGL((seg_error_kernel<II, true, true>), dim3(sgrid), dim3(256), 0, s, w, n_seg, \
+                                           cb, bt, signed_norm, T2, partials);                                       \
+    else if (bt.fast) hipLaunchKernelGGL((seg_error_kernel<II, true, false>), dim3(sgrid), dim3(256), 0, s, w, n_seg,  \
+                                         cb, bt, signed_norm, T2, partials);                                         \
+    else if (opq) hipLaunchKernelGGL((seg_error_kernel<II, false, true>), dim3(sgrid), dim3(256), 0, s, w, n_seg, cb,  \
+                                     bt, signed_norm, T2, partials);                                                 \
+    else hipLaunchKernelGGL((seg_error_kernel<II, false, false>), dim3(sgrid), dim3(256), 0, s, w, n_seg, cb, bt,      \
+                            signed_norm, T2, partials);
+    switch (block) {
+        case 32: BOF4_LAUNCH_ERR(32) break;
+        case 64: BOF4_LAUNCH_ERR(64) break;
+        case 128: BOF4_LAUNCH_ERR(128) break;
+        default: BOF4_LAUNCH_ERR(256) break;
+    }
+#undef BOF4_LAUNCH_ERR
+    timing_end(s);
+    double* rec_dev = partials + (uint64_t)sgrid * ERR_PART;
+    double* direct = (double*)device_view_of_host(out_host);
+    if (direct) out_host->n = FLAG_PENDING;  // the word the final kernel writes last
+    hipLaunchKernelGGL(error_final_kernel, dim3(1), dim3(64), 0, s, partials, sgrid, n, direct ? direct : rec_dev);
+    HIP_TRY(hipGetLastError());
+    if (direct) {
+        HIP_TRY(wait_for_flag(s, &out_host->n));
+    } else {
+        HIP_TRY(hipMemcpyAsync(out_host, rec_dev, sizeof(bof4_error_stats), hipMemcpyDeviceToHost, s));
+        HIP_TRY(wait_for_stream(s));
+    }
     return BOF4_OK;
 }
 

@@ -1,0 +1,112 @@
+"""GPU parity of bof4_quant_error (quantise, decode and compare in one pass) against the oracle, which quantises,
+decodes and subtracts step by step: outlier count and largest error exact, the two binary64 sums to relative 1e-9
+(every term is the exact difference of two bfloat16 numbers - or off by 2^-24 of it where the two lie more than 2^16
+apart; the orders of summation differ)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_06653_amd import binding, codebooks, inputs
+from test_gpu_parity import cb_for, make_weights
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+RTOL = 1e-9
+
+
+def assert_error_close(g, o):
+    assert g["n"] == o["n"] and g["n_outliers"] == o["n_outliers"]
+    assert g["max_abs"] == o["max_abs"]
+    assert abs(g["sse"] - o["sse"]) <= RTOL * o["sse"]
+    assert abs(g["sae"] - o["sae"]) <= RTOL * o["sae"]
+
+
+@pytest.mark.parametrize("block", [32, 64, 128, 256])
+@pytest.mark.parametrize("signed", [0, 1])
+@pytest.mark.parametrize("opq", [0, 1])
+def test_quant_error_parity(block, signed, opq):
+    w = make_weights(29, 1024, seed=700 + block + signed)  # 14.5 wave tiles, ragged tail
+    T = oracle.opq_threshold(0.95, block) if opq else 0.0
+    cb = cb_for(block, signed)
+    st, o = oracle.quant_error(inputs.bits(w), block, cb, signed, T)
+    assert st == oracle.OK and (o["n_outliers"] > 0) == bool(opq) and o["sse"] > 0
+    assert_error_close(binding.bof4_quant_error(w.to(DEV), block, cb, signed, opq_T=T), o)
+
+
+@pytest.mark.parametrize("opq", [0, 1])
+def test_quant_error_codebook_without_a_zero_level_and_one_outside_the_bin_table(opq):
+    """Without a zero level the placeholder of an outlier decodes to something, which must not count as the error of a
+    zero weight; two thresholds inside one 1/16 bin send the kernel through its 15-compare search."""
+    w = make_weights(16, 1024, seed=710)
+    T = oracle.opq_threshold(0.95, 64) if opq else 0.0
+    no_zero = cb_for(64, 1) + 0.013 * np.linspace(-1, 1, 16) ** 2 + 0.004
+    crowded = np.array([-1, -.8, -.6, -.45, -.3, -.2, -.1, 0.0, 0.01, 0.02, .15, .3, .45, .6, .8, 1.0])
+    for cb in (no_zero, crowded):
+        st, o = oracle.quant_error(inputs.bits(w), 64, cb, 1, T)
+        assert st == oracle.OK
+        assert_error_close(binding.bof4_quant_error(w.to(DEV), 64, cb, 1, opq_T=T), o)
+
+
+def test_quant_error_edge_blocks():
+    blocks = [torch.zeros(64), torch.full((64,), 0.75), torch.linspace(-1, 1, 64) * 3e-6,
+              torch.linspace(-1, 1, 64) * 6.0e4, torch.linspace(-1, 1, 64) * 1e-30]
+    t = torch.zeros(64)
+    t[7] = 3.0e5  # an outlier beyond binary16's range: stored as infinity, its error is infinite on both sides
+    t[8:40] = torch.linspace(-1, 1, 32) * 0.01
+    w = torch.cat(blocks).to(torch.bfloat16)
+    cb = cb_for(64, 1)
+    for T in (0.0, oracle.opq_threshold(0.95, 64)):
+        st, o = oracle.quant_error(inputs.bits(w), 64, cb, 1, T)
+        assert_error_close(binding.bof4_quant_error(w.to(DEV), 64, cb, 1, opq_T=T), o)
+    wz = torch.zeros(128, dtype=torch.bfloat16)
+    g = binding.bof4_quant_error(wz.to(DEV), 64, cb, 1)
+    assert g["sse"] == 0.0 and g["sae"] == 0.0 and g["max_abs"] == 0.0 and g["n"] == 128
+    big = torch.cat([t, torch.zeros(64)]).to(torch.bfloat16)
+    T = oracle.opq_threshold(0.95, 64)
+    st, o = oracle.quant_error(inputs.bits(big), 64, cb, 1, T)
+    g = binding.bof4_quant_error(big.to(DEV), 64, cb, 1, opq_T=T)
+    assert o["n_outliers"] == g["n_outliers"] == 1 and np.isinf(o["sse"]) and np.isinf(g["sse"])
+
+
+def test_quant_error_agrees_with_quantise_then_dequantise_on_the_gpu_and_repeats_bit_for_bit():
+    w = make_weights(64, 2048, seed=720).to(DEV)
+    cb = cb_for(64, 1)
+    T = oracle.opq_threshold(0.95, 64)
+    rec, keep = binding.pinned_error_stats()
+    g1 = binding.bof4_quant_error(w, 64, cb, 1, opq_T=T, out=rec)
+    g2 = binding.bof4_quant_error(w, 64, cb, 1, opq_T=T)
+    assert g1 == g2
+    codes, scales, oi, ov, k = binding.bof4_quantize(w, 64, cb, 1, opq_T=T, out_capacity=w.numel() // 20)
+    deq = binding.bof4_dequantize(codes, scales, w.numel(), 64, cb, oi, ov, n_outliers=k)
+    d = w.double() - deq.double()
+    assert k == g1["n_outliers"]
+    assert float(d.abs().max()) == g1["max_abs"]
+    assert abs(float((d * d).sum()) - g1["sse"]) <= RTOL * g1["sse"]
+    assert abs(float(d.abs().sum()) - g1["sae"]) <= RTOL * g1["sae"]
+
+
+def test_quant_error_argument_errors():
+    w = make_weights(4, 1024, seed=730).to(DEV)
+    cb = cb_for(64, 1)
+    for kw in (dict(block=48), dict(opq_T=-1.0), dict(ws=torch.empty(256, dtype=torch.uint8, device=DEV))):
+        args = dict(block=64, opq_T=0.0, ws=None)
+        args.update(kw)
+        with pytest.raises(binding.Bof4Error) as e:
+            binding.bof4_quant_error(w, args["block"], cb, 1, opq_T=args["opq_T"], ws=args["ws"])
+        assert e.value.code in (binding.BOF4_ERR_ARG, binding.BOF4_ERR_WORKSPACE)
+    bad = cb.copy()
+    bad[2] = bad[1]
+    with pytest.raises(binding.Bof4Error):
+        binding.bof4_quant_error(w, 64, bad, 1)
+
+
+def test_quant_error_workload1_full_size():
+    """All 202,375,168 weights of workload 1, block 64, signed constants, OPQ q = 0.95, against the oracle."""
+    w = inputs.flatten(inputs.llama7b_block(seed=60, device=DEV))
+    cb = cb_for(64, 1)
+    T = oracle.opq_threshold(0.95, 64)
+    g = binding.bof4_quant_error(w, 64, cb, 1, opq_T=T)
+    st, o = oracle.quant_error(inputs.bits(w.cpu()), 64, cb, 1, T)
+    assert st == oracle.OK and o["n"] == 202375168
+    assert_error_close(g, o)
