@@ -221,6 +221,21 @@ def main():
                                     out=mae_rec)
     torch.cuda.synchronize()
     t_mae = (time.perf_counter() - t_mae) / 3
+    # the error pass (MSE / MAE of the tensor against its quantised form; not part of the timed step)
+    err_rec, _keep4 = binding.pinned_error_stats()
+    err_ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for e in err_ev:
+        e.record()
+    binding.bof4_quant_error(ws_list[0], BLOCK, cb, 1, opq_T=T, ws=ws, out=err_rec)
+    torch.cuda.synchronize()
+    t_err = time.perf_counter()
+    for r in range(3):
+        if r == 2:
+            binding.bof4_time_next_call(err_ev[0], err_ev[1])
+        err = binding.bof4_quant_error(ws_list[r % len(ws_list)], BLOCK, cb, 1, opq_T=T, ws=ws, out=err_rec)
+    torch.cuda.synchronize()
+    t_err = (time.perf_counter() - t_err) / 3
+    k_err = err_ev[0].elapsed_time(err_ev[1])
     gemv = gemv_block_pass(ws_list[0], cb, T if args.opq else 0.0, dev)
     # one plain device copy of known size (2 * n bytes read, 2 * n written), outside the timed region: the reference
     # against which a counter profile of this same command scales FETCH_SIZE / WRITE_SIZE
@@ -261,6 +276,11 @@ def main():
         "mae_step": {"call_ms": t_mae * 1e3, "weights_per_s": n / t_mae,
                      "note": "bof4_lloyd_step_mae (exact weighted medians of the 14 free levels, three passes over the weights), outside the "
                              "timed step"},
+        "quant_error": {"call_ms": t_err * 1e3, "kernel_ms": k_err, "GBps_algorithmic": 2.0 * n / (k_err * 1e-3) / 1e9,
+                        "hbm_frac": 2.0 * n / (k_err * 1e-3) / 1e9 / HBM_PEAK_GBS, "mse": err["sse"] / err["n"],
+                        "mae": err["sae"] / err["n"],
+                        "note": "bof4_quant_error (quantise, decode and compare in registers: 2 bytes per weight), outside "
+                                "the timed step"},
         "gemv_block_pass": gemv,
         "per_call": per_call,
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
