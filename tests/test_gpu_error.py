@@ -110,3 +110,26 @@ def test_quant_error_workload1_full_size():
     st, o = oracle.quant_error(inputs.bits(w.cpu()), 64, cb, 1, T)
     assert st == oracle.OK and o["n"] == 202375168
     assert_error_close(g, o)
+
+
+def test_error_against_block_size_on_gaussian_weights_as_in_the_papers_figure():
+    """Section 5, the error-against-block-size figure: 2^25 samples of N(0, 1), I = 32 ... 256.  Both errors grow with
+    the block size, signed normalisation stays below absolute normalisation, and every point equals the oracle's."""
+    n = 1 << 25
+    w = inputs.gaussian_blocks(n // 256, 256, seed=90, device=DEV).reshape(-1)
+    wb = inputs.bits(w.cpu())
+    prev = None
+    for block in (32, 64, 128, 256):
+        cb_s = codebooks.array(codebooks.BOF4S_MSE[block])
+        cb_u = codebooks.array(codebooks.BOF4_MSE_64)  # the paper prints the absolute-normalisation codebook for I = 64
+        g_s = binding.bof4_quant_error(w, block, cb_s, 1)
+        g_u = binding.bof4_quant_error(w, block, cb_u, 0)
+        st, o_s = oracle.quant_error(wb, block, cb_s, 1)
+        assert st == oracle.OK
+        assert_error_close(g_s, o_s)
+        mse_s, mae_s = g_s["sse"] / n, g_s["sae"] / n
+        mse_u, mae_u = g_u["sse"] / n, g_u["sae"] / n
+        assert mse_s < mse_u and mae_s < mae_u
+        if prev is not None:
+            assert mse_s > prev[0] and mae_s > prev[1] and mse_u > prev[2] and mae_u > prev[3]
+        prev = (mse_s, mae_s, mse_u, mae_u)
