@@ -28,24 +28,28 @@ from paper_2505_06653_amd import binding, codebooks, inputs  # noqa: E402
 HBM_PEAK_GBS = 8000.0
 BLOCK = 64
 # measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this command (see profiles/), bytes per launch
-PROFILED_TRAFFIC_BYTES = {"lloyd_step": 405.4e6, "quantize": 529.5e6, "dequantize": 526.2e6}
+PROFILED_TRAFFIC_BYTES = {"lloyd_step": 405.4e6, "quantize": 530.1e6, "dequantize": 526.2e6}
 
 
-def gemv_block_pass(w_flat, cb, T, dev, passes=20):
-    """The decoder in use (not part of the timed step): one token through the quantised matrices of the block,
-    y = W~ x per matrix with bof4_gemv, outliers included.  Projections that read the same input are one matrix, as
-    an inference engine stores them (q, k, v are adjacent in the flat block, and so are gate and up).  Returns the
-    time of one pass over the block and the rate on the algorithmic bytes (codes, constants, 8 bytes per outlier
-    table entry)."""
+def gemv_block_pass(codes, scales, oidx, oval, k_all, cb, dev, passes=20):
+    """The decoder in use (not part of the timed step): one token through the quantised matrices of the block, as the
+    last benchmark step left them (codes, constants and the outlier list of the flat tensor), y = W~ x per matrix with
+    bof4_gemv, outliers included.  Projections that read the same input are one matrix, as an inference engine
+    stores them (q, k, v are adjacent in the flat block, and so are gate and up).  Returns the time of one pass over
+    the block and the rate on the algorithmic bytes (codes, constants, 8 bytes per outlier table entry)."""
     mats, off = [], 0
+    idx_all = oidx[:k_all]
     for name, r, c in (("qkv", 3 * 4096, 4096), ("o", 4096, 4096), ("gate_up", 2 * 11008, 4096), ("down", 4096, 11008)):
-        w = w_flat[off:off + r * c]
-        off += r * c
-        codes, scales, oi, ov, k = binding.bof4_quantize(w, BLOCK, cb, 1, opq_T=T, out_capacity=(r * c) // 50 if T else 0)
-        tab = binding.bof4_gemv_outlier_table(codes, scales, r, c, BLOCK, cb, oi, ov, n_outliers=k) if k else None
+        nw = r * c
+        a, b = (int(v) for v in torch.searchsorted(idx_all, torch.tensor([off, off + nw], device=dev)))
+        k = b - a
+        mc, ms = codes[off // 2:(off + nw) // 2], scales[off // BLOCK:(off + nw) // BLOCK]
+        tab = binding.bof4_gemv_outlier_table(mc, ms, r, c, BLOCK, cb, (idx_all[a:b] - off).contiguous(),
+                                              oval[a:b].contiguous(), n_outliers=k) if k else None
+        off += nw
         x = torch.randn((1, c), device=dev).to(torch.bfloat16)
         y = torch.empty((1, r), dtype=torch.float32, device=dev)
-        mats.append((name, r, c, codes, scales, tab, k, x, y))
+        mats.append((name, r, c, mc, ms, tab, k, x, y))
     def one_pass():
         for name, r, c, codes, scales, tab, k, x, y in mats:
             binding.bof4_gemv(codes, scales, r, c, BLOCK, cb, x, tab, k, out=y)
@@ -236,7 +240,7 @@ def main():
     torch.cuda.synchronize()
     t_err = (time.perf_counter() - t_err) / 3
     k_err = err_ev[0].elapsed_time(err_ev[1])
-    gemv = gemv_block_pass(ws_list[0], cb, T if args.opq else 0.0, dev)
+    gemv = gemv_block_pass(codes, scales, oidx, oval, n_out_seen, cb, dev)
     # one plain device copy of known size (2 * n bytes read, 2 * n written), outside the timed region: the reference
     # against which a counter profile of this same command scales FETCH_SIZE / WRITE_SIZE
     deq.copy_(ws_list[0])
