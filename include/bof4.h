@@ -4,7 +4,8 @@
  *
  * Conventions
  *   - "dev" pointers are device (HBM) addresses owned by the caller; "host" pointers are ordinary host memory.
- *     The library keeps no state between calls, allocates nothing and frees nothing.
+ *     The library allocates nothing and frees nothing, and keeps no state between calls beyond constants it works out
+ *     once (device properties, table layouts).
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Work is enqueued on it; a call that
  *     returns results to host memory waits for them before returning (how is stated per call).
  *   - Weights are bfloat16 bit patterns, flat; block b is elements [b*block, (b+1)*block).  `block` must be

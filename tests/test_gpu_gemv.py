@@ -77,8 +77,11 @@ def test_gemv_parity(block, opq, n_tokens):
     check(cb, codes, scales, oi if opq else None, ov if opq else None, rows, cols, block, rand_x(n_tokens, cols, 7))
 
 
-@pytest.mark.parametrize("rows,cols", [(1, 32), (3, 64), (130, 6144), (65, 4096 + 2048 + 1024)])
+@pytest.mark.parametrize("rows,cols", [(1, 32), (3, 64), (130, 6144), (65, 4096 + 2048 + 1024), (21, 20480 + 512),
+                                       (9, 32768)])
 def test_gemv_shapes(rows, cols):
+    """Up to eight strips of 2048 columns a workgroup has one wave per strip; wider matrices (the last two: 11 and 16
+    strips) make a wave take several strips in turn."""
     cb, codes, scales, oi, ov = quantized(rows, cols, 32, 0, 1, seed=31 + rows)
     check(cb, codes, scales, oi, ov, rows, cols, 32, rand_x(2, cols, 11))
 
@@ -203,10 +206,10 @@ def test_gemv_argument_errors():
         binding.bof4_gemv(cd, sd, rows, cols, block, bad_cb, x)
 
 
-@pytest.mark.parametrize("rows,cols", [(4096, 4096), (4096, 11008), (11008, 4096)])
-def test_gemv_llama7b_matrices_with_opq(rows, cols):
-    """The three matrix shapes of workload 1 at full size, signed constants, block 64, OPQ q = 0.95, two tokens: every
-    output against the oracle."""
+@pytest.mark.parametrize("rows,cols", [(4096, 4096), (4096, 11008), (11008, 4096), (8192, 28672)])
+def test_gemv_llama_matrices_with_opq(rows, cols):
+    """The three matrix shapes of workload 1 and the widest one of workload 4 at full size, signed constants, block 64,
+    OPQ q = 0.95, two tokens: every output against the oracle."""
     wm = inputs.student_t_matrix(rows, cols, 5.0, 0.02, 0.3, seed=rows + cols)
     cb = cb_for(64, 1)
     T = oracle.opq_threshold(0.95, 64)
