@@ -100,7 +100,7 @@ __global__ __launch_bounds__(64 * GEMV_MAX_WAVES, 4) void gemv_kernel(const uint
                                                     const uint32_t* __restrict__ strip_ptr,
                                                     const uint2* __restrict__ entries, uint32_t n_out,
                                                     const uint16_t* __restrict__ x, float* __restrict__ y) {
-    constexpr uint32_t U = (T == 1 && !OUTLIERS) ? 4 : 2;
+    constexpr uint32_t U = T == 2 ? 1 : (OUTLIERS ? 2 : 4);  // measured best for each variant
     struct Shared {  // one object, so that the table sits at LDS offset 0 (reachable by an immediate offset)
         float tab[16];
         float part[GEMV_MAX_WAVES * GEMV_MAX_RC * T];
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(64 * GEMV_MAX_WAVES, 4) void gemv_kernel(const uint
             c[t] = fmaf(__uint_as_float(e.y),
                         bf16_bits_to_f32(x_lds[((uint32_t)t * n_waves + wave) * GEMV_STRIP + col]), c[t]);
     };
-    struct Group {  // U rows in flight: codes, block constants, and the rows' first 64 list entries
+    struct Group {  // U rows at a time: codes, block constants, and the rows' first 64 list entries
         uint4 q[U];
         float m[U];
         uint32_t pa[U], pb[U];
@@ -203,8 +203,6 @@ __global__ __launch_bounds__(64 * GEMV_MAX_WAVES, 4) void gemv_kernel(const uint
             for (int t = 0; t < T; ++t) c[t] = 0.0f;
             if (OUTLIERS) {
                 correction(g.oe[u], c);  // no entry: delta 0 (a non-finite x makes every row non-finite anyway)
-                for (uint32_t k = g.pa[u] + 64 + lane; k < g.pb[u]; k += 64)  // over 64 entries in one row and strip
-                    correction(entries[k], c);
             }
 #pragma unroll
             for (int t = 0; t < T; ++t) {
@@ -216,25 +214,31 @@ __global__ __launch_bounds__(64 * GEMV_MAX_WAVES, 4) void gemv_kernel(const uint
             }
         }
     };
-    if (T == 1 && OUTLIERS) {
-        // two buffers: the loads of the next U rows (list entries included) are in flight while the current ones are
-        // decoded.  Measured: worth 10-35 % with a list; without one the extra registers cost more than they gain.
-        Group A, B;
-        issue(r0, A);
-        for (uint32_t r = r0; r < r1; r += 2 * U) {
-            const bool second = r + U < r1;  // wave-uniform
-            if (second) issue(r + U, B);
-            compute(r, A);
-            if (second) {
-                if (r + 2 * U < r1) issue(r + 2 * U, A);
-                compute(r + U, B);
+    // No second buffer of rows in flight: it was tried (with and without a list) and the registers it takes cost more
+    // occupancy than the overlap gains; other waves cover the loads.
+    for (uint32_t r = r0; r < r1; r += U) {
+        Group g;
+        issue(r, g);
+        compute(r, g);
+    }
+    if (OUTLIERS) {
+        // Rows with more than 64 list entries inside this strip: the loop above took the first 64 (one per lane); the
+        // rest is added here, outside the hot loop (a loop of unknown length inside it cost 30 registers).
+        unsigned long long many = __builtin_amdgcn_ballot_w64(lane < r1 - r0 && p_hi > p_lo && p_hi - p_lo > 64u);
+        while (many != 0ull) {  // wave-uniform
+            const uint32_t j = (uint32_t)__builtin_ctzll(many);
+            many &= many - 1ull;
+            const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)p_lo, (int)j) + 64u;
+            const uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)p_hi, (int)j);
+            float c[T];
+#pragma unroll
+            for (int t = 0; t < T; ++t) c[t] = 0.0f;
+            for (uint32_t k = a + lane; k < b; k += 64) correction(entries[k], c);
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const float s = wave_sum_lane63(c[t]);
+                if (lane == 63) sh.part[(wave * rc + j) * T + t] += s;
             }
-        }
-    } else {
-        for (uint32_t r = r0; r < r1; r += U) {
-            Group A;
-            issue(r, A);
-            compute(r, A);
         }
     }
     }  // strips of this wave
