@@ -278,7 +278,7 @@ def main():
                    "n_weights": n, "block": BLOCK, "outlier_fraction": rho, "replicas": len(ws_list)},
         "lloyd_weights_per_s": n / (kms["lloyd_step"] * 1e-3),
         "mae_step": {"call_ms": t_mae * 1e3, "weights_per_s": n / t_mae,
-                     "note": "bof4_lloyd_step_mae (exact weighted medians of the 14 free levels, three passes over the weights), outside the "
+                     "note": "bof4_lloyd_step_mae (exact weighted medians of the 14 free levels: two passes over the weights, one over a candidate list), outside the "
                              "timed step"},
         "quant_error": {"call_ms": t_err * 1e3, "kernel_ms": k_err, "GBps_algorithmic": 2.0 * n / (k_err * 1e-3) / 1e9,
                         "hbm_frac": 2.0 * n / (k_err * 1e-3) / 1e9 / HBM_PEAK_GBS, "mse": err["sse"] / err["n"],

@@ -103,12 +103,14 @@ typedef struct {
  * The expectation pass for the MAE criterion (section 3.2 eq. 7-8, appendix B.4).  Normalisation, assignment and OPQ
  * as in bof4_lloyd_step; per region the exact weighted median of the normalised weights (weights: the absolute block
  * maximum as stored in binary16, for absolute and signed normalisation alike) is found by a radix search that reads
- * the weights three or four times.  The appendix's closing formula names the element before the weighted median;
+ * the weights twice and then a list of the few elements still in question (in the workspace: n / 4 bytes; if the list
+ * runs full - a tensor of equal numbers - or outliers must be tracked through the region around zero, the weights are
+ * read three or four times instead).  The appendix's closing formula names the element before the weighted median;
  * what is returned is the minimiser that its derivation arrives at.  Weights are added as exact 64-bit integers, which
  * needs sum over all weights of |block constant| < 2^38 (BOF4_ERR_ARG otherwise).
  *   skip_mask   bit l set: the median of region l is not wanted (a pinned level) and is reported as NaN; cnt and den
- *               of the region are still returned.  The region that contains zero needs a fourth pass over the
- *               weights, so skipping it (it is pinned in every BOF4 codebook) saves a quarter of the time
+ *               of the region are still returned.  The region that contains zero needs a fourth pass, so skipping it
+ *               (it is pinned in every BOF4 codebook) saves time
  * Other arguments, workspace and the hand-over of the result as for bof4_lloyd_step.  Medians, counts and den are
  * bit-reproducible.
  */

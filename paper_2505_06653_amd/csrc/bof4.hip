@@ -232,10 +232,16 @@ hipError_t wait_for_flag(hipStream_t s, const uint64_t* flag_host) {
 }
 size_t lloyd_ws_bytes() { return ((size_t)SEG_GRID + 1) * LLOYD_PART * 8; }
 // MAE step: histogram, search state, per-wave counts, per-workgroup floating-point partials, result record.
+// Entries of the candidate list of the MAE step: n / 32 (about five times what a pass leaves), at most 2^27; dealt
+// out evenly to the waves of the pass kernels.
+uint64_t mae_cand_entries(uint64_t n) {
+    const uint64_t e = n / 32;
+    return e < (1ull << 27) ? e : (1ull << 27);
+}
 struct MaeWsLayout {
-    size_t hist, state, cnt_part, sae_part, record, total;
+    size_t hist, state, cnt_part, sae_part, record, cand_count, cand_full, cand, total;
 };
-MaeWsLayout mae_ws_layout() {
+MaeWsLayout mae_ws_layout(uint64_t n) {
     MaeWsLayout L;
     size_t o = 0;
     L.hist = o;     o += 16 * 256 * 8;
@@ -243,6 +249,9 @@ MaeWsLayout mae_ws_layout() {
     L.cnt_part = o; o += align_up((size_t)17 * SEG_GRID * WAVES_PER_WG * 8, 256);
     L.sae_part = o; o += align_up((size_t)SEG_GRID * 2 * 8, 256);
     L.record = o;   o += align_up(MAE_REC * 8, 256);
+    L.cand_count = o; o += align_up((size_t)SEG_GRID * WAVES_PER_WG * 4, 256);
+    L.cand_full = o;  o += 256;
+    L.cand = o;       o += align_up(mae_cand_entries(n) * 8, 256);
     L.total = o;
     return L;
 }
@@ -603,7 +612,7 @@ int bof4_last_hip_error(void) { return g_hip_err; }
 size_t bof4_workspace_bytes(uint64_t n, uint32_t block, uint64_t out_capacity) {
     if (!valid_block(block) || n == 0 || n % block != 0) return 0;
     size_t q = quant_ws_bytes(n, out_capacity);
-    const size_t l = lloyd_ws_bytes(), m = mae_ws_layout().total;
+    const size_t l = lloyd_ws_bytes(), m = mae_ws_layout(n).total;
     if (l > q) q = l;
     return m > q ? m : q;
 }
@@ -1083,7 +1092,7 @@ int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const dou
     if (!(opq_T >= 0.0) || !std::isfinite(opq_T)) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: opq_T must be finite and >= 0");
     if (!aligned(w_dev, 16)) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: misaligned pointer");
     if (!ws_dev || !aligned(ws_dev, 256)) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: workspace null or misaligned");
-    const MaeWsLayout ML = mae_ws_layout();
+    const MaeWsLayout ML = mae_ws_layout(n);
     if (ws_bytes < ML.total) return fail(BOF4_ERR_WORKSPACE, "bof4_lloyd_step_mae: workspace too small");
     static_assert(sizeof(bof4_mae_stats) == MAE_REC * 8, "result record and bof4_mae_stats must match");
     hipStream_t s = (hipStream_t)stream;
@@ -1121,19 +1130,38 @@ int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const dou
     const uint4* w = (const uint4*)w_dev;
     double* direct = (double*)device_view_of_host(out_host);
     if (direct) out_host->n_used = FLAG_PENDING;  // the word the last kernel writes last
+    // The candidate list: written by the second pass, read by the passes after it.  Not used when there is no third
+    // pass, when a wave's stretch would be tiny, or when zeroed outliers run through the search of the region around
+    // zero (they are taken out again by a negative weight, which an entry cannot carry).
+    uint32_t* cand_count = (uint32_t*)(base + ML.cand_count);
+    uint32_t* cand_full = (uint32_t*)(base + ML.cand_full);
+    unsigned long long* cand = (unsigned long long*)(base + ML.cand);
+    const uint32_t cand_waves = sgrid * WAVES_PER_WG;
+    const uint32_t cand_cap = (uint32_t)(mae_cand_entries(n) / cand_waves);
+    const bool zero_region_searched = !((skip_mask >> bt.code_of_zero) & 1u);
+    const bool use_list = passes >= 3 && cand_cap >= 8 && !(opq && zero_region_searched);
     hipLaunchKernelGGL(mae_init_kernel, dim3(16), dim3(256), 0, s, lc, state, hist);
     for (uint32_t p = 0; p < passes; ++p) {
         const bool first = p == 0;
+        const bool writes_list = use_list && p == 1, reads_list = use_list && p >= 2;
+        unsigned long long* cand_w = writes_list ? cand : nullptr;
+        const uint32_t* gate = reads_list ? cand_full : nullptr;  // the scan only runs if the list ran full
         if (first) timing_begin(s);
+        if (reads_list)
+            hipLaunchKernelGGL(mae_list_kernel, dim3(sgrid), dim3(256), 0, s, cand, cand_count, cand_cap, cand_full,
+                               state, hist);
 #define BOF4_LAUNCH_MAE(II, FIRST_)                                                                                   \
     if (bt.fast && opq) hipLaunchKernelGGL((mae_pass_kernel<II, true, true, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,  \
-                                           n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part);      \
+                                           n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part, cand_w, \
+                                           cand_count, cand_cap, gate);                                             \
     else if (bt.fast) hipLaunchKernelGGL((mae_pass_kernel<II, true, false, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,   \
-                                         n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part);        \
+                                         n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part, cand_w,   \
+                                         cand_count, cand_cap, gate);                                               \
     else if (opq) hipLaunchKernelGGL((mae_pass_kernel<II, false, true, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,       \
-                                     n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part);            \
+                                     n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part, cand_w,       \
+                                     cand_count, cand_cap, gate);                                                   \
     else hipLaunchKernelGGL((mae_pass_kernel<II, false, false, FIRST_>), dim3(sgrid), dim3(256), 0, s, w, n_seg, cb,    \
-                            bt, signed_norm, T2, state, hist, cnt_part, sae_part);
+                            bt, signed_norm, T2, state, hist, cnt_part, sae_part, cand_w, cand_count, cand_cap, gate);
 #define BOF4_LAUNCH_MAE_BLOCK(FIRST_)                \
     switch (block) {                                 \
         case 32: BOF4_LAUNCH_MAE(32, FIRST_) break;   \
@@ -1150,7 +1178,9 @@ int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const dou
 #undef BOF4_LAUNCH_MAE
         if (first) timing_end(s);
         hipLaunchKernelGGL(mae_select_kernel, dim3(1), dim3(1024), 0, s, state, hist, cnt_part, sae_part, sgrid,
-                           first ? 1 : 0, p + 1 == passes ? 1 : 0, (uint32_t)skip_mask, direct ? direct : rec_dev);
+                           first ? 1 : 0, p + 1 == passes ? 1 : 0, (uint32_t)skip_mask,
+                           writes_list ? cand_count : (const uint32_t*)nullptr, cand_waves, cand_cap, cand_full,
+                           direct ? direct : rec_dev);
     }
     HIP_TRY(hipGetLastError());
     if (direct) {

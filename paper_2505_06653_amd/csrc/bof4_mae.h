@@ -9,6 +9,10 @@
 // region's total.  Three passes settle an ordinary region, four the one that contains zero (its keys span both
 // signs).  Weights are exact integers, |block constant| * 2^24 (the constant is a binary16 number), added in 64
 // bits; additions of integers commute, so the result does not depend on the order of the atomics.
+// The second pass also writes every element that agrees with the first digit of its region (about one in 200) to a
+// list - key, region and block constant in 8 bytes - and the passes after it read that list instead of the weights.
+// Every wave appends to a region of its own; if one of them runs full (a tensor of equal numbers), the later passes
+// scan the weights as before.
 //
 // What is computed is "the smallest x_k with 2 * sum_{x_j <= x_k} a_j >= sum_j a_j" - the lower weighted median,
 // which minimises sum a_j |x_j - c|.  (The closing formula of appendix B.4 names the element before it; its own
@@ -68,8 +72,14 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
                                                            const MaeLevelState* __restrict__ state,
                                                            unsigned long long* __restrict__ hist_g,
                                                            unsigned long long* __restrict__ cnt_part,
-                                                           double* __restrict__ sae_part) {
+                                                           double* __restrict__ sae_part,
+                                                           unsigned long long* __restrict__ cand,
+                                                           uint32_t* __restrict__ cand_count, uint32_t cand_cap,
+                                                           const uint32_t* __restrict__ gate) {
     using C = SegCfg<I>;
+    // `gate`: this launch only matters if the word it points to is set (the scan that stands in for a list that ran
+    // full).  `cand`: append the elements that still count to this wave's stretch of the list.
+    if (gate != nullptr && *gate == 0u) return;
     struct Shared {  // one object, so that the table sits at LDS offset 0 (reachable by an immediate offset)
         uint2 tab[40];
         uint4 info[16];    // per region: klo, (lo | hi << 8 | digit mask << 16), then prefix and active flag -
@@ -112,6 +122,8 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
     const uint32_t key0 = order_key(0.0f);
     double sae = 0.0, w_est = 0.0;
     uint32_t kout = 0, tiles_since_flush = 0;
+    uint32_t wave_cand = 0;  // entries this wave has appended to the list (wave-uniform; may pass the capacity)
+    uint2* my_cand = reinterpret_cast<uint2*>(cand) + gw * cand_cap;  // this wave's stretch of the list
     // The 16-bit lane counters are added up over the wave before they can overflow; lane l < 16 keeps the wave's count
     // of region l.  (Every wave adding its counts to 17 shared words at the end of the kernel cost more than the pass.)
     unsigned long long wave_cnt = 0ull;
@@ -155,6 +167,7 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
         // |block constant| in units of 2^-24; a constant beyond binary16 (infinite) carries no weight
         const unsigned long long W = (a < 65536.0f) ? (unsigned long long)((double)a * 16777216.0) : 0ull;
         const bool fast = FAST && __builtin_amdgcn_ballot_w64(!maxabs_is_ordinary(maxabs)) == 0;
+        const uint32_t m15_shifted = (f32_to_f16_bits(a) & 0x7fffu) << 4;
         if (active) {
             const BlockDiv dv = make_block_div(m_eff);
             double dsum = 0.0;
@@ -185,11 +198,12 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
                 uint4 inf[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) inf[e] = sh.info[code[e]];
-                uint32_t bin[8];
+                uint32_t bin[8], subk[8];
                 bool counts[8], any = false;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const uint32_t sub = order_key(x[e]) - inf[e].x;
+                    subk[e] = sub;
                     const uint32_t lo = inf[e].y & 0xffu, hi = (inf[e].y >> 8) & 0xffu, dmask = inf[e].y >> 16;
                     counts[e] = FIRST ? (hi != 0u && (sub >> hi) == 0u) : (inf[e].w != 0u && (sub >> hi) == inf[e].z);
                     bin[e] = code[e] * 256 + ((sub >> lo) & dmask);
@@ -207,8 +221,18 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
                     }
                 } else if (__builtin_amdgcn_ballot_w64(any) != 0) {  // later passes: one weight in 256 still counts
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
+                    for (int e = 0; e < 8; ++e) {
+                        const unsigned long long who = __builtin_amdgcn_ballot_w64(counts[e]);
+                        if (who == 0ull) continue;  // wave-uniform: three times out of four nobody's element e counts
                         if (counts[e]) atomicAdd(&sh.hist[bin[e]], W);
+                        if (cand != nullptr) {  // wave-uniform
+                            const uint32_t pos = wave_cand + __builtin_amdgcn_mbcnt_hi(
+                                (uint32_t)(who >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)who, 0u));
+                            if (counts[e] && pos < cand_cap)  // entry: key | region << 32 | constant << 36
+                                my_cand[pos] = make_uint2(subk[e], code[e] | m15_shifted);
+                            wave_cand += (uint32_t)__builtin_popcountll(who);
+                        }
+                    }
                 }
             }
             if (OPQ && k_out != 0u) {
@@ -263,10 +287,49 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
             sae_part[2 * blockIdx.x + 1] = s1;
         }
     }
+    if (cand != nullptr && lane == 0) cand_count[gw] = wave_cand;
     __syncthreads();
     // 64-bit integer atomics: exact and order-free (measured: no slower than writing per-workgroup partials)
     for (uint32_t i = tid; i < 16 * 256; i += 256) {
         const unsigned long long v = sh.hist[i];
+        if (v != 0ull) atomicAdd(&hist_g[i], v);
+    }
+}
+
+// A pass over the list instead of the weights: every wave reads the stretch the wave of the same number wrote.  Does
+// nothing when the list ran full (*full != 0: the gated scan of the weights runs instead).
+__global__ __launch_bounds__(256) void mae_list_kernel(const unsigned long long* __restrict__ cand,
+                                                       const uint32_t* __restrict__ cand_count, uint32_t cand_cap,
+                                                       const uint32_t* __restrict__ full,
+                                                       const MaeLevelState* __restrict__ state,
+                                                       unsigned long long* __restrict__ hist_g) {
+    if (*full != 0u) return;
+    __shared__ uint4 info[16];
+    __shared__ unsigned long long hist[16 * 256];
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < 16) {
+        const MaeLevelState s = state[tid];
+        const uint32_t hi = s.hi, lo = hi > 8 ? hi - 8 : 0;
+        info[tid] = make_uint4(lo, hi, s.prefix, (hi != 0 && s.total != 0ull && s.pad == 0u) ? 1u : 0u);
+    }
+    for (uint32_t i = tid; i < 16 * 256; i += 256) hist[i] = 0ull;
+    __syncthreads();
+    const uint64_t gw = (uint64_t)blockIdx.x * WAVES_PER_WG + wave;
+    const uint32_t count = cand_count[gw];  // at most cand_cap, or the list would count as full
+    const unsigned long long* mine = cand + gw * cand_cap;
+    for (uint32_t i = lane; i < count; i += 64) {
+        const unsigned long long e = mine[i];
+        const uint32_t sub = (uint32_t)e, l = (uint32_t)(e >> 32) & 15u, m15 = (uint32_t)(e >> 36) & 0x7fffu;
+        const uint4 inf = info[l];
+        if (inf.w != 0u && (sub >> inf.y) == inf.z) {
+            const float a = f16_bits_to_f32(m15);
+            const unsigned long long W = (a < 65536.0f) ? (unsigned long long)((double)a * 16777216.0) : 0ull;
+            atomicAdd(&hist[l * 256 + ((sub >> inf.x) & ((1u << (inf.y - inf.x)) - 1u))], W);
+        }
+    }
+    __syncthreads();
+    for (uint32_t i = tid; i < 16 * 256; i += 256) {
+        const unsigned long long v = hist[i];
         if (v != 0ull) atomicAdd(&hist_g[i], v);
     }
 }
@@ -280,8 +343,17 @@ __global__ __launch_bounds__(1024) void mae_select_kernel(MaeLevelState* __restr
                                                           const unsigned long long* __restrict__ cnt_part,
                                                           const double* __restrict__ sae_part, uint32_t n_part,
                                                           int first, int last, uint32_t skip_mask,
+                                                          const uint32_t* __restrict__ cand_count,
+                                                          uint32_t cand_waves, uint32_t cand_cap,
+                                                          uint32_t* __restrict__ cand_full,
                                                           double* __restrict__ out) {
     const uint32_t lane = threadIdx.x & 63, l = threadIdx.x >> 6;  // wave l = region l
+    if (cand_count != nullptr) {  // after the pass that wrote the list: did every wave's stretch hold its entries?
+        uint32_t over = 0;
+        for (uint32_t i = threadIdx.x; i < cand_waves; i += 1024) over |= cand_count[i] > cand_cap ? 1u : 0u;
+        const int any = __syncthreads_or((int)over);
+        if (threadIdx.x == 0) *cand_full = any ? 1u : 0u;
+    }
     MaeLevelState s = state[l];
     unsigned long long b[4], sum = 0ull;
 #pragma unroll
@@ -350,11 +422,23 @@ __global__ __launch_bounds__(1024) void mae_select_kernel(MaeLevelState* __restr
         if (l == 15) cnt[16] = k_out;
     }
     __syncthreads();
+    // the floating-point partials in a fixed order: lane i of wave 0 adds records 8 i .. 8 i + 7, then the 64 sums in order
+    __shared__ double part_sum[64][2];
+    if (l == 0) {
+        double s0 = 0.0, s1 = 0.0;
+        for (uint32_t p = 8 * lane; p < min(8 * lane + 8, n_part); ++p) {
+            s0 += sae_part[2 * p];
+            s1 += sae_part[2 * p + 1];
+        }
+        part_sum[lane][0] = s0;
+        part_sum[lane][1] = s1;
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
         double sae = 0.0, w_est = 0.0;
-        for (uint32_t p = 0; p < n_part; ++p) {  // fixed order
-            sae += sae_part[2 * p];
-            w_est += sae_part[2 * p + 1];
+        for (int i = 0; i < 64; ++i) {
+            sae += part_sum[i][0];
+            w_est += part_sum[i][1];
         }
         unsigned long long used = 0ull;
         const bool too_large = !(w_est < 0x1p38);  // 64-bit weight sums need sum |constant| < 2^39 (NaN counts too)
