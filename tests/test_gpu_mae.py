@@ -62,7 +62,8 @@ def test_mae_em_iterations_follow_the_oracle():
 
 def test_mae_degenerate_inputs():
     """All-zero blocks (no weight: NaN medians, counts still right), a constant tensor, many equal values, blocks whose
-    maxima differ by 2^20, and a region that stays empty."""
+    maxima differ by 2^20, and a region that stays empty.  The constant tensor and the one of six values put every
+    element on the list of candidates, which runs full: the passes after it fall back to scanning the weights."""
     cb = mae_cb(64, 1)
     cases = []
     cases.append(torch.zeros(64 * 70, dtype=torch.bfloat16))
@@ -118,14 +119,17 @@ def test_mae_step_refuses_weights_too_large_for_exact_sums():
 
 
 @pytest.mark.parametrize("signed", [0, 1])
-def test_mae_step_skips_pinned_regions(signed):
+@pytest.mark.parametrize("opq", [0, 1])
+def test_mae_step_skips_pinned_regions(signed, opq):
     """With the pinned levels skipped (no fourth pass for the region around zero) the other medians, every count
-    and every mass are unchanged; the skipped medians come back as NaN."""
+    and every mass are unchanged; the skipped medians come back as NaN.  (With OPQ this is the configuration in which
+    the passes after the second read the list of candidates; without the mask and with OPQ they scan the weights.)"""
     w = make_weights(29, 1024, seed=610 + signed)
     cb = mae_cb(64, signed)
     pin = codebooks.PIN_BOF4S if signed else codebooks.PIN_BOF4
-    st, o = oracle.lloyd_step_mae(inputs.bits(w), 64, cb, signed)
-    g = binding.bof4_lloyd_step_mae(w.to(DEV), 64, cb, signed, skip_mask=pin)
+    T = oracle.opq_threshold(0.95, 64) if opq else 0.0
+    st, o = oracle.lloyd_step_mae(inputs.bits(w), 64, cb, signed, opq_T=T)
+    g = binding.bof4_lloyd_step_mae(w.to(DEV), 64, cb, signed, opq_T=T, skip_mask=pin)
     skipped = np.array([(pin >> l) & 1 for l in range(16)], dtype=bool)
     assert np.isnan(g["median"][skipped]).all()
     assert np.array_equal(g["median"][~skipped], o["median"][~skipped])
