@@ -107,3 +107,35 @@ def test_argument_validation_returns_error_codes_without_touching_the_gpu():
     nan_cb[4] = np.nan
     assert L.bof4_thresholds(nan_cb.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
                              (ctypes.c_float * 15)()) == binding.BOF4_ERR_ARG
+
+
+def test_argument_validation_of_the_later_entry_points_without_touching_the_gpu():
+    """bof4_lloyd_step_mae, bof4_quant_error, bof4_gemv and bof4_gemv_outlier_table refuse bad arguments before any
+    GPU call; the table size is a host formula."""
+    L = binding.lib()
+    cbp = CB.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+    bad_cb = CB[::-1].copy()
+    bad_cbp = bad_cb.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+    fake, odd, ws = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004), ctypes.c_void_p(0x10000)
+    ms, es = binding.MaeStats(), binding.ErrorStats()
+    assert L.bof4_lloyd_step_mae(fake, 1000, 64, cbp, 1, 0.0, 0, ctypes.byref(ms), ws, 1 << 30, None) == binding.BOF4_ERR_ARG
+    assert L.bof4_lloyd_step_mae(fake, 1024, 64, bad_cbp, 1, 0.0, 0, ctypes.byref(ms), ws, 1 << 30, None) == binding.BOF4_ERR_ARG
+    assert L.bof4_lloyd_step_mae(fake, 1024, 64, cbp, 1, 0.0, 0, ctypes.byref(ms), ws, 64, None) == binding.BOF4_ERR_WORKSPACE
+    assert L.bof4_quant_error(fake, 1024, 48, cbp, 1, 0.0, ctypes.byref(es), ws, 1 << 30, None) == binding.BOF4_ERR_ARG
+    assert L.bof4_quant_error(fake, 1024, 64, cbp, 1, -2.0, ctypes.byref(es), ws, 1 << 30, None) == binding.BOF4_ERR_ARG
+    assert L.bof4_quant_error(fake, 1024, 64, cbp, 1, 0.0, ctypes.byref(es), ws, 64, None) == binding.BOF4_ERR_WORKSPACE
+    g = lambda codes, rows, cols, blk, c, table, k, x, nt: L.bof4_gemv(codes, fake, rows, cols, blk, c, table, k, x, nt, fake, None)
+    assert g(None, 4, 128, 64, cbp, None, 0, fake, 1) == binding.BOF4_ERR_ARG        # null codes
+    assert g(fake, 4, 96, 64, cbp, None, 0, fake, 1) == binding.BOF4_ERR_ARG         # cols not a multiple of block
+    assert g(fake, 4, 128, 64, cbp, None, 0, fake, 0) == binding.BOF4_ERR_ARG        # no tokens
+    assert g(fake, 4, 128, 64, bad_cbp, None, 0, fake, 1) == binding.BOF4_ERR_ARG    # unsorted codebook
+    assert g(fake, 4, 128, 64, cbp, None, 3, fake, 1) == binding.BOF4_ERR_ARG        # outliers without their table
+    assert g(odd, 4, 128, 64, cbp, None, 0, fake, 1) == binding.BOF4_ERR_ARG         # codes not 16-byte aligned
+    assert g(fake, 4, 32768 + 64, 64, cbp, None, 0, fake, 1) == binding.BOF4_ERR_ARG  # too wide
+    assert b"32768" in L.bof4_last_error()
+    t = lambda rows, cols, k, tab, nbytes: L.bof4_gemv_outlier_table(fake, fake, rows, cols, 64, cbp, fake, fake, k, tab, nbytes, None)
+    need = binding.bof4_gemv_outlier_table_bytes(10, 4096 + 64, 7)
+    assert need == (10 * 3 + 1 + 1) // 2 * 8 + 7 * 8 and binding.bof4_gemv_outlier_table_bytes(0, 64, 0) == 0
+    assert t(10, 4096 + 64, 7, ws, need - 8) == binding.BOF4_ERR_WORKSPACE
+    assert t(10, 4096 + 32, 7, ws, need) == binding.BOF4_ERR_ARG
+    assert t(10, 4096 + 64, 7, None, need) == binding.BOF4_ERR_ARG
