@@ -151,3 +151,56 @@ def test_config4_llama70b_layer(block):
     check_quantize_dequantize(w, block, cb, 1, T, w.numel() // 32)
     st, o = oracle.lloyd_step(host_bits(w), block, cb, 1, opq_T=T)
     assert_stats_close(binding.bof4_lloyd_step(w, block, cb, 1, opq_T=T), o)
+
+
+def test_config2_mae_step_and_error_pass_by_their_defining_properties(workload2):
+    """6.48 G weights are more than the sorting oracle can take, so the MAE step is checked at this size by what
+    defines its results, with plain torch arithmetic block by block: per region the counts and masses, and for every
+    reported median c that twice the weight at or below c reaches the region's total while twice the weight below c
+    does not (weights are exact integers, |constant| * 2^24).  The error pass is checked against the same torch
+    pass (decoded weights from the thresholds and levels)."""
+    w, _ = workload2
+    cb = codebooks.array(codebooks.BOF4S_MAE_64)
+    pin = codebooks.PIN_BOF4S
+    n = w.numel()
+    g = binding.bof4_lloyd_step_mae(w, 64, cb, 1, skip_mask=pin)
+    e = binding.bof4_quant_error(w, 64, cb, 1)
+    assert g["n_used"] == n and g["n_outliers"] == 0 and e["n"] == n
+    thr = torch.tensor(binding.bof4_thresholds(cb), dtype=torch.float32, device=DEV)
+    lv = torch.tensor(cb, dtype=torch.float64, device=DEV).float()
+    med = torch.tensor(np.nan_to_num(g["median"], nan=0.0), dtype=torch.float32, device=DEV)
+    cnt = torch.zeros(16, dtype=torch.int64, device=DEV)
+    mass = torch.zeros(16, dtype=torch.int64, device=DEV)
+    below = torch.zeros(16, dtype=torch.int64, device=DEV)
+    upto = torch.zeros(16, dtype=torch.int64, device=DEV)
+    sse = torch.zeros((), dtype=torch.float64, device=DEV)
+    sae = torch.zeros((), dtype=torch.float64, device=DEV)
+    step = 64 * (1 << 20)
+    for a in range(0, n, step):
+        blk = w[a:a + step].view(-1, 64)
+        mag = blk.view(torch.int16).int() & 0x7fff
+        key = (mag << 6) | (63 - torch.arange(64, device=DEV, dtype=torch.int32))  # largest magnitude, lowest index
+        idx = 63 - (key.max(dim=1).values & 63)
+        m = blk.gather(1, idx[:, None].long()).to(torch.float16).float()           # the stored constant
+        x = torch.where(m != 0, blk.float() / m, torch.zeros_like(m))
+        code = torch.bucketize(x, thr)                                             # number of thresholds below x
+        wt = (m.abs().double() * 16777216.0).long().expand(-1, 64)
+        cnt += torch.bincount(code.reshape(-1), minlength=16)
+        mass.scatter_add_(0, code.reshape(-1), wt.reshape(-1))
+        c = med[code]
+        below.scatter_add_(0, code.reshape(-1), torch.where(x < c, wt, torch.zeros_like(wt)).reshape(-1))
+        upto.scatter_add_(0, code.reshape(-1), torch.where(x <= c, wt, torch.zeros_like(wt)).reshape(-1))
+        d = blk.double() - (m * lv[code]).to(torch.bfloat16).double()
+        sse += (d * d).sum()
+        sae += d.abs().sum()
+        del blk, mag, key, idx, m, x, code, wt, c, d
+    cnt, mass, below, upto = (t.cpu().numpy() for t in (cnt, mass, below, upto))
+    assert np.array_equal(g["cnt"], cnt)
+    assert np.array_equal(g["den"], mass.astype(np.float64) / 16777216.0)
+    for l in range(16):
+        if (pin >> l) & 1:
+            assert np.isnan(g["median"][l])
+        else:
+            assert 2 * upto[l] >= mass[l] > 2 * below[l], l
+    assert abs(e["sse"] - float(sse)) <= 1e-9 * float(sse)
+    assert abs(e["sae"] - float(sae)) <= 1e-9 * float(sae)
