@@ -140,7 +140,7 @@ def main():
                     help="instead of the benchmark step: bof4_gemv on a table of matrix shapes, one JSON line")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build is single-GPU; run with --gpus 1 (sharding is described in DESIGN.md)",
+        print("bench.py: this build is single-GPU; run with --gpus 1 (how the path would shard is part of the design notes)",
               file=sys.stderr)
         sys.exit(2)
     dev = torch.device("cuda:0")
