@@ -136,6 +136,9 @@ def main():
     ap.add_argument("--replicas", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--opq", type=int, default=1, help="0 runs the path without outlier extraction (not the headline)")
+    ap.add_argument("--serial", action="store_true",
+                    help="every call waits for its result before the next is enqueued (default: the Lloyd kernels are "
+                         "enqueued behind the quantiser before the host waits for the outlier count)")
     ap.add_argument("--gemv-shapes", action="store_true",
                     help="instead of the benchmark step: bof4_gemv on a table of matrix shapes, one JSON line")
     args = ap.parse_args()
@@ -162,6 +165,7 @@ def main():
     oval = torch.empty(cap, dtype=torch.float16, device=dev)
     deq = torch.empty(n, dtype=torch.bfloat16, device=dev)
     ws = binding.alloc_workspace(n, BLOCK, cap, dev)
+    ws_lloyd = binding.alloc_workspace(n, BLOCK, 0, dev)  # the Lloyd kernels run between the halves of the quantiser
     stats_rec, _keep1 = binding.pinned_lloyd_stats()   # results land in pinned host memory: no copy
     counter, _keep2 = binding.pinned_counter()
     names = ("quantize", "dequantize", "lloyd_step")
@@ -175,6 +179,7 @@ def main():
     n_out_seen = 0
 
     def step(i, timed_call=None, events=None):
+        """One step, every call waiting for its result before the next is enqueued."""
         nonlocal n_out_seen
         w = ws_list[i % len(ws_list)]
         if events:
@@ -199,12 +204,34 @@ def main():
         binding.bof4_codebook_update(st, codebooks.PIN_BOF4S, cb)
         n_out_seen = k
 
+    def step_pipelined(i, timed_call=None):
+        """The same calls on the same stream, enqueued so that the GPU always has the next kernel waiting: quantiser,
+        Lloyd kernels (they do not depend on the quantiser), then the host collects the outlier count, enqueues the
+        decoder, collects the sums and updates the codebook while the decoder runs."""
+        nonlocal n_out_seen
+        w = ws_list[i % len(ws_list)]
+        if timed_call == 0:
+            binding.bof4_time_next_call(kev[i][0], kev[i][1])
+        flight = binding.bof4_quantize_begin(w, BLOCK, cb, 1, T, cap, codes, scales, oidx, oval, ws, counter)
+        if timed_call == 2:
+            binding.bof4_time_next_call(kev[i][0], kev[i][1])
+        binding.bof4_lloyd_step_begin(w, BLOCK, cb, 1, stats_rec, ws=ws_lloyd)
+        k = flight.finish()
+        if timed_call == 1:
+            binding.bof4_time_next_call(kev[i][0], kev[i][1])
+        binding.bof4_dequantize(codes, scales, n, BLOCK, cb, oidx if k else None, oval if k else None, out=deq,
+                                n_outliers=k)
+        binding.bof4_wait_result(stats_rec)
+        binding.bof4_codebook_update(stats_rec, codebooks.PIN_BOF4S, cb)
+        n_out_seen = k
+
+    timed_step = step if args.serial else step_pipelined
     for i in range(args.warmup):
-        step(i)
+        timed_step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i, timed_call=i % 3)
+        timed_step(i, timed_call=i % 3)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     # per-call times (kernels, helper kernels and host waits of one call), from a few extra steps outside the timed
@@ -275,7 +302,9 @@ def main():
         "config": {"workload": "configs[1]: one Llama-7B-shaped block, 202,375,168 bf16 weights, Student-t(5) std 0.02 "
                                "with log-normal(0,0.3) row scale, block 64, signed absmax (BOF4-S), OPQ q=0.95" + ("" if args.opq else " OFF") + "; "
                                "step = quantize + dequantize + lloyd_step + codebook_update",
-                   "n_weights": n, "block": BLOCK, "outlier_fraction": rho, "replicas": len(ws_list)},
+                   "n_weights": n, "block": BLOCK, "outlier_fraction": rho, "replicas": len(ws_list),
+                   "enqueue_order": "one call after the other, each waiting for its result" if args.serial else
+                                    "quantize kernels, lloyd kernels, outlier count, dequantize, lloyd sums (one stream)"},
         "lloyd_weights_per_s": n / (kms["lloyd_step"] * 1e-3),
         "mae_step": {"call_ms": t_mae * 1e3, "weights_per_s": n / t_mae,
                      "note": "bof4_lloyd_step_mae (exact weighted medians of the 14 free levels: two passes over the weights, one over a candidate list), outside the "

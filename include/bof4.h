@@ -83,6 +83,19 @@ int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double*
                     double opq_T, int weight_by_max2, bof4_lloyd_stats* out_host, void* ws_dev, size_t ws_bytes,
                     void* stream);
 
+/*
+ * The same call in two halves, for a caller that wants to enqueue other work on `stream` before it needs the sums (the
+ * kernels of the next call then run while the host is still waiting for this one).  bof4_lloyd_step_begin takes the
+ * arguments of bof4_lloyd_step, needs out_host in pinned (device-visible) host memory (BOF4_ERR_ARG otherwise),
+ * enqueues and returns; the record is complete once bof4_wait_result(&out_host->n_used, stream) has returned.
+ * bof4_wait_result waits for a result word that the GPU writes last into pinned host memory: &stats->n_used of the
+ * Lloyd and MAE steps, &stats->n of the error pass.
+ */
+int bof4_lloyd_step_begin(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                          double opq_T, int weight_by_max2, bof4_lloyd_stats* out_host, void* ws_dev, size_t ws_bytes,
+                          void* stream);
+int bof4_wait_result(const uint64_t* word_host, void* stream);
+
 /* Maximisation step (section 3.2, eq. 6 and its last paragraph): level l moves to num[l]/den[l] unless bit l of
  * pinned_mask is set or the region is empty (den[l] == 0).  Pure host function; cb_host is updated in place. */
 int bof4_codebook_update(const bof4_lloyd_stats* stats_host, uint16_t pinned_mask, double* cb_host);
@@ -142,6 +155,23 @@ int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* c
                   double opq_T, uint8_t* codes_dev, uint16_t* scales_dev, int64_t* out_idx_dev,
                   uint16_t* out_val_dev, uint64_t out_capacity, uint64_t* n_outliers_host, void* ws_dev,
                   size_t ws_bytes, void* stream);
+
+/*
+ * bof4_quantize in two halves (same arguments both times): bof4_quantize_begin enqueues the kernels and returns;
+ * bof4_quantize_finish waits for the outlier count and completes the call exactly as bof4_quantize would (count in
+ * *n_outliers_host, BOF4_ERR_CAPACITY, the re-run for outliers piled up in one stretch).  With opq_T > 0 the counter
+ * must lie in pinned host memory (BOF4_ERR_ARG otherwise).  Between the two the caller may enqueue other work on
+ * `stream` that does not touch the outputs; nothing that reads codes, constants or the list may be enqueued before
+ * bof4_quantize_finish has returned.
+ */
+int bof4_quantize_begin(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                        double opq_T, uint8_t* codes_dev, uint16_t* scales_dev, int64_t* out_idx_dev,
+                        uint16_t* out_val_dev, uint64_t out_capacity, uint64_t* n_outliers_host, void* ws_dev,
+                        size_t ws_bytes, void* stream);
+int bof4_quantize_finish(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                         double opq_T, uint8_t* codes_dev, uint16_t* scales_dev, int64_t* out_idx_dev,
+                         uint16_t* out_val_dev, uint64_t out_capacity, uint64_t* n_outliers_host, void* ws_dev,
+                         size_t ws_bytes, void* stream);
 
 /*
  * Dequantise (section 2.1 eq. 3): w~ = block constant * level[code] as one binary32 product rounded to

@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(HERE, "libbof4_hip.so")
 BOF4_OK, BOF4_ERR_ARG, BOF4_ERR_CAPACITY, BOF4_ERR_WORKSPACE, BOF4_ERR_HIP = 0, -1, -2, -3, -4
 EXPORTS = ("bof4_workspace_bytes", "bof4_opq_threshold", "bof4_thresholds", "bof4_bin_table", "bof4_lloyd_step",
            "bof4_codebook_update", "bof4_lloyd_step_mae", "bof4_codebook_update_mae", "bof4_quantize",
-           "bof4_dequantize", "bof4_quant_error", "bof4_gemv", "bof4_gemv_outlier_table",
+           "bof4_dequantize", "bof4_quantize_begin", "bof4_quantize_finish", "bof4_lloyd_step_begin", "bof4_wait_result",
+           "bof4_quant_error", "bof4_gemv", "bof4_gemv_outlier_table",
            "bof4_gemv_outlier_table_bytes", "bof4_time_next_call", "bof4_last_error",
            "bof4_last_hip_error")
 
@@ -90,6 +91,13 @@ def lib():
         L.bof4_quantize.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint32, f64p, ctypes.c_int, ctypes.c_double,
                                     vp, vp, vp, vp, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint64), vp,
                                     ctypes.c_size_t, vp]
+        for name in ("bof4_quantize_begin", "bof4_quantize_finish"):
+            getattr(L, name).restype = ctypes.c_int
+            getattr(L, name).argtypes = L.bof4_quantize.argtypes
+        L.bof4_lloyd_step_begin.restype = ctypes.c_int
+        L.bof4_lloyd_step_begin.argtypes = L.bof4_lloyd_step.argtypes
+        L.bof4_wait_result.restype = ctypes.c_int
+        L.bof4_wait_result.argtypes = [vp, vp]
         L.bof4_dequantize.restype = ctypes.c_int
         L.bof4_dequantize.argtypes = [vp, vp, ctypes.c_uint64, ctypes.c_uint32, f64p, vp, vp, ctypes.c_uint64, vp, vp]
         L.bof4_quant_error.restype = ctypes.c_int
@@ -359,6 +367,51 @@ def bof4_quantize(w, block, cb, signed, opq_T=0.0, out_capacity=0, codes=None, s
     k = min(int(nout.value), out_capacity)
     return (codes, scales, None if out_idx is None else out_idx[:k], None if out_val is None else out_val[:k],
             int(nout.value))
+
+
+class QuantizeInFlight:
+    """bof4_quantize_begin has been called with these arguments; finish() waits for the outlier count and returns it."""
+
+    def __init__(self, args, counter, keep):
+        self.args, self.counter, self.keep = args, counter, keep
+
+    def finish(self, allow_overflow=False):
+        code = lib().bof4_quantize_finish(*self.args)
+        _check(code, allow=(BOF4_ERR_CAPACITY,) if allow_overflow else ())
+        return int(self.counter.value)
+
+
+def bof4_quantize_begin(w, block, cb, signed, opq_T, out_capacity, codes, scales, out_idx, out_val, ws, counter,
+                        stream=None):
+    """Enqueues bof4_quantize into caller-owned buffers (counter: from pinned_counter()) and returns a
+    QuantizeInFlight; other work may be enqueued on the stream before its finish() is called."""
+    n = w.numel()
+    cb, cbp = _cb(cb)
+    args = (_ptr(w), n, block, cbp, int(signed), float(opq_T), _ptr(codes), _ptr(scales), _ptr(out_idx),
+            _ptr(out_val), out_capacity, ctypes.byref(counter), _ptr(ws), 0 if ws is None else ws.numel(),
+            _stream(stream))
+    _check(lib().bof4_quantize_begin(*args))
+    return QuantizeInFlight(args, counter, (w, cb, codes, scales, out_idx, out_val, ws))
+
+
+def bof4_lloyd_step_begin(w, block, cb, signed, out, opq_T=0.0, weight_by_max2=True, ws=None, stream=None):
+    """Enqueues bof4_lloyd_step; `out` is a LloydStats in pinned host memory (pinned_lloyd_stats()), complete after
+    bof4_wait_result(out)."""
+    n = w.numel()
+    cb, cbp = _cb(cb)
+    if ws is None:
+        ws = alloc_workspace(n, block, 0, w.device)
+    _check(lib().bof4_lloyd_step_begin(_ptr(w), n, block, cbp, int(signed), float(opq_T), int(bool(weight_by_max2)),
+                                       ctypes.byref(out), _ptr(ws), ws.numel(), _stream(stream)))
+    return out
+
+
+def bof4_wait_result(stats, stream=None):
+    """Waits until the GPU has written the record `stats` (LloydStats / MaeStats: word n_used; ErrorStats: word n)."""
+    field = "n" if isinstance(stats, ErrorStats) else "n_used"
+    addr = ctypes.addressof(stats) + getattr(type(stats), field).offset
+    _check(lib().bof4_wait_result(ctypes.c_void_p(addr), _stream(stream)))
+    return stats
 
 
 def bof4_dequantize(codes, scales, n, block, cb, out_idx=None, out_val=None, out=None, stream=None, n_outliers=None):

@@ -715,8 +715,14 @@ int bof4_codebook_update(const bof4_lloyd_stats* st, uint16_t pinned_mask, doubl
     return BOF4_OK;
 }
 
-int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm, double opq_T,
-                  uint8_t* codes_dev, uint16_t* scales_dev, int64_t* out_idx_dev, uint16_t* out_val_dev,
+}  // extern "C"
+
+namespace {
+// bof4_quantize in two halves.  phase 0: enqueue the kernels and collect the count (the plain call); 1: enqueue only
+// (the count has to go to pinned host memory, where phase 2 finds it); 2: collect only, for the same arguments.
+enum QuantPhase { QUANT_WHOLE = 0, QUANT_ENQUEUE = 1, QUANT_COLLECT = 2 };
+int quantize_impl(int phase, const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                  double opq_T, uint8_t* codes_dev, uint16_t* scales_dev, int64_t* out_idx_dev, uint16_t* out_val_dev,
                   uint64_t out_capacity, uint64_t* n_outliers_host, void* ws_dev, size_t ws_bytes, void* stream) {
     if (!w_dev || !codes_dev || !scales_dev || !n_outliers_host) return fail(BOF4_ERR_ARG, "bof4_quantize: null pointer");
     if (!valid_block(block) || n == 0 || n % block != 0) return fail(BOF4_ERR_ARG, "bof4_quantize: bad n or block");
@@ -756,6 +762,10 @@ int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* c
         os.val = (uint16_t*)(base + SL.val);
         os.region_cap = SL.region_cap;
     }
+    uint64_t* direct = opq ? (uint64_t*)device_view_of_host(n_outliers_host) : nullptr;
+    if (phase != QUANT_WHOLE && opq && !direct)
+        return fail(BOF4_ERR_ARG, "bof4_quantize_begin / _finish: the outlier count must go to pinned host memory");
+    if (phase != QUANT_COLLECT) {
     timing_begin(s);
 #define BOF4_LAUNCH_SEGQ(II)                                                                                           \
     if (bt.fast && opq) hipLaunchKernelGGL((seg_quantize_kernel<II, true, true>), dim3(sgrid), dim3(256), 0, s, wv,    \
@@ -782,11 +792,15 @@ int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* c
 
     // total_dev[0] = count, with bit 63 set if a wave overflowed its staging region.  A caller's counter in pinned
     // host memory receives it straight from the gather kernel.
-    uint64_t* direct = (uint64_t*)device_view_of_host(n_outliers_host);
     *n_outliers_host = direct ? FLAG_PENDING : 0;
     hipLaunchKernelGGL(seg_outlier_gather_kernel, dim3(n_waves), dim3(64), 0, s, os, n_waves, out_idx_dev, out_val_dev,
                        out_capacity, direct ? direct : total_dev);
     HIP_TRY(hipGetLastError());
+    if (phase == QUANT_ENQUEUE) return BOF4_OK;
+    } else if (!opq) {
+        *n_outliers_host = 0;
+        return BOF4_OK;
+    }
     uint64_t head = 0;
     if (direct) {
         HIP_TRY(wait_for_flag(s, n_outliers_host));
@@ -828,6 +842,32 @@ int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* c
     *n_outliers_host = tot;
     if (tot > out_capacity) return fail(BOF4_ERR_CAPACITY, "bof4_quantize: outlier buffers too small");
     return BOF4_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int bof4_quantize(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm, double opq_T,
+                  uint8_t* codes_dev, uint16_t* scales_dev, int64_t* out_idx_dev, uint16_t* out_val_dev,
+                  uint64_t out_capacity, uint64_t* n_outliers_host, void* ws_dev, size_t ws_bytes, void* stream) {
+    return quantize_impl(QUANT_WHOLE, w_dev, n, block, cb_host, signed_norm, opq_T, codes_dev, scales_dev, out_idx_dev,
+                         out_val_dev, out_capacity, n_outliers_host, ws_dev, ws_bytes, stream);
+}
+
+int bof4_quantize_begin(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                        double opq_T, uint8_t* codes_dev, uint16_t* scales_dev, int64_t* out_idx_dev,
+                        uint16_t* out_val_dev, uint64_t out_capacity, uint64_t* n_outliers_host, void* ws_dev,
+                        size_t ws_bytes, void* stream) {
+    return quantize_impl(QUANT_ENQUEUE, w_dev, n, block, cb_host, signed_norm, opq_T, codes_dev, scales_dev,
+                         out_idx_dev, out_val_dev, out_capacity, n_outliers_host, ws_dev, ws_bytes, stream);
+}
+
+int bof4_quantize_finish(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                         double opq_T, uint8_t* codes_dev, uint16_t* scales_dev, int64_t* out_idx_dev,
+                         uint16_t* out_val_dev, uint64_t out_capacity, uint64_t* n_outliers_host, void* ws_dev,
+                         size_t ws_bytes, void* stream) {
+    return quantize_impl(QUANT_COLLECT, w_dev, n, block, cb_host, signed_norm, opq_T, codes_dev, scales_dev,
+                         out_idx_dev, out_val_dev, out_capacity, n_outliers_host, ws_dev, ws_bytes, stream);
 }
 
 int bof4_dequantize(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t n, uint32_t block,
@@ -1011,7 +1051,11 @@ int bof4_gemv(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t row
     return BOF4_OK;
 }
 
-int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+}  // extern "C"
+
+namespace {
+// wait = false: enqueue only; the record must lie in pinned host memory, where bof4_wait_result finds it.
+int lloyd_step_impl(bool wait, const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
                     double opq_T, int weight_by_max2, bof4_lloyd_stats* out_host, void* ws_dev, size_t ws_bytes,
                     void* stream) {
     if (!w_dev || !out_host) return fail(BOF4_ERR_ARG, "bof4_lloyd_step: null pointer");
@@ -1060,10 +1104,13 @@ int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double*
         static_assert(sizeof(bof4_lloyd_stats) == 51 * 8, "result record and bof4_lloyd_stats must match");
         double* rec_dev = partials + (uint64_t)n_part * LLOYD_PART;
         double* direct = (double*)device_view_of_host(out_host);
+        if (!wait && !direct)
+            return fail(BOF4_ERR_ARG, "bof4_lloyd_step_begin: the record must lie in pinned host memory");
         if (direct) out_host->n_used = FLAG_PENDING;  // the word the final kernel writes last
         hipLaunchKernelGGL(seg_lloyd_final_kernel, dim3(1), dim3(1024), 0, s, partials, n_part, cb, bt.code_of_zero,
                            direct ? direct : rec_dev);
         HIP_TRY(hipGetLastError());
+        if (!wait) return BOF4_OK;
         if (direct) {
             HIP_TRY(wait_for_flag(s, &out_host->n_used));
         } else {
@@ -1071,6 +1118,29 @@ int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double*
             HIP_TRY(wait_for_stream(s));
         }
     }
+    return BOF4_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                    double opq_T, int weight_by_max2, bof4_lloyd_stats* out_host, void* ws_dev, size_t ws_bytes,
+                    void* stream) {
+    return lloyd_step_impl(true, w_dev, n, block, cb_host, signed_norm, opq_T, weight_by_max2, out_host, ws_dev,
+                           ws_bytes, stream);
+}
+
+int bof4_lloyd_step_begin(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                          double opq_T, int weight_by_max2, bof4_lloyd_stats* out_host, void* ws_dev, size_t ws_bytes,
+                          void* stream) {
+    return lloyd_step_impl(false, w_dev, n, block, cb_host, signed_norm, opq_T, weight_by_max2, out_host, ws_dev,
+                           ws_bytes, stream);
+}
+
+int bof4_wait_result(const uint64_t* word_host, void* stream) {
+    if (!word_host) return fail(BOF4_ERR_ARG, "bof4_wait_result: null pointer");
+    HIP_TRY(wait_for_flag((hipStream_t)stream, word_host));
     return BOF4_OK;
 }
 

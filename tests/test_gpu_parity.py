@@ -3,6 +3,8 @@ inputs small enough for the oracle yet spanning several tiles and a ragged last 
 
 Bars: codes, scales, outlier lists, dequantised bf16 and Lloyd counts bit-exact; Lloyd sums, updated levels and
 MSE within relative 1e-9 (binary64 sums whose terms are exact products, added in a different order)."""
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -307,3 +309,51 @@ def test_calls_on_a_side_stream(pinned):
         assert np.array_equal(gc.cpu().numpy(), o_codes) and np.array_equal(to_np_u16(gs), o_scales)
         assert np.array_equal(to_np_u16(gd), o_deq)
         assert_stats_close(g_stats, o_stats)
+
+
+def test_calls_in_two_halves_give_the_results_of_the_plain_calls():
+    """bof4_quantize_begin / _finish and bof4_lloyd_step_begin / bof4_wait_result with other work enqueued in between
+    (the order the benchmark uses: quantise, Lloyd step, then the count, the decoder, then the sums) against the
+    plain calls; also the errors of the first halves when their result cannot go to pinned memory."""
+    w = make_weights(48, 1024, seed=77).to(DEV)
+    n = w.numel()
+    cb = cb_for(64, 1)
+    T = oracle.opq_threshold(0.95, 64)
+    cap = n // 16
+    ref_codes, ref_scales, ref_idx, ref_val, ref_k = binding.bof4_quantize(w, 64, cb, 1, opq_T=T, out_capacity=cap)
+    ref_stats = binding.bof4_lloyd_step(w, 64, cb, 1)
+    ref_deq = binding.bof4_dequantize(ref_codes, ref_scales, n, 64, cb, ref_idx, ref_val)
+    codes = torch.empty(n // 2, dtype=torch.uint8, device=DEV)
+    scales = torch.empty(n // 64, dtype=torch.float16, device=DEV)
+    oidx = torch.empty(cap, dtype=torch.int64, device=DEV)
+    oval = torch.empty(cap, dtype=torch.float16, device=DEV)
+    ws_q = binding.alloc_workspace(n, 64, cap, DEV)
+    ws_l = binding.alloc_workspace(n, 64, 0, DEV)
+    counter, keep1 = binding.pinned_counter()
+    rec, keep2 = binding.pinned_lloyd_stats()
+    for _ in range(3):
+        flight = binding.bof4_quantize_begin(w, 64, cb, 1, T, cap, codes, scales, oidx, oval, ws_q, counter)
+        binding.bof4_lloyd_step_begin(w, 64, cb, 1, rec, ws=ws_l)
+        k = flight.finish()
+        deq = binding.bof4_dequantize(codes, scales, n, 64, cb, oidx, oval, n_outliers=k)
+        stats = binding.bof4_wait_result(rec).as_dict()
+        torch.cuda.synchronize()
+        assert k == ref_k and torch.equal(codes, ref_codes) and torch.equal(scales, ref_scales)
+        assert torch.equal(oidx[:k], ref_idx) and torch.equal(oval[:k], ref_val) and torch.equal(deq, ref_deq)
+        assert np.array_equal(stats["cnt"], ref_stats["cnt"]) and np.array_equal(stats["num"], ref_stats["num"])
+        assert stats["sse"] == ref_stats["sse"] and stats["n_used"] == n
+    # without outlier extraction the first half needs no counter in pinned memory; with it, it does
+    plain = ctypes.c_uint64(7)
+    flight = binding.bof4_quantize_begin(w, 64, cb, 1, 0.0, 0, codes, scales, None, None, None, plain)
+    assert flight.finish() == 0
+    with pytest.raises(binding.Bof4Error) as e:
+        binding.bof4_quantize_begin(w, 64, cb, 1, T, cap, codes, scales, oidx, oval, ws_q, plain)
+    assert e.value.code == binding.BOF4_ERR_ARG
+    with pytest.raises(binding.Bof4Error) as e:
+        binding.bof4_lloyd_step_begin(w, 64, cb, 1, binding.LloydStats(), ws=ws_l)
+    assert e.value.code == binding.BOF4_ERR_ARG
+    # too small a list: the second half reports it like the plain call
+    flight = binding.bof4_quantize_begin(w, 64, cb, 1, T, 8, codes, scales, oidx, oval, ws_q, counter)
+    with pytest.raises(binding.Bof4Error) as e:
+        flight.finish()
+    assert e.value.code == binding.BOF4_ERR_CAPACITY and counter.value == ref_k
