@@ -405,9 +405,19 @@ __global__ __launch_bounds__(1024) void mae_select_kernel(MaeLevelState* __restr
     __shared__ unsigned long long cnt[17];
     const uint32_t n_waves = n_part * WAVES_PER_WG;
     unsigned long long k_l = 0ull, k_out = 0ull;
-    for (uint32_t i = lane; i < n_waves; i += 64) {
-        k_l += cnt_part[l * n_waves + i];
-        if (l == 15) k_out += cnt_part[16 * n_waves + i];
+    for (uint32_t i0 = lane; i0 < n_waves; i0 += 64 * 8) {  // eight independent loads in flight (integers: any order)
+        unsigned long long a[8], b[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const uint32_t i = i0 + 64 * u;
+            a[u] = i < n_waves ? cnt_part[l * n_waves + i] : 0ull;
+            b[u] = (l == 15 && i < n_waves) ? cnt_part[16 * n_waves + i] : 0ull;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            k_l += a[u];
+            k_out += b[u];
+        }
     }
 #pragma unroll
     for (int mk = 32; mk >= 1; mk >>= 1) {
