@@ -4,11 +4,12 @@
 //   y[t][r] = sum_c w~[r][c] x[t][c],   w~ = m_b * level[code]  (exact product of eq. 3), outliers as stored.
 //
 // The matrix is read once as 4-bit codes (0.5 + 2/I bytes per weight): the kernel is a streaming scan bounded by HBM,
-// not a dense contraction worth matrix cores at one to four tokens.  One wave owns a strip of 2048 columns (32 per
+// not a dense contraction worth matrix cores at one or two tokens.  One wave owns a strip of 2048 columns (32 per
 // lane, one 16-byte load per lane and row) and keeps its slice of x in registers as binary32; it walks the rows of its
 // workgroup's chunk, looks the 32 levels up in a 16-entry LDS table (conflict-free: 16 words in 16 banks), multiplies
 // the row-and-lane sum by the block constant once and adds the 64 lanes up with six DPP additions.  The strips of one
-// row meet in LDS.  With an outlier list, a table made once per matrix holds per entry its column and
+// row meet in LDS (a workgroup has at most eight waves; on matrices wider than 16384 columns a wave takes several
+// strips in turn).  With an outlier list, a table made once per matrix holds per entry its column and
 // value - m * level[code], and where the entries of each row and strip begin; they go one to a lane, and
 // (value - m * level[code]) * x[col] joins that lane's sum before the wave adds up.
 // Every sum has a fixed order, so y is bit-reproducible.
