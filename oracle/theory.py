@@ -1,4 +1,4 @@
-"""Theoretical (data-free) MSE centroids for Gaussian weights - TEST INFRASTRUCTURE, used to pin the oracle.
+"""Theoretical (data-free) MSE and MAE centroids for Gaussian weights - TEST INFRASTRUCTURE, used to pin the oracle.
 
 Implements the closed form of appendix B.2 ("Simplified Solution for Gaussian Network Weights") by numerical
 integration over the block maximum m:
@@ -102,3 +102,40 @@ def distance_db(theo, emp, block, signed):
     emp = np.asarray(emp, dtype=np.float64)
     p = region_probabilities(theo, block, signed)
     return 10.0 * np.log10(np.sum(p * (theo - emp) ** 2) / np.sum(p * theo ** 2))
+
+
+def _weighted_mass_below(x, block, m, wts):
+    """INT m p_M(m) F_X^cont(x | M = m) dm up to factors that do not depend on x (and a term constant in x):
+    INT m (2G(m) - 1)^(I-2) g(m) G(m x) dm - the quantity whose differences appear in the MAE condition of
+    section 3.2 eq. 7 (appendix B.4) for Gaussian weights."""
+    core = np.zeros_like(m)
+    core[1:] = (2.0 * ndtr(m[1:]) - 1.0) ** (block - 2) * _pdf(m[1:])
+    return np.sum(wts * m * core * ndtr(m * x))
+
+
+def mae_centroid_update(cb, block, pinned_mask):
+    """One theoretical Lloyd iteration under the MAE criterion: every unpinned level moves to the point of its region
+    below which half of the region's mass, weighted by the block maximum, lies (eq. 7: the zero of a monotone function,
+    found by bisection).  Same restrictions on the outermost regions as centroid_update."""
+    cb = np.asarray(cb, dtype=np.float64)
+    xi = 0.5 * (cb[:-1] + cb[1:])
+    m, wts = _grid()
+    new = cb.copy()
+    for l in range(16):
+        if (pinned_mask >> l) & 1:
+            continue
+        if l == 15:
+            raise ValueError("the region holding the point mass at +1 is not supported; pin level 15")
+        a = max(xi[l - 1], -1.0) if l > 0 else -1.0
+        b = xi[l]
+        ha, hb = _weighted_mass_below(a, block, m, wts), _weighted_mass_below(b, block, m, wts)
+        target = ha + 0.5 * (hb - ha)
+        lo, hi = a, b
+        for _ in range(100):
+            mid = 0.5 * (lo + hi)
+            if _weighted_mass_below(mid, block, m, wts) < target:
+                lo = mid
+            else:
+                hi = mid
+        new[l] = 0.5 * (lo + hi)
+    return new

@@ -650,3 +650,31 @@ def test_quant_error_argument_errors():
     assert oracle.quant_error(wb[:40], 32, CB_S64, 1)[0] == oracle.ERR_ARG
     st, e = oracle.quant_error(wb, 64, CB_S64, 1)
     assert st == oracle.OK and e["sse"] == 0.0 and e["sae"] == 0.0  # all-zero block: decoded as zeros
+
+
+# ------------------------------------------------------------------- MAE criterion against its theoretical condition
+@pytest.mark.parametrize("signed", [0, 1])
+def test_printed_mae_codebooks_satisfy_the_theoretical_mae_condition(signed):
+    """Section 3.2 eq. 7 (appendix B.4): the MAE-optimal level of a region halves the region's mass weighted by the
+    block maximum.  Evaluated for Gaussian weights by numerical integration and bisection, with no data: the printed
+    MAE codebooks (appendix C, I = 64) are fixed points to 1e-4 - and the MSE codebooks are not."""
+    cb = codebooks.array(codebooks.BOF4S_MAE_64 if signed else codebooks.BOF4_MAE_64)
+    pin = codebooks.PIN_BOF4S if signed else codebooks.PIN_BOF4
+    new = theory.mae_centroid_update(cb, 64, pin)
+    assert np.max(np.abs(new - cb)) < 1e-4
+    mse_cb = codebooks.array(codebooks.BOF4S_MSE[64] if signed else codebooks.BOF4_MSE_64)
+    assert np.max(np.abs(theory.mae_centroid_update(mse_cb, 64, pin) - mse_cb)) > 5e-3
+
+
+def test_oracle_mae_step_agrees_with_the_theoretical_mae_condition_away_from_the_fixed_point():
+    """From the MSE-optimal codebook (not a fixed point of the MAE criterion) one data-driven MAE update on 2^18
+    Gaussian blocks and one theoretical update move every free level to the same place."""
+    cb = codebooks.array(codebooks.BOF4S_MSE[64])
+    pin = codebooks.PIN_BOF4S
+    wb = inputs.bits(inputs.gaussian_blocks(1 << 18, 64, seed=51))
+    st, s = oracle.lloyd_step_mae(wb, 64, cb, 1)
+    assert st == oracle.OK
+    emp = oracle.codebook_update_mae(s, pin, cb)
+    theo = theory.mae_centroid_update(cb, 64, pin)
+    assert np.max(np.abs(emp - theo)) < 6e-4
+    assert np.max(np.abs(theo - cb)) > 5e-3  # the update is far larger than the agreement
