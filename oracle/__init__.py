@@ -70,6 +70,8 @@ def lib():
         L.oracle_gemv.restype = ctypes.c_int
         L.oracle_gemv.argtypes = [u8p, u16p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint32, f64p, i64p, u16p,
                                   ctypes.c_uint64, u16p, ctypes.c_uint32, f64p, f64p]
+        L.oracle_gemm.restype = ctypes.c_int
+        L.oracle_gemm.argtypes = L.oracle_gemv.argtypes
         L.oracle_lloyd_step.restype = ctypes.c_int
         L.oracle_lloyd_step.argtypes = [u16p, ctypes.c_uint64, ctypes.c_uint32, f64p, ctypes.c_int,
                                         ctypes.c_double, ctypes.c_int, ctypes.POINTER(LloydStats)]
@@ -172,6 +174,28 @@ def gemv(codes, scales, rows, cols, block, cb, x, out_idx=None, out_val=None):
     y = np.zeros((x.shape[0], rows), dtype=np.float64)
     a = np.zeros((x.shape[0], rows), dtype=np.float64)
     st = lib().oracle_gemv(_p(codes, ctypes.c_uint8), _p(scales, ctypes.c_uint16), rows, cols, block,
+                           _p(cb, ctypes.c_double), _p(out_idx, ctypes.c_int64) if k else None,
+                           _p(out_val, ctypes.c_uint16) if k else None, k, _p(x, ctypes.c_uint16), x.shape[0],
+                           _p(y, ctypes.c_double), _p(a, ctypes.c_double))
+    return st, y, a
+
+
+def gemm(codes, scales, rows, cols, block, cb, x, out_idx=None, out_val=None):
+    """As gemv, over the decoded bfloat16 matrix (every weight rounded as oracle_dequantize rounds it)."""
+    cb = _cb(cb)
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.uint16)
+    x = np.ascontiguousarray(x, dtype=np.uint16)
+    if x.ndim == 1:
+        x = x[None, :]
+    assert x.shape[1] == cols
+    k = 0 if out_idx is None else int(out_idx.size)
+    if k:
+        out_idx = np.ascontiguousarray(out_idx, dtype=np.int64)
+        out_val = np.ascontiguousarray(out_val, dtype=np.uint16)
+    y = np.zeros((x.shape[0], rows), dtype=np.float64)
+    a = np.zeros((x.shape[0], rows), dtype=np.float64)
+    st = lib().oracle_gemm(_p(codes, ctypes.c_uint8), _p(scales, ctypes.c_uint16), rows, cols, block,
                            _p(cb, ctypes.c_double), _p(out_idx, ctypes.c_int64) if k else None,
                            _p(out_val, ctypes.c_uint16) if k else None, k, _p(x, ctypes.c_uint16), x.shape[0],
                            _p(y, ctypes.c_double), _p(a, ctypes.c_double))

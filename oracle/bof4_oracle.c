@@ -26,6 +26,9 @@
  *   decoder inside a matrix-vector product: constant codes (level times sum of x), unit vectors (one column of
  *                                the decoded matrix), planted outliers, linearity, and the decoded bfloat16 matrix
  *                                times x within the decoder's rounding bound
+ *   the product over the decoded bfloat16 matrix: equals a binary64 matrix product of oracle_dequantize's output
+ *                                (library routine on an independently pinned function); unit vectors; within the
+ *                                decoder's rounding of oracle_gemv
  *   tie rules (equal |w| of opposite sign, exact mid-point x, all-zero block, -0.0): parity unpinned by the
  *   paper - fixed only by the definitions written below.
  *
@@ -395,6 +398,38 @@ int oracle_gemv(const uint8_t* codes, const uint16_t* scales, uint64_t rows, uin
         }
     free(wt);
     return ORACLE_OK;
+}
+
+/*
+ * The same product for many tokens as an inference engine runs it (the paper's decode path: decode the matrix to
+ * bfloat16, then a bfloat16 matrix product): y[t][r] = sum_c W^[r][c] * x[t][c] with W^ exactly what oracle_dequantize
+ * returns - every weight rounded to bfloat16 (section 2.1 eq. 3), outliers written back (section 3.3).  Binary64 sums.
+ */
+int oracle_gemm(const uint8_t* codes, const uint16_t* scales, uint64_t rows, uint64_t cols, uint32_t I,
+                const double* cb, const int64_t* out_idx, const uint16_t* out_val, uint64_t n_outliers,
+                const uint16_t* x, uint32_t n_tokens, double* y, double* abs_out) {
+    if (!codes || !scales || !cb || !x || !y) return ORACLE_ERR_ARG;
+    if (rows == 0 || cols == 0 || n_tokens == 0 || (valid_block(I) && cols % I != 0)) return ORACLE_ERR_ARG;
+    const uint64_t n = rows * cols;
+    uint16_t* deq = (uint16_t*)malloc(n * sizeof(uint16_t));
+    if (!deq) return ORACLE_ERR_ARG;
+    int st = oracle_dequantize(codes, scales, n, I, cb, out_idx, out_val, n_outliers, deq);
+    if (st == ORACLE_OK) {
+        for (uint32_t t = 0; t < n_tokens; ++t)
+            for (uint64_t r = 0; r < rows; ++r) {
+                double acc = 0.0, aacc = 0.0;
+                for (uint64_t c = 0; c < cols; ++c) {
+                    const double term = (double)bf16_to_f32(deq[r * cols + c]) *
+                                        (double)bf16_to_f32(x[(uint64_t)t * cols + c]);
+                    acc += term;
+                    aacc += fabs(term);
+                }
+                y[(uint64_t)t * rows + r] = acc;
+                if (abs_out) abs_out[(uint64_t)t * rows + r] = aacc;
+            }
+    }
+    free(deq);
+    return st;
 }
 
 /* ---------------------------------------------------------------- Lloyd / EM ------------------------------ */

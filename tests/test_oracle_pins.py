@@ -678,3 +678,31 @@ def test_oracle_mae_step_agrees_with_the_theoretical_mae_condition_away_from_the
     theo = theory.mae_centroid_update(cb, 64, pin)
     assert np.max(np.abs(emp - theo)) < 6e-4
     assert np.max(np.abs(theo - cb)) > 5e-3  # the update is far larger than the agreement
+
+
+# ------------------------------------------------------------------ the product over the decoded bfloat16 matrix
+def test_gemm_is_the_matrix_product_of_the_decoded_matrix():
+    """oracle.gemm against numpy's binary64 matrix product of what oracle.dequantize returns (itself pinned above), with
+    outliers; a unit vector returns one decoded column bit for bit; and it stays within the decoder's rounding of the
+    unrounded product (oracle.gemv)."""
+    rows, cols, block = 12, 256, 64
+    rng = np.random.default_rng(12)
+    w = bf16_bits(rng.standard_normal(rows * cols).astype(np.float32) * 0.02)
+    w[rng.choice(w.size, 9, replace=False)] = bf16_bits(np.full(9, -0.3, dtype=np.float32))
+    T = oracle.opq_threshold(0.95, block)
+    st, codes, scales, oi, ov, k = oracle.quantize(w, block, CB_S64, True, T)
+    assert st == oracle.OK and k >= 9
+    st, deq = oracle.dequantize(codes, scales, w.size, block, CB_S64, oi, ov)
+    x = bf16_bits(rng.standard_normal((5, cols)).astype(np.float32)).reshape(5, cols)
+    st, y, a = oracle.gemm(codes, scales, rows, cols, block, CB_S64, x, oi, ov)
+    assert st == oracle.OK
+    W = bf16_val(deq).astype(np.float64).reshape(rows, cols)
+    X = bf16_val(x).astype(np.float64)
+    assert np.allclose(y, X @ W.T, rtol=0, atol=1e-15 * np.max(a))
+    assert np.allclose(a, np.abs(X) @ np.abs(W).T, rtol=1e-14)
+    e = np.zeros((1, cols), dtype=np.float32)
+    e[0, 77] = 1.0
+    st, ye, _ = oracle.gemm(codes, scales, rows, cols, block, CB_S64, bf16_bits(e).reshape(1, cols), oi, ov)
+    assert np.array_equal(ye[0], W[:, 77])
+    st, yv, av = oracle.gemv(codes, scales, rows, cols, block, CB_S64, x, oi, ov)
+    assert np.all(np.abs(y - yv) <= 2.0 ** -9 * av) and np.max(np.abs(y - yv)) > 0
