@@ -238,7 +238,33 @@ int bof4_gemv_outlier_table(const uint8_t* codes_dev, const uint16_t* scales_dev
                             void* stream);
 size_t bof4_gemv_outlier_table_bytes(uint64_t rows, uint64_t cols, uint64_t n_outliers);
 
-/* Measurement aid: the next bof4_quantize / bof4_dequantize / bof4_lloyd_step / bof4_quant_error / bof4_gemv call made by this thread records
+/*
+ * The decoder inside a matrix product for many tokens, as the paper's inference path runs it: the matrix is decoded to
+ * bfloat16 (section 2.1 eq. 3 rounded as bof4_dequantize rounds it, outliers of section 3.3 as stored) and multiplied
+ * with bfloat16 activations, binary32 accumulation - without the decoded matrix ever reaching memory:
+ *     y[t][r] = sum_c W^[r][c] * x[t][c],     W^ = what bof4_dequantize returns for the same arguments.
+ * Every product of two bfloat16 numbers is exact in binary32; the sums are binary32 (matrix cores, 32 tokens per
+ * pass over the codes) in a fixed order: y is bit-reproducible and lies within (cols + 64) * 2^-24 * sum_c |W^ x| of
+ * the exact sum (an outlier position counts with its decoded placeholder as well as with its value), and is exact
+ * whenever every partial sum is a binary32 number.
+ *   codes_dev, scales_dev, x_dev, y_dev   as for bof4_gemv
+ *   table_dev   what bof4_gemm_outlier_table made of the outlier list: layout and size of bof4_gemv's table
+ *               (bof4_gemv_outlier_table_bytes), but per entry (bfloat16(value) - bfloat16(constant * level));
+ *               may be NULL when n_outliers == 0
+ *   ws_dev      bof4_gemm_workspace_bytes(rows, cols, n_tokens) bytes (device, 4-byte aligned; 0 bytes - and then
+ *               NULL is fine - for matrices with enough rows to fill the chip), BOF4_ERR_WORKSPACE if smaller
+ * Limits: cols <= 32768.  Only enqueues.
+ */
+int bof4_gemm(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols, uint32_t block,
+              const double* cb_host, const void* table_dev, uint64_t n_outliers, const void* x_dev,
+              uint32_t n_tokens, float* y_dev, void* ws_dev, size_t ws_bytes, void* stream);
+int bof4_gemm_outlier_table(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols,
+                            uint32_t block, const double* cb_host, const int64_t* out_idx_dev,
+                            const uint16_t* out_val_dev, uint64_t n_outliers, void* table_dev, size_t table_bytes,
+                            void* stream);
+size_t bof4_gemm_workspace_bytes(uint64_t rows, uint64_t cols, uint32_t n_tokens);
+
+/* Measurement aid: the next bof4_quantize / bof4_dequantize / bof4_lloyd_step / bof4_quant_error / bof4_gemv / bof4_gemm call made by this thread records
  * the caller-owned hipEvent_t `start_event` immediately before and `stop_event` immediately after its main kernel
  * (the one that streams over the weights), on the call's stream; helper kernels and host synchronisation lie
  * outside the pair.  The request is consumed by that call.  Pass NULLs to cancel. */

@@ -25,6 +25,7 @@
 #include "bof4_segment.h"
 #include "bof4_mae.h"
 #include "bof4_gemv.h"
+#include "bof4_gemm.h"
 #include "bof4_error.h"
 
 namespace {
@@ -963,23 +964,27 @@ size_t bof4_gemv_outlier_table_bytes(uint64_t rows, uint64_t cols, uint64_t n_ou
     return gemv_table_layout(rows, (cols + GEMV_STRIP - 1) / GEMV_STRIP, n_outliers).total;
 }
 
-int bof4_gemv_outlier_table(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols,
-                            uint32_t block, const double* cb_host, const int64_t* out_idx_dev,
-                            const uint16_t* out_val_dev, uint64_t n_outliers, void* table_dev, size_t table_bytes,
-                            void* stream) {
+}  // extern "C"
+
+namespace {
+// rounded = false: the entries of bof4_gemv (value - m * level); true: those of bof4_gemm (both terms in bfloat16).
+int outlier_table_impl(bool rounded, const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows,
+                       uint64_t cols, uint32_t block, const double* cb_host, const int64_t* out_idx_dev,
+                       const uint16_t* out_val_dev, uint64_t n_outliers, void* table_dev, size_t table_bytes,
+                       void* stream) {
     if (!codes_dev || !scales_dev || !table_dev || (n_outliers > 0 && (!out_idx_dev || !out_val_dev)))
-        return fail(BOF4_ERR_ARG, "bof4_gemv_outlier_table: null pointer");
+        return fail(BOF4_ERR_ARG, "outlier table: null pointer");
     if (!valid_block(block) || rows == 0 || cols == 0 || cols % block != 0)
-        return fail(BOF4_ERR_ARG, "bof4_gemv_outlier_table: bad rows, cols (a positive multiple of block) or block");
+        return fail(BOF4_ERR_ARG, "outlier table: bad rows, cols (a positive multiple of block) or block");
     const uint64_t strips = (cols + GEMV_STRIP - 1) / GEMV_STRIP;
     if (rows > 0xfffffffeull || strips > GEMV_MAX_STRIPS || n_outliers > 0xffffffffull)
-        return fail(BOF4_ERR_ARG, "bof4_gemv_outlier_table: rows and the list length must fit 32 bits, cols <= 32768");
+        return fail(BOF4_ERR_ARG, "outlier table: rows and the list length must fit 32 bits, cols <= 32768");
     if (!valid_codebook(cb_host))
-        return fail(BOF4_ERR_ARG, "bof4_gemv_outlier_table: codebook must be 16 finite ascending levels");
+        return fail(BOF4_ERR_ARG, "outlier table: codebook must be 16 finite ascending levels");
     if (!aligned(out_idx_dev, 8) || !aligned(out_val_dev, 2) || !aligned(scales_dev, 2) || !aligned(table_dev, 8))
-        return fail(BOF4_ERR_ARG, "bof4_gemv_outlier_table: misaligned pointer (the table needs 8 bytes)");
+        return fail(BOF4_ERR_ARG, "outlier table: misaligned pointer (the table needs 8 bytes)");
     const GemvTableLayout L = gemv_table_layout(rows, strips, n_outliers);
-    if (table_bytes < L.total) return fail(BOF4_ERR_WORKSPACE, "bof4_gemv_outlier_table: table buffer too small");
+    if (table_bytes < L.total) return fail(BOF4_ERR_WORKSPACE, "outlier table: table buffer too small");
     hipStream_t s = (hipStream_t)stream;
     const CodebookArgs cb = make_codebook_args(cb_host);
     uint32_t log2_block = 5;
@@ -990,7 +995,93 @@ int bof4_gemv_outlier_table(const uint8_t* codes_dev, const uint16_t* scales_dev
     if (n_outliers > 0)
         hipLaunchKernelGGL(outlier_delta_kernel, dim3((uint32_t)((n_outliers + 255) / 256)), dim3(256), 0, s,
                            codes_dev, scales_dev, rows * cols, cols, log2_block, cb, out_idx_dev, out_val_dev,
-                           (uint32_t)n_outliers, (uint2*)((char*)table_dev + L.entries));
+                           (uint32_t)n_outliers, rounded ? 1u : 0u, (uint2*)((char*)table_dev + L.entries));
+    HIP_TRY(hipGetLastError());
+    return BOF4_OK;
+}
+
+// How many workgroups share the columns of one 32-row tile: enough to put GEMM_TARGET_WGS workgroups on the chip,
+// each with at least one chunk per wave.
+uint32_t gemm_split(uint64_t rows, uint64_t cols) {
+    const uint64_t tiles = (rows + GEMM_ROWS - 1) / GEMM_ROWS, chunks = (cols + GEMM_CHUNK - 1) / GEMM_CHUNK;
+    uint64_t split = (GEMM_TARGET_WGS + tiles - 1) / tiles;
+    const uint64_t most = chunks / GEMM_MAX_WAVES;
+    if (split > most) split = most;
+    return (uint32_t)(split < 1 ? 1 : split);
+}
+}  // namespace
+
+extern "C" {
+
+int bof4_gemv_outlier_table(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols,
+                            uint32_t block, const double* cb_host, const int64_t* out_idx_dev,
+                            const uint16_t* out_val_dev, uint64_t n_outliers, void* table_dev, size_t table_bytes,
+                            void* stream) {
+    return outlier_table_impl(false, codes_dev, scales_dev, rows, cols, block, cb_host, out_idx_dev, out_val_dev,
+                              n_outliers, table_dev, table_bytes, stream);
+}
+
+int bof4_gemm_outlier_table(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols,
+                            uint32_t block, const double* cb_host, const int64_t* out_idx_dev,
+                            const uint16_t* out_val_dev, uint64_t n_outliers, void* table_dev, size_t table_bytes,
+                            void* stream) {
+    return outlier_table_impl(true, codes_dev, scales_dev, rows, cols, block, cb_host, out_idx_dev, out_val_dev,
+                              n_outliers, table_dev, table_bytes, stream);
+}
+
+size_t bof4_gemm_workspace_bytes(uint64_t rows, uint64_t cols, uint32_t n_tokens) {
+    if (rows == 0 || cols == 0 || n_tokens == 0) return 0;
+    const uint32_t split = gemm_split(rows, cols);
+    if (split == 1) return 0;
+    const uint64_t nt = n_tokens < GEMM_TOKENS ? n_tokens : GEMM_TOKENS;
+    return (size_t)(split * nt * rows * 4);
+}
+
+int bof4_gemm(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols, uint32_t block,
+              const double* cb_host, const void* table_dev, uint64_t n_outliers, const void* x_dev,
+              uint32_t n_tokens, float* y_dev, void* ws_dev, size_t ws_bytes, void* stream) {
+    if (!codes_dev || !scales_dev || !x_dev || !y_dev) return fail(BOF4_ERR_ARG, "bof4_gemm: null pointer");
+    if (!valid_block(block) || rows == 0 || cols == 0 || cols % block != 0 || n_tokens == 0)
+        return fail(BOF4_ERR_ARG, "bof4_gemm: bad rows, cols (a positive multiple of block), block or n_tokens");
+    const uint64_t strips = (cols + GEMV_STRIP - 1) / GEMV_STRIP;
+    if (rows > 0xfffffffeull || strips > GEMV_MAX_STRIPS)
+        return fail(BOF4_ERR_ARG, "bof4_gemm: at most 2^32 - 2 rows and 32768 columns");
+    if (!valid_codebook(cb_host)) return fail(BOF4_ERR_ARG, "bof4_gemm: codebook must be 16 finite ascending levels");
+    if (n_outliers > 0 && !table_dev) return fail(BOF4_ERR_ARG, "bof4_gemm: outliers without their table");
+    if (n_outliers > 0xffffffffull) return fail(BOF4_ERR_ARG, "bof4_gemm: more than 2^32 - 1 outliers");
+    if (!aligned(codes_dev, 16) || !aligned(x_dev, 16) || !aligned(scales_dev, 2) || !aligned(y_dev, 4) ||
+        !aligned(table_dev, 8) || !aligned(ws_dev, 4))
+        return fail(BOF4_ERR_ARG, "bof4_gemm: misaligned pointer (codes and x need 16 bytes, the table 8)");
+    const size_t need = bof4_gemm_workspace_bytes(rows, cols, n_tokens);
+    if (need > 0 && (!ws_dev || ws_bytes < need)) return fail(BOF4_ERR_WORKSPACE, "bof4_gemm: workspace too small");
+    const uint32_t* offsets_dev = (const uint32_t*)table_dev;
+    const uint2* entries_dev =
+        table_dev ? (const uint2*)((const char*)table_dev + gemv_table_layout(rows, strips, n_outliers).entries) : nullptr;
+    hipStream_t s = (hipStream_t)stream;
+    const CodebookArgs cb = make_codebook_args(cb_host);
+    uint32_t log2_block = 5;
+    while ((1u << log2_block) < block) ++log2_block;
+    const uint32_t split = gemm_split(rows, cols);
+    const uint64_t chunks = (cols + GEMM_CHUNK - 1) / GEMM_CHUNK, per_wg = (chunks + split - 1) / split;
+    const uint32_t waves = (uint32_t)(per_wg < GEMM_MAX_WAVES ? per_wg : GEMM_MAX_WAVES);
+    const uint32_t tiles = (uint32_t)((rows + GEMM_ROWS - 1) / GEMM_ROWS);
+    const uint16_t* x = (const uint16_t*)x_dev;
+    timing_begin(s);
+    for (uint32_t t0 = 0; t0 < n_tokens; t0 += GEMM_TOKENS) {
+        const uint32_t nt = n_tokens - t0 < GEMM_TOKENS ? n_tokens - t0 : GEMM_TOKENS;
+        const uint16_t* xt = x + (uint64_t)t0 * cols;
+        float* yt = y_dev + (uint64_t)t0 * rows;
+        float* part = split > 1 ? (float*)ws_dev : yt;
+        hipLaunchKernelGGL(gemm_kernel, dim3(tiles, split), dim3(64 * waves), 0, s, (const uint4*)codes_dev,
+                           scales_dev, (uint32_t)rows, (uint32_t)cols, log2_block, cb, xt, nt, part);
+        if (split > 1 || n_outliers > 0) {
+            const uint64_t total = (uint64_t)nt * rows;
+            hipLaunchKernelGGL(gemm_finish_kernel, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, s, part,
+                               split, (uint32_t)rows, (uint32_t)cols, nt, offsets_dev, entries_dev,
+                               (uint32_t)n_outliers, (uint32_t)strips, xt, yt);
+        }
+    }
+    timing_end(s);
     HIP_TRY(hipGetLastError());
     return BOF4_OK;
 }

@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256) void outlier_delta_kernel(const uint8_t* __res
                                                             uint64_t cols, uint32_t log2_block, CodebookArgs cb,
                                                             const int64_t* __restrict__ out_idx,
                                                             const uint16_t* __restrict__ out_val, uint32_t n_out,
-                                                            uint2* __restrict__ entries) {
+                                                            uint32_t rounded, uint2* __restrict__ entries) {
     const uint32_t k = blockIdx.x * 256 + threadIdx.x;
     if (k >= n_out) return;
     const uint64_t idx = (uint64_t)out_idx[k];
@@ -77,8 +77,12 @@ __global__ __launch_bounds__(256) void outlier_delta_kernel(const uint8_t* __res
     if (idx < n) {
         const uint32_t code = (codes8[idx >> 1] >> ((idx & 1u) * 4)) & 15u;
         e.x = (uint32_t)(idx % cols);
-        e.y = __float_as_uint(fmaf(-f16_bits_to_f32(scales[idx >> log2_block]), cb.lv32[code],  // one rounding
-                                   f16_bits_to_f32(out_val[k])));
+        const float msc = f16_bits_to_f32(scales[idx >> log2_block]), val = f16_bits_to_f32(out_val[k]);
+        if (rounded)  // both as the decoder stores them in bfloat16: for products over the decoded matrix
+            e.y = __float_as_uint(bf16_bits_to_f32(f32_to_bf16_rne(val)) -
+                                  bf16_bits_to_f32(f32_to_bf16_rne(msc * cb.lv32[code])));
+        else
+            e.y = __float_as_uint(fmaf(-msc, cb.lv32[code], val));  // one rounding
     }
     entries[k] = e;
 }

@@ -1,0 +1,183 @@
+"""GPU parity of the decoder inside a matrix product for many tokens (bof4_gemm) against the oracle, which multiplies
+the decoded bfloat16 matrix with x in binary64.
+
+Every product of two bfloat16 numbers is exact in binary32, so the kernel's only roundings are those of its binary32
+additions: at most one per column inside the matrix cores' accumulation chain, a few across the waves and the column
+splits, and the outlier corrections - under (cols + 64) roundings of relative size 2^-24 against the sum of the
+magnitudes of the terms.  An outlier's correction (value - decoded placeholder) * x brings the placeholder's magnitude
+in as well, so the bound uses the magnitudes with and without the list.  Where every partial sum is a binary32 number
+(small integers times powers of two) the result must equal the oracle's bit for bit: that case catches a term that is
+dropped, doubled or paired with the wrong x, however small."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_06653_amd import binding, inputs
+from test_gpu_parity import cb_for
+from test_gpu_gemv import dev_i64, dev_u16, quantized, rand_x
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+U = 2.0 ** -24
+
+
+def run_gpu(cb, codes, scales, oi, ov, rows, cols, block, x):
+    cd = torch.from_numpy(codes).to(DEV)
+    sd = dev_u16(scales)
+    k = 0 if oi is None else int(oi.size)
+    if k:
+        tab = binding.bof4_gemm_outlier_table(cd, sd, rows, cols, block, cb, dev_i64(oi), dev_u16(ov))
+        y = binding.bof4_gemm(cd, sd, rows, cols, block, cb, x.to(DEV), tab, k)
+    else:
+        y = binding.bof4_gemm(cd, sd, rows, cols, block, cb, x.to(DEV))
+    torch.cuda.synchronize()
+    return y.cpu().numpy().astype(np.float64)
+
+
+def check(cb, codes, scales, oi, ov, rows, cols, block, x):
+    xb = inputs.bits(x).reshape(x.shape)
+    st, y_o, a = oracle.gemm(codes, scales, rows, cols, block, cb, xb, oi, ov)
+    assert st == oracle.OK
+    if oi is not None and oi.size:
+        st, _, a0 = oracle.gemm(codes, scales, rows, cols, block, cb, xb)
+        a = a + a0
+    y_g = run_gpu(cb, codes, scales, oi, ov, rows, cols, block, x)
+    assert y_g.shape == y_o.shape
+    err = np.abs(y_g - y_o)
+    assert np.all(err <= (cols + 64) * U * a + 1e-37), float(np.max(err / (a + 1e-300)))
+    return y_g, y_o
+
+
+@pytest.mark.parametrize("block", [32, 64, 128, 256])
+@pytest.mark.parametrize("opq", [0, 1])
+@pytest.mark.parametrize("n_tokens", [1, 7, 32, 40])
+def test_gemm_parity(block, opq, n_tokens):
+    rows, cols = 37, 2304  # two row tiles, the second with 5 rows; 36 chunks of 64 columns over 4 workgroups each
+    cb, codes, scales, oi, ov = quantized(rows, cols, block, 1, opq, seed=900 + block)
+    check(cb, codes, scales, oi if opq else None, ov if opq else None, rows, cols, block, rand_x(n_tokens, cols, 7))
+
+
+@pytest.mark.parametrize("rows,cols", [(1, 32), (3, 64), (130, 6144), (65, 4096 + 2048 + 1024), (33, 32768),
+                                       (16390, 128), (16390, 32)])
+def test_gemm_shapes(rows, cols):
+    """Half a chunk, one chunk, many; the last two have more than 512 row tiles, so that one workgroup takes all columns
+    of its rows and the list is applied to the result in place."""
+    cb, codes, scales, oi, ov = quantized(rows, cols, 32, 0, 1, seed=31 + rows)
+    assert (binding.bof4_gemm_workspace_bytes(rows, cols, 5) == 0) == (rows > 16000 or cols < 1024)
+    check(cb, codes, scales, oi, ov, rows, cols, 32, rand_x(5, cols, 11))
+
+
+@pytest.mark.parametrize("rows,cols,n_tokens", [(70, 1536, 33), (16390, 128, 9)])
+def test_gemm_is_exact_where_every_partial_sum_is_a_binary32_number(rows, cols, n_tokens):
+    """Levels k / 8, constants 2^e, x small integers, list values multiples of 1 / 8: every product and every sum of
+    them is a multiple of 2^-9 below 2^15, so no addition rounds, in any order."""
+    block = 32
+    rng = np.random.default_rng(rows)
+    cb = (np.arange(16) - 8) / 8.0
+    codes = rng.integers(0, 256, rows * cols // 2, dtype=np.uint8)
+    scales = (2.0 ** rng.integers(-6, 3, rows * cols // block)).astype(np.float16).view(np.uint16)
+    x = torch.from_numpy(rng.integers(-4, 5, (n_tokens, cols)).astype(np.float32)).to(torch.bfloat16)
+    xb = inputs.bits(x).reshape(x.shape)
+    oi = np.sort(rng.choice(rows * cols, rows * cols // 300, replace=False)).astype(np.int64)
+    ov = (rng.integers(-32, 33, oi.size) / 8.0).astype(np.float16).view(np.uint16)
+    for lst in ((None, None), (oi, ov)):
+        st, y_o, _ = oracle.gemm(codes, scales, rows, cols, block, cb, xb, *lst)
+        assert st == oracle.OK
+        y_g = run_gpu(cb, codes, scales, lst[0], lst[1], rows, cols, block, x)
+        assert np.array_equal(y_g, y_o)
+
+
+def test_gemm_unit_vectors_pick_single_decoded_weights():
+    """x = a unit vector per token: the product returns one column of the decoded matrix, exactly."""
+    rows, cols, block = 45, 2304, 64
+    cb, codes, scales, oi, ov = quantized(rows, cols, block, 1, 1, seed=79)
+    picks = [0, 1, 7, 8, 31, 32, 63, 64, 65, 2049, 2303]
+    x = torch.zeros((len(picks), cols), dtype=torch.bfloat16)
+    for t, c in enumerate(picks):
+        x[t, c] = 1.0
+    y_g, y_o = check(cb, codes, scales, oi, ov, rows, cols, block, x)
+    st, deq = oracle.dequantize(codes, scales, rows * cols, block, cb, oi, ov)
+    assert st == oracle.OK
+    w_hat = (deq.astype(np.uint32) << 16).view(np.float32).reshape(rows, cols).astype(np.float64)
+    assert np.array_equal(y_g, w_hat[:, picks].T)
+
+
+def test_gemm_on_the_quantisers_output_equals_the_product_over_the_decoders_output():
+    rows, cols, block = 257, 4096, 64
+    w = inputs.student_t_matrix(rows, cols, 5.0, 0.02, 0.3, seed=5).reshape(-1).to(DEV)
+    cb = cb_for(block, 1)
+    T = oracle.opq_threshold(0.95, block)
+    codes, scales, oi, ov, k = binding.bof4_quantize(w, block, cb, 1, opq_T=T, out_capacity=w.numel() // 20)
+    assert k > 0
+    tab = binding.bof4_gemm_outlier_table(codes, scales, rows, cols, block, cb, oi, ov, n_outliers=k)
+    x = rand_x(48, cols, 21).to(DEV)
+    y = binding.bof4_gemm(codes, scales, rows, cols, block, cb, x, tab, k)
+    deq = binding.bof4_dequantize(codes, scales, w.numel(), block, cb, oi, ov, n_outliers=k).reshape(rows, cols)
+    ref = x.double() @ deq.double().T
+    mag = x.double().abs() @ deq.double().abs().T
+    assert torch.all((y.double() - ref).abs() <= (cols + 64) * U * 2 * mag)
+
+
+def test_gemm_is_bit_reproducible_and_respects_out_workspace_and_stream():
+    rows, cols, block = 130, 4096, 64
+    cb, codes, scales, oi, ov = quantized(rows, cols, block, 1, 1, seed=80)
+    cd, sd, oid, ovd = torch.from_numpy(codes).to(DEV), dev_u16(scales), dev_i64(oi), dev_u16(ov)
+    tab = binding.bof4_gemm_outlier_table(cd, sd, rows, cols, block, cb, oid, ovd)
+    x = rand_x(35, cols, 5).to(DEV)
+    y1 = binding.bof4_gemm(cd, sd, rows, cols, block, cb, x, tab, oi.size)
+    out = torch.full((35, rows), float("nan"), device=DEV)
+    ws = torch.empty(binding.bof4_gemm_workspace_bytes(rows, cols, 35), dtype=torch.uint8, device=DEV)
+    assert ws.numel() > 0
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        y2 = binding.bof4_gemm(cd, sd, rows, cols, block, cb, x, tab, oi.size, out=out, ws=ws)
+    side.synchronize()
+    torch.cuda.synchronize()
+    assert y2 is out and torch.equal(y1, y2)
+    # one token alone gives the same numbers as inside a batch
+    y3 = binding.bof4_gemm(cd, sd, rows, cols, block, cb, x[33:34].contiguous(), tab, oi.size)
+    assert torch.equal(y3[0], y1[33])
+
+
+def test_gemm_argument_errors():
+    rows, cols, block = 64, 2048, 64
+    cb, codes, scales, oi, ov = quantized(rows, cols, block, 1, 1, seed=81)
+    cd, sd = torch.from_numpy(codes).to(DEV), dev_u16(scales)
+    x = rand_x(3, cols, 1).to(DEV)
+    with pytest.raises(binding.Bof4Error) as e:
+        binding.bof4_gemm(cd, sd, rows, 96, 64, cb, x[:, :96].contiguous())
+    assert e.value.code == binding.BOF4_ERR_ARG
+    with pytest.raises(binding.Bof4Error) as e:
+        binding.bof4_gemm(cd, sd, rows, cols, 48, cb, x)
+    assert e.value.code == binding.BOF4_ERR_ARG
+    with pytest.raises(binding.Bof4Error) as e:  # codes not 16-byte aligned
+        binding.bof4_gemm(cd[4:], sd, rows - 1, cols, block, cb, x)
+    assert e.value.code == binding.BOF4_ERR_ARG
+    need = binding.bof4_gemm_workspace_bytes(rows, cols, 3)
+    assert need == 4 * 3 * rows * 4  # 32 chunks of 64 columns: four workgroups of eight waves per row tile
+    with pytest.raises(binding.Bof4Error) as e:
+        binding.bof4_gemm(cd, sd, rows, cols, block, cb, x, ws=torch.empty(need - 4, dtype=torch.uint8, device=DEV))
+    assert e.value.code == binding.BOF4_ERR_WORKSPACE
+    with pytest.raises(ValueError):
+        binding.bof4_gemm(cd, sd, rows, cols, block, cb, x, None, 3)  # outliers without their table
+    with pytest.raises(ValueError):
+        binding.bof4_gemm(cd, sd, rows, cols, block, cb, x.float())
+    big = 32768 + 2048
+    with pytest.raises(binding.Bof4Error) as e:
+        binding.bof4_gemm(cd, sd, 1, big, 64, cb, torch.zeros((1, big), dtype=torch.bfloat16, device=DEV))
+    assert e.value.code == binding.BOF4_ERR_ARG
+
+
+@pytest.mark.parametrize("rows,cols,n_tokens", [(4096, 4096, 32), (4096, 11008, 32), (11008, 4096, 64),
+                                                (8192, 28672, 8)])
+def test_gemm_llama_matrices_with_opq(rows, cols, n_tokens):
+    """The three matrix shapes of workload 1 and the widest one of workload 4 at full size, signed constants, block 64,
+    OPQ q = 0.95: every output against the oracle."""
+    wm = inputs.student_t_matrix(rows, cols, 5.0, 0.02, 0.3, seed=rows + cols)
+    cb = cb_for(64, 1)
+    T = oracle.opq_threshold(0.95, 64)
+    st, codes, scales, oi, ov, k = oracle.quantize(inputs.bits(wm.reshape(-1)), 64, cb, 1, opq_T=T)
+    assert st == oracle.OK and k > 1000
+    check(cb, codes, scales, oi, ov, rows, cols, 64, rand_x(n_tokens, cols, 9))
