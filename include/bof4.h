@@ -242,22 +242,34 @@ size_t bof4_gemv_outlier_table_bytes(uint64_t rows, uint64_t cols, uint64_t n_ou
  * The decoder inside a matrix product for many tokens, as the paper's inference path runs it: the matrix is decoded to
  * bfloat16 (section 2.1 eq. 3 rounded as bof4_dequantize rounds it, outliers of section 3.3 as stored) and multiplied
  * with bfloat16 activations, binary32 accumulation - without the decoded matrix ever reaching memory:
- *     y[t][r] = sum_c W^[r][c] * x[t][c],     W^ = what bof4_dequantize returns for the same arguments.
- * Every product of two bfloat16 numbers is exact in binary32; the sums are binary32 (matrix cores, 32 tokens per
- * pass over the codes) in a fixed order: y is bit-reproducible and lies within (cols + 64) * 2^-24 * sum_c |W^ x| of
- * the exact sum (an outlier position counts with its decoded placeholder as well as with its value), and is exact
+ *     y[t][r] = sum_c W^[r][c] * x[t][c],     W^ = what bof4_dequantize returns for the same quantised tensor.
+ * Every product of two bfloat16 numbers is exact in binary32; the sums are binary32 (matrix cores, up to 128 tokens
+ * per pass over the codes) in a fixed order: y is bit-reproducible and lies within (cols + 64) * 2^-24 * sum_c |W^ x|
+ * of the exact sum (an outlier position counts with its decoded placeholder as well as with its value), and is exact
  * whenever every partial sum is a binary32 number.
- *   codes_dev, scales_dev, x_dev, y_dev   as for bof4_gemv
- *   table_dev   what bof4_gemm_outlier_table made of the outlier list: layout and size of bof4_gemv's table
- *               (bof4_gemv_outlier_table_bytes), but per entry (bfloat16(value) - bfloat16(constant * level));
- *               may be NULL when n_outliers == 0
- *   ws_dev      bof4_gemm_workspace_bytes(rows, cols, n_tokens) bytes (device, 4-byte aligned; 0 bytes - and then
- *               NULL is fine - for matrices with enough rows to fill the chip), BOF4_ERR_WORKSPACE if smaller
- * Limits: cols <= 32768.  Only enqueues.
+ *
+ * The matrix is read from a copy in the order of the matrix cores' operands, made once per matrix by bof4_gemm_pack
+ * from what bof4_quantize wrote for n = rows * cols (row-major [rows x cols], cols a multiple of block):
+ * bof4_gemm_packed_bytes(rows, cols) bytes (device, 16-byte aligned) - per tile of 32 rows x 64 columns 1024 bytes of
+ * codes and 64 binary16 constants, 0.5625 bytes per weight; BOF4_ERR_WORKSPACE if the buffer is smaller.
+ *   packed_dev  that copy
+ *   table_dev   what bof4_gemm_outlier_table made of the outlier list (from the unpacked codes and constants): layout
+ *               and size of bof4_gemv's table (bof4_gemv_outlier_table_bytes), but per entry
+ *               (bfloat16(value) - bfloat16(constant * level)); may be NULL when n_outliers == 0
+ *   x_dev       n_tokens x cols bfloat16 (device, 16-byte aligned), y_dev  n_tokens x rows binary32 (device)
+ *   ws_dev      bof4_gemm_workspace_bytes(rows, cols, n_tokens) bytes (device, 256-byte aligned),
+ *               BOF4_ERR_WORKSPACE if smaller: x reordered for the matrix cores and transposed for the list (4 bytes
+ *               per token slot and column, token slots in 32s), and - for matrices with too few rows to fill the
+ *               chip - the partial results of the workgroups that share a row
+ * Limits: cols <= 32768 and a multiple of 32, n_tokens <= 65536.  The codes are read once per 128 tokens.  All three
+ * calls only enqueue.
  */
-int bof4_gemm(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols, uint32_t block,
-              const double* cb_host, const void* table_dev, uint64_t n_outliers, const void* x_dev,
-              uint32_t n_tokens, float* y_dev, void* ws_dev, size_t ws_bytes, void* stream);
+int bof4_gemm(const void* packed_dev, uint64_t rows, uint64_t cols, const double* cb_host, const void* table_dev,
+              uint64_t n_outliers, const void* x_dev, uint32_t n_tokens, float* y_dev, void* ws_dev, size_t ws_bytes,
+              void* stream);
+int bof4_gemm_pack(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols, uint32_t block,
+                   void* packed_dev, size_t packed_bytes, void* stream);
+size_t bof4_gemm_packed_bytes(uint64_t rows, uint64_t cols);
 int bof4_gemm_outlier_table(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols,
                             uint32_t block, const double* cb_host, const int64_t* out_idx_dev,
                             const uint16_t* out_val_dev, uint64_t n_outliers, void* table_dev, size_t table_bytes,

@@ -17,7 +17,8 @@ EXPORTS = ("bof4_workspace_bytes", "bof4_opq_threshold", "bof4_thresholds", "bof
            "bof4_codebook_update", "bof4_lloyd_step_mae", "bof4_codebook_update_mae", "bof4_quantize",
            "bof4_dequantize", "bof4_quantize_begin", "bof4_quantize_finish", "bof4_lloyd_step_begin", "bof4_wait_result",
            "bof4_quant_error", "bof4_gemv", "bof4_gemv_outlier_table",
-           "bof4_gemv_outlier_table_bytes", "bof4_gemm", "bof4_gemm_outlier_table", "bof4_gemm_workspace_bytes",
+           "bof4_gemv_outlier_table_bytes", "bof4_gemm", "bof4_gemm_pack", "bof4_gemm_packed_bytes",
+           "bof4_gemm_outlier_table", "bof4_gemm_workspace_bytes",
            "bof4_time_next_call", "bof4_last_error",
            "bof4_last_hip_error")
 
@@ -113,8 +114,12 @@ def lib():
         L.bof4_gemv_outlier_table_bytes.restype = ctypes.c_size_t
         L.bof4_gemv_outlier_table_bytes.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64]
         L.bof4_gemm.restype = ctypes.c_int
-        L.bof4_gemm.argtypes = [vp, vp, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint32, f64p, vp, ctypes.c_uint64,
-                                vp, ctypes.c_uint32, vp, vp, ctypes.c_size_t, vp]
+        L.bof4_gemm.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint64, f64p, vp, ctypes.c_uint64, vp, ctypes.c_uint32,
+                                vp, vp, ctypes.c_size_t, vp]
+        L.bof4_gemm_pack.restype = ctypes.c_int
+        L.bof4_gemm_pack.argtypes = [vp, vp, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint32, vp, ctypes.c_size_t, vp]
+        L.bof4_gemm_packed_bytes.restype = ctypes.c_size_t
+        L.bof4_gemm_packed_bytes.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
         L.bof4_gemm_outlier_table.restype = ctypes.c_int
         L.bof4_gemm_outlier_table.argtypes = L.bof4_gemv_outlier_table.argtypes
         L.bof4_gemm_workspace_bytes.restype = ctypes.c_size_t
@@ -321,14 +326,30 @@ def bof4_gemm_outlier_table(codes, scales, rows, cols, block, cb, out_idx, out_v
     return out
 
 
-def bof4_gemm(codes, scales, rows, cols, block, cb, x, table=None, n_outliers=0, out=None, ws=None, stream=None):
-    """y = x W^^T for the decoded (bfloat16) form of the quantised row-major [rows, cols] matrix; x is bf16
-    [n_tokens, cols] on the device, the result float32 [n_tokens, rows].  `table` (bof4_gemm_outlier_table) brings
-    n_outliers outliers in; `ws`: optional uint8 device tensor of bof4_gemm_workspace_bytes(...) bytes."""
+def bof4_gemm_packed_bytes(rows, cols):
+    return int(lib().bof4_gemm_packed_bytes(rows, cols))
+
+
+def bof4_gemm_pack(codes, scales, rows, cols, block, out=None, stream=None):
+    """Codes and block constants of one quantised matrix in the order bof4_gemm reads them (uint8 device tensor;
+    made once)."""
+    if out is None:
+        out = torch.empty(bof4_gemm_packed_bytes(rows, cols), dtype=torch.uint8, device=codes.device)
+    _check(lib().bof4_gemm_pack(_ptr(codes), _ptr(scales), rows, cols, block, _ptr(out), out.numel(), _stream(stream)))
+    return out
+
+
+def bof4_gemm(packed, rows, cols, cb, x, table=None, n_outliers=0, out=None, ws=None, stream=None):
+    """y = x W^^T for the decoded (bfloat16) form of the quantised row-major [rows, cols] matrix, given as
+    bof4_gemm_pack made it; x is bf16 [n_tokens, cols] on the device, the result float32 [n_tokens, rows].  `table`
+    (bof4_gemm_outlier_table) brings n_outliers outliers in; `ws`: optional uint8 device tensor of
+    bof4_gemm_workspace_bytes(...) bytes."""
     cb, cbp = _cb(cb)
     x2 = x if x.dim() == 2 else x[None, :]
     if x2.dtype != torch.bfloat16 or x2.shape[1] != cols or not x2.is_contiguous():
         raise ValueError("x must be a contiguous bfloat16 tensor of [n_tokens, cols]")
+    if packed.numel() < bof4_gemm_packed_bytes(rows, cols):
+        raise ValueError("packed matrix too small for rows x cols (bof4_gemm_pack)")
     n_tokens = int(x2.shape[0])
     if out is None:
         out = torch.empty((n_tokens, rows), dtype=torch.float32, device=x.device)
@@ -336,11 +357,9 @@ def bof4_gemm(codes, scales, rows, cols, block, cb, x, table=None, n_outliers=0,
     if k and table is None:
         raise ValueError("outliers need their table (bof4_gemm_outlier_table)")
     if ws is None:
-        need = bof4_gemm_workspace_bytes(rows, cols, n_tokens)
-        ws = torch.empty(need, dtype=torch.uint8, device=x.device) if need else None
-    _check(lib().bof4_gemm(_ptr(codes), _ptr(scales), rows, cols, block, cbp, _ptr(table) if k else None, k,
-                           _ptr(x2), n_tokens, _ptr(out), _ptr(ws) if ws is not None else None,
-                           ws.numel() if ws is not None else 0, _stream(stream)))
+        ws = torch.empty(bof4_gemm_workspace_bytes(rows, cols, n_tokens), dtype=torch.uint8, device=x.device)
+    _check(lib().bof4_gemm(_ptr(packed), rows, cols, cbp, _ptr(table) if k else None, k, _ptr(x2), n_tokens,
+                           _ptr(out), _ptr(ws), ws.numel(), _stream(stream)))
     return out
 
 

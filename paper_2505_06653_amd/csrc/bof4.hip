@@ -1009,6 +1009,23 @@ uint32_t gemm_split(uint64_t rows, uint64_t cols) {
     if (split > most) split = most;
     return (uint32_t)(split < 1 ? 1 : split);
 }
+
+// Workspace of bof4_gemm: x in the order of the products, x transposed (for the list), the partial results.
+constexpr uint32_t GEMM_MAX_TOKENS = 65536;
+struct GemmWsLayout {
+    size_t xp, xt, part, total;
+};
+GemmWsLayout gemm_ws_layout(uint64_t rows, uint64_t cols, uint64_t n_tokens) {
+    const uint64_t n_pad = (n_tokens + GEMM_TOKENS - 1) / GEMM_TOKENS * GEMM_TOKENS;
+    const uint64_t chunks = (cols + GEMM_CHUNK - 1) / GEMM_CHUNK, split = gemm_split(rows, cols);
+    const uint64_t per_launch = n_pad < GEMM_TOKENS * GEMM_MAX_TILES ? n_pad : GEMM_TOKENS * GEMM_MAX_TILES;
+    GemmWsLayout L;
+    L.xp = 0;
+    L.xt = align_up(L.xp + n_pad * chunks * GEMM_CHUNK * 2, 256);
+    L.part = align_up(L.xt + cols * n_pad * 2, 256);
+    L.total = L.part + (split > 1 ? split * per_launch * rows * 4 : 0);
+    return L;
+}
 }  // namespace
 
 extern "C" {
@@ -1031,55 +1048,94 @@ int bof4_gemm_outlier_table(const uint8_t* codes_dev, const uint16_t* scales_dev
 
 size_t bof4_gemm_workspace_bytes(uint64_t rows, uint64_t cols, uint32_t n_tokens) {
     if (rows == 0 || cols == 0 || n_tokens == 0) return 0;
-    const uint32_t split = gemm_split(rows, cols);
-    if (split == 1) return 0;
-    const uint64_t nt = n_tokens < GEMM_TOKENS ? n_tokens : GEMM_TOKENS;
-    return (size_t)(split * nt * rows * 4);
+    return gemm_ws_layout(rows, cols, n_tokens).total;
 }
 
-int bof4_gemm(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols, uint32_t block,
-              const double* cb_host, const void* table_dev, uint64_t n_outliers, const void* x_dev,
-              uint32_t n_tokens, float* y_dev, void* ws_dev, size_t ws_bytes, void* stream) {
-    if (!codes_dev || !scales_dev || !x_dev || !y_dev) return fail(BOF4_ERR_ARG, "bof4_gemm: null pointer");
-    if (!valid_block(block) || rows == 0 || cols == 0 || cols % block != 0 || n_tokens == 0)
-        return fail(BOF4_ERR_ARG, "bof4_gemm: bad rows, cols (a positive multiple of block), block or n_tokens");
+size_t bof4_gemm_packed_bytes(uint64_t rows, uint64_t cols) {
+    return (size_t)(((rows + GEMM_ROWS - 1) / GEMM_ROWS) * ((cols + GEMM_CHUNK - 1) / GEMM_CHUNK) * GEMM_TILE_BYTES);
+}
+
+int bof4_gemm_pack(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols, uint32_t block,
+                   void* packed_dev, size_t packed_bytes, void* stream) {
+    if (!codes_dev || !scales_dev || !packed_dev) return fail(BOF4_ERR_ARG, "bof4_gemm_pack: null pointer");
+    if (!valid_block(block) || rows == 0 || cols == 0 || cols % block != 0)
+        return fail(BOF4_ERR_ARG, "bof4_gemm_pack: bad rows, cols (a positive multiple of block) or block");
+    if (rows > 0xfffffffeull || cols > GEMV_MAX_STRIPS * GEMV_STRIP)
+        return fail(BOF4_ERR_ARG, "bof4_gemm_pack: at most 2^32 - 2 rows and 32768 columns");
+    if (!aligned(codes_dev, 16) || !aligned(scales_dev, 2) || !aligned(packed_dev, 16))
+        return fail(BOF4_ERR_ARG, "bof4_gemm_pack: misaligned pointer (codes and the packed copy need 16 bytes)");
+    if (packed_bytes < bof4_gemm_packed_bytes(rows, cols))
+        return fail(BOF4_ERR_WORKSPACE, "bof4_gemm_pack: buffer for the packed copy too small");
+    uint32_t log2_block = 5;
+    while ((1u << log2_block) < block) ++log2_block;
+    const uint32_t chunks = (uint32_t)((cols + GEMM_CHUNK - 1) / GEMM_CHUNK);
+    const uint64_t n_tiles = ((rows + GEMM_ROWS - 1) / GEMM_ROWS) * chunks;
+    hipLaunchKernelGGL(gemm_pack_weights_kernel, dim3((uint32_t)((n_tiles * 64 + 255) / 256)), dim3(256), 0,
+                       (hipStream_t)stream, (const uint4*)codes_dev, scales_dev, (uint32_t)rows, (uint32_t)cols,
+                       log2_block, chunks, n_tiles, (char*)packed_dev);
+    HIP_TRY(hipGetLastError());
+    return BOF4_OK;
+}
+
+int bof4_gemm(const void* packed_dev, uint64_t rows, uint64_t cols, const double* cb_host, const void* table_dev,
+              uint64_t n_outliers, const void* x_dev, uint32_t n_tokens, float* y_dev, void* ws_dev, size_t ws_bytes,
+              void* stream) {
+    if (!packed_dev || !x_dev || !y_dev || !ws_dev) return fail(BOF4_ERR_ARG, "bof4_gemm: null pointer");
+    if (rows == 0 || cols == 0 || cols % 32 != 0 || n_tokens == 0)
+        return fail(BOF4_ERR_ARG, "bof4_gemm: bad rows, cols (a positive multiple of 32) or n_tokens");
     const uint64_t strips = (cols + GEMV_STRIP - 1) / GEMV_STRIP;
-    if (rows > 0xfffffffeull || strips > GEMV_MAX_STRIPS)
-        return fail(BOF4_ERR_ARG, "bof4_gemm: at most 2^32 - 2 rows and 32768 columns");
+    if (rows > 0xfffffffeull || strips > GEMV_MAX_STRIPS || n_tokens > GEMM_MAX_TOKENS)
+        return fail(BOF4_ERR_ARG, "bof4_gemm: at most 2^32 - 2 rows, 32768 columns and 65536 tokens");
     if (!valid_codebook(cb_host)) return fail(BOF4_ERR_ARG, "bof4_gemm: codebook must be 16 finite ascending levels");
     if (n_outliers > 0 && !table_dev) return fail(BOF4_ERR_ARG, "bof4_gemm: outliers without their table");
     if (n_outliers > 0xffffffffull) return fail(BOF4_ERR_ARG, "bof4_gemm: more than 2^32 - 1 outliers");
-    if (!aligned(codes_dev, 16) || !aligned(x_dev, 16) || !aligned(scales_dev, 2) || !aligned(y_dev, 4) ||
-        !aligned(table_dev, 8) || !aligned(ws_dev, 4))
-        return fail(BOF4_ERR_ARG, "bof4_gemm: misaligned pointer (codes and x need 16 bytes, the table 8)");
-    const size_t need = bof4_gemm_workspace_bytes(rows, cols, n_tokens);
-    if (need > 0 && (!ws_dev || ws_bytes < need)) return fail(BOF4_ERR_WORKSPACE, "bof4_gemm: workspace too small");
+    if (!aligned(packed_dev, 16) || !aligned(x_dev, 16) || !aligned(y_dev, 4) || !aligned(table_dev, 8) ||
+        !aligned(ws_dev, 256))
+        return fail(BOF4_ERR_ARG, "bof4_gemm: misaligned pointer (packed matrix and x need 16 bytes, the table 8, the workspace 256)");
+    const GemmWsLayout L = gemm_ws_layout(rows, cols, n_tokens);
+    if (ws_bytes < L.total) return fail(BOF4_ERR_WORKSPACE, "bof4_gemm: workspace too small");
     const uint32_t* offsets_dev = (const uint32_t*)table_dev;
     const uint2* entries_dev =
         table_dev ? (const uint2*)((const char*)table_dev + gemv_table_layout(rows, strips, n_outliers).entries) : nullptr;
     hipStream_t s = (hipStream_t)stream;
     const CodebookArgs cb = make_codebook_args(cb_host);
-    uint32_t log2_block = 5;
-    while ((1u << log2_block) < block) ++log2_block;
     const uint32_t split = gemm_split(rows, cols);
-    const uint64_t chunks = (cols + GEMM_CHUNK - 1) / GEMM_CHUNK, per_wg = (chunks + split - 1) / split;
-    const uint32_t waves = (uint32_t)(per_wg < GEMM_MAX_WAVES ? per_wg : GEMM_MAX_WAVES);
-    const uint32_t tiles = (uint32_t)((rows + GEMM_ROWS - 1) / GEMM_ROWS);
-    const uint16_t* x = (const uint16_t*)x_dev;
+    const uint32_t chunks = (uint32_t)((cols + GEMM_CHUNK - 1) / GEMM_CHUNK), per_wg = (chunks + split - 1) / split;
+    const uint32_t waves = per_wg < GEMM_MAX_WAVES ? per_wg : GEMM_MAX_WAVES;
+    const uint32_t row_tiles = (uint32_t)((rows + GEMM_ROWS - 1) / GEMM_ROWS);
+    const uint32_t n_pad = (n_tokens + GEMM_TOKENS - 1) / GEMM_TOKENS * GEMM_TOKENS, tok_tiles = n_pad / GEMM_TOKENS;
+    const uint4* xp = (const uint4*)((char*)ws_dev + L.xp);
+    const uint16_t* xt = (const uint16_t*)((char*)ws_dev + L.xt);
+    float* part = (float*)((char*)ws_dev + L.part);
+    {
+        const uint64_t total = (uint64_t)tok_tiles * chunks * 256;
+        hipLaunchKernelGGL(gemm_pack_x_kernel, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, s,
+                           (const uint16_t*)x_dev, n_tokens, (uint32_t)cols, chunks, n_pad, (uint4*)xp,
+                           n_outliers > 0 ? (uint16_t*)xt : nullptr);
+    }
     timing_begin(s);
-    for (uint32_t t0 = 0; t0 < n_tokens; t0 += GEMM_TOKENS) {
-        const uint32_t nt = n_tokens - t0 < GEMM_TOKENS ? n_tokens - t0 : GEMM_TOKENS;
-        const uint16_t* xt = x + (uint64_t)t0 * cols;
+    for (uint32_t tile0 = 0; tile0 < tok_tiles;) {
+        const uint32_t left = tok_tiles - tile0, nt_tiles = left >= 4 ? 4 : left >= 2 ? 2 : 1;
+        const uint32_t t0 = tile0 * GEMM_TOKENS;
+        const uint32_t nt = n_tokens - t0 < nt_tiles * GEMM_TOKENS ? n_tokens - t0 : nt_tiles * GEMM_TOKENS;
         float* yt = y_dev + (uint64_t)t0 * rows;
-        float* part = split > 1 ? (float*)ws_dev : yt;
-        hipLaunchKernelGGL(gemm_kernel, dim3(tiles, split), dim3(64 * waves), 0, s, (const uint4*)codes_dev,
-                           scales_dev, (uint32_t)rows, (uint32_t)cols, log2_block, cb, xt, nt, part);
-        if (split > 1 || n_outliers > 0) {
-            const uint64_t total = (uint64_t)nt * rows;
-            hipLaunchKernelGGL(gemm_finish_kernel, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, s, part,
-                               split, (uint32_t)rows, (uint32_t)cols, nt, offsets_dev, entries_dev,
-                               (uint32_t)n_outliers, (uint32_t)strips, xt, yt);
+        float* dst = split > 1 ? part : yt;
+#define BOF4_LAUNCH_GEMM(NT_, OUT_)                                                                               \
+    hipLaunchKernelGGL((gemm_kernel<NT_, OUT_>), dim3(row_tiles, split), dim3(64 * waves), 0, s,                  \
+                       (const char*)packed_dev, (uint32_t)rows, (uint32_t)cols, cb, offsets_dev, entries_dev,     \
+                       (uint32_t)n_outliers, (uint32_t)strips, xp, xt, n_pad, tile0, nt, dst);
+        if (n_outliers > 0) {
+            if (nt_tiles == 4) { BOF4_LAUNCH_GEMM(4, true) } else if (nt_tiles == 2) { BOF4_LAUNCH_GEMM(2, true) } else { BOF4_LAUNCH_GEMM(1, true) }
+        } else {
+            if (nt_tiles == 4) { BOF4_LAUNCH_GEMM(4, false) } else if (nt_tiles == 2) { BOF4_LAUNCH_GEMM(2, false) } else { BOF4_LAUNCH_GEMM(1, false) }
         }
+#undef BOF4_LAUNCH_GEMM
+        if (split > 1) {
+            const uint64_t count = (uint64_t)nt * rows;
+            hipLaunchKernelGGL(gemm_sum_kernel, dim3((uint32_t)((count + 255) / 256)), dim3(256), 0, s, part, split,
+                               count, yt);
+        }
+        tile0 += nt_tiles;
     }
     timing_end(s);
     HIP_TRY(hipGetLastError());

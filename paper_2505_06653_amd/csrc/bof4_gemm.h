@@ -7,16 +7,17 @@
 // The codes are still read once (0.5 + 2/I bytes per weight) and decoded once per 32 tokens, so per weight the cost is
 // that of the matrix-vector kernel (extract, look the level up, one multiply, one conversion); the 32 multiply-adds
 // per weight that follow are a dense contraction and go to the matrix cores: v_mfma_f32_32x32x16_bf16, A = 32 rows x
-// 16 columns of decoded weights, B = the same 16 columns of 32 tokens, binary32 accumulators.  Lane l supplies
+// 16 columns of decoded weights, B = the same 16 columns of 32 tokens, binary32 accumulators; up to four tiles of
+// 32 tokens share one decoded A.  Codes, constants and x are read in that order from copies laid out for it (the
+// matrix once, x per call), so that every load of a wave is one run of consecutive bytes.  Lane l supplies
 // row l % 32 of A and token l % 32 of B, eight consecutive columns each; which eight is the same for both (half
 // l / 32 of a 64-column chunk takes its columns 32 (l / 32) + 8 j .. + 7 in the j-th of four products), so a lane
 // decodes one 16-byte load of its row per chunk.
 // A workgroup owns 32 rows; its waves take the 64-column chunks in turn and their 32 x 32 partial results are added
 // in wave order through LDS.  Outliers: the decoded placeholder went through the product, so what is added per list
 // entry is (value - bfloat16(m * level[code])) * x[t][col], from the table bof4_gemv_outlier_table makes in its
-// rounded form, in list order, by a second small kernel; the same kernel adds the partial results when the columns
-// of a matrix with few rows are split over several workgroups to fill the chip.  Every order is fixed: the result is
-// bit-reproducible.
+// rounded form.  When the columns of a matrix with few rows are split over several workgroups to fill the chip, a
+// second small kernel adds their partial results.  Every order is fixed: the result is bit-reproducible.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -29,7 +30,8 @@
 namespace bof4 {
 
 constexpr uint32_t GEMM_ROWS = 32;    // rows per workgroup (M of the matrix-core product)
-constexpr uint32_t GEMM_TOKENS = 32;  // tokens per launch (N)
+constexpr uint32_t GEMM_TOKENS = 32;  // tokens per tile (N of the matrix-core product)
+constexpr uint32_t GEMM_MAX_TILES = 4;  // token tiles per launch: the codes are decoded once per 128 tokens
 constexpr uint32_t GEMM_CHUNK = 64;   // columns per wave and step: four products of K = 16
 constexpr uint32_t GEMM_MAX_WAVES = 8;
 constexpr uint32_t GEMM_TARGET_WGS = 512;  // two workgroups on each of the 256 compute units
@@ -47,42 +49,118 @@ __device__ __forceinline__ uint32_t gemm_pack_bf16(float lo, float hi) {
     return u;
 }
 
-// Workgroup (t, s): rows 32 t .. 32 t + 31, the chunks s * waves + wave, + n_split * waves, ... of the row.  Its sum
-// goes to dst[(s * n_tokens + token) * rows + row]: the result itself when n_split is 1, else one of n_split partial
-// results that gemm_finish_kernel adds.
+// The codes and block constants in the order the products read them, made once per matrix: per tile of 32 rows and
+// chunk of 64 columns GEMM_TILE_BYTES consecutive bytes - one 16-byte word of codes per lane (row = lane % 32 of the
+// tile, columns 32 (lane / 32) .. + 31 of the chunk), then one binary16 constant per lane (that of the lane's 32
+// columns).  Rows past the matrix and columns past its width hold code 0 and constant 0: they add nothing.
+constexpr uint32_t GEMM_TILE_BYTES = 64 * 16 + 64 * 2;
+__global__ __launch_bounds__(256) void gemm_pack_weights_kernel(const uint4* __restrict__ codes,
+                                                                const uint16_t* __restrict__ scales, uint32_t rows,
+                                                                uint32_t cols, uint32_t log2_block, uint32_t n_chunks,
+                                                                uint64_t n_tiles, char* __restrict__ packed) {
+    const uint64_t idx = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= n_tiles * 64) return;
+    const uint32_t lane = (uint32_t)(idx & 63);
+    const uint64_t tile = idx >> 6;
+    const uint32_t ch = (uint32_t)(tile % n_chunks), rt = (uint32_t)(tile / n_chunks);
+    const uint32_t row = rt * GEMM_ROWS + (lane & 31), c = ch * GEMM_CHUNK + 32 * (lane >> 5);
+    uint4 q = make_uint4(0u, 0u, 0u, 0u);
+    uint16_t m = 0;
+    if (row < rows && c < cols) {
+        const uint64_t e = (uint64_t)row * cols + c;
+        q = codes[e >> 5];
+        m = scales[e >> log2_block];
+    }
+    char* out = packed + tile * GEMM_TILE_BYTES;
+    reinterpret_cast<uint4*>(out)[lane] = q;
+    reinterpret_cast<uint16_t*>(out + 1024)[lane] = m;
+}
+
+// x in the order the products read it, made once per call: for every tile of 32 tokens, chunk of 64 columns and
+// product j one 16-byte word per lane (token = lane % 32 of the tile, columns 32 (lane / 32) + 8 j .. + 7 of the
+// chunk), so that a wave's load is 1 KiB of consecutive memory; zeros past the last token and the last column.
+// With a list also x transposed, xt[column][token] (n_pad tokens per column), for the outlier entries.
+__global__ __launch_bounds__(256) void gemm_pack_x_kernel(const uint16_t* __restrict__ x, uint32_t n_tokens,
+                                                          uint32_t cols, uint32_t n_chunks, uint32_t n_pad,
+                                                          uint4* __restrict__ xp, uint16_t* __restrict__ xt) {
+    const uint64_t idx = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    const uint64_t total = (uint64_t)(n_pad / 32) * n_chunks * 256;
+    if (idx >= total) return;
+    const uint32_t lane = (uint32_t)(idx & 63), j = (uint32_t)((idx >> 6) & 3);
+    const uint64_t tc = idx >> 8;
+    const uint32_t ch = (uint32_t)(tc % n_chunks), tile = (uint32_t)(tc / n_chunks);
+    const uint32_t n = tile * 32 + (lane & 31), c = ch * GEMM_CHUNK + 32 * (lane >> 5) + 8 * j;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (n < n_tokens && c < cols) v = *reinterpret_cast<const uint4*>(x + (uint64_t)n * cols + c);
+    xp[idx] = v;
+    if (xt != nullptr && c < cols) {
+        const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            xt[(uint64_t)(c + i) * n_pad + n] = (uint16_t)(wv[i >> 1] >> (16 * (i & 1)));
+    }
+}
+
+// Workgroup (b, s): rows 32 b .. 32 b + 31, the chunks s * waves + wave, + n_split * waves, ... of the row, NT tiles
+// of 32 tokens (tile0 ..).  Its sum goes to dst[(s * n_tokens + token) * rows + row], token counted from the first
+// of tile0: the result itself when n_split is 1, else one of n_split partial results that gemm_sum_kernel adds.
+// The outlier entries of a row are added by one of the workgroups that share it: per row and token one binary32 chain
+// c = fma(delta, x, c) in list order, added to that workgroup's sum.
+template <int NT, bool OUTLIERS>
 __global__ __launch_bounds__(64 * GEMM_MAX_WAVES) void gemm_kernel(
-    const uint4* __restrict__ codes, const uint16_t* __restrict__ scales, uint32_t rows, uint32_t cols,
-    uint32_t log2_block, CodebookArgs cb, const uint16_t* __restrict__ x, uint32_t n_tokens, float* __restrict__ dst) {
+    const char* __restrict__ packed, uint32_t rows, uint32_t cols, CodebookArgs cb,
+    const uint32_t* __restrict__ strip_ptr, const uint2* __restrict__ entries, uint32_t n_out, uint32_t n_strips,
+    const uint4* __restrict__ xp, const uint16_t* __restrict__ xt, uint32_t n_pad, uint32_t tile0, uint32_t n_tokens,
+    float* __restrict__ dst) {
     struct Shared {
         float tab[16];
-        float red[GEMM_MAX_WAVES * 16 * 64];  // per wave: accumulator register i of lane l at [i * 64 + l]
+        float red[GEMM_MAX_WAVES * 16 * 64];         // per wave: accumulator register i of lane l at [i * 64 + l]
+        float corr[OUTLIERS ? NT * 32 * 32 : 1];     // [tile][row][token]
     };
     __shared__ __attribute__((aligned(16))) Shared sh;
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_waves = blockDim.x >> 6;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, n_waves = blockDim.x >> 6;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     if (tid < 16) sh.tab[tid] = cb.lv32[tid];
     __syncthreads();
     const char* tab = reinterpret_cast<const char*>(sh.tab);
     const uint32_t r0 = blockIdx.x * GEMM_ROWS;
     const uint32_t m = lane & 31, kh = lane >> 5;
-    const uint32_t row = min(r0 + m, rows - 1);  // rows past the matrix repeat its last row and are dropped
-    const bool tok_ok = m < n_tokens;            // lane l also supplies token l % 32
-    const uint16_t* xrow = x + (uint64_t)min(m, n_tokens - 1) * cols;
     const uint32_t n_chunks = (cols + GEMM_CHUNK - 1) / GEMM_CHUNK;
+    const uint32_t stride = gridDim.y * n_waves;
 
-    gemm_f32x16 acc;
+    gemm_f32x16 acc[NT];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
-    for (uint32_t ch = blockIdx.y * n_waves + wave; ch < n_chunks; ch += gridDim.y * n_waves) {
-        const uint32_t c = ch * GEMM_CHUNK + 32 * kh;  // this lane's 32 columns of the chunk
-        const bool valid = c < cols;
-        const uint64_t e = (uint64_t)row * cols + c;
-        const uint4 q = valid ? load_stream(&codes[e >> 5]) : make_uint4(0u, 0u, 0u, 0u);
-        const float msc = valid ? f16_bits_to_f32(__builtin_nontemporal_load(&scales[e >> log2_block])) : 0.0f;
-        uint4 xb[4];
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            xb[j] = (valid && tok_ok) ? *reinterpret_cast<const uint4*>(xrow + c + 8 * j) : make_uint4(0u, 0u, 0u, 0u);
-        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+        for (int i = 0; i < 16; ++i) acc[t][i] = 0.0f;
+
+    // What the chunk after this one needs (codes, constants and - up to 64 tokens, where the registers allow it - x)
+    // is on its way while this one is decoded and multiplied, in two sets of registers used in turn.  Past the last
+    // chunk the last one is read again and not used.
+    constexpr bool X_AHEAD = NT <= 2;
+    struct Operands {
+        uint4 q, xb[NT][4];
+        uint16_t m;
+    };
+    auto fetch_x = [&](Operands& o, uint32_t chunk) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                o.xb[t][j] = xp[((uint64_t)(tile0 + t) * n_chunks + chunk) * 256 + j * 64 + lane];
+    };
+    const char* my_tiles = packed + (uint64_t)blockIdx.x * n_chunks * GEMM_TILE_BYTES;
+    auto fetch = [&](Operands& o, uint32_t chunk) {  // this lane's 32 columns of the chunk
+        const char* tile = my_tiles + (uint64_t)chunk * GEMM_TILE_BYTES;
+        o.q = load_stream(reinterpret_cast<const uint4*>(tile) + lane);
+        o.m = __builtin_nontemporal_load(reinterpret_cast<const uint16_t*>(tile + 1024) + lane);
+        if (X_AHEAD) fetch_x(o, chunk);
+    };
+    auto multiply = [&](Operands& o, uint32_t chunk) {
+        if (!X_AHEAD) fetch_x(o, chunk);
+        const float msc = f16_bits_to_f32(o.m);
+        const uint32_t w[4] = {o.q.x, o.q.y, o.q.z, o.q.w};
+        gemm_bf16x8 A[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             // byte i of `even` = 4 * code of element 2 i of the word, of `odd` = 4 * code of element 2 i + 1
@@ -94,51 +172,119 @@ __global__ __launch_bounds__(64 * GEMM_MAX_WAVES) void gemm_kernel(
                 const float lo = *reinterpret_cast<const float*>(tab + ((odd >> (8 * i)) & 0xffu));
                 a[i] = gemm_pack_bf16(msc * le, msc * lo);  // the decoder's product and rounding
             }
-            gemm_bf16x8 A, B;
-            const uint32_t bw[4] = {xb[j].x, xb[j].y, xb[j].z, xb[j].w};
-            __builtin_memcpy(&A, a, 16);
-            __builtin_memcpy(&B, bw, 16);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B, acc, 0, 0, 0);
+            __builtin_memcpy(&A[j], a, 16);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                gemm_bf16x8 B;
+                const uint32_t bw[4] = {o.xb[t][j].x, o.xb[t][j].y, o.xb[t][j].z, o.xb[t][j].w};
+                __builtin_memcpy(&B, bw, 16);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[j], B, acc[t], 0, 0, 0);
+            }
+    };
+    Operands o0, o1;
+    uint32_t ch = blockIdx.y * n_waves + wave;
+    const uint32_t last = n_chunks - 1;
+    const uint32_t n_iter = ch < n_chunks ? (last - ch) / stride + 1 : 0;
+    fetch(o0, min(ch, last));
+    if (n_iter & 1u) {  // an odd one first, so that the rest goes in pairs
+        multiply(o0, ch);
+        ch += stride;
+        fetch(o0, min(ch, last));
+    }
+    for (uint32_t it = n_iter >> 1; it > 0; --it) {  // o0 holds chunk ch
+        fetch(o1, ch + stride);
+        __builtin_amdgcn_sched_barrier(0);  // the loads first, then the arithmetic
+        multiply(o0, ch);
+        fetch(o0, min(ch + 2 * stride, last));
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(o1, ch + stride);
+        ch += 2 * stride;
+    }
+
+    // The list: row mr of the tile belongs to the workgroup with s = mr % (number of workgroups sharing the tile),
+    // whose waves take their rows in turn.  A wave reads up to 64 entries of the row at once, one per lane, and goes
+    // through them in list order, lane = token: c = fma(delta, x[token][column], c).
+    const uint32_t lists = min(gridDim.y, GEMM_ROWS);
+    const bool with_list = OUTLIERS && blockIdx.y < lists;
+    if (with_list) {
+        constexpr int TG = (NT * 32 + 63) / 64;  // groups of 64 tokens
+        for (uint32_t mr = blockIdx.y + lists * wave; mr < GEMM_ROWS; mr += lists * n_waves) {
+            uint32_t ea = 0, eb = 0;
+            if (r0 + mr < rows) {
+                ea = min(strip_ptr[(uint64_t)(r0 + mr) * n_strips], n_out);
+                eb = min(strip_ptr[(uint64_t)(r0 + mr + 1) * n_strips], n_out);
+            }
+            float c0[TG];
+#pragma unroll
+            for (int g = 0; g < TG; ++g) c0[g] = 0.0f;
+            const uint16_t* xl = xt + tile0 * 32 + lane;
+            for (uint32_t base = ea; base < eb; base += 64) {
+                const uint32_t cnt = min(64u, eb - base);
+                const uint2 en = lane < cnt ? entries[base + lane] : make_uint2(0u, 0u);
+                auto column = [&](uint32_t k) {
+                    return min((uint32_t)__builtin_amdgcn_readlane((int)en.x, (int)k), cols - 1);
+                };
+                auto delta = [&](uint32_t k) {
+                    return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)en.y, (int)k));
+                };
+                uint32_t k = 0;
+                for (; k + 4 <= cnt; k += 4) {  // four loads in flight, the chain in list order
+                    uint16_t xv[4][TG];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const uint16_t* xc = xl + (uint64_t)column(k + u) * n_pad;
+#pragma unroll
+                        for (int g = 0; g < TG; ++g) xv[u][g] = (g * 64 + lane < NT * 32) ? xc[g * 64] : (uint16_t)0;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+#pragma unroll
+                        for (int g = 0; g < TG; ++g) c0[g] = fmaf(delta(k + u), bf16_bits_to_f32(xv[u][g]), c0[g]);
+                }
+                for (; k < cnt; ++k) {
+                    const uint16_t* xc = xl + (uint64_t)column(k) * n_pad;
+#pragma unroll
+                    for (int g = 0; g < TG; ++g)
+                        if (g * 64 + lane < NT * 32) c0[g] = fmaf(delta(k), bf16_bits_to_f32(xc[g * 64]), c0[g]);
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < TG; ++g) {
+                const uint32_t tok = g * 64 + lane;
+                if (tok < NT * 32) sh.corr[((tok >> 5) * 32 + mr) * 32 + (tok & 31)] = c0[g];
+            }
         }
     }
     float* mine = sh.red + wave * 16 * 64;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) mine[i * 64 + lane] = acc[i];
-    __syncthreads();
-    // The waves' results in wave order.  Accumulator i of lane l: row 8 (i / 4) + 4 (l / 32) + i % 4, token l % 32.
     float* out = dst + (uint64_t)blockIdx.y * n_tokens * rows;
-    for (uint32_t idx = tid; idx < 16 * 64; idx += blockDim.x) {
-        float s = 0.0f;
-        for (uint32_t wv = 0; wv < n_waves; ++wv) s += sh.red[wv * 16 * 64 + idx];
-        const uint32_t i = idx >> 6, l = idx & 63;
-        const uint32_t mr = 8 * (i >> 2) + 4 * (l >> 5) + (i & 3u), n = l & 31;
-        if (r0 + mr < rows && n < n_tokens) out[(uint64_t)n * rows + r0 + mr] = s;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        if (t > 0) __syncthreads();  // the sums of the tile before have been read
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mine[i * 64 + lane] = acc[t][i];
+        __syncthreads();
+        // The waves' results in wave order.  Accumulator i of lane l: row 8 (i / 4) + 4 (l / 32) + i % 4, token l % 32.
+        for (uint32_t idx = tid; idx < 16 * 64; idx += blockDim.x) {
+            float s = 0.0f;
+            for (uint32_t wv = 0; wv < n_waves; ++wv) s += sh.red[wv * 16 * 64 + idx];
+            const uint32_t i = idx >> 6, l = idx & 63;
+            const uint32_t mr = 8 * (i >> 2) + 4 * (l >> 5) + (i & 3u), n = 32 * t + (l & 31);
+            if (with_list && mr % lists == blockIdx.y) s += sh.corr[(t * 32 + mr) * 32 + (l & 31)];
+            if (r0 + mr < rows && n < n_tokens) out[(uint64_t)n * rows + r0 + mr] = s;
+        }
     }
 }
 
-// y[token][row] = the n_split partial results in order, then the row's outlier entries in list order, each
-// fma(delta, x[token][column], .) on a sum of their own that is added last.  part may be y itself when n_split is 1.
-__global__ __launch_bounds__(256) void gemm_finish_kernel(const float* part, uint32_t n_split, uint32_t rows,
-                                                          uint32_t cols, uint32_t n_tokens,
-                                                          const uint32_t* __restrict__ strip_ptr,
-                                                          const uint2* __restrict__ entries, uint32_t n_out,
-                                                          uint32_t n_strips, const uint16_t* __restrict__ x,
-                                                          float* y) {
-    const uint64_t idx = (uint64_t)blockIdx.x * 256 + threadIdx.x, total = (uint64_t)n_tokens * rows;
-    if (idx >= total) return;
-    const uint32_t n = (uint32_t)(idx / rows), r = (uint32_t)(idx % rows);
+// y = the n_split partial results in order (count elements each).
+__global__ __launch_bounds__(256) void gemm_sum_kernel(const float* __restrict__ part, uint32_t n_split, uint64_t count,
+                                                       float* __restrict__ y) {
+    const uint64_t idx = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= count) return;
     float s = 0.0f;
-    for (uint32_t k = 0; k < n_split; ++k) s += part[k * total + idx];
-    if (n_out != 0) {
-        const uint32_t ea = min(strip_ptr[(uint64_t)r * n_strips], n_out);
-        const uint32_t eb = min(strip_ptr[(uint64_t)(r + 1) * n_strips], n_out);
-        float c = 0.0f;
-        for (uint32_t k = ea; k < eb; ++k) {
-            const uint2 en = entries[k];
-            c = fmaf(__uint_as_float(en.y), bf16_bits_to_f32(x[(uint64_t)n * cols + min(en.x, cols - 1)]), c);
-        }
-        s += c;
-    }
+    for (uint32_t k = 0; k < n_split; ++k) s += part[k * count + idx];
     y[idx] = s;
 }
 

@@ -26,11 +26,12 @@ def run_gpu(cb, codes, scales, oi, ov, rows, cols, block, x):
     cd = torch.from_numpy(codes).to(DEV)
     sd = dev_u16(scales)
     k = 0 if oi is None else int(oi.size)
+    packed = binding.bof4_gemm_pack(cd, sd, rows, cols, block)
     if k:
         tab = binding.bof4_gemm_outlier_table(cd, sd, rows, cols, block, cb, dev_i64(oi), dev_u16(ov))
-        y = binding.bof4_gemm(cd, sd, rows, cols, block, cb, x.to(DEV), tab, k)
+        y = binding.bof4_gemm(packed, rows, cols, cb, x.to(DEV), tab, k)
     else:
-        y = binding.bof4_gemm(cd, sd, rows, cols, block, cb, x.to(DEV))
+        y = binding.bof4_gemm(packed, rows, cols, cb, x.to(DEV))
     torch.cuda.synchronize()
     return y.cpu().numpy().astype(np.float64)
 
@@ -51,9 +52,11 @@ def check(cb, codes, scales, oi, ov, rows, cols, block, x):
 
 @pytest.mark.parametrize("block", [32, 64, 128, 256])
 @pytest.mark.parametrize("opq", [0, 1])
-@pytest.mark.parametrize("n_tokens", [1, 7, 32, 40])
+@pytest.mark.parametrize("n_tokens", [1, 7, 32, 40, 96, 130, 224])
 def test_gemm_parity(block, opq, n_tokens):
-    rows, cols = 37, 2304  # two row tiles, the second with 5 rows; 36 chunks of 64 columns over 4 workgroups each
+    # two row tiles, the second with 5 rows; 36 chunks of 64 columns over 4 workgroups each; token tiles (of 32) taken
+    # four, two or one at a time
+    rows, cols = 37, 2304
     cb, codes, scales, oi, ov = quantized(rows, cols, block, 1, opq, seed=900 + block)
     check(cb, codes, scales, oi if opq else None, ov if opq else None, rows, cols, block, rand_x(n_tokens, cols, 7))
 
@@ -64,7 +67,9 @@ def test_gemm_shapes(rows, cols):
     """Half a chunk, one chunk, many; the last two have more than 512 row tiles, so that one workgroup takes all columns
     of its rows and the list is applied to the result in place."""
     cb, codes, scales, oi, ov = quantized(rows, cols, 32, 0, 1, seed=31 + rows)
-    assert (binding.bof4_gemm_workspace_bytes(rows, cols, 5) == 0) == (rows > 16000 or cols < 1024)
+    packed_x = 32 * ((cols + 63) // 64 * 64) * 2 + cols * 32 * 2  # in product order and transposed, 32 token slots
+    extra = binding.bof4_gemm_workspace_bytes(rows, cols, 5) - packed_x
+    assert 0 <= extra < 512 if (rows > 16000 or cols < 1024) else extra >= 2 * 32 * rows * 4
     check(cb, codes, scales, oi, ov, rows, cols, 32, rand_x(5, cols, 11))
 
 
@@ -111,8 +116,9 @@ def test_gemm_on_the_quantisers_output_equals_the_product_over_the_decoders_outp
     codes, scales, oi, ov, k = binding.bof4_quantize(w, block, cb, 1, opq_T=T, out_capacity=w.numel() // 20)
     assert k > 0
     tab = binding.bof4_gemm_outlier_table(codes, scales, rows, cols, block, cb, oi, ov, n_outliers=k)
+    packed = binding.bof4_gemm_pack(codes, scales, rows, cols, block)
     x = rand_x(48, cols, 21).to(DEV)
-    y = binding.bof4_gemm(codes, scales, rows, cols, block, cb, x, tab, k)
+    y = binding.bof4_gemm(packed, rows, cols, cb, x, tab, k)
     deq = binding.bof4_dequantize(codes, scales, w.numel(), block, cb, oi, ov, n_outliers=k).reshape(rows, cols)
     ref = x.double() @ deq.double().T
     mag = x.double().abs() @ deq.double().abs().T
@@ -124,21 +130,42 @@ def test_gemm_is_bit_reproducible_and_respects_out_workspace_and_stream():
     cb, codes, scales, oi, ov = quantized(rows, cols, block, 1, 1, seed=80)
     cd, sd, oid, ovd = torch.from_numpy(codes).to(DEV), dev_u16(scales), dev_i64(oi), dev_u16(ov)
     tab = binding.bof4_gemm_outlier_table(cd, sd, rows, cols, block, cb, oid, ovd)
+    packed = binding.bof4_gemm_pack(cd, sd, rows, cols, block)
     x = rand_x(35, cols, 5).to(DEV)
-    y1 = binding.bof4_gemm(cd, sd, rows, cols, block, cb, x, tab, oi.size)
+    y1 = binding.bof4_gemm(packed, rows, cols, cb, x, tab, oi.size)
     out = torch.full((35, rows), float("nan"), device=DEV)
     ws = torch.empty(binding.bof4_gemm_workspace_bytes(rows, cols, 35), dtype=torch.uint8, device=DEV)
-    assert ws.numel() > 0
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
-        y2 = binding.bof4_gemm(cd, sd, rows, cols, block, cb, x, tab, oi.size, out=out, ws=ws)
+        y2 = binding.bof4_gemm(packed, rows, cols, cb, x, tab, oi.size, out=out, ws=ws)
     side.synchronize()
     torch.cuda.synchronize()
     assert y2 is out and torch.equal(y1, y2)
     # one token alone gives the same numbers as inside a batch
-    y3 = binding.bof4_gemm(cd, sd, rows, cols, block, cb, x[33:34].contiguous(), tab, oi.size)
+    y3 = binding.bof4_gemm(packed, rows, cols, cb, x[33:34].contiguous(), tab, oi.size)
     assert torch.equal(y3[0], y1[33])
+
+
+def test_gemm_pack_layout():
+    """Per tile of 32 rows and 64 columns: 64 words of 16 bytes (row lane % 32, columns 32 (lane / 32) .. + 31), then
+    64 constants; zeros past the last row and the last column."""
+    rows, cols, block = 45, 2304 + 32, 32  # a ragged row tile and half a chunk at the end
+    cb, codes, scales, _, _ = quantized(rows, cols, block, 1, 0, seed=83)
+    packed = binding.bof4_gemm_pack(torch.from_numpy(codes).to(DEV), dev_u16(scales), rows, cols, block).cpu().numpy()
+    n_chunks = (cols + 63) // 64
+    assert packed.size == binding.bof4_gemm_packed_bytes(rows, cols) == 2 * n_chunks * (1024 + 128)
+    tiles = packed.reshape(2, n_chunks, 1152)
+    code_rows = codes.reshape(rows, cols // 2)
+    scale_rows = scales.reshape(rows, cols // block)
+    for rt, ch, lane in [(0, 0, 0), (0, 0, 33), (0, 5, 63), (1, 7, 12), (1, 36, 3), (1, 36, 35), (1, 2, 13), (1, 2, 45)]:
+        row, c = rt * 32 + lane % 32, ch * 64 + 32 * (lane // 32)
+        got_q = tiles[rt, ch, 16 * lane: 16 * lane + 16]
+        got_m = tiles[rt, ch, 1024 + 2 * lane: 1024 + 2 * lane + 2].view(np.uint16)[0]
+        if row < rows and c < cols:
+            assert np.array_equal(got_q, code_rows[row, c // 2: c // 2 + 16]) and got_m == scale_rows[row, c // block]
+        else:
+            assert not got_q.any() and got_m == 0
 
 
 def test_gemm_argument_errors():
@@ -147,27 +174,40 @@ def test_gemm_argument_errors():
     cd, sd = torch.from_numpy(codes).to(DEV), dev_u16(scales)
     x = rand_x(3, cols, 1).to(DEV)
     with pytest.raises(binding.Bof4Error) as e:
-        binding.bof4_gemm(cd, sd, rows, 96, 64, cb, x[:, :96].contiguous())
+        binding.bof4_gemm_pack(cd, sd, rows, 96, 64)
     assert e.value.code == binding.BOF4_ERR_ARG
     with pytest.raises(binding.Bof4Error) as e:
-        binding.bof4_gemm(cd, sd, rows, cols, 48, cb, x)
+        binding.bof4_gemm_pack(cd, sd, rows, cols, 48)
     assert e.value.code == binding.BOF4_ERR_ARG
     with pytest.raises(binding.Bof4Error) as e:  # codes not 16-byte aligned
-        binding.bof4_gemm(cd[4:], sd, rows - 1, cols, block, cb, x)
+        binding.bof4_gemm_pack(cd[4:], sd, rows - 1, cols, block)
     assert e.value.code == binding.BOF4_ERR_ARG
-    need = binding.bof4_gemm_workspace_bytes(rows, cols, 3)
-    assert need == 4 * 3 * rows * 4  # 32 chunks of 64 columns: four workgroups of eight waves per row tile
     with pytest.raises(binding.Bof4Error) as e:
-        binding.bof4_gemm(cd, sd, rows, cols, block, cb, x, ws=torch.empty(need - 4, dtype=torch.uint8, device=DEV))
+        binding.bof4_gemm_pack(cd, sd, rows, cols, block, out=torch.empty(1152 * 63, dtype=torch.uint8, device=DEV))
+    assert e.value.code == binding.BOF4_ERR_WORKSPACE
+    packed = binding.bof4_gemm_pack(cd, sd, rows, cols, block)
+    need = binding.bof4_gemm_workspace_bytes(rows, cols, 3)
+    # x twice (in product order and transposed, 32 token slots), then the partial results of four workgroups per row
+    # tile (32 chunks of 64 columns, eight waves each)
+    assert need == 2 * 32 * cols * 2 + 4 * 32 * rows * 4
+    with pytest.raises(binding.Bof4Error) as e:
+        binding.bof4_gemm(packed, rows, cols, cb, x, ws=torch.empty(need - 256, dtype=torch.uint8, device=DEV))
     assert e.value.code == binding.BOF4_ERR_WORKSPACE
     with pytest.raises(ValueError):
-        binding.bof4_gemm(cd, sd, rows, cols, block, cb, x, None, 3)  # outliers without their table
+        binding.bof4_gemm(packed, rows, cols, cb, x, None, 3)  # outliers without their table
     with pytest.raises(ValueError):
-        binding.bof4_gemm(cd, sd, rows, cols, block, cb, x.float())
+        binding.bof4_gemm(packed, rows, cols, cb, x.float())
+    with pytest.raises(ValueError):
+        binding.bof4_gemm(packed, rows + 1, cols, cb, x)  # a packed copy of fewer row tiles
     big = 32768 + 2048
     with pytest.raises(binding.Bof4Error) as e:
-        binding.bof4_gemm(cd, sd, 1, big, 64, cb, torch.zeros((1, big), dtype=torch.bfloat16, device=DEV))
+        binding.bof4_gemm(torch.zeros(binding.bof4_gemm_packed_bytes(1, big), dtype=torch.uint8, device=DEV), 1, big, cb,
+                          torch.zeros((1, big), dtype=torch.bfloat16, device=DEV))
     assert e.value.code == binding.BOF4_ERR_ARG
+    bad_cb = cb.copy()
+    bad_cb[3] = bad_cb[4]
+    with pytest.raises(binding.Bof4Error):
+        binding.bof4_gemm(packed, rows, cols, bad_cb, x)
 
 
 @pytest.mark.parametrize("rows,cols,n_tokens", [(4096, 4096, 32), (4096, 11008, 32), (11008, 4096, 64),
