@@ -205,56 +205,64 @@ __global__ __launch_bounds__(64 * GEMM_MAX_WAVES) void gemm_kernel(
     }
 
     // The list: row mr of the tile belongs to the workgroup with s = mr % (number of workgroups sharing the tile),
-    // whose waves take their rows in turn.  A wave reads up to 64 entries of the row at once, one per lane, and goes
-    // through them in list order, lane = token: c = fma(delta, x[token][column], c).
+    // whose waves take their rows in turn.  Per row and tile of 32 tokens the wave works as 16 slots of 4 lanes: slot
+    // e takes the entries e, e + 16, ... of the row in that order, its lane g the tokens 8 g .. 8 g + 7 (one run of
+    // 16 bytes of x transposed): c[token] = fma(delta, x[token][column], c[token]); then the 16 slots' sums are added
+    // pairwise (slots 1, 2, 4, 8 apart).
     const uint32_t lists = min(gridDim.y, GEMM_ROWS);
     const bool with_list = OUTLIERS && blockIdx.y < lists;
     if (with_list) {
-        constexpr int TG = (NT * 32 + 63) / 64;  // groups of 64 tokens
+        const uint32_t slot = lane >> 2, g = lane & 3;
         for (uint32_t mr = blockIdx.y + lists * wave; mr < GEMM_ROWS; mr += lists * n_waves) {
             uint32_t ea = 0, eb = 0;
             if (r0 + mr < rows) {
                 ea = min(strip_ptr[(uint64_t)(r0 + mr) * n_strips], n_out);
                 eb = min(strip_ptr[(uint64_t)(r0 + mr + 1) * n_strips], n_out);
             }
-            float c0[TG];
+            float c[NT][8];
 #pragma unroll
-            for (int g = 0; g < TG; ++g) c0[g] = 0.0f;
-            const uint16_t* xl = xt + tile0 * 32 + lane;
-            for (uint32_t base = ea; base < eb; base += 64) {
-                const uint32_t cnt = min(64u, eb - base);
-                const uint2 en = lane < cnt ? entries[base + lane] : make_uint2(0u, 0u);
-                auto column = [&](uint32_t k) {
-                    return min((uint32_t)__builtin_amdgcn_readlane((int)en.x, (int)k), cols - 1);
-                };
-                auto delta = [&](uint32_t k) {
-                    return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)en.y, (int)k));
-                };
-                uint32_t k = 0;
-                for (; k + 4 <= cnt; k += 4) {  // four loads in flight, the chain in list order
-                    uint16_t xv[4][TG];
+            for (int t = 0; t < NT; ++t)
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const uint16_t* xc = xl + (uint64_t)column(k + u) * n_pad;
+                for (int i = 0; i < 8; ++i) c[t][i] = 0.0f;
+            const uint16_t* xg = xt + tile0 * 32 + 8 * g;
+            constexpr int U = 8 / NT;  // entries per lane and round: 8 loads of x in flight per lane
+            for (uint32_t k0 = ea + slot; k0 < eb; k0 += 16 * U) {
+                uint2 en[U];
 #pragma unroll
-                        for (int g = 0; g < TG; ++g) xv[u][g] = (g * 64 + lane < NT * 32) ? xc[g * 64] : (uint16_t)0;
+                for (int u = 0; u < U; ++u) en[u] = entries[min(k0 + 16 * u, eb - 1)];  // past the row: read, not used
+                uint4 xv[U][NT];
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int t = 0; t < NT; ++t)
+                        xv[u][t] = *reinterpret_cast<const uint4*>(xg + (uint64_t)min(en[u].x, cols - 1) * n_pad + 32 * t);
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const bool ok = k0 + 16 * u < eb;
+                    const float delta = __uint_as_float(en[u].y);
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        const uint32_t wv[4] = {xv[u][t].x, xv[u][t].y, xv[u][t].z, xv[u][t].w};
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float lo = fmaf(delta, __uint_as_float(wv[i] << 16), c[t][2 * i]);
+                            const float hi = fmaf(delta, __uint_as_float(wv[i] & 0xffff0000u), c[t][2 * i + 1]);
+                            c[t][2 * i] = ok ? lo : c[t][2 * i];
+                            c[t][2 * i + 1] = ok ? hi : c[t][2 * i + 1];
+                        }
                     }
-#pragma unroll
-                    for (int u = 0; u < 4; ++u)
-#pragma unroll
-                        for (int g = 0; g < TG; ++g) c0[g] = fmaf(delta(k + u), bf16_bits_to_f32(xv[u][g]), c0[g]);
-                }
-                for (; k < cnt; ++k) {
-                    const uint16_t* xc = xl + (uint64_t)column(k) * n_pad;
-#pragma unroll
-                    for (int g = 0; g < TG; ++g)
-                        if (g * 64 + lane < NT * 32) c0[g] = fmaf(delta(k), bf16_bits_to_f32(xc[g * 64]), c0[g]);
                 }
             }
 #pragma unroll
-            for (int g = 0; g < TG; ++g) {
-                const uint32_t tok = g * 64 + lane;
-                if (tok < NT * 32) sh.corr[((tok >> 5) * 32 + mr) * 32 + (tok & 31)] = c0[g];
+            for (int t = 0; t < NT; ++t) {
+#pragma unroll
+                for (int mask = 4; mask <= 32; mask <<= 1)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) c[t][i] += __shfl_xor(c[t][i], mask, 64);
+                if (slot == 0) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) sh.corr[(t * 32 + mr) * 32 + 8 * g + i] = c[t][i];
+                }
             }
         }
     }
