@@ -1000,11 +1000,20 @@ int outlier_table_impl(bool rounded, const uint8_t* codes_dev, const uint16_t* s
     return BOF4_OK;
 }
 
-// How many workgroups share the columns of one 32-row tile: enough to put GEMM_TARGET_WGS workgroups on the chip,
-// each with at least one chunk per wave.
-uint32_t gemm_split(uint64_t rows, uint64_t cols) {
-    const uint64_t tiles = (rows + GEMM_ROWS - 1) / GEMM_ROWS, chunks = (cols + GEMM_CHUNK - 1) / GEMM_CHUNK;
-    uint64_t split = (GEMM_TARGET_WGS + tiles - 1) / tiles;
+// Tiles of 32 rows per wave: with two, every word of x read serves 64 rows, at twice the accumulators.  Measured
+// better for more than 32 tokens on all but small matrices, and for very large ones at any number of tokens.
+uint32_t gemm_row_tiles_per_wg(uint64_t rows, uint64_t cols, uint64_t n_tokens) {
+    return ((n_tokens > GEMM_TOKENS && (rows >= 8192 || cols >= 8192)) || rows * cols >= (1ull << 27)) ? 2 : 1;
+}
+uint64_t gemm_row_tiles(uint64_t rows) {  // in the packed matrix: a multiple of GEMM_MAX_R
+    return (rows + GEMM_ROWS * GEMM_MAX_R - 1) / (GEMM_ROWS * GEMM_MAX_R) * GEMM_MAX_R;
+}
+// How many workgroups share the columns of their rows: enough to put GEMM_TARGET_WGS workgroups on the chip, each
+// with at least one chunk per wave.
+uint32_t gemm_split(uint64_t rows, uint64_t cols, uint64_t n_tokens) {
+    const uint64_t groups = gemm_row_tiles(rows) / gemm_row_tiles_per_wg(rows, cols, n_tokens);
+    const uint64_t chunks = (cols + GEMM_CHUNK - 1) / GEMM_CHUNK;
+    uint64_t split = (GEMM_TARGET_WGS + groups - 1) / groups;
     const uint64_t most = chunks / GEMM_MAX_WAVES;
     if (split > most) split = most;
     return (uint32_t)(split < 1 ? 1 : split);
@@ -1017,7 +1026,7 @@ struct GemmWsLayout {
 };
 GemmWsLayout gemm_ws_layout(uint64_t rows, uint64_t cols, uint64_t n_tokens) {
     const uint64_t n_pad = (n_tokens + GEMM_TOKENS - 1) / GEMM_TOKENS * GEMM_TOKENS;
-    const uint64_t chunks = (cols + GEMM_CHUNK - 1) / GEMM_CHUNK, split = gemm_split(rows, cols);
+    const uint64_t chunks = (cols + GEMM_CHUNK - 1) / GEMM_CHUNK, split = gemm_split(rows, cols, n_tokens);
     const uint64_t per_launch = n_pad < GEMM_TOKENS * GEMM_MAX_TILES ? n_pad : GEMM_TOKENS * GEMM_MAX_TILES;
     GemmWsLayout L;
     L.xp = 0;
@@ -1052,7 +1061,7 @@ size_t bof4_gemm_workspace_bytes(uint64_t rows, uint64_t cols, uint32_t n_tokens
 }
 
 size_t bof4_gemm_packed_bytes(uint64_t rows, uint64_t cols) {
-    return (size_t)(((rows + GEMM_ROWS - 1) / GEMM_ROWS) * ((cols + GEMM_CHUNK - 1) / GEMM_CHUNK) * GEMM_TILE_BYTES);
+    return (size_t)(gemm_row_tiles(rows) * ((cols + GEMM_CHUNK - 1) / GEMM_CHUNK) * GEMM_TILE_BYTES);
 }
 
 int bof4_gemm_pack(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t rows, uint64_t cols, uint32_t block,
@@ -1069,7 +1078,7 @@ int bof4_gemm_pack(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_
     uint32_t log2_block = 5;
     while ((1u << log2_block) < block) ++log2_block;
     const uint32_t chunks = (uint32_t)((cols + GEMM_CHUNK - 1) / GEMM_CHUNK);
-    const uint64_t n_tiles = ((rows + GEMM_ROWS - 1) / GEMM_ROWS) * chunks;
+    const uint64_t n_tiles = gemm_row_tiles(rows) * chunks;
     hipLaunchKernelGGL(gemm_pack_weights_kernel, dim3((uint32_t)((n_tiles * 64 + 255) / 256)), dim3(256), 0,
                        (hipStream_t)stream, (const uint4*)codes_dev, scales_dev, (uint32_t)rows, (uint32_t)cols,
                        log2_block, chunks, n_tiles, (char*)packed_dev);
@@ -1099,10 +1108,11 @@ int bof4_gemm(const void* packed_dev, uint64_t rows, uint64_t cols, const double
         table_dev ? (const uint2*)((const char*)table_dev + gemv_table_layout(rows, strips, n_outliers).entries) : nullptr;
     hipStream_t s = (hipStream_t)stream;
     const CodebookArgs cb = make_codebook_args(cb_host);
-    const uint32_t split = gemm_split(rows, cols);
+    const uint32_t split = gemm_split(rows, cols, n_tokens);
     const uint32_t chunks = (uint32_t)((cols + GEMM_CHUNK - 1) / GEMM_CHUNK), per_wg = (chunks + split - 1) / split;
     const uint32_t waves = per_wg < GEMM_MAX_WAVES ? per_wg : GEMM_MAX_WAVES;
-    const uint32_t row_tiles = (uint32_t)((rows + GEMM_ROWS - 1) / GEMM_ROWS);
+    const uint32_t per_wg_tiles = gemm_row_tiles_per_wg(rows, cols, n_tokens);
+    const uint32_t row_groups = (uint32_t)(gemm_row_tiles(rows) / per_wg_tiles);
     const uint32_t n_pad = (n_tokens + GEMM_TOKENS - 1) / GEMM_TOKENS * GEMM_TOKENS, tok_tiles = n_pad / GEMM_TOKENS;
     const uint4* xp = (const uint4*)((char*)ws_dev + L.xp);
     const uint16_t* xt = (const uint16_t*)((char*)ws_dev + L.xt);
@@ -1120,15 +1130,19 @@ int bof4_gemm(const void* packed_dev, uint64_t rows, uint64_t cols, const double
         const uint32_t nt = n_tokens - t0 < nt_tiles * GEMM_TOKENS ? n_tokens - t0 : nt_tiles * GEMM_TOKENS;
         float* yt = y_dev + (uint64_t)t0 * rows;
         float* dst = split > 1 ? part : yt;
-#define BOF4_LAUNCH_GEMM(NT_, OUT_)                                                                               \
-    hipLaunchKernelGGL((gemm_kernel<NT_, OUT_>), dim3(row_tiles, split), dim3(64 * waves), 0, s,                  \
+#define BOF4_LAUNCH_GEMM(R_, NT_, OUT_)                                                                           \
+    hipLaunchKernelGGL((gemm_kernel<R_, NT_, OUT_>), dim3(row_groups, split), dim3(64 * waves), 0, s,             \
                        (const char*)packed_dev, (uint32_t)rows, (uint32_t)cols, cb, offsets_dev, entries_dev,     \
                        (uint32_t)n_outliers, (uint32_t)strips, xp, xt, n_pad, tile0, nt, dst);
+#define BOF4_LAUNCH_GEMM_NT(R_, OUT_)                                                                             \
+    if (nt_tiles == 4) { BOF4_LAUNCH_GEMM(R_, 4, OUT_) } else if (nt_tiles == 2) { BOF4_LAUNCH_GEMM(R_, 2, OUT_) } \
+    else { BOF4_LAUNCH_GEMM(R_, 1, OUT_) }
         if (n_outliers > 0) {
-            if (nt_tiles == 4) { BOF4_LAUNCH_GEMM(4, true) } else if (nt_tiles == 2) { BOF4_LAUNCH_GEMM(2, true) } else { BOF4_LAUNCH_GEMM(1, true) }
+            if (per_wg_tiles == 2) { BOF4_LAUNCH_GEMM_NT(2, true) } else { BOF4_LAUNCH_GEMM_NT(1, true) }
         } else {
-            if (nt_tiles == 4) { BOF4_LAUNCH_GEMM(4, false) } else if (nt_tiles == 2) { BOF4_LAUNCH_GEMM(2, false) } else { BOF4_LAUNCH_GEMM(1, false) }
+            if (per_wg_tiles == 2) { BOF4_LAUNCH_GEMM_NT(2, false) } else { BOF4_LAUNCH_GEMM_NT(1, false) }
         }
+#undef BOF4_LAUNCH_GEMM_NT
 #undef BOF4_LAUNCH_GEMM
         if (split > 1) {
             const uint64_t count = (uint64_t)nt * rows;

@@ -29,7 +29,8 @@
 
 namespace bof4 {
 
-constexpr uint32_t GEMM_ROWS = 32;    // rows per workgroup (M of the matrix-core product)
+constexpr uint32_t GEMM_ROWS = 32;    // rows per tile (M of the matrix-core product)
+constexpr uint32_t GEMM_MAX_R = 2;    // tiles of rows per workgroup: each word of x read serves up to 64 rows
 constexpr uint32_t GEMM_TOKENS = 32;  // tokens per tile (N of the matrix-core product)
 constexpr uint32_t GEMM_MAX_TILES = 4;  // token tiles per launch: the codes are decoded once per 128 tokens
 constexpr uint32_t GEMM_CHUNK = 64;   // columns per wave and step: four products of K = 16
@@ -101,12 +102,12 @@ __global__ __launch_bounds__(256) void gemm_pack_x_kernel(const uint16_t* __rest
     }
 }
 
-// Workgroup (b, s): rows 32 b .. 32 b + 31, the chunks s * waves + wave, + n_split * waves, ... of the row, NT tiles
-// of 32 tokens (tile0 ..).  Its sum goes to dst[(s * n_tokens + token) * rows + row], token counted from the first
-// of tile0: the result itself when n_split is 1, else one of n_split partial results that gemm_sum_kernel adds.
-// The outlier entries of a row are added by one of the workgroups that share it: per row and token one binary32 chain
-// c = fma(delta, x, c) in list order, added to that workgroup's sum.
-template <int NT, bool OUTLIERS>
+// Workgroup (b, s): R tiles of 32 rows (32 R b ..), the chunks s * waves + wave, + n_split * waves, ... of the row,
+// NT tiles of 32 tokens (tile0 ..).  Its sum goes to dst[(s * n_tokens + token) * rows + row], token counted from
+// the first of tile0: the result itself when n_split is 1, else one of n_split partial results that gemm_sum_kernel
+// adds.  The outlier entries of a row are added by one of the workgroups that share it, to that workgroup's sum.
+// The packed matrix holds a multiple of GEMM_MAX_R row tiles.
+template <int R, int NT, bool OUTLIERS>
 __global__ __launch_bounds__(64 * GEMM_MAX_WAVES) void gemm_kernel(
     const char* __restrict__ packed, uint32_t rows, uint32_t cols, CodebookArgs cb,
     const uint32_t* __restrict__ strip_ptr, const uint2* __restrict__ entries, uint32_t n_out, uint32_t n_strips,
@@ -115,7 +116,7 @@ __global__ __launch_bounds__(64 * GEMM_MAX_WAVES) void gemm_kernel(
     struct Shared {
         float tab[16];
         float red[GEMM_MAX_WAVES * 16 * 64];         // per wave: accumulator register i of lane l at [i * 64 + l]
-        float corr[OUTLIERS ? NT * 32 * 32 : 1];     // [tile][row][token]
+        float corr[OUTLIERS ? NT * 32 * 32 : 1];     // [token tile][row][token] of one tile of rows
     };
     __shared__ __attribute__((aligned(16))) Shared sh;
     const uint32_t tid = threadIdx.x, lane = tid & 63, n_waves = blockDim.x >> 6;
@@ -123,24 +124,24 @@ __global__ __launch_bounds__(64 * GEMM_MAX_WAVES) void gemm_kernel(
     if (tid < 16) sh.tab[tid] = cb.lv32[tid];
     __syncthreads();
     const char* tab = reinterpret_cast<const char*>(sh.tab);
-    const uint32_t r0 = blockIdx.x * GEMM_ROWS;
-    const uint32_t m = lane & 31, kh = lane >> 5;
     const uint32_t n_chunks = (cols + GEMM_CHUNK - 1) / GEMM_CHUNK;
     const uint32_t stride = gridDim.y * n_waves;
 
-    gemm_f32x16 acc[NT];
+    gemm_f32x16 acc[R][NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+    for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[t][i] = 0.0f;
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[r][t][i] = 0.0f;
 
-    // What the chunk after this one needs (codes, constants and - up to 64 tokens, where the registers allow it - x)
-    // is on its way while this one is decoded and multiplied, in two sets of registers used in turn.  Past the last
-    // chunk the last one is read again and not used.
-    constexpr bool X_AHEAD = NT <= 2;
+    // What the chunk after this one needs (codes, constants and - where the registers allow it - x) is on its way
+    // while this one is decoded and multiplied, in two sets of registers used in turn.  Past the last chunk the last
+    // one is read again and not used.
+    constexpr bool X_AHEAD = R * NT <= 2;
     struct Operands {
-        uint4 q, xb[NT][4];
-        uint16_t m;
+        uint4 q[R], xb[NT][4];
+        uint16_t m[R];
     };
     auto fetch_x = [&](Operands& o, uint32_t chunk) {
 #pragma unroll
@@ -149,40 +150,46 @@ __global__ __launch_bounds__(64 * GEMM_MAX_WAVES) void gemm_kernel(
             for (int j = 0; j < 4; ++j)
                 o.xb[t][j] = xp[((uint64_t)(tile0 + t) * n_chunks + chunk) * 256 + j * 64 + lane];
     };
-    const char* my_tiles = packed + (uint64_t)blockIdx.x * n_chunks * GEMM_TILE_BYTES;
-    auto fetch = [&](Operands& o, uint32_t chunk) {  // this lane's 32 columns of the chunk
-        const char* tile = my_tiles + (uint64_t)chunk * GEMM_TILE_BYTES;
-        o.q = load_stream(reinterpret_cast<const uint4*>(tile) + lane);
-        o.m = __builtin_nontemporal_load(reinterpret_cast<const uint16_t*>(tile + 1024) + lane);
+    const char* my_tiles = packed + (uint64_t)blockIdx.x * R * n_chunks * GEMM_TILE_BYTES;
+    auto fetch = [&](Operands& o, uint32_t chunk) {  // this lane's 32 columns of the chunk, in each tile of rows
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const char* tile = my_tiles + ((uint64_t)r * n_chunks + chunk) * GEMM_TILE_BYTES;
+            o.q[r] = load_stream(reinterpret_cast<const uint4*>(tile) + lane);
+            o.m[r] = __builtin_nontemporal_load(reinterpret_cast<const uint16_t*>(tile + 1024) + lane);
+        }
         if (X_AHEAD) fetch_x(o, chunk);
     };
     auto multiply = [&](Operands& o, uint32_t chunk) {
         if (!X_AHEAD) fetch_x(o, chunk);
-        const float msc = f16_bits_to_f32(o.m);
-        const uint32_t w[4] = {o.q.x, o.q.y, o.q.z, o.q.w};
-        gemm_bf16x8 A[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            // byte i of `even` = 4 * code of element 2 i of the word, of `odd` = 4 * code of element 2 i + 1
-            const uint32_t even = (w[j] << 2) & 0x3c3c3c3cu, odd = (w[j] >> 2) & 0x3c3c3c3cu;
-            uint32_t a[4];
+        for (int r = 0; r < R; ++r) {
+            const float msc = f16_bits_to_f32(o.m[r]);
+            const uint32_t w[4] = {o.q[r].x, o.q[r].y, o.q[r].z, o.q[r].w};
+            gemm_bf16x8 A[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float le = *reinterpret_cast<const float*>(tab + ((even >> (8 * i)) & 0xffu));
-                const float lo = *reinterpret_cast<const float*>(tab + ((odd >> (8 * i)) & 0xffu));
-                a[i] = gemm_pack_bf16(msc * le, msc * lo);  // the decoder's product and rounding
+            for (int j = 0; j < 4; ++j) {
+                // byte i of `even` = 4 * code of element 2 i of the word, of `odd` = 4 * code of element 2 i + 1
+                const uint32_t even = (w[j] << 2) & 0x3c3c3c3cu, odd = (w[j] >> 2) & 0x3c3c3c3cu;
+                uint32_t a[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float le = *reinterpret_cast<const float*>(tab + ((even >> (8 * i)) & 0xffu));
+                    const float lo = *reinterpret_cast<const float*>(tab + ((odd >> (8 * i)) & 0xffu));
+                    a[i] = gemm_pack_bf16(msc * le, msc * lo);  // the decoder's product and rounding
+                }
+                __builtin_memcpy(&A[j], a, 16);
             }
-            __builtin_memcpy(&A[j], a, 16);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    gemm_bf16x8 B;
+                    const uint32_t bw[4] = {o.xb[t][j].x, o.xb[t][j].y, o.xb[t][j].z, o.xb[t][j].w};
+                    __builtin_memcpy(&B, bw, 16);
+                    acc[r][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[j], B, acc[r][t], 0, 0, 0);
+                }
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                gemm_bf16x8 B;
-                const uint32_t bw[4] = {o.xb[t][j].x, o.xb[t][j].y, o.xb[t][j].z, o.xb[t][j].w};
-                __builtin_memcpy(&B, bw, 16);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[j], B, acc[t], 0, 0, 0);
-            }
     };
     Operands o0, o1;
     uint32_t ch = blockIdx.y * n_waves + wave;
@@ -204,84 +211,91 @@ __global__ __launch_bounds__(64 * GEMM_MAX_WAVES) void gemm_kernel(
         ch += 2 * stride;
     }
 
-    // The list: row mr of the tile belongs to the workgroup with s = mr % (number of workgroups sharing the tile),
-    // whose waves take their rows in turn.  Per row and tile of 32 tokens the wave works as 16 slots of 4 lanes: slot
-    // e takes the entries e, e + 16, ... of the row in that order, its lane g the tokens 8 g .. 8 g + 7 (one run of
-    // 16 bytes of x transposed): c[token] = fma(delta, x[token][column], c[token]); then the 16 slots' sums are added
-    // pairwise (slots 1, 2, 4, 8 apart).
     const uint32_t lists = min(gridDim.y, GEMM_ROWS);
     const bool with_list = OUTLIERS && blockIdx.y < lists;
-    if (with_list) {
-        const uint32_t slot = lane >> 2, g = lane & 3;
-        for (uint32_t mr = blockIdx.y + lists * wave; mr < GEMM_ROWS; mr += lists * n_waves) {
-            uint32_t ea = 0, eb = 0;
-            if (r0 + mr < rows) {
-                ea = min(strip_ptr[(uint64_t)(r0 + mr) * n_strips], n_out);
-                eb = min(strip_ptr[(uint64_t)(r0 + mr + 1) * n_strips], n_out);
-            }
-            float c[NT][8];
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-#pragma unroll
-                for (int i = 0; i < 8; ++i) c[t][i] = 0.0f;
-            const uint16_t* xg = xt + tile0 * 32 + 8 * g;
-            constexpr int U = 8 / NT;  // entries per lane and round: 8 loads of x in flight per lane
-            for (uint32_t k0 = ea + slot; k0 < eb; k0 += 16 * U) {
-                uint2 en[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) en[u] = entries[min(k0 + 16 * u, eb - 1)];  // past the row: read, not used
-                uint4 xv[U][NT];
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-#pragma unroll
-                    for (int t = 0; t < NT; ++t)
-                        xv[u][t] = *reinterpret_cast<const uint4*>(xg + (uint64_t)min(en[u].x, cols - 1) * n_pad + 32 * t);
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const bool ok = k0 + 16 * u < eb;
-                    const float delta = __uint_as_float(en[u].y);
-#pragma unroll
-                    for (int t = 0; t < NT; ++t) {
-                        const uint32_t wv[4] = {xv[u][t].x, xv[u][t].y, xv[u][t].z, xv[u][t].w};
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const float lo = fmaf(delta, __uint_as_float(wv[i] << 16), c[t][2 * i]);
-                            const float hi = fmaf(delta, __uint_as_float(wv[i] & 0xffff0000u), c[t][2 * i + 1]);
-                            c[t][2 * i] = ok ? lo : c[t][2 * i];
-                            c[t][2 * i + 1] = ok ? hi : c[t][2 * i + 1];
-                        }
-                    }
-                }
-            }
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-#pragma unroll
-                for (int mask = 4; mask <= 32; mask <<= 1)
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) c[t][i] += __shfl_xor(c[t][i], mask, 64);
-                if (slot == 0) {
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) sh.corr[(t * 32 + mr) * 32 + 8 * g + i] = c[t][i];
-                }
-            }
-        }
-    }
     float* mine = sh.red + wave * 16 * 64;
     float* out = dst + (uint64_t)blockIdx.y * n_tokens * rows;
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        if (t > 0) __syncthreads();  // the sums of the tile before have been read
+    for (int r = 0; r < R; ++r) {
+        const uint32_t r0 = (blockIdx.x * R + r) * GEMM_ROWS;
+        // The list: row mr of the tile belongs to the workgroup with s = mr % (number of workgroups sharing the
+        // tile), whose waves take their rows in turn.  Per row the wave works as 16 slots of 4 lanes: slot e takes the
+        // entries e, e + 16, ... of the row in that order, its lane g the tokens 8 g .. 8 g + 7 of every token tile
+        // (runs of 16 bytes of x transposed): c[token] = fma(delta, x[token][column], c[token]); then the 16 slots'
+        // sums are added pairwise (slots 1, 2, 4, 8 apart).
+        if (with_list) {
+            if (r > 0) __syncthreads();  // the corrections of the tile of rows before have been read
+            const uint32_t slot = lane >> 2, g = lane & 3;
+            for (uint32_t mr = blockIdx.y + lists * wave; mr < GEMM_ROWS; mr += lists * n_waves) {
+                uint32_t ea = 0, eb = 0;
+                if (r0 + mr < rows) {
+                    ea = min(strip_ptr[(uint64_t)(r0 + mr) * n_strips], n_out);
+                    eb = min(strip_ptr[(uint64_t)(r0 + mr + 1) * n_strips], n_out);
+                }
+                float c[NT][8];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) mine[i * 64 + lane] = acc[t][i];
-        __syncthreads();
-        // The waves' results in wave order.  Accumulator i of lane l: row 8 (i / 4) + 4 (l / 32) + i % 4, token l % 32.
-        for (uint32_t idx = tid; idx < 16 * 64; idx += blockDim.x) {
-            float s = 0.0f;
-            for (uint32_t wv = 0; wv < n_waves; ++wv) s += sh.red[wv * 16 * 64 + idx];
-            const uint32_t i = idx >> 6, l = idx & 63;
-            const uint32_t mr = 8 * (i >> 2) + 4 * (l >> 5) + (i & 3u), n = 32 * t + (l & 31);
-            if (with_list && mr % lists == blockIdx.y) s += sh.corr[(t * 32 + mr) * 32 + (l & 31)];
-            if (r0 + mr < rows && n < n_tokens) out[(uint64_t)n * rows + r0 + mr] = s;
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) c[t][i] = 0.0f;
+                const uint16_t* xg = xt + tile0 * 32 + 8 * g;
+                constexpr int U = 8 / NT;  // entries per lane and round: 8 loads of x in flight per lane
+                for (uint32_t k0 = ea + slot; k0 < eb; k0 += 16 * U) {
+                    uint2 en[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) en[u] = entries[min(k0 + 16 * u, eb - 1)];  // past the row: not used
+                    uint4 xv[U][NT];
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+#pragma unroll
+                        for (int t = 0; t < NT; ++t)
+                            xv[u][t] = *reinterpret_cast<const uint4*>(xg + (uint64_t)min(en[u].x, cols - 1) * n_pad +
+                                                                       32 * t);
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const bool ok = k0 + 16 * u < eb;
+                        const float delta = __uint_as_float(en[u].y);
+#pragma unroll
+                        for (int t = 0; t < NT; ++t) {
+                            const uint32_t wv[4] = {xv[u][t].x, xv[u][t].y, xv[u][t].z, xv[u][t].w};
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const float lo = fmaf(delta, __uint_as_float(wv[i] << 16), c[t][2 * i]);
+                                const float hi = fmaf(delta, __uint_as_float(wv[i] & 0xffff0000u), c[t][2 * i + 1]);
+                                c[t][2 * i] = ok ? lo : c[t][2 * i];
+                                c[t][2 * i + 1] = ok ? hi : c[t][2 * i + 1];
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+#pragma unroll
+                    for (int mask = 4; mask <= 32; mask <<= 1)
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) c[t][i] += __shfl_xor(c[t][i], mask, 64);
+                    if (slot == 0) {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) sh.corr[(t * 32 + mr) * 32 + 8 * g + i] = c[t][i];
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            if (r > 0 || t > 0) __syncthreads();  // the sums of the round before have been read
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mine[i * 64 + lane] = acc[r][t][i];
+            __syncthreads();
+            // The waves' results in wave order.  Accumulator i of lane l: row 8 (i / 4) + 4 (l / 32) + i % 4 of the
+            // tile, token l % 32.
+            for (uint32_t idx = tid; idx < 16 * 64; idx += blockDim.x) {
+                float s = 0.0f;
+                for (uint32_t wv = 0; wv < n_waves; ++wv) s += sh.red[wv * 16 * 64 + idx];
+                const uint32_t i = idx >> 6, l = idx & 63;
+                const uint32_t mr = 8 * (i >> 2) + 4 * (l >> 5) + (i & 3u), n = 32 * t + (l & 31);
+                if (with_list && mr % lists == blockIdx.y) s += sh.corr[(t * 32 + mr) * 32 + (l & 31)];
+                if (r0 + mr < rows && n < n_tokens) out[(uint64_t)n * rows + r0 + mr] = s;
+            }
         }
     }
 }

@@ -73,16 +73,28 @@ def test_gemm_shapes(rows, cols):
     check(cb, codes, scales, oi, ov, rows, cols, 32, rand_x(5, cols, 11))
 
 
-@pytest.mark.parametrize("rows,cols,n_tokens", [(70, 1536, 33), (16390, 128, 9)])
+@pytest.mark.parametrize("rows,cols,n_tokens", [(33, 32768, 40), (70, 8192, 130), (16390, 128, 70)])
+def test_gemm_with_two_tiles_of_rows_per_wave(rows, cols, n_tokens):
+    """More than 32 tokens on a matrix with 8192 or more rows or columns: a wave multiplies two tiles of 32 rows with
+    every word of x it reads.  Row counts that leave the second tile nearly empty, absent (an odd number of tiles)
+    or ragged."""
+    cb, codes, scales, oi, ov = quantized(rows, cols, 64, 1, 1, seed=41 + rows)
+    check(cb, codes, scales, oi, ov, rows, cols, 64, rand_x(n_tokens, cols, 13))
+    check(cb, codes, scales, None, None, rows, cols, 64, rand_x(n_tokens, cols, 14))
+
+
+@pytest.mark.parametrize("rows,cols,n_tokens", [(70, 1536, 33), (16390, 128, 9), (16390, 128, 45), (70, 8192, 33)])
 def test_gemm_is_exact_where_every_partial_sum_is_a_binary32_number(rows, cols, n_tokens):
     """Levels k / 8, constants 2^e, x small integers, list values multiples of 1 / 8: every product and every sum of
-    them is a multiple of 2^-9 below 2^15, so no addition rounds, in any order."""
+    them is a multiple of 2^-9 below 2^15, so no addition rounds, in any order.  (The last two cases take two tiles
+    of rows per wave.)"""
     block = 32
     rng = np.random.default_rng(rows)
     cb = (np.arange(16) - 8) / 8.0
     codes = rng.integers(0, 256, rows * cols // 2, dtype=np.uint8)
-    scales = (2.0 ** rng.integers(-6, 3, rows * cols // block)).astype(np.float16).view(np.uint16)
-    x = torch.from_numpy(rng.integers(-4, 5, (n_tokens, cols)).astype(np.float32)).to(torch.bfloat16)
+    top, xmax = (3, 4) if cols <= 2048 else (1, 2)  # |product| <= 2^(top - 1) * xmax, times cols below 2^15
+    scales = (2.0 ** rng.integers(-6, top, rows * cols // block)).astype(np.float16).view(np.uint16)
+    x = torch.from_numpy(rng.integers(-xmax, xmax + 1, (n_tokens, cols)).astype(np.float32)).to(torch.bfloat16)
     xb = inputs.bits(x).reshape(x.shape)
     oi = np.sort(rng.choice(rows * cols, rows * cols // 300, replace=False)).astype(np.int64)
     ov = (rng.integers(-32, 33, oi.size) / 8.0).astype(np.float16).view(np.uint16)
