@@ -104,6 +104,59 @@ def gemv_shapes(dev, calls=50):
     return rows_out
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def gemm_shapes(dev, calls=30):
+    """bof4_gemm on the matrix shapes of workloads 1 and 4 (Student-t weights, block 64, signed, with and without the
+    OPQ outliers, 32 and 128 tokens): microseconds per call (all its kernels) from HIP events around `calls`
+    back-to-back calls; next to it, on the same decoded matrix, bof4_dequantize and the library's bfloat16 product
+    (torch.matmul), the path the fused call replaces."""
+    cb = codebooks.array(codebooks.BOF4S_MSE[BLOCK])
+    T = binding.bof4_opq_threshold(0.95, BLOCK)
+
+    def timed(f):
+        for _ in range(3):
+            f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(calls):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / calls
+
+    rows_out = []
+    for rows, cols in ((4096, 4096), (12288, 4096), (22016, 4096), (4096, 11008), (8192, 28672), (28672, 8192)):
+        w = inputs.student_t_matrix(rows, cols, 5.0, 0.02, 0.3, seed=rows + cols, device=dev).reshape(-1)
+        n = rows * cols
+        for opq in (0, 1):
+            codes, scales, oi, ov, k = binding.bof4_quantize(w, BLOCK, cb, 1, opq_T=T if opq else 0.0,
+                                                             out_capacity=n // 50 if opq else 0)
+            k = int(k) if opq else 0
+            packed = binding.bof4_gemm_pack(codes, scales, rows, cols, BLOCK)
+            tab = binding.bof4_gemm_outlier_table(codes, scales, rows, cols, BLOCK, cb, oi, ov, n_outliers=k) if k else None
+            deq = torch.empty(n, dtype=torch.bfloat16, device=dev)
+            us_deq = timed(lambda: binding.bof4_dequantize(codes, scales, n, BLOCK, cb, oi, ov, n_outliers=k, out=deq))
+            wm = deq.reshape(rows, cols)
+            for nt in (32, 128):
+                x = torch.randn((nt, cols), device=dev).to(torch.bfloat16)
+                y = torch.empty((nt, rows), dtype=torch.float32, device=dev)
+                ws = torch.empty(binding.bof4_gemm_workspace_bytes(rows, cols, nt), dtype=torch.uint8, device=dev)
+                us = timed(lambda: binding.bof4_gemm(packed, rows, cols, cb, x, tab, k, out=y, ws=ws))
+                us_mm = timed(lambda: torch.matmul(x, wm.T))
+                nbytes = (0.5 + 2.0 / 32) * n * ((nt + 127) // 128) + 8.0 * k
+                rows_out.append({"rows": rows, "cols": cols, "outliers": k, "tokens": nt, "us_per_call": us,
+                                 "GBps_algorithmic": nbytes / us / 1e3, "hbm_frac": nbytes / us / 1e3 / HBM_PEAK_GBS,
+                                 "TFLOPs": 2.0 * n * nt / us / 1e6,
+                                 "mfma_frac": 2.0 * n * nt / us / 1e6 / MFMA_BF16_PEAK_TFLOPS,
+                                 "us_dequantize": us_deq, "us_bf16_matmul_on_decoded": us_mm})
+            del deq, wm, packed
+        del w
+    return rows_out
+
+
 def cpu_baseline(w_samples, cb, T):
     """Oracle (as it stands) on a bounded sample of the same workload; reported baseline only."""
     import oracle
@@ -141,6 +194,8 @@ def main():
                          "enqueued behind the quantiser before the host waits for the outlier count)")
     ap.add_argument("--gemv-shapes", action="store_true",
                     help="instead of the benchmark step: bof4_gemv on a table of matrix shapes, one JSON line")
+    ap.add_argument("--gemm-shapes", action="store_true",
+                    help="instead of the benchmark step: bof4_gemm (32 and 128 tokens) on the same table, one JSON line")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (how the path would shard is part of the design notes)",
@@ -150,6 +205,10 @@ def main():
     if args.gemv_shapes:
         torch.cuda.set_device(dev)
         print(json.dumps({"bof4_gemv": gemv_shapes(dev)}))
+        return
+    if args.gemm_shapes:
+        torch.cuda.set_device(dev)
+        print(json.dumps({"bof4_gemm": gemm_shapes(dev)}))
         return
     torch.cuda.set_device(dev)
     binding.lib()

@@ -42,6 +42,17 @@ typedef __bf16 gemm_bf16x2 __attribute__((ext_vector_type(2)));
 typedef float gemm_f32x2 __attribute__((ext_vector_type(2)));
 typedef float gemm_f32x16 __attribute__((ext_vector_type(16)));
 
+// Sum over each row of 16 lanes, delivered in its lane 15 (the other lanes hold prefixes): shifts by 1, 2, 4, 8.
+__device__ __forceinline__ float row16_sum_lane15(float x) {
+#define BOF4_ROW_SHR_F32(v, ctrl) __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), ctrl, 0xf, 0xf, true))
+    x += BOF4_ROW_SHR_F32(x, 0x111);
+    x += BOF4_ROW_SHR_F32(x, 0x112);
+    x += BOF4_ROW_SHR_F32(x, 0x114);
+    x += BOF4_ROW_SHR_F32(x, 0x118);
+#undef BOF4_ROW_SHR_F32
+    return x;
+}
+
 __device__ __forceinline__ uint32_t gemm_pack_bf16(float lo, float hi) {
     gemm_f32x2 v = {lo, hi};
     gemm_bf16x2 r = __builtin_convertvector(v, gemm_bf16x2);
@@ -161,7 +172,10 @@ __global__ __launch_bounds__(64 * GEMM_MAX_WAVES) void gemm_kernel(
         if (X_AHEAD) fetch_x(o, chunk);
     };
     auto multiply = [&](Operands& o, uint32_t chunk) {
-        if (!X_AHEAD) fetch_x(o, chunk);
+        if (!X_AHEAD) {
+            fetch_x(o, chunk);
+            __builtin_amdgcn_sched_barrier(0);  // x is on its way while the first tile of rows is decoded
+        }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const float msc = f16_bits_to_f32(o.m[r]);
@@ -219,13 +233,13 @@ __global__ __launch_bounds__(64 * GEMM_MAX_WAVES) void gemm_kernel(
     for (int r = 0; r < R; ++r) {
         const uint32_t r0 = (blockIdx.x * R + r) * GEMM_ROWS;
         // The list: row mr of the tile belongs to the workgroup with s = mr % (number of workgroups sharing the
-        // tile), whose waves take their rows in turn.  Per row the wave works as 16 slots of 4 lanes: slot e takes the
-        // entries e, e + 16, ... of the row in that order, its lane g the tokens 8 g .. 8 g + 7 of every token tile
-        // (runs of 16 bytes of x transposed): c[token] = fma(delta, x[token][column], c[token]); then the 16 slots'
-        // sums are added pairwise (slots 1, 2, 4, 8 apart).
+        // tile), whose waves take their rows in turn.  Per row the wave works as 16 slots of 4 lanes (lane = 16 g +
+        // slot): slot e takes the entries e, e + 16, ... of the row in that order, its lane g the tokens 8 g .. 8 g + 7
+        // of every token tile (runs of 16 bytes of x transposed): c[token] = fma(delta, x[token][column], c[token]);
+        // then the 16 slots' sums are added inside their row of 16 lanes (shifts by 1, 2, 4, 8: no LDS traffic).
         if (with_list) {
             if (r > 0) __syncthreads();  // the corrections of the tile of rows before have been read
-            const uint32_t slot = lane >> 2, g = lane & 3;
+            const uint32_t slot = lane & 15, g = lane >> 4;
             for (uint32_t mr = blockIdx.y + lists * wave; mr < GEMM_ROWS; mr += lists * n_waves) {
                 uint32_t ea = 0, eb = 0;
                 if (r0 + mr < rows) {
@@ -270,10 +284,8 @@ __global__ __launch_bounds__(64 * GEMM_MAX_WAVES) void gemm_kernel(
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
 #pragma unroll
-                    for (int mask = 4; mask <= 32; mask <<= 1)
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) c[t][i] += __shfl_xor(c[t][i], mask, 64);
-                    if (slot == 0) {
+                    for (int i = 0; i < 8; ++i) c[t][i] = row16_sum_lane15(c[t][i]);
+                    if (slot == 15) {
 #pragma unroll
                         for (int i = 0; i < 8; ++i) sh.corr[(t * 32 + mr) * 32 + 8 * g + i] = c[t][i];
                     }
