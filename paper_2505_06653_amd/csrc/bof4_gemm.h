@@ -266,17 +266,16 @@ __global__ __launch_bounds__(64 * GEMM_MAX_WAVES) void gemm_kernel(
                                                                        32 * t);
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        const bool ok = k0 + 16 * u < eb;
-                        const float delta = __uint_as_float(en[u].y);
+                        // Past the row's last entry that entry is read again and counts with delta 0.  (Where its
+                        // x is not finite the sum is not finite already.)
+                        const float delta = k0 + 16 * u < eb ? __uint_as_float(en[u].y) : 0.0f;
 #pragma unroll
                         for (int t = 0; t < NT; ++t) {
                             const uint32_t wv[4] = {xv[u][t].x, xv[u][t].y, xv[u][t].z, xv[u][t].w};
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
-                                const float lo = fmaf(delta, __uint_as_float(wv[i] << 16), c[t][2 * i]);
-                                const float hi = fmaf(delta, __uint_as_float(wv[i] & 0xffff0000u), c[t][2 * i + 1]);
-                                c[t][2 * i] = ok ? lo : c[t][2 * i];
-                                c[t][2 * i + 1] = ok ? hi : c[t][2 * i + 1];
+                                c[t][2 * i] = fmaf(delta, __uint_as_float(wv[i] << 16), c[t][2 * i]);
+                                c[t][2 * i + 1] = fmaf(delta, __uint_as_float(wv[i] & 0xffff0000u), c[t][2 * i + 1]);
                             }
                         }
                     }

@@ -139,3 +139,42 @@ def test_argument_validation_of_the_later_entry_points_without_touching_the_gpu(
     assert t(10, 4096 + 64, 7, ws, need - 8) == binding.BOF4_ERR_WORKSPACE
     assert t(10, 4096 + 32, 7, ws, need) == binding.BOF4_ERR_ARG
     assert t(10, 4096 + 64, 7, None, need) == binding.BOF4_ERR_ARG
+
+
+def test_argument_validation_and_size_formulas_of_the_matrix_product_without_touching_the_gpu():
+    """bof4_gemm, bof4_gemm_pack and bof4_gemm_outlier_table refuse bad arguments before any GPU call; the sizes of the
+    packed matrix and of the workspace are host formulas."""
+    L = binding.lib()
+    cbp = CB.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+    bad_cb = CB[::-1].copy()
+    bad_cbp = bad_cb.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+    fake, odd, ws = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004), ctypes.c_void_p(0x10000)
+    # tiles of 32 rows (an even number of them) x chunks of 64 columns, 1024 bytes of codes + 64 constants each
+    assert binding.bof4_gemm_packed_bytes(64, 128) == 2 * 2 * 1152
+    assert binding.bof4_gemm_packed_bytes(65, 96) == 4 * 2 * 1152
+    assert binding.bof4_gemm_packed_bytes(4096, 11008) == 128 * 172 * 1152
+    # x twice, token slots in 32s; partial results only where the rows alone do not give 512 workgroups
+    assert binding.bof4_gemm_workspace_bytes(32768, 4096, 7) == 2 * 32 * 4096 * 2
+    assert binding.bof4_gemm_workspace_bytes(4096, 4096, 40) == 2 * 64 * 4096 * 2 + 4 * 64 * 4096 * 4
+    assert binding.bof4_gemm_workspace_bytes(0, 64, 1) == 0
+    pk = lambda codes, rows, cols, blk, out, nbytes: L.bof4_gemm_pack(codes, fake, rows, cols, blk, out, nbytes, None)
+    assert pk(None, 64, 128, 64, ws, 1 << 20) == binding.BOF4_ERR_ARG
+    assert pk(fake, 64, 96, 64, ws, 1 << 20) == binding.BOF4_ERR_ARG          # cols not a multiple of block
+    assert pk(odd, 64, 128, 64, ws, 1 << 20) == binding.BOF4_ERR_ARG           # codes not 16-byte aligned
+    assert pk(fake, 64, 128, 64, ws, 4 * 1152 - 1) == binding.BOF4_ERR_WORKSPACE
+    assert pk(fake, 64, 32768 + 64, 64, ws, 1 << 30) == binding.BOF4_ERR_ARG
+    g = lambda packed, rows, cols, c, table, k, x, nt, w, wb: L.bof4_gemm(packed, rows, cols, c, table, k, x, nt, fake,
+                                                                           w, wb, None)
+    assert g(None, 64, 128, cbp, None, 0, fake, 1, ws, 1 << 20) == binding.BOF4_ERR_ARG
+    assert g(fake, 64, 80, cbp, None, 0, fake, 1, ws, 1 << 20) == binding.BOF4_ERR_ARG      # cols not a multiple of 32
+    assert g(fake, 64, 128, cbp, None, 0, fake, 0, ws, 1 << 20) == binding.BOF4_ERR_ARG     # no tokens
+    assert g(fake, 64, 128, bad_cbp, None, 0, fake, 1, ws, 1 << 20) == binding.BOF4_ERR_ARG
+    assert g(fake, 64, 128, cbp, None, 3, fake, 1, ws, 1 << 20) == binding.BOF4_ERR_ARG     # outliers without table
+    assert g(odd, 64, 128, cbp, None, 0, fake, 1, ws, 1 << 20) == binding.BOF4_ERR_ARG      # misaligned
+    assert g(fake, 64, 128, cbp, None, 0, fake, 1, None, 1 << 20) == binding.BOF4_ERR_ARG   # no workspace
+    assert g(fake, 64, 128, cbp, None, 0, fake, 1, ws, 100) == binding.BOF4_ERR_WORKSPACE
+    assert g(fake, 64, 128, cbp, None, 0, fake, 70000, ws, 1 << 40) == binding.BOF4_ERR_ARG  # too many tokens
+    t = lambda rows, cols, k, tab, nbytes: L.bof4_gemm_outlier_table(fake, fake, rows, cols, 64, cbp, fake, fake, k, tab, nbytes, None)
+    need = binding.bof4_gemv_outlier_table_bytes(10, 4096 + 64, 7)
+    assert t(10, 4096 + 64, 7, ws, need - 8) == binding.BOF4_ERR_WORKSPACE
+    assert t(10, 4096 + 32, 7, ws, need) == binding.BOF4_ERR_ARG
