@@ -70,6 +70,45 @@ def gemv_block_pass(codes, scales, oidx, oval, k_all, cb, dev, passes=20):
                     "fp32 accumulation), back to back on one stream, outside the timed step"}
 
 
+def gemm_block_pass(codes, scales, oidx, oval, k_all, cb, dev, n_tokens=128, passes=10):
+    """As gemv_block_pass, for 128 tokens at once with bof4_gemm (matrix cores; the matrices packed once)."""
+    mats, off = [], 0
+    idx_all = oidx[:k_all]
+    for name, r, c in (("qkv", 3 * 4096, 4096), ("o", 4096, 4096), ("gate_up", 2 * 11008, 4096), ("down", 4096, 11008)):
+        nw = r * c
+        a, b = (int(v) for v in torch.searchsorted(idx_all, torch.tensor([off, off + nw], device=dev)))
+        k = b - a
+        mc, ms = codes[off // 2:(off + nw) // 2], scales[off // BLOCK:(off + nw) // BLOCK]
+        packed = binding.bof4_gemm_pack(mc, ms, r, c, BLOCK)
+        tab = binding.bof4_gemm_outlier_table(mc, ms, r, c, BLOCK, cb, (idx_all[a:b] - off).contiguous(),
+                                              oval[a:b].contiguous(), n_outliers=k) if k else None
+        off += nw
+        x = torch.randn((n_tokens, c), device=dev).to(torch.bfloat16)
+        y = torch.empty((n_tokens, r), dtype=torch.float32, device=dev)
+        ws = torch.empty(binding.bof4_gemm_workspace_bytes(r, c, n_tokens), dtype=torch.uint8, device=dev)
+        mats.append((r, c, packed, tab, k, x, y, ws))
+    def one_pass():
+        for r, c, packed, tab, k, x, y, ws in mats:
+            binding.bof4_gemm(packed, r, c, cb, x, tab, k, out=y, ws=ws)
+    for _ in range(3):
+        one_pass()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(passes):
+        one_pass()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / passes
+    flops = sum(2.0 * r * c * n_tokens for r, c, *_ in mats)
+    return {"ms": ms, "tokens": n_tokens, "TFLOPs": flops / (ms * 1e-3) / 1e12,
+            "mfma_frac": flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "outliers": int(sum(m[4] for m in mats)),
+            "note": "four bof4_gemm calls (qkv, o, gate+up, down of the block, packed once; bf16 weights decoded "
+                    "in registers, fp32 accumulation on the matrix cores), back to back on one stream, outside the "
+                    "timed step"}
+
+
 def gemv_shapes(dev, calls=50):
     """bof4_gemv on the matrix shapes of workloads 1 and 4 (Student-t weights, block 64, signed, with and without the
     OPQ outliers, one and two tokens): microseconds per call from HIP events around `calls` back-to-back calls."""
@@ -327,6 +366,7 @@ def main():
     t_err = (time.perf_counter() - t_err) / 3
     k_err = err_ev[0].elapsed_time(err_ev[1])
     gemv = gemv_block_pass(codes, scales, oidx, oval, n_out_seen, cb, dev)
+    gemm = gemm_block_pass(codes, scales, oidx, oval, n_out_seen, cb, dev)
     # one plain device copy of known size (2 * n bytes read, 2 * n written), outside the timed region: the reference
     # against which a counter profile of this same command scales FETCH_SIZE / WRITE_SIZE
     deq.copy_(ws_list[0])
@@ -374,6 +414,7 @@ def main():
                         "note": "bof4_quant_error (quantise, decode and compare in registers: 2 bytes per weight), outside "
                                 "the timed step"},
         "gemv_block_pass": gemv,
+        "gemm_block_pass": gemm,
         "per_call": per_call,
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic},
