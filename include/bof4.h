@@ -121,6 +121,10 @@ typedef struct {
  * read three or four times instead).  The appendix's closing formula names the element before the weighted median;
  * what is returned is the minimiser that its derivation arrives at.  Weights are added as exact 64-bit integers, which
  * needs sum over all weights of |block constant| < 2^38 (BOF4_ERR_ARG otherwise).
+ *   weight_by_max  nonzero: the paper's criterion (eq. 8).  0: every weight counts one unit - the plain median of the
+ *               normalised weights (appendix D, the MAE of the normalised weights, which the paper shows to be the
+ *               inferior objective); den then counts the weights of the region whose block constant is a binary16
+ *               number, and sae is the sum of |x - level[code]|
  *   skip_mask   bit l set: the median of region l is not wanted (a pinned level) and is reported as NaN; cnt and den
  *               of the region are still returned.  The region that contains zero needs a fourth pass, so skipping it
  *               (it is pinned in every BOF4 codebook) saves time
@@ -128,8 +132,8 @@ typedef struct {
  * bit-reproducible.
  */
 int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
-                        double opq_T, uint16_t skip_mask, bof4_mae_stats* out_host, void* ws_dev, size_t ws_bytes,
-                        void* stream);
+                        double opq_T, int weight_by_max, uint16_t skip_mask, bof4_mae_stats* out_host, void* ws_dev,
+                        size_t ws_bytes, void* stream);
 
 /* Maximisation step for the MAE criterion: level l moves to median[l] unless bit l of pinned_mask is set or the region
  * carries no weight.  Pure host function; cb_host is updated in place. */

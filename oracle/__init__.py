@@ -79,7 +79,7 @@ def lib():
         L.oracle_codebook_update.argtypes = [ctypes.POINTER(LloydStats), ctypes.c_uint16, f64p]
         L.oracle_lloyd_step_mae.restype = ctypes.c_int
         L.oracle_lloyd_step_mae.argtypes = [u16p, ctypes.c_uint64, ctypes.c_uint32, f64p, ctypes.c_int,
-                                            ctypes.c_double, ctypes.POINTER(MaeStats)]
+                                            ctypes.c_double, ctypes.c_int, ctypes.POINTER(MaeStats)]
         L.oracle_codebook_update_mae.restype = ctypes.c_int
         L.oracle_codebook_update_mae.argtypes = [ctypes.POINTER(MaeStats), ctypes.c_uint16, f64p]
         L.oracle_f32_to_f16.restype = ctypes.c_uint16
@@ -227,12 +227,13 @@ def codebook_update(stats, pinned_mask, cb):
     return cb
 
 
-def lloyd_step_mae(w, block, cb, signed, opq_T=0.0):
-    """MAE criterion (weighted medians).  Returns (status, dict with median, den, cnt, sae, n_used, n_outliers)."""
+def lloyd_step_mae(w, block, cb, signed, opq_T=0.0, weight_by_max=True):
+    """MAE criterion (weighted medians; weight_by_max=False: plain medians of the normalised weights).  Returns
+    (status, dict with median, den, cnt, sae, n_used, n_outliers)."""
     w, cb = _w(w), _cb(cb)
     s = MaeStats()
     st = lib().oracle_lloyd_step_mae(_p(w, ctypes.c_uint16), w.size, block, _p(cb, ctypes.c_double), int(signed),
-                                     float(opq_T), ctypes.byref(s))
+                                     float(opq_T), int(bool(weight_by_max)), ctypes.byref(s))
     return st, s.as_dict()
 
 

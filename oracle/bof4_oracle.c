@@ -547,6 +547,13 @@ static uint64_t weight_units(uint16_t a16) {
     return (uint64_t)ldexp((double)f16_to_f32(a16), 24);
 }
 
+/* What a normalised weight counts with in its region's median: its block's constant (eq. 8), or one unit for the
+ * plain median of appendix D. */
+static uint64_t sample_weight(uint16_t a16, int weight_by_max) {
+    if (a16 >= 0x7C00u) return 0;
+    return weight_by_max ? weight_units(a16) : 1;
+}
+
 /*
  * One expectation pass of Lloyd's algorithm under the MAE criterion (section 3.2 eq. 7-8; appendix B.4): the
  * new level of region l minimises f(c) = sum_k a_k |x_k - c| over the normalised weights x_k of the region, a_k
@@ -561,7 +568,7 @@ static uint64_t weight_units(uint16_t a16) {
  * zero (all-zero blocks) cannot move f and are left out; a region without weight reports NaN and keeps its level.
  */
 int oracle_lloyd_step_mae(const uint16_t* w, uint64_t n, uint32_t I, const double* cb, int signed_norm, double T,
-                          oracle_mae_stats* out) {
+                          int weight_by_max, oracle_mae_stats* out) {
     if (!w || !cb || !out) return ORACLE_ERR_ARG;
     if (!valid_block(I) || n == 0 || n % I != 0 || !valid_codebook(cb) || !(T >= 0.0)) return ORACLE_ERR_ARG;
     double xi[NLEVELS - 1];
@@ -598,7 +605,7 @@ int oracle_lloyd_step_mae(const uint16_t* w, uint64_t n, uint32_t I, const doubl
         }
         out->cnt[code_of[e]]++;
         out->n_used++;
-        out->sae += (double)f16_to_f32(all[e].a16) * fabs((double)all[e].x - cb[code_of[e]]);
+        out->sae += (weight_by_max ? (double)f16_to_f32(all[e].a16) : 1.0) * fabs((double)all[e].x - cb[code_of[e]]);
     }
     int failed = 0;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -616,12 +623,14 @@ int oracle_lloyd_step_mae(const uint16_t* w, uint64_t n, uint32_t I, const doubl
             if (code_of[e] == (uint8_t)l) reg[k++] = all[e];
         qsort(reg, (size_t)K, sizeof(mae_sample), cmp_mae_sample);
         unsigned __int128 total = 0, run = 0;
-        for (uint64_t j = 0; j < K; ++j) total += weight_units(reg[j].a16);
-        out->den[l] = ldexp((double)total, -24);
+        /* appendix D (weight_by_max == 0): one unit per weight - the plain median; a block whose constant is not a
+           binary16 number carries no weight either way */
+        for (uint64_t j = 0; j < K; ++j) total += sample_weight(reg[j].a16, weight_by_max);
+        out->den[l] = weight_by_max ? ldexp((double)total, -24) : (double)total;
         if (total != 0) {
             /* equal x are adjacent: the test is made where a value ends, on everything up to and including it */
             for (uint64_t j = 0; j < K; ++j) {
-                run += weight_units(reg[j].a16);
+                run += sample_weight(reg[j].a16, weight_by_max);
                 if (j + 1 < K && reg[j + 1].x == reg[j].x) continue;
                 if (2 * run >= total) {
                     out->median[l] = (double)reg[j].x;

@@ -86,7 +86,8 @@ def lib():
         L.bof4_codebook_update.argtypes = [ctypes.POINTER(LloydStats), ctypes.c_uint16, vp]
         L.bof4_lloyd_step_mae.restype = ctypes.c_int
         L.bof4_lloyd_step_mae.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint32, f64p, ctypes.c_int, ctypes.c_double,
-                                          ctypes.c_uint16, ctypes.POINTER(MaeStats), vp, ctypes.c_size_t, vp]
+                                          ctypes.c_int, ctypes.c_uint16, ctypes.POINTER(MaeStats), vp, ctypes.c_size_t,
+                                          vp]
         L.bof4_codebook_update_mae.restype = ctypes.c_int
         L.bof4_codebook_update_mae.argtypes = [ctypes.POINTER(MaeStats), ctypes.c_uint16, vp]
         L.bof4_quantize.restype = ctypes.c_int
@@ -378,9 +379,10 @@ def bof4_lloyd_step(w, block, cb, signed, opq_T=0.0, weight_by_max2=True, ws=Non
     return out if raw else out.as_dict()
 
 
-def bof4_lloyd_step_mae(w, block, cb, signed, opq_T=0.0, skip_mask=0, ws=None, stream=None, raw=False, out=None):
-    """MAE criterion: per-region weighted medians.  w: flat bf16 device tensor.  skip_mask: regions (pinned levels)
-    whose median is not wanted.  Returns the statistics as a dict (or the ctypes struct with raw=True)."""
+def bof4_lloyd_step_mae(w, block, cb, signed, opq_T=0.0, skip_mask=0, ws=None, stream=None, raw=False, out=None,
+                        weight_by_max=True):
+    """MAE criterion: per-region weighted medians (weight_by_max=False: plain medians of the normalised weights).
+    w: flat bf16 device tensor.  skip_mask: regions (pinned levels) whose median is not wanted.  Returns the statistics as a dict (or the ctypes struct with raw=True)."""
     assert w.dtype == torch.bfloat16 and w.is_cuda and w.is_contiguous()
     n = w.numel()
     cb, cbp = _cb(cb)
@@ -388,7 +390,8 @@ def bof4_lloyd_step_mae(w, block, cb, signed, opq_T=0.0, skip_mask=0, ws=None, s
         ws = alloc_workspace(n, block, 0, w.device)
     if out is None:
         out = MaeStats()
-    _check(lib().bof4_lloyd_step_mae(_ptr(w), n, block, cbp, int(signed), float(opq_T), int(skip_mask),
+    _check(lib().bof4_lloyd_step_mae(_ptr(w), n, block, cbp, int(signed), float(opq_T), int(bool(weight_by_max)),
+                                     int(skip_mask),
                                      ctypes.byref(out), _ptr(ws), ws.numel(), _stream(stream)))
     return out if raw else out.as_dict()
 

@@ -1315,8 +1315,8 @@ int bof4_codebook_update_mae(const bof4_mae_stats* st, uint16_t pinned_mask, dou
 }
 
 int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
-                        double opq_T, uint16_t skip_mask, bof4_mae_stats* out_host, void* ws_dev, size_t ws_bytes,
-                        void* stream) {
+                        double opq_T, int weight_by_max, uint16_t skip_mask, bof4_mae_stats* out_host, void* ws_dev,
+                        size_t ws_bytes, void* stream) {
     if (!w_dev || !out_host) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: null pointer");
     if (!valid_block(block) || n == 0 || n % block != 0) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: bad n or block");
     if (!valid_codebook(cb_host)) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: codebook must be 16 finite ascending levels");
@@ -1352,6 +1352,7 @@ int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const dou
     double* sae_part = (double*)(base + ML.sae_part);
     double* rec_dev = (double*)(base + ML.record);
     const bool opq = opq_T > 0.0;
+    const int unweighted = weight_by_max ? 0 : 1;
     const double T2 = opq_T * opq_T;
     const uint32_t seg = block < 64 ? block : 64;
     const uint64_t n_seg = n / seg;
@@ -1380,19 +1381,20 @@ int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const dou
         if (first) timing_begin(s);
         if (reads_list)
             hipLaunchKernelGGL(mae_list_kernel, dim3(sgrid), dim3(256), 0, s, cand, cand_count, cand_cap, cand_full,
-                               state, hist);
+                               state, hist, unweighted);
 #define BOF4_LAUNCH_MAE(II, FIRST_)                                                                                   \
     if (bt.fast && opq) hipLaunchKernelGGL((mae_pass_kernel<II, true, true, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,  \
                                            n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part, cand_w, \
-                                           cand_count, cand_cap, gate);                                             \
+                                           cand_count, cand_cap, gate, unweighted);                                       \
     else if (bt.fast) hipLaunchKernelGGL((mae_pass_kernel<II, true, false, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,   \
                                          n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part, cand_w,   \
-                                         cand_count, cand_cap, gate);                                               \
+                                         cand_count, cand_cap, gate, unweighted);                                   \
     else if (opq) hipLaunchKernelGGL((mae_pass_kernel<II, false, true, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,       \
                                      n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part, cand_w,       \
-                                     cand_count, cand_cap, gate);                                                   \
+                                     cand_count, cand_cap, gate, unweighted);                                       \
     else hipLaunchKernelGGL((mae_pass_kernel<II, false, false, FIRST_>), dim3(sgrid), dim3(256), 0, s, w, n_seg, cb,    \
-                            bt, signed_norm, T2, state, hist, cnt_part, sae_part, cand_w, cand_count, cand_cap, gate);
+                            bt, signed_norm, T2, state, hist, cnt_part, sae_part, cand_w, cand_count, cand_cap, gate, \
+                            unweighted);
 #define BOF4_LAUNCH_MAE_BLOCK(FIRST_)                \
     switch (block) {                                 \
         case 32: BOF4_LAUNCH_MAE(32, FIRST_) break;   \
@@ -1411,7 +1413,7 @@ int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const dou
         hipLaunchKernelGGL(mae_select_kernel, dim3(1), dim3(1024), 0, s, state, hist, cnt_part, sae_part, sgrid,
                            first ? 1 : 0, p + 1 == passes ? 1 : 0, (uint32_t)skip_mask,
                            writes_list ? cand_count : (const uint32_t*)nullptr, cand_waves, cand_cap, cand_full,
-                           direct ? direct : rec_dev);
+                           direct ? direct : rec_dev, unweighted);
     }
     HIP_TRY(hipGetLastError());
     if (direct) {

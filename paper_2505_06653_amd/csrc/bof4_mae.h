@@ -1,5 +1,6 @@
 // bof4_mae.h - Lloyd step under the MAE criterion (section 3.2 eq. 7-8, appendix B.4): per region the weighted
-// median of the normalised weights, weighted by the absolute block maximum.
+// median of the normalised weights, weighted by the absolute block maximum - or, on request, the plain median of
+// appendix D (every weight one unit).
 //
 // A weighted median over 10^8 samples is found without sorting, by a radix search on an order-preserving integer
 // key of x.  Region l can only hold keys between klo[l] (its lower threshold) and its upper threshold, so the search
@@ -75,7 +76,7 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
                                                            double* __restrict__ sae_part,
                                                            unsigned long long* __restrict__ cand,
                                                            uint32_t* __restrict__ cand_count, uint32_t cand_cap,
-                                                           const uint32_t* __restrict__ gate) {
+                                                           const uint32_t* __restrict__ gate, int unweighted) {
     using C = SegCfg<I>;
     // `gate`: this launch only matters if the word it points to is set (the scan that stands in for a list that ran
     // full).  `cand`: append the elements that still count to this wave's stretch of the list.
@@ -165,7 +166,10 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
         const float m_eff = f16_bits_to_f32(f32_to_f16_bits(m));
         const float a = fabsf(m_eff);
         // |block constant| in units of 2^-24; a constant beyond binary16 (infinite) carries no weight
-        const unsigned long long W = (a < 65536.0f) ? (unsigned long long)((double)a * 16777216.0) : 0ull;
+        // (unweighted: the plain median of the normalised weights - every element of such a block weighs one unit)
+        const unsigned long long W =
+            (a < 65536.0f) ? (unweighted ? 1ull : (unsigned long long)((double)a * 16777216.0)) : 0ull;
+        const double a_sum = unweighted ? 1.0 : (double)a;  // what an element's |x - level| counts with in the error sum
         const bool fast = FAST && __builtin_amdgcn_ballot_w64(!maxabs_is_ordinary(maxabs)) == 0;
         const uint32_t m15_shifted = (f32_to_f16_bits(a) & 0x7fffu) << 4;
         if (active) {
@@ -249,8 +253,8 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
                 }
             }
             if (FIRST) {
-                sae = fma((double)a, dsum, sae);
-                w_est = fma((double)a, (double)(C::SEG - k_out), w_est);
+                sae = fma(a_sum, dsum, sae);
+                w_est = fma(a_sum, (double)(C::SEG - k_out), w_est);
             }
         }
         if (FIRST && ++tiles_since_flush == 65535u / C::SEG) {
@@ -302,7 +306,7 @@ __global__ __launch_bounds__(256) void mae_list_kernel(const unsigned long long*
                                                        const uint32_t* __restrict__ cand_count, uint32_t cand_cap,
                                                        const uint32_t* __restrict__ full,
                                                        const MaeLevelState* __restrict__ state,
-                                                       unsigned long long* __restrict__ hist_g) {
+                                                       unsigned long long* __restrict__ hist_g, int unweighted) {
     if (*full != 0u) return;
     __shared__ uint4 info[16];
     __shared__ unsigned long long hist[16 * 256];
@@ -323,7 +327,8 @@ __global__ __launch_bounds__(256) void mae_list_kernel(const unsigned long long*
         const uint4 inf = info[l];
         if (inf.w != 0u && (sub >> inf.y) == inf.z) {
             const float a = f16_bits_to_f32(m15);
-            const unsigned long long W = (a < 65536.0f) ? (unsigned long long)((double)a * 16777216.0) : 0ull;
+            const unsigned long long W =
+                (a < 65536.0f) ? (unweighted ? 1ull : (unsigned long long)((double)a * 16777216.0)) : 0ull;
             atomicAdd(&hist[l * 256 + ((sub >> inf.x) & ((1u << (inf.y - inf.x)) - 1u))], W);
         }
     }
@@ -346,7 +351,7 @@ __global__ __launch_bounds__(1024) void mae_select_kernel(MaeLevelState* __restr
                                                           const uint32_t* __restrict__ cand_count,
                                                           uint32_t cand_waves, uint32_t cand_cap,
                                                           uint32_t* __restrict__ cand_full,
-                                                          double* __restrict__ out) {
+                                                          double* __restrict__ out, int unweighted) {
     const uint32_t lane = threadIdx.x & 63, l = threadIdx.x >> 6;  // wave l = region l
     if (cand_count != nullptr) {  // after the pass that wrote the list: did every wave's stretch hold its entries?
         uint32_t over = 0;
@@ -427,7 +432,7 @@ __global__ __launch_bounds__(1024) void mae_select_kernel(MaeLevelState* __restr
     if (lane == 0) {
         med[l] = (s.total != 0ull && s.hi == 0u && s.pad == 0u) ? (double)key_to_float(s.klo + s.prefix)
                                                                   : __builtin_nan("");
-        den[l] = (double)s.total * 0x1p-24;  // correctly rounded conversion of the integer
+        den[l] = (double)s.total * (unweighted ? 1.0 : 0x1p-24);  // correctly rounded conversion of the integer
         cnt[l] = k_l;
         if (l == 15) cnt[16] = k_out;
     }

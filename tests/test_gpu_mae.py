@@ -41,6 +41,31 @@ def test_mae_step_parity(block, signed, opq):
     assert_mae_close(g, o)
 
 
+@pytest.mark.parametrize("block", [32, 64, 256])
+@pytest.mark.parametrize("signed", [0, 1])
+@pytest.mark.parametrize("opq", [0, 1])
+def test_mae_step_without_weights_parity(block, signed, opq):
+    """Appendix D's objective (weight_by_max = 0): plain medians of the normalised weights, den = counts,
+    sae = sum |x - level|.  2^17 weights, so that the search reads its list in the third pass."""
+    w = make_weights(128, 1024, seed=540 + block + signed)
+    T = oracle.opq_threshold(0.95, block) if opq else 0.0
+    cb = mae_cb(block, signed)
+    st, o = oracle.lloyd_step_mae(inputs.bits(w), block, cb, signed, opq_T=T, weight_by_max=False)
+    st2, ow = oracle.lloyd_step_mae(inputs.bits(w), block, cb, signed, opq_T=T)
+    assert st == oracle.OK and np.any(o["median"] != ow["median"])
+    pin = codebooks.PIN_BOF4S if signed else codebooks.PIN_BOF4
+    for skip in (0, pin):
+        g = binding.bof4_lloyd_step_mae(w.to(DEV), block, cb, signed, opq_T=T, weight_by_max=False, skip_mask=skip)
+        if skip:
+            wanted = np.array([not ((skip >> l) & 1) for l in range(16)])
+            assert np.all(np.isnan(g["median"][~wanted]))
+            assert np.array_equal(g["median"][wanted], o["median"][wanted])
+            assert np.array_equal(g["den"], o["den"]) and np.array_equal(g["cnt"], o["cnt"])
+            assert abs(g["sae"] - o["sae"]) <= RTOL * o["sae"]
+        else:
+            assert_mae_close(g, o)
+
+
 def test_mae_em_iterations_follow_the_oracle():
     """Twelve EM iterations with the MAE criterion from the quantile start: same codebooks as the oracle at every
     step (the medians are exact), objective never rising."""

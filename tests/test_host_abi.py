@@ -118,9 +118,9 @@ def test_argument_validation_of_the_later_entry_points_without_touching_the_gpu(
     bad_cbp = bad_cb.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
     fake, odd, ws = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004), ctypes.c_void_p(0x10000)
     ms, es = binding.MaeStats(), binding.ErrorStats()
-    assert L.bof4_lloyd_step_mae(fake, 1000, 64, cbp, 1, 0.0, 0, ctypes.byref(ms), ws, 1 << 30, None) == binding.BOF4_ERR_ARG
-    assert L.bof4_lloyd_step_mae(fake, 1024, 64, bad_cbp, 1, 0.0, 0, ctypes.byref(ms), ws, 1 << 30, None) == binding.BOF4_ERR_ARG
-    assert L.bof4_lloyd_step_mae(fake, 1024, 64, cbp, 1, 0.0, 0, ctypes.byref(ms), ws, 64, None) == binding.BOF4_ERR_WORKSPACE
+    assert L.bof4_lloyd_step_mae(fake, 1000, 64, cbp, 1, 0.0, 1, 0, ctypes.byref(ms), ws, 1 << 30, None) == binding.BOF4_ERR_ARG
+    assert L.bof4_lloyd_step_mae(fake, 1024, 64, bad_cbp, 1, 0.0, 1, 0, ctypes.byref(ms), ws, 1 << 30, None) == binding.BOF4_ERR_ARG
+    assert L.bof4_lloyd_step_mae(fake, 1024, 64, cbp, 1, 0.0, 0, 0, ctypes.byref(ms), ws, 64, None) == binding.BOF4_ERR_WORKSPACE
     assert L.bof4_quant_error(fake, 1024, 48, cbp, 1, 0.0, ctypes.byref(es), ws, 1 << 30, None) == binding.BOF4_ERR_ARG
     assert L.bof4_quant_error(fake, 1024, 64, cbp, 1, -2.0, ctypes.byref(es), ws, 1 << 30, None) == binding.BOF4_ERR_ARG
     assert L.bof4_quant_error(fake, 1024, 64, cbp, 1, 0.0, ctypes.byref(es), ws, 64, None) == binding.BOF4_ERR_WORKSPACE

@@ -417,6 +417,30 @@ def test_mae_step_with_equal_block_maxima_is_the_plain_lower_median():
         assert s["den"][l] == xs.size
 
 
+@pytest.mark.parametrize("signed", [0, 1])
+def test_mae_step_without_weights_is_the_plain_lower_median_of_every_region(signed):
+    """Appendix D: minimising the MAE of the normalised weights makes the level the plain median.  Blocks with very
+    different maxima (so that the weighted median of eq. 8 differs): numpy's sorted element (K - 1) // 2 per region,
+    den counts the region, sae is sum |x - level| in binary64."""
+    rng = np.random.default_rng(60 + signed)
+    cb = codebooks.array(codebooks.BOF4S_MAE_64 if signed else codebooks.BOF4_MAE_64)
+    scale = np.float32(2.0) ** rng.integers(-6, 5, size=(300, 1)).astype(np.float32)
+    wb = bf16_bits((rng.standard_normal((300, 64)).astype(np.float32) * scale).ravel())
+    st, s = oracle.lloyd_step_mae(wb, 64, cb, signed, weight_by_max=False)
+    st2, sw = oracle.lloyd_step_mae(wb, 64, cb, signed)
+    assert st == oracle.OK and st2 == oracle.OK
+    x, code, a = _normalised_and_codes(wb, 64, cb, signed)
+    differs = 0
+    for l in range(16):
+        xs = np.sort(x[code == l])
+        assert s["cnt"][l] == xs.size == sw["cnt"][l] and s["den"][l] == xs.size
+        assert s["median"][l] == float(xs[(xs.size - 1) // 2])
+        differs += s["median"][l] != sw["median"][l]
+    assert differs >= 8  # the weights matter on this input
+    direct = np.abs(x.astype(np.float64) - cb[code]).sum()
+    assert abs(s["sae"] - direct) <= 1e-12 * direct
+
+
 def test_mae_step_error_sum_matches_the_dequantised_weights():
     """sae = sum |m| |x - c| equals sum |w - m c| up to the rounding of x (one binary32 division)."""
     wb = inputs.bits(inputs.student_t_matrix(64, 512, nu=5.0, std=0.02, row_sigma=0.3, seed=46))
