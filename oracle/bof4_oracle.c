@@ -18,7 +18,9 @@
  *   MAE step (weighted median): brute-force minimiser of sum a|x - c| on tiny inputs; the plain lower median
  *                                when all blocks weigh the same; fixed point on Gaussian samples equals the
  *                                printed MAE codebooks; one update from the MSE codebook equals the theoretical
- *                                update of section 3.2 eq. 7 (numerical integration, bisection)
+ *                                update of section 3.2 eq. 7 (numerical integration, bisection); without weights
+ *                                (appendix D) numpy's sorted lower median of every region on blocks of very
+ *                                different maxima
  *   quantisation error         : zero on a tensor that is already decoded (Q is idempotent); one hand-made block;
  *                                within the decoder's rounding of the Lloyd step's sse (appendix B.3); the orderings
  *                                the paper reports (signed below absolute, MAE-/MSE-optimised best on their own
