@@ -185,11 +185,13 @@ __global__ __launch_bounds__(64 * GEMM_MAX_WAVES) void gemm_kernel(
             for (int j = 0; j < 4; ++j) {
                 // byte i of `even` = 4 * code of element 2 i of the word, of `odd` = 4 * code of element 2 i + 1
                 const uint32_t even = (w[j] << 2) & 0x3c3c3c3cu, odd = (w[j] >> 2) & 0x3c3c3c3cu;
+                const uint32_t oe[4] = {byte_of<0>(even), byte_of<1>(even), byte_of<2>(even), byte_of<3>(even)};
+                const uint32_t oo[4] = {byte_of<0>(odd), byte_of<1>(odd), byte_of<2>(odd), byte_of<3>(odd)};
                 uint32_t a[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const float le = *reinterpret_cast<const float*>(tab + ((even >> (8 * i)) & 0xffu));
-                    const float lo = *reinterpret_cast<const float*>(tab + ((odd >> (8 * i)) & 0xffu));
+                    const float le = *reinterpret_cast<const float*>(tab + oe[i]);
+                    const float lo = *reinterpret_cast<const float*>(tab + oo[i]);
                     a[i] = gemm_pack_bf16(msc * le, msc * lo);  // the decoder's product and rounding
                 }
                 __builtin_memcpy(&A[j], a, 16);
