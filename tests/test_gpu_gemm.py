@@ -105,6 +105,30 @@ def test_gemm_is_exact_where_every_partial_sum_is_a_binary32_number(rows, cols, 
         assert np.array_equal(y_g, y_o)
 
 
+@pytest.mark.parametrize("n_tokens", [7, 100])
+def test_gemm_dense_outlier_rows_take_several_rounds_and_empty_rows_none(n_tokens):
+    """A hand-made list: a third of the weights of rows 4..11 (thousands of entries per row), single entries in the
+    first and last column elsewhere, nothing in most rows; values unrelated to the codes; a codebook without a zero
+    level, so every placeholder decodes to something."""
+    rows, cols, block = 40, 6144, 64
+    cb, codes, scales, _, _ = quantized(rows, cols, block, 1, 0, seed=77)
+    cb = cb + 0.013 * np.linspace(-1, 1, 16) ** 2 + 0.004
+    rng = np.random.default_rng(5)
+    mask = np.zeros((rows, cols), dtype=bool)
+    mask[4:12] = rng.random((8, cols)) < 0.33
+    mask[20, 0] = True
+    mask[39, cols - 1] = True
+    oi = np.flatnonzero(mask.reshape(-1)).astype(np.int64)
+    ov = (rng.standard_normal(oi.size).astype(np.float32) * 0.3).astype(np.float16).view(np.uint16)
+    x = rand_x(n_tokens, cols, 3)
+    y_g, y_o = check(cb, codes, scales, oi, ov, rows, cols, block, x)
+    y_none = run_gpu(cb, codes, scales, None, None, rows, cols, block, x)
+    touched = np.zeros(rows, dtype=bool)
+    touched[4:12] = touched[20] = touched[39] = True
+    assert np.array_equal(y_g[:, ~touched], y_none[:, ~touched])  # rows without entries: the dense result, bit for bit
+    assert np.max(np.abs(y_g[:, 4:12] - y_none[:, 4:12])) > 1e-3  # the list matters
+
+
 def test_gemm_unit_vectors_pick_single_decoded_weights():
     """x = a unit vector per token: the product returns one column of the decoded matrix, exactly."""
     rows, cols, block = 45, 2304, 64
