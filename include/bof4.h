@@ -250,7 +250,9 @@ size_t bof4_gemv_outlier_table_bytes(uint64_t rows, uint64_t cols, uint64_t n_ou
  * Every product of two bfloat16 numbers is exact in binary32; the sums are binary32 (matrix cores, up to 128 tokens
  * per pass over the codes) in a fixed order: y is bit-reproducible and lies within (cols + 64) * 2^-24 * sum_c |W^ x|
  * of the exact sum (an outlier position counts with its decoded placeholder as well as with its value), and is exact
- * whenever every partial sum is a binary32 number.
+ * whenever every partial sum is a binary32 number.  The order of the additions depends on rows, cols and n_tokens
+ * (how the columns are dealt out over workgroups), so the same token may differ in its last bits between calls with
+ * different n_tokens; equal calls give equal bits.
  *
  * The matrix is read from a copy in the order of the matrix cores' operands, made once per matrix by bof4_gemm_pack
  * from what bof4_quantize wrote for n = rows * cols (row-major [rows x cols], cols a multiple of block):
