@@ -231,6 +231,9 @@ def main():
     ap.add_argument("--serial", action="store_true",
                     help="every call waits for its result before the next is enqueued (default: the Lloyd kernels are "
                          "enqueued behind the quantiser before the host waits for the outlier count)")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="enqueue the Lloyd kernels on a second stream, so that they overlap with the quantiser and the "
+                         "decoder (not the default: the kernel times of the roofline record are taken without overlap)")
     ap.add_argument("--gemv-shapes", action="store_true",
                     help="instead of the benchmark step: bof4_gemv on a table of matrix shapes, one JSON line")
     ap.add_argument("--gemm-shapes", action="store_true",
@@ -313,16 +316,18 @@ def main():
         flight = binding.bof4_quantize_begin(w, BLOCK, cb, 1, T, cap, codes, scales, oidx, oval, ws, counter)
         if timed_call == 2:
             binding.bof4_time_next_call(kev[i][0], kev[i][1])
-        binding.bof4_lloyd_step_begin(w, BLOCK, cb, 1, stats_rec, ws=ws_lloyd)
+        binding.bof4_lloyd_step_begin(w, BLOCK, cb, 1, stats_rec, ws=ws_lloyd, stream=side)
         k = flight.finish()
         if timed_call == 1:
             binding.bof4_time_next_call(kev[i][0], kev[i][1])
         binding.bof4_dequantize(codes, scales, n, BLOCK, cb, oidx if k else None, oval if k else None, out=deq,
                                 n_outliers=k)
-        binding.bof4_wait_result(stats_rec)
+        binding.bof4_wait_result(stats_rec, stream=side)
         binding.bof4_codebook_update(stats_rec, codebooks.PIN_BOF4S, cb)
         n_out_seen = k
 
+    # --two-streams: the Lloyd kernels (which read only the weights) go to a stream of their own
+    side = torch.cuda.Stream() if args.two_streams else None
     timed_step = step if args.serial else step_pipelined
     for i in range(args.warmup):
         timed_step(i)
@@ -403,7 +408,9 @@ def main():
                                "step = quantize + dequantize + lloyd_step + codebook_update",
                    "n_weights": n, "block": BLOCK, "outlier_fraction": rho, "replicas": len(ws_list),
                    "enqueue_order": "one call after the other, each waiting for its result" if args.serial else
-                                    "quantize kernels, lloyd kernels, outlier count, dequantize, lloyd sums (one stream)"},
+                                    "quantize kernels, lloyd kernels, outlier count, dequantize, lloyd sums (" +
+                                    ("lloyd kernels on a second stream: kernel times include the overlap)"
+                                     if args.two_streams else "one stream)")},
         "lloyd_weights_per_s": n / (kms["lloyd_step"] * 1e-3),
         "mae_step": {"call_ms": t_mae * 1e3, "weights_per_s": n / t_mae,
                      "note": "bof4_lloyd_step_mae (exact weighted medians of the 14 free levels: two passes over the weights, one over a candidate list), outside the "
