@@ -1008,8 +1008,8 @@ uint32_t gemm_row_tiles_per_wg(uint64_t rows, uint64_t cols, uint64_t n_tokens) 
 uint64_t gemm_row_tiles(uint64_t rows) {  // in the packed matrix: a multiple of GEMM_MAX_R
     return (rows + GEMM_ROWS * GEMM_MAX_R - 1) / (GEMM_ROWS * GEMM_MAX_R) * GEMM_MAX_R;
 }
-// How many workgroups share the columns of their rows: enough to put GEMM_TARGET_WGS workgroups on the chip, each
-// with at least one chunk per wave.
+// How many workgroups share the columns of their rows: the fewest that put GEMM_TARGET_WGS workgroups on the chip,
+// each with at least one chunk per wave.
 uint32_t gemm_split(uint64_t rows, uint64_t cols, uint64_t n_tokens) {
     const uint64_t groups = gemm_row_tiles(rows) / gemm_row_tiles_per_wg(rows, cols, n_tokens);
     const uint64_t chunks = (cols + GEMM_CHUNK - 1) / GEMM_CHUNK;

@@ -35,7 +35,10 @@ constexpr uint32_t GEMM_TOKENS = 32;  // tokens per tile (N of the matrix-core p
 constexpr uint32_t GEMM_MAX_TILES = 4;  // token tiles per launch: the codes are decoded once per 128 tokens
 constexpr uint32_t GEMM_CHUNK = 64;   // columns per wave and step: four products of K = 16
 constexpr uint32_t GEMM_MAX_WAVES = 8;
-constexpr uint32_t GEMM_TARGET_WGS = 512;  // two workgroups on each of the 256 compute units
+// Workgroups wanted before the columns are also split over workgroups: three quarters of the 256 compute units.
+// Measured: splitting further (to 256, 512 or 1024 workgroups) costs more in partial results and in the epilogue per
+// workgroup than the fuller chip gains; fewer than 192 leave too much of it idle.
+constexpr uint32_t GEMM_TARGET_WGS = 192;
 
 typedef __bf16 gemm_bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 gemm_bf16x2 __attribute__((ext_vector_type(2)));

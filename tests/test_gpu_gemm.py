@@ -64,8 +64,8 @@ def test_gemm_parity(block, opq, n_tokens):
 @pytest.mark.parametrize("rows,cols", [(1, 32), (3, 64), (130, 6144), (65, 4096 + 2048 + 1024), (33, 32768),
                                        (16390, 128), (16390, 32)])
 def test_gemm_shapes(rows, cols):
-    """Half a chunk, one chunk, many; the last two have more than 512 row tiles, so that one workgroup takes all columns
-    of its rows and the list is applied to the result in place."""
+    """Half a chunk, one chunk, many; the last two have hundreds of row tiles, so that one workgroup takes all columns of
+    its rows and writes the result itself."""
     cb, codes, scales, oi, ov = quantized(rows, cols, 32, 0, 1, seed=31 + rows)
     packed_x = 32 * ((cols + 63) // 64 * 64) * 2 + cols * 32 * 2  # in product order and transposed, 32 token slots
     extra = binding.bof4_gemm_workspace_bytes(rows, cols, 5) - packed_x

@@ -153,9 +153,9 @@ def test_argument_validation_and_size_formulas_of_the_matrix_product_without_tou
     assert binding.bof4_gemm_packed_bytes(64, 128) == 2 * 2 * 1152
     assert binding.bof4_gemm_packed_bytes(65, 96) == 4 * 2 * 1152
     assert binding.bof4_gemm_packed_bytes(4096, 11008) == 128 * 172 * 1152
-    # x twice, token slots in 32s; partial results only where the rows alone do not give 512 workgroups
+    # x twice, token slots in 32s; partial results only where the rows alone do not give 192 workgroups
     assert binding.bof4_gemm_workspace_bytes(32768, 4096, 7) == 2 * 32 * 4096 * 2
-    assert binding.bof4_gemm_workspace_bytes(4096, 4096, 40) == 2 * 64 * 4096 * 2 + 4 * 64 * 4096 * 4
+    assert binding.bof4_gemm_workspace_bytes(4096, 4096, 40) == 2 * 64 * 4096 * 2 + 2 * 64 * 4096 * 4
     assert binding.bof4_gemm_workspace_bytes(0, 64, 1) == 0
     pk = lambda codes, rows, cols, blk, out, nbytes: L.bof4_gemm_pack(codes, fake, rows, cols, blk, out, nbytes, None)
     assert pk(None, 64, 128, 64, ws, 1 << 20) == binding.BOF4_ERR_ARG
