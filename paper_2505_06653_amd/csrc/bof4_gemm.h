@@ -258,19 +258,24 @@ __global__ __launch_bounds__(64 * GEMM_MAX_WAVES) void gemm_kernel(
                     for (int i = 0; i < 8; ++i) c[t][i] = 0.0f;
                 const uint16_t* xg = xt + tile0 * 32 + 8 * g;
                 constexpr int U = 8 / NT;  // entries per lane and round: 8 loads of x in flight per lane
-                for (uint32_t k0 = ea + slot; k0 < eb; k0 += 16 * U) {
+                for (uint32_t kb = ea; kb < eb; kb += 16 * U) {  // kb: the round's first entry (the same in all lanes)
+                    const uint32_t k0 = kb + slot;
                     uint2 en[U];
 #pragma unroll
-                    for (int u = 0; u < U; ++u) en[u] = entries[min(k0 + 16 * u, eb - 1)];  // past the row: not used
+                    for (int u = 0; u < U; ++u)
+                        if (kb + 16 * u < eb) en[u] = entries[min(k0 + 16 * u, eb - 1)];  // past the row: not used
                     uint4 xv[U][NT];
 #pragma unroll
                     for (int u = 0; u < U; ++u)
+                        if (kb + 16 * u < eb) {
 #pragma unroll
-                        for (int t = 0; t < NT; ++t)
-                            xv[u][t] = *reinterpret_cast<const uint4*>(xg + (uint64_t)min(en[u].x, cols - 1) * n_pad +
-                                                                       32 * t);
+                            for (int t = 0; t < NT; ++t)
+                                xv[u][t] = *reinterpret_cast<const uint4*>(
+                                    xg + (uint64_t)min(en[u].x, cols - 1) * n_pad + 32 * t);
+                        }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
+                        if (kb + 16 * u >= eb) break;  // no slot has an entry from here on
                         // Past the row's last entry that entry is read again and counts with delta 0.  (Where its
                         // x is not finite the sum is not finite already.)
                         const float delta = k0 + 16 * u < eb ? __uint_as_float(en[u].y) : 0.0f;
