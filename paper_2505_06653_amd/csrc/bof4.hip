@@ -1125,7 +1125,7 @@ int bof4_gemm(const void* packed_dev, uint64_t rows, uint64_t cols, const double
     }
     timing_begin(s);
     for (uint32_t tile0 = 0; tile0 < tok_tiles;) {
-        const uint32_t left = tok_tiles - tile0, nt_tiles = left >= 4 ? 4 : left >= 2 ? 2 : 1;
+        const uint32_t left = tok_tiles - tile0, nt_tiles = left >= 4 ? 4 : left;
         const uint32_t t0 = tile0 * GEMM_TOKENS;
         const uint32_t nt = n_tokens - t0 < nt_tiles * GEMM_TOKENS ? n_tokens - t0 : nt_tiles * GEMM_TOKENS;
         float* yt = y_dev + (uint64_t)t0 * rows;
@@ -1135,8 +1135,8 @@ int bof4_gemm(const void* packed_dev, uint64_t rows, uint64_t cols, const double
                        (const char*)packed_dev, (uint32_t)rows, (uint32_t)cols, cb, offsets_dev, entries_dev,     \
                        (uint32_t)n_outliers, (uint32_t)strips, xp, xt, n_pad, tile0, nt, dst);
 #define BOF4_LAUNCH_GEMM_NT(R_, OUT_)                                                                             \
-    if (nt_tiles == 4) { BOF4_LAUNCH_GEMM(R_, 4, OUT_) } else if (nt_tiles == 2) { BOF4_LAUNCH_GEMM(R_, 2, OUT_) } \
-    else { BOF4_LAUNCH_GEMM(R_, 1, OUT_) }
+    if (nt_tiles == 4) { BOF4_LAUNCH_GEMM(R_, 4, OUT_) } else if (nt_tiles == 3) { BOF4_LAUNCH_GEMM(R_, 3, OUT_) } \
+    else if (nt_tiles == 2) { BOF4_LAUNCH_GEMM(R_, 2, OUT_) } else { BOF4_LAUNCH_GEMM(R_, 1, OUT_) }
         if (n_outliers > 0) {
             if (per_wg_tiles == 2) { BOF4_LAUNCH_GEMM_NT(2, true) } else { BOF4_LAUNCH_GEMM_NT(1, true) }
         } else {
