@@ -13,8 +13,8 @@
 // row l % 32 of A and token l % 32 of B, eight consecutive columns each; which eight is the same for both (half
 // l / 32 of a 64-column chunk takes its columns 32 (l / 32) + 8 j .. + 7 in the j-th of four products), so a lane
 // decodes one 16-byte load of its row per chunk.
-// A workgroup owns 32 rows; its waves take the 64-column chunks in turn and their 32 x 32 partial results are added
-// in wave order through LDS.  Outliers: the decoded placeholder went through the product, so what is added per list
+// A workgroup owns 32 or 64 rows (one or two tiles per wave: with two, every word of x read serves both); its waves
+// take the 64-column chunks in turn and their 32 x 32 partial results are added in wave order through LDS.  Outliers: the decoded placeholder went through the product, so what is added per list
 // entry is (value - bfloat16(m * level[code])) * x[t][col], from the table bof4_gemv_outlier_table makes in its
 // rounded form.  When the columns of a matrix with few rows are split over several workgroups to fill the chip, a
 // second small kernel adds their partial results.  Every order is fixed: the result is bit-reproducible.
