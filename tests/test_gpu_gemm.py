@@ -14,7 +14,7 @@ import torch
 
 import oracle
 from paper_2505_06653_amd import binding, inputs
-from test_gpu_parity import cb_for
+from test_gpu_parity import cb_for, make_weights
 from test_gpu_gemv import dev_i64, dev_u16, quantized, rand_x
 
 pytestmark = pytest.mark.gpu
@@ -71,6 +71,32 @@ def test_gemm_shapes(rows, cols):
     extra = binding.bof4_gemm_workspace_bytes(rows, cols, 5) - packed_x
     assert 0 <= extra < 512 if (rows > 16000 or cols < 1024) else extra >= 2 * 32 * rows * 4
     check(cb, codes, scales, oi, ov, rows, cols, 32, rand_x(5, cols, 11))
+
+
+def _random_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(count):
+        block = int(rng.choice([32, 64, 128, 256]))
+        wide = i % 4 == 3  # every fourth case has 8192 or more columns: two tiles of rows per wave above 32 tokens
+        cols = block * int(rng.integers(8192 // block, 8192 // block + 6) if wide else rng.integers(1, 3072 // block + 1))
+        rows = int(rng.integers(1, 40 if wide else 200))
+        n_tokens = int(rng.choice([1, 2, 31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 200]))
+        cases.append((rows, cols, block, n_tokens, int(rng.integers(0, 2)), int(rng.integers(0, 2))))
+    return cases
+
+
+@pytest.mark.parametrize("rows,cols,block,n_tokens,signed,opq", _random_cases(24, seed=2025))
+def test_gemm_random_shapes(rows, cols, block, n_tokens, signed, opq):
+    """Shapes, block sizes and token counts drawn once from a seeded generator: ragged row tiles, half chunks, every
+    number of token tiles per launch."""
+    w = make_weights(rows, cols, seed=rows * 7 + cols, outliers=False)
+    cb = cb_for(block, signed)
+    T = oracle.opq_threshold(0.9, block) if opq else 0.0
+    st, codes, scales, oi, ov, k = oracle.quantize(inputs.bits(w), block, cb, signed, opq_T=T)
+    assert st == oracle.OK
+    lst = (oi, ov) if (opq and k) else (None, None)
+    check(cb, codes, scales, lst[0], lst[1], rows, cols, block, rand_x(n_tokens, cols, seed=cols + n_tokens))
 
 
 @pytest.mark.parametrize("rows,cols,n_tokens", [(33, 32768, 40), (70, 8192, 130), (16390, 128, 70)])
