@@ -86,6 +86,30 @@ def test_gemv_shapes(rows, cols):
     check(cb, codes, scales, oi, ov, rows, cols, 32, rand_x(2, cols, 11))
 
 
+def _random_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(count):
+        block = int(rng.choice([32, 64, 128, 256]))
+        top = 32768 if i % 4 == 3 else 6144  # every fourth case may be many strips wide
+        cols = block * int(rng.integers(1, top // block + 1))
+        rows = int(rng.integers(1, 24 if cols > 8192 else 150))
+        cases.append((rows, cols, block, int(rng.integers(1, 6)), int(rng.integers(0, 2)), int(rng.integers(0, 2))))
+    return cases
+
+
+@pytest.mark.parametrize("rows,cols,block,n_tokens,signed,opq", _random_cases(16, seed=2024))
+def test_gemv_random_shapes(rows, cols, block, n_tokens, signed, opq):
+    """Shapes, block sizes and token counts drawn once from a seeded generator: ragged last strips and row chunks."""
+    w = make_weights(rows, cols, seed=rows * 5 + cols, outliers=False)
+    cb = cb_for(block, signed)
+    T = oracle.opq_threshold(0.9, block) if opq else 0.0
+    st, codes, scales, oi, ov, k = oracle.quantize(inputs.bits(w), block, cb, signed, opq_T=T)
+    assert st == oracle.OK
+    lst = (oi, ov) if (opq and k) else (None, None)
+    check(cb, codes, scales, lst[0], lst[1], rows, cols, block, rand_x(n_tokens, cols, seed=cols + n_tokens))
+
+
 def test_gemv_dense_outlier_rows_take_several_rounds_and_empty_rows_none():
     """A hand-made list: a third of the weights of rows 4..11 (thousands of entries per row chunk), nothing elsewhere,
     values unrelated to the codes; a codebook without a zero level, so every placeholder decodes to something."""
