@@ -155,6 +155,24 @@ def test_gemm_dense_outlier_rows_take_several_rounds_and_empty_rows_none(n_token
     assert np.max(np.abs(y_g[:, 4:12] - y_none[:, 4:12])) > 1e-3  # the list matters
 
 
+@pytest.mark.parametrize("opq", [0, 1])
+def test_gemm_a_token_that_is_not_finite_stays_on_its_own(opq):
+    """One token carries an infinity: its own results are not finite (every row multiplies it), every other token's are
+    what they are without it - nothing leaks through padding, clamped list slots or shared registers."""
+    rows, cols, block = 70, 2304, 64
+    cb, codes, scales, oi, ov = quantized(rows, cols, block, 1, opq, seed=91)
+    lst = (oi, ov) if opq else (None, None)
+    x = rand_x(37, cols, 17)
+    y_clean = run_gpu(cb, codes, scales, lst[0], lst[1], rows, cols, block, x)
+    x[5, 1000] = float("inf")
+    x[33, 3] = float("nan")
+    y = run_gpu(cb, codes, scales, lst[0], lst[1], rows, cols, block, x)
+    bad = np.zeros(37, dtype=bool)
+    bad[[5, 33]] = True
+    assert not np.isfinite(y[bad]).any()
+    assert np.array_equal(y[~bad], y_clean[~bad])
+
+
 def test_gemm_unit_vectors_pick_single_decoded_weights():
     """x = a unit vector per token: the product returns one column of the decoded matrix, exactly."""
     rows, cols, block = 45, 2304, 64
