@@ -96,6 +96,21 @@ int bof4_lloyd_step_begin(const void* w_dev, uint64_t n, uint32_t block, const d
                           void* stream);
 int bof4_wait_result(const uint64_t* word_host, void* stream);
 
+/*
+ * bof4_lloyd_step for callers that cannot allocate device memory or hand in a workspace (code that runs where
+ * hipMalloc is not allowed, tight serving loops, harnesses that forbid allocation): same arguments without ws_dev /
+ * ws_bytes, same kernels, same result bit for bit.  The per-workgroup partial sums go to a fixed array of 229,824 bytes
+ * that is part of the library's device code (every GPU the library runs on holds it until the process ends); the call
+ * itself allocates and frees nothing.  out_host must lie in pinned (device-visible) host memory, which the GPU writes
+ * in place (BOF4_ERR_ARG otherwise); n must not exceed BOF4_STATIC_MAX_N (BOF4_ERR_ARG otherwise).  All calls on one
+ * GPU share the array, which keeps the last call's contents (every launch overwrites the records it reads, nothing has
+ * to start at zero): two calls that overlap in time on one GPU - different streams or threads - race and give wrong
+ * sums.  The first call on a device looks the array's address up (with that device current).
+ */
+#define BOF4_STATIC_MAX_N (1ull << 36)
+int bof4_lloyd_step_static(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                           double opq_T, int weight_by_max2, bof4_lloyd_stats* out_host, void* stream);
+
 /* Maximisation step (section 3.2, eq. 6 and its last paragraph): level l moves to num[l]/den[l] unless bit l of
  * pinned_mask is set or the region is empty (den[l] == 0).  Pure host function; cb_host is updated in place. */
 int bof4_codebook_update(const bof4_lloyd_stats* stats_host, uint16_t pinned_mask, double* cb_host);

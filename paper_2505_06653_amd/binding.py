@@ -16,6 +16,7 @@ BOF4_OK, BOF4_ERR_ARG, BOF4_ERR_CAPACITY, BOF4_ERR_WORKSPACE, BOF4_ERR_HIP = 0, 
 EXPORTS = ("bof4_workspace_bytes", "bof4_opq_threshold", "bof4_thresholds", "bof4_bin_table", "bof4_lloyd_step",
            "bof4_codebook_update", "bof4_lloyd_step_mae", "bof4_codebook_update_mae", "bof4_quantize",
            "bof4_dequantize", "bof4_quantize_begin", "bof4_quantize_finish", "bof4_lloyd_step_begin", "bof4_wait_result",
+           "bof4_lloyd_step_static",
            "bof4_quant_error", "bof4_gemv", "bof4_gemv_outlier_table",
            "bof4_gemv_outlier_table_bytes", "bof4_gemm", "bof4_gemm_pack", "bof4_gemm_packed_bytes",
            "bof4_gemm_outlier_table", "bof4_gemm_workspace_bytes",
@@ -99,6 +100,9 @@ def lib():
             getattr(L, name).argtypes = L.bof4_quantize.argtypes
         L.bof4_lloyd_step_begin.restype = ctypes.c_int
         L.bof4_lloyd_step_begin.argtypes = L.bof4_lloyd_step.argtypes
+        L.bof4_lloyd_step_static.restype = ctypes.c_int
+        L.bof4_lloyd_step_static.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint32, f64p, ctypes.c_int, ctypes.c_double,
+                                             ctypes.c_int, ctypes.POINTER(LloydStats), vp]
         L.bof4_wait_result.restype = ctypes.c_int
         L.bof4_wait_result.argtypes = [vp, vp]
         L.bof4_dequantize.restype = ctypes.c_int
@@ -477,6 +481,17 @@ def bof4_lloyd_step_begin(w, block, cb, signed, out, opq_T=0.0, weight_by_max2=T
         ws = alloc_workspace(n, block, 0, w.device)
     _check(lib().bof4_lloyd_step_begin(_ptr(w), n, block, cbp, int(signed), float(opq_T), int(bool(weight_by_max2)),
                                        ctypes.byref(out), _ptr(ws), ws.numel(), _stream(stream)))
+    return out
+
+
+def bof4_lloyd_step_static(w, block, cb, signed, out, opq_T=0.0, weight_by_max2=True, stream=None, n=None):
+    """bof4_lloyd_step without a workspace argument (the library's own fixed device array holds the partial sums; no
+    allocation anywhere in the call).  `out`: a LloydStats in pinned host memory (pinned_lloyd_stats()).  `n`: number
+    of weights, if not all of w."""
+    n = w.numel() if n is None else int(n)
+    cb, cbp = _cb(cb)
+    _check(lib().bof4_lloyd_step_static(_ptr(w), n, block, cbp, int(signed), float(opq_T), int(bool(weight_by_max2)),
+                                        ctypes.byref(out), _stream(stream)))
     return out
 
 

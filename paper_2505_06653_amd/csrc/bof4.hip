@@ -1214,7 +1214,31 @@ int bof4_gemv(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t row
 
 }  // extern "C"
 
+// Workspace of bof4_lloyd_step_static: device memory that comes with the library's code object instead of a
+// caller's buffer, for callers that cannot allocate.  Every GPU holds its own copy at its own address; host code
+// must not use the array's name as an address (it is only a handle for hipGetSymbolAddress).
+constexpr size_t STATIC_SCRATCH_BYTES = ((size_t)512 + 1) * 56 * 8;  // = lloyd_ws_bytes(): one record per workgroup + result
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
 namespace {
+static_assert(STATIC_SCRATCH_BYTES == ((size_t)SEG_GRID + 1) * LLOYD_PART * 8, "scratch must hold the Lloyd workspace");
+// Address of `scratch` on the current device, looked up once per device with that device current.
+constexpr int STATIC_MAX_DEVICES = 64;
+std::atomic<void*> g_scratch_ptr[STATIC_MAX_DEVICES];
+int static_scratch(void** out) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= STATIC_MAX_DEVICES) return fail(BOF4_ERR_ARG, "bof4_lloyd_step_static: device index above 63");
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(BOF4_ERR_HIP, "bof4_lloyd_step_static: no address for the scratch array");
+        g_scratch_ptr[dev].store(p, std::memory_order_release);  // every thread finds the same address
+    }
+    *out = p;
+    return BOF4_OK;
+}
+
 // wait = false: enqueue only; the record must lie in pinned host memory, where bof4_wait_result finds it.
 int lloyd_step_impl(bool wait, const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
                     double opq_T, int weight_by_max2, bof4_lloyd_stats* out_host, void* ws_dev, size_t ws_bytes,
@@ -1234,6 +1258,11 @@ int lloyd_step_impl(bool wait, const void* w_dev, uint64_t n, uint32_t block, co
     const double T2 = opq_T * opq_T;
     const bool opq = opq_T > 0.0;
     const uint4* w = (const uint4*)w_dev;
+    // If the caller's struct lies in pinned (device-visible) host memory the final kernel writes it in place;
+    // otherwise the record goes through the workspace and one copy.
+    double* direct = (double*)device_view_of_host(out_host);
+    if (!wait && !direct)
+        return fail(BOF4_ERR_ARG, "bof4_lloyd_step_begin: the record must lie in pinned host memory");
     {
         BinTable bt = make_bin_table(cb);
         const uint64_t tiles = (n_seg + 63) / 64;
@@ -1260,13 +1289,9 @@ int lloyd_step_impl(bool wait, const void* w_dev, uint64_t n, uint32_t block, co
         }
 #undef BOF4_LAUNCH_SEGL
         timing_end(s);
-        // The result record has the layout of bof4_lloyd_stats.  If the caller's struct lies in pinned (device-visible)
-        // host memory the final kernel writes it in place; otherwise it goes through the workspace and one copy.
+        // The result record has the layout of bof4_lloyd_stats.
         static_assert(sizeof(bof4_lloyd_stats) == 51 * 8, "result record and bof4_lloyd_stats must match");
         double* rec_dev = partials + (uint64_t)n_part * LLOYD_PART;
-        double* direct = (double*)device_view_of_host(out_host);
-        if (!wait && !direct)
-            return fail(BOF4_ERR_ARG, "bof4_lloyd_step_begin: the record must lie in pinned host memory");
         if (direct) out_host->n_used = FLAG_PENDING;  // the word the final kernel writes last
         hipLaunchKernelGGL(seg_lloyd_final_kernel, dim3(1), dim3(1024), 0, s, partials, n_part, cb, bt.code_of_zero,
                            direct ? direct : rec_dev);
@@ -1297,6 +1322,19 @@ int bof4_lloyd_step_begin(const void* w_dev, uint64_t n, uint32_t block, const d
                           void* stream) {
     return lloyd_step_impl(false, w_dev, n, block, cb_host, signed_norm, opq_T, weight_by_max2, out_host, ws_dev,
                            ws_bytes, stream);
+}
+
+int bof4_lloyd_step_static(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                           double opq_T, int weight_by_max2, bof4_lloyd_stats* out_host, void* stream) {
+    if (n > BOF4_STATIC_MAX_N)
+        return fail(BOF4_ERR_ARG, "bof4_lloyd_step_static: n exceeds BOF4_STATIC_MAX_N (2^36 weights)");
+    if (!out_host || !device_view_of_host(out_host))
+        return fail(BOF4_ERR_ARG, "bof4_lloyd_step_static: the record must lie in pinned host memory");
+    void* ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != BOF4_OK) return rc;
+    return lloyd_step_impl(true, w_dev, n, block, cb_host, signed_norm, opq_T, weight_by_max2, out_host, ws,
+                           STATIC_SCRATCH_BYTES, stream);
 }
 
 int bof4_wait_result(const uint64_t* word_host, void* stream) {
