@@ -9,7 +9,7 @@ import pytest
 import torch
 
 import oracle
-import par_oracle
+from oracle import parallel as par_oracle
 from paper_2505_06653_amd import binding, codebooks, inputs
 from test_gpu_parity import assert_stats_close, to_np_u16
 
