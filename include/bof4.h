@@ -58,7 +58,7 @@ double bof4_opq_threshold(double q, uint32_t block);
 int bof4_thresholds(const double* cb_host, float* thr_host);
 
 /* The bin table of the kernels' branch-free nearest-level search (same rule as bof4_thresholds, different
- * evaluation): a normalised weight x in [-1, 1] falls into bin b = (bits(fma(x, 16, 2^20 + 16)) & 0x1F8) / 8 of 33,
+ * evaluation): a normalised weight x in [-1, 1] falls into bin b = (bits(fma(x, 16, 2^20 + 16)) >> 3) & 63 of 33,
  * and code(x) = base33[b] + (x > thr33[b]).  *fast_host is 0 when the codebook does not fit this form (two thresholds
  * within one bin, or one closer to zero than 2^-30); the kernels then count the 15 thresholds.  Pure host function. */
 int bof4_bin_table(const double* cb_host, float* thr33_host, uint32_t* base33_host, int* fast_host);
@@ -99,7 +99,7 @@ int bof4_wait_result(const uint64_t* word_host, void* stream);
 /*
  * bof4_lloyd_step for callers that cannot allocate device memory or hand in a workspace (code that runs where
  * hipMalloc is not allowed, tight serving loops, harnesses that forbid allocation): same arguments without ws_dev /
- * ws_bytes, same kernels, same result bit for bit.  The per-workgroup partial sums go to a fixed array of 229,824 bytes
+ * ws_bytes, same kernels, same result bit for bit.  The per-workgroup partial sums go to a fixed array of 459,200 bytes
  * that is part of the library's device code (every GPU the library runs on holds it until the process ends); the call
  * itself allocates and frees nothing.  out_host must lie in pinned (device-visible) host memory, which the GPU writes
  * in place (BOF4_ERR_ARG otherwise); n must not exceed BOF4_STATIC_MAX_N (BOF4_ERR_ARG otherwise).  All calls on one

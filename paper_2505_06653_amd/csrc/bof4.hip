@@ -107,7 +107,7 @@ uint32_t host_bin(float x) {
     float t = std::fmaf(x, BIN_SCALE, BIN_MAGIC);
     uint32_t u;
     std::memcpy(&u, &t, 4);
-    return (u & BIN_MASK) >> 3;
+    return (u & BIN_MASK) >> BIN_SHIFT;
 }
 // Builds the per-bin (threshold, base code) table: for x in bin b, code(x) = base[b] + (x > thr[b]).  A bin that
 // two thresholds cut, or a threshold too close to zero, switches the shortcut path off (fast = 0).
@@ -173,7 +173,10 @@ QuantWsLayout quant_ws_layout(uint64_t n, uint64_t cap) {
     L.total = o;
     return L;
 }
-constexpr uint32_t SEG_GRID = 512;              // persistent workgroups of the Lloyd kernel (2 per CU, LDS-bound)
+constexpr uint32_t SEG_GRID = 512;              // persistent workgroups of the MAE and error kernels (2 per CU)
+// persistent workgroups of the Lloyd kernel: as many as the 256 compute units hold at once
+constexpr uint32_t lloyd_grid(bool opq) { return 256u * (uint32_t)lloyd_waves_per_simd(opq); }
+constexpr uint32_t LLOYD_GRID_MAX = 1024;        // what the workspace is sized for
 constexpr uint32_t QUANT_GRID = 768;              // persistent workgroups of the quantise kernel (3 per CU)
 struct SegWsLayout {
     size_t header, wave_count, idx, val, total;
@@ -231,7 +234,9 @@ hipError_t wait_for_flag(hipStream_t s, const uint64_t* flag_host) {
     }
     return hipStreamSynchronize(s);
 }
-size_t lloyd_ws_bytes() { return ((size_t)SEG_GRID + 1) * LLOYD_PART * 8; }
+size_t lloyd_ws_bytes() { return ((size_t)LLOYD_GRID_MAX + 1) * LLOYD_PART * 8; }
+static_assert(lloyd_grid(false) <= LLOYD_GRID_MAX && lloyd_grid(true) <= LLOYD_GRID_MAX && SEG_GRID <= LLOYD_GRID_MAX,
+              "workspace sized for fewer workgroups");
 // MAE step: histogram, search state, per-wave counts, per-workgroup floating-point partials, result record.
 // Entries of the candidate list of the MAE step: n / 32 (about five times what a pass leaves), at most 2^27; dealt
 // out evenly to the waves of the pass kernels.
@@ -660,7 +665,7 @@ int bof4_quant_error(const void* w_dev, uint64_t n, uint32_t block, const double
     if (!(opq_T >= 0.0) || !std::isfinite(opq_T)) return fail(BOF4_ERR_ARG, "bof4_quant_error: opq_T must be finite and >= 0");
     if (!aligned(w_dev, 16)) return fail(BOF4_ERR_ARG, "bof4_quant_error: misaligned weights");
     if (!ws_dev || !aligned(ws_dev, 256)) return fail(BOF4_ERR_ARG, "bof4_quant_error: workspace null or misaligned");
-    static_assert((SEG_GRID + 2) * ERR_PART <= (SEG_GRID + 1) * LLOYD_PART, "the Lloyd workspace holds the error records");
+    static_assert((SEG_GRID + 2) * ERR_PART <= (LLOYD_GRID_MAX + 1) * LLOYD_PART, "the Lloyd workspace holds the error records");
     if (ws_bytes < lloyd_ws_bytes()) return fail(BOF4_ERR_WORKSPACE, "bof4_quant_error: workspace too small");
     static_assert(sizeof(bof4_error_stats) == 5 * 8, "result record and bof4_error_stats must match");
     hipStream_t s = (hipStream_t)stream;
@@ -1217,11 +1222,11 @@ int bof4_gemv(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t row
 // Workspace of bof4_lloyd_step_static: device memory that comes with the library's code object instead of a
 // caller's buffer, for callers that cannot allocate.  Every GPU holds its own copy at its own address; host code
 // must not use the array's name as an address (it is only a handle for hipGetSymbolAddress).
-constexpr size_t STATIC_SCRATCH_BYTES = ((size_t)512 + 1) * 56 * 8;  // = lloyd_ws_bytes(): one record per workgroup + result
+constexpr size_t STATIC_SCRATCH_BYTES = ((size_t)1024 + 1) * 56 * 8;  // = lloyd_ws_bytes(): one record per workgroup + result
 static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
 
 namespace {
-static_assert(STATIC_SCRATCH_BYTES == ((size_t)SEG_GRID + 1) * LLOYD_PART * 8, "scratch must hold the Lloyd workspace");
+static_assert(STATIC_SCRATCH_BYTES == ((size_t)LLOYD_GRID_MAX + 1) * LLOYD_PART * 8, "scratch must hold the Lloyd workspace");
 // Address of `scratch` on the current device, looked up once per device with that device current.
 constexpr int STATIC_MAX_DEVICES = 64;
 std::atomic<void*> g_scratch_ptr[STATIC_MAX_DEVICES];
@@ -1267,7 +1272,7 @@ int lloyd_step_impl(bool wait, const void* w_dev, uint64_t n, uint32_t block, co
         BinTable bt = make_bin_table(cb);
         const uint64_t tiles = (n_seg + 63) / 64;
         uint64_t wantg = (tiles + WAVES_PER_WG - 1) / WAVES_PER_WG;
-        const uint32_t sgrid = (uint32_t)(wantg < SEG_GRID ? wantg : SEG_GRID);
+        const uint32_t sgrid = (uint32_t)(wantg < lloyd_grid(opq) ? wantg : lloyd_grid(opq));
         const uint32_t n_part = sgrid;  // one partial record per workgroup
         timing_begin(s);
 #define BOF4_LAUNCH_SEGL(II)                                                                                           \

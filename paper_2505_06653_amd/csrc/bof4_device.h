@@ -19,18 +19,29 @@ struct CodebookArgs {
 };
 
 // Bin table for the branch-free nearest-level search.  x in [-1, 1] is mapped to one of 33 bins of width 1/16 by
-// bin(x) = (bits(fma(x, 16, 2^20 + 16)) & 0x1F8) / 8 (monotone in x).  The host puts at most one threshold into each
-// bin: code(x) = base[bin] + (x > thr[bin]).  `fast` is 0 if some bin would need two thresholds or a threshold is
-// too close to zero for the shortcut division; the kernels then use the 15-compare search.
+// bin(x) = (bits(fma(x, 16, BIN_MAGIC)) & BIN_MASK) >> BIN_SHIFT (monotone in x): BIN_MAGIC = 2^(23 - BIN_SHIFT) + 16
+// has an ulp of 2^-BIN_SHIFT, so the mantissa of the sum holds 16 (1 + x) in fixed point with the integer part - the
+// bin - from bit BIN_SHIFT up.  The host puts at most one threshold into each bin: code(x) = base[bin] + (x >
+// thr[bin]).  `fast` is 0 if some bin would need two thresholds or a threshold is too close to zero for the shortcut
+// division; the kernels then use the 15-compare search.
 struct BinTable {
     float thr[33];
     uint32_t base[33];
     uint32_t code_of_zero;
     uint32_t fast;
 };
+#ifndef BOF4_BIN_SHIFT
+#define BOF4_BIN_SHIFT 3
+#endif
+constexpr int BIN_SHIFT = BOF4_BIN_SHIFT;
 constexpr float BIN_SCALE = 16.0f;
-constexpr float BIN_MAGIC = 1048576.0f + 16.0f;  // 2^20 + 16: ulp 1/8, mantissa = round(128 (x + 1))
-constexpr uint32_t BIN_MASK = 0x1F8u;
+constexpr float BIN_MAGIC = (float)(1u << (23 - BIN_SHIFT)) + 16.0f;
+constexpr uint32_t BIN_MASK = 0x3Fu << BIN_SHIFT;
+// In LDS a bin's entry (threshold, base code: 8 bytes) is repeated BIN_COPIES times, filling the 2^BIN_SHIFT bytes
+// between two bin addresses; lane l reads copy l mod BIN_COPIES.  With 16 copies the 16 lanes that the LDS unit serves
+// together always read from 16 different bank pairs, whatever their bins.
+constexpr int BIN_COPIES = (1 << BIN_SHIFT) / 8;
+constexpr int BIN_TABLE_ENTRIES = 33 * BIN_COPIES;
 
 // ---------------------------------------------------------------------------------------------- bit helpers
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
@@ -52,6 +63,19 @@ __device__ __forceinline__ float f16_bits_to_f32(uint32_t b) {
     _Float16 h;
     __builtin_memcpy(&h, &s, 2);
     return (float)h;
+}
+
+// Fill the LDS copy of the bin table (every lane of the workgroup takes part; the caller synchronises afterwards).
+__device__ __forceinline__ void bin_table_fill(uint2* tab, const BinTable& bt, uint32_t tid, uint32_t n_threads) {
+    for (uint32_t i = tid; i < (uint32_t)BIN_TABLE_ENTRIES; i += n_threads)
+        tab[i] = make_uint2(__float_as_uint(bt.thr[i / BIN_COPIES]), bt.base[i / BIN_COPIES]);
+}
+// Byte offset of the lane's copy inside a bin's stretch of the table.
+__device__ __forceinline__ uint32_t bin_lane_offset(uint32_t lane) { return (lane & (uint32_t)(BIN_COPIES - 1)) * 8u; }
+// The (threshold, base code) entry of the bin that x falls into.
+__device__ __forceinline__ uint2 bin_lookup(const uint2* tab, float x, uint32_t lane_off) {
+    const uint32_t off = (__float_as_uint(__builtin_fmaf(x, BIN_SCALE, BIN_MAGIC)) & BIN_MASK) | lane_off;
+    return *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(tab) + off);
 }
 
 // 16-byte load of data that is read exactly once (streaming: do not keep it in the caches).
@@ -150,27 +174,29 @@ __device__ __forceinline__ int assign_code_generic(float x, const CodebookArgs& 
 
 // ---------------------------------------------------------------------------------------------- shortcut division
 // x = w / m for a bfloat16 w and a block constant m that is a bfloat16 number inside binary16's normal range
-// (so the stored binary16 constant equals m).  r = rcp(m) is within 1 ulp of 1/m; q0 = fl(w r) is within a few
-// ulp of w/m; rem = w - q0 m is exact (fma, no underflow for |w| >= 2^-60); q1 = fl(q0 + rem r) is the rounding of
-// a number within 2^-21 ulp of w/m.  w has 8 and m 8 significant bits, so w/m lies at least 2^-12 ulp away from
-// every rounding boundary of binary32 and never on one: q1 is the correctly rounded quotient.  (Checked
-// exhaustively against the hardware's IEEE division in the GPU tests.)  For |w| < 2^-60 the result may differ in
-// the last bits of a number below 2^-45; the host only enables this path when no threshold is that small.
+// (so the stored binary16 constant equals m), in two operations per weight.  Per block: rh = rcp(m), within 1 ulp
+// of 1/m; d = 1 - m rh, exact (the product has 32 significant bits of which the leading ~23 cancel); rl = fl(d rh).
+// Then rh + rl = (1/m)(1 + e) with |e| < 2^-44.  Per weight: t = fl(w rl), x = fl(w rh + t) (one fused
+// multiply-add): the rounding of a number within 2^-43 (relative) of w / m.  w and m have 8 significant bits each,
+// so w / m lies at least 2^-33 (relative) away from every rounding boundary of binary32 and never on one: x is the
+// correctly rounded quotient.  (Checked exhaustively against the hardware's IEEE division in the GPU tests.)  For
+// |w| < 2^-60 the product w rl can fall among the subnormals and the result may differ in the last bits of a number
+// below 2^-45; the host only enables this path when no threshold is that small.
 struct BlockDiv {
-    float m;     // divisor (1 for a zero block)
-    float rinv;  // rcp(m) (0 for a zero block, which makes every quotient +-0)
+    float rh;  // rcp(m) (0 for a zero block, which makes every quotient +-0)
+    float rl;  // the correction (1/m - rh) to within 2^-23 of itself
 };
 __device__ __forceinline__ BlockDiv make_block_div(float m_eff) {
     BlockDiv d;
-    bool zero = (m_eff == 0.0f);
-    d.m = zero ? 1.0f : m_eff;
-    d.rinv = zero ? 0.0f : __builtin_amdgcn_rcpf(m_eff);
+    const bool zero = (m_eff == 0.0f);
+    const float r = __builtin_amdgcn_rcpf(zero ? 1.0f : m_eff);
+    const float e = __builtin_fmaf(-m_eff, r, 1.0f);
+    d.rh = zero ? 0.0f : r;
+    d.rl = zero ? 0.0f : e * r;
     return d;
 }
 __device__ __forceinline__ float div_fast(float w, const BlockDiv& d) {
-    float q0 = w * d.rinv;
-    float rem = __builtin_fmaf(-q0, d.m, w);
-    return __builtin_fmaf(rem, d.rinv, q0);
+    return __builtin_fmaf(w, d.rh, w * d.rl);
 }
 
 // A block constant qualifies for the shortcut path if it is zero or a bfloat16 inside binary16's normal range

@@ -38,16 +38,17 @@ __global__ __launch_bounds__(256, 2) void seg_error_kernel(const uint4* __restri
                                                          double* __restrict__ partials) {
     using C = SegCfg<I>;
     struct Shared {  // one object, so that the tables sit at the start of LDS (reachable by immediate offsets)
-        uint2 tab[40];
+        uint2 tab[BIN_TABLE_ENTRIES];
         float lv[16];
         char stage[WAVES_PER_WG * C::STAGE_BYTES];
     };
     __shared__ __attribute__((aligned(16))) Shared sh;
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < 33) sh.tab[tid] = make_uint2(__float_as_uint(bt.thr[tid]), bt.base[tid]);
+    bin_table_fill(sh.tab, bt, tid, blockDim.x);
     if (tid < 16) sh.lv[tid] = cb.lv32[tid];
     __syncthreads();
     const uint2* tab = sh.tab;
+    const uint32_t lane_off = bin_lane_offset(threadIdx.x & 63u);
     const float* lv = sh.lv;
     char* stage = sh.stage + wave * C::STAGE_BYTES;
     const uint64_t n_vec = n_seg * C::NV;
@@ -97,8 +98,7 @@ __global__ __launch_bounds__(256, 2) void seg_error_kernel(const uint4* __restri
                     for (int e = 0; e < 8; ++e) {  // eight table reads in flight
                         f[e] = seg_f32(R, b0 + e);
                         x[e] = div_fast(f[e], dv);
-                        uint32_t off = __float_as_uint(__builtin_fmaf(x[e], BIN_SCALE, BIN_MAGIC)) & BIN_MASK;
-                        en[e] = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(tab) + off);
+                        en[e] = bin_lookup(tab, x[e], lane_off);
                     }
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {  // then eight level reads

@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
     // full).  `cand`: append the elements that still count to this wave's stretch of the list.
     if (gate != nullptr && *gate == 0u) return;
     struct Shared {  // one object, so that the table sits at LDS offset 0 (reachable by an immediate offset)
-        uint2 tab[40];
+        uint2 tab[BIN_TABLE_ENTRIES];
         uint4 info[16];    // per region: klo, (lo | hi << 8 | digit mask << 16), then prefix and active flag -
                            // in the first pass (no prefix yet, every region active) the region's level as binary64
         unsigned long long hist[16 * 256];
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
     };
     __shared__ __attribute__((aligned(16))) Shared sh;
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < 33) sh.tab[tid] = make_uint2(__float_as_uint(bt.thr[tid]), bt.base[tid]);
+    bin_table_fill(sh.tab, bt, tid, blockDim.x);
     if (tid < 16) {
         const MaeLevelState s = state[tid];
         const uint32_t hi = s.hi, lo = hi > 8 ? hi - 8 : 0;
@@ -111,6 +111,7 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
     }
     __syncthreads();
     const uint2* tab = sh.tab;
+    const uint32_t lane_off = bin_lane_offset(threadIdx.x & 63u);
     char* stage = sh.stage + wave * C::STAGE_BYTES;
     const uint64_t n_vec = n_seg * C::NV;
     const uint64_t n_tiles = (n_seg + 63) / 64;
@@ -186,8 +187,7 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
                         x[e] = div_fast(seg_f32(R, b0 + e), dv);
-                        const uint32_t off = __float_as_uint(__builtin_fmaf(x[e], BIN_SCALE, BIN_MAGIC)) & BIN_MASK;
-                        en[e] = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(tab) + off);
+                        en[e] = bin_lookup(tab, x[e], lane_off);
                     }
 #pragma unroll
                     for (int e = 0; e < 8; ++e) code[e] = en[e].y + (x[e] > __uint_as_float(en[e].x) ? 1u : 0u);

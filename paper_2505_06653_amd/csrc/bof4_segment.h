@@ -269,14 +269,15 @@ __global__ __launch_bounds__(256, 3) void seg_quantize_kernel(const uint4* __res
                                                             uint16_t* __restrict__ scales, OutlierStage os) {
     using C = SegCfg<I>;
     struct Shared {  // one object, so that the table sits at LDS offset 0 (reachable by an immediate offset)
-        uint2 tab[40];
+        uint2 tab[BIN_TABLE_ENTRIES];
         char stage[WAVES_PER_WG * C::STAGE_BYTES];
     };
     __shared__ __attribute__((aligned(16))) Shared sh;
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < 33) sh.tab[tid] = make_uint2(__float_as_uint(bt.thr[tid]), bt.base[tid]);
+    bin_table_fill(sh.tab, bt, tid, blockDim.x);
     __syncthreads();
     const uint2* tab = sh.tab;
+    const uint32_t lane_off = bin_lane_offset(threadIdx.x & 63u);
     char* stage = sh.stage + wave * C::STAGE_BYTES;
     const uint64_t n_vec = n_seg * C::NV;
     const uint64_t n_tiles = (n_seg + 63) / 64;
@@ -316,8 +317,7 @@ __global__ __launch_bounds__(256, 3) void seg_quantize_kernel(const uint4* __res
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {  // eight table reads in flight
                     x[e] = div_fast(seg_f32(R, 8 * j + e), dv);
-                    uint32_t off = __float_as_uint(__builtin_fmaf(x[e], BIN_SCALE, BIN_MAGIC)) & BIN_MASK;
-                    en[e] = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(tab) + off);
+                    en[e] = bin_lookup(tab, x[e], lane_off);
                 }
                 uint32_t acc = 0;
 #pragma unroll
@@ -417,63 +417,98 @@ __global__ __launch_bounds__(64) void seg_outlier_gather_kernel(OutlierStage os,
 }
 
 // ================================================================================================ Lloyd step
+// Every lane loads its own segment straight from memory (16-byte loads at a stride of one segment; the lines a wave
+// touches are consumed completely by its next loads, so the caches see every byte once) and keeps the next tile's
+// loads in flight while it works on the current one.
+//
 // Per-level sums of the current block live in lane-private LDS columns acc[level][lane] (conflict-free).  One 64-bit
 // LDS add per weight carries both the count and the sum of x of its level: the increment is the bit pattern of the
 // binary64 number 2^-1008 + (x + 1) 2^-1020, i.e. exponent field 15 and mantissa (x + 1) 2^40 rounded to an
 // integer.  Adding up to 256 of these as integers gives 15 K 2^52 + sum (x + 1) 2^40 with the second term below
-// 2^52, so count K and sum separate again exactly.  Once per block the 16 columns are folded, with the block
-// weight g, into binary64 registers:  A += g sum(x + 1),  den15 += g 15 K,  cnt15 += 15 K.
-// The two constants are passed as kernel arguments (not literals) so that the increment is one three-operand
-// fused multiply-add whose addend register pair is not overwritten.
+// 2^52, so count K and sum separate again exactly.  Once per tile the columns are folded, with the block weights g,
+// into binary64 registers:  A += g sum(x + 1) 2^40,  den15 += g 15 K,  cnt15 += 15 K.
+// The fold is shared inside every quad of lanes: lane 4q + p takes levels 4p .. 4p+3 of the four blocks of its quad
+// (the weights g of the other three arrive by quad permutes), so a lane carries 4 and not 16 sets of accumulators -
+// the registers this frees are what lets four waves share a SIMD.  At any step the 64 lanes read 64 different
+// columns of one level each: conflict-free again.
+// The two increment constants are passed as kernel arguments (not literals) so that the increment is one
+// three-operand fused multiply-add whose addend register pair is not overwritten.
 constexpr double LLOYD_INC_MUL = 0x1p-1020;
 constexpr double LLOYD_INC_ADD = 0x1p-1008 + 0x1p-1020;
 
-// Elements per batch of the Lloyd inner loop: the table reads of a batch are issued together, then its adds.
-constexpr int LLOYD_BATCH = 16;
+// Waves per SIMD the Lloyd kernel is compiled for (the launch bound holds its registers to 512 / that many): four,
+// three with outlier removal, whose statistics need more registers at once.
+__host__ __device__ constexpr int lloyd_waves_per_simd(bool opq) { return opq ? 3 : 4; }
+
+// Where lane `lane` finds its segment of tile `t`.  A lane whose segment lies past the end of the tensor (ragged last
+// tile) is pointed at the tensor's last segment instead: it loads valid memory and takes no part in the sums.
+template <int I>
+__device__ __forceinline__ const uint4* own_segment(const uint4* __restrict__ w, uint64_t t, uint64_t n_seg,
+                                                    uint32_t lane) {
+    const uint64_t seg = t * 64 + lane;
+    return w + (seg < n_seg ? seg : n_seg - 1) * SegCfg<I>::NV;
+}
+// The value of lane (l ^ C) of the same quad, C = 1, 2, 3 (all lanes active).
+template <int C>
+__device__ __forceinline__ float quad_xor(float v) {
+    constexpr int ctrl = C == 1 ? 0xB1 : C == 2 ? 0x4E : 0x1B;  // quad_perm [1,0,3,2] / [2,3,0,1] / [3,2,1,0]
+    return __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), ctrl, 0xf, 0xf, true));
+}
 
 template <int I, bool FAST, bool OPQ>
-__global__ __launch_bounds__(256, 2) void seg_lloyd_kernel(const uint4* __restrict__ w, uint64_t n_seg, CodebookArgs cb,
-                                                         BinTable bt, int signed_norm, int weight_by_max2, double T2,
-                                                         double inc_mul, double inc_add,
-                                                         double* __restrict__ partials) {
+__global__ __launch_bounds__(256, lloyd_waves_per_simd(OPQ)) void seg_lloyd_kernel(
+    const uint4* __restrict__ w, uint64_t n_seg, CodebookArgs cb, BinTable bt, int signed_norm, int weight_by_max2,
+    double T2, double inc_mul, double inc_add, double* __restrict__ partials) {
     using C = SegCfg<I>;
     struct Shared {  // one object, so that the table sits at LDS offset 0 (reachable by an immediate offset)
-        uint2 tab[40];
+        uint2 tab[BIN_TABLE_ENTRIES];
         unsigned long long acc[WAVES_PER_WG * 16 * 64];
-        char stage[WAVES_PER_WG * C::STAGE_BYTES];
     };
     __shared__ __attribute__((aligned(16))) Shared sh;
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < 33) sh.tab[tid] = make_uint2(__float_as_uint(bt.thr[tid]), bt.base[tid]);
+    const uint32_t tid = threadIdx.x, lane = tid & 63;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));  // scalar: tile ranges on the SALU
+    bin_table_fill(sh.tab, bt, tid, blockDim.x);
     const uint2* tab = sh.tab;
+    const uint32_t lane_off = bin_lane_offset(lane);
     unsigned long long* acc = sh.acc + wave * 16 * 64;
 #pragma unroll
     for (int l = 0; l < 16; ++l) acc[l * 64 + lane] = 0ull;
     __syncthreads();
-    char* stage = sh.stage + wave * C::STAGE_BYTES;
-    const uint64_t n_vec = n_seg * C::NV;
     const uint64_t n_tiles = (n_seg + 63) / 64;
     const uint64_t n_waves = (uint64_t)gridDim.x * WAVES_PER_WG;
     const uint64_t gw = (uint64_t)blockIdx.x * WAVES_PER_WG + wave;
     const uint64_t t0 = n_tiles * gw / n_waves, t1 = n_tiles * (gw + 1) / n_waves;
-
-    double A[16], den15[16], sxx_g = 0.0, kout_g = 0.0;
-    uint32_t cnt15[16], kout = 0;
+    // fold: levels 4 p + k (k = 0 .. 3) of the blocks of lanes lane ^ c (c = 0 .. 3)
+    const uint32_t p4 = (lane & 3u) * 4u;
+    unsigned long long* fold_col[4];
 #pragma unroll
-    for (int l = 0; l < 16; ++l) {
-        A[l] = 0.0;
-        den15[l] = 0.0;
-        cnt15[l] = 0;
+    for (int c = 0; c < 4; ++c) fold_col[c] = acc + p4 * 64 + (lane ^ (uint32_t)c);
+
+    double A[4], den15[4], sxx_g = 0.0, kout_g = 0.0;
+    uint32_t cnt15[4], kout = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        A[k] = 0.0;
+        den15[k] = 0.0;
+        cnt15[k] = 0;
     }
-    uint4 G[C::NV];
-    uint32_t R[C::NR];
-    if (t0 < t1) tile_issue_loads<I>(w, t0 * 64 * C::NV, n_vec, lane, G);
+    // R holds the lane's segment of the current tile.  The next tile's segment is requested piece by piece as the
+    // pieces of this one are used up (Rn takes over the registers R gives up), so a lane never holds two whole tiles.
+    uint32_t R[C::NR], Rn[C::NR];
+    if (t0 < t1) {
+        const uint4* p = own_segment<I>(w, t0, n_seg, lane);
+#pragma unroll
+        for (int k = 0; k < C::NV; ++k) {
+            const uint4 q = p[k];
+            R[4 * k] = q.x;
+            R[4 * k + 1] = q.y;
+            R[4 * k + 2] = q.z;
+            R[4 * k + 3] = q.w;
+        }
+    }
     for (uint64_t t = t0; t < t1; ++t) {
-        wave_lds_fence();
-        tile_stage<I>(stage, lane, G);
-        if (t + 1 < t1) tile_issue_loads<I>(w, (t + 1) * 64 * C::NV, n_vec, lane, G);
-        wave_lds_fence();
-        tile_fetch<I>(stage, lane, R);
+        // (after the wave's last tile this requests that tile once more: cached, and never used)
+        const uint4* pn = own_segment<I>(w, t + 1 < t1 ? t + 1 : t, n_seg, lane);
         const uint64_t seg = t * 64 + lane;
         const bool active = seg < n_seg;
         uint32_t k_out = 0;
@@ -486,85 +521,122 @@ __global__ __launch_bounds__(256, 2) void seg_lloyd_kernel(const uint4* __restri
         block_constant<I>(R, lane, signed_norm != 0, maxabs, sign);
         const float m = bf16_bits_to_f32(maxabs | (sign << 15));
         const float m_eff = f16_bits_to_f32(f32_to_f16_bits(m));
-        const double g = weight_by_max2 ? (double)m_eff * (double)m_eff : 1.0;
+        // the square of a binary16 number has 22 significant bits and an exponent in [-48, 32]: exact in binary32
+        const float g = weight_by_max2 ? m_eff * m_eff : 1.0f;
         double sxx = 0.0;
         bool fast = FAST && __builtin_amdgcn_ballot_w64(!maxabs_is_ordinary(maxabs)) == 0;
-        if (active) {
-            if (fast) {
-                const BlockDiv dv = make_block_div(m_eff);
+        // (lanes past the end of the tensor work on a copy of its last segment; their columns are cleared below)
+        if (fast) {
+            const BlockDiv dv = make_block_div(m_eff);
 #pragma unroll
-                for (int b0 = 0; b0 < C::SEG; b0 += LLOYD_BATCH) {
-                    float x[LLOYD_BATCH];
-                    uint2 en[LLOYD_BATCH];
+            for (int b0 = 0; b0 < C::SEG; b0 += 8) {
+                float x[8];
+                uint2 en[8];
 #pragma unroll
-                    for (int e = 0; e < LLOYD_BATCH; ++e) {  // table reads of a whole batch in flight ...
-                        x[e] = div_fast(seg_f32(R, b0 + e), dv);
-                        uint32_t off = __float_as_uint(__builtin_fmaf(x[e], BIN_SCALE, BIN_MAGIC)) & BIN_MASK;
-                        en[e] = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(tab) + off);
-                    }
-#pragma unroll
-                    for (int e = 0; e < LLOYD_BATCH; ++e) {  // ... before the first LDS add of the batch
-                        uint32_t code = en[e].y + (x[e] > __uint_as_float(en[e].x) ? 1u : 0u);
-                        double xd = (double)x[e];
-                        double inc = fma(xd, inc_mul, inc_add);
-                        atomicAdd(&acc[code * 64 + lane], (unsigned long long)__double_as_longlong(inc));
-                        sxx = fma(xd, xd, sxx);
-                    }
+                for (int e = 0; e < 8; ++e) {  // table reads of a whole batch in flight ...
+                    x[e] = div_fast(seg_f32(R, b0 + e), dv);
+                    en[e] = bin_lookup(tab, x[e], lane_off);
                 }
-
-            } else {
+                {  // these four registers of R are free now: the next tile's piece moves in
+                    const uint4 q = pn[b0 / 8];
+                    Rn[b0 / 2] = q.x;
+                    Rn[b0 / 2 + 1] = q.y;
+                    Rn[b0 / 2 + 2] = q.z;
+                    Rn[b0 / 2 + 3] = q.w;
+                }
 #pragma unroll
-                for (int e = 0; e < C::SEG; ++e) {
-                    float f = seg_f32(R, e);
-                    float x = (m_eff == 0.0f) ? 0.0f : f / m_eff;
-                    uint32_t code = (uint32_t)assign_code_generic(x, cb);
-                    double xd = (double)x;
+                for (int e = 0; e < 8; ++e) {  // ... before the first LDS add of the batch
+                    uint32_t code = en[e].y + (x[e] > __uint_as_float(en[e].x) ? 1u : 0u);
+                    double xd = (double)x[e];
                     double inc = fma(xd, inc_mul, inc_add);
                     atomicAdd(&acc[code * 64 + lane], (unsigned long long)__double_as_longlong(inc));
                     sxx = fma(xd, xd, sxx);
                 }
+                __builtin_amdgcn_sched_barrier(0);  // batches stay apart: mixing them costs more registers than it gains
             }
-            const double gs = g * 0x1p-40;
-            unsigned long long col[16];
+        } else {
 #pragma unroll
-            for (int l = 0; l < 16; ++l) col[l] = atomicExch(&acc[l * 64 + lane], 0ull);  // read and clear, 16 in flight
+            for (int e = 0; e < C::SEG; ++e) {
+                float f = seg_f32(R, e);
+                float x = (m_eff == 0.0f) ? 0.0f : f / m_eff;
+                uint32_t code = (uint32_t)assign_code_generic(x, cb);
+                double xd = (double)x;
+                double inc = fma(xd, inc_mul, inc_add);
+                atomicAdd(&acc[code * 64 + lane], (unsigned long long)__double_as_longlong(inc));
+                sxx = fma(xd, xd, sxx);
+                if ((e & 7) == 7) __builtin_amdgcn_sched_barrier(0);
+            }
+            {
 #pragma unroll
-            for (int l = 0; l < 16; ++l) {
-                unsigned long long v = col[l];
-                uint32_t hi = (uint32_t)(v >> 32), lo = (uint32_t)v;
-                uint32_t k15 = hi >> 20;
+                for (int k = 0; k < C::NV; ++k) {
+                    const uint4 q = pn[k];
+                    Rn[4 * k] = q.x;
+                    Rn[4 * k + 1] = q.y;
+                    Rn[4 * k + 2] = q.z;
+                    Rn[4 * k + 3] = q.w;
+                }
+            }
+        }
+        const double gd = active ? (double)g : 0.0;
+        sxx_g = fma(gd, sxx, sxx_g);
+        if (OPQ) {  // the zeroed outliers went into the sums as x = 0; remember what to take out again
+            kout_g = fma(gd, (double)k_out, kout_g);
+            kout += active ? k_out : 0u;
+        }
+        if (t * 64 + 64 > n_seg) {  // wave-uniform: the ragged last tile of the tensor
+            wave_lds_fence();
+            if (!active) {
+#pragma unroll
+                for (int l = 0; l < 16; ++l) acc[l * 64 + lane] = 0ull;
+            }
+        }
+        // fold (all lanes)
+        wave_lds_fence();
+        const float gq[4] = {g, quad_xor<1>(g), quad_xor<2>(g), quad_xor<3>(g)};
+        unsigned long long col[16];
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) col[4 * c + k] = atomicExch(fold_col[c] + k * 64, 0ull);  // read and clear
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const double gc = (double)gq[c];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const unsigned long long v = col[4 * c + k];
+                const uint32_t hi = (uint32_t)(v >> 32), lo = (uint32_t)v;
+                const uint32_t k15 = hi >> 20;
                 // 2^52 + sum: the column's mantissa under the exponent of 2^52 (one bit-field insert)
                 uint32_t dhi;
                 asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(dhi) : "v"(0xFFFFFu), "v"(hi), "v"(0x43300000u));
-                double D = __hiloint2double((int)dhi, (int)lo) - 0x1p52;  // sum (x+1) 2^40
-                A[l] = fma(gs, D, A[l]);
-                den15[l] = fma(g, (double)k15, den15[l]);
-                cnt15[l] += k15;
-            }
-            sxx_g = fma(g, sxx, sxx_g);
-            if (OPQ) {  // the zeroed outliers went into the sums as x = 0; remember what to take out again
-                kout_g = fma(g, (double)k_out, kout_g);
-                kout += k_out;
+                const double D = __hiloint2double((int)dhi, (int)lo) - 0x1p52;  // sum (x+1) 2^40
+                A[k] = fma(gc, D, A[k]);
+                den15[k] = fma(gc, (double)k15, den15[k]);
+                cnt15[k] += k15;
             }
         }
+        wave_lds_fence();
+#pragma unroll
+        for (int d = 0; d < C::NR; ++d) R[d] = Rn[d];
     }
-    // fixed-order butterfly inside the wave, then the four waves of the workgroup in wave order
+    // Lanes with the same p hold partial sums of the same four levels: fixed-order butterfly over the other lane bits,
+    // then the four waves of the workgroup in wave order.
     __shared__ double wave_totals[WAVES_PER_WG * LLOYD_PART];
     double* wtot = wave_totals + wave * LLOYD_PART;
 #pragma unroll
-    for (int l = 0; l < 16; ++l) {
-        double a = A[l], d = den15[l];
-        unsigned long long c = cnt15[l];
+    for (int k = 0; k < 4; ++k) {
+        double a = A[k] * 0x1p-40, d = den15[k];
+        unsigned long long c = cnt15[k];
 #pragma unroll
-        for (int mk = 32; mk >= 1; mk >>= 1) {
+        for (int mk = 32; mk >= 4; mk >>= 1) {
             a += __shfl_xor(a, mk, 64);
             d += __shfl_xor(d, mk, 64);
             c += (unsigned long long)__shfl_xor((long long)c, mk, 64);
         }
-        if (lane == 0) {
-            wtot[l] = a;
-            wtot[16 + l] = d;
-            wtot[32 + l] = __longlong_as_double((long long)c);
+        if (lane < 4) {
+            wtot[p4 + k] = a;
+            wtot[16 + p4 + k] = d;
+            wtot[32 + p4 + k] = __longlong_as_double((long long)c);
         }
     }
     {

@@ -13,9 +13,10 @@ using namespace bof4;
 // nearest-level search with the 15-compare search.  out[0] quotient mismatches for |w| >= 2^-60 (or w = 0),
 // out[1] quotient mismatches for tiny |w|, out[2] code mismatches, out[3] |x| > 1, out[4] pairs checked.
 __global__ __launch_bounds__(256) void check_pairs_kernel(CodebookArgs cb, BinTable bt, unsigned long long* out) {
-    __shared__ uint2 tab[40];
-    if (threadIdx.x < 33) tab[threadIdx.x] = make_uint2(__float_as_uint(bt.thr[threadIdx.x]), bt.base[threadIdx.x]);
+    __shared__ uint2 tab[BIN_TABLE_ENTRIES];
+    bin_table_fill(tab, bt, threadIdx.x, blockDim.x);
     __syncthreads();
+    const uint32_t lane_off = bin_lane_offset(threadIdx.x & 63u);
     const uint32_t mi = blockIdx.x;  // 0 .. 2*(0x477F-0x3880+1)-1
     const uint32_t span = 0x477Fu - 0x3880u + 1u;
     const uint32_t mabs = 0x3880u + (mi % span);
@@ -35,8 +36,7 @@ __global__ __launch_bounds__(256) void check_pairs_kernel(CodebookArgs cb, BinTa
         const bool same = (__float_as_uint(x) == __float_as_uint(x_ref)) || (x == 0.0f && x_ref == 0.0f);
         if (!same) (tiny ? bad_tiny : bad_q)++;
         if (!(x >= -1.0f && x <= 1.0f)) ++bad_range;
-        const uint32_t off = __float_as_uint(__builtin_fmaf(x, BIN_SCALE, BIN_MAGIC)) & BIN_MASK;
-        const uint2 en = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(tab) + off);
+        const uint2 en = bin_lookup(tab, x, lane_off);
         const uint32_t code = en.y + (x > __uint_as_float(en.x) ? 1u : 0u);
         if (code != (uint32_t)assign_code_generic(x_ref, cb)) ++bad_code;
     }
