@@ -42,9 +42,13 @@ typedef struct {
     uint64_t n_outliers; /* weights excluded by OPQ                                                            */
 } bof4_lloyd_stats;
 
-/* Bytes of device workspace that bof4_quantize (with outlier buffers of `out_capacity` entries; 0 if OPQ is not
- * used), bof4_lloyd_step and bof4_lloyd_step_mae need for `n` weights in blocks of `block` - the largest of the
- * three.  Pure host function; 0 on invalid arguments. */
+/* Bytes of device workspace that bof4_quantize, bof4_quantize_lloyd (with outlier buffers of `out_capacity` entries; 0
+ * if OPQ is not used), bof4_lloyd_step, bof4_quant_error and bof4_lloyd_step_mae need for `n` weights in blocks of
+ * `block` - the largest of them.  What it is made of: for the outlier extraction one staging region per wave of the
+ * largest grid (4096 regions of 4 * ceil(out_capacity / 4096) + 64 entries of 10 bytes: about 40 bytes per entry of
+ * out_capacity, i.e. 0.64 bytes per weight at out_capacity = n / 64), or, if larger, the per-tile tables of the
+ * fallback path (20 bytes per 2048 weights + 10 bytes per entry); behind it 459,200 bytes of partial sums; for the MAE
+ * step n / 4 bytes (its candidate list) + about 0.8 MB.  Pure host function; 0 on invalid arguments. */
 size_t bof4_workspace_bytes(uint64_t n, uint32_t block, uint64_t out_capacity);
 
 /* OPQ threshold T = F_M^{-1}(q) for Gaussian weights (section 3.3 eq. 9 with F_M = (2G-1)^I of appendix B.1):
@@ -191,6 +195,33 @@ int bof4_quantize_finish(const void* w_dev, uint64_t n, uint32_t block, const do
                          double opq_T, uint8_t* codes_dev, uint16_t* scales_dev, int64_t* out_idx_dev,
                          uint16_t* out_val_dev, uint64_t out_capacity, uint64_t* n_outliers_host, void* ws_dev,
                          size_t ws_bytes, void* stream);
+
+/*
+ * Quantise and take the Lloyd sums in one pass over the weights (sections 2.1, 3.1, 3.3 and section 3.2 eq. 6 /
+ * appendix B.3 on the same normalised weights): the outputs of bof4_quantize and the record of bof4_lloyd_step for
+ * the same arguments (codes, constants and the outlier list bit for bit; the sums up to the order of the additions),
+ * reading the weights once instead of twice.  With opq_T > 0 the outliers are extracted and take no part in the sums.
+ * Arguments as for the two calls; ws_dev needs bof4_workspace_bytes(n, block, out_capacity) bytes also when
+ * opq_T == 0 (the partial sums live there).  The call waits for the outlier count and for the record, each as its own
+ * call does (pinned host memory is written by the GPU in place).
+ * bof4_quantize_lloyd_begin / _finish split it like bof4_quantize_begin / _finish: the counter (if opq_T > 0) and the
+ * record must lie in pinned host memory (BOF4_ERR_ARG otherwise); _finish waits for the count and completes the
+ * quantiser's part; the record is complete once bof4_wait_result(&stats_host->n_used, stream) has returned.
+ */
+int bof4_quantize_lloyd(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                        double opq_T, int weight_by_max2, uint8_t* codes_dev, uint16_t* scales_dev,
+                        int64_t* out_idx_dev, uint16_t* out_val_dev, uint64_t out_capacity, uint64_t* n_outliers_host,
+                        bof4_lloyd_stats* stats_host, void* ws_dev, size_t ws_bytes, void* stream);
+int bof4_quantize_lloyd_begin(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                              double opq_T, int weight_by_max2, uint8_t* codes_dev, uint16_t* scales_dev,
+                              int64_t* out_idx_dev, uint16_t* out_val_dev, uint64_t out_capacity,
+                              uint64_t* n_outliers_host, bof4_lloyd_stats* stats_host, void* ws_dev, size_t ws_bytes,
+                              void* stream);
+int bof4_quantize_lloyd_finish(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                               double opq_T, int weight_by_max2, uint8_t* codes_dev, uint16_t* scales_dev,
+                               int64_t* out_idx_dev, uint16_t* out_val_dev, uint64_t out_capacity,
+                               uint64_t* n_outliers_host, bof4_lloyd_stats* stats_host, void* ws_dev, size_t ws_bytes,
+                               void* stream);
 
 /*
  * Dequantise (section 2.1 eq. 3): w~ = block constant * level[code] as one binary32 product rounded to

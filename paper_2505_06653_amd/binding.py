@@ -16,7 +16,7 @@ BOF4_OK, BOF4_ERR_ARG, BOF4_ERR_CAPACITY, BOF4_ERR_WORKSPACE, BOF4_ERR_HIP = 0, 
 EXPORTS = ("bof4_workspace_bytes", "bof4_opq_threshold", "bof4_thresholds", "bof4_bin_table", "bof4_lloyd_step",
            "bof4_codebook_update", "bof4_lloyd_step_mae", "bof4_codebook_update_mae", "bof4_quantize",
            "bof4_dequantize", "bof4_quantize_begin", "bof4_quantize_finish", "bof4_lloyd_step_begin", "bof4_wait_result",
-           "bof4_lloyd_step_static",
+           "bof4_lloyd_step_static", "bof4_quantize_lloyd", "bof4_quantize_lloyd_begin", "bof4_quantize_lloyd_finish",
            "bof4_quant_error", "bof4_gemv", "bof4_gemv_outlier_table",
            "bof4_gemv_outlier_table_bytes", "bof4_gemm", "bof4_gemm_pack", "bof4_gemm_packed_bytes",
            "bof4_gemm_outlier_table", "bof4_gemm_workspace_bytes",
@@ -98,6 +98,11 @@ def lib():
         for name in ("bof4_quantize_begin", "bof4_quantize_finish"):
             getattr(L, name).restype = ctypes.c_int
             getattr(L, name).argtypes = L.bof4_quantize.argtypes
+        for name in ("bof4_quantize_lloyd", "bof4_quantize_lloyd_begin", "bof4_quantize_lloyd_finish"):
+            getattr(L, name).restype = ctypes.c_int
+            getattr(L, name).argtypes = [vp, ctypes.c_uint64, ctypes.c_uint32, f64p, ctypes.c_int, ctypes.c_double,
+                                         ctypes.c_int, vp, vp, vp, vp, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint64),
+                                         ctypes.POINTER(LloydStats), vp, ctypes.c_size_t, vp]
         L.bof4_lloyd_step_begin.restype = ctypes.c_int
         L.bof4_lloyd_step_begin.argtypes = L.bof4_lloyd_step.argtypes
         L.bof4_lloyd_step_static.restype = ctypes.c_int
@@ -445,6 +450,66 @@ def bof4_quantize(w, block, cb, signed, opq_T=0.0, out_capacity=0, codes=None, s
     k = min(int(nout.value), out_capacity)
     return (codes, scales, None if out_idx is None else out_idx[:k], None if out_val is None else out_val[:k],
             int(nout.value))
+
+
+def bof4_quantize_lloyd(w, block, cb, signed, opq_T=0.0, out_capacity=0, weight_by_max2=True, codes=None, scales=None,
+                        out_idx=None, out_val=None, ws=None, stream=None, allow_overflow=False, counter=None,
+                        stats=None, trim=True, raw=False):
+    """bof4_quantize and bof4_lloyd_step in one pass.  Returns (codes, scales, out_idx, out_val, n_outliers, stats):
+    the first five as bof4_quantize returns them, stats as bof4_lloyd_step does (dict, or the struct with raw=True)."""
+    assert w.dtype == torch.bfloat16 and w.is_cuda and w.is_contiguous()
+    n = w.numel()
+    dev = w.device
+    cb, cbp = _cb(cb)
+    if codes is None:
+        codes = torch.empty(max(n // 2, 1), dtype=torch.uint8, device=dev)
+    if scales is None:
+        scales = torch.empty(max(n // max(block, 1), 1), dtype=torch.float16, device=dev)
+    if opq_T > 0:
+        if out_idx is None:
+            out_idx = torch.empty(max(out_capacity, 1), dtype=torch.int64, device=dev)
+        if out_val is None:
+            out_val = torch.empty(max(out_capacity, 1), dtype=torch.float16, device=dev)
+    if ws is None:
+        ws = alloc_workspace(n, block, out_capacity, dev)
+    nout = counter if counter is not None else ctypes.c_uint64(0)
+    st = stats if stats is not None else LloydStats()
+    code = lib().bof4_quantize_lloyd(_ptr(w), n, block, cbp, int(signed), float(opq_T), int(bool(weight_by_max2)),
+                                     _ptr(codes), _ptr(scales), _ptr(out_idx), _ptr(out_val), out_capacity,
+                                     ctypes.byref(nout), ctypes.byref(st), _ptr(ws), ws.numel(), _stream(stream))
+    _check(code, allow=(BOF4_ERR_CAPACITY,) if allow_overflow else ())
+    stats_out = st if raw else st.as_dict()
+    if not trim:
+        return codes, scales, out_idx, out_val, int(nout.value), stats_out
+    k = min(int(nout.value), out_capacity)
+    return (codes, scales, None if out_idx is None else out_idx[:k], None if out_val is None else out_val[:k],
+            int(nout.value), stats_out)
+
+
+class QuantizeLloydInFlight:
+    """bof4_quantize_lloyd_begin has been called with these arguments; finish() waits for the outlier count and
+    returns it (the sums: bof4_wait_result(stats))."""
+
+    def __init__(self, args, counter, keep):
+        self.args, self.counter, self.keep = args, counter, keep
+
+    def finish(self, allow_overflow=False):
+        code = lib().bof4_quantize_lloyd_finish(*self.args)
+        _check(code, allow=(BOF4_ERR_CAPACITY,) if allow_overflow else ())
+        return int(self.counter.value)
+
+
+def bof4_quantize_lloyd_begin(w, block, cb, signed, opq_T, out_capacity, codes, scales, out_idx, out_val, ws, counter,
+                              stats, weight_by_max2=True, stream=None):
+    """Enqueues bof4_quantize_lloyd into caller-owned buffers (counter: pinned_counter(), stats:
+    pinned_lloyd_stats()) and returns a QuantizeLloydInFlight."""
+    n = w.numel()
+    cb, cbp = _cb(cb)
+    args = (_ptr(w), n, block, cbp, int(signed), float(opq_T), int(bool(weight_by_max2)), _ptr(codes), _ptr(scales),
+            _ptr(out_idx), _ptr(out_val), out_capacity, ctypes.byref(counter), ctypes.byref(stats), _ptr(ws),
+            0 if ws is None else ws.numel(), _stream(stream))
+    _check(lib().bof4_quantize_lloyd_begin(*args))
+    return QuantizeLloydInFlight(args, counter, (w, cb, codes, scales, out_idx, out_val, ws, stats))
 
 
 class QuantizeInFlight:

@@ -174,17 +174,18 @@ QuantWsLayout quant_ws_layout(uint64_t n, uint64_t cap) {
     return L;
 }
 constexpr uint32_t SEG_GRID = 512;              // persistent workgroups of the MAE and error kernels (2 per CU)
-// persistent workgroups of the Lloyd kernel: as many as the 256 compute units hold at once
-constexpr uint32_t lloyd_grid(bool opq) { return 256u * (uint32_t)lloyd_waves_per_simd(opq); }
-constexpr uint32_t LLOYD_GRID_MAX = 1024;        // what the workspace is sized for
-constexpr uint32_t QUANT_GRID = 768;              // persistent workgroups of the quantise kernel (3 per CU)
+// persistent workgroups of a pass: as many as the 256 compute units hold at once
+constexpr uint32_t pass_grid(bool opq, bool quant, bool lloyd) {
+    return 256u * (uint32_t)pass_waves_per_simd(opq, quant, lloyd);
+}
+constexpr uint32_t PASS_GRID_MAX = 1024;         // what the workspaces are sized for
 struct SegWsLayout {
     size_t header, wave_count, idx, val, total;
     uint32_t region_cap;
 };
 SegWsLayout seg_ws_layout(uint64_t cap) {
     SegWsLayout L;
-    const uint64_t nw = (uint64_t)QUANT_GRID * WAVES_PER_WG;
+    const uint64_t nw = (uint64_t)PASS_GRID_MAX * WAVES_PER_WG;  // one staging region per wave of the largest grid
     uint64_t rc = 4 * ((cap + nw - 1) / nw) + 64;  // four times the even share: room for uneven outlier density
     if (rc > 0x7fffffffull) rc = 0x7fffffffull;
     L.region_cap = (uint32_t)rc;
@@ -200,6 +201,8 @@ size_t quant_ws_bytes(uint64_t n, uint64_t cap) {
     size_t a = quant_ws_layout(n, cap).total, b = seg_ws_layout(cap).total;
     return a > b ? a : b;
 }
+// Where the Lloyd records of bof4_quantize_lloyd lie: behind the quantiser's part of the workspace, if it has one.
+size_t fused_lloyd_offset(uint64_t n, uint64_t cap, bool opq) { return opq ? align_up(quant_ws_bytes(n, cap), 256) : 0; }
 // Wait for the stream to drain.  The calls that hand results to the host are short (a fraction of a millisecond), so
 // the host first polls the stream, which notices completion sooner than the blocking wait; work that takes longer
 // than the polling budget falls through to the blocking wait.
@@ -234,8 +237,9 @@ hipError_t wait_for_flag(hipStream_t s, const uint64_t* flag_host) {
     }
     return hipStreamSynchronize(s);
 }
-size_t lloyd_ws_bytes() { return ((size_t)LLOYD_GRID_MAX + 1) * LLOYD_PART * 8; }
-static_assert(lloyd_grid(false) <= LLOYD_GRID_MAX && lloyd_grid(true) <= LLOYD_GRID_MAX && SEG_GRID <= LLOYD_GRID_MAX,
+size_t lloyd_ws_bytes() { return ((size_t)PASS_GRID_MAX + 1) * LLOYD_PART * 8; }
+static_assert(pass_grid(false, true, false) <= PASS_GRID_MAX && pass_grid(false, false, true) <= PASS_GRID_MAX &&
+                  SEG_GRID <= PASS_GRID_MAX,
               "workspace sized for fewer workgroups");
 // MAE step: histogram, search state, per-wave counts, per-workgroup floating-point partials, result record.
 // Entries of the candidate list of the MAE step: n / 32 (about five times what a pass leaves), at most 2^27; dealt
@@ -585,6 +589,53 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restr
 }
 
 // ------------------------------------------------------------------------------------------------ dispatch
+// Arguments of one pass over the weights (seg_pass_kernel) and the launch of the variant that fits them.
+struct PassArgs {
+    const uint4* w;
+    uint64_t n_seg;
+    CodebookArgs cb;
+    BinTable bt;
+    int signed_norm, weight_by_max2;
+    double T2;
+    uint32_t* codes;
+    uint16_t* scales;
+    OutlierStage os;
+    double* partials;
+};
+template <int I, bool QUANT, bool LLOYD>
+void launch_pass_i(bool opq, uint32_t grid, hipStream_t s, const PassArgs& a) {
+#define BOF4_PASS(FAST_, OPQ_)                                                                                       \
+    hipLaunchKernelGGL((seg_pass_kernel<I, FAST_, OPQ_, QUANT, LLOYD>), dim3(grid), dim3(256), 0, s, a.w, a.n_seg,   \
+                       a.cb, a.bt, a.signed_norm, a.weight_by_max2, a.T2, LLOYD_INC_MUL, LLOYD_INC_ADD, a.codes,    \
+                       a.scales, a.os, a.partials)
+    if (a.bt.fast && opq) BOF4_PASS(true, true);
+    else if (a.bt.fast) BOF4_PASS(true, false);
+    else if (opq) BOF4_PASS(false, true);
+    else BOF4_PASS(false, false);
+#undef BOF4_PASS
+}
+// Returns the grid it launched (one Lloyd partial record per workgroup, four outlier staging regions).
+template <bool QUANT, bool LLOYD>
+uint32_t launch_pass(uint32_t block, bool opq, hipStream_t s, const PassArgs& a) {
+    const uint64_t tiles = (a.n_seg + 63) / 64;
+    const uint64_t want = (tiles + WAVES_PER_WG - 1) / WAVES_PER_WG;
+    const uint32_t full = pass_grid(opq, QUANT, LLOYD);
+    const uint32_t grid = (uint32_t)(want < full ? want : full);
+    switch (block) {
+        case 32: launch_pass_i<32, QUANT, LLOYD>(opq, grid, s, a); break;
+        case 64: launch_pass_i<64, QUANT, LLOYD>(opq, grid, s, a); break;
+        case 128: launch_pass_i<128, QUANT, LLOYD>(opq, grid, s, a); break;
+        default: launch_pass_i<256, QUANT, LLOYD>(opq, grid, s, a); break;
+    }
+    return grid;
+}
+uint32_t pass_grid_for(uint64_t n_seg, bool opq, bool quant, bool lloyd) {
+    const uint64_t tiles = (n_seg + 63) / 64;
+    const uint64_t want = (tiles + WAVES_PER_WG - 1) / WAVES_PER_WG;
+    const uint32_t full = pass_grid(opq, quant, lloyd);
+    return (uint32_t)(want < full ? want : full);
+}
+
 template <int I, bool SIGNED, bool OPQ>
 void launch_quantize(dim3 grid, hipStream_t s, const uint4* w, uint64_t n_vec, const CodebookArgs& cb, double T2,
                      uint32_t* codes, uint16_t* scales, uint64_t* total, uint32_t* tc, uint64_t* tb, int64_t* si,
@@ -617,9 +668,9 @@ int bof4_last_hip_error(void) { return g_hip_err; }
 
 size_t bof4_workspace_bytes(uint64_t n, uint32_t block, uint64_t out_capacity) {
     if (!valid_block(block) || n == 0 || n % block != 0) return 0;
-    size_t q = quant_ws_bytes(n, out_capacity);
-    const size_t l = lloyd_ws_bytes(), m = mae_ws_layout(n).total;
-    if (l > q) q = l;
+    // the quantiser's part and, behind it, the Lloyd records (bof4_quantize_lloyd uses both at once)
+    size_t q = fused_lloyd_offset(n, out_capacity, true) + lloyd_ws_bytes();
+    const size_t m = mae_ws_layout(n).total;
     return m > q ? m : q;
 }
 
@@ -665,7 +716,7 @@ int bof4_quant_error(const void* w_dev, uint64_t n, uint32_t block, const double
     if (!(opq_T >= 0.0) || !std::isfinite(opq_T)) return fail(BOF4_ERR_ARG, "bof4_quant_error: opq_T must be finite and >= 0");
     if (!aligned(w_dev, 16)) return fail(BOF4_ERR_ARG, "bof4_quant_error: misaligned weights");
     if (!ws_dev || !aligned(ws_dev, 256)) return fail(BOF4_ERR_ARG, "bof4_quant_error: workspace null or misaligned");
-    static_assert((SEG_GRID + 2) * ERR_PART <= (LLOYD_GRID_MAX + 1) * LLOYD_PART, "the Lloyd workspace holds the error records");
+    static_assert((SEG_GRID + 2) * ERR_PART <= (PASS_GRID_MAX + 1) * LLOYD_PART, "the Lloyd workspace holds the error records");
     if (ws_bytes < lloyd_ws_bytes()) return fail(BOF4_ERR_WORKSPACE, "bof4_quant_error: workspace too small");
     static_assert(sizeof(bof4_error_stats) == 5 * 8, "result record and bof4_error_stats must match");
     hipStream_t s = (hipStream_t)stream;
@@ -727,9 +778,11 @@ namespace {
 // bof4_quantize in two halves.  phase 0: enqueue the kernels and collect the count (the plain call); 1: enqueue only
 // (the count has to go to pinned host memory, where phase 2 finds it); 2: collect only, for the same arguments.
 enum QuantPhase { QUANT_WHOLE = 0, QUANT_ENQUEUE = 1, QUANT_COLLECT = 2 };
+// With stats_host the same pass also takes the Lloyd sums (bof4_quantize_lloyd).
 int quantize_impl(int phase, const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
                   double opq_T, uint8_t* codes_dev, uint16_t* scales_dev, int64_t* out_idx_dev, uint16_t* out_val_dev,
-                  uint64_t out_capacity, uint64_t* n_outliers_host, void* ws_dev, size_t ws_bytes, void* stream) {
+                  uint64_t out_capacity, uint64_t* n_outliers_host, void* ws_dev, size_t ws_bytes, void* stream,
+                  bof4_lloyd_stats* stats_host = nullptr, int weight_by_max2 = 1) {
     if (!w_dev || !codes_dev || !scales_dev || !n_outliers_host) return fail(BOF4_ERR_ARG, "bof4_quantize: null pointer");
     if (!valid_block(block) || n == 0 || n % block != 0) return fail(BOF4_ERR_ARG, "bof4_quantize: bad n or block");
     if (!valid_codebook(cb_host)) return fail(BOF4_ERR_ARG, "bof4_quantize: codebook must be 16 finite ascending levels");
@@ -737,23 +790,26 @@ int quantize_impl(int phase, const void* w_dev, uint64_t n, uint32_t block, cons
     if (!aligned(w_dev, 16) || !aligned(codes_dev, 4) || !aligned(scales_dev, 2))
         return fail(BOF4_ERR_ARG, "bof4_quantize: misaligned pointer");
     const bool opq = opq_T > 0.0;
+    const bool lloyd = stats_host != nullptr;
     hipStream_t s = (hipStream_t)stream;
     const uint64_t n_tiles = (n + QTILE - 1) / QTILE;
     if (n_tiles > 0x7fffffffull) return fail(BOF4_ERR_ARG, "bof4_quantize: n too large for one call");
+    const size_t lloyd_off = fused_lloyd_offset(n, out_capacity, opq);
     if (opq) {
         if (out_capacity > 0 && (!out_idx_dev || !out_val_dev)) return fail(BOF4_ERR_ARG, "bof4_quantize: null outlier buffers");
         if (!aligned(out_idx_dev, 8) || !aligned(out_val_dev, 2)) return fail(BOF4_ERR_ARG, "bof4_quantize: misaligned outlier buffers");
+    }
+    if (opq || lloyd) {
         if (!ws_dev || !aligned(ws_dev, 256)) return fail(BOF4_ERR_ARG, "bof4_quantize: workspace null or misaligned");
-        if (ws_bytes < quant_ws_bytes(n, out_capacity)) return fail(BOF4_ERR_WORKSPACE, "bof4_quantize: workspace too small");
+        if (ws_bytes < (lloyd ? lloyd_off + lloyd_ws_bytes() : quant_ws_bytes(n, out_capacity)))
+            return fail(BOF4_ERR_WORKSPACE, "bof4_quantize: workspace too small");
     }
     const CodebookArgs cb = make_codebook_args(cb_host);
     const BinTable bt = make_bin_table(cb);
     const double T2 = opq_T * opq_T;
     const uint32_t seg = block < 64 ? block : 64;
     const uint64_t n_seg = n / seg;
-    const uint64_t tiles = (n_seg + 63) / 64;
-    const uint64_t want = (tiles + WAVES_PER_WG - 1) / WAVES_PER_WG;
-    const uint32_t sgrid = (uint32_t)(want < QUANT_GRID ? want : QUANT_GRID);
+    const uint32_t sgrid = pass_grid_for(n_seg, opq, true, lloyd);
     const uint32_t n_waves = sgrid * WAVES_PER_WG;
     const uint4* wv = (const uint4*)w_dev;
     uint32_t* cd = (uint32_t*)codes_dev;
@@ -771,39 +827,45 @@ int quantize_impl(int phase, const void* w_dev, uint64_t n, uint32_t block, cons
     uint64_t* direct = opq ? (uint64_t*)device_view_of_host(n_outliers_host) : nullptr;
     if (phase != QUANT_WHOLE && opq && !direct)
         return fail(BOF4_ERR_ARG, "bof4_quantize_begin / _finish: the outlier count must go to pinned host memory");
+    double* partials = lloyd ? (double*)((char*)ws_dev + lloyd_off) : nullptr;
+    double* rec_dev = lloyd ? partials + (uint64_t)sgrid * LLOYD_PART : nullptr;
+    double* stats_direct = lloyd ? (double*)device_view_of_host(stats_host) : nullptr;
+    if (phase != QUANT_WHOLE && lloyd && !stats_direct)
+        return fail(BOF4_ERR_ARG, "bof4_quantize_lloyd_begin: the record must lie in pinned host memory");
     if (phase != QUANT_COLLECT) {
+    const PassArgs pa = {wv, n_seg, cb, bt, signed_norm, weight_by_max2, T2, cd, scales_dev, os, partials};
     timing_begin(s);
-#define BOF4_LAUNCH_SEGQ(II)                                                                                           \
-    if (bt.fast && opq) hipLaunchKernelGGL((seg_quantize_kernel<II, true, true>), dim3(sgrid), dim3(256), 0, s, wv,    \
-                                           n_seg, cb, bt, signed_norm, T2, cd, scales_dev, os);                        \
-    else if (bt.fast) hipLaunchKernelGGL((seg_quantize_kernel<II, true, false>), dim3(sgrid), dim3(256), 0, s, wv,     \
-                                         n_seg, cb, bt, signed_norm, T2, cd, scales_dev, os);                          \
-    else if (opq) hipLaunchKernelGGL((seg_quantize_kernel<II, false, true>), dim3(sgrid), dim3(256), 0, s, wv, n_seg,  \
-                                     cb, bt, signed_norm, T2, cd, scales_dev, os);                                     \
-    else hipLaunchKernelGGL((seg_quantize_kernel<II, false, false>), dim3(sgrid), dim3(256), 0, s, wv, n_seg, cb, bt,  \
-                            signed_norm, T2, cd, scales_dev, os);
-    switch (block) {
-        case 32: BOF4_LAUNCH_SEGQ(32) break;
-        case 64: BOF4_LAUNCH_SEGQ(64) break;
-        case 128: BOF4_LAUNCH_SEGQ(128) break;
-        default: BOF4_LAUNCH_SEGQ(256) break;
-    }
-#undef BOF4_LAUNCH_SEGQ
+    if (lloyd) launch_pass<true, true>(block, opq, s, pa);
+    else launch_pass<true, false>(block, opq, s, pa);
     timing_end(s);
     HIP_TRY(hipGetLastError());
-    if (!opq) {
-        *n_outliers_host = 0;
+    if (opq) {
+        // total_dev[0] = count, with bit 63 set if a wave overflowed its staging region.  A caller's counter in pinned
+        // host memory receives it straight from the gather kernel.
+        *n_outliers_host = direct ? FLAG_PENDING : 0;
+        hipLaunchKernelGGL(seg_outlier_gather_kernel, dim3(n_waves), dim3(64), 0, s, os, n_waves, out_idx_dev,
+                           out_val_dev, out_capacity, direct ? direct : total_dev);
+    }
+    if (lloyd) {
+        if (stats_direct) stats_host->n_used = FLAG_PENDING;  // the word the final kernel writes last
+        hipLaunchKernelGGL(seg_lloyd_final_kernel, dim3(1), dim3(1024), 0, s, partials, sgrid, cb, bt.code_of_zero,
+                           stats_direct ? stats_direct : rec_dev);
+    }
+    HIP_TRY(hipGetLastError());
+    if (phase == QUANT_ENQUEUE) {
+        if (!opq) *n_outliers_host = 0;
         return BOF4_OK;
     }
-
-    // total_dev[0] = count, with bit 63 set if a wave overflowed its staging region.  A caller's counter in pinned
-    // host memory receives it straight from the gather kernel.
-    *n_outliers_host = direct ? FLAG_PENDING : 0;
-    hipLaunchKernelGGL(seg_outlier_gather_kernel, dim3(n_waves), dim3(64), 0, s, os, n_waves, out_idx_dev, out_val_dev,
-                       out_capacity, direct ? direct : total_dev);
-    HIP_TRY(hipGetLastError());
-    if (phase == QUANT_ENQUEUE) return BOF4_OK;
-    } else if (!opq) {
+    if (lloyd) {  // the plain call hands the sums over as well
+        if (stats_direct) {
+            HIP_TRY(wait_for_flag(s, &stats_host->n_used));
+        } else {
+            HIP_TRY(hipMemcpyAsync(stats_host, rec_dev, sizeof(bof4_lloyd_stats), hipMemcpyDeviceToHost, s));
+            HIP_TRY(wait_for_stream(s));
+        }
+    }
+    }
+    if (!opq) {
         *n_outliers_host = 0;
         return BOF4_OK;
     }
@@ -874,6 +936,38 @@ int bof4_quantize_finish(const void* w_dev, uint64_t n, uint32_t block, const do
                          size_t ws_bytes, void* stream) {
     return quantize_impl(QUANT_COLLECT, w_dev, n, block, cb_host, signed_norm, opq_T, codes_dev, scales_dev,
                          out_idx_dev, out_val_dev, out_capacity, n_outliers_host, ws_dev, ws_bytes, stream);
+}
+
+int bof4_quantize_lloyd(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                        double opq_T, int weight_by_max2, uint8_t* codes_dev, uint16_t* scales_dev,
+                        int64_t* out_idx_dev, uint16_t* out_val_dev, uint64_t out_capacity, uint64_t* n_outliers_host,
+                        bof4_lloyd_stats* stats_host, void* ws_dev, size_t ws_bytes, void* stream) {
+    if (!stats_host) return fail(BOF4_ERR_ARG, "bof4_quantize_lloyd: null pointer");
+    return quantize_impl(QUANT_WHOLE, w_dev, n, block, cb_host, signed_norm, opq_T, codes_dev, scales_dev, out_idx_dev,
+                         out_val_dev, out_capacity, n_outliers_host, ws_dev, ws_bytes, stream, stats_host,
+                         weight_by_max2);
+}
+
+int bof4_quantize_lloyd_begin(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                              double opq_T, int weight_by_max2, uint8_t* codes_dev, uint16_t* scales_dev,
+                              int64_t* out_idx_dev, uint16_t* out_val_dev, uint64_t out_capacity,
+                              uint64_t* n_outliers_host, bof4_lloyd_stats* stats_host, void* ws_dev, size_t ws_bytes,
+                              void* stream) {
+    if (!stats_host) return fail(BOF4_ERR_ARG, "bof4_quantize_lloyd_begin: null pointer");
+    return quantize_impl(QUANT_ENQUEUE, w_dev, n, block, cb_host, signed_norm, opq_T, codes_dev, scales_dev,
+                         out_idx_dev, out_val_dev, out_capacity, n_outliers_host, ws_dev, ws_bytes, stream, stats_host,
+                         weight_by_max2);
+}
+
+int bof4_quantize_lloyd_finish(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
+                               double opq_T, int weight_by_max2, uint8_t* codes_dev, uint16_t* scales_dev,
+                               int64_t* out_idx_dev, uint16_t* out_val_dev, uint64_t out_capacity,
+                               uint64_t* n_outliers_host, bof4_lloyd_stats* stats_host, void* ws_dev, size_t ws_bytes,
+                               void* stream) {
+    if (!stats_host) return fail(BOF4_ERR_ARG, "bof4_quantize_lloyd_finish: null pointer");
+    return quantize_impl(QUANT_COLLECT, w_dev, n, block, cb_host, signed_norm, opq_T, codes_dev, scales_dev,
+                         out_idx_dev, out_val_dev, out_capacity, n_outliers_host, ws_dev, ws_bytes, stream, stats_host,
+                         weight_by_max2);
 }
 
 int bof4_dequantize(const uint8_t* codes_dev, const uint16_t* scales_dev, uint64_t n, uint32_t block,
@@ -1226,7 +1320,7 @@ constexpr size_t STATIC_SCRATCH_BYTES = ((size_t)1024 + 1) * 56 * 8;  // = lloyd
 static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
 
 namespace {
-static_assert(STATIC_SCRATCH_BYTES == ((size_t)LLOYD_GRID_MAX + 1) * LLOYD_PART * 8, "scratch must hold the Lloyd workspace");
+static_assert(STATIC_SCRATCH_BYTES == ((size_t)PASS_GRID_MAX + 1) * LLOYD_PART * 8, "scratch must hold the Lloyd workspace");
 // Address of `scratch` on the current device, looked up once per device with that device current.
 constexpr int STATIC_MAX_DEVICES = 64;
 std::atomic<void*> g_scratch_ptr[STATIC_MAX_DEVICES];
@@ -1270,29 +1364,10 @@ int lloyd_step_impl(bool wait, const void* w_dev, uint64_t n, uint32_t block, co
         return fail(BOF4_ERR_ARG, "bof4_lloyd_step_begin: the record must lie in pinned host memory");
     {
         BinTable bt = make_bin_table(cb);
-        const uint64_t tiles = (n_seg + 63) / 64;
-        uint64_t wantg = (tiles + WAVES_PER_WG - 1) / WAVES_PER_WG;
-        const uint32_t sgrid = (uint32_t)(wantg < lloyd_grid(opq) ? wantg : lloyd_grid(opq));
-        const uint32_t n_part = sgrid;  // one partial record per workgroup
+        const OutlierStage no_stage = {nullptr, nullptr, nullptr, 0};
+        const PassArgs pa = {w, n_seg, cb, bt, signed_norm, weight_by_max2, T2, nullptr, nullptr, no_stage, partials};
         timing_begin(s);
-#define BOF4_LAUNCH_SEGL(II)                                                                                           \
-    if (bt.fast && opq) hipLaunchKernelGGL((seg_lloyd_kernel<II, true, true>), dim3(sgrid), dim3(256), 0, s, w, n_seg, \
-                                           cb, bt, signed_norm, weight_by_max2, T2, LLOYD_INC_MUL, LLOYD_INC_ADD,      \
-                                           partials);                                                                  \
-    else if (bt.fast) hipLaunchKernelGGL((seg_lloyd_kernel<II, true, false>), dim3(sgrid), dim3(256), 0, s, w, n_seg,  \
-                                         cb, bt, signed_norm, weight_by_max2, T2, LLOYD_INC_MUL, LLOYD_INC_ADD,        \
-                                         partials);                                                                    \
-    else if (opq) hipLaunchKernelGGL((seg_lloyd_kernel<II, false, true>), dim3(sgrid), dim3(256), 0, s, w, n_seg, cb,  \
-                                     bt, signed_norm, weight_by_max2, T2, LLOYD_INC_MUL, LLOYD_INC_ADD, partials);     \
-    else hipLaunchKernelGGL((seg_lloyd_kernel<II, false, false>), dim3(sgrid), dim3(256), 0, s, w, n_seg, cb, bt,      \
-                            signed_norm, weight_by_max2, T2, LLOYD_INC_MUL, LLOYD_INC_ADD, partials);
-        switch (block) {
-            case 32: BOF4_LAUNCH_SEGL(32) break;
-            case 64: BOF4_LAUNCH_SEGL(64) break;
-            case 128: BOF4_LAUNCH_SEGL(128) break;
-            default: BOF4_LAUNCH_SEGL(256) break;
-        }
-#undef BOF4_LAUNCH_SEGL
+        const uint32_t n_part = launch_pass<false, true>(block, opq, s, pa);  // one partial record per workgroup
         timing_end(s);
         // The result record has the layout of bof4_lloyd_stats.
         static_assert(sizeof(bof4_lloyd_stats) == 51 * 8, "result record and bof4_lloyd_stats must match");

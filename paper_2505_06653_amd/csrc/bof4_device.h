@@ -110,6 +110,32 @@ __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
     return o;
 }
 
+// Largest / smallest of three packed pairs of 16-bit patterns in binary16 order (one instruction each).  For
+// patterns that are not binary16 NaNs (magnitude field <= 0x7C00) that order is the order of the bfloat16 values with
+// the same patterns: sign first, then magnitude, +0 above -0; subnormal patterns are compared, not flushed.  A NaN
+// pattern among the inputs comes out as a NaN pattern (callers test for it and fall back on integer compares).
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_max3_f16(uint32_t a, uint32_t b, uint32_t c) {
+    f16x2 x, y, z;
+    __builtin_memcpy(&x, &a, 4);
+    __builtin_memcpy(&y, &b, 4);
+    __builtin_memcpy(&z, &c, 4);
+    f16x2 r = __builtin_elementwise_maximum(__builtin_elementwise_maximum(x, y), z);
+    uint32_t o;
+    __builtin_memcpy(&o, &r, 4);
+    return o;
+}
+__device__ __forceinline__ uint32_t pk_min3_f16(uint32_t a, uint32_t b, uint32_t c) {
+    f16x2 x, y, z;
+    __builtin_memcpy(&x, &a, 4);
+    __builtin_memcpy(&y, &b, 4);
+    __builtin_memcpy(&z, &c, 4);
+    f16x2 r = __builtin_elementwise_minimum(__builtin_elementwise_minimum(x, y), z);
+    uint32_t o;
+    __builtin_memcpy(&o, &r, 4);
+    return o;
+}
+
 __device__ __forceinline__ uint32_t pk_sub_i16(uint32_t a, uint32_t b) {
     s16x2 x, y;
     __builtin_memcpy(&x, &a, 4);

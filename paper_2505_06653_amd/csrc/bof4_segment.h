@@ -94,18 +94,33 @@ __device__ __forceinline__ float seg_f32(const uint32_t* R, int e) {
 }
 
 // ---------------------------------------------------------------------------------------------- block constant
-// Largest magnitude of the block and the sign of its first occurrence (lowest index).  Packed 16-bit maxima give
-// P = largest positive pattern (signed compare) and N = largest negative pattern (unsigned compare); only when +a
-// and -a are both present at the maximum does the order matter, and only then the segment is scanned.
+// Largest magnitude of the block and the sign of its first occurrence (lowest index).  P = largest pattern in value
+// order, N = smallest: if the segment holds a non-negative number P is the largest of them, if it holds a negative
+// number N is the one of largest magnitude.  Only when +a and -a are both present at the maximum does the order of
+// the elements matter, and only then the segment is scanned.  The packed three-operand binary16 maximum / minimum
+// does two registers (four weights) per instruction; if a pattern that binary16 reads as NaN turns up (a bfloat16
+// beyond 2^121: never in the ordinary range) the wave repeats the search with integer compares.
 template <int I>
 __device__ __forceinline__ void block_constant(const uint32_t (&R)[SegCfg<I>::NR], uint32_t lane, bool signed_norm,
                                                uint32_t& maxabs, uint32_t& sign) {
     using C = SegCfg<I>;
-    uint32_t P = R[0], N = R[0];
+    static_assert(C::NR % 2 == 0, "registers are taken in pairs");
+    uint32_t P = pk_max3_f16(R[0], R[1], R[1]), N = pk_min3_f16(R[0], R[1], R[1]);
 #pragma unroll
-    for (int d = 1; d < C::NR; ++d) {
-        P = pk_max_i16(P, R[d]);
-        N = pk_max_u16(N, R[d]);
+    for (int d = 2; d < C::NR; d += 2) {
+        P = pk_max3_f16(P, R[d], R[d + 1]);
+        N = pk_min3_f16(N, R[d], R[d + 1]);
+    }
+    const uint32_t nan_test = ((P & 0x7fffu) > 0x7C00u) | ((P & 0x7fff0000u) > 0x7C000000u) |
+                              ((N & 0x7fffu) > 0x7C00u) | ((N & 0x7fff0000u) > 0x7C000000u);
+    if (__builtin_amdgcn_ballot_w64(nan_test != 0) != 0) {  // wave-uniform: out-of-range input only
+        P = R[0];
+        N = R[0];
+#pragma unroll
+        for (int d = 1; d < C::NR; ++d) {
+            P = pk_max_i16(P, R[d]);
+            N = pk_max_u16(N, R[d]);
+        }
     }
     int p = max((int)(short)(P & 0xffffu), (int)P >> 16);  // >= 0 iff a non-negative pattern exists
     uint32_t n = max(N & 0xffffu, N >> 16);                // >= 0x8000 iff a negative pattern exists
@@ -248,116 +263,177 @@ __device__ __forceinline__ uint32_t opq_pop_lowest(uint32_t (&map)[2]) {
     return (first ? 0u : 32u) + 2u * k + (take_lo ? 0u : 1u);
 }
 
-// ================================================================================================ quantise
-// Outlier staging of the quantise kernel: every wave appends the outliers of its (contiguous, ascending) tile range to
-// a region of its own, in ascending flat index, and reports how many it found.  A later pass turns the per-wave
-// counts into offsets and copies the regions into the caller's list.  A wave that finds more than its region holds
-// keeps counting (the count stays exact); the scan pass notices it and the host repeats the call on the general path.
+// ================================================================================================ the pass
+// One kernel streams over the weights and does the quantiser's work (codes, block constants, outlier list: sections
+// 2.1, 3.1, 3.3), the Lloyd step's (per-region sums of section 3.2 eq. 6), or both on the same normalised weights.
+//
+// Loads.  Every lane loads its own segment straight from memory (16-byte loads at a stride of one segment; the lines
+// a wave touches are consumed completely by its next loads, so the caches see every byte once) and requests the next
+// tile's pieces as it uses this one up: a lane never holds two whole tiles.
+//
+// Outlier staging of the quantiser: every wave appends the outliers of its (contiguous, ascending) tile range to a
+// region of its own, in ascending flat index, and reports how many it found.  A later pass turns the per-wave counts
+// into offsets and copies the regions into the caller's list.  A wave that finds more than its region holds keeps
+// counting (the count stays exact); the scan pass notices it and the host repeats the call on the general path.  The
+// outliers' original values are read back from a copy of the tile that the wave parks in LDS before it zeroes them.
+//
+// Lloyd sums.  Per-level sums of the current block live in lane-private LDS columns acc[level][lane]
+// (conflict-free).  One 64-bit LDS add per weight carries both the count and the sum of x of its level: the increment
+// is the bit pattern of the binary64 number 2^-1008 + (x + 1) 2^-1020, i.e. exponent field 15 and mantissa
+// (x + 1) 2^40 rounded to an integer.  Adding up to 256 of these as integers gives 15 K 2^52 + sum (x + 1) 2^40 with
+// the second term below 2^52, so count K and sum separate again exactly.  Once per tile the columns are folded, with
+// the block weights g, into binary64 registers:  A += g sum(x + 1) 2^40,  den15 += g 15 K,  cnt15 += 15 K.
+// The fold is shared inside every quad of lanes: lane 4q + p takes levels 4p .. 4p+3 of the four blocks of its quad
+// (the weights g of the other three arrive by quad permutes), so a lane carries 4 and not 16 sets of accumulators -
+// the registers this frees are what lets four waves share a SIMD.  At any step the 64 lanes read 64 different
+// columns of one level each: conflict-free again.  The two increment constants are passed as kernel arguments (not
+// literals) so that the increment is one three-operand fused multiply-add whose addend register pair is not
+// overwritten.
 struct OutlierStage {
     int64_t* idx;          // [n_waves * region_cap]
     uint16_t* val;         // [n_waves * region_cap]
     uint32_t* wave_count;  // [n_waves]
     uint32_t region_cap;
 };
+constexpr double LLOYD_INC_MUL = 0x1p-1020;
+constexpr double LLOYD_INC_ADD = 0x1p-1008 + 0x1p-1020;
 
-// Three workgroups per compute unit (three waves per SIMD): the launch bound holds the register count to what that
-// takes; with outlier extraction the kernel is bound by instruction issue and the third wave is worth 8 %.
-template <int I, bool FAST, bool OPQ>
-__global__ __launch_bounds__(256, 3) void seg_quantize_kernel(const uint4* __restrict__ w, uint64_t n_seg,
-                                                            CodebookArgs cb, BinTable bt, int signed_norm, double T2,
-                                                            uint32_t* __restrict__ codes,
-                                                            uint16_t* __restrict__ scales, OutlierStage os) {
+// Waves per SIMD a variant of the pass is compiled for (the launch bound holds its registers to 512 / that many).
+__host__ __device__ constexpr int pass_waves_per_simd(bool opq, bool quant, bool lloyd) {
+    return (quant && lloyd) ? 3 : lloyd ? (opq ? 3 : 4) : 4;
+}
+
+// Where lane `lane` finds its segment of tile `t`.  A lane whose segment lies past the end of the tensor (ragged last
+// tile) is pointed at the tensor's last segment instead: it loads valid memory and contributes nothing.
+template <int I>
+__device__ __forceinline__ const uint4* own_segment(const uint4* __restrict__ w, uint64_t t, uint64_t n_seg,
+                                                    uint32_t lane) {
+    const uint64_t seg = t * 64 + lane;
+    return w + (seg < n_seg ? seg : n_seg - 1) * SegCfg<I>::NV;
+}
+// The value of lane (l ^ C) of the same quad, C = 1, 2, 3 (all lanes active).
+template <int C>
+__device__ __forceinline__ float quad_xor(float v) {
+    constexpr int ctrl = C == 1 ? 0xB1 : C == 2 ? 0x4E : 0x1B;  // quad_perm [1,0,3,2] / [2,3,0,1] / [3,2,1,0]
+    return __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), ctrl, 0xf, 0xf, true));
+}
+// The tile parked in LDS for the outlier values: lane l's k-th 16-byte piece sits at piece slot k ^ swz(l) of the
+// lane's stretch of SEG * 2 bytes, which spreads any 16 neighbouring lanes over all banks.
+template <int I>
+__device__ __forceinline__ uint32_t park_swizzle(uint32_t lane) {
+    constexpr uint32_t PER = 256u / (SegCfg<I>::SEG * 2u);  // lanes per 256 bytes
+    return (lane / PER) & (uint32_t)(SegCfg<I>::NV - 1);
+}
+
+// STAGED (the quantiser on its own, which is bound by memory traffic and not by instruction issue): the wave loads
+// whole tiles with fully coalesced 16-byte loads, parks them in a padded LDS buffer and reads them back transposed;
+// the parked tile also serves the outlier values.
+__host__ __device__ constexpr bool pass_staged(bool quant, bool lloyd) { return quant && !lloyd; }
+
+template <int I, bool FAST, bool OPQ, bool QUANT, bool LLOYD>
+__global__ __launch_bounds__(256, pass_waves_per_simd(OPQ, QUANT, LLOYD)) void seg_pass_kernel(
+    const uint4* __restrict__ w, uint64_t n_seg, CodebookArgs cb, BinTable bt, int signed_norm, int weight_by_max2,
+    double T2, double inc_mul, double inc_add, uint32_t* __restrict__ codes, uint16_t* __restrict__ scales,
+    OutlierStage os, double* __restrict__ partials) {
     using C = SegCfg<I>;
+    static_assert(QUANT || LLOYD, "a pass does something");
+    constexpr bool STAGED = pass_staged(QUANT, LLOYD);
+    constexpr bool EXTRACT = QUANT && OPQ;     // outliers go to the wave's staging region
+    constexpr bool PARK = EXTRACT && !STAGED;  // the wave keeps a copy of the tile in LDS for the outlier values
+    constexpr bool COLS = LLOYD || PARK;       // 8 KB per wave: the Lloyd columns, and / or the parked tile
     struct Shared {  // one object, so that the table sits at LDS offset 0 (reachable by an immediate offset)
         uint2 tab[BIN_TABLE_ENTRIES];
-        char stage[WAVES_PER_WG * C::STAGE_BYTES];
+        unsigned long long cols[COLS ? WAVES_PER_WG * 16 * 64 : 1];
+        char stage[STAGED ? WAVES_PER_WG * C::STAGE_BYTES : 16];
     };
     __shared__ __attribute__((aligned(16))) Shared sh;
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t tid = threadIdx.x, lane = tid & 63;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));  // scalar: tile ranges on the SALU
     bin_table_fill(sh.tab, bt, tid, blockDim.x);
-    __syncthreads();
     const uint2* tab = sh.tab;
-    const uint32_t lane_off = bin_lane_offset(threadIdx.x & 63u);
-    char* stage = sh.stage + wave * C::STAGE_BYTES;
-    const uint64_t n_vec = n_seg * C::NV;
+    const uint32_t lane_off = bin_lane_offset(lane);
+    unsigned long long* acc = sh.cols + (COLS ? wave * 16 * 64 : 0);
+    if (LLOYD) {
+#pragma unroll
+        for (int l = 0; l < 16; ++l) acc[l * 64 + lane] = 0ull;
+    }
+    __syncthreads();
     const uint64_t n_tiles = (n_seg + 63) / 64;
     const uint64_t n_waves = (uint64_t)gridDim.x * WAVES_PER_WG;
     const uint64_t gw = (uint64_t)blockIdx.x * WAVES_PER_WG + wave;
     const uint64_t t0 = n_tiles * gw / n_waves, t1 = n_tiles * (gw + 1) / n_waves;
+    // fold: levels 4 p + k (k = 0 .. 3) of the blocks of lanes lane ^ c (c = 0 .. 3)
+    const uint32_t p4 = (lane & 3u) * 4u;
+    unsigned long long* fold_col[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) fold_col[c] = acc + p4 * 64 + (lane ^ (uint32_t)c);
+    char* park = reinterpret_cast<char*>(acc) + lane * (C::SEG * 2);
+    const uint32_t swz = park_swizzle<I>(lane);
+    char* stage = sh.stage + (STAGED ? wave * C::STAGE_BYTES : 0);
+    const uint64_t n_vec = n_seg * C::NV;
+
+    double A[4], den15[4], sxx_g = 0.0, kout_g = 0.0;
+    uint32_t cnt15[4], kout = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        A[k] = 0.0;
+        den15[k] = 0.0;
+        cnt15[k] = 0;
+    }
     uint32_t wcount = 0;  // outliers this wave has found so far (wave-uniform)
+    // R holds the lane's segment of the current tile; Rn takes over the registers R gives up.
+    uint32_t R[C::NR], Rn[C::NR];
     uint4 G[C::NV];
-    uint32_t R[C::NR];
-    if (t0 < t1) tile_issue_loads<I>(w, t0 * 64 * C::NV, n_vec, lane, G);
+    if constexpr (STAGED) {
+        if (t0 < t1) tile_issue_loads<I>(w, t0 * 64 * C::NV, n_vec, lane, G);
+    } else if (t0 < t1) {
+        const uint4* p = own_segment<I>(w, t0, n_seg, lane);
+#pragma unroll
+        for (int k = 0; k < C::NV; ++k) {
+            const uint4 q = p[k];
+            R[4 * k] = q.x;
+            R[4 * k + 1] = q.y;
+            R[4 * k + 2] = q.z;
+            R[4 * k + 3] = q.w;
+        }
+    }
     for (uint64_t t = t0; t < t1; ++t) {
-        wave_lds_fence();
-        tile_stage<I>(stage, lane, G);
-        if (t + 1 < t1) tile_issue_loads<I>(w, (t + 1) * 64 * C::NV, n_vec, lane, G);
-        wave_lds_fence();
-        tile_fetch<I>(stage, lane, R);
+        // (after the wave's last tile this requests that tile once more: cached, and never used)
+        const uint4* pn = own_segment<I>(w, t + 1 < t1 ? t + 1 : t, n_seg, lane);
+        if constexpr (STAGED) {
+            wave_lds_fence();
+            tile_stage<I>(stage, lane, G);
+            if (t + 1 < t1) tile_issue_loads<I>(w, (t + 1) * 64 * C::NV, n_vec, lane, G);
+            wave_lds_fence();
+            tile_fetch<I>(stage, lane, R);
+        }
         const uint64_t seg = t * 64 + lane;
         const bool active = seg < n_seg;
         uint32_t k_out = 0, omap[2] = {0, 0};
         if (OPQ) {
+            if (PARK) {  // the original values, before the outliers are zeroed
+#pragma unroll
+                for (int k = 0; k < C::NV; ++k)
+                    *reinterpret_cast<uint4*>(park + (((uint32_t)k ^ swz) << 4)) =
+                        make_uint4(R[4 * k], R[4 * k + 1], R[4 * k + 2], R[4 * k + 3]);
+            }
             opq_zero_outliers<I>(R, opq_theta<I>(R, T2), omap);
-            k_out = opq_count(omap);
+            k_out = active ? opq_count(omap) : 0u;
         }
-        uint32_t maxabs, sign;
-        block_constant<I>(R, lane, signed_norm != 0, maxabs, sign);
-        const float m = bf16_bits_to_f32(maxabs | (sign << 15));
-        const uint32_t s16 = f32_to_f16_bits(m);
-        const float m_eff = f16_bits_to_f32(s16);
-        uint32_t out[C::SEG / 8];
-        bool fast = FAST && __builtin_amdgcn_ballot_w64(!maxabs_is_ordinary(maxabs)) == 0;
-        if (fast) {
-            const BlockDiv dv = make_block_div(m_eff);
-#pragma unroll
-            for (int j = 0; j < C::SEG / 8; ++j) {
-                float x[8];
-                uint2 en[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {  // eight table reads in flight
-                    x[e] = div_fast(seg_f32(R, 8 * j + e), dv);
-                    en[e] = bin_lookup(tab, x[e], lane_off);
-                }
-                uint32_t acc = 0;
-#pragma unroll
-                for (int e = 7; e >= 0; --e) {
-                    uint32_t code = en[e].y + (x[e] > __uint_as_float(en[e].x) ? 1u : 0u);
-                    acc = (acc << 4) + code;
-                }
-                out[j] = acc;
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < C::SEG / 8; ++j) {
-                uint32_t acc = 0;
-#pragma unroll
-                for (int e = 7; e >= 0; --e) {
-                    float f = seg_f32(R, 8 * j + e);
-                    float x = (m_eff == 0.0f) ? 0.0f : f / m_eff;
-                    acc = (acc << 4) + (uint32_t)assign_code_generic(x, cb);
-                }
-                out[j] = acc;
-            }
-        }
-        if (active) {
-            uint4* dst = reinterpret_cast<uint4*>(codes + seg * (C::SEG / 8));
-#pragma unroll
-            for (int q = 0; q < C::SEG / 32; ++q)
-                store_stream(&dst[q], make_uint4(out[4 * q], out[4 * q + 1], out[4 * q + 2], out[4 * q + 3]));
-            if ((lane & (C::LPB - 1)) == 0) scales[seg / C::LPB] = (uint16_t)s16;
-        }
-        if (OPQ) {
+        if (EXTRACT) {
             // inclusive prefix of the per-lane counts = order of the flat indices
             const uint32_t incl = wave_inclusive_scan_u32(k_out);
             const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+            wave_lds_fence();
             if (total != 0) {  // wave-uniform
                 uint32_t pos = wcount + incl - k_out;
                 const uint64_t region = gw * (uint64_t)os.region_cap;
-                const char* myseg = stage + lane * C::PITCH;  // the staged tile still holds the original values
+                if (!active) omap[0] = omap[1] = 0;
                 while ((omap[0] | omap[1]) != 0u) {  // lanes run dry at different times
                     const uint32_t e = opq_pop_lowest(omap);
-                    const uint32_t b = *reinterpret_cast<const uint16_t*>(myseg + 2 * e);
+                    const uint32_t b =
+                        STAGED ? *reinterpret_cast<const uint16_t*>(stage + lane * C::PITCH + 2 * e)
+                               : *reinterpret_cast<const uint16_t*>(park + ((((e >> 3) ^ swz) << 4) | ((e & 7u) << 1)));
                     if (pos < os.region_cap) {
                         os.idx[region + pos] = (int64_t)(seg * C::SEG + e);
                         os.val[region + pos] = (uint16_t)f32_to_f16_bits(bf16_bits_to_f32(b));
@@ -366,9 +442,190 @@ __global__ __launch_bounds__(256, 3) void seg_quantize_kernel(const uint4* __res
                 }
                 wcount += total;
             }
+            if (LLOYD && PARK) {  // the parked tile lay on the Lloyd columns: they start every tile at zero
+                wave_lds_fence();
+#pragma unroll
+                for (int l = 0; l < 16; ++l) acc[l * 64 + lane] = 0ull;
+                wave_lds_fence();
+            }
+        }
+        uint32_t maxabs, sign;
+        block_constant<I>(R, lane, signed_norm != 0, maxabs, sign);
+        const float m = bf16_bits_to_f32(maxabs | (sign << 15));
+        const uint32_t s16 = f32_to_f16_bits(m);
+        const float m_eff = f16_bits_to_f32(s16);
+        // the square of a binary16 number has 22 significant bits and an exponent in [-48, 32]: exact in binary32
+        const float g = weight_by_max2 ? m_eff * m_eff : 1.0f;
+        double sxx = 0.0;
+        uint32_t out[QUANT ? C::SEG / 8 : 1];
+        const bool fast = FAST && __builtin_amdgcn_ballot_w64(!maxabs_is_ordinary(maxabs)) == 0;
+        // (lanes past the end of the tensor work on a copy of its last segment; what they produce is dropped below)
+        if (fast) {
+            const BlockDiv dv = make_block_div(m_eff);
+#pragma unroll
+            for (int b0 = 0; b0 < C::SEG; b0 += 8) {
+                float x[8];
+                uint2 en[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {  // table reads of a whole batch in flight ...
+                    x[e] = div_fast(seg_f32(R, b0 + e), dv);
+                    en[e] = bin_lookup(tab, x[e], lane_off);
+                }
+                if (!STAGED) {  // these four registers of R are free now: the next tile's piece moves in
+                    const uint4 q = pn[b0 / 8];
+                    Rn[b0 / 2] = q.x;
+                    Rn[b0 / 2 + 1] = q.y;
+                    Rn[b0 / 2 + 2] = q.z;
+                    Rn[b0 / 2 + 3] = q.w;
+                }
+                uint32_t packed = 0;
+#pragma unroll
+                for (int e = 7; e >= 0; --e) {  // ... before the first LDS add of the batch
+                    const uint32_t code = en[e].y + (x[e] > __uint_as_float(en[e].x) ? 1u : 0u);
+                    if (QUANT) packed = (packed << 4) + code;
+                    if (LLOYD) {
+                        const double xd = (double)x[e];
+                        const double inc = fma(xd, inc_mul, inc_add);
+                        atomicAdd(&acc[code * 64 + lane], (unsigned long long)__double_as_longlong(inc));
+                        sxx = fma(xd, xd, sxx);
+                    }
+                }
+                if (QUANT) out[b0 / 8] = packed;
+                __builtin_amdgcn_sched_barrier(0);  // batches stay apart: mixing them costs more registers than it gains
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < C::SEG / 8; ++j) {
+                uint32_t packed = 0;
+#pragma unroll
+                for (int e = 7; e >= 0; --e) {
+                    const float f = seg_f32(R, 8 * j + e);
+                    const float x = (m_eff == 0.0f) ? 0.0f : f / m_eff;
+                    const uint32_t code = (uint32_t)assign_code_generic(x, cb);
+                    if (QUANT) packed = (packed << 4) + code;
+                    if (LLOYD) {
+                        const double xd = (double)x;
+                        const double inc = fma(xd, inc_mul, inc_add);
+                        atomicAdd(&acc[code * 64 + lane], (unsigned long long)__double_as_longlong(inc));
+                        sxx = fma(xd, xd, sxx);
+                    }
+                }
+                if (QUANT) out[j] = packed;
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int k = 0; k < (STAGED ? 0 : C::NV); ++k) {
+                const uint4 q = pn[k];
+                Rn[4 * k] = q.x;
+                Rn[4 * k + 1] = q.y;
+                Rn[4 * k + 2] = q.z;
+                Rn[4 * k + 3] = q.w;
+            }
+        }
+        if (QUANT && active) {
+            uint4* dst = reinterpret_cast<uint4*>(codes + seg * (C::SEG / 8));
+#pragma unroll
+            for (int q = 0; q < C::SEG / 32; ++q)
+                store_stream(&dst[q], make_uint4(out[4 * q], out[4 * q + 1], out[4 * q + 2], out[4 * q + 3]));
+            if ((lane & (C::LPB - 1)) == 0) scales[seg / C::LPB] = (uint16_t)s16;
+        }
+        if (LLOYD) {
+            const double gd = active ? (double)g : 0.0;
+            sxx_g = fma(gd, sxx, sxx_g);
+            if (OPQ) {  // the zeroed outliers went into the sums as x = 0; remember what to take out again
+                kout_g = fma(gd, (double)k_out, kout_g);
+                kout += k_out;
+            }
+            if (t * 64 + 64 > n_seg) {  // wave-uniform: the ragged last tile of the tensor
+                wave_lds_fence();
+                if (!active) {
+#pragma unroll
+                    for (int l = 0; l < 16; ++l) acc[l * 64 + lane] = 0ull;
+                }
+            }
+            // fold (all lanes)
+            wave_lds_fence();
+            const float gq[4] = {g, quad_xor<1>(g), quad_xor<2>(g), quad_xor<3>(g)};
+            unsigned long long col[16];
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) col[4 * c + k] = atomicExch(fold_col[c] + k * 64, 0ull);  // read and clear
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const double gc = (double)gq[c];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const unsigned long long v = col[4 * c + k];
+                    const uint32_t hi = (uint32_t)(v >> 32), lo = (uint32_t)v;
+                    const uint32_t k15 = hi >> 20;
+                    // 2^52 + sum: the column's mantissa under the exponent of 2^52 (one bit-field insert)
+                    uint32_t dhi;
+                    asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(dhi) : "v"(0xFFFFFu), "v"(hi), "v"(0x43300000u));
+                    const double D = __hiloint2double((int)dhi, (int)lo) - 0x1p52;  // sum (x+1) 2^40
+                    A[k] = fma(gc, D, A[k]);
+                    den15[k] = fma(gc, (double)k15, den15[k]);
+                    cnt15[k] += k15;
+                }
+            }
+            wave_lds_fence();
+        } else if (PARK) {
+            wave_lds_fence();  // the next tile is parked over this one
+        }
+        if (!STAGED) {
+#pragma unroll
+            for (int d = 0; d < C::NR; ++d) R[d] = Rn[d];
         }
     }
-    if (OPQ && lane == 0) os.wave_count[gw] = wcount;
+    if (EXTRACT && lane == 0) os.wave_count[gw] = wcount;
+    if (!LLOYD) return;
+    // Lanes with the same p hold partial sums of the same four levels: fixed-order butterfly over the other lane bits,
+    // then the four waves of the workgroup in wave order.
+    __shared__ double wave_totals[LLOYD ? WAVES_PER_WG * LLOYD_PART : 1];
+    double* wtot = wave_totals + wave * LLOYD_PART;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        double a = A[k] * 0x1p-40, d = den15[k];
+        unsigned long long c = cnt15[k];
+#pragma unroll
+        for (int mk = 32; mk >= 4; mk >>= 1) {
+            a += __shfl_xor(a, mk, 64);
+            d += __shfl_xor(d, mk, 64);
+            c += (unsigned long long)__shfl_xor((long long)c, mk, 64);
+        }
+        if (lane < 4) {
+            wtot[p4 + k] = a;
+            wtot[16 + p4 + k] = d;
+            wtot[32 + p4 + k] = __longlong_as_double((long long)c);
+        }
+    }
+    {
+        double a = sxx_g, kg = kout_g;
+        unsigned long long kc = kout;
+#pragma unroll
+        for (int mk = 32; mk >= 1; mk >>= 1) {
+            a += __shfl_xor(a, mk, 64);
+            kg += __shfl_xor(kg, mk, 64);
+            kc += (unsigned long long)__shfl_xor((long long)kc, mk, 64);
+        }
+        if (lane == 0) {
+            wtot[48] = a;
+            wtot[49] = kg;                                  // sum of g * (outliers of the block)
+            wtot[50] = __longlong_as_double((long long)kc); // outlier count
+        }
+    }
+    __syncthreads();
+    if (tid < 51) {
+        const double* all = wave_totals;
+        const bool is_int = (tid >= 32 && tid < 48) || tid == 50;
+        double sd = 0.0;
+        unsigned long long si = 0;
+        for (int k = 0; k < WAVES_PER_WG; ++k) {
+            if (is_int) si += (unsigned long long)__double_as_longlong(all[k * LLOYD_PART + tid]);
+            else sd += all[k * LLOYD_PART + tid];
+        }
+        partials[(uint64_t)blockIdx.x * LLOYD_PART + tid] = is_int ? __longlong_as_double((long long)si) : sd;
+    }
 }
 
 // One wave per staging region: it adds up the outlier counts of the regions before its own (that sum is where its
@@ -413,258 +670,6 @@ __global__ __launch_bounds__(64) void seg_outlier_gather_kernel(OutlierStage os,
             out_idx[before + j] = os.idx[src + j];
             out_val[before + j] = os.val[src + j];
         }
-    }
-}
-
-// ================================================================================================ Lloyd step
-// Every lane loads its own segment straight from memory (16-byte loads at a stride of one segment; the lines a wave
-// touches are consumed completely by its next loads, so the caches see every byte once) and keeps the next tile's
-// loads in flight while it works on the current one.
-//
-// Per-level sums of the current block live in lane-private LDS columns acc[level][lane] (conflict-free).  One 64-bit
-// LDS add per weight carries both the count and the sum of x of its level: the increment is the bit pattern of the
-// binary64 number 2^-1008 + (x + 1) 2^-1020, i.e. exponent field 15 and mantissa (x + 1) 2^40 rounded to an
-// integer.  Adding up to 256 of these as integers gives 15 K 2^52 + sum (x + 1) 2^40 with the second term below
-// 2^52, so count K and sum separate again exactly.  Once per tile the columns are folded, with the block weights g,
-// into binary64 registers:  A += g sum(x + 1) 2^40,  den15 += g 15 K,  cnt15 += 15 K.
-// The fold is shared inside every quad of lanes: lane 4q + p takes levels 4p .. 4p+3 of the four blocks of its quad
-// (the weights g of the other three arrive by quad permutes), so a lane carries 4 and not 16 sets of accumulators -
-// the registers this frees are what lets four waves share a SIMD.  At any step the 64 lanes read 64 different
-// columns of one level each: conflict-free again.
-// The two increment constants are passed as kernel arguments (not literals) so that the increment is one
-// three-operand fused multiply-add whose addend register pair is not overwritten.
-constexpr double LLOYD_INC_MUL = 0x1p-1020;
-constexpr double LLOYD_INC_ADD = 0x1p-1008 + 0x1p-1020;
-
-// Waves per SIMD the Lloyd kernel is compiled for (the launch bound holds its registers to 512 / that many): four,
-// three with outlier removal, whose statistics need more registers at once.
-__host__ __device__ constexpr int lloyd_waves_per_simd(bool opq) { return opq ? 3 : 4; }
-
-// Where lane `lane` finds its segment of tile `t`.  A lane whose segment lies past the end of the tensor (ragged last
-// tile) is pointed at the tensor's last segment instead: it loads valid memory and takes no part in the sums.
-template <int I>
-__device__ __forceinline__ const uint4* own_segment(const uint4* __restrict__ w, uint64_t t, uint64_t n_seg,
-                                                    uint32_t lane) {
-    const uint64_t seg = t * 64 + lane;
-    return w + (seg < n_seg ? seg : n_seg - 1) * SegCfg<I>::NV;
-}
-// The value of lane (l ^ C) of the same quad, C = 1, 2, 3 (all lanes active).
-template <int C>
-__device__ __forceinline__ float quad_xor(float v) {
-    constexpr int ctrl = C == 1 ? 0xB1 : C == 2 ? 0x4E : 0x1B;  // quad_perm [1,0,3,2] / [2,3,0,1] / [3,2,1,0]
-    return __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), ctrl, 0xf, 0xf, true));
-}
-
-template <int I, bool FAST, bool OPQ>
-__global__ __launch_bounds__(256, lloyd_waves_per_simd(OPQ)) void seg_lloyd_kernel(
-    const uint4* __restrict__ w, uint64_t n_seg, CodebookArgs cb, BinTable bt, int signed_norm, int weight_by_max2,
-    double T2, double inc_mul, double inc_add, double* __restrict__ partials) {
-    using C = SegCfg<I>;
-    struct Shared {  // one object, so that the table sits at LDS offset 0 (reachable by an immediate offset)
-        uint2 tab[BIN_TABLE_ENTRIES];
-        unsigned long long acc[WAVES_PER_WG * 16 * 64];
-    };
-    __shared__ __attribute__((aligned(16))) Shared sh;
-    const uint32_t tid = threadIdx.x, lane = tid & 63;
-    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));  // scalar: tile ranges on the SALU
-    bin_table_fill(sh.tab, bt, tid, blockDim.x);
-    const uint2* tab = sh.tab;
-    const uint32_t lane_off = bin_lane_offset(lane);
-    unsigned long long* acc = sh.acc + wave * 16 * 64;
-#pragma unroll
-    for (int l = 0; l < 16; ++l) acc[l * 64 + lane] = 0ull;
-    __syncthreads();
-    const uint64_t n_tiles = (n_seg + 63) / 64;
-    const uint64_t n_waves = (uint64_t)gridDim.x * WAVES_PER_WG;
-    const uint64_t gw = (uint64_t)blockIdx.x * WAVES_PER_WG + wave;
-    const uint64_t t0 = n_tiles * gw / n_waves, t1 = n_tiles * (gw + 1) / n_waves;
-    // fold: levels 4 p + k (k = 0 .. 3) of the blocks of lanes lane ^ c (c = 0 .. 3)
-    const uint32_t p4 = (lane & 3u) * 4u;
-    unsigned long long* fold_col[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) fold_col[c] = acc + p4 * 64 + (lane ^ (uint32_t)c);
-
-    double A[4], den15[4], sxx_g = 0.0, kout_g = 0.0;
-    uint32_t cnt15[4], kout = 0;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        A[k] = 0.0;
-        den15[k] = 0.0;
-        cnt15[k] = 0;
-    }
-    // R holds the lane's segment of the current tile.  The next tile's segment is requested piece by piece as the
-    // pieces of this one are used up (Rn takes over the registers R gives up), so a lane never holds two whole tiles.
-    uint32_t R[C::NR], Rn[C::NR];
-    if (t0 < t1) {
-        const uint4* p = own_segment<I>(w, t0, n_seg, lane);
-#pragma unroll
-        for (int k = 0; k < C::NV; ++k) {
-            const uint4 q = p[k];
-            R[4 * k] = q.x;
-            R[4 * k + 1] = q.y;
-            R[4 * k + 2] = q.z;
-            R[4 * k + 3] = q.w;
-        }
-    }
-    for (uint64_t t = t0; t < t1; ++t) {
-        // (after the wave's last tile this requests that tile once more: cached, and never used)
-        const uint4* pn = own_segment<I>(w, t + 1 < t1 ? t + 1 : t, n_seg, lane);
-        const uint64_t seg = t * 64 + lane;
-        const bool active = seg < n_seg;
-        uint32_t k_out = 0;
-        if (OPQ) {
-            uint32_t omap[2];
-            opq_zero_outliers<I>(R, opq_theta<I>(R, T2), omap);
-            k_out = opq_count(omap);
-        }
-        uint32_t maxabs, sign;
-        block_constant<I>(R, lane, signed_norm != 0, maxabs, sign);
-        const float m = bf16_bits_to_f32(maxabs | (sign << 15));
-        const float m_eff = f16_bits_to_f32(f32_to_f16_bits(m));
-        // the square of a binary16 number has 22 significant bits and an exponent in [-48, 32]: exact in binary32
-        const float g = weight_by_max2 ? m_eff * m_eff : 1.0f;
-        double sxx = 0.0;
-        bool fast = FAST && __builtin_amdgcn_ballot_w64(!maxabs_is_ordinary(maxabs)) == 0;
-        // (lanes past the end of the tensor work on a copy of its last segment; their columns are cleared below)
-        if (fast) {
-            const BlockDiv dv = make_block_div(m_eff);
-#pragma unroll
-            for (int b0 = 0; b0 < C::SEG; b0 += 8) {
-                float x[8];
-                uint2 en[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {  // table reads of a whole batch in flight ...
-                    x[e] = div_fast(seg_f32(R, b0 + e), dv);
-                    en[e] = bin_lookup(tab, x[e], lane_off);
-                }
-                {  // these four registers of R are free now: the next tile's piece moves in
-                    const uint4 q = pn[b0 / 8];
-                    Rn[b0 / 2] = q.x;
-                    Rn[b0 / 2 + 1] = q.y;
-                    Rn[b0 / 2 + 2] = q.z;
-                    Rn[b0 / 2 + 3] = q.w;
-                }
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {  // ... before the first LDS add of the batch
-                    uint32_t code = en[e].y + (x[e] > __uint_as_float(en[e].x) ? 1u : 0u);
-                    double xd = (double)x[e];
-                    double inc = fma(xd, inc_mul, inc_add);
-                    atomicAdd(&acc[code * 64 + lane], (unsigned long long)__double_as_longlong(inc));
-                    sxx = fma(xd, xd, sxx);
-                }
-                __builtin_amdgcn_sched_barrier(0);  // batches stay apart: mixing them costs more registers than it gains
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < C::SEG; ++e) {
-                float f = seg_f32(R, e);
-                float x = (m_eff == 0.0f) ? 0.0f : f / m_eff;
-                uint32_t code = (uint32_t)assign_code_generic(x, cb);
-                double xd = (double)x;
-                double inc = fma(xd, inc_mul, inc_add);
-                atomicAdd(&acc[code * 64 + lane], (unsigned long long)__double_as_longlong(inc));
-                sxx = fma(xd, xd, sxx);
-                if ((e & 7) == 7) __builtin_amdgcn_sched_barrier(0);
-            }
-            {
-#pragma unroll
-                for (int k = 0; k < C::NV; ++k) {
-                    const uint4 q = pn[k];
-                    Rn[4 * k] = q.x;
-                    Rn[4 * k + 1] = q.y;
-                    Rn[4 * k + 2] = q.z;
-                    Rn[4 * k + 3] = q.w;
-                }
-            }
-        }
-        const double gd = active ? (double)g : 0.0;
-        sxx_g = fma(gd, sxx, sxx_g);
-        if (OPQ) {  // the zeroed outliers went into the sums as x = 0; remember what to take out again
-            kout_g = fma(gd, (double)k_out, kout_g);
-            kout += active ? k_out : 0u;
-        }
-        if (t * 64 + 64 > n_seg) {  // wave-uniform: the ragged last tile of the tensor
-            wave_lds_fence();
-            if (!active) {
-#pragma unroll
-                for (int l = 0; l < 16; ++l) acc[l * 64 + lane] = 0ull;
-            }
-        }
-        // fold (all lanes)
-        wave_lds_fence();
-        const float gq[4] = {g, quad_xor<1>(g), quad_xor<2>(g), quad_xor<3>(g)};
-        unsigned long long col[16];
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-#pragma unroll
-            for (int k = 0; k < 4; ++k) col[4 * c + k] = atomicExch(fold_col[c] + k * 64, 0ull);  // read and clear
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const double gc = (double)gq[c];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const unsigned long long v = col[4 * c + k];
-                const uint32_t hi = (uint32_t)(v >> 32), lo = (uint32_t)v;
-                const uint32_t k15 = hi >> 20;
-                // 2^52 + sum: the column's mantissa under the exponent of 2^52 (one bit-field insert)
-                uint32_t dhi;
-                asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(dhi) : "v"(0xFFFFFu), "v"(hi), "v"(0x43300000u));
-                const double D = __hiloint2double((int)dhi, (int)lo) - 0x1p52;  // sum (x+1) 2^40
-                A[k] = fma(gc, D, A[k]);
-                den15[k] = fma(gc, (double)k15, den15[k]);
-                cnt15[k] += k15;
-            }
-        }
-        wave_lds_fence();
-#pragma unroll
-        for (int d = 0; d < C::NR; ++d) R[d] = Rn[d];
-    }
-    // Lanes with the same p hold partial sums of the same four levels: fixed-order butterfly over the other lane bits,
-    // then the four waves of the workgroup in wave order.
-    __shared__ double wave_totals[WAVES_PER_WG * LLOYD_PART];
-    double* wtot = wave_totals + wave * LLOYD_PART;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        double a = A[k] * 0x1p-40, d = den15[k];
-        unsigned long long c = cnt15[k];
-#pragma unroll
-        for (int mk = 32; mk >= 4; mk >>= 1) {
-            a += __shfl_xor(a, mk, 64);
-            d += __shfl_xor(d, mk, 64);
-            c += (unsigned long long)__shfl_xor((long long)c, mk, 64);
-        }
-        if (lane < 4) {
-            wtot[p4 + k] = a;
-            wtot[16 + p4 + k] = d;
-            wtot[32 + p4 + k] = __longlong_as_double((long long)c);
-        }
-    }
-    {
-        double a = sxx_g, kg = kout_g;
-        unsigned long long kc = kout;
-#pragma unroll
-        for (int mk = 32; mk >= 1; mk >>= 1) {
-            a += __shfl_xor(a, mk, 64);
-            kg += __shfl_xor(kg, mk, 64);
-            kc += (unsigned long long)__shfl_xor((long long)kc, mk, 64);
-        }
-        if (lane == 0) {
-            wtot[48] = a;
-            wtot[49] = kg;                                  // sum of g * (outliers of the block)
-            wtot[50] = __longlong_as_double((long long)kc); // outlier count
-        }
-    }
-    __syncthreads();
-    if (tid < 51) {
-        const double* all = wave_totals;
-        const bool is_int = (tid >= 32 && tid < 48) || tid == 50;
-        double sd = 0.0;
-        unsigned long long si = 0;
-        for (int k = 0; k < WAVES_PER_WG; ++k) {
-            if (is_int) si += (unsigned long long)__double_as_longlong(all[k * LLOYD_PART + tid]);
-            else sd += all[k * LLOYD_PART + tid];
-        }
-        partials[(uint64_t)blockIdx.x * LLOYD_PART + tid] = is_int ? __longlong_as_double((long long)si) : sd;
     }
 }
 

@@ -153,3 +153,42 @@ extern "C" int bof4_check_scan(uint64_t seed, uint32_t blocks, uint32_t rounds, 
     hipLaunchKernelGGL(check_scan_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, seed, rounds, out_dev);
     return (int)hipGetLastError();
 }
+
+// ------------------------------------------------------------------------------------------------ packed max / min
+// pk_max3_f16 / pk_min3_f16 on all 2^32 pairs (a, b) of 16-bit patterns against the order the block-maximum search
+// relies on: sign first, then magnitude, +0 above -0, subnormal patterns compared like any other.  Pairs with a
+// pattern that binary16 reads as NaN (magnitude field above 0x7C00) must come out as such a pattern (the kernels test
+// for that and repeat the search with integer compares).  out[0] wrong maxima, out[1] wrong minima, out[2] NaN inputs
+// that did not give a NaN pattern, out[3] pairs checked.
+__device__ __forceinline__ int pattern_rank(uint32_t p) {  // value order of a non-NaN pattern
+    return (p & 0x8000u) ? -(int)(p & 0x7fffu) - 1 : (int)(p & 0x7fffu);
+}
+__global__ __launch_bounds__(256) void check_pkmax_kernel(unsigned long long* out) {
+    const uint32_t a = blockIdx.x;  // 0 .. 65535
+    unsigned long long bad_max = 0, bad_min = 0, bad_nan = 0, n = 0;
+    for (uint32_t b = threadIdx.x; b < 65536u; b += 256) {
+        const uint32_t ab = a | (b << 16), ba = b | (a << 16);
+        // three-operand form as the kernels use it: running value, then two new registers
+        const uint32_t mx = pk_max3_f16(ab, ba, ab), mn = pk_min3_f16(ab, ba, ab);
+        const bool nan_in = (a & 0x7fffu) > 0x7C00u || (b & 0x7fffu) > 0x7C00u;
+        ++n;
+        if (nan_in) {
+            if ((mx & 0x7fffu) <= 0x7C00u || (mx >> 16 & 0x7fffu) <= 0x7C00u || (mn & 0x7fffu) <= 0x7C00u ||
+                (mn >> 16 & 0x7fffu) <= 0x7C00u)
+                ++bad_nan;
+            continue;
+        }
+        const uint32_t want_max = pattern_rank(a) >= pattern_rank(b) ? a : b;
+        const uint32_t want_min = pattern_rank(a) <= pattern_rank(b) ? a : b;
+        if ((mx & 0xffffu) != want_max || (mx >> 16) != want_max) ++bad_max;
+        if ((mn & 0xffffu) != want_min || (mn >> 16) != want_min) ++bad_min;
+    }
+    atomicAdd(&out[0], bad_max);
+    atomicAdd(&out[1], bad_min);
+    atomicAdd(&out[2], bad_nan);
+    atomicAdd(&out[3], n);
+}
+extern "C" int bof4_check_pkmax(unsigned long long* out_dev, void* stream) {
+    hipLaunchKernelGGL(check_pkmax_kernel, dim3(65536), dim3(256), 0, (hipStream_t)stream, out_dev);
+    return (int)hipGetLastError();
+}

@@ -74,3 +74,18 @@ def test_wave_prefix_sum_with_dpp_moves_equals_the_serial_sum():
     torch.cuda.synchronize()
     bad, n = out.cpu().numpy()
     assert n == 512 * 256 * 64 and bad == 0
+
+
+def test_packed_binary16_maximum_orders_bfloat16_patterns_like_their_values():
+    """The block-maximum search takes the largest and smallest of packed 16-bit patterns with the three-operand
+    binary16 maximum / minimum: on all 2^32 pairs of patterns it must pick by sign and magnitude (+0 above -0,
+    subnormal patterns not flushed) and turn every pair with a binary16 NaN pattern into a NaN pattern."""
+    L = ctypes.CDLL(os.path.join(HERE, "libbof4_device_checks.so"))
+    L.bof4_check_pkmax.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    out = torch.zeros(4, dtype=torch.int64, device="cuda")
+    rc = L.bof4_check_pkmax(ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    assert rc == 0
+    torch.cuda.synchronize()
+    bad_max, bad_min, bad_nan, n = out.cpu().numpy()
+    assert n == 1 << 32
+    assert bad_max == 0 and bad_min == 0 and bad_nan == 0
