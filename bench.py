@@ -3,9 +3,10 @@
 Default workload (`--config 4`): layers of the Llama-70B-shaped stack (855,638,016 bf16 weights each, Student-t(4),
 std 0.015), block 64, signed absmax (BOF4-S) + OPQ at q = 0.95.  A "step" is one pass of the whole hot path over
 `--layers` distinct resident layers, one after the other:
-    bof4_quantize (OPQ statistics, outlier extraction, absmax, normalise, assign, pack)
-    bof4_lloyd_step (the same front end with OPQ on, per-level sums of eq. 6)  ->  bof4_codebook_update (host)
+    bof4_quantize_lloyd (one pass: OPQ statistics, outlier extraction, absmax, normalise, assign, pack, and the
+        per-level sums of eq. 6 on the same normalised weights, outliers excluded)  ->  bof4_codebook_update (host)
     bof4_dequantize (decode + outlier write-back)
+(`--unfused` takes bof4_quantize and bof4_lloyd_step as two passes instead.)
 Inputs are resident in HBM before the timed region; a layer (1.7 GB) is far larger than the last-level cache, and
 successive calls walk different layers.  `--config 0..3` run the other workloads (see WORKLOADS below); `--config 2`
 is the 13 GB Lloyd loop.
@@ -90,6 +91,14 @@ def measure_ceilings(n_weights, dev, grids=(1024, 2048, 4096, 8192, 0), reps=5, 
 
 
 # ------------------------------------------------------------------------------------------------ workloads
+def step_calls(args):
+    return ("quantize", "lloyd_step", "dequantize") if args.unfused else ("quantize_lloyd", "dequantize")
+
+
+def step_text(args):
+    return "quantize + lloyd_step" if args.unfused else "quantize_lloyd (quantiser and Lloyd sums in one pass)"
+
+
 def make_workload(cfg, args, dev):
     """Returns dict: tensors (flat bf16, resident), block, signed, T (OPQ threshold or 0), cb, pin, calls (which of
     quantize / lloyd_step / dequantize a step runs), lloyd_T, per_step (tensors walked per step), desc, matrices."""
@@ -97,10 +106,9 @@ def make_workload(cfg, args, dev):
     if cfg == 0:
         ts = [inputs.gaussian_matrix(1024, 1024, 0.02, seed=0, device=dev).reshape(-1)]
         return dict(tensors=ts, block=64, signed=1, T=0.0, lloyd_T=0.0, cb=codebooks.gaussian_quantile_init(),
-                    pin=codebooks.PIN_BOF4S, calls=("quantize", "lloyd_step", "dequantize"), per_step=1, move_cb=True,
-                    matrices=None,
-                    desc="configs[0]: 1024x1024 N(0,0.02^2), block 64, signed absmax; step = quantize + lloyd_step + "
-                         "codebook_update + dequantize (cache-resident, launch-bound)")
+                    pin=codebooks.PIN_BOF4S, calls=step_calls(args), per_step=1, move_cb=True, matrices=None,
+                    desc="configs[0]: 1024x1024 N(0,0.02^2), block 64, signed absmax; step = " + step_text(args) +
+                         " + codebook_update + dequantize (cache-resident, launch-bound)")
     if cfg in (1, 3):
         ts = []
         for r in range(args.replicas):
@@ -133,12 +141,13 @@ def make_workload(cfg, args, dev):
         ts = [inputs.flatten(inputs.llama70b_layer(seed=4000 + k, device=dev)) for k in range(args.layers)]
         T = binding.bof4_opq_threshold(0.95, block)
         return dict(tensors=ts, block=block, signed=1, T=T, lloyd_T=T, cb=codebooks.array(codebooks.BOF4S_MSE[block]),
-                    pin=codebooks.PIN_BOF4S, calls=("quantize", "lloyd_step", "dequantize"), per_step=args.layers,
+                    pin=codebooks.PIN_BOF4S, calls=step_calls(args), per_step=args.layers,
                     move_cb=True, matrices=(("qkv", 8192 + 2 * 1024, 8192), ("o", 8192, 8192),
                                             ("gate_up", 2 * 28672, 8192), ("down", 8192, 28672)),
                     desc=f"configs[4]: Llama-70B-shaped layers (855,638,016 bf16 weights each, Student-t(4) std 0.015), "
-                         f"block {block}, signed absmax (BOF4-S) + OPQ q=0.95; step = quantize + lloyd_step (OPQ on) + "
-                         f"codebook_update + dequantize on each of {args.layers} distinct resident layers in turn")
+                         f"block {block}, signed absmax (BOF4-S) + OPQ q=0.95; step = {step_text(args)} (outliers "
+                         f"excluded from the sums) + codebook_update + dequantize on each of {args.layers} distinct "
+                         f"resident layers in turn")
     raise ValueError("config must be 0..4")
 
 
@@ -149,7 +158,8 @@ def alg_bytes_per_weight(call, block, rho):
     return 2.0 + 0.5 + 2.0 / block + 10.0 * rho  # quantize: read 2, write the rest; dequantize: the reverse
 
 
-CEILING_OF_CALL = {"quantize": "read4_write1", "dequantize": "read1_write4", "lloyd_step": "read"}
+CEILING_OF_CALL = {"quantize": "read4_write1", "quantize_lloyd": "read4_write1", "dequantize": "read1_write4",
+                   "lloyd_step": "read"}
 
 
 # ------------------------------------------------------------------------------------------------ decoder in use
@@ -343,7 +353,8 @@ def cpu_baseline(w_dev, wl, sample_weights):
         return t
     one, many = run(1), run(threads)
     gomp.omp_set_num_threads(threads)
-    calls = wl["calls"]
+    # the oracle has no fused call: its step is the same work as two functions
+    calls = [c for call in wl["calls"] for c in (("quantize", "lloyd_step") if call == "quantize_lloyd" else (call,))]
 
     def table(t):
         d = {c: {"seconds": t[c], "weights_per_s": n / t[c], "GBps_bf16": 2.0 * n / t[c] / 1e9} for c in calls}
@@ -373,6 +384,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the calls timed outside the step (MAE step, error "
                     "pass, decoder inside the products)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27, help="weights in the CPU oracle's sample")
+    ap.add_argument("--unfused", action="store_true", help="bof4_quantize and bof4_lloyd_step as two passes over the "
+                    "weights instead of bof4_quantize_lloyd")
     ap.add_argument("--serial", action="store_true",
                     help="every call waits for its result before the next is enqueued (default: the Lloyd kernels are "
                          "enqueued behind the quantiser before the host waits for the outlier count)")
@@ -413,7 +426,8 @@ def main():
     cb = wl["cb"]
     n = tensors[0].numel()
     assert all(t.numel() == n for t in tensors)
-    do_q, do_l, do_d = "quantize" in calls, "lloyd_step" in calls, "dequantize" in calls
+    do_f = "quantize_lloyd" in calls
+    do_q, do_l, do_d = "quantize" in calls or do_f, "lloyd_step" in calls or do_f, "dequantize" in calls
     cap = n // 64 if T > 0 else 0
     if do_q:
         codes = torch.empty(n // 2, dtype=torch.uint8, device=dev)
@@ -445,7 +459,17 @@ def main():
         k = 0
         if events:
             events[0].record()
-        if do_q:
+        if do_f:
+            if timed_call == "quantize_lloyd":
+                binding.bof4_time_next_call(kev[j][0], kev[j][1])
+            if serial:
+                k = binding.bof4_quantize_lloyd(w, block, cb, signed, opq_T=T, out_capacity=cap, codes=codes,
+                                                scales=scales, out_idx=oidx, out_val=oval, ws=ws, counter=counter,
+                                                stats=stats_rec, trim=False, raw=True)[4]
+            else:
+                flight = binding.bof4_quantize_lloyd_begin(w, block, cb, signed, T, cap, codes, scales, oidx, oval, ws,
+                                                           counter, stats_rec)
+        elif do_q:
             if timed_call == "quantize":
                 binding.bof4_time_next_call(kev[j][0], kev[j][1])
             if serial:
@@ -455,7 +479,7 @@ def main():
                 flight = binding.bof4_quantize_begin(w, block, cb, signed, T, cap, codes, scales, oidx, oval, ws, counter)
         if events:
             events[1].record()
-        if do_l:
+        if do_l and not do_f:
             if timed_call == "lloyd_step":
                 binding.bof4_time_next_call(kev[j][0], kev[j][1])
             if serial:
@@ -500,7 +524,7 @@ def main():
         item(n_items + i, events=ev[i], serial=True)
     torch.cuda.synchronize()
     call_ms = {nm: float(np.mean([ev[i][k].elapsed_time(ev[i][k + 1]) for i in range(n_extra)]))
-               for k, nm in enumerate(("quantize", "lloyd_step", "dequantize")) if nm in calls}
+               for k, nm in enumerate(("quantize_lloyd" if do_f else "quantize", "lloyd_step", "dequantize")) if nm in calls}
     kms = {}
     for c, nm in enumerate(calls):
         samples = [kev[j][0].elapsed_time(kev[j][1]) for j in range(n_items) if j % len(calls) == c]
@@ -527,8 +551,8 @@ def main():
         "config": {"workload": wl["desc"], "n_weights_per_tensor": n, "tensors_per_step": per_step,
                    "resident_tensors": len(tensors), "block": block, "outlier_fraction": rho,
                    "enqueue_order": "one call after the other, each waiting for its result" if args.serial else
-                                    "per tensor: quantize kernels, lloyd kernels, outlier count, dequantize, lloyd sums "
-                                    "+ codebook update (one stream)"},
+                                    "per tensor: pass kernels, outlier count, dequantize, lloyd sums + codebook update "
+                                    "(one stream; the host never lets the GPU wait)"},
         "per_call": per_call,
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": prof[0] if prof else None,
@@ -537,7 +561,7 @@ def main():
     if ceilings:
         out["ceilings_GBps"] = ceilings
     if do_l:
-        out["lloyd_weights_per_s"] = n / (kms["lloyd_step"] * 1e-3)
+        out["lloyd_weights_per_s"] = n / (kms["quantize_lloyd" if do_f else "lloyd_step"] * 1e-3)
         out["mse_last"] = mse_last
     if mse_trace is not None:
         out["mse_per_iteration"] = mse_trace
