@@ -367,6 +367,51 @@ def cpu_baseline(w_dev, wl, sample_weights):
             "single_thread": table(one), "all_threads": table(many)}
 
 
+# ------------------------------------------------------------------------------------------------ config 4, whole
+def stack_run(dev, layers=80, blocks=(64, 128, 256)):
+    """The Llama-70B-shaped stack (80 layers, 68,451,041,280 weights, 136.9 GB) does not fit beside its decoded copy,
+    so the layers are generated (seed 4000 + layer), quantised with the Lloyd sums taken in the same pass, and
+    decoded one at a time into the same buffers; the sums are added up over the stack (fixed layer order) and give
+    one codebook update.  GPU time = HIP events around the calls of a layer, generation excluded."""
+    n = 855_638_016
+    out = {"workload": "configs[4] whole: 80 layers x 855,638,016 weights, signed absmax + OPQ q=0.95, "
+                       "quantize_lloyd + dequantize per layer", "per_block": {}}
+    for block in blocks:
+        T = binding.bof4_opq_threshold(0.95, block)
+        cb = codebooks.array(codebooks.BOF4S_MSE[block])
+        cap = n // 32
+        codes = torch.empty(n // 2, dtype=torch.uint8, device=dev)
+        scales = torch.empty(n // block, dtype=torch.float16, device=dev)
+        oidx = torch.empty(cap, dtype=torch.int64, device=dev)
+        oval = torch.empty(cap, dtype=torch.float16, device=dev)
+        deq = torch.empty(n, dtype=torch.bfloat16, device=dev)
+        ws = binding.alloc_workspace(n, block, cap, dev)
+        tot = {"num": np.zeros(16), "den": np.zeros(16), "cnt": np.zeros(16, dtype=np.uint64), "sse": 0.0}
+        n_out, gpu_ms = 0, 0.0
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for layer in range(layers):
+            w = inputs.flatten(inputs.llama70b_layer(seed=4000 + layer, device=dev))
+            e0.record()
+            k, g = binding.bof4_quantize_lloyd(w, block, cb, 1, opq_T=T, out_capacity=cap, codes=codes, scales=scales,
+                                               out_idx=oidx, out_val=oval, ws=ws, trim=False)[4:6]
+            binding.bof4_dequantize(codes, scales, n, block, cb, oidx, oval, out=deq, n_outliers=k)
+            e1.record()
+            torch.cuda.synchronize()
+            gpu_ms += e0.elapsed_time(e1)
+            n_out += k
+            for f in ("num", "den", "cnt"):
+                tot[f] += g[f]
+            tot["sse"] += g["sse"]
+            del w
+        used = layers * n - n_out
+        new_cb = binding.bof4_codebook_update({**tot, "n_used": used, "n_outliers": n_out}, codebooks.PIN_BOF4S, cb)
+        out["per_block"][str(block)] = {
+            "weights": layers * n, "outliers": n_out, "outlier_fraction": n_out / (layers * n),
+            "mse": tot["sse"] / used, "gpu_ms_total": gpu_ms, "GBps_bf16": 2.0 * layers * n / (gpu_ms * 1e-3) / 1e9,
+            "levels_after_one_step": [float(v) for v in new_cb]}
+    return out
+
+
 # ------------------------------------------------------------------------------------------------ main
 def main():
     ap = argparse.ArgumentParser()
@@ -389,6 +434,10 @@ def main():
     ap.add_argument("--serial", action="store_true",
                     help="every call waits for its result before the next is enqueued (default: the Lloyd kernels are "
                          "enqueued behind the quantiser before the host waits for the outlier count)")
+    ap.add_argument("--stack", action="store_true",
+                    help="instead of the benchmark step: config 4 taken whole - all 80 layers (one resident at a time, each "
+                         "from its own seed) x block sizes 64, 128, 256 through quantize_lloyd + dequantize, totals "
+                         "summed; one JSON line")
     ap.add_argument("--ceilings", action="store_true",
                     help="instead of the benchmark step: the plain streaming kernels over all launch shapes, one JSON line")
     ap.add_argument("--gemv-shapes", action="store_true",
@@ -415,6 +464,9 @@ def main():
                                   "(read + written) per second; per mix the best launch shape"}))
         return
     binding.lib()
+    if args.stack:
+        print(json.dumps(stack_run(dev)))
+        return
     if args.steps is None:
         args.steps = {0: 200, 1: 50, 2: 100, 3: 50, 4: 20}[args.config]
     if args.warmup is None:

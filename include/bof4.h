@@ -119,6 +119,29 @@ int bof4_lloyd_step_static(const void* w_dev, uint64_t n, uint32_t block, const 
  * pinned_mask is set or the region is empty (den[l] == 0).  Pure host function; cb_host is updated in place. */
 int bof4_codebook_update(const bof4_lloyd_stats* stats_host, uint16_t pinned_mask, double* cb_host);
 
+/*
+ * One maximisation step of the data-free codebook design: every level that is not pinned moves to the theoretical MSE
+ * centroid of its region for weights drawn from a given symmetric distribution (section 3.2 eq. 5; appendix B.2, the
+ * boxed general centroid with the conditional expectation of "Expectation of Normalized Weights", p_M and F_X of
+ * appendix B.1).  With the common factors cancelled,
+ *     level(l) = INT m [Phi1(m x)]_a^b A(m)^(block-2) p_W(m) dm  /  INT m^2 [F_W(m x)]_a^b A(m)^(block-2) p_W(m) dm,
+ * a, b the mid-point thresholds of the region, A = 2 F_W - 1, Phi1(t) = INT_-inf^t u p_W(u) du (for Gaussian weights
+ * Phi1 = -g: the appendix's closed form, whose boxed copy lacks the minus sign).
+ *   pdf_host, cdf_host   p_W and F_W on the uniform grid u_k = k u_max / (n_grid - 1), k = 0 .. n_grid - 1 (host;
+ *               n_grid odd, 3 .. 2^24; F_W(0) = 1/2; p_W is even, the negative side is implied); u_max large enough for
+ *               the tail beyond it not to matter.  Phi1 is made from p_W by the trapezoid rule, values between grid
+ *               points by linear interpolation, the integrals over m by the composite Simpson rule on the same grid
+ *   pinned_mask level 15 (the region with the point mass at +1) must be pinned, and level 0 for absolute normalisation
+ *               (signed_norm = 0); BOF4_ERR_ARG otherwise.  With signed_norm = 1 the leftmost region starts at -1
+ *   cb_out_host receives the 16 new levels (host; pinned and empty regions keep theirs)
+ *   ws_dev      bof4_theory_workspace_bytes(n_grid) bytes (device, 256-byte aligned)
+ * Copies the tables to the device, runs two small kernels, synchronises `stream`.
+ */
+int bof4_theory_centroids(const double* pdf_host, const double* cdf_host, uint32_t n_grid, double u_max, uint32_t block,
+                          const double* cb_host, uint16_t pinned_mask, int signed_norm, double* cb_out_host,
+                          void* ws_dev, size_t ws_bytes, void* stream);
+size_t bof4_theory_workspace_bytes(uint32_t n_grid);
+
 /* Per-region results of one Lloyd / EM expectation pass under the MAE criterion (section 3.2 eq. 7-8; appendix B.4). */
 typedef struct {
     double median[16];   /* weighted median of the normalised weights of region l, weights = absolute block maximum:

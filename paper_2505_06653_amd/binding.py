@@ -20,7 +20,7 @@ EXPORTS = ("bof4_workspace_bytes", "bof4_opq_threshold", "bof4_thresholds", "bof
            "bof4_quant_error", "bof4_gemv", "bof4_gemv_outlier_table",
            "bof4_gemv_outlier_table_bytes", "bof4_gemm", "bof4_gemm_pack", "bof4_gemm_packed_bytes",
            "bof4_gemm_outlier_table", "bof4_gemm_workspace_bytes",
-           "bof4_time_next_call", "bof4_last_error",
+           "bof4_theory_centroids", "bof4_theory_workspace_bytes", "bof4_time_next_call", "bof4_last_error",
            "bof4_last_hip_error")
 
 
@@ -134,6 +134,11 @@ def lib():
         L.bof4_gemm_outlier_table.argtypes = L.bof4_gemv_outlier_table.argtypes
         L.bof4_gemm_workspace_bytes.restype = ctypes.c_size_t
         L.bof4_gemm_workspace_bytes.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint32]
+        L.bof4_theory_workspace_bytes.restype = ctypes.c_size_t
+        L.bof4_theory_workspace_bytes.argtypes = [ctypes.c_uint32]
+        L.bof4_theory_centroids.restype = ctypes.c_int
+        L.bof4_theory_centroids.argtypes = [f64p, f64p, ctypes.c_uint32, ctypes.c_double, ctypes.c_uint32, f64p,
+                                            ctypes.c_uint16, ctypes.c_int, f64p, vp, ctypes.c_size_t, vp]
         L.bof4_time_next_call.restype = ctypes.c_int
         L.bof4_time_next_call.argtypes = [vp, vp]
         L.bof4_last_error.restype = ctypes.c_char_p
@@ -226,6 +231,24 @@ def bof4_codebook_update(stats, pinned_mask, cb):
         s.sse, s.n_used, s.n_outliers = float(stats["sse"]), int(stats["n_used"]), int(stats["n_outliers"])
         stats = s
     _check(lib().bof4_codebook_update(ctypes.byref(stats), pinned_mask, out.ctypes.data))
+    return out
+
+
+def bof4_theory_centroids(pdf, cdf, u_max, block, cb, pinned_mask, signed, ws=None, stream=None, device="cuda"):
+    """One theoretical maximisation step for the distribution tabulated in pdf / cdf (float64 arrays over [0, u_max]).
+    Returns the new float64[16] codebook."""
+    pdf = np.ascontiguousarray(pdf, dtype=np.float64)
+    cdf = np.ascontiguousarray(cdf, dtype=np.float64)
+    if pdf.shape != cdf.shape or pdf.ndim != 1:
+        raise ValueError("pdf and cdf must be 1-d arrays of one length")
+    cb, cbp = _cb(cb)
+    n = int(pdf.size)
+    if ws is None:
+        ws = torch.empty(int(lib().bof4_theory_workspace_bytes(n)), dtype=torch.uint8, device=device)
+    out = np.zeros(16, dtype=np.float64)
+    _check(lib().bof4_theory_centroids(pdf.ctypes.data_as(_F64P), cdf.ctypes.data_as(_F64P), n, float(u_max), block,
+                                       cbp, int(pinned_mask), int(signed), out.ctypes.data_as(_F64P), _ptr(ws),
+                                       ws.numel(), _stream(stream)))
     return out
 
 

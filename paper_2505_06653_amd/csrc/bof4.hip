@@ -27,6 +27,7 @@
 #include "bof4_gemv.h"
 #include "bof4_gemm.h"
 #include "bof4_error.h"
+#include "bof4_theory.h"
 
 namespace {
 using namespace bof4;
@@ -752,6 +753,50 @@ int bof4_quant_error(const void* w_dev, uint64_t n, uint32_t block, const double
     } else {
         HIP_TRY(hipMemcpyAsync(out_host, rec_dev, sizeof(bof4_error_stats), hipMemcpyDeviceToHost, s));
         HIP_TRY(wait_for_stream(s));
+    }
+    return BOF4_OK;
+}
+
+size_t bof4_theory_workspace_bytes(uint32_t n_grid) { return ((size_t)3 * n_grid + 32) * sizeof(double); }
+
+int bof4_theory_centroids(const double* pdf_host, const double* cdf_host, uint32_t n_grid, double u_max, uint32_t block,
+                          const double* cb_host, uint16_t pinned_mask, int signed_norm, double* cb_out_host,
+                          void* ws_dev, size_t ws_bytes, void* stream) {
+    if (!pdf_host || !cdf_host || !cb_out_host || !ws_dev) return fail(BOF4_ERR_ARG, "bof4_theory_centroids: null pointer");
+    if (n_grid < 3 || n_grid % 2 == 0 || n_grid > (1u << 24) || !(u_max > 0.0) || !std::isfinite(u_max))
+        return fail(BOF4_ERR_ARG, "bof4_theory_centroids: the grid needs an odd number of points (3 .. 2^24) and u_max > 0");
+    if (block < 2) return fail(BOF4_ERR_ARG, "bof4_theory_centroids: block must be at least 2");
+    if (!valid_codebook(cb_host)) return fail(BOF4_ERR_ARG, "bof4_theory_centroids: codebook must be 16 finite ascending levels");
+    if (!((pinned_mask >> 15) & 1u) || (!signed_norm && !(pinned_mask & 1u)))
+        return fail(BOF4_ERR_ARG, "bof4_theory_centroids: a region that holds a point mass of the normalised weights "
+                                  "(level 15; level 0 for absolute normalisation) must be pinned");
+    if (cb_host[0] < -1.0 || cb_host[15] > 1.0) return fail(BOF4_ERR_ARG, "bof4_theory_centroids: levels outside [-1, 1]");
+    if (!aligned(ws_dev, 256)) return fail(BOF4_ERR_ARG, "bof4_theory_centroids: workspace misaligned");
+    if (ws_bytes < bof4_theory_workspace_bytes(n_grid)) return fail(BOF4_ERR_WORKSPACE, "bof4_theory_centroids: workspace too small");
+    hipStream_t s = (hipStream_t)stream;
+    double* pdf = (double*)ws_dev;
+    double* cdf = pdf + n_grid;
+    double* psi = cdf + n_grid;
+    double* sums = psi + n_grid;
+    const double h = u_max / (double)(n_grid - 1);
+    TheoryRegions rg;
+    rg.skip_mask = pinned_mask;
+    for (int l = 0; l < 16; ++l) {
+        const double a = l > 0 ? 0.5 * (cb_host[l - 1] + cb_host[l]) : -1.0;
+        rg.a[l] = a < -1.0 ? -1.0 : a;
+        rg.b[l] = l < 15 ? 0.5 * (cb_host[l] + cb_host[l + 1]) : 1.0;
+    }
+    HIP_TRY(hipMemcpyAsync(pdf, pdf_host, (size_t)n_grid * 8, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(cdf, cdf_host, (size_t)n_grid * 8, hipMemcpyHostToDevice, s));
+    hipLaunchKernelGGL(theory_psi_kernel, dim3(1), dim3(1024), 0, s, pdf, n_grid, h, psi);
+    hipLaunchKernelGGL(theory_centroid_kernel, dim3(16), dim3(256), 0, s, pdf, cdf, psi, n_grid, h, block, rg, sums);
+    HIP_TRY(hipGetLastError());
+    double host_sums[32];
+    HIP_TRY(hipMemcpyAsync(host_sums, sums, sizeof(host_sums), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    for (int l = 0; l < 16; ++l) {
+        cb_out_host[l] = cb_host[l];
+        if (!((pinned_mask >> l) & 1u) && host_sums[2 * l + 1] > 0.0) cb_out_host[l] = host_sums[2 * l] / host_sums[2 * l + 1];
     }
     return BOF4_OK;
 }

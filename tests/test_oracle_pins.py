@@ -730,3 +730,71 @@ def test_gemm_is_the_matrix_product_of_the_decoded_matrix():
     assert np.array_equal(ye[0], W[:, 77])
     st, yv, av = oracle.gemv(codes, scales, rows, cols, block, CB_S64, x, oi, ov)
     assert np.all(np.abs(y - yv) <= 2.0 ** -9 * av) and np.max(np.abs(y - yv)) > 0
+
+
+# ------------------------------------------------------------------ theoretical centroids for a tabulated distribution
+def _gauss_tables(u_max=16.0, n=65537):
+    from oracle import theory_general
+    from scipy.special import ndtr
+    return theory_general.tables(lambda u: np.exp(-0.5 * u * u) / np.sqrt(2.0 * np.pi), ndtr, u_max, n)
+
+
+def test_general_centroid_reduces_to_the_gaussian_closed_form(tables):
+    """Section 3.2 eq. 5 evaluated from tables of p_W and F_W: with the standard normal tables it must give what the
+    Gaussian closed form of appendix B.2 gives (oracle/theory.py, itself pinned by the printed column), on the printed
+    theoretical codebook - which it must leave in place - and on a codebook away from the fixed point; block 64 and 32."""
+    from oracle import theory_general
+    pdf, cdf = _gauss_tables()
+    theo = tables["emp_theo"][:, 1]
+    got = theory_general.centroid_update(theo, 64, codebooks.PIN_BOF4, 0, pdf, cdf, 16.0)
+    assert np.max(np.abs(got - theory.centroid_update(theo, 64, codebooks.PIN_BOF4))) < 1e-7
+    assert np.max(np.abs(got - theo)) < 1e-6
+    start = codebooks.gaussian_quantile_init()
+    for block in (32, 64):
+        a = theory_general.centroid_update(start, block, codebooks.PIN_BOF4S, 1, pdf, cdf, 16.0)
+        b = theory.centroid_update(start, block, codebooks.PIN_BOF4S)
+        assert np.max(np.abs(a - b)) < 1e-7 and np.max(np.abs(a - start)) > 1e-3
+
+
+def test_general_centroid_agrees_with_the_monte_carlo_centroid_for_student_t_weights():
+    """A distribution that is not Gaussian: for Student-t (nu = 5) weights the centroids from the tables must agree
+    with the empirical centroids of eq. 6 on 6.4e7 samples to Monte-Carlo accuracy, while the Gaussian tables give
+    something visibly different (so the comparison can tell the two apart)."""
+    from scipy import stats
+    from oracle import theory_general
+    w = inputs.student_t_matrix(1_000_000, 64, 5.0, 1.0, 0.0, seed=77).reshape(-1)
+    cb = codebooks.array(codebooks.BOF4S_MSE[64])
+    st, o = oracle.lloyd_step(inputs.bits(w), 64, cb, 1)
+    assert st == oracle.OK
+    emp = oracle.codebook_update(o, codebooks.PIN_BOF4S, cb)
+    t5 = stats.t(5)
+    pdf, cdf = theory_general.tables(t5.pdf, t5.cdf, 512.0, (1 << 19) + 1)
+    got = theory_general.centroid_update(cb, 64, codebooks.PIN_BOF4S, 1, pdf, cdf, 512.0)
+    gpdf, gcdf = _gauss_tables()
+    gauss = theory_general.centroid_update(cb, 64, codebooks.PIN_BOF4S, 1, gpdf, gcdf, 16.0)
+    assert np.max(np.abs(got - emp)) < 2e-4          # (7e-5 on this draw)
+    assert np.max(np.abs(gauss - emp)) > 2e-3        # ten times that: the Gaussian tables do not pass for t weights
+
+
+def test_general_centroid_needs_the_weighting_by_the_squared_block_maximum():
+    """Control: without the factor m^2 of eq. 5 (the centroid of the normalised weights, appendix D) the result moves by
+    a thousand times the 1e-7 to which the general form and the closed form agree - a dropped weighting would not
+    pass."""
+    from oracle import theory_general
+    pdf, cdf = _gauss_tables()
+    theo_like = codebooks.gaussian_quantile_init()
+    right = theory_general.centroid_update(theo_like, 64, codebooks.PIN_BOF4S, 1, pdf, cdf, 16.0)
+    # same recipe with m^0 instead of m^2: num INT (1/m) [Phi1], den INT [F]
+    n, h = pdf.size, 16.0 / (pdf.size - 1)
+    m = np.arange(n) * h
+    ws = np.ones(n); ws[1:-1:2] = 4.0; ws[2:-1:2] = 2.0; ws *= h / 3.0
+    psi = theory_general.upper_first_moment(pdf, 16.0)
+    core = np.zeros(n); core[1:] = (2.0 * cdf[1:] - 1.0) ** 62 * pdf[1:]
+    xi = 0.5 * (theo_like[:-1] + theo_like[1:])
+    l = 3
+    a, b = xi[l - 1], xi[l]
+    F = lambda t: np.where(t < 0, 1.0 - np.interp(np.abs(t), m, cdf), np.interp(np.abs(t), m, cdf))
+    P = lambda t: -np.interp(np.abs(t), m, psi)
+    inv_m = np.zeros(n); inv_m[1:] = 1.0 / m[1:]
+    wrong = np.sum(ws * inv_m * (P(m * b) - P(m * a)) * core) / np.sum(ws * (F(m * b) - F(m * a)) * core)
+    assert abs(wrong - right[l]) > 1e-4
