@@ -41,6 +41,7 @@ __global__ __launch_bounds__(256, 2) void seg_error_kernel(const uint4* __restri
         uint2 tab[BIN_TABLE_ENTRIES];
         float lv[16];
         char stage[WAVES_PER_WG * C::STAGE_BYTES];
+        uint16_t tie[WAVES_PER_WG * TIE_BUF_HALFWORDS] __attribute__((aligned(16)));
     };
     __shared__ __attribute__((aligned(16))) Shared sh;
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -51,6 +52,7 @@ __global__ __launch_bounds__(256, 2) void seg_error_kernel(const uint4* __restri
     const uint32_t lane_off = bin_lane_offset(threadIdx.x & 63u);
     const float* lv = sh.lv;
     char* stage = sh.stage + wave * C::STAGE_BYTES;
+    uint16_t* tie_buf = sh.tie + wave * TIE_BUF_HALFWORDS;
     const uint64_t n_vec = n_seg * C::NV;
     const uint64_t n_tiles = (n_seg + 63) / 64;
     const uint64_t n_waves = (uint64_t)gridDim.x * WAVES_PER_WG;
@@ -77,7 +79,7 @@ __global__ __launch_bounds__(256, 2) void seg_error_kernel(const uint4* __restri
             k_out = opq_count(omap);
         }
         uint32_t maxabs, sign;
-        block_constant<I>(R, lane, signed_norm != 0, maxabs, sign);
+        block_constant<I>(R, lane, signed_norm != 0, maxabs, sign, tie_buf);
         const float m = bf16_bits_to_f32(maxabs | (sign << 15));
         const float m_eff = f16_bits_to_f32(f32_to_f16_bits(m));
         // what a zeroed outlier's placeholder decodes to (0 for every codebook with a zero level)

@@ -96,13 +96,17 @@ __device__ __forceinline__ float seg_f32(const uint32_t* R, int e) {
 // ---------------------------------------------------------------------------------------------- block constant
 // Largest magnitude of the block and the sign of its first occurrence (lowest index).  P = largest pattern in value
 // order, N = smallest: if the segment holds a non-negative number P is the largest of them, if it holds a negative
-// number N is the one of largest magnitude.  Only when +a and -a are both present at the maximum does the order of
-// the elements matter, and only then the segment is scanned.  The packed three-operand binary16 maximum / minimum
-// does two registers (four weights) per instruction; if a pattern that binary16 reads as NaN turns up (a bfloat16
-// beyond 2^121: never in the ordinary range) the wave repeats the search with integer compares.
+// number N is the one of largest magnitude.  The packed three-operand binary16 maximum / minimum does two registers
+// (four weights) per instruction; if a pattern that binary16 reads as NaN turns up (a bfloat16 beyond 2^121: never in
+// the ordinary range) the wave repeats the search with integer compares.
+// Only when +a and -a are both present at the maximum does the order of the elements matter.  Such blocks (a few in a
+// thousand for bfloat16 weights, i.e. one in every third tile) are settled one at a time by the whole wave: the
+// block's lanes write their segments to `tie_buf` (wave-private LDS, I halfwords), every lane looks at I / 64 of the
+// elements, and two ballots give the first element of that magnitude and its sign.
+constexpr int TIE_BUF_HALFWORDS = 256;  // per wave: the largest block
 template <int I>
 __device__ __forceinline__ void block_constant(const uint32_t (&R)[SegCfg<I>::NR], uint32_t lane, bool signed_norm,
-                                               uint32_t& maxabs, uint32_t& sign) {
+                                               uint32_t& maxabs, uint32_t& sign, uint16_t* tie_buf) {
     using C = SegCfg<I>;
     static_assert(C::NR % 2 == 0, "registers are taken in pairs");
     uint32_t P = pk_max3_f16(R[0], R[1], R[1]), N = pk_min3_f16(R[0], R[1], R[1]);
@@ -134,19 +138,38 @@ __device__ __forceinline__ void block_constant(const uint32_t (&R)[SegCfg<I>::NR
         sign = 0;
         return;
     }
-    bool tie = (absP == absN);
-    if (__builtin_amdgcn_ballot_w64(tie) != 0) {  // wave-uniform: rare
-        uint32_t key = 0xffffffffu;
-        if (tie) {
-            const uint32_t lane_in_block = lane & (C::LPB - 1);
+    unsigned long long ties = __builtin_amdgcn_ballot_w64(absP == absN);
+    constexpr int K = I >= 64 ? I / 64 : 1;  // elements of the block a lane looks at
+    while (ties != 0ull) {  // wave-uniform: one block per turn
+        const uint32_t first_lane = (uint32_t)__builtin_ctzll(ties) & ~(uint32_t)(C::LPB - 1);
+        const bool mine = (lane & ~(uint32_t)(C::LPB - 1)) == first_lane;
+        wave_lds_fence();  // the readers of the previous turn are done
+        if (mine) {
+            uint4* dst = reinterpret_cast<uint4*>(tie_buf + (lane - first_lane) * C::SEG);
 #pragma unroll
-            for (int e = C::SEG - 1; e >= 0; --e) {
-                uint32_t b = seg_bits(R, e);
-                if ((b & 0x7fffu) == maxabs) key = ((lane_in_block * C::SEG + e) << 1) | (b >> 15);
+            for (int k = 0; k < C::NV; ++k) dst[k] = make_uint4(R[4 * k], R[4 * k + 1], R[4 * k + 2], R[4 * k + 3]);
+        }
+        wave_lds_fence();
+        const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)maxabs, (int)first_lane);
+        uint32_t best = 0xffffffffu, best_sign = 0;  // uniform: lowest element index of magnitude a, and its sign bit
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            const uint32_t e = lane * K + j;
+            const uint32_t b = (I >= 64 || lane < 32) ? (uint32_t)tie_buf[e] : 0xffffu;
+            const bool hit = (b & 0x7fffu) == a && (I >= 64 || lane < 32);
+            const unsigned long long hits = __builtin_amdgcn_ballot_w64(hit);
+            const unsigned long long negs = __builtin_amdgcn_ballot_w64(hit && (b >> 15) != 0u);
+            if (hits != 0ull) {
+                const uint32_t l0 = (uint32_t)__builtin_ctzll(hits);
+                const uint32_t idx = l0 * K + j;
+                if (idx < best) {
+                    best = idx;
+                    best_sign = (uint32_t)((negs >> l0) & 1ull);
+                }
             }
         }
-        key = group_min_u32<C::LPB>(key);
-        if (tie) sign = key & 1u;
+        if (mine) sign = best_sign;
+        ties &= ~(((C::LPB == 64 ? 0ull : (1ull << C::LPB)) - 1ull) << first_lane);
     }
 }
 
@@ -164,10 +187,13 @@ __device__ __forceinline__ bool opq_is_out(uint32_t b, double rhs) {
     const double v = (double)bf16_bits_to_f32(b);
     return (v * v) * II1 > rhs;
 }
-template <int I>
+template <int I, bool F32_ROOT = false>
 __device__ __forceinline__ uint32_t opq_theta_of(double rhs) {
     constexpr double II1 = (double)I * (double)(I - 1);
-    const float t = (float)__builtin_sqrt(rhs * (1.0 / II1));  // binary64 root: no under/overflow of tau^2
+    // the root only has to land within one bfloat16 pattern of tau = sqrt(rhs / (I (I - 1))): the exact tests below
+    // settle the rest.  The binary64 root never under- or overflows; the binary32 one (an instruction instead of a
+    // dozen) is for callers that keep rhs / (I (I - 1)) inside binary32's normal range.
+    const float t = F32_ROOT ? __builtin_amdgcn_sqrtf((float)(rhs * (1.0 / II1))) : (float)__builtin_sqrt(rhs * (1.0 / II1));
     uint32_t b0 = __float_as_uint(t) >> 16;
     b0 = min(max(b0, 1u), 0x7F7Eu);
     uint32_t theta = b0 - 1;
@@ -222,8 +248,11 @@ __device__ __forceinline__ uint32_t opq_theta(const uint32_t (&R)[SegCfg<I>::NR]
     const double V = fma(-(double)Sf, (double)Sf, IQ), E = (3.05 * EPS) * IQ;
     bool settled = false;
     uint32_t theta = 0x7FFFu;
-    if (Qf > 0x1p-80f && Qf < 0x1p100f && V - E > 0.0) {
-        theta = opq_theta_of<I>(T2 * (V - E));
+    // (the bounds on T^2 (V - E) keep the argument of the binary32 root inside [2^-100, 2^120])
+    const double rhs_lo = T2 * (V - E);
+    if (Qf > 0x1p-80f && Qf < 0x1p100f && rhs_lo > 0x1p-100 * ((double)I * (double)(I - 1)) &&
+        rhs_lo < 0x1p120 * ((double)I * (double)(I - 1))) {
+        theta = opq_theta_of<I, true>(rhs_lo);
         settled = opq_is_out<I>(theta + 1, T2 * (V + E));
     }
     if (__builtin_amdgcn_ballot_w64(!settled) != 0) theta = opq_theta_exact<I>(R, T2);  // wave-uniform
@@ -345,10 +374,12 @@ __global__ __launch_bounds__(256, pass_waves_per_simd(OPQ, QUANT, LLOYD)) void s
         uint2 tab[BIN_TABLE_ENTRIES];
         unsigned long long cols[COLS ? WAVES_PER_WG * 16 * 64 : 1];
         char stage[STAGED ? WAVES_PER_WG * C::STAGE_BYTES : 16];
+        uint16_t tie[WAVES_PER_WG * TIE_BUF_HALFWORDS] __attribute__((aligned(16)));
     };
     __shared__ __attribute__((aligned(16))) Shared sh;
     const uint32_t tid = threadIdx.x, lane = tid & 63;
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));  // scalar: tile ranges on the SALU
+    uint16_t* tie_buf = sh.tie + wave * TIE_BUF_HALFWORDS;
     bin_table_fill(sh.tab, bt, tid, blockDim.x);
     const uint2* tab = sh.tab;
     const uint32_t lane_off = bin_lane_offset(lane);
@@ -450,7 +481,7 @@ __global__ __launch_bounds__(256, pass_waves_per_simd(OPQ, QUANT, LLOYD)) void s
             }
         }
         uint32_t maxabs, sign;
-        block_constant<I>(R, lane, signed_norm != 0, maxabs, sign);
+        block_constant<I>(R, lane, signed_norm != 0, maxabs, sign, tie_buf);
         const float m = bf16_bits_to_f32(maxabs | (sign << 15));
         const uint32_t s16 = f32_to_f16_bits(m);
         const float m_eff = f16_bits_to_f32(s16);
