@@ -5,8 +5,8 @@
 // segments: it loads the tile with fully coalesced 16-byte loads, parks it in a wave-private, padded LDS buffer and
 // reads it back transposed, so that every lane ends up holding one whole segment in registers.  All per-block work
 // (maximum search of section 2.1 eq. 1 / section 3.1 eq. 4, normalisation eq. 2, nearest-level search of section
-// 3.2, the sums of eq. 6) then runs inside a lane without cross-lane traffic.  Every wave owns a contiguous range
-// of tiles.
+// 3.2, the sums of eq. 6) then runs inside a lane without cross-lane traffic.  A wave that writes an outlier list
+// owns a contiguous range of tiles; otherwise the tiles are dealt out to the waves in turn.
 #pragma once
 #include "bof4_device.h"
 
@@ -392,7 +392,14 @@ __global__ __launch_bounds__(256, pass_waves_per_simd(OPQ, QUANT, LLOYD)) void s
     const uint64_t n_tiles = (n_seg + 63) / 64;
     const uint64_t n_waves = (uint64_t)gridDim.x * WAVES_PER_WG;
     const uint64_t gw = (uint64_t)blockIdx.x * WAVES_PER_WG + wave;
-    const uint64_t t0 = n_tiles * gw / n_waves, t1 = n_tiles * (gw + 1) / n_waves;
+    // Which tiles the wave takes.  With an outlier list to write, a contiguous range (the wave appends to its staging
+    // region in ascending order of the flat index).  Otherwise the tiles are dealt out in turn, wave g taking tiles
+    // g, g + n_waves, ...: at any moment the chip then works on one compact stretch of the tensor instead of
+    // thousands of far-apart ones, which the memory system takes 4 to 7 % faster where codes are written; the
+    // assignment is still a fixed function of the launch, so the sums stay bit-reproducible.
+    constexpr bool DEAL = !(QUANT && OPQ);
+    const uint64_t t0 = DEAL ? gw : n_tiles * gw / n_waves, t1 = DEAL ? n_tiles : n_tiles * (gw + 1) / n_waves;
+    const uint64_t t_step = DEAL ? n_waves : 1;
     // fold: levels 4 p + k (k = 0 .. 3) of the blocks of lanes lane ^ c (c = 0 .. 3)
     const uint32_t p4 = (lane & 3u) * 4u;
     unsigned long long* fold_col[4];
@@ -428,13 +435,13 @@ __global__ __launch_bounds__(256, pass_waves_per_simd(OPQ, QUANT, LLOYD)) void s
             R[4 * k + 3] = q.w;
         }
     }
-    for (uint64_t t = t0; t < t1; ++t) {
+    for (uint64_t t = t0; t < t1; t += t_step) {
         // (after the wave's last tile this requests that tile once more: cached, and never used)
-        const uint4* pn = own_segment<I>(w, t + 1 < t1 ? t + 1 : t, n_seg, lane);
+        const uint4* pn = own_segment<I>(w, t + t_step < t1 ? t + t_step : t, n_seg, lane);
         if constexpr (STAGED) {
             wave_lds_fence();
             tile_stage<I>(stage, lane, G);
-            if (t + 1 < t1) tile_issue_loads<I>(w, (t + 1) * 64 * C::NV, n_vec, lane, G);
+            if (t + t_step < t1) tile_issue_loads<I>(w, (t + t_step) * 64 * C::NV, n_vec, lane, G);
             wave_lds_fence();
             tile_fetch<I>(stage, lane, R);
         }
