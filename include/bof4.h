@@ -160,7 +160,11 @@ typedef struct {
  * maximum as stored in binary16, for absolute and signed normalisation alike) is found by a radix search that reads
  * the weights twice and then a list of the few elements still in question (in the workspace: n / 4 bytes; if the list
  * runs full - a tensor of equal numbers - or outliers must be tracked through the region around zero, the weights are
- * read three or four times instead).  The appendix's closing formula names the element before the weighted median;
+ * read three or four times instead).  From 2^26 weights up (at block 64) the weights are read once, after a look at
+ * one tile of 4096 weights in 16 that tells the search where to expect the medians; if those tiles are unlike the rest
+ * of the tensor the search notices and reads the weights again as above - the result is the same either way.  Two
+ * environment variables help when looking into this: BOF4_MAE_TRACE (set: every call prints to stderr which way it
+ * went) and BOF4_MAE_NO_SAMPLING (set: always the two-pass search).  The appendix's closing formula names the element before the weighted median;
  * what is returned is the minimiser that its derivation arrives at.  Weights are added as exact 64-bit integers, which
  * needs sum over all weights of |block constant| < 2^38 (BOF4_ERR_ARG otherwise).
  *   weight_by_max  nonzero: the paper's criterion (eq. 8).  0: every weight counts one unit - the plain median of the

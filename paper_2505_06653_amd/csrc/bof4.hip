@@ -18,6 +18,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 #include "bof4.h"
@@ -245,6 +246,10 @@ static_assert(pass_grid(false, true, false) <= PASS_GRID_MAX && pass_grid(false,
 // MAE step: histogram, search state, per-wave counts, per-workgroup floating-point partials, result record.
 // Entries of the candidate list of the MAE step: n / 32 (about five times what a pass leaves), at most 2^27; dealt
 // out evenly to the waves of the pass kernels.
+// The MAE step samples one tile in 16 to place its windows, from 16384 wave tiles (2^26 weights at block 64) up: below
+// that the second pass over the weights costs less than it would save.
+constexpr uint32_t MAE_SAMPLE_MASK = 15;
+constexpr uint64_t MAE_SAMPLING_MIN_TILES = 16384;
 uint64_t mae_cand_entries(uint64_t n) {
     const uint64_t e = n / 32;
     return e < (1ull << 27) ? e : (1ull << 27);
@@ -1528,55 +1533,75 @@ int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const dou
     const uint32_t cand_cap = (uint32_t)(mae_cand_entries(n) / cand_waves);
     const bool zero_region_searched = !((skip_mask >> bt.code_of_zero) & 1u);
     const bool use_list = passes >= 3 && cand_cap >= 8 && !(opq && zero_region_searched);
+    // One pass over all the weights instead of two (large tensors): a sampling pass over one tile in 16 tells the full
+    // first pass which first digits to write to the list (bof4_mae.h).
+    const bool sampling = use_list && tiles >= MAE_SAMPLING_MIN_TILES && std::getenv("BOF4_MAE_NO_SAMPLING") == nullptr;
     hipLaunchKernelGGL(mae_init_kernel, dim3(16), dim3(256), 0, s, lc, state, hist);
+#define BOF4_LAUNCH_MAE(II, FIRST_, CAPTURE_, CAND_, GATE_, SAMPLE_)                                                  \
+    if (bt.fast && opq) hipLaunchKernelGGL((mae_pass_kernel<II, true, true, FIRST_, CAPTURE_>), dim3(sgrid), dim3(256), \
+                                           0, s, w, n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part,  \
+                                           CAND_, cand_count, cand_cap, GATE_, unweighted, SAMPLE_);                  \
+    else if (bt.fast) hipLaunchKernelGGL((mae_pass_kernel<II, true, false, FIRST_, CAPTURE_>), dim3(sgrid), dim3(256),  \
+                                         0, s, w, n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part,    \
+                                         CAND_, cand_count, cand_cap, GATE_, unweighted, SAMPLE_);                    \
+    else if (opq) hipLaunchKernelGGL((mae_pass_kernel<II, false, true, FIRST_, CAPTURE_>), dim3(sgrid), dim3(256), 0,   \
+                                     s, w, n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part, CAND_,    \
+                                     cand_count, cand_cap, GATE_, unweighted, SAMPLE_);                               \
+    else hipLaunchKernelGGL((mae_pass_kernel<II, false, false, FIRST_, CAPTURE_>), dim3(sgrid), dim3(256), 0, s, w,     \
+                            n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part, CAND_, cand_count,       \
+                            cand_cap, GATE_, unweighted, SAMPLE_);
+#define BOF4_LAUNCH_MAE_BLOCK(FIRST_, CAPTURE_, CAND_, GATE_, SAMPLE_)                 \
+    switch (block) {                                                                   \
+        case 32: BOF4_LAUNCH_MAE(32, FIRST_, CAPTURE_, CAND_, GATE_, SAMPLE_) break;   \
+        case 64: BOF4_LAUNCH_MAE(64, FIRST_, CAPTURE_, CAND_, GATE_, SAMPLE_) break;   \
+        case 128: BOF4_LAUNCH_MAE(128, FIRST_, CAPTURE_, CAND_, GATE_, SAMPLE_) break; \
+        default: BOF4_LAUNCH_MAE(256, FIRST_, CAPTURE_, CAND_, GATE_, SAMPLE_) break;  \
+    }
+    unsigned long long* const no_cand = nullptr;
+    const uint32_t* const no_gate = nullptr;
+    if (sampling) {
+        BOF4_LAUNCH_MAE_BLOCK(true, false, no_cand, no_gate, MAE_SAMPLE_MASK)
+        hipLaunchKernelGGL(mae_predict_kernel, dim3(1), dim3(1024), 0, s, state, hist, cnt_part, sgrid,
+                           (uint32_t)skip_mask);
+    }
     for (uint32_t p = 0; p < passes; ++p) {
         const bool first = p == 0;
-        const bool writes_list = use_list && p == 1, reads_list = use_list && p >= 2;
+        // the pass that writes the list: the first one if it captures by windows, else the second
+        const uint32_t list_pass = sampling ? 0u : 1u;
+        const bool writes_list = use_list && p == list_pass, reads_list = use_list && p > list_pass;
         unsigned long long* cand_w = writes_list ? cand : nullptr;
-        const uint32_t* gate = reads_list ? cand_full : nullptr;  // the scan only runs if the list ran full
+        const uint32_t* gate = reads_list ? cand_full : nullptr;  // the scan only runs if the list cannot be used
         if (first) timing_begin(s);
         if (reads_list)
             hipLaunchKernelGGL(mae_list_kernel, dim3(sgrid), dim3(256), 0, s, cand, cand_count, cand_cap, cand_full,
                                state, hist, unweighted);
-#define BOF4_LAUNCH_MAE(II, FIRST_)                                                                                   \
-    if (bt.fast && opq) hipLaunchKernelGGL((mae_pass_kernel<II, true, true, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,  \
-                                           n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part, cand_w, \
-                                           cand_count, cand_cap, gate, unweighted);                                       \
-    else if (bt.fast) hipLaunchKernelGGL((mae_pass_kernel<II, true, false, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,   \
-                                         n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part, cand_w,   \
-                                         cand_count, cand_cap, gate, unweighted);                                   \
-    else if (opq) hipLaunchKernelGGL((mae_pass_kernel<II, false, true, FIRST_>), dim3(sgrid), dim3(256), 0, s, w,       \
-                                     n_seg, cb, bt, signed_norm, T2, state, hist, cnt_part, sae_part, cand_w,       \
-                                     cand_count, cand_cap, gate, unweighted);                                       \
-    else hipLaunchKernelGGL((mae_pass_kernel<II, false, false, FIRST_>), dim3(sgrid), dim3(256), 0, s, w, n_seg, cb,    \
-                            bt, signed_norm, T2, state, hist, cnt_part, sae_part, cand_w, cand_count, cand_cap, gate, \
-                            unweighted);
-#define BOF4_LAUNCH_MAE_BLOCK(FIRST_)                \
-    switch (block) {                                 \
-        case 32: BOF4_LAUNCH_MAE(32, FIRST_) break;   \
-        case 64: BOF4_LAUNCH_MAE(64, FIRST_) break;   \
-        case 128: BOF4_LAUNCH_MAE(128, FIRST_) break; \
-        default: BOF4_LAUNCH_MAE(256, FIRST_) break;  \
-    }
-        if (first) {
-            BOF4_LAUNCH_MAE_BLOCK(true)
+        if (first && sampling) {
+            BOF4_LAUNCH_MAE_BLOCK(true, true, cand_w, gate, 0u)
+        } else if (first) {
+            BOF4_LAUNCH_MAE_BLOCK(true, false, cand_w, gate, 0u)
         } else {
-            BOF4_LAUNCH_MAE_BLOCK(false)
+            BOF4_LAUNCH_MAE_BLOCK(false, false, cand_w, gate, 0u)
         }
-#undef BOF4_LAUNCH_MAE_BLOCK
-#undef BOF4_LAUNCH_MAE
         if (first) timing_end(s);
         hipLaunchKernelGGL(mae_select_kernel, dim3(1), dim3(1024), 0, s, state, hist, cnt_part, sae_part, sgrid,
                            first ? 1 : 0, p + 1 == passes ? 1 : 0, (uint32_t)skip_mask,
                            writes_list ? cand_count : (const uint32_t*)nullptr, cand_waves, cand_cap, cand_full,
-                           direct ? direct : rec_dev, unweighted);
+                           (writes_list && sampling) ? 1 : 0, direct ? direct : rec_dev, unweighted);
     }
+#undef BOF4_LAUNCH_MAE_BLOCK
+#undef BOF4_LAUNCH_MAE
     HIP_TRY(hipGetLastError());
     if (direct) {
         HIP_TRY(wait_for_flag(s, &out_host->n_used));
     } else {
         HIP_TRY(hipMemcpyAsync(out_host, rec_dev, sizeof(bof4_mae_stats), hipMemcpyDeviceToHost, s));
         HIP_TRY(wait_for_stream(s));
+    }
+    if (std::getenv("BOF4_MAE_TRACE") != nullptr) {  // debugging aid: which way the search went
+        uint32_t unusable = 0;
+        if (use_list) HIP_TRY(hipMemcpy(&unusable, cand_full, 4, hipMemcpyDeviceToHost));
+        std::fprintf(stderr, "bof4_lloyd_step_mae: passes %u, list %d, sampling %d, list unusable %u\n", passes,
+                     (int)use_list, (int)sampling, unusable);
     }
     if (out_host->sae != out_host->sae)
         return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: block constants too large for exact weighted medians");

@@ -14,6 +14,11 @@
 // list - key, region and block constant in 8 bytes - and the passes after it read that list instead of the weights.
 // Every wave appends to a region of its own; if one of them runs full (a tensor of equal numbers), the later passes
 // scan the weights as before.
+// Large tensors get by with ONE pass over all the weights: a first-digit histogram over one tile in 16 (picked by a
+// hash of the tile number) says where every region's median will be to within a few digits; the full first pass then
+// writes the elements whose first digit lies in that window to the list while it fills the exact histogram.  If the
+// exact first digit of every region falls inside its window (it does unless the sampled tiles differ from the rest),
+// all later passes read the list; if not, they scan the weights, as they do when the list runs full.
 //
 // What is computed is "the smallest x_k with 2 * sum_{x_j <= x_k} a_j >= sum_j a_j" - the lower weighted median,
 // which minimises sum a_j |x_j - c|.  (The closing formula of appendix B.4 names the element before it; its own
@@ -31,6 +36,8 @@ struct MaeLevelState {
     uint32_t pad;     // 1: the caller does not want this region's median (no search after the first pass)
     unsigned long long base;   // weight of the elements whose sub lies below prefix << hi
     unsigned long long total;  // weight of the whole region
+    uint32_t win_lo;   // first digits win_lo .. win_lo + win_len - 1: what a capturing first pass writes to the list
+    uint32_t win_len;
 };
 // Per-region constants from the host: key range of the region.
 struct MaeLevelConst {
@@ -61,13 +68,22 @@ __global__ __launch_bounds__(256) void mae_init_kernel(MaeLevelConst lc, MaeLeve
         s.pad = 0;
         s.base = 0ull;
         s.total = 0ull;
+        s.win_lo = 0;
+        s.win_len = 0;
         state[t] = s;
     }
 }
 
+// Which tiles the sampling pass looks at: one in (sample_mask + 1), spread by a multiplicative hash so that the choice
+// does not follow the rows and columns of the matrices behind the tensor.
+__host__ __device__ inline bool mae_tile_sampled(uint64_t t, uint32_t sample_mask) {
+    return ((((uint32_t)t * 0x9E3779B1u) >> 16) & sample_mask) == 0u;
+}
+
 // One pass over the weights.  FIRST also counts the regions' elements and accumulates the error sum
-// sum |block constant| |x - level| at the current codebook.
-template <int I, bool FAST, bool OPQ, bool FIRST>
+// sum |block constant| |x - level| at the current codebook; with CAPTURE it writes the elements whose first digit lies
+// in the region's window to the list.  sample_mask != 0: only the sampled tiles.
+template <int I, bool FAST, bool OPQ, bool FIRST, bool CAPTURE = false>
 __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restrict__ w, uint64_t n_seg, CodebookArgs cb,
                                                            BinTable bt, int signed_norm, double T2,
                                                            const MaeLevelState* __restrict__ state,
@@ -76,15 +92,18 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
                                                            double* __restrict__ sae_part,
                                                            unsigned long long* __restrict__ cand,
                                                            uint32_t* __restrict__ cand_count, uint32_t cand_cap,
-                                                           const uint32_t* __restrict__ gate, int unweighted) {
+                                                           const uint32_t* __restrict__ gate, int unweighted,
+                                                           uint32_t sample_mask) {
     using C = SegCfg<I>;
+    static_assert(FIRST || !CAPTURE, "only the first pass captures by window");
     // `gate`: this launch only matters if the word it points to is set (the scan that stands in for a list that ran
     // full).  `cand`: append the elements that still count to this wave's stretch of the list.
     if (gate != nullptr && *gate == 0u) return;
     struct Shared {  // one object, so that the table sits at LDS offset 0 (reachable by an immediate offset)
         uint2 tab[BIN_TABLE_ENTRIES];
-        uint4 info[16];    // per region: klo, (lo | hi << 8 | digit mask << 16), then prefix and active flag -
-                           // in the first pass (no prefix yet, every region active) the region's level as binary64
+        uint4 info[16];    // per region: klo, (lo | hi << 8 | digit mask << 16), then prefix and active flag; in
+                           // the first pass (no prefix yet, every region active, its key range has exactly hi bits):
+                           // klo, (lo | window start << 8 | window length << 16), the region's level as binary64
         unsigned long long hist[16 * 256];
         uint32_t cntcol[WAVES_PER_WG * 8 * 64];  // per lane, two 16-bit counters per word: regions 2p and 2p + 1
         char stage[WAVES_PER_WG * C::STAGE_BYTES];
@@ -99,7 +118,7 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
         const uint32_t packed = lo | (hi << 8) | (((1u << (hi - lo)) - 1u) << 16);
         if (FIRST) {
             const unsigned long long lv = (unsigned long long)__double_as_longlong(cb.cb64[tid]);
-            sh.info[tid] = make_uint4(s.klo, packed, (uint32_t)lv, (uint32_t)(lv >> 32));
+            sh.info[tid] = make_uint4(s.klo, lo | (s.win_lo << 8) | (s.win_len << 16), (uint32_t)lv, (uint32_t)(lv >> 32));
         } else {
             sh.info[tid] = make_uint4(s.klo, packed, s.prefix, (hi != 0 && s.total != 0ull && s.pad == 0u) ? 1u : 0u);
         }
@@ -148,11 +167,18 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
     };
     uint4 G[C::NV];
     uint32_t R[C::NR];
-    if (t0 < t1) tile_issue_loads<I>(w, t0 * 64 * C::NV, n_vec, lane, G);
-    for (uint64_t t = t0; t < t1; ++t) {
+    // the wave's tiles in turn - all of them, or those the sampling picks (wave-uniform)
+    auto next_tile = [&](uint64_t t) {
+        while (sample_mask != 0u && t < t1 && !mae_tile_sampled(t, sample_mask)) ++t;
+        return t;
+    };
+    uint64_t t_first = next_tile(t0);
+    if (t_first < t1) tile_issue_loads<I>(w, t_first * 64 * C::NV, n_vec, lane, G);
+    for (uint64_t t = t_first, t_next; t < t1; t = t_next) {
+        t_next = next_tile(t + 1);
         wave_lds_fence();
         tile_stage<I>(stage, lane, G);
-        if (t + 1 < t1) tile_issue_loads<I>(w, (t + 1) * 64 * C::NV, n_vec, lane, G);
+        if (t_next < t1) tile_issue_loads<I>(w, t_next * 64 * C::NV, n_vec, lane, G);
         wave_lds_fence();
         tile_fetch<I>(stage, lane, R);
         const uint64_t seg = t * 64 + lane;
@@ -210,20 +236,40 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
                 for (int e = 0; e < 8; ++e) {
                     const uint32_t sub = order_key(x[e]) - inf[e].x;
                     subk[e] = sub;
-                    const uint32_t lo = inf[e].y & 0xffu, hi = (inf[e].y >> 8) & 0xffu, dmask = inf[e].y >> 16;
-                    counts[e] = FIRST ? (hi != 0u && (sub >> hi) == 0u) : (inf[e].w != 0u && (sub >> hi) == inf[e].z);
-                    bin[e] = code[e] * 256 + ((sub >> lo) & dmask);
+                    if (FIRST) {
+                        // the region's keys span exactly its hi bits, of which the first pass takes the top 8 (all of
+                        // them if there are fewer): sub >> lo is the digit, and every element counts
+                        const uint32_t digit = sub >> (inf[e].y & 31u);
+                        bin[e] = code[e] * 256 + digit;
+                        counts[e] = CAPTURE && (digit - ((inf[e].y >> 8) & 255u)) < (inf[e].y >> 16);
+                    } else {
+                        const uint32_t lo = inf[e].y & 0xffu, hi = (inf[e].y >> 8) & 0xffu, dmask = inf[e].y >> 16;
+                        counts[e] = inf[e].w != 0u && (sub >> hi) == inf[e].z;
+                        bin[e] = code[e] * 256 + ((sub >> lo) & dmask);
+                    }
                     any = any || counts[e];
                 }
                 if (FIRST) {  // every weight lands in some bin: no branches
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        atomicAdd(&sh.hist[bin[e]], counts[e] ? W : 0ull);
+                        atomicAdd(&sh.hist[bin[e]], W);
                         atomicAdd(&cntcol[(code[e] >> 1) * 64 + lane], 1u << ((code[e] & 1u) * 16u));
                         dsum += fabs((double)x[e] - __hiloint2double((int)inf[e].w, (int)inf[e].z));
                         // pin the addition here: left alone, the compiler sinks all of them below the loop and keeps
                         // every x and level alive until then (it spilled 300 registers)
                         asm volatile("" : "+v"(dsum));
+                    }
+                    if (CAPTURE && __builtin_amdgcn_ballot_w64(any) != 0) {  // about one weight in 100 is captured
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const unsigned long long who = __builtin_amdgcn_ballot_w64(counts[e]);
+                            if (who == 0ull) continue;  // wave-uniform
+                            const uint32_t pos = wave_cand + __builtin_amdgcn_mbcnt_hi(
+                                (uint32_t)(who >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)who, 0u));
+                            if (counts[e] && pos < cand_cap)  // entry: key | region << 32 | constant << 36
+                                my_cand[pos] = make_uint2(subk[e], code[e] | m15_shifted);
+                            wave_cand += (uint32_t)__builtin_popcountll(who);
+                        }
                     }
                 } else if (__builtin_amdgcn_ballot_w64(any) != 0) {  // later passes: one weight in 256 still counts
 #pragma unroll
@@ -244,8 +290,9 @@ __global__ __launch_bounds__(256, 2) void mae_pass_kernel(const uint4* __restric
             if (OPQ && k_out != 0u) {
                 const uint4 inf = sh.info[cz];
                 const uint32_t sub = key0 - inf.x;
-                const uint32_t lo = inf.y & 0xffu, hi = (inf.y >> 8) & 0xffu, dmask = inf.y >> 16;
-                const bool counts = FIRST ? (hi != 0u && (sub >> hi) == 0u) : (inf.w != 0u && (sub >> hi) == inf.z);
+                const uint32_t lo = FIRST ? (inf.y & 31u) : (inf.y & 0xffu), hi = (inf.y >> 8) & 0xffu;
+                const uint32_t dmask = FIRST ? 0xffu : (inf.y >> 16);
+                const bool counts = FIRST ? true : (inf.w != 0u && (sub >> hi) == inf.z);
                 if (counts)
                     atomicAdd(&sh.hist[cz * 256 + ((sub >> lo) & dmask)], 0ull - (unsigned long long)k_out * W);
                 if (FIRST) {
@@ -341,6 +388,73 @@ __global__ __launch_bounds__(256) void mae_list_kernel(const unsigned long long*
     }
 }
 
+// After the sampling pass: one wave per region reads the sampled first-digit histogram, finds where the sample's
+// weighted median lies, and sets the window of first digits that the full first pass will capture: the sampled place
+// plus or minus six standard deviations of a sampled quantile (0.5 / sqrt(samples), widened by half for the unequal
+// weights), converted to digits by the share of the region's weight that the median's digit holds, at least half a
+// digit to either side.  Clears the bins.  The search state proper is left alone.
+__global__ __launch_bounds__(1024) void mae_predict_kernel(MaeLevelState* __restrict__ state,
+                                                           unsigned long long* __restrict__ hist,
+                                                           const unsigned long long* __restrict__ cnt_part,
+                                                           uint32_t n_part, uint32_t skip_mask) {
+    const uint32_t lane = threadIdx.x & 63, l = threadIdx.x >> 6;  // wave l = region l
+    unsigned long long b[4], sum = 0ull;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        b[k] = hist[l * 256 + 4 * lane + k];
+        hist[l * 256 + 4 * lane + k] = 0ull;
+        sum += b[k];
+    }
+    unsigned long long incl = sum;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned long long up = (unsigned long long)__shfl_up((long long)incl, d, 64);
+        if (lane >= (uint32_t)d) incl += up;
+    }
+    const unsigned long long total = (unsigned long long)__shfl((long long)incl, 63, 64);
+    const uint32_t n_waves = n_part * WAVES_PER_WG;
+    unsigned long long samples = 0ull;
+    for (uint32_t i = lane; i < n_waves; i += 64) samples += cnt_part[l * n_waves + i];
+#pragma unroll
+    for (int mk = 32; mk >= 1; mk >>= 1) samples += (unsigned long long)__shfl_xor((long long)samples, mk, 64);
+    uint32_t win_lo = 0, win_len = 0;
+    if (total != 0ull && samples != 0ull && ((skip_mask >> l) & 1u) == 0u) {  // wave-uniform
+        const unsigned long long ballot = __builtin_amdgcn_ballot_w64(2ull * incl >= total);
+        const uint32_t L = ballot ? (uint32_t)__builtin_ctzll(ballot) : 63u;
+        unsigned long long c = incl - sum;  // weight below this lane's four bins
+        uint32_t k_sel = 3;
+        unsigned long long below = c, mass = b[3];
+        bool found = false;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (!found && 2ull * (c + b[k]) >= total) {
+                found = true;
+                k_sel = (uint32_t)k;
+                below = c;
+                mass = b[k];
+            }
+            c += b[k];
+        }
+        const uint32_t digit = (uint32_t)__shfl((int)(4 * lane + k_sel), (int)L, 64);
+        const double below_d = (double)(unsigned long long)__shfl((long long)below, (int)L, 64);
+        const double mass_d = (double)(unsigned long long)__shfl((long long)mass, (int)L, 64);
+        const double tot = (double)total;
+        const double place = (double)digit + (mass_d > 0.0 ? (0.5 * tot - below_d) / mass_d : 0.5);
+        const double sigma_q = 0.75 / sqrt((double)samples);
+        double half = mass_d > 0.0 ? 6.0 * sigma_q * tot / mass_d : 256.0;
+        if (half < 0.5) half = 0.5;
+        if (half > 256.0) half = 256.0;
+        const double lo_d = floor(place - half), hi_d = floor(place + half);
+        const int lo_i = lo_d < 0.0 ? 0 : (int)lo_d, hi_i = hi_d > 255.0 ? 255 : (int)hi_d;
+        win_lo = (uint32_t)lo_i;
+        win_len = hi_i >= lo_i ? (uint32_t)(hi_i - lo_i + 1) : 0u;
+    }
+    if (lane == 0) {
+        state[l].win_lo = win_lo;
+        state[l].win_len = win_len;
+    }
+}
+
 // After a pass: one wave per region reads its 256 bins, fixes the next digit and clears the bins.  FIRST also takes
 // the region's total from the bins.  LAST writes the result record (layout of bof4_mae_stats): [0..15] median,
 // [16..31] den, [32..47] cnt (integers), [48] sae, [49] n_used, [50] n_outliers (integers); word 49 is stored last, at
@@ -352,15 +466,14 @@ __global__ __launch_bounds__(1024) void mae_select_kernel(MaeLevelState* __restr
                                                           int first, int last, uint32_t skip_mask,
                                                           const uint32_t* __restrict__ cand_count,
                                                           uint32_t cand_waves, uint32_t cand_cap,
-                                                          uint32_t* __restrict__ cand_full,
+                                                          uint32_t* __restrict__ cand_full, int check_window,
                                                           double* __restrict__ out, int unweighted) {
     const uint32_t lane = threadIdx.x & 63, l = threadIdx.x >> 6;  // wave l = region l
-    if (cand_count != nullptr) {  // after the pass that wrote the list: did every wave's stretch hold its entries?
-        uint32_t over = 0;
-        for (uint32_t i = threadIdx.x; i < cand_waves; i += 1024) over |= cand_count[i] > cand_cap ? 1u : 0u;
-        const int any = __syncthreads_or((int)over);
-        if (threadIdx.x == 0) *cand_full = any ? 1u : 0u;
-    }
+    // after the pass that wrote the list: did every wave's stretch hold its entries?  (and, below, if the list was
+    // captured by windows: does every region's digit lie inside its window?)
+    uint32_t list_bad = 0;
+    if (cand_count != nullptr)
+        for (uint32_t i = threadIdx.x; i < cand_waves; i += 1024) list_bad |= cand_count[i] > cand_cap ? 1u : 0u;
     MaeLevelState s = state[l];
     unsigned long long b[4], sum = 0ull;
 #pragma unroll
@@ -405,8 +518,13 @@ __global__ __launch_bounds__(1024) void mae_select_kernel(MaeLevelState* __restr
         s.prefix = (s.prefix << (s.hi - lo)) | digit;
         s.base = nb;
         s.hi = lo;
+        if (check_window && !((digit - s.win_lo) < s.win_len)) list_bad = 1u;
     }
     if (lane == 0) state[l] = s;
+    if (cand_count != nullptr) {  // uniform
+        const int any = __syncthreads_or((int)list_bad);
+        if (threadIdx.x == 0) *cand_full = any ? 1u : 0u;
+    }
     if (!last) return;
     __shared__ double med[16], den[16];
     __shared__ unsigned long long cnt[17];

@@ -162,3 +162,42 @@ def test_mae_step_skips_pinned_regions(signed, opq):
     assert abs(g["sae"] - o["sae"]) <= RTOL * o["sae"]
     new_g = binding.bof4_codebook_update_mae(g, pin, cb)
     assert np.array_equal(new_g, oracle.codebook_update_mae(o, pin, cb))
+
+
+def _sampled_tiles(n_tiles):
+    """Which wave tiles (4096 weights at block 64) the sampling pass of the MAE step looks at: one in 16, by the
+    multiplicative hash that bof4_mae.h documents."""
+    t = np.arange(n_tiles, dtype=np.uint64)
+    return (((t * np.uint64(0x9E3779B1)) & np.uint64(0xFFFFFFFF)) >> np.uint64(16)) & np.uint64(15) == 0
+
+
+@pytest.mark.parametrize("misled", [False, True])
+def test_mae_one_pass_search_and_its_fallback(misled, capfd, monkeypatch):
+    """From 2^26 weights up the step reads the weights once: a sampling pass over one tile in 16 places a window of
+    first digits per region, the full pass writes the elements inside to the list.  On ordinary data the exact first
+    digit falls inside the window and the list serves all later passes; if the sampled tiles are unlike the rest
+    (here: cubed, which moves every region's median) the windows miss and the later passes scan the weights.  Both
+    ways return the oracle's medians bit for bit; the library's trace line says which way was taken."""
+    n_tiles = 16384 + 37
+    g = torch.Generator().manual_seed(4242)
+    w = torch.randn(n_tiles * 4096, generator=g)
+    if misled:
+        pick = torch.from_numpy(np.repeat(_sampled_tiles(n_tiles), 4096))
+        w[pick] = w[pick] ** 3
+    w = w.to(torch.bfloat16)
+    cb = mae_cb(64, 1)
+    pin = codebooks.PIN_BOF4S
+    st, o = oracle.lloyd_step_mae(inputs.bits(w), 64, cb, 1)
+    assert st == oracle.OK
+    monkeypatch.setenv("BOF4_MAE_TRACE", "1")
+    capfd.readouterr()
+    got = binding.bof4_lloyd_step_mae(w.to(DEV), 64, cb, 1, skip_mask=pin)
+    trace = capfd.readouterr().err
+    assert "sampling 1" in trace and f"list unusable {1 if misled else 0}" in trace, trace
+    wanted = np.array([not ((pin >> l) & 1) for l in range(16)])
+    assert np.array_equal(got["median"][wanted], o["median"][wanted]) and np.all(np.isnan(got["median"][~wanted]))
+    assert np.array_equal(got["den"], o["den"]) and np.array_equal(got["cnt"], o["cnt"])
+    assert abs(got["sae"] - o["sae"]) <= RTOL * o["sae"]
+    monkeypatch.setenv("BOF4_MAE_NO_SAMPLING", "1")
+    two = binding.bof4_lloyd_step_mae(w.to(DEV), 64, cb, 1, skip_mask=pin)
+    assert np.array_equal(two["median"], got["median"], equal_nan=True) and two["sae"] == got["sae"]
