@@ -303,8 +303,13 @@ __device__ __forceinline__ uint32_t opq_pop_lowest(uint32_t (&map)[2]) {
 // Outlier staging of the quantiser: every wave appends the outliers of its (contiguous, ascending) tile range to a
 // region of its own, in ascending flat index, and reports how many it found.  A later pass turns the per-wave counts
 // into offsets and copies the regions into the caller's list.  A wave that finds more than its region holds keeps
-// counting (the count stays exact); the scan pass notices it and the host repeats the call on the general path.  The
-// outliers' original values are read back from a copy of the tile that the wave parks in LDS before it zeroes them.
+// counting (the count stays exact); the scan pass notices it and the host repeats the call on the general path.
+// The outliers' original values (the registers hold zeros in their place by then): the quantiser on its own reads
+// them back from the tile it has staged in LDS anyway.  The one-pass variant has no such copy, and making one (the
+// tile parked on the Lloyd columns, which then have to be cleared again) cost 14 % of the kernel: there every lane
+// writes (lane, element) of its outliers to a short wave-private list in LDS, one lane per entry reads the value
+// again from memory (the line was fetched a moment ago: a cache hit) and keeps it in a register, and the entries are
+// stored - neighbouring lanes to neighbouring places - at the end of the tile, when the value has long arrived.
 //
 // Lloyd sums.  Per-level sums of the current block live in lane-private LDS columns acc[level][lane]
 // (conflict-free).  One 64-bit LDS add per weight carries both the count and the sum of x of its level: the increment
@@ -346,17 +351,9 @@ __device__ __forceinline__ float quad_xor(float v) {
     constexpr int ctrl = C == 1 ? 0xB1 : C == 2 ? 0x4E : 0x1B;  // quad_perm [1,0,3,2] / [2,3,0,1] / [3,2,1,0]
     return __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(v), ctrl, 0xf, 0xf, true));
 }
-// The tile parked in LDS for the outlier values: lane l's k-th 16-byte piece sits at piece slot k ^ swz(l) of the
-// lane's stretch of SEG * 2 bytes, which spreads any 16 neighbouring lanes over all banks.
-template <int I>
-__device__ __forceinline__ uint32_t park_swizzle(uint32_t lane) {
-    constexpr uint32_t PER = 256u / (SegCfg<I>::SEG * 2u);  // lanes per 256 bytes
-    return (lane / PER) & (uint32_t)(SegCfg<I>::NV - 1);
-}
-
 // STAGED (the quantiser on its own, which is bound by memory traffic and not by instruction issue): the wave loads
 // whole tiles with fully coalesced 16-byte loads, parks them in a padded LDS buffer and reads them back transposed;
-// the parked tile also serves the outlier values.
+// the staged tile also serves the outlier values.
 __host__ __device__ constexpr bool pass_staged(bool quant, bool lloyd) { return quant && !lloyd; }
 
 template <int I, bool FAST, bool OPQ, bool QUANT, bool LLOYD>
@@ -368,8 +365,8 @@ __global__ __launch_bounds__(256, pass_waves_per_simd(OPQ, QUANT, LLOYD)) void s
     static_assert(QUANT || LLOYD, "a pass does something");
     constexpr bool STAGED = pass_staged(QUANT, LLOYD);
     constexpr bool EXTRACT = QUANT && OPQ;     // outliers go to the wave's staging region
-    constexpr bool PARK = EXTRACT && !STAGED;  // the wave keeps a copy of the tile in LDS for the outlier values
-    constexpr bool COLS = LLOYD || PARK;       // 8 KB per wave: the Lloyd columns, and / or the parked tile
+    constexpr bool RELOAD = EXTRACT && !STAGED;  // no copy of the tile in LDS: outlier values are read again from memory
+    constexpr bool COLS = LLOYD;                 // 8 KB per wave: the Lloyd columns
     struct Shared {  // one object, so that the table sits at LDS offset 0 (reachable by an immediate offset)
         uint2 tab[BIN_TABLE_ENTRIES];
         unsigned long long cols[COLS ? WAVES_PER_WG * 16 * 64 : 1];
@@ -405,8 +402,6 @@ __global__ __launch_bounds__(256, pass_waves_per_simd(OPQ, QUANT, LLOYD)) void s
     unsigned long long* fold_col[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) fold_col[c] = acc + p4 * 64 + (lane ^ (uint32_t)c);
-    char* park = reinterpret_cast<char*>(acc) + lane * (C::SEG * 2);
-    const uint32_t swz = park_swizzle<I>(lane);
     char* stage = sh.stage + (STAGED ? wave * C::STAGE_BYTES : 0);
     const uint64_t n_vec = n_seg * C::NV;
 
@@ -449,42 +444,46 @@ __global__ __launch_bounds__(256, pass_waves_per_simd(OPQ, QUANT, LLOYD)) void s
         const bool active = seg < n_seg;
         uint32_t k_out = 0, omap[2] = {0, 0};
         if (OPQ) {
-            if (PARK) {  // the original values, before the outliers are zeroed
-#pragma unroll
-                for (int k = 0; k < C::NV; ++k)
-                    *reinterpret_cast<uint4*>(park + (((uint32_t)k ^ swz) << 4)) =
-                        make_uint4(R[4 * k], R[4 * k + 1], R[4 * k + 2], R[4 * k + 3]);
-            }
             opq_zero_outliers<I>(R, opq_theta<I>(R, T2), omap);
             k_out = active ? opq_count(omap) : 0u;
         }
+        // entries whose value is on its way from memory: lane l < pend_n stores entry pend_first + l at the tile's end
+        uint32_t pend_n = 0, pend_first = 0, pend_entry = 0, pend_raw = 0;
         if (EXTRACT) {
             // inclusive prefix of the per-lane counts = order of the flat indices
             const uint32_t incl = wave_inclusive_scan_u32(k_out);
             const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
             wave_lds_fence();
             if (total != 0) {  // wave-uniform
-                uint32_t pos = wcount + incl - k_out;
                 const uint64_t region = gw * (uint64_t)os.region_cap;
                 if (!active) omap[0] = omap[1] = 0;
-                while ((omap[0] | omap[1]) != 0u) {  // lanes run dry at different times
-                    const uint32_t e = opq_pop_lowest(omap);
-                    const uint32_t b =
-                        STAGED ? *reinterpret_cast<const uint16_t*>(stage + lane * C::PITCH + 2 * e)
-                               : *reinterpret_cast<const uint16_t*>(park + ((((e >> 3) ^ swz) << 4) | ((e & 7u) << 1)));
-                    if (pos < os.region_cap) {
-                        os.idx[region + pos] = (int64_t)(seg * C::SEG + e);
-                        os.val[region + pos] = (uint16_t)f32_to_f16_bits(bf16_bits_to_f32(b));
+                if (RELOAD && total <= 64u) {  // wave-uniform: the ordinary case
+                    // (lane, element) of every outlier of the tile, in order, in the wave's tie buffer (free here)
+                    uint32_t slot = incl - k_out;
+                    while ((omap[0] | omap[1]) != 0u) tie_buf[slot++] = (uint16_t)(opq_pop_lowest(omap) | (lane << 6));
+                    wave_lds_fence();
+                    if (lane < total) {
+                        pend_entry = tie_buf[lane];
+                        const uint64_t flat = (t * 64 + (pend_entry >> 6)) * C::SEG + (pend_entry & 63u);
+                        pend_raw = reinterpret_cast<const uint16_t*>(w)[flat];
                     }
-                    ++pos;
+                    pend_n = total;
+                    pend_first = wcount;
+                    wave_lds_fence();  // the buffer is read: the search for the block constants may use it again
+                } else {
+                    uint32_t pos = wcount + incl - k_out;
+                    while ((omap[0] | omap[1]) != 0u) {  // lanes run dry at different times
+                        const uint32_t e = opq_pop_lowest(omap);
+                        const uint32_t b = STAGED ? *reinterpret_cast<const uint16_t*>(stage + lane * C::PITCH + 2 * e)
+                                                  : reinterpret_cast<const uint16_t*>(w)[seg * C::SEG + e];
+                        if (pos < os.region_cap) {
+                            os.idx[region + pos] = (int64_t)(seg * C::SEG + e);
+                            os.val[region + pos] = (uint16_t)f32_to_f16_bits(bf16_bits_to_f32(b));
+                        }
+                        ++pos;
+                    }
                 }
                 wcount += total;
-            }
-            if (LLOYD && PARK) {  // the parked tile lay on the Lloyd columns: they start every tile at zero
-                wave_lds_fence();
-#pragma unroll
-                for (int l = 0; l < 16; ++l) acc[l * 64 + lane] = 0ull;
-                wave_lds_fence();
             }
         }
         uint32_t maxabs, sign;
@@ -567,6 +566,14 @@ __global__ __launch_bounds__(256, pass_waves_per_simd(OPQ, QUANT, LLOYD)) void s
                 store_stream(&dst[q], make_uint4(out[4 * q], out[4 * q + 1], out[4 * q + 2], out[4 * q + 3]));
             if ((lane & (C::LPB - 1)) == 0) scales[seg / C::LPB] = (uint16_t)s16;
         }
+        if (RELOAD && pend_n != 0u) {  // wave-uniform
+            const uint32_t pos = pend_first + lane;
+            if (lane < pend_n && pos < os.region_cap) {
+                const uint64_t at = gw * (uint64_t)os.region_cap + pos;
+                os.idx[at] = (int64_t)((t * 64 + (pend_entry >> 6)) * C::SEG + (pend_entry & 63u));
+                os.val[at] = (uint16_t)f32_to_f16_bits(bf16_bits_to_f32(pend_raw));
+            }
+        }
         if (LLOYD) {
             const double gd = active ? (double)g : 0.0;
             sxx_g = fma(gd, sxx, sxx_g);
@@ -607,8 +614,6 @@ __global__ __launch_bounds__(256, pass_waves_per_simd(OPQ, QUANT, LLOYD)) void s
                 }
             }
             wave_lds_fence();
-        } else if (PARK) {
-            wave_lds_fence();  // the next tile is parked over this one
         }
         if (!STAGED) {
 #pragma unroll

@@ -113,3 +113,17 @@ def test_fused_pass_outliers_piled_up_and_capacity_error():
     assert nout > 300  # far more than the 68 entries of one wave's staging region, all inside two waves
     g = binding.bof4_quantize_lloyd(w.to(DEV), 64, cb, 1, opq_T=T, out_capacity=nout - 1, allow_overflow=True)
     assert g[4] == nout
+
+
+@pytest.mark.parametrize("block", [32, 64, 256])
+def test_fused_pass_tile_with_more_outliers_than_lanes(block):
+    """The one-pass call reads an outlier's value again from memory, one lane per outlier of the tile; a tile of 4096
+    weights (2048 at block 32) with more than 64 outliers takes the loop that handles them one by one instead.  With a
+    capacity large enough for every wave's staging region to hold such a tile, that loop's entries are the result."""
+    w = make_weights(301, 1024, seed=761, outliers=False).clone()
+    w[3 * 4096 + 5:4 * 4096:40] = 25.0      # 103 outliers in one tile (52 per tile at block 32)
+    w[9 * 4096 + 1:10 * 4096:16] = -31.0    # 256 in another (128 per tile at block 32)
+    cb = cb_for(block, 1)
+    T = oracle.opq_threshold(0.95, block)
+    nout = check_fused(w, block, cb, 1, T, cap_extra=1 << 20)
+    assert nout >= 103 + 256
