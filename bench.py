@@ -638,8 +638,9 @@ def main():
         torch.cuda.synchronize()
         t_mae = (time.perf_counter() - t_mae) / 3
         out["mae_step"] = {"call_ms": t_mae * 1e3, "weights_per_s": n / t_mae,
-                           "note": "bof4_lloyd_step_mae (exact weighted medians of the free levels: two passes over the "
-                                   "weights, one over a candidate list), outside the timed step"}
+                           "note": "bof4_lloyd_step_mae (exact weighted medians of the free levels: a sampling pass over one "
+                                   "tile in 16, one full pass over the weights that also writes the candidate "
+                                   "list, the remaining passes over that list), outside the timed step"}
         # the error pass (MSE / MAE of the tensor against its quantised form; not part of the timed step)
         err_rec, _keep4 = binding.pinned_error_stats()
         err_ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
