@@ -48,7 +48,8 @@ typedef struct {
  * largest grid (4096 regions of 4 * ceil(out_capacity / 4096) + 64 entries of 10 bytes: about 40 bytes per entry of
  * out_capacity, i.e. 0.64 bytes per weight at out_capacity = n / 64), or, if larger, the per-tile tables of the
  * fallback path (20 bytes per 2048 weights + 10 bytes per entry); behind it 459,200 bytes of partial sums; for the MAE
- * step n / 4 bytes (its candidate list) + about 0.8 MB.  Pure host function; 0 on invalid arguments. */
+ * step n / 4 bytes (its candidate list; n / 2 bytes below 2^29 weights) + about 0.8 MB.  Pure host function; 0 on
+ * invalid arguments. */
 size_t bof4_workspace_bytes(uint64_t n, uint32_t block, uint64_t out_capacity);
 
 /* OPQ threshold T = F_M^{-1}(q) for Gaussian weights (section 3.3 eq. 9 with F_M = (2G-1)^I of appendix B.1):
@@ -158,14 +159,15 @@ typedef struct {
  * The expectation pass for the MAE criterion (section 3.2 eq. 7-8, appendix B.4).  Normalisation, assignment and OPQ
  * as in bof4_lloyd_step; per region the exact weighted median of the normalised weights (weights: the absolute block
  * maximum as stored in binary16, for absolute and signed normalisation alike) is found by a radix search that reads
- * the weights twice and then a list of the few elements still in question (in the workspace: n / 4 bytes; if the list
- * runs full - a tensor of equal numbers - or outliers must be tracked through the region around zero, the weights are
+ * the weights twice and then a list of the few elements still in question (in the workspace: n / 4 bytes, n / 2
+ * below 2^29 weights; if the list runs full - a tensor of equal numbers - or outliers must be tracked through the region around zero, the weights are
  * read three or four times instead).  From 2^26 weights up (at block 64) the weights are read once, after a look at
  * one tile of 4096 weights in 16 that tells the search where to expect the medians; if those tiles are unlike the rest
  * of the tensor the search notices and reads the weights again as above - the result is the same either way.  Two
  * environment variables help when looking into this: BOF4_MAE_TRACE (set: every call prints to stderr which way it
- * went) and BOF4_MAE_NO_SAMPLING (set: always the two-pass search).  The appendix's closing formula names the element before the weighted median;
- * what is returned is the minimiser that its derivation arrives at.  Weights are added as exact 64-bit integers, which
+ * went; set to 2: also how full the fullest wave's stretch of the list got and every region's window) and
+ * BOF4_MAE_NO_SAMPLING (set: always the two-pass search).  The appendix's closing formula names the element before the
+ * weighted median; what is returned is the minimiser that its derivation arrives at.  Weights are added as exact 64-bit integers, which
  * needs sum over all weights of |block constant| < 2^38 (BOF4_ERR_ARG otherwise).
  *   weight_by_max  nonzero: the paper's criterion (eq. 8).  0: every weight counts one unit - the plain median of the
  *               normalised weights (appendix D, the MAE of the normalised weights, which the paper shows to be the

@@ -19,6 +19,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <vector>
 #include <cstring>
 
 #include "bof4.h"
@@ -244,14 +245,16 @@ static_assert(pass_grid(false, true, false) <= PASS_GRID_MAX && pass_grid(false,
                   SEG_GRID <= PASS_GRID_MAX,
               "workspace sized for fewer workgroups");
 // MAE step: histogram, search state, per-wave counts, per-workgroup floating-point partials, result record.
-// Entries of the candidate list of the MAE step: n / 32 (about five times what a pass leaves), at most 2^27; dealt
-// out evenly to the waves of the pass kernels.
+// Entries of the candidate list of the MAE step, dealt out evenly to the waves of the pass kernels: n / 32 (four
+// times what the windows of the one-pass search let through on a large tensor, five times what a second pass
+// leaves), at most 2^27; below 2^29 weights n / 16, because the windows are wider there (fewer samples to place them:
+// 4 to 5 % of the weights at 2^26) and a wave's share of the list is small enough for its fill to vary.
 // The MAE step samples one tile in 16 to place its windows, from 16384 wave tiles (2^26 weights at block 64) up: below
 // that the second pass over the weights costs less than it would save.
 constexpr uint32_t MAE_SAMPLE_MASK = 15;
 constexpr uint64_t MAE_SAMPLING_MIN_TILES = 16384;
 uint64_t mae_cand_entries(uint64_t n) {
-    const uint64_t e = n / 32;
+    const uint64_t e = n < (1ull << 29) ? n / 16 : n / 32;
     return e < (1ull << 27) ? e : (1ull << 27);
 }
 struct MaeWsLayout {
@@ -1602,6 +1605,19 @@ int bof4_lloyd_step_mae(const void* w_dev, uint64_t n, uint32_t block, const dou
         if (use_list) HIP_TRY(hipMemcpy(&unusable, cand_full, 4, hipMemcpyDeviceToHost));
         std::fprintf(stderr, "bof4_lloyd_step_mae: passes %u, list %d, sampling %d, list unusable %u\n", passes,
                      (int)use_list, (int)sampling, unusable);
+        if (use_list && std::getenv("BOF4_MAE_TRACE")[0] == '2') {  // the fullest stretch of the list, the windows
+            std::vector<uint32_t> counts(cand_waves);
+            HIP_TRY(hipMemcpy(counts.data(), cand_count, (size_t)cand_waves * 4, hipMemcpyDeviceToHost));
+            uint32_t most = 0;
+            for (uint32_t c : counts) most = c > most ? c : most;
+            MaeLevelState st[16];
+            HIP_TRY(hipMemcpy(st, state, sizeof(st), hipMemcpyDeviceToHost));
+            std::fprintf(stderr, "  fullest stretch %u of %u entries;", most, cand_cap);
+            for (int l = 0; l < 16; ++l)
+                std::fprintf(stderr, " [%d: window %u+%u, key %u of %u bits]", l, st[l].win_lo, st[l].win_len,
+                             st[l].prefix, lc.bits[l]);
+            std::fprintf(stderr, "\n");
+        }
     }
     if (out_host->sae != out_host->sae)
         return fail(BOF4_ERR_ARG, "bof4_lloyd_step_mae: block constants too large for exact weighted medians");

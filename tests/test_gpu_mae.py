@@ -201,3 +201,29 @@ def test_mae_one_pass_search_and_its_fallback(misled, capfd, monkeypatch):
     monkeypatch.setenv("BOF4_MAE_NO_SAMPLING", "1")
     two = binding.bof4_lloyd_step_mae(w.to(DEV), 64, cb, 1, skip_mask=pin)
     assert np.array_equal(two["median"], got["median"], equal_nan=True) and two["sae"] == got["sae"]
+
+
+@pytest.mark.parametrize("block,signed,weighted", [(128, 0, True), (32, 1, False)])
+def test_mae_one_pass_search_with_opq(block, signed, weighted, capfd, monkeypatch):
+    """The one-pass search on heavy-tailed weights with the outlier rule on, the pinned levels skipped (with the
+    region around zero wanted the zeroed outliers would run through its search and the step keeps off the list), for
+    the absolute and the signed normalisation, weighted and plain medians: medians, masses and counts as the
+    oracle's, bit for bit, and the trace line says that the list served the later passes."""
+    tile = 64 * min(block, 64)
+    n = (16384 + 21) * tile + 3 * block  # just above the size from which the search samples, ragged tail
+    w = make_weights(1, n, seed=977 + block)
+    T = oracle.opq_threshold(0.95, block)
+    cb = mae_cb(block, signed)
+    pin = codebooks.PIN_BOF4S if signed else codebooks.PIN_BOF4
+    st, o = oracle.lloyd_step_mae(inputs.bits(w), block, cb, signed, opq_T=T, weight_by_max=weighted)
+    assert st == oracle.OK and o["n_outliers"] > 0
+    monkeypatch.setenv("BOF4_MAE_TRACE", "1")
+    capfd.readouterr()
+    got = binding.bof4_lloyd_step_mae(w.to(DEV), block, cb, signed, opq_T=T, weight_by_max=weighted, skip_mask=pin)
+    trace = capfd.readouterr().err
+    assert "sampling 1" in trace and "list unusable 0" in trace, trace
+    wanted = np.array([not ((pin >> l) & 1) for l in range(16)])
+    assert np.array_equal(got["median"][wanted], o["median"][wanted]) and np.all(np.isnan(got["median"][~wanted]))
+    assert np.array_equal(got["den"], o["den"]) and np.array_equal(got["cnt"], o["cnt"])
+    assert got["n_used"] == o["n_used"] and got["n_outliers"] == o["n_outliers"]
+    assert abs(got["sae"] - o["sae"]) <= RTOL * o["sae"]
