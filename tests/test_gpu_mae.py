@@ -203,7 +203,7 @@ def test_mae_one_pass_search_and_its_fallback(misled, capfd, monkeypatch):
     assert np.array_equal(two["median"], got["median"], equal_nan=True) and two["sae"] == got["sae"]
 
 
-@pytest.mark.parametrize("block,signed,weighted", [(128, 0, True), (32, 1, False)])
+@pytest.mark.parametrize("block,signed,weighted", [(128, 0, True), (32, 1, False), (256, 1, True)])
 def test_mae_one_pass_search_with_opq(block, signed, weighted, capfd, monkeypatch):
     """The one-pass search on heavy-tailed weights with the outlier rule on, the pinned levels skipped (with the
     region around zero wanted the zeroed outliers would run through its search and the step keeps off the list), for
