@@ -82,7 +82,11 @@ int bof4_bin_table(const double* cb_host, float* thr33_host, uint32_t* base33_ho
  *               and the call returns as soon as the record has arrived (the stream may still be finishing the
  *               call's last kernel; later work on `stream` is ordered behind it as usual)
  *   ws_dev      workspace of at least bof4_workspace_bytes(n, block, 0) bytes (device); contents undefined after
- * The result is bit-identical from run to run (fixed reduction order).
+ * The result is bit-identical from run to run (fixed reduction order).  Out of contract: a block whose largest
+ * magnitude exceeds binary16's range (65504) - its stored constant is infinite, and the sums are not finite then
+ * (bof4_quantize and bof4_dequantize stay defined there: every weight of such a block normalises to zero).  A
+ * constant below binary16's normal range (2^-14) is stored with the bits binary16 has for it; the weights of such a
+ * block normalise to up to 1.5 in magnitude and are counted as they are.
  */
 int bof4_lloyd_step(const void* w_dev, uint64_t n, uint32_t block, const double* cb_host, int signed_norm,
                     double opq_T, int weight_by_max2, bof4_lloyd_stats* out_host, void* ws_dev, size_t ws_bytes,

@@ -313,10 +313,13 @@ __device__ __forceinline__ uint32_t opq_pop_lowest(uint32_t (&map)[2]) {
 //
 // Lloyd sums.  Per-level sums of the current block live in lane-private LDS columns acc[level][lane]
 // (conflict-free).  One 64-bit LDS add per weight carries both the count and the sum of x of its level: the increment
-// is the bit pattern of the binary64 number 2^-1008 + (x + 1) 2^-1020, i.e. exponent field 15 and mantissa
-// (x + 1) 2^40 rounded to an integer.  Adding up to 256 of these as integers gives 15 K 2^52 + sum (x + 1) 2^40 with
-// the second term below 2^52, so count K and sum separate again exactly.  Once per tile the columns are folded, with
-// the block weights g, into binary64 registers:  A += g sum(x + 1) 2^40,  den15 += g 15 K,  cnt15 += 15 K.
+// is the bit pattern of the binary64 number 2^-1008 + (x + 2) 2^-1020, i.e. exponent field 15 and mantissa
+// (x + 2) 2^40 rounded to an integer.  Adding up to 256 of these as integers gives 15 K 2^52 + sum (x + 2) 2^40 with
+// the second term below 2^52, so count K and sum separate again exactly.  (x + 2, not x + 1: a block constant below
+// binary16's normal range is stored with fewer bits than it has, and the weights of such a block normalise to up to
+// 1.5 in magnitude; the addend must stay positive, or the increment leaves its binade and the count loses a unit.)
+// Once per tile the columns are folded, with the block weights g, into binary64 registers:
+// A += g sum(x + 2) 2^40,  den15 += g 15 K,  cnt15 += 15 K.
 // The fold is shared inside every quad of lanes: lane 4q + p takes levels 4p .. 4p+3 of the four blocks of its quad
 // (the weights g of the other three arrive by quad permutes), so a lane carries 4 and not 16 sets of accumulators -
 // the registers this frees are what lets four waves share a SIMD.  At any step the 64 lanes read 64 different
@@ -330,7 +333,7 @@ struct OutlierStage {
     uint32_t region_cap;
 };
 constexpr double LLOYD_INC_MUL = 0x1p-1020;
-constexpr double LLOYD_INC_ADD = 0x1p-1008 + 0x1p-1020;
+constexpr double LLOYD_INC_ADD = 0x1p-1008 + 0x1p-1019;
 
 // Waves per SIMD a variant of the pass is compiled for (the launch bound holds its registers to 512 / that many).
 __host__ __device__ constexpr int pass_waves_per_simd(bool opq, bool quant, bool lloyd) {
@@ -607,7 +610,7 @@ __global__ __launch_bounds__(256, pass_waves_per_simd(OPQ, QUANT, LLOYD)) void s
                     // 2^52 + sum: the column's mantissa under the exponent of 2^52 (one bit-field insert)
                     uint32_t dhi;
                     asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(dhi) : "v"(0xFFFFFu), "v"(hi), "v"(0x43300000u));
-                    const double D = __hiloint2double((int)dhi, (int)lo) - 0x1p52;  // sum (x+1) 2^40
+                    const double D = __hiloint2double((int)dhi, (int)lo) - 0x1p52;  // sum (x+2) 2^40
                     A[k] = fma(gc, D, A[k]);
                     den15[k] = fma(gc, (double)k15, den15[k]);
                     cnt15[k] += k15;
@@ -717,7 +720,7 @@ __global__ __launch_bounds__(64) void seg_outlier_gather_kernel(OutlierStage os,
 }
 
 // Reduce the per-wave partials in a fixed order and turn them into the statistics of the C ABI:
-//   num = A - den,  sse = sum g x^2 - 2 sum_l c_l num_l + sum_l c_l^2 den_l   (the three sums of the expanded square).
+//   num = A - 2 den,  sse = sum g x^2 - 2 sum_l c_l num_l + sum_l c_l^2 den_l   (the three sums of the expanded square).
 // `out` has the memory layout of bof4_lloyd_stats: [0..15] num, [16..31] den, [32..47] cnt (integers), [48] sse,
 // [49] n_used, [50] n_outliers (integers); it may point into the workspace or at device-visible host memory.
 __global__ __launch_bounds__(1024) void seg_lloyd_final_kernel(const double* __restrict__ partials, uint32_t n_part,
@@ -772,10 +775,10 @@ __global__ __launch_bounds__(1024) void seg_lloyd_final_kernel(const double* __r
         unsigned long long c = (unsigned long long)((double)(unsigned long long)__double_as_longlong(tot[32 + l]) / 15.0);
         if (l == code_of_zero) {  // zeroed outliers were counted as x = 0: take them out again
             den -= koutg;
-            a -= koutg;
+            a -= 2.0 * koutg;
             c -= kout;
         }
-        double num = a - den;
+        double num = a - 2.0 * den;
         out[l] = num;
         out[16 + l] = den;
         out[32 + l] = __longlong_as_double((long long)c);

@@ -357,3 +357,27 @@ def test_calls_in_two_halves_give_the_results_of_the_plain_calls():
     with pytest.raises(binding.Bof4Error) as e:
         flight.finish()
     assert e.value.code == binding.BOF4_ERR_CAPACITY and counter.value == ref_k
+
+
+@pytest.mark.parametrize("block", [32, 64, 256])
+@pytest.mark.parametrize("signed", [0, 1])
+def test_lloyd_sums_of_blocks_whose_constant_binary16_stores_with_fewer_bits(block, signed):
+    """A block maximum below binary16's normal range loses bits when it is stored (1.4375 x 2^-24 becomes 2^-24), so
+    the weights of such a block normalise to more than 1 in magnitude, here to -1.4375 and +1.4375.  They are counted
+    with that x, in the outermost regions: counts as the oracle's, sums to 1e-9, for the Lloyd step alone and in one
+    pass with the quantiser (a sum of x + 1 kept as a nonnegative integer would lose a count here)."""
+    g = torch.Generator().manual_seed(31 + block)
+    n_blocks = 3 * 64 * min(block, 64) // block + 5  # three wave tiles and a ragged tail
+    w = (torch.randn(n_blocks, block, generator=g) * 0.02)
+    tiny = 1.4375 * 2.0 ** -24
+    for b in range(0, n_blocks, 3):  # every third block: tiny, its extreme elements of both signs, the largest first
+        w[b] = torch.randn(block, generator=g) * 0.3 * tiny
+        w[b, 1], w[b, 5], w[b, 7] = tiny, -tiny, -tiny
+    w = w.reshape(-1).to(torch.bfloat16)
+    cb = cb_for(block, signed)
+    st, o = oracle.lloyd_step(inputs.bits(w), block, cb, signed)
+    assert st == oracle.OK and o["cnt"][0] >= 2 * (n_blocks // 3)  # the -1.4375s sit in the lowest region
+    assert_stats_close(binding.bof4_lloyd_step(w.to(DEV), block, cb, signed), o)
+    got = binding.bof4_quantize_lloyd(w.to(DEV), block, cb, signed)
+    assert_stats_close(got[5], o)
+    compare_quantize(w, block, cb, signed, 0.0)

@@ -1,0 +1,80 @@
+"""A seeded sweep over sizes, block sizes, normalisations, outlier thresholds and input structure that the fixed cases
+do not name: every entry point of the hot path against the CPU oracle on the same input, to the bars of the fixed
+tests (codes, constants, outlier lists, decoded weights, counts and medians bit for bit; sums to relative 1e-9)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_06653_amd import binding, codebooks, inputs
+from test_gpu_fused import check_fused
+from test_gpu_mae import assert_mae_close, mae_cb
+from test_gpu_parity import assert_stats_close, cb_for, compare_quantize
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def sweep_case(k):
+    """Case k of the sweep: weights (bf16, flat), block, signed, outlier threshold T, and a word that names it."""
+    rng = np.random.default_rng(77000 + k)
+    block = int(rng.choice([32, 64, 128, 256]))
+    signed = int(rng.integers(0, 2))
+    # sizes around the edges the kernels have: a few blocks, just under / over a wave tile (64 segments of up to 64
+    # weights), several tiles with a ragged tail, more tiles than the grid has waves
+    kind = int(rng.integers(0, 5))
+    seg = min(block, 64)
+    tile_blocks = 64 * seg // block
+    n_blocks = [int(rng.integers(1, 9)), tile_blocks - 1 + int(rng.integers(0, 3)),
+                int(rng.integers(2, 40)) * tile_blocks + int(rng.integers(0, tile_blocks)),
+                4096 * 4 * tile_blocks // 16 + int(rng.integers(0, 3 * tile_blocks)),
+                int(rng.integers(1, 3000))][kind]
+    n = n_blocks * block
+    g = torch.Generator().manual_seed(88000 + k)
+    shape = int(rng.integers(0, 4))
+    if shape == 0:  # Gaussian
+        w = torch.randn(n, generator=g) * 0.02
+    elif shape == 1:  # heavy tails
+        w = torch.randn(n, generator=g) * 0.02 / torch.sqrt(torch.randn(n, 4, generator=g).square().mean(dim=1))
+    elif shape == 2:  # block scales spread over many octaves, some blocks all zero
+        s = torch.exp2(torch.randint(-30, 12, (n_blocks, 1), generator=g).float())
+        s[torch.rand(n_blocks, 1, generator=g) < 0.05] = 0.0
+        w = (torch.randn(n_blocks, block, generator=g) * s).reshape(-1)
+    else:  # few distinct values: ties in the block maximum, weights on level mid-points
+        w = torch.randint(-8, 9, (n,), generator=g).float() * 0.0625
+    if rng.random() < 0.5 and n >= 64:  # a pile of large values in one stretch, others spread out
+        a = int(rng.integers(0, n - 32))
+        w[a:a + int(rng.integers(1, 33))] *= 50.0
+        w[torch.randint(0, n, (max(1, n // 500),), generator=g)] *= 30.0
+    T = 0.0 if rng.random() < 0.35 else float(oracle.opq_threshold(float(rng.choice([0.9, 0.95, 0.99])), block))
+    return w.to(torch.bfloat16), block, signed, T, f"block {block} signed {signed} n {n} kind {kind} shape {shape} T {T:.3f}"
+
+
+@pytest.mark.parametrize("k", range(80))
+def test_sweep_quantize_dequantize_lloyd_fused(k):
+    w, block, signed, T, name = sweep_case(k)
+    print(name, flush=True)
+    cb = cb_for(block, signed)
+    compare_quantize(w, block, cb, signed, T)
+    if float(w.float().abs().max()) > 65504.0:
+        return  # some block constant is infinite in binary16: the sums are out of contract (not finite either way)
+    st, o = oracle.lloyd_step(inputs.bits(w), block, cb, signed, opq_T=T)
+    assert st == oracle.OK
+    assert_stats_close(binding.bof4_lloyd_step(w.to(DEV), block, cb, signed, opq_T=T), o)
+    check_fused(w, block, cb, signed, T, cap_extra=int(k % 5))
+
+
+@pytest.mark.parametrize("k", range(80, 120))
+def test_sweep_mae_step(k):
+    w, block, signed, T, name = sweep_case(k)
+    print(name, flush=True)
+    cb = mae_cb(block, signed)
+    weighted = bool(k % 2)
+    if float(w.float().abs().max()) > 65504.0:
+        w = w.float().clamp(-6.0e4, 6.0e4).to(torch.bfloat16)  # keep the block constants finite in binary16
+    st, o = oracle.lloyd_step_mae(inputs.bits(w), block, cb, signed, opq_T=T, weight_by_max=weighted)
+    if st != oracle.OK:  # block constants too large for exact 64-bit sums: the library must refuse as well
+        with pytest.raises(binding.Bof4Error):
+            binding.bof4_lloyd_step_mae(w.to(DEV), block, cb, signed, opq_T=T, weight_by_max=weighted)
+        return
+    assert_mae_close(binding.bof4_lloyd_step_mae(w.to(DEV), block, cb, signed, opq_T=T, weight_by_max=weighted), o)
