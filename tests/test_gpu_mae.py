@@ -227,3 +227,28 @@ def test_mae_one_pass_search_with_opq(block, signed, weighted, capfd, monkeypatc
     assert np.array_equal(got["den"], o["den"]) and np.array_equal(got["cnt"], o["cnt"])
     assert got["n_used"] == o["n_used"] and got["n_outliers"] == o["n_outliers"]
     assert abs(got["sae"] - o["sae"]) <= RTOL * o["sae"]
+
+
+@pytest.mark.parametrize("block,signed", [(32, 1), (64, 0), (256, 1)])
+def test_mae_step_on_blocks_whose_constant_binary16_stores_with_fewer_bits(block, signed):
+    """A block maximum below binary16's normal range loses bits when stored (1.4375 x 2^-24 becomes 2^-24): the
+    block's extreme weights normalise to -1.4375 and +1.4375, outside [-1, 1], and belong to the outermost regions
+    with that value - also as medians, when such elements make up most of a region."""
+    g = torch.Generator().manual_seed(57 + block)
+    n_blocks = 3 * 64 * min(block, 64) // block + 5
+    tiny = 1.4375 * 2.0 ** -24
+    w = torch.randn(n_blocks, block, generator=g) * 0.05 * tiny  # tiny blocks: only the planted extremes lie far out
+    w[:, 1], w[:, 5], w[:, 7] = tiny, -tiny, -tiny
+    w[::4] = torch.randn((n_blocks + 3) // 4, block, generator=g) * 0.02  # and some ordinary blocks
+    w = w.reshape(-1).to(torch.bfloat16)
+    cb = mae_cb(block, signed)
+    for weighted in (True, False):
+        st, o = oracle.lloyd_step_mae(inputs.bits(w), block, cb, signed, weight_by_max=weighted)
+        assert st == oracle.OK
+        if not weighted:
+            assert o["median"][0] == -1.4375  # most elements of the lowest region are the tiny blocks' minima
+        assert_mae_close(binding.bof4_lloyd_step_mae(w.to(DEV), block, cb, signed, weight_by_max=weighted), o)
+    st, e = oracle.quant_error(inputs.bits(w), block, cb, signed, 0.0)
+    ge = binding.bof4_quant_error(w.to(DEV), block, cb, signed)
+    assert ge["n"] == e["n"] and ge["max_abs"] == e["max_abs"] and abs(ge["sse"] - e["sse"]) <= RTOL * e["sse"]
+    assert abs(ge["sae"] - e["sae"]) <= RTOL * e["sae"]

@@ -7,12 +7,35 @@ import torch
 
 import oracle
 from paper_2505_06653_amd import binding, codebooks, inputs
+import test_gpu_gemm
+import test_gpu_gemv
+from test_gpu_error import assert_error_close
 from test_gpu_fused import check_fused
 from test_gpu_mae import assert_mae_close, mae_cb
 from test_gpu_parity import assert_stats_close, cb_for, compare_quantize
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
+
+
+def structured_weights(n_blocks, block, shape, rng, g):
+    """n_blocks * block float weights of one of four structures (see sweep_case)."""
+    n = n_blocks * block
+    if shape == 0:  # Gaussian
+        w = torch.randn(n, generator=g) * 0.02
+    elif shape == 1:  # heavy tails
+        w = torch.randn(n, generator=g) * 0.02 / torch.sqrt(torch.randn(n, 4, generator=g).square().mean(dim=1))
+    elif shape == 2:  # block scales spread over many octaves, some blocks all zero
+        s = torch.exp2(torch.randint(-30, 12, (n_blocks, 1), generator=g).float())
+        s[torch.rand(n_blocks, 1, generator=g) < 0.05] = 0.0
+        w = (torch.randn(n_blocks, block, generator=g) * s).reshape(-1)
+    else:  # few distinct values: ties in the block maximum, weights on level mid-points
+        w = torch.randint(-8, 9, (n,), generator=g).float() * 0.0625
+    if rng.random() < 0.5 and n >= 64:  # a pile of large values in one stretch, others spread out
+        a = int(rng.integers(0, n - 32))
+        w[a:a + int(rng.integers(1, 33))] *= 50.0
+        w[torch.randint(0, n, (max(1, n // 500),), generator=g)] *= 30.0
+    return w
 
 
 def sweep_case(k):
@@ -32,20 +55,7 @@ def sweep_case(k):
     n = n_blocks * block
     g = torch.Generator().manual_seed(88000 + k)
     shape = int(rng.integers(0, 4))
-    if shape == 0:  # Gaussian
-        w = torch.randn(n, generator=g) * 0.02
-    elif shape == 1:  # heavy tails
-        w = torch.randn(n, generator=g) * 0.02 / torch.sqrt(torch.randn(n, 4, generator=g).square().mean(dim=1))
-    elif shape == 2:  # block scales spread over many octaves, some blocks all zero
-        s = torch.exp2(torch.randint(-30, 12, (n_blocks, 1), generator=g).float())
-        s[torch.rand(n_blocks, 1, generator=g) < 0.05] = 0.0
-        w = (torch.randn(n_blocks, block, generator=g) * s).reshape(-1)
-    else:  # few distinct values: ties in the block maximum, weights on level mid-points
-        w = torch.randint(-8, 9, (n,), generator=g).float() * 0.0625
-    if rng.random() < 0.5 and n >= 64:  # a pile of large values in one stretch, others spread out
-        a = int(rng.integers(0, n - 32))
-        w[a:a + int(rng.integers(1, 33))] *= 50.0
-        w[torch.randint(0, n, (max(1, n // 500),), generator=g)] *= 30.0
+    w = structured_weights(n_blocks, block, shape, rng, g)
     T = 0.0 if rng.random() < 0.35 else float(oracle.opq_threshold(float(rng.choice([0.9, 0.95, 0.99])), block))
     return w.to(torch.bfloat16), block, signed, T, f"block {block} signed {signed} n {n} kind {kind} shape {shape} T {T:.3f}"
 
@@ -78,3 +88,40 @@ def test_sweep_mae_step(k):
             binding.bof4_lloyd_step_mae(w.to(DEV), block, cb, signed, opq_T=T, weight_by_max=weighted)
         return
     assert_mae_close(binding.bof4_lloyd_step_mae(w.to(DEV), block, cb, signed, opq_T=T, weight_by_max=weighted), o)
+
+
+@pytest.mark.parametrize("k", range(120, 150))
+def test_sweep_error_pass(k):
+    w, block, signed, T, name = sweep_case(k)
+    print(name, flush=True)
+    if float(w.float().abs().max()) > 65504.0:
+        w = w.float().clamp(-6.0e4, 6.0e4).to(torch.bfloat16)  # keep the block constants finite in binary16
+    cb = cb_for(block, signed)
+    st, o = oracle.quant_error(inputs.bits(w), block, cb, signed, T)
+    assert st == oracle.OK
+    assert_error_close(binding.bof4_quant_error(w.to(DEV), block, cb, signed, opq_T=T), o)
+
+
+@pytest.mark.parametrize("k", range(150, 180))
+def test_sweep_decoder_inside_the_matrix_products(k):
+    """bof4_gemv and bof4_gemm on matrices of the sweep's structures (codes, constants and list from the oracle's
+    quantiser), random shapes and token counts, to the error bounds of their own test files."""
+    rng = np.random.default_rng(99000 + k)
+    block = int(rng.choice([32, 64, 128, 256]))
+    signed = int(rng.integers(0, 2))
+    cols = block * int(rng.integers(1, max(2, min(32768 // block, 8192 // block) + 1)))
+    rows = int(rng.integers(1, 1 + max(1, min(300, 600000 // cols))))
+    shape = int(rng.integers(0, 4))
+    g = torch.Generator().manual_seed(99500 + k)
+    w = structured_weights(rows * cols // block, block, shape, rng, g).clamp(-6.0e4, 6.0e4).to(torch.bfloat16)
+    T = 0.0 if rng.random() < 0.4 else float(oracle.opq_threshold(0.95, block))
+    print(f"block {block} signed {signed} rows {rows} cols {cols} shape {shape} T {T:.3f}", flush=True)
+    cb = cb_for(block, signed)
+    st, codes, scales, oi, ov, n_out = oracle.quantize(inputs.bits(w), block, cb, signed, opq_T=T)
+    assert st == oracle.OK
+    lst = (oi, ov) if n_out > 0 else (None, None)
+    xg = torch.Generator().manual_seed(99900 + k)
+    x1 = torch.randn((int(rng.integers(1, 6)), cols), generator=xg).to(torch.bfloat16)
+    test_gpu_gemv.check(cb, codes, scales, lst[0], lst[1], rows, cols, block, x1)
+    x2 = torch.randn((int(rng.choice([1, 31, 32, 33, 64, 100, 128, 129, 200])), cols), generator=xg).to(torch.bfloat16)
+    test_gpu_gemm.check(cb, codes, scales, lst[0], lst[1], rows, cols, block, x2)
