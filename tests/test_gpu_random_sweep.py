@@ -125,3 +125,40 @@ def test_sweep_decoder_inside_the_matrix_products(k):
     test_gpu_gemv.check(cb, codes, scales, lst[0], lst[1], rows, cols, block, x1)
     x2 = torch.randn((int(rng.choice([1, 31, 32, 33, 64, 100, 128, 129, 200])), cols), generator=xg).to(torch.bfloat16)
     test_gpu_gemm.check(cb, codes, scales, lst[0], lst[1], rows, cols, block, x2)
+
+
+def random_codebook(rng):
+    """16 ascending levels that are not the paper's: anywhere in [-1.2, 1.2], with or without a zero, sometimes with
+    two levels closer together than a bin of the kernels' search table is wide (that switches them to the general
+    search), sometimes with the outermost levels at -1 and 1."""
+    lv = np.sort(rng.uniform(-1.2, 1.2, 16))
+    if rng.random() < 0.5:
+        lv[int(np.argmin(np.abs(lv)))] = 0.0
+    if rng.random() < 0.5:
+        lv[0], lv[15] = -1.0, 1.0
+    if rng.random() < 0.4:
+        j = int(rng.integers(1, 14))
+        lv[j + 1] = lv[j] + rng.uniform(1e-4, 4e-3)
+    lv = np.sort(lv)
+    for j in range(1, 16):  # strictly ascending
+        if lv[j] <= lv[j - 1]:
+            lv[j] = np.nextafter(lv[j - 1], 2.0)
+    return lv.astype(np.float64)
+
+
+@pytest.mark.parametrize("k", range(180, 230))
+def test_sweep_other_codebooks(k):
+    w, block, signed, T, name = sweep_case(k)
+    if float(w.float().abs().max()) > 65504.0:
+        w = w.float().clamp(-6.0e4, 6.0e4).to(torch.bfloat16)  # keep the block constants finite in binary16
+    cb = random_codebook(np.random.default_rng(55000 + k))
+    print(name, " ".join(f"{v:.5f}" for v in cb), flush=True)
+    wb = inputs.bits(w)
+    compare_quantize(w, block, cb, signed, T)
+    check_fused(w, block, cb, signed, T, w2=bool(k % 2))
+    st, o = oracle.lloyd_step_mae(wb, block, cb, signed, opq_T=T)
+    assert st == oracle.OK
+    assert_mae_close(binding.bof4_lloyd_step_mae(w.to(DEV), block, cb, signed, opq_T=T), o)
+    st, e = oracle.quant_error(wb, block, cb, signed, T)
+    assert st == oracle.OK
+    assert_error_close(binding.bof4_quant_error(w.to(DEV), block, cb, signed, opq_T=T), e)
