@@ -165,6 +165,29 @@ def test_argmax_tie_takes_lowest_index_and_zero_block():
     assert deq[5] == mone
 
 
+def test_block_constant_below_binary16s_normal_range_is_stored_with_the_bits_binary16_has():
+    """A hand-made block: largest magnitude 1.4375 x 2^-24 (a bfloat16 number).  binary16 has one significant bit at
+    2^-24, so the constant is stored as 2^-24 (pattern 0x0001); dividing by the stored constant puts the extreme
+    weights at +-1.4375, outside [-1, 1], where the outermost levels are nearest; the decoder returns level x 2^-24.
+    In the Lloyd sums such a weight counts with its x: numerator g x, g = (2^-24)^2, by hand below."""
+    q = 2.0 ** -24
+    vals = np.zeros(64, dtype=np.float32)
+    vals[3], vals[10], vals[20] = 1.4375 * q, -1.4375 * q, 0.5 * q
+    blk = bf16_bits(vals)
+    assert np.array_equal(bf16_val(blk), vals)  # all three are bfloat16 numbers
+    st, codes, scales, _, _, _ = oracle.quantize(blk, 64, CB_S64, 1)
+    assert st == oracle.OK and scales[0] == 0x0001
+    c = unpack(codes, 64)
+    assert c[3] == 15 and c[10] == 0 and c[20] == int(np.argmin(np.abs(CB_S64 - 0.5)))
+    st, deq = oracle.dequantize(codes, scales, 64, 64, CB_S64)
+    assert bf16_val(deq)[3] == np.float32(q) and bf16_val(deq)[10] == bf16_val(bf16_bits(np.float32(CB_S64[0] * q)))
+    st, o = oracle.lloyd_step(blk, 64, CB_S64, 1)
+    assert st == oracle.OK and o["cnt"][0] == 1 and o["cnt"][15] == 1 and o["n_used"] == 64
+    assert o["num"][0] == -1.4375 * q * q and o["num"][15] == 1.4375 * q * q and o["den"][0] == q * q
+    st, m = oracle.lloyd_step_mae(blk, 64, codebooks.array(codebooks.BOF4S_MAE_64), 1)
+    assert st == oracle.OK and m["median"][0] == -1.4375 and m["median"][15] == 1.4375
+
+
 def test_pack_layout_and_dequantize_definition():
     rng = np.random.default_rng(5)
     n, block = 256, 32
