@@ -14,8 +14,13 @@ from test_gpu_fused import check_fused
 from test_gpu_mae import assert_mae_close, mae_cb
 from test_gpu_parity import assert_stats_close, cb_for, compare_quantize
 
+import os
+
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
+# BOF4_SWEEP_SHIFT=<integer> in the environment moves every case of the sweep to other seeds (for a longer hunt than
+# the committed cases; the default run is the committed one).
+SHIFT = 1000003 * int(os.environ.get("BOF4_SWEEP_SHIFT", "0"))
 
 
 def structured_weights(n_blocks, block, shape, rng, g):
@@ -40,7 +45,7 @@ def structured_weights(n_blocks, block, shape, rng, g):
 
 def sweep_case(k):
     """Case k of the sweep: weights (bf16, flat), block, signed, outlier threshold T, and a word that names it."""
-    rng = np.random.default_rng(77000 + k)
+    rng = np.random.default_rng(77000 + k + SHIFT)
     block = int(rng.choice([32, 64, 128, 256]))
     signed = int(rng.integers(0, 2))
     # sizes around the edges the kernels have: a few blocks, just under / over a wave tile (64 segments of up to 64
@@ -53,7 +58,7 @@ def sweep_case(k):
                 4096 * 4 * tile_blocks // 16 + int(rng.integers(0, 3 * tile_blocks)),
                 int(rng.integers(1, 3000))][kind]
     n = n_blocks * block
-    g = torch.Generator().manual_seed(88000 + k)
+    g = torch.Generator().manual_seed(88000 + k + SHIFT)
     shape = int(rng.integers(0, 4))
     w = structured_weights(n_blocks, block, shape, rng, g)
     T = 0.0 if rng.random() < 0.35 else float(oracle.opq_threshold(float(rng.choice([0.9, 0.95, 0.99])), block))
@@ -106,13 +111,13 @@ def test_sweep_error_pass(k):
 def test_sweep_decoder_inside_the_matrix_products(k):
     """bof4_gemv and bof4_gemm on matrices of the sweep's structures (codes, constants and list from the oracle's
     quantiser), random shapes and token counts, to the error bounds of their own test files."""
-    rng = np.random.default_rng(99000 + k)
+    rng = np.random.default_rng(99000 + k + SHIFT)
     block = int(rng.choice([32, 64, 128, 256]))
     signed = int(rng.integers(0, 2))
     cols = block * int(rng.integers(1, max(2, min(32768 // block, 8192 // block) + 1)))
     rows = int(rng.integers(1, 1 + max(1, min(300, 600000 // cols))))
     shape = int(rng.integers(0, 4))
-    g = torch.Generator().manual_seed(99500 + k)
+    g = torch.Generator().manual_seed(99500 + k + SHIFT)
     w = structured_weights(rows * cols // block, block, shape, rng, g).clamp(-6.0e4, 6.0e4).to(torch.bfloat16)
     T = 0.0 if rng.random() < 0.4 else float(oracle.opq_threshold(0.95, block))
     print(f"block {block} signed {signed} rows {rows} cols {cols} shape {shape} T {T:.3f}", flush=True)
@@ -120,7 +125,7 @@ def test_sweep_decoder_inside_the_matrix_products(k):
     st, codes, scales, oi, ov, n_out = oracle.quantize(inputs.bits(w), block, cb, signed, opq_T=T)
     assert st == oracle.OK
     lst = (oi, ov) if n_out > 0 else (None, None)
-    xg = torch.Generator().manual_seed(99900 + k)
+    xg = torch.Generator().manual_seed(99900 + k + SHIFT)
     x1 = torch.randn((int(rng.integers(1, 6)), cols), generator=xg).to(torch.bfloat16)
     test_gpu_gemv.check(cb, codes, scales, lst[0], lst[1], rows, cols, block, x1)
     x2 = torch.randn((int(rng.choice([1, 31, 32, 33, 64, 100, 128, 129, 200])), cols), generator=xg).to(torch.bfloat16)
@@ -151,7 +156,7 @@ def test_sweep_other_codebooks(k):
     w, block, signed, T, name = sweep_case(k)
     if float(w.float().abs().max()) > 65504.0:
         w = w.float().clamp(-6.0e4, 6.0e4).to(torch.bfloat16)  # keep the block constants finite in binary16
-    cb = random_codebook(np.random.default_rng(55000 + k))
+    cb = random_codebook(np.random.default_rng(55000 + k + SHIFT))
     print(name, " ".join(f"{v:.5f}" for v in cb), flush=True)
     wb = inputs.bits(w)
     compare_quantize(w, block, cb, signed, T)
