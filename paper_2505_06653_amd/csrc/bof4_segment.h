@@ -779,6 +779,9 @@ __global__ __launch_bounds__(1024) void seg_lloyd_final_kernel(const double* __r
             c -= kout;
         }
         double num = a - 2.0 * den;
+        // a region left empty once the outliers are taken out has no mass: the two subtractions above leave rounding
+        // residue there (the sums were added in another order than the amounts taken out), the exact count says so
+        if (c == 0ull) den = num = 0.0;
         out[l] = num;
         out[16 + l] = den;
         out[32 + l] = __longlong_as_double((long long)c);

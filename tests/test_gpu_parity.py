@@ -381,3 +381,28 @@ def test_lloyd_sums_of_blocks_whose_constant_binary16_stores_with_fewer_bits(blo
     got = binding.bof4_quantize_lloyd(w.to(DEV), block, cb, signed)
     assert_stats_close(got[5], o)
     compare_quantize(w, block, cb, signed, 0.0)
+
+
+@pytest.mark.parametrize("signed", [0, 1])
+def test_lloyd_sums_of_a_zero_region_that_holds_only_outliers(signed):
+    """One block in which no weight lies near zero; its one outlier is zeroed, runs through the sums as x = 0 and is
+    taken out again.  The region of the zero level is then empty:
+    count 0 and mass exactly 0 (not the rounding residue of adding and subtracting the same amount in two orders),
+    so that an update leaves its level alone."""
+    w = torch.full((64,), 0.02)
+    w[1::2] = -0.02
+    w[::7] *= 0.7
+    w[9] = 3.0  # the outlier
+    w = w.to(torch.bfloat16)
+    cb = cb_for(64, signed)
+    T = oracle.opq_threshold(0.95, 64)
+    st, o = oracle.lloyd_step(inputs.bits(w), 64, cb, signed, opq_T=T)
+    assert st == oracle.OK and o["n_outliers"] == 1 and o["cnt"][7] == 0 and o["den"][7] == 0.0
+    g = binding.bof4_lloyd_step(w.to(DEV), 64, cb, signed, opq_T=T)
+    assert g["den"][7] == 0.0 and g["num"][7] == 0.0
+    assert_stats_close(g, o)
+    got = binding.bof4_quantize_lloyd(w.to(DEV), 64, cb, signed, opq_T=T, out_capacity=8)
+    assert got[5]["den"][7] == 0.0 and got[5]["num"][7] == 0.0
+    assert_stats_close(got[5], o)
+    new_g, new_o = binding.bof4_codebook_update(g, 0, cb), oracle.codebook_update(o, 0, cb)
+    assert new_g[7] == cb[7] and np.allclose(new_g, new_o, rtol=RTOL, atol=0)
