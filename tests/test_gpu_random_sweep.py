@@ -73,10 +73,11 @@ def test_sweep_quantize_dequantize_lloyd_fused(k):
     compare_quantize(w, block, cb, signed, T)
     if float(w.float().abs().max()) > 65504.0:
         return  # some block constant is infinite in binary16: the sums are out of contract (not finite either way)
-    st, o = oracle.lloyd_step(inputs.bits(w), block, cb, signed, opq_T=T)
+    w2 = k % 3 != 0  # every third case: the sums of the normalised error (appendix D) instead of eq. 6's
+    st, o = oracle.lloyd_step(inputs.bits(w), block, cb, signed, opq_T=T, weight_by_max2=w2)
     assert st == oracle.OK
-    assert_stats_close(binding.bof4_lloyd_step(w.to(DEV), block, cb, signed, opq_T=T), o)
-    check_fused(w, block, cb, signed, T, cap_extra=int(k % 5))
+    assert_stats_close(binding.bof4_lloyd_step(w.to(DEV), block, cb, signed, opq_T=T, weight_by_max2=w2), o)
+    check_fused(w, block, cb, signed, T, w2=w2, cap_extra=int(k % 5))
 
 
 @pytest.mark.parametrize("k", range(80, 120))
@@ -93,6 +94,12 @@ def test_sweep_mae_step(k):
             binding.bof4_lloyd_step_mae(w.to(DEV), block, cb, signed, opq_T=T, weight_by_max=weighted)
         return
     assert_mae_close(binding.bof4_lloyd_step_mae(w.to(DEV), block, cb, signed, opq_T=T, weight_by_max=weighted), o)
+    skip = int(np.random.default_rng(66000 + k + SHIFT).integers(1, 1 << 16))  # medians of some regions not wanted
+    got = binding.bof4_lloyd_step_mae(w.to(DEV), block, cb, signed, opq_T=T, weight_by_max=weighted, skip_mask=skip)
+    wanted = np.array([not ((skip >> l) & 1) for l in range(16)])
+    assert np.array_equal(got["median"][wanted], o["median"][wanted], equal_nan=True)
+    assert np.all(np.isnan(got["median"][~wanted]))
+    assert np.array_equal(got["den"], o["den"]) and np.array_equal(got["cnt"], o["cnt"])
 
 
 @pytest.mark.parametrize("k", range(120, 150))
