@@ -174,3 +174,27 @@ def test_sweep_other_codebooks(k):
     st, e = oracle.quant_error(wb, block, cb, signed, T)
     assert st == oracle.OK
     assert_error_close(binding.bof4_quant_error(w.to(DEV), block, cb, signed, opq_T=T), e)
+
+
+@pytest.mark.parametrize("shape,signed,T_q", [(2, 1, 0.0), (3, 0, 0.0), (3, 1, 0.95), (1, 0, 0.9)])
+def test_mae_one_pass_search_on_structured_weights(shape, signed, T_q):
+    """The sampled one-pass search of the MAE step (from 2^26 weights) on inputs whose keys do not spread like a
+    Gaussian's: block scales over 42 octaves (most blocks' constants below or near binary16's normal range), 17
+    distinct values (a region's elements share a handful of keys, so a window takes in all of them and the list runs
+    full: the step must fall back to scanning), heavy tails.  Whichever way it goes, the medians are the oracle's."""
+    block = 64
+    n_blocks = (16384 + 9) * 64 + 3
+    rng = np.random.default_rng(4711 + shape)
+    w = structured_weights(n_blocks, block, shape, rng, torch.Generator().manual_seed(4712 + shape))
+    w = w.clamp(-6.0e4, 6.0e4).to(torch.bfloat16)
+    T = float(oracle.opq_threshold(T_q, block)) if T_q else 0.0
+    cb = mae_cb(block, signed)
+    pin = codebooks.PIN_BOF4S if signed else codebooks.PIN_BOF4
+    st, o = oracle.lloyd_step_mae(inputs.bits(w), block, cb, signed, opq_T=T)
+    assert st == oracle.OK
+    got = binding.bof4_lloyd_step_mae(w.to(DEV), block, cb, signed, opq_T=T, skip_mask=pin)
+    wanted = np.array([not ((pin >> l) & 1) for l in range(16)])
+    assert np.array_equal(got["median"][wanted], o["median"][wanted], equal_nan=True)
+    assert np.array_equal(got["den"], o["den"]) and np.array_equal(got["cnt"], o["cnt"])
+    assert got["n_used"] == o["n_used"] and got["n_outliers"] == o["n_outliers"]
+    assert abs(got["sae"] - o["sae"]) <= 1e-9 * o["sae"]
