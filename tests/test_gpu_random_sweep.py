@@ -198,3 +198,31 @@ def test_mae_one_pass_search_on_structured_weights(shape, signed, T_q):
     assert np.array_equal(got["den"], o["den"]) and np.array_equal(got["cnt"], o["cnt"])
     assert got["n_used"] == o["n_used"] and got["n_outliers"] == o["n_outliers"]
     assert abs(got["sae"] - o["sae"]) <= 1e-9 * o["sae"]
+
+
+@pytest.mark.parametrize("k", range(230, 254))
+def test_sweep_theory_centroids(k):
+    """The general centroid of section 3.2 eq. 5 on the GPU for weight distributions that are mixtures of zero-mean
+    Gaussians of random widths (even densities, as the recipe requires), random grids, block sizes, both
+    normalisations and codebooks around the paper's: every level as the oracle's evaluation of the same recipe."""
+    from scipy.special import ndtr
+    from oracle import theory_general
+    rng = np.random.default_rng(31000 + k + SHIFT)
+    sig = rng.uniform(0.3, 3.0, int(rng.integers(1, 4)))
+    wt = rng.dirichlet(np.ones(sig.size))
+    pdf_f = lambda u: sum(a * np.exp(-0.5 * (u / s) ** 2) / (s * np.sqrt(2.0 * np.pi)) for a, s in zip(wt, sig))
+    cdf_f = lambda u: sum(a * ndtr(u / s) for a, s in zip(wt, sig))
+    u_max = float(rng.uniform(6.0, 14.0) * sig.max())
+    n_grid = 2 * int(rng.integers(200, 40000)) + 1
+    pdf, cdf = theory_general.tables(pdf_f, cdf_f, u_max, n_grid)
+    block = int(rng.choice([32, 64, 128, 256]))
+    signed = int(rng.integers(0, 2))
+    pin = codebooks.PIN_BOF4S if signed else codebooks.PIN_BOF4
+    cb = (codebooks.array(codebooks.BOF4S_MSE[block]) if signed else codebooks.array(codebooks.BOF4_MSE_64)).copy()
+    free = np.array([not ((pin >> l) & 1) for l in range(16)])
+    cb[free] = np.sort(cb[free] + rng.uniform(-0.02, 0.02, int(free.sum())))  # stays ascending between the pins
+    assert np.all(np.diff(cb) > 0)
+    print(f"block {block} signed {signed} grid {n_grid} u_max {u_max:.2f} widths {sig}", flush=True)
+    want = theory_general.centroid_update(cb, block, pin, signed, pdf, cdf, u_max)
+    got = binding.bof4_theory_centroids(pdf, cdf, u_max, block, cb, pin, signed)
+    assert np.all(np.abs(got - want) <= 1e-10 * np.maximum(np.abs(want), 1e-3))
