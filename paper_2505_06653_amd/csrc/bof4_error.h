@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256, 2) void seg_error_kernel(const uint4* __restri
     const uint64_t t0 = n_tiles * gw / n_waves, t1 = n_tiles * (gw + 1) / n_waves;
 
     double sse = 0.0, sae = 0.0;
-    float mx = 0.0f;
+    double mx = 0.0;
     uint32_t kout = 0;
     uint4 G[C::NV];
     uint32_t R[C::NR];
@@ -111,13 +111,14 @@ __global__ __launch_bounds__(256, 2) void seg_error_kernel(const uint4* __restri
                     for (int e = 0; e < 8; e += 2) {
                         float q0, q1;
                         round_pair_to_bf16(q[e], q[e + 1], q0, q1);
-                        const float d0 = f[e] - q0, d1 = f[e + 1] - q1;
-                        const double dd0 = (double)d0, dd1 = (double)d1;
+                        // the difference in binary64: in binary32 it rounds where the two numbers lie
+                        // more than 2^16 apart (a weight next to nothing against a level that is not zero)
+                        const double dd0 = (double)f[e] - (double)q0, dd1 = (double)f[e + 1] - (double)q1;
                         sse = fma(dd0, dd0, sse);
                         sse = fma(dd1, dd1, sse);
                         sae += fabs(dd0);
                         sae += fabs(dd1);
-                        mx = fmaxf(mx, fmaxf(fabsf(d0), fabsf(d1)));
+                        mx = fmax(mx, fmax(fabs(dd0), fabs(dd1)));
                     }
                 }
             } else {
@@ -129,11 +130,10 @@ __global__ __launch_bounds__(256, 2) void seg_error_kernel(const uint4* __restri
                     const uint32_t code = (uint32_t)assign_code_generic(x, cb);
                     float q0, q1;
                     round_pair_to_bf16(m_eff * lv[code], 0.0f, q0, q1);
-                    const float d = f - q0;
-                    const double dd = (double)d;
+                    const double dd = (double)f - (double)q0;
                     sse = fma(dd, dd, sse);
                     sae += fabs(dd);
-                    mx = fmaxf(mx, fabsf(d));
+                    mx = fmax(mx, fabs(dd));
                 }
             }
             if (OPQ && k_out != 0) {
@@ -145,18 +145,17 @@ __global__ __launch_bounds__(256, 2) void seg_error_kernel(const uint4* __restri
                     const float f = bf16_bits_to_f32(*reinterpret_cast<const uint16_t*>(myseg + 2 * e));
                     float back, unused;
                     round_pair_to_bf16(f16_bits_to_f32(f32_to_f16_bits(f)), 0.0f, back, unused);
-                    const float d = f - back;
-                    const double dd = (double)d;
+                    const double dd = (double)f - (double)back;
                     sse = fma(dd, dd, sse);
                     sae += fabs(dd);
-                    mx = fmaxf(mx, fabsf(d));
+                    mx = fmax(mx, fabs(dd));
                 }
                 kout += k_out;
             }
         }
     }
     // fixed-order butterfly inside the wave, then the four waves of the workgroup in wave order
-    double mxd = (double)mx;
+    double mxd = mx;
     unsigned long long kc = kout;
 #pragma unroll
     for (int mk = 32; mk >= 1; mk >>= 1) {
