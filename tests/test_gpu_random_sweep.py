@@ -24,7 +24,7 @@ SHIFT = 1000003 * int(os.environ.get("BOF4_SWEEP_SHIFT", "0"))
 
 
 def structured_weights(n_blocks, block, shape, rng, g):
-    """n_blocks * block float weights of one of four structures (see sweep_case)."""
+    """n_blocks * block float weights of one of five structures."""
     n = n_blocks * block
     if shape == 0:  # Gaussian
         w = torch.randn(n, generator=g) * 0.02
@@ -34,8 +34,11 @@ def structured_weights(n_blocks, block, shape, rng, g):
         s = torch.exp2(torch.randint(-30, 12, (n_blocks, 1), generator=g).float())
         s[torch.rand(n_blocks, 1, generator=g) < 0.05] = 0.0
         w = (torch.randn(n_blocks, block, generator=g) * s).reshape(-1)
-    else:  # few distinct values: ties in the block maximum, weights on level mid-points
+    elif shape == 3:  # few distinct values: ties in the block maximum, weights on level mid-points
         w = torch.randint(-8, 9, (n,), generator=g).float() * 0.0625
+    else:  # the bottom of bfloat16's range (subnormal and smallest normal numbers) next to ordinary blocks
+        s = torch.where(torch.rand(n_blocks, 1, generator=g) < 0.5, torch.tensor(2.0 ** -132), torch.tensor(0.02))
+        w = (torch.randn(n_blocks, block, generator=g) * s).reshape(-1)
     if rng.random() < 0.5 and n >= 64:  # a pile of large values in one stretch, others spread out
         a = int(rng.integers(0, n - 32))
         w[a:a + int(rng.integers(1, 33))] *= 50.0
@@ -59,7 +62,7 @@ def sweep_case(k):
                 int(rng.integers(1, 3000))][kind]
     n = n_blocks * block
     g = torch.Generator().manual_seed(88000 + k + SHIFT)
-    shape = int(rng.integers(0, 4))
+    shape = int(rng.integers(0, 5))
     w = structured_weights(n_blocks, block, shape, rng, g)
     T = 0.0 if rng.random() < 0.35 else float(oracle.opq_threshold(float(rng.choice([0.9, 0.95, 0.99])), block))
     return w.to(torch.bfloat16), block, signed, T, f"block {block} signed {signed} n {n} kind {kind} shape {shape} T {T:.3f}"
@@ -123,7 +126,7 @@ def test_sweep_decoder_inside_the_matrix_products(k):
     signed = int(rng.integers(0, 2))
     cols = block * int(rng.integers(1, max(2, min(32768 // block, 8192 // block) + 1)))
     rows = int(rng.integers(1, 1 + max(1, min(300, 600000 // cols))))
-    shape = int(rng.integers(0, 4))
+    shape = int(rng.integers(0, 5))
     g = torch.Generator().manual_seed(99500 + k + SHIFT)
     w = structured_weights(rows * cols // block, block, shape, rng, g).clamp(-6.0e4, 6.0e4).to(torch.bfloat16)
     T = 0.0 if rng.random() < 0.4 else float(oracle.opq_threshold(0.95, block))
