@@ -229,3 +229,18 @@ def test_sweep_theory_centroids(k):
     want = theory_general.centroid_update(cb, block, pin, signed, pdf, cdf, u_max)
     got = binding.bof4_theory_centroids(pdf, cdf, u_max, block, cb, pin, signed)
     assert np.all(np.abs(got - want) <= 1e-10 * np.maximum(np.abs(want), 1e-3))
+
+
+@pytest.mark.parametrize("shape,block,signed,T_q", [(2, 64, 1, 0.9), (1, 128, 0, 0.9), (4, 32, 1, 0.95)])
+def test_quantiser_chain_on_large_structured_tensors(shape, block, signed, T_q):
+    """Quantiser, decoder and the one-pass variant at 2^26 weights (every wave of the persistent grids busy for many
+    tiles, outlier lists of 10^5 to 10^6 entries) on the sweep's less ordinary structures: outputs as the oracle's."""
+    n_blocks = (1 << 26) // block + 7
+    rng = np.random.default_rng(5200 + shape)
+    w = structured_weights(n_blocks, block, shape, rng, torch.Generator().manual_seed(5201 + shape))
+    w = w.clamp(-6.0e4, 6.0e4).to(torch.bfloat16)
+    T = float(oracle.opq_threshold(T_q, block))
+    cb = cb_for(block, signed)
+    nout = compare_quantize(w, block, cb, signed, T)
+    print(f"shape {shape} block {block}: {nout} outliers", flush=True)
+    check_fused(w, block, cb, signed, T)
