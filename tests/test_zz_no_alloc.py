@@ -49,3 +49,23 @@ def test_static_entry_point_rejects():
     with pytest.raises(binding.Bof4Error) as e:  # a record in ordinary memory would need a copy
         binding.bof4_lloyd_step_static(w, 64, cb, 1, binding.LloydStats())
     assert e.value.code == binding.BOF4_ERR_ARG
+
+
+@pytest.mark.parametrize("k", range(254, 270))
+def test_static_entry_point_on_the_sweeps_inputs(k):
+    """The same comparison on inputs of the seeded sweep (tests/test_gpu_random_sweep.py): sizes around the tile
+    edges, all block sizes, both normalisations, with and without the outlier rule, both weightings."""
+    from test_gpu_parity import cb_for
+    from test_gpu_random_sweep import sweep_case
+    w, block, signed, T, name = sweep_case(k)
+    if float(w.float().abs().max()) > 65504.0:
+        w = w.float().clamp(-6.0e4, 6.0e4).to(torch.bfloat16)
+    print(name, flush=True)
+    cb = cb_for(block, signed)
+    wd = w.to("cuda:0")
+    rec, keep = binding.pinned_lloyd_stats()
+    w2 = bool(k % 2)
+    ref = binding.bof4_lloyd_step(wd, block, cb, signed, opq_T=T, weight_by_max2=w2, raw=True)
+    ctypes.memset(ctypes.addressof(rec), 0xEE, ctypes.sizeof(rec))
+    got = binding.bof4_lloyd_step_static(wd, block, cb, signed, rec, opq_T=T, weight_by_max2=w2)
+    _same(got, ref)
