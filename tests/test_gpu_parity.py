@@ -406,3 +406,37 @@ def test_lloyd_sums_of_a_zero_region_that_holds_only_outliers(signed):
     assert_stats_close(got[5], o)
     new_g, new_o = binding.bof4_codebook_update(g, 0, cb), oracle.codebook_update(o, 0, cb)
     assert new_g[7] == cb[7] and np.allclose(new_g, new_o, rtol=RTOL, atol=0)
+
+
+def test_calls_in_flight_on_three_streams_at_once_do_not_disturb_each_other():
+    """Two Lloyd steps (each with its own workspace and its own pinned record) and a decoder call enqueued on three
+    streams before any of them is waited for, several rounds: every result equals that of the same call made alone.
+    The library keeps no device state between calls other than what the caller hands it."""
+    cb = cb_for(64, 1)
+    T = oracle.opq_threshold(0.95, 64)
+    wa = make_weights(1536, 1024, seed=811).to(DEV)   # long enough for the calls to overlap
+    wb_ = make_weights(1300, 1024, seed=812).to(DEV)
+    n = wa.numel()
+    codes, scales, oi, ov, k = binding.bof4_quantize(wa, 64, cb, 1, opq_T=T, out_capacity=n // 32)
+    ref_a = binding.bof4_lloyd_step(wa, 64, cb, 1, opq_T=T, raw=True)
+    ref_b = binding.bof4_lloyd_step(wb_, 64, cb, 1, raw=True)
+    ref_d = binding.bof4_dequantize(codes, scales, n, 64, cb, oi, ov, n_outliers=int(k))
+    ws_a, ws_b = binding.alloc_workspace(n, 64, 0, DEV), binding.alloc_workspace(wb_.numel(), 64, 0, DEV)
+    rec_a, keep_a = binding.pinned_lloyd_stats()
+    rec_b, keep_b = binding.pinned_lloyd_stats()
+    out_d = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    s1, s2, s3 = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        out_d.zero_()
+        torch.cuda.synchronize()
+        binding.bof4_lloyd_step_begin(wa, 64, cb, 1, rec_a, opq_T=T, ws=ws_a, stream=s1)
+        binding.bof4_lloyd_step_begin(wb_, 64, cb, 1, rec_b, ws=ws_b, stream=s2)
+        binding.bof4_dequantize(codes, scales, n, 64, cb, oi, ov, n_outliers=int(k), out=out_d, stream=s3)
+        binding.bof4_wait_result(rec_b, stream=s2)
+        binding.bof4_wait_result(rec_a, stream=s1)
+        s3.synchronize()
+        for got, ref in ((rec_a, ref_a), (rec_b, ref_b)):
+            assert list(got.cnt[:]) == list(ref.cnt[:]) and (got.n_used, got.n_outliers) == (ref.n_used, ref.n_outliers)
+            assert list(got.num[:]) == list(ref.num[:]) and list(got.den[:]) == list(ref.den[:]) and got.sse == ref.sse
+        assert torch.equal(out_d.view(torch.int16), ref_d.view(torch.int16))
