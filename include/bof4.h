@@ -84,7 +84,8 @@ int bof4_bin_table(const double* cb_host, float* thr33_host, uint32_t* base33_ho
  *   ws_dev      workspace of at least bof4_workspace_bytes(n, block, 0) bytes (device); contents undefined after
  * The result is bit-identical from run to run (fixed reduction order).  Out of contract: a block whose largest
  * magnitude exceeds binary16's range (65504) - its stored constant is infinite, and the sums are not finite then
- * (bof4_quantize and bof4_dequantize stay defined there: every weight of such a block normalises to zero).  A
+ * (bof4_quantize and bof4_dequantize follow the definitions there as well: every weight of such a block normalises
+ * to zero and decodes to infinity times the zero level's value, i.e. not to a number).  A
  * constant below binary16's normal range (2^-14) is stored with the bits binary16 has for it; the weights of such a
  * block normalise to up to 1.5 in magnitude and are counted as they are.
  */
@@ -164,14 +165,15 @@ typedef struct {
  * as in bof4_lloyd_step; per region the exact weighted median of the normalised weights (weights: the absolute block
  * maximum as stored in binary16, for absolute and signed normalisation alike) is found by a radix search that reads
  * the weights twice and then a list of the few elements still in question (in the workspace: n / 4 bytes, n / 2
- * below 2^29 weights; if the list runs full - a tensor of equal numbers - or outliers must be tracked through the region around zero, the weights are
- * read three or four times instead).  From 2^26 weights up (at block 64) the weights are read once, after a look at
+ * below 2^29 weights; if the list runs full - a tensor of equal numbers - or outliers must be tracked through the
+ * region around zero, the weights are read three or four times instead).  From 2^26 weights up (at block 64) the weights are read once, after a look at
  * one tile of 4096 weights in 16 that tells the search where to expect the medians; if those tiles are unlike the rest
  * of the tensor the search notices and reads the weights again as above - the result is the same either way.  Two
  * environment variables help when looking into this: BOF4_MAE_TRACE (set: every call prints to stderr which way it
  * went; set to 2: also how full the fullest wave's stretch of the list got and every region's window) and
  * BOF4_MAE_NO_SAMPLING (set: always the two-pass search).  The appendix's closing formula names the element before the
- * weighted median; what is returned is the minimiser that its derivation arrives at.  Weights are added as exact 64-bit integers, which
+ * weighted median; what is returned is the minimiser that its derivation arrives at.  Weights are added as exact
+ * 64-bit integers, which
  * needs sum over all weights of |block constant| < 2^38 (BOF4_ERR_ARG otherwise).
  *   weight_by_max  nonzero: the paper's criterion (eq. 8).  0: every weight counts one unit - the plain median of the
  *               normalised weights (appendix D, the MAE of the normalised weights, which the paper shows to be the
