@@ -21,6 +21,8 @@ DEV = "cuda"
 # BOF4_SWEEP_SHIFT=<integer> in the environment moves every case of the sweep to other seeds (for a longer hunt than
 # the committed cases; the default run is the committed one).
 SHIFT = 1000003 * int(os.environ.get("BOF4_SWEEP_SHIFT", "0"))
+# BOF4_SWEEP_BIG=<factor> multiplies the sizes of the cases with many tiles (default 1).
+BIG = int(os.environ.get("BOF4_SWEEP_BIG", "1"))
 
 
 def structured_weights(n_blocks, block, shape, rng, g):
@@ -60,6 +62,8 @@ def sweep_case(k):
                 int(rng.integers(2, 40)) * tile_blocks + int(rng.integers(0, tile_blocks)),
                 4096 * 4 * tile_blocks // 16 + int(rng.integers(0, 3 * tile_blocks)),
                 int(rng.integers(1, 3000))][kind]
+    if kind >= 2:
+        n_blocks = n_blocks * BIG + (BIG - 1) * int(rng.integers(0, 7))
     n = n_blocks * block
     g = torch.Generator().manual_seed(88000 + k + SHIFT)
     shape = int(rng.integers(0, 5))
