@@ -68,7 +68,7 @@ def sweep_case(k):
     g = torch.Generator().manual_seed(88000 + k + SHIFT)
     shape = int(rng.integers(0, 5))
     w = structured_weights(n_blocks, block, shape, rng, g)
-    T = 0.0 if rng.random() < 0.35 else float(oracle.opq_threshold(float(rng.choice([0.9, 0.95, 0.99])), block))
+    T = 0.0 if rng.random() < 0.35 else float(oracle.opq_threshold(float(rng.choice([0.2, 0.5, 0.9, 0.95, 0.99])), block))
     return w.to(torch.bfloat16), block, signed, T, f"block {block} signed {signed} n {n} kind {kind} shape {shape} T {T:.3f}"
 
 
