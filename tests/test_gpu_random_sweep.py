@@ -133,9 +133,9 @@ def test_sweep_decoder_inside_the_matrix_products(k):
     shape = int(rng.integers(0, 5))
     g = torch.Generator().manual_seed(99500 + k + SHIFT)
     w = structured_weights(rows * cols // block, block, shape, rng, g).clamp(-6.0e4, 6.0e4).to(torch.bfloat16)
-    T = 0.0 if rng.random() < 0.4 else float(oracle.opq_threshold(0.95, block))
+    T = 0.0 if rng.random() < 0.4 else float(oracle.opq_threshold(float(rng.choice([0.5, 0.95])), block))
     print(f"block {block} signed {signed} rows {rows} cols {cols} shape {shape} T {T:.3f}", flush=True)
-    cb = cb_for(block, signed)
+    cb = cb_for(block, signed) if k % 2 else random_codebook(rng)
     st, codes, scales, oi, ov, n_out = oracle.quantize(inputs.bits(w), block, cb, signed, opq_T=T)
     assert st == oracle.OK
     lst = (oi, ov) if n_out > 0 else (None, None)
