@@ -893,7 +893,7 @@ int quantize_impl(int phase, const void* w_dev, uint64_t n, uint32_t block, cons
         // total_dev[0] = count, with bit 63 set if a wave overflowed its staging region.  A caller's counter in pinned
         // host memory receives it straight from the gather kernel.
         *n_outliers_host = direct ? FLAG_PENDING : 0;
-        hipLaunchKernelGGL(seg_outlier_gather_kernel, dim3(n_waves), dim3(64), 0, s, os, n_waves, out_idx_dev,
+        hipLaunchKernelGGL(seg_outlier_gather_kernel, dim3(n_waves), dim3(256), 0, s, os, n_waves, out_idx_dev,
                            out_val_dev, out_capacity, direct ? direct : total_dev);
     }
     if (lloyd) {

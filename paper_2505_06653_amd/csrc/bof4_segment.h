@@ -674,26 +674,26 @@ __global__ __launch_bounds__(256, pass_waves_per_simd(OPQ, QUANT, LLOYD)) void s
     }
 }
 
-// One wave per staging region: it adds up the outlier counts of the regions before its own (that sum is where its
-// entries start in the caller's ascending list) and copies its region there.  The wave of the last region has then
-// seen every count: it publishes *total_out = number of outliers, with bit 63 set if some wave overflowed its
+// One workgroup per staging region: it adds up the outlier counts of the regions before its own (that sum is where
+// its entries start in the caller's ascending list) and copies its region there.  The workgroup of the last region
+// has then seen every count: it publishes *total_out = number of outliers, with bit 63 set if some wave overflowed its
 // staging region.
-__global__ __launch_bounds__(64) void seg_outlier_gather_kernel(OutlierStage os, uint32_t n_waves,
-                                                                 int64_t* __restrict__ out_idx,
-                                                                 uint16_t* __restrict__ out_val, uint64_t capacity,
-                                                                 uint64_t* __restrict__ total_out) {
-    const uint32_t r = blockIdx.x, lane = threadIdx.x;
+__global__ __launch_bounds__(256) void seg_outlier_gather_kernel(OutlierStage os, uint32_t n_waves,
+                                                                  int64_t* __restrict__ out_idx,
+                                                                  uint16_t* __restrict__ out_val, uint64_t capacity,
+                                                                  uint64_t* __restrict__ total_out) {
+    const uint32_t r = blockIdx.x, tid = threadIdx.x;
     uint64_t before = 0;
     uint32_t over = 0;
-    for (uint32_t i0 = 0; i0 < r; i0 += 64 * 16) {  // 16 independent loads in flight per lane
-        uint32_t ci[16];
+    for (uint32_t i0 = 0; i0 < r; i0 += 256 * 4) {  // four independent loads in flight per lane
+        uint32_t ci[4];
 #pragma unroll
-        for (int t = 0; t < 16; ++t) {
-            const uint32_t i = i0 + 64 * t + lane;
+        for (int t = 0; t < 4; ++t) {
+            const uint32_t i = i0 + 256 * t + tid;
             ci[t] = i < r ? os.wave_count[i] : 0u;
         }
 #pragma unroll
-        for (int t = 0; t < 16; ++t) {
+        for (int t = 0; t < 4; ++t) {
             before += ci[t];
             over |= (ci[t] > os.region_cap) ? 1u : 0u;
         }
@@ -703,15 +703,24 @@ __global__ __launch_bounds__(64) void seg_outlier_gather_kernel(OutlierStage os,
         before += (uint64_t)__shfl_xor((long long)before, d, 64);
         over |= (uint32_t)__shfl_xor((int)over, d, 64);
     }
+    __shared__ uint64_t before_w[4];
+    __shared__ uint32_t over_w[4];
+    if ((tid & 63u) == 0) {
+        before_w[tid >> 6] = before;
+        over_w[tid >> 6] = over;
+    }
+    __syncthreads();
+    before = (before_w[0] + before_w[1]) + (before_w[2] + before_w[3]);  // integers: any order
+    over = over_w[0] | over_w[1] | over_w[2] | over_w[3];
     const uint32_t own = os.wave_count[r];
-    if (r == n_waves - 1 && lane == 0)  // one 64-bit store at system scope: a host that watches the word sees it whole
+    if (r == n_waves - 1 && tid == 0)  // one 64-bit store at system scope: a host that watches the word sees it whole
         __hip_atomic_store(reinterpret_cast<unsigned long long*>(total_out),
                            (unsigned long long)((before + own) |
                                                 ((uint64_t)((over | (own > os.region_cap ? 1u : 0u)) != 0) << 63)),
                            __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     const uint32_t c = own > os.region_cap ? os.region_cap : own;
     const uint64_t src = (uint64_t)r * os.region_cap;
-    for (uint32_t j = lane; j < c; j += 64) {
+    for (uint32_t j = tid; j < c; j += 256) {
         if (before + j < capacity) {
             out_idx[before + j] = os.idx[src + j];
             out_val[before + j] = os.val[src + j];
