@@ -24,7 +24,7 @@ struct SegCfg {
 };
 
 constexpr int WAVES_PER_WG = 4;
-constexpr int LLOYD_PART = 56;  // doubles per per-wave partial: A[16] den15[16] cnt15[16] sxx kout_g kout nout (+pad)
+constexpr int LLOYD_PART = 56;  // doubles per per-wave partial: A[16] den15[16] cnt15[16] sxx (unused) kout nout (+pad)
 
 // ---------------------------------------------------------------------------------------------- tile movement
 template <int I>
@@ -408,7 +408,7 @@ __global__ __launch_bounds__(256, pass_waves_per_simd(OPQ, QUANT, LLOYD)) void s
     char* stage = sh.stage + (STAGED ? wave * C::STAGE_BYTES : 0);
     const uint64_t n_vec = n_seg * C::NV;
 
-    double A[4], den15[4], sxx_g = 0.0, kout_g = 0.0;
+    double A[4], den15[4], sxx_g = 0.0;
     uint32_t cnt15[4], kout = 0;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -580,8 +580,14 @@ __global__ __launch_bounds__(256, pass_waves_per_simd(OPQ, QUANT, LLOYD)) void s
         if (LLOYD) {
             const double gd = active ? (double)g : 0.0;
             sxx_g = fma(gd, sxx, sxx_g);
-            if (OPQ) {  // the zeroed outliers went into the sums as x = 0; remember what to take out again
-                kout_g = fma(gd, (double)k_out, kout_g);
+            if (OPQ) {
+                // The zeroed outliers went through the loop as x = 0 and sit in this lane's column of the zero level:
+                // take out again exactly what they put there, k_out times the operand of x = 0, as integers - the
+                // column then holds the block's other weights only, count and sum, and nothing has to be corrected
+                // later in floating point (where a region whose other weights all weigh nothing kept a residue).
+                if (k_out != 0u)
+                    atomicAdd(&acc[bt.code_of_zero * 64 + lane],
+                              0ull - (unsigned long long)k_out * (unsigned long long)__double_as_longlong(inc_add));
                 kout += k_out;
             }
             if (t * 64 + 64 > n_seg) {  // wave-uniform: the ragged last tile of the tensor
@@ -646,17 +652,16 @@ __global__ __launch_bounds__(256, pass_waves_per_simd(OPQ, QUANT, LLOYD)) void s
         }
     }
     {
-        double a = sxx_g, kg = kout_g;
+        double a = sxx_g;
         unsigned long long kc = kout;
 #pragma unroll
         for (int mk = 32; mk >= 1; mk >>= 1) {
             a += __shfl_xor(a, mk, 64);
-            kg += __shfl_xor(kg, mk, 64);
             kc += (unsigned long long)__shfl_xor((long long)kc, mk, 64);
         }
         if (lane == 0) {
             wtot[48] = a;
-            wtot[49] = kg;                                  // sum of g * (outliers of the block)
+            wtot[49] = 0.0;                                 // (not used)
             wtot[50] = __longlong_as_double((long long)kc); // outlier count
         }
     }
@@ -776,21 +781,13 @@ __global__ __launch_bounds__(1024) void seg_lloyd_final_kernel(const double* __r
     __shared__ unsigned long long cnt_part[16];
     if (threadIdx.x < 16) {
         const uint32_t l = threadIdx.x;
-        const double koutg = tot[49];
         const unsigned long long kout = (unsigned long long)__double_as_longlong(tot[50]);
         double den = tot[16 + l] * (1.0 / 15.0);
         double a = tot[l];
         // 15 K is a multiple of 15 below 2^53: the binary64 quotient is the exact integer
         unsigned long long c = (unsigned long long)((double)(unsigned long long)__double_as_longlong(tot[32 + l]) / 15.0);
-        if (l == code_of_zero) {  // zeroed outliers were counted as x = 0: take them out again
-            den -= koutg;
-            a -= 2.0 * koutg;
-            c -= kout;
-        }
         double num = a - 2.0 * den;
-        // a region left empty once the outliers are taken out has no mass: the two subtractions above leave rounding
-        // residue there (the sums were added in another order than the amounts taken out), the exact count says so
-        if (c == 0ull) den = num = 0.0;
+        if (c == 0ull) den = num = 0.0;  // an empty region has no mass (a - 2 den may leave rounding residue)
         out[l] = num;
         out[16 + l] = den;
         out[32 + l] = __longlong_as_double((long long)c);

@@ -384,20 +384,24 @@ def test_lloyd_sums_of_blocks_whose_constant_binary16_stores_with_fewer_bits(blo
 
 
 @pytest.mark.parametrize("signed", [0, 1])
-def test_lloyd_sums_of_a_zero_region_that_holds_only_outliers(signed):
+@pytest.mark.parametrize("weightless", [0, 1])
+def test_lloyd_sums_of_a_zero_region_that_holds_only_outliers(signed, weightless):
     """One block in which no weight lies near zero; its one outlier is zeroed, runs through the sums as x = 0 and is
-    taken out again.  The region of the zero level is then empty:
-    count 0 and mass exactly 0 (not the rounding residue of adding and subtracting the same amount in two orders),
-    so that an update leaves its level alone."""
+    taken out again.  The region of the zero level is then empty: count 0 and mass exactly 0 (not the rounding residue
+    of adding and subtracting the same amount in floating point), so that an update leaves its level alone.  With
+    `weightless` a second block of numbers too small for a binary16 constant (constant 0, every x = 0, weight 0) puts
+    64 elements into that region that weigh nothing: count 64, mass still exactly 0."""
     w = torch.full((64,), 0.02)
     w[1::2] = -0.02
     w[::7] *= 0.7
     w[9] = 3.0  # the outlier
+    if weightless:
+        w = torch.cat([w, torch.full((64,), 2.0 ** -132) * torch.arange(-32, 32)])
     w = w.to(torch.bfloat16)
     cb = cb_for(64, signed)
     T = oracle.opq_threshold(0.95, 64)
     st, o = oracle.lloyd_step(inputs.bits(w), 64, cb, signed, opq_T=T)
-    assert st == oracle.OK and o["n_outliers"] == 1 and o["cnt"][7] == 0 and o["den"][7] == 0.0
+    assert st == oracle.OK and o["n_outliers"] == 1 and o["cnt"][7] == 64 * weightless and o["den"][7] == 0.0
     g = binding.bof4_lloyd_step(w.to(DEV), 64, cb, signed, opq_T=T)
     assert g["den"][7] == 0.0 and g["num"][7] == 0.0
     assert_stats_close(g, o)
