@@ -41,9 +41,9 @@ CEIL_LIB = os.path.join(ROOT, "libbench_ceilings.so")
 # it reads for the plain copy at the end of the run); keyed by (config, block, kernel).  Filled in from the summaries
 # under profiles/ named beside each entry; a workload or kernel without a profile reports null.
 PROFILED_TRAFFIC = {
-    (4, 64, "quantize_lloyd"): (1_905_284_656 + 587_288_273, "profiles/bench_config4_block64_opq_hbm_traffic.md: "
+    (4, 64, "quantize_lloyd"): (1_907_670_111 + 584_580_390, "profiles/bench_config4_block64_opq_hbm_traffic.md: "
                                 "seg_pass_kernel<64, true, true, true, true>, fetched + written per launch"),
-    (4, 64, "dequantize"): (538_338_548 + 1_710_994_806, "profiles/bench_config4_block64_opq_hbm_traffic.md: "
+    (4, 64, "dequantize"): (538_325_903 + 1_710_990_916, "profiles/bench_config4_block64_opq_hbm_traffic.md: "
                             "dequantize_kernel<64>, fetched + written per launch"),
 }
 
